@@ -1,0 +1,161 @@
+/*
+ * pbdr.h -- C ABI of the MI355X (gfx950) splatting rasterizer: the per-view compute of point-based
+ * differentiable rendering with 3D Gaussians, forward and backward.
+ *
+ * The three main calls follow the paper's three-function view of a PBDR algorithm (Sec. 3.1):
+ *   pbdr_preprocess   = pts_culling + pts_splatting : point parameters + camera -> per-view splat state
+ *   pbdr_render_fwd   = image_render                : splat state -> image (+ what the backward needs)
+ *   pbdr_render_bwd   = image_render.backward + pts_splatting.backward (Alg. 1 lines 17-18, 22-24)
+ *
+ * Conventions for every call
+ *   - Pointers inside the structs and the image / workspace pointers are DEVICE pointers owned by the caller
+ *     (e.g. PyTorch allocations). The structs themselves, `bg` and the camera live in HOST memory.
+ *   - The library allocates, frees and retains nothing. Work is enqueued on `hip_stream` (a hipStream_t, NULL =
+ *     default stream) and the call returns without synchronising, except pbdr_query_lists which synchronises.
+ *   - All arrays are fp32 / int32 / uint32 planes ("structure of arrays"): an attribute with l components of n
+ *     points is stored as [l][n], i.e. component-major, so that one wavefront reads 64 consecutive floats.
+ *     This is the paper's S x l tensor (Sec. 3.1) transposed. Every pointer must be 16-byte aligned.
+ *   - Return value: PBDR_OK or a negative pbdr_status. Invalid arguments are detected on the host before
+ *     anything is enqueued. No exceptions or C++ types cross this boundary.
+ *   - Calls that share a workspace, a gradient buffer or an output must be ordered on one stream by the caller.
+ *
+ * Numerical rules (the paper leaves them to its rendering kernels; these are this library's readings, and the
+ * CPU oracle states the same): scale = exp(log_scale), rotation = normalised quaternion (w,x,y,z), opacity =
+ * sigmoid(logit); depth = camera-space z; first-order ("affine", App. B) projection of the covariance with the
+ * ray slope clamped to 1.3 x the half field of view and 0.3 px^2 blur; extent = ceil(3 sigma_max); 16x16 tiles;
+ * colour = max(0, 0.5 + SH(dir)); alpha = min(0.99, o exp(-sigma)); alpha < 1/255 skipped; a splat that would
+ * take the transmittance below 1e-4 is not blended and ends the pixel; depth ties ordered by point index.
+ */
+#ifndef PBDR_H
+#define PBDR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PBDR_TILE 16
+#define PBDR_VERSION 100
+
+typedef enum pbdr_status {
+    PBDR_OK = 0,
+    PBDR_ERR_INVALID_ARG = -1,         /* null / misaligned pointer, n < 0, sh_degree outside 0..3, bad image size */
+    PBDR_ERR_WORKSPACE_TOO_SMALL = -2, /* workspace smaller than pbdr_workspace_bytes() for these sizes */
+    PBDR_ERR_CAPACITY = -3,            /* more (tile, splat) pairs than dup_capacity (reported by pbdr_query_lists) */
+    PBDR_ERR_HIP = -4                  /* a HIP call failed; see pbdr_last_hip_error() */
+} pbdr_status;
+
+/* Point cloud shard ("model state", Sec. 3.1; 3DGS attributes Sec. 2.1 / 3.2): 59 floats per point at degree 3. */
+typedef struct pbdr_scene {
+    int32_t n;                  /* number of points, >= 0 */
+    int32_t sh_degree;          /* 0..3; K = (sh_degree+1)^2 coefficients per colour channel */
+    const float* mean;          /* [3][n] world-space position */
+    const float* log_scale;     /* [3][n] */
+    const float* quat;          /* [4][n] (w,x,y,z), need not be normalised */
+    const float* opacity_logit; /* [n] */
+    const float* sh;            /* [K][3][n] coefficient-major, then channel */
+} pbdr_scene;
+
+/* Gradient w.r.t. pbdr_scene, same layout. pbdr_render_bwd / pbdr_preprocess_bwd ACCUMULATE (+=) into it,
+ * which is how Alg. 1 lines 22-24 sum the views of a batch; the caller zeroes it once per batch. */
+typedef struct pbdr_scene_grads {
+    int32_t n;
+    int32_t sh_degree;
+    float* mean;
+    float* log_scale;
+    float* quat;
+    float* opacity_logit;
+    float* sh;
+} pbdr_scene_grads;
+
+/* Pinhole view. World -> camera: p = R x + t, R row-major; camera axes +x right, +y down, +z forward.
+ * Pixel (i,j) has its centre at (i+0.5, j+0.5). far_plane and radius_clip are the two per-view filters the paper
+ * uses for street scenes (App. E.1); radius_clip = 0 and far_plane = 1e10 disable them. near_plane must be > 0. */
+typedef struct pbdr_camera {
+    int32_t width, height;
+    float fx, fy, cx, cy;
+    float R[9];
+    float t[3];
+    float near_plane, far_plane, radius_clip;
+} pbdr_camera;
+
+/* Per-view splat state, exactly the 11 elements / 44 bytes per point of Table 3a.
+ * radius == 0 marks a culled point; its other fields are then unspecified. */
+typedef struct pbdr_splats {
+    int32_t n;
+    float* mean2d;   /* [2][n] pixel coordinates */
+    float* conic;    /* [3][n] inverse 2D covariance (a, b, c) */
+    float* opacity;  /* [n] */
+    float* color;    /* [3][n] */
+    int32_t* radius; /* [n] extent in pixels */
+    float* depth;    /* [n] camera-space z */
+} pbdr_splats;
+
+/* Gradient w.r.t. the differentiable part of pbdr_splats (what Alg. 1 line 19-20 sends back). Overwritten. */
+typedef struct pbdr_splat_grads {
+    int32_t n;
+    float* mean2d;  /* [2][n] */
+    float* conic;   /* [3][n] */
+    float* opacity; /* [n] */
+    float* color;   /* [3][n] */
+} pbdr_splat_grads;
+
+/* Bytes of workspace that pbdr_render_fwd / pbdr_render_bwd / pbdr_bin_sort need for n points, a width x height
+ * image and at most dup_capacity (tile, splat) pairs. The workspace must be 256-byte aligned. */
+int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes);
+
+/* pts_culling + pts_splatting (Sec. 3.1, Sec. 3.2 "3DGS"; Alg. 1 lines 2-4). One pass over the shard: near/far
+ * cull, covariance projection, conic, extent, off-screen and radius_clip cull, SH colour. Writes all of `out`. */
+int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream);
+
+/* The sorting half of image_render (Sec. 2.1: "sorts these view-dependent splats by their distance to the camera
+ * plane"): per-splat tile count, device prefix sum, (tile << 32 | depth bits) keys, radix sort, per-tile ranges.
+ * Results stay in the workspace; pbdr_lists_view gives their addresses. If more than dup_capacity pairs exist the
+ * excess is dropped, nothing is written out of bounds, and pbdr_query_lists reports PBDR_ERR_CAPACITY. */
+int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t dup_capacity, void* workspace,
+                  size_t workspace_bytes, void* hip_stream);
+
+/* image_render forward (Sec. 2.1 blending; Alg. 1 line 12) = pbdr_bin_sort followed by per-tile front-to-back
+ * compositing. image [3][H][W], final_T [H][W], last_idx [H][W] = 1-based position, within the pixel's tile list,
+ * of the last splat blended into the pixel (0 = none). The workspace keeps the lists for pbdr_render_bwd. */
+int pbdr_render_fwd(const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
+                    float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* image_render.backward then pts_splatting.backward (Alg. 1 lines 17-18 and 22-24). Needs the workspace exactly
+ * as pbdr_render_fwd left it for the same splats, camera and dup_capacity. dL_dimage [3][H][W]. g_splats is overwritten with
+ * dL/d(splat state). If scene and grads are both non-NULL the parameter gradient is then ACCUMULATED into grads;
+ * if both are NULL the call stops after g_splats (the point where the paper's system exchanges gradients). */
+int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3],
+                    uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                    pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* pts_splatting.backward alone (Alg. 1 lines 22-24): chain rule from g_splats to the raw parameters, ACCUMULATED
+ * into grads. Points with splats->radius == 0 receive nothing. Depth and radius carry no gradient. */
+int pbdr_preprocess_bwd(const pbdr_scene* scene, const pbdr_camera* cam, const pbdr_splats* splats,
+                        const pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* hip_stream);
+
+/* Device addresses, inside a workspace laid out for these sizes, of the results of pbdr_bin_sort / pbdr_render_fwd:
+ * sorted keys [P] (tile << 32 | bits(depth)), vals [P] (point index), ranges [tiles][2] ([start,end) per tile,
+ * {0,0} for an empty tile), num_dup [1] (P before clamping to dup_capacity). Any out pointer may be NULL. */
+int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                    uint64_t dup_capacity, const uint64_t** keys, const uint32_t** vals, const uint32_t** ranges,
+                    const uint32_t** num_dup);
+
+/* Synchronises hip_stream and reads back the number of (tile, splat) pairs found by the last pbdr_bin_sort /
+ * pbdr_render_fwd on this workspace. Returns PBDR_ERR_CAPACITY if it exceeded dup_capacity (the lists were then
+ * truncated), else PBDR_OK. Optional: callers that know a safe capacity never need to call it. */
+int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                     uint64_t dup_capacity, void* hip_stream, uint64_t* num_dup);
+
+const char* pbdr_status_string(int status);
+int pbdr_last_hip_error(void); /* hipError_t of the most recent PBDR_ERR_HIP on this thread */
+int pbdr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBDR_H */

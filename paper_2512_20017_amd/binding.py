@@ -1,0 +1,291 @@
+"""Thin ctypes binding over libpbdr.so (the C ABI in include/pbdr.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels. PyTorch supplies device memory and the
+current stream. There is no fallback: if the library is missing, loading raises.
+
+Tensor layouts are the library's structure-of-arrays planes: an attribute with l components is a contiguous
+[l, n] float32 tensor (the paper's S x l tensor, transposed); images are [3, H, W].
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpbdr.so")
+
+PBDR_OK = 0
+PBDR_ERR_INVALID_ARG = -1
+PBDR_ERR_WORKSPACE_TOO_SMALL = -2
+PBDR_ERR_CAPACITY = -3
+PBDR_ERR_HIP = -4
+
+EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_render_fwd", "pbdr_render_bwd",
+           "pbdr_preprocess_bwd", "pbdr_lists_view", "pbdr_query_lists", "pbdr_status_string", "pbdr_last_hip_error",
+           "pbdr_version")
+
+_f = C.POINTER(C.c_float)
+
+
+class CScene(C.Structure):
+    _fields_ = [("n", C.c_int32), ("sh_degree", C.c_int32), ("mean", C.c_void_p), ("log_scale", C.c_void_p),
+                ("quat", C.c_void_p), ("opacity_logit", C.c_void_p), ("sh", C.c_void_p)]
+
+
+class CCamera(C.Structure):
+    _fields_ = [("width", C.c_int32), ("height", C.c_int32), ("fx", C.c_float), ("fy", C.c_float), ("cx", C.c_float),
+                ("cy", C.c_float), ("R", C.c_float * 9), ("t", C.c_float * 3), ("near_plane", C.c_float),
+                ("far_plane", C.c_float), ("radius_clip", C.c_float)]
+
+
+class CSplats(C.Structure):
+    _fields_ = [("n", C.c_int32), ("mean2d", C.c_void_p), ("conic", C.c_void_p), ("opacity", C.c_void_p),
+                ("color", C.c_void_p), ("radius", C.c_void_p), ("depth", C.c_void_p)]
+
+
+class CSplatGrads(C.Structure):
+    _fields_ = [("n", C.c_int32), ("mean2d", C.c_void_p), ("conic", C.c_void_p), ("opacity", C.c_void_p),
+                ("color", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libpbdr.so; raises if it has not been built (python -m paper_2512_20017_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python paper_2512_20017_amd/build.py`")
+        L = C.CDLL(LIB_PATH)
+        L.pbdr_status_string.restype = C.c_char_p
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+class PbdrError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__(f"pbdr: {lib().pbdr_status_string(C.c_int(status)).decode()} ({status})")
+
+
+def _check(status):
+    if status != PBDR_OK:
+        raise PbdrError(status)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def camera_struct(cam: dict) -> CCamera:
+    c = CCamera()
+    c.width, c.height = int(cam["width"]), int(cam["height"])
+    c.fx, c.fy, c.cx, c.cy = (float(cam[k]) for k in ("fx", "fy", "cx", "cy"))
+    R = np.asarray(cam["R"], dtype=np.float32).reshape(9)
+    t = np.asarray(cam["t"], dtype=np.float32).reshape(3)
+    for i in range(9):
+        c.R[i] = float(R[i])
+    for i in range(3):
+        c.t[i] = float(t[i])
+    c.near_plane = float(cam.get("near", 0.2))
+    c.far_plane = float(cam.get("far", 1e10))
+    c.radius_clip = float(cam.get("radius_clip", 0.0))
+    return c
+
+
+def _dev(t):
+    return C.c_void_p(t.data_ptr()) if t is not None and t.numel() > 0 else C.c_void_p(0)
+
+
+@dataclass
+class Scene:
+    """Point parameters on the device, SoA planes: mean[3,n], log_scale[3,n], quat[4,n], logit[n], sh[K,3,n]."""
+    n: int
+    sh_degree: int
+    mean: torch.Tensor
+    log_scale: torch.Tensor
+    quat: torch.Tensor
+    logit: torch.Tensor
+    sh: torch.Tensor
+
+    @staticmethod
+    def from_numpy(sc: dict, device="cuda") -> "Scene":
+        """From the S x l host layout (mean[n,3], ..., sh[n,K,3]) to device planes."""
+        def up(a, perm):
+            return torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=np.float32).transpose(perm))).to(device)
+        n = int(sc["mean"].shape[0])
+        return Scene(n, int(sc["sh_degree"]), up(sc["mean"], (1, 0)), up(sc["log_scale"], (1, 0)), up(sc["quat"], (1, 0)),
+                     torch.from_numpy(np.ascontiguousarray(sc["logit"], dtype=np.float32)).to(device),
+                     up(sc["sh"], (1, 2, 0)))
+
+    def zeros_like(self) -> "Scene":
+        return Scene(self.n, self.sh_degree, torch.zeros_like(self.mean), torch.zeros_like(self.log_scale),
+                     torch.zeros_like(self.quat), torch.zeros_like(self.logit), torch.zeros_like(self.sh))
+
+    def to_numpy(self) -> dict:
+        return dict(mean=self.mean.cpu().numpy().T.copy(), log_scale=self.log_scale.cpu().numpy().T.copy(),
+                    quat=self.quat.cpu().numpy().T.copy(), logit=self.logit.cpu().numpy().copy(),
+                    sh=self.sh.cpu().numpy().transpose(2, 0, 1).copy(), sh_degree=self.sh_degree)
+
+    def struct(self) -> CScene:
+        return CScene(self.n, self.sh_degree, _dev(self.mean), _dev(self.log_scale), _dev(self.quat), _dev(self.logit),
+                      _dev(self.sh))
+
+
+@dataclass
+class Splats:
+    """Per-view splat state (Table 3a), SoA planes."""
+    n: int
+    mean2d: torch.Tensor
+    conic: torch.Tensor
+    opacity: torch.Tensor
+    color: torch.Tensor
+    radius: torch.Tensor
+    depth: torch.Tensor
+
+    @staticmethod
+    def empty(n, device="cuda") -> "Splats":
+        f = dict(dtype=torch.float32, device=device)
+        return Splats(n, torch.empty((2, n), **f), torch.empty((3, n), **f), torch.empty(n, **f), torch.empty((3, n), **f),
+                      torch.empty(n, dtype=torch.int32, device=device), torch.empty(n, **f))
+
+    @staticmethod
+    def from_numpy(st: dict, device="cuda") -> "Splats":
+        """From host arrays mean2d[n,2], conic[n,3], opacity[n], color[n,3], radius[n], depth[n]."""
+        def up(a, dt=np.float32):
+            a = np.asarray(a, dtype=dt)
+            return torch.from_numpy(np.ascontiguousarray(a.T if a.ndim == 2 else a)).to(device)
+        n = int(np.asarray(st["opacity"]).shape[0])
+        return Splats(n, up(st["mean2d"]), up(st["conic"]), up(st["opacity"]), up(st["color"]),
+                      up(st["radius"], np.int32), up(st["depth"]))
+
+    def to_numpy(self) -> dict:
+        return dict(mean2d=self.mean2d.cpu().numpy().T.copy(), conic=self.conic.cpu().numpy().T.copy(),
+                    opacity=self.opacity.cpu().numpy().copy(), color=self.color.cpu().numpy().T.copy(),
+                    radius=self.radius.cpu().numpy().copy(), depth=self.depth.cpu().numpy().copy())
+
+    def struct(self) -> CSplats:
+        return CSplats(self.n, _dev(self.mean2d), _dev(self.conic), _dev(self.opacity), _dev(self.color),
+                       _dev(self.radius), _dev(self.depth))
+
+
+@dataclass
+class SplatGrads:
+    n: int
+    mean2d: torch.Tensor
+    conic: torch.Tensor
+    opacity: torch.Tensor
+    color: torch.Tensor
+
+    @staticmethod
+    def empty(n, device="cuda") -> "SplatGrads":
+        f = dict(dtype=torch.float32, device=device)
+        return SplatGrads(n, torch.empty((2, n), **f), torch.empty((3, n), **f), torch.empty(n, **f), torch.empty((3, n), **f))
+
+    @staticmethod
+    def from_numpy(d: dict, device="cuda") -> "SplatGrads":
+        def up(a):
+            a = np.asarray(a, dtype=np.float32)
+            return torch.from_numpy(np.ascontiguousarray(a.T if a.ndim == 2 else a)).to(device)
+        n = int(np.asarray(d["opacity"]).shape[0])
+        return SplatGrads(n, up(d["mean2d"]), up(d["conic"]), up(d["opacity"]), up(d["color"]))
+
+    def to_numpy(self) -> dict:
+        return dict(mean2d=self.mean2d.cpu().numpy().T.copy(), conic=self.conic.cpu().numpy().T.copy(),
+                    opacity=self.opacity.cpu().numpy().copy(), color=self.color.cpu().numpy().T.copy())
+
+    def struct(self) -> CSplatGrads:
+        return CSplatGrads(self.n, _dev(self.mean2d), _dev(self.conic), _dev(self.opacity), _dev(self.color))
+
+
+def pbdr_version() -> int:
+    return int(lib().pbdr_version())
+
+
+def pbdr_workspace_bytes(n, width, height, dup_capacity) -> int:
+    out = C.c_size_t(0)
+    _check(lib().pbdr_workspace_bytes(C.c_int32(n), C.c_int32(width), C.c_int32(height), C.c_uint64(dup_capacity),
+                                      C.byref(out)))
+    return int(out.value)
+
+
+def alloc_workspace(n, width, height, dup_capacity, device="cuda") -> torch.Tensor:
+    nbytes = pbdr_workspace_bytes(n, width, height, dup_capacity)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws[off:off + nbytes]
+
+
+def pbdr_preprocess(scene: Scene, cam: dict, out: Splats, stream=None) -> None:
+    s, c, o = scene.struct(), camera_struct(cam), out.struct()
+    _check(lib().pbdr_preprocess(C.byref(s), C.byref(c), C.byref(o), _stream(stream)))
+
+
+def pbdr_bin_sort(splats: Splats, cam: dict, dup_capacity: int, ws: torch.Tensor, stream=None) -> None:
+    s, c = splats.struct(), camera_struct(cam)
+    _check(lib().pbdr_bin_sort(C.byref(s), C.byref(c), C.c_uint64(dup_capacity), C.c_void_p(ws.data_ptr()),
+                               C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def pbdr_render_fwd(splats: Splats, cam: dict, bg, dup_capacity: int, image, final_T, last_idx, ws, stream=None) -> None:
+    s, c = splats.struct(), camera_struct(cam)
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    _check(lib().pbdr_render_fwd(C.byref(s), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(image), _dev(final_T),
+                                 _dev(last_idx), C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
+                    g_splats: SplatGrads, grads, ws, stream=None) -> None:
+    """scene/grads: both Scene (gradient accumulated into grads) or both None (stop at g_splats)."""
+    sp, c, g2 = splats.struct(), camera_struct(cam), g_splats.struct()
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    if scene is not None:
+        sc, g = scene.struct(), grads.struct()
+        psc, pg = C.byref(sc), C.byref(g)
+    else:
+        psc, pg = None, None
+    _check(lib().pbdr_render_bwd(psc, C.byref(sp), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(final_T), _dev(last_idx),
+                                 _dev(dL_dimage), C.byref(g2), pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
+                                 _stream(stream)))
+
+
+def pbdr_preprocess_bwd(scene: Scene, cam: dict, splats: Splats, g_splats: SplatGrads, grads: Scene, stream=None) -> None:
+    sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct()
+    _check(lib().pbdr_preprocess_bwd(C.byref(sc), C.byref(c), C.byref(sp), C.byref(g2), C.byref(g), _stream(stream)))
+
+
+def pbdr_query_lists(ws, n, width, height, dup_capacity, stream=None):
+    """Synchronises. Returns (num_dup, overflowed)."""
+    out = C.c_uint64(0)
+    st = lib().pbdr_query_lists(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
+                                C.c_int32(height), C.c_uint64(dup_capacity), _stream(stream), C.byref(out))
+    if st not in (PBDR_OK, PBDR_ERR_CAPACITY):
+        raise PbdrError(st)
+    return int(out.value), st == PBDR_ERR_CAPACITY
+
+
+def pbdr_lists_view(ws, n, width, height, dup_capacity):
+    """Copies the sorted lists out of the workspace (synchronises): dict(P, keys, vals, ranges) as numpy."""
+    keys, vals, ranges, nd = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(lib().pbdr_lists_view(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
+                                 C.c_int32(height), C.c_uint64(dup_capacity), C.byref(keys), C.byref(vals),
+                                 C.byref(ranges), C.byref(nd)))
+    torch.cuda.synchronize()
+    base = ws.data_ptr()
+    host = ws.cpu().numpy()
+
+    def view(ptr, count, dt):
+        off = ptr.value - base
+        return host[off:off + count * np.dtype(dt).itemsize].view(dt).copy()
+    tiles = ((width + 15) // 16) * ((height + 15) // 16)
+    P_raw = int(view(nd, 1, np.uint32)[0])
+    P = min(P_raw, max(int(dup_capacity), 1))
+    return dict(P=P, P_raw=P_raw, keys=view(keys, P, np.uint64), vals=view(vals, P, np.uint32),
+                ranges=view(ranges, 2 * tiles, np.uint32).reshape(tiles, 2))

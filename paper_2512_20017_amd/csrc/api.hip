@@ -1,0 +1,240 @@
+// C ABI of libpbdr: argument checks, workspace layout, camera conversion, kernel sequencing. No allocation here.
+#include "../../include/pbdr.h"
+#include "pbdr_internal.h"
+
+#include <cmath>
+
+namespace pbdr {
+
+static thread_local int g_last_hip_error = 0;
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
+{
+    if (n < 0 || W <= 0 || H <= 0 || W > 65536 || H > 65536) return false;
+    if (cap == 0) cap = 1;
+    if (cap > 0x7fffffffull) return false;
+    L->n = n; L->W = W; L->H = H;
+    L->TX = (W + kTile - 1) / kTile; L->TY = (H + kTile - 1) / kTile;
+    L->tiles = L->TX * L->TY;
+    L->cap = (uint32_t)cap;
+    int tile_bits = 0;
+    while ((1 << tile_bits) < L->tiles) ++tile_bits;
+    L->sort_bits = 32 + tile_bits;
+    L->sort_passes = (L->sort_bits + 7) / 8;
+    L->sort_blocks = (uint32_t)((cap + kSortItems - 1) / kSortItems);
+    L->hist_len = 256u * L->sort_blocks;
+    const size_t scan_max = (size_t)((uint32_t)n > L->hist_len ? (uint32_t)n : L->hist_len);
+    size_t off = 0;
+    L->off_status = off;    off = align256(off + kStWords * sizeof(uint32_t));
+    L->off_packed = off;    off = align256(off + (size_t)n * sizeof(Packed));
+    L->off_offsets = off;   off = align256(off + ((size_t)n + 1) * sizeof(uint32_t));
+    L->off_scan_part = off; off = align256(off + (scan_max / kScanItems + 4) * sizeof(uint32_t));
+    L->off_keys0 = off;     off = align256(off + (size_t)cap * sizeof(uint64_t));
+    L->off_keys1 = off;     off = align256(off + (size_t)cap * sizeof(uint64_t));
+    L->off_vals0 = off;     off = align256(off + (size_t)cap * sizeof(uint32_t));
+    L->off_vals1 = off;     off = align256(off + (size_t)cap * sizeof(uint32_t));
+    L->off_hist = off;      off = align256(off + (size_t)L->hist_len * sizeof(uint32_t));
+    L->off_ranges = off;    off = align256(off + (size_t)L->tiles * 2 * sizeof(uint32_t));
+    L->total = off;
+    return true;
+}
+
+static inline bool aligned16(const void* p) { return p != nullptr && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static bool check_camera(const pbdr_camera* cam)
+{
+    if (!cam) return false;
+    if (cam->width <= 0 || cam->height <= 0 || cam->width > 65536 || cam->height > 65536) return false;
+    if (!(cam->fx > 0.f) || !(cam->fy > 0.f) || !(cam->near_plane > 0.f) || !(cam->far_plane > cam->near_plane)) return false;
+    if (!(cam->radius_clip >= 0.f)) return false;
+    for (int i = 0; i < 9; ++i) if (!std::isfinite(cam->R[i])) return false;
+    for (int i = 0; i < 3; ++i) if (!std::isfinite(cam->t[i])) return false;
+    return std::isfinite(cam->cx) && std::isfinite(cam->cy);
+}
+
+static CamDev to_dev(const pbdr_camera* cam)
+{
+    CamDev c;
+    c.W = cam->width; c.H = cam->height;
+    c.TX = (cam->width + kTile - 1) / kTile; c.TY = (cam->height + kTile - 1) / kTile;
+    c.fx = cam->fx; c.fy = cam->fy; c.cx = cam->cx; c.cy = cam->cy;
+    for (int i = 0; i < 9; ++i) c.R[i] = cam->R[i];
+    for (int i = 0; i < 3; ++i) c.t[i] = cam->t[i];
+    for (int i = 0; i < 3; ++i)   // camera centre = -R^T t, formed in double on the host
+        c.campos[i] = (float)(-((double)cam->R[i] * cam->t[0] + (double)cam->R[3 + i] * cam->t[1] + (double)cam->R[6 + i] * cam->t[2]));
+    c.near_p = cam->near_plane; c.far_p = cam->far_plane; c.radius_clip = cam->radius_clip;
+    c.lim_x = (float)((double)kGuard * 0.5 * cam->width / cam->fx);
+    c.lim_y = (float)((double)kGuard * 0.5 * cam->height / cam->fy);
+    return c;
+}
+
+static bool check_scene(const pbdr_scene* sc)
+{
+    if (!sc || sc->n < 0 || sc->sh_degree < 0 || sc->sh_degree > 3) return false;
+    if (sc->n == 0) return true;
+    return aligned16(sc->mean) && aligned16(sc->log_scale) && aligned16(sc->quat) && aligned16(sc->opacity_logit) && aligned16(sc->sh);
+}
+static bool check_scene_grads(const pbdr_scene_grads* g, const pbdr_scene* sc)
+{
+    if (!g || g->n != sc->n || g->sh_degree != sc->sh_degree) return false;
+    if (g->n == 0) return true;
+    return aligned16(g->mean) && aligned16(g->log_scale) && aligned16(g->quat) && aligned16(g->opacity_logit) && aligned16(g->sh);
+}
+static bool check_splats(const pbdr_splats* sp)
+{
+    if (!sp || sp->n < 0) return false;
+    if (sp->n == 0) return true;
+    return aligned16(sp->mean2d) && aligned16(sp->conic) && aligned16(sp->opacity) && aligned16(sp->color) &&
+           aligned16(sp->radius) && aligned16(sp->depth);
+}
+static bool check_splat_grads(const pbdr_splat_grads* g, int n)
+{
+    if (!g || g->n != n) return false;
+    if (n == 0) return true;
+    return aligned16(g->mean2d) && aligned16(g->conic) && aligned16(g->opacity) && aligned16(g->color);
+}
+
+static SceneDev dev(const pbdr_scene* s) { return SceneDev{s->n, s->sh_degree, s->mean, s->log_scale, s->quat, s->opacity_logit, s->sh}; }
+static SceneGradDev dev(const pbdr_scene_grads* g) { return SceneGradDev{g->mean, g->log_scale, g->quat, g->opacity_logit, g->sh}; }
+static SplatsDev dev(const pbdr_splats* s) { return SplatsDev{s->n, s->mean2d, s->conic, s->opacity, s->color, s->radius, s->depth}; }
+static SplatGradDev dev(const pbdr_splat_grads* g) { return SplatGradDev{g->mean2d, g->conic, g->opacity, g->color}; }
+
+static int hip_result(hipError_t e)
+{
+    if (e == hipSuccess) return PBDR_OK;
+    g_last_hip_error = (int)e;
+    return PBDR_ERR_HIP;
+}
+
+static int workspace_ok(void* ws, size_t bytes, int n, int W, int H, uint64_t cap, Layout* L)
+{
+    if (!make_layout(n, W, H, cap, L)) return PBDR_ERR_INVALID_ARG;
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return PBDR_ERR_INVALID_ARG;
+    if (bytes < L->total) return PBDR_ERR_WORKSPACE_TOO_SMALL;
+    return PBDR_OK;
+}
+
+}  // namespace pbdr
+
+using namespace pbdr;
+
+extern "C" {
+
+int pbdr_version(void) { return PBDR_VERSION; }
+
+int pbdr_last_hip_error(void) { return g_last_hip_error; }
+
+const char* pbdr_status_string(int status)
+{
+    switch (status) {
+        case PBDR_OK: return "ok";
+        case PBDR_ERR_INVALID_ARG: return "invalid argument";
+        case PBDR_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case PBDR_ERR_CAPACITY: return "more (tile, splat) pairs than dup_capacity";
+        case PBDR_ERR_HIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes)
+{
+    Layout L;
+    if (!out_bytes || !make_layout(n, width, height, dup_capacity, &L)) return PBDR_ERR_INVALID_ARG;
+    *out_bytes = L.total;
+    return PBDR_OK;
+}
+
+int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream)
+{
+    if (!check_scene(scene) || !check_camera(cam) || !check_splats(out) || out->n != scene->n) return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_preprocess(dev(scene), to_dev(cam), dev(out), (hipStream_t)hip_stream));
+}
+
+int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t dup_capacity, void* workspace,
+                  size_t workspace_bytes, void* hip_stream)
+{
+    if (!check_splats(splats) || !check_camera(cam)) return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    return hip_result(launch_bin_sort(dev(splats), to_dev(cam), L, (char*)workspace, (hipStream_t)hip_stream));
+}
+
+int pbdr_render_fwd(const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
+                    float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
+{
+    if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(image) || !aligned16(final_T) || !aligned16(last_idx))
+        return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    const CamDev c = to_dev(cam);
+    hipError_t e = launch_bin_sort(dev(splats), c, L, (char*)workspace, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_result(e);
+    return hip_result(launch_composite_fwd(c, L, (char*)workspace, bg, image, final_T, last_idx, (hipStream_t)hip_stream));
+}
+
+int pbdr_preprocess_bwd(const pbdr_scene* scene, const pbdr_camera* cam, const pbdr_splats* splats,
+                        const pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* hip_stream)
+{
+    if (!check_scene(scene) || !check_camera(cam) || !check_splats(splats) || splats->n != scene->n ||
+        !check_splat_grads(g_splats, scene->n) || !check_scene_grads(grads, scene))
+        return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_preprocess_bwd(dev(scene), to_dev(cam), splats->radius, dev(g_splats), dev(grads),
+                                            (hipStream_t)hip_stream));
+}
+
+int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3],
+                    uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                    pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
+{
+    if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) ||
+        !aligned16(dL_dimage) || !check_splat_grads(g_splats, splats->n))
+        return PBDR_ERR_INVALID_ARG;
+    if ((scene == nullptr) != (grads == nullptr)) return PBDR_ERR_INVALID_ARG;
+    if (scene && (!check_scene(scene) || scene->n != splats->n || !check_scene_grads(grads, scene))) return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    const CamDev c = to_dev(cam);
+    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
+                                        (hipStream_t)hip_stream);
+    if (e != hipSuccess || !scene) return hip_result(e);
+    return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), (hipStream_t)hip_stream));
+}
+
+int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                    uint64_t dup_capacity, const uint64_t** keys, const uint32_t** vals, const uint32_t** ranges,
+                    const uint32_t** num_dup)
+{
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    char* ws = (char*)workspace;
+    if (keys) *keys = reinterpret_cast<const uint64_t*>(ws + sorted_keys_off(L));
+    if (vals) *vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
+    if (ranges) *ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
+    if (num_dup) *num_dup = reinterpret_cast<const uint32_t*>(ws + L.off_status) + kStNumDup;
+    return PBDR_OK;
+}
+
+int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                     uint64_t dup_capacity, void* hip_stream, uint64_t* num_dup)
+{
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    uint32_t host[2] = {0, 0};
+    hipError_t e = hipMemcpyAsync(host, (char*)workspace + L.off_status, sizeof(host), hipMemcpyDeviceToHost,
+                                  (hipStream_t)hip_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_result(e);
+    if (num_dup) *num_dup = host[kStNumDup];
+    return (host[kStNumDup] > L.cap) ? PBDR_ERR_CAPACITY : PBDR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,234 @@
+// Tile binning: per-splat tile count + raster record, device prefix sum, key/value duplication, tile ranges.
+// These are the steps between pts_splatting and the per-pixel blend that realise "sorts these view-dependent
+// splats by their distance to the camera plane" (paper Sec. 2.1) per 16x16 tile.  All HBM-bound, integer work.
+#include "pbdr_internal.h"
+
+namespace pbdr {
+
+__device__ __forceinline__ void rect_of(const CamDev& cam, float mx, float my, int r, int& x0, int& y0, int& x1, int& y1)
+{
+    // floor((m - r)/16) == (floor(m) - r) >> 4 because r and 16 are integers: exact in integer arithmetic
+    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
+    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
+    x0 = min(max((ix - r) >> 4, 0), cam.TX);
+    y0 = min(max((iy - r) >> 4, 0), cam.TY);
+    x1 = min(max((ix + r + 15) >> 4, 0), cam.TX);
+    y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+}
+
+// One thread per point: number of tiles its square touches, and the 48-byte raster record.
+__global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, uint32_t* __restrict__ tiles_touched,
+                                                    Packed* __restrict__ packed)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sp.n) return;
+    const size_t N = (size_t)sp.n;
+    const int r = sp.radius[i];
+    uint32_t cnt = 0;
+    if (r > 0) {
+        const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
+        int x0, y0, x1, y1;
+        rect_of(cam, mx, my, r, x0, y0, x1, y1);
+        cnt = (uint32_t)((x1 - x0) * (y1 - y0));
+        float4* dst = reinterpret_cast<float4*>(packed + i);
+        dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
+        dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
+        dst[2] = make_float4(sp.color[2 * N + i], 0.f, 0.f, 0.f);
+    }
+    tiles_touched[i] = cnt;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Exclusive prefix sum over uint32: reduce per 4096-element block, scan the block sums in one
+// workgroup, rescan each block with its offset. No inter-workgroup waiting.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// exclusive scan of one value per thread across a 256-thread block; returns the block total through `total`
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* lds_wave /*[4]*/, uint32_t& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t inc = wave_inclusive_scan(v);
+    if (lane == 63) lds_wave[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t t = lds_wave[w];
+        if (w < wave) base += t;
+    }
+    total = lds_wave[0] + lds_wave[1] + lds_wave[2] + lds_wave[3];
+    __syncthreads();
+    return base + inc - v;
+}
+
+constexpr int kScanPerThread = kScanItems / 256;  // 16
+
+__global__ __launch_bounds__(256) void k_scan_reduce(const uint32_t* __restrict__ in, uint32_t n, uint32_t* __restrict__ partials)
+{
+    __shared__ uint32_t lds[4];
+    const uint32_t base = blockIdx.x * (uint32_t)kScanItems + threadIdx.x * kScanPerThread;
+    uint32_t s = 0;
+    if (base + kScanPerThread <= n) {
+        const uint4* p = reinterpret_cast<const uint4*>(in + base);
+#pragma unroll
+        for (int k = 0; k < kScanPerThread / 4; ++k) { const uint4 v = p[k]; s += v.x + v.y + v.z + v.w; }
+    } else {
+        for (int k = 0; k < kScanPerThread; ++k) if (base + k < n) s += in[base + k];
+    }
+    uint32_t total;
+    (void)block_exclusive_scan_256(s, lds, total);
+    if (threadIdx.x == 0) partials[blockIdx.x] = total;
+}
+
+// one workgroup of 1024 threads scans the `nb` block sums in place (exclusive); writes the grand total
+__global__ __launch_bounds__(1024) void k_scan_partials(uint32_t* __restrict__ partials, uint32_t nb, uint32_t* __restrict__ total_out)
+{
+    __shared__ uint32_t lds[16];
+    __shared__ uint32_t carry_s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (uint32_t start = 0; start < nb; start += 1024) {
+        const uint32_t idx = start + threadIdx.x;
+        const uint32_t v = idx < nb ? partials[idx] : 0u;
+        const uint32_t inc = wave_inclusive_scan(v);
+        if (lane == 63) lds[wave] = inc;
+        __syncthreads();
+        uint32_t base = carry_s, chunk = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { const uint32_t t = lds[w]; if (w < wave) base += t; chunk += t; }
+        if (idx < nb) partials[idx] = base + inc - v;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s += chunk;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { partials[nb] = carry_s; if (total_out) *total_out = carry_s; }
+}
+
+// `in` and `out` may be the same array: every thread reads its 16 elements before it writes them
+__global__ __launch_bounds__(256) void k_scan_apply(const uint32_t* in, uint32_t* out, uint32_t n,
+                                                    const uint32_t* __restrict__ partials)
+{
+    __shared__ uint32_t lds[4];
+    const uint32_t base = blockIdx.x * (uint32_t)kScanItems + threadIdx.x * kScanPerThread;
+    uint32_t v[kScanPerThread];
+    const bool full = base + kScanPerThread <= n;
+    if (full) {
+        const uint4* p = reinterpret_cast<const uint4*>(in + base);
+#pragma unroll
+        for (int k = 0; k < kScanPerThread / 4; ++k) { const uint4 t = p[k]; v[4 * k] = t.x; v[4 * k + 1] = t.y; v[4 * k + 2] = t.z; v[4 * k + 3] = t.w; }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kScanPerThread; ++k) v[k] = (base + k < n) ? in[base + k] : 0u;
+    }
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) s += v[k];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan_256(s, lds, total) + partials[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) { const uint32_t t = v[k]; v[k] = run; run += t; }
+    if (full) {
+        uint4* q = reinterpret_cast<uint4*>(out + base);
+#pragma unroll
+        for (int k = 0; k < kScanPerThread / 4; ++k) q[k] = make_uint4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < kScanPerThread; ++k) if (base + k < n) out[base + k] = v[k];
+    }
+}
+
+hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* partials, uint32_t* total_out,
+                                 hipStream_t s)
+{
+    const uint32_t nb = (n + kScanItems - 1) / kScanItems;
+    if (nb > 0) hipLaunchKernelGGL(k_scan_reduce, dim3(nb), dim3(256), 0, s, in, n, partials);
+    hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, partials, nb, total_out);
+    if (nb > 0) hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(256), 0, s, in, out, n, partials);
+    return hipGetLastError();
+}
+
+// One thread per point: write its (tile << 32 | depth bits, index) pairs, row-major over its tile rectangle.
+__global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ offsets,
+                                                   uint64_t* __restrict__ keys, uint32_t* __restrict__ vals, uint32_t cap,
+                                                   uint32_t* __restrict__ status)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sp.n) return;
+    const int r = sp.radius[i];
+    if (r <= 0) return;
+    const size_t N = (size_t)sp.n;
+    int x0, y0, x1, y1;
+    rect_of(cam, sp.mean2d[i], sp.mean2d[N + i], r, x0, y0, x1, y1);
+    const uint32_t bits = __float_as_uint(sp.depth[i]);
+    uint32_t at = offsets[i];
+    bool dropped = false;
+    for (int ty = y0; ty < y1; ++ty)
+        for (int tx = x0; tx < x1; ++tx) {
+            if (at < cap) {
+                keys[at] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | bits;
+                vals[at] = (uint32_t)i;
+            } else {
+                dropped = true;
+            }
+            ++at;
+        }
+    if (dropped) status[kStOverflow] = 1u;
+}
+
+__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+// One thread per sorted pair: mark where each tile's run starts and ends.
+__global__ __launch_bounds__(256) void k_tile_ranges(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ status,
+                                                     uint32_t cap, uint32_t* __restrict__ ranges)
+{
+    const uint32_t P = min(status[kStNumDup], cap);
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= P) return;
+    const uint32_t tile = (uint32_t)(keys[i] >> 32);
+    if (i == 0 || (uint32_t)(keys[i - 1] >> 32) != tile) ranges[2 * tile] = i;
+    if (i + 1 == P || (uint32_t)(keys[i + 1] >> 32) != tile) ranges[2 * tile + 1] = i + 1;
+}
+
+hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
+{
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
+    Packed* packed = reinterpret_cast<Packed*>(ws + L.off_packed);
+    uint32_t* offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
+    uint32_t* part = reinterpret_cast<uint32_t*>(ws + L.off_scan_part);
+    uint64_t* keys0 = reinterpret_cast<uint64_t*>(ws + L.off_keys0);
+    uint32_t* vals0 = reinterpret_cast<uint32_t*>(ws + L.off_vals0);
+    uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
+    const unsigned nblk = (unsigned)((sp.n + 255) / 256);
+
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
+                       2 * (size_t)L.tiles);
+    if (sp.n > 0) {
+        hipLaunchKernelGGL(k_count_pack, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, packed);
+        hipError_t e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n, part, status + kStNumDup, s);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, keys0, vals0, L.cap, status);
+        e = launch_radix_sort(L, ws, s);
+        if (e != hipSuccess) return e;
+        const uint64_t* sorted = reinterpret_cast<const uint64_t*>(ws + sorted_keys_off(L));
+        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, ranges);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pbdr

@@ -1,0 +1,94 @@
+// Internal declarations shared by the HIP translation units of libpbdr (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace pbdr {
+
+constexpr int kTile = 16;
+constexpr float kBlur = 0.3f;
+constexpr float kAlphaMax = 0.99f;
+constexpr float kAlphaMin = 1.0f / 255.0f;
+constexpr float kTStop = 1e-4f;
+constexpr float kGuard = 1.3f;
+constexpr float kEigFloor = 0.1f;
+constexpr int kRadiusMax = 1 << 20;
+constexpr float kPixMax = 1073741824.0f;
+
+// Camera as the kernels see it (passed by value as a kernel argument -> lives in SGPRs).
+struct CamDev {
+    int W, H, TX, TY;
+    float fx, fy, cx, cy;
+    float R[9];
+    float t[3];
+    float campos[3];
+    float near_p, far_p, radius_clip;
+    float lim_x, lim_y;
+};
+
+// Raster record: everything the compositing kernels need about one splat, gathered with three 16-byte loads.
+struct __attribute__((aligned(16))) Packed {
+    float mx, my, qa, qb;   // mean2d, conic a, b
+    float qc, o, r, g;      // conic c, opacity, red, green
+    float b, pad0, pad1, pad2;
+};
+static_assert(sizeof(Packed) == 48, "raster record is 48 bytes");
+
+struct SceneDev {
+    int n, sh_degree;
+    const float *mean, *log_scale, *quat, *logit, *sh;
+};
+struct SceneGradDev {
+    float *mean, *log_scale, *quat, *logit, *sh;
+};
+struct SplatsDev {
+    int n;
+    float *mean2d, *conic, *opacity, *color;
+    int32_t* radius;
+    float* depth;
+};
+struct SplatGradDev {
+    float *mean2d, *conic, *opacity, *color;
+};
+
+// Status words at the head of the workspace.
+enum { kStNumDup = 0, kStOverflow = 1, kStWords = 64 };
+
+// Workspace layout for (n, W, H, capacity). All offsets are multiples of 256 bytes.
+struct Layout {
+    int n, W, H, TX, TY, tiles;
+    uint32_t cap;
+    int sort_bits, sort_passes;
+    uint32_t sort_blocks;     // blocks of kSortItems pairs covering `cap`
+    uint32_t hist_len;        // 256 * sort_blocks
+    size_t off_status, off_packed, off_offsets, off_scan_part, off_keys0, off_keys1, off_vals0, off_vals1,
+        off_hist, off_ranges, total;
+};
+constexpr int kSortItems = 4096;   // pairs per radix-sort block
+constexpr int kScanItems = 4096;   // elements per scan block
+bool make_layout(int n, int W, int H, uint64_t cap, Layout* L);
+
+// ---- launchers (each enqueues on `s` and returns the launch status) ----
+hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, hipStream_t s);
+hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
+                                 const SceneGradDev& g, hipStream_t s);
+hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
+hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
+                                float* final_T, uint32_t* last_idx, hipStream_t s);
+hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3],
+                                const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                                const SplatGradDev& g2, hipStream_t s);
+
+// exclusive prefix sum of n uint32 (in -> out, may alias), total written to *total_out if non-null.
+// `partials` needs ceil(n / kScanItems) + 1 uint32.
+hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* partials,
+                                 uint32_t* total_out, hipStream_t s);
+// same, but the element count is min(*n_dev_items * mult, n_max) read on the device (grid sized for n_max)
+hipError_t launch_radix_sort(const Layout& L, char* ws, hipStream_t s);
+
+// final location of the sorted lists (depends on the parity of the pass count)
+inline size_t sorted_keys_off(const Layout& L) { return (L.sort_passes & 1) ? L.off_keys1 : L.off_keys0; }
+inline size_t sorted_vals_off(const Layout& L) { return (L.sort_passes & 1) ? L.off_vals1 : L.off_vals0; }
+
+}  // namespace pbdr

@@ -1,0 +1,322 @@
+// Per-point kernels: cull + project + SH colour (pts_culling + pts_splatting, paper Sec. 3.1 / 3.2, Alg. 1
+// lines 2-4) and its derivative (pts_splatting.backward, Alg. 1 lines 22-24).
+//
+// One thread per point, structure-of-arrays planes: a wavefront reads 64 consecutive floats of every
+// attribute (256-byte coalesced segments); the 48 SH planes are only touched by points that survive culling.
+// HBM-bound: 236 B read + 44 B written per surviving point, 12 B + 4 B per point culled by depth.
+#include "pbdr_internal.h"
+
+namespace pbdr {
+
+struct Proj {
+    float s[3], q[4], qinv, Rq[9], A[9], T[6];
+    float px, py, pz, iz, tx, ty;
+    bool tx_free, ty_free;
+    float J00, J02, J11, J12;
+    float a, b, c, det;
+};
+
+__device__ __forceinline__ void quat_rot(const float q[4], float R[9])
+{
+    const float w = q[0], x = q[1], y = q[2], z = q[3];
+    R[0] = 1.f - 2.f * (y * y + z * z); R[1] = 2.f * (x * y - w * z);       R[2] = 2.f * (x * z + w * y);
+    R[3] = 2.f * (x * y + w * z);       R[4] = 1.f - 2.f * (x * x + z * z); R[5] = 2.f * (y * z - w * x);
+    R[6] = 2.f * (x * z - w * y);       R[7] = 2.f * (y * z + w * x);       R[8] = 1.f - 2.f * (x * x + y * y);
+}
+
+// Covariance projection of a point already known to pass the depth test.
+// cov2d = T T^T + blur I with T = J R_cam R_q diag(s): never forms the 3D covariance.
+__device__ __forceinline__ void project_cov(const CamDev& cam, const float ls[3], const float qraw[4], Proj& P)
+{
+#pragma unroll
+    for (int k = 0; k < 3; ++k) P.s[k] = expf(ls[k]);
+    P.qinv = 1.0f / sqrtf(qraw[0] * qraw[0] + qraw[1] * qraw[1] + qraw[2] * qraw[2] + qraw[3] * qraw[3]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) P.q[k] = qraw[k] * P.qinv;
+    quat_rot(P.q, P.Rq);
+    // A = R_cam * Rq * diag(s)
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+            P.A[3 * i + j] = (cam.R[3 * i] * P.Rq[j] + cam.R[3 * i + 1] * P.Rq[3 + j] + cam.R[3 * i + 2] * P.Rq[6 + j]) * P.s[j];
+    P.iz = 1.0f / P.pz;
+    float tx = P.px * P.iz, ty = P.py * P.iz;
+    P.tx_free = (tx <= cam.lim_x) && (tx >= -cam.lim_x);
+    P.ty_free = (ty <= cam.lim_y) && (ty >= -cam.lim_y);
+    tx = fminf(cam.lim_x, fmaxf(-cam.lim_x, tx));
+    ty = fminf(cam.lim_y, fmaxf(-cam.lim_y, ty));
+    P.tx = tx; P.ty = ty;
+    P.J00 = cam.fx * P.iz; P.J02 = -cam.fx * tx * P.iz;
+    P.J11 = cam.fy * P.iz; P.J12 = -cam.fy * ty * P.iz;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        P.T[j] = P.J00 * P.A[j] + P.J02 * P.A[6 + j];
+        P.T[3 + j] = P.J11 * P.A[3 + j] + P.J12 * P.A[6 + j];
+    }
+    const float a0 = P.T[0] * P.T[0] + P.T[1] * P.T[1] + P.T[2] * P.T[2];
+    const float c0 = P.T[3] * P.T[3] + P.T[4] * P.T[4] + P.T[5] * P.T[5];
+    P.b = P.T[0] * P.T[3] + P.T[1] * P.T[4] + P.T[2] * P.T[5];
+    // |T0|^2 |T1|^2 - (T0.T1)^2 = |T0 x T1|^2 : the determinant without the cancellation of a*c - b*b
+    const float xx = P.T[1] * P.T[5] - P.T[2] * P.T[4];
+    const float xy = P.T[2] * P.T[3] - P.T[0] * P.T[5];
+    const float xz = P.T[0] * P.T[4] - P.T[1] * P.T[3];
+    P.a = a0 + kBlur; P.c = c0 + kBlur;
+    P.det = (xx * xx + xy * xy + xz * xz) + kBlur * (a0 + c0) + kBlur * kBlur;
+}
+
+__device__ __forceinline__ void tile_rect(const CamDev& cam, float mx, float my, int r, int& x0, int& y0, int& x1, int& y1)
+{
+    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
+    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
+    x0 = min(max((ix - r) >> 4, 0), cam.TX);
+    y0 = min(max((iy - r) >> 4, 0), cam.TY);
+    x1 = min(max((ix + r + 15) >> 4, 0), cam.TX);
+    y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+}
+
+// Real SH basis, index l*l+l+m, Condon-Shortley phase kept (so l=1 is (-y, z, -x)).
+__device__ __forceinline__ void sh_basis(int deg, float x, float y, float z, float Y[16])
+{
+    Y[0] = 0.28209479177387814f;
+    if (deg < 1) return;
+    Y[1] = -0.4886025119029199f * y; Y[2] = 0.4886025119029199f * z; Y[3] = -0.4886025119029199f * x;
+    if (deg < 2) return;
+    const float xx = x * x, yy = y * y, zz = z * z;
+    Y[4] = 1.0925484305920792f * x * y;
+    Y[5] = -1.0925484305920792f * y * z;
+    Y[6] = 0.31539156525252005f * (2.f * zz - xx - yy);
+    Y[7] = -1.0925484305920792f * x * z;
+    Y[8] = 0.5462742152960396f * (xx - yy);
+    if (deg < 3) return;
+    Y[9] = -0.5900435899266435f * y * (3.f * xx - yy);
+    Y[10] = 2.890611442640554f * x * y * z;
+    Y[11] = -0.4570457994644658f * y * (4.f * zz - xx - yy);
+    Y[12] = 0.3731763325901154f * z * (2.f * zz - 3.f * xx - 3.f * yy);
+    Y[13] = -0.4570457994644658f * x * (4.f * zz - xx - yy);
+    Y[14] = 1.445305721320277f * z * (xx - yy);
+    Y[15] = -0.5900435899266435f * x * (xx - 3.f * yy);
+}
+
+__global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, SplatsDev out)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = (size_t)n;
+    const float m0 = sc.mean[i], m1 = sc.mean[N + i], m2 = sc.mean[2 * N + i];
+    Proj P;
+    P.px = cam.R[0] * m0 + cam.R[1] * m1 + cam.R[2] * m2 + cam.t[0];
+    P.py = cam.R[3] * m0 + cam.R[4] * m1 + cam.R[5] * m2 + cam.t[1];
+    P.pz = cam.R[6] * m0 + cam.R[7] * m1 + cam.R[8] * m2 + cam.t[2];
+    if (!(P.pz >= cam.near_p && P.pz <= cam.far_p)) { out.radius[i] = 0; return; }
+    const float ls[3] = {sc.log_scale[i], sc.log_scale[N + i], sc.log_scale[2 * N + i]};
+    const float qr[4] = {sc.quat[i], sc.quat[N + i], sc.quat[2 * N + i], sc.quat[3 * N + i]};
+    project_cov(cam, ls, qr, P);
+    if (!(P.det > 0.f)) { out.radius[i] = 0; return; }
+    const float idet = 1.0f / P.det;
+    const float mx = cam.fx * P.px * P.iz + cam.cx;
+    const float my = cam.fy * P.py * P.iz + cam.cy;
+    const float mid = 0.5f * (P.a + P.c);
+    // (a-c)^2/4 + b^2 is mid^2 - (a c - b^2) written without cancellation
+    const float hd = 0.5f * (P.a - P.c);
+    const float disc = fmaxf(kEigFloor, hd * hd + P.b * P.b);
+    const float ext = ceilf(3.0f * sqrtf(mid + sqrtf(disc)));
+    const int r = (ext < (float)kRadiusMax) ? (int)ext : kRadiusMax;
+    if ((float)r <= cam.radius_clip) { out.radius[i] = 0; return; }
+    int x0, y0, x1, y1;
+    tile_rect(cam, mx, my, r, x0, y0, x1, y1);
+    if ((x1 - x0) * (y1 - y0) <= 0) { out.radius[i] = 0; return; }
+    // colour
+    const float vx = m0 - cam.campos[0], vy = m1 - cam.campos[1], vz = m2 - cam.campos[2];
+    const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
+    float Y[16];
+    sh_basis(sc.sh_degree, vx * vinv, vy * vinv, vz * vinv, Y);
+    const int K = (sc.sh_degree + 1) * (sc.sh_degree + 1);
+    float rgb[3] = {0.5f, 0.5f, 0.5f};
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * sc.sh[(size_t)(3 * k + c) * N + i];
+    }
+    const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
+    out.mean2d[i] = mx; out.mean2d[N + i] = my;
+    out.conic[i] = P.c * idet; out.conic[N + i] = -P.b * idet; out.conic[2 * N + i] = P.a * idet;
+    out.opacity[i] = o;
+    out.color[i] = fmaxf(rgb[0], 0.f); out.color[N + i] = fmaxf(rgb[1], 0.f); out.color[2 * N + i] = fmaxf(rgb[2], 0.f);
+    out.radius[i] = r;
+    out.depth[i] = P.pz;
+}
+
+// d(colour)/d(direction): partial derivatives of the SH polynomials contracted with the coefficients.
+__device__ __forceinline__ void sh_basis_grad(int deg, float x, float y, float z, float dY[16][3])
+{
+#pragma unroll
+    for (int k = 0; k < 16; ++k) dY[k][0] = dY[k][1] = dY[k][2] = 0.f;
+    if (deg < 1) return;
+    const float c1 = 0.4886025119029199f;
+    dY[1][1] = -c1; dY[2][2] = c1; dY[3][0] = -c1;
+    if (deg < 2) return;
+    const float c2a = 1.0925484305920792f, c2b = 0.31539156525252005f, c2c = 0.5462742152960396f;
+    dY[4][0] = c2a * y; dY[4][1] = c2a * x;
+    dY[5][1] = -c2a * z; dY[5][2] = -c2a * y;
+    dY[6][0] = -2.f * c2b * x; dY[6][1] = -2.f * c2b * y; dY[6][2] = 4.f * c2b * z;
+    dY[7][0] = -c2a * z; dY[7][2] = -c2a * x;
+    dY[8][0] = 2.f * c2c * x; dY[8][1] = -2.f * c2c * y;
+    if (deg < 3) return;
+    const float c3a = 0.5900435899266435f, c3b = 2.890611442640554f, c3c = 0.4570457994644658f,
+                c3d = 0.3731763325901154f, c3e = 1.445305721320277f;
+    const float xx = x * x, yy = y * y, zz = z * z;
+    dY[9][0] = -6.f * c3a * x * y;             dY[9][1] = -3.f * c3a * (xx - yy);
+    dY[10][0] = c3b * y * z;                   dY[10][1] = c3b * x * z;                  dY[10][2] = c3b * x * y;
+    dY[11][0] = 2.f * c3c * x * y;             dY[11][1] = -c3c * (4.f * zz - xx - 3.f * yy); dY[11][2] = -8.f * c3c * y * z;
+    dY[12][0] = -6.f * c3d * x * z;            dY[12][1] = -6.f * c3d * y * z;           dY[12][2] = 3.f * c3d * (2.f * zz - xx - yy);
+    dY[13][0] = -c3c * (4.f * zz - 3.f * xx - yy); dY[13][1] = 2.f * c3c * x * y;        dY[13][2] = -8.f * c3c * x * z;
+    dY[14][0] = 2.f * c3e * x * z;             dY[14][1] = -2.f * c3e * y * z;           dY[14][2] = c3e * (xx - yy);
+    dY[15][0] = -3.f * c3a * (xx - yy);        dY[15][1] = 6.f * c3a * x * y;
+}
+
+__global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ radius,
+                                                        SplatGradDev g2, SceneGradDev g)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    if (radius[i] <= 0) return;
+    const size_t N = (size_t)n;
+    const float m0 = sc.mean[i], m1 = sc.mean[N + i], m2 = sc.mean[2 * N + i];
+    Proj P;
+    P.px = cam.R[0] * m0 + cam.R[1] * m1 + cam.R[2] * m2 + cam.t[0];
+    P.py = cam.R[3] * m0 + cam.R[4] * m1 + cam.R[5] * m2 + cam.t[1];
+    P.pz = cam.R[6] * m0 + cam.R[7] * m1 + cam.R[8] * m2 + cam.t[2];
+    const float ls[3] = {sc.log_scale[i], sc.log_scale[N + i], sc.log_scale[2 * N + i]};
+    const float qr[4] = {sc.quat[i], sc.quat[N + i], sc.quat[2 * N + i], sc.quat[3 * N + i]};
+    project_cov(cam, ls, qr, P);
+    const float idet = 1.0f / P.det;
+    const float qa = P.c * idet, qb = -P.b * idet, qc = P.a * idet;
+
+    // ---- opacity
+    {
+        const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
+        g.logit[i] += g2.opacity[i] * o * (1.f - o);
+    }
+    float dmu0 = 0.f, dmu1 = 0.f, dmu2 = 0.f;
+    // ---- colour: SH coefficients and the view direction
+    {
+        const float vx = m0 - cam.campos[0], vy = m1 - cam.campos[1], vz = m2 - cam.campos[2];
+        const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
+        const float dx = vx * vinv, dy = vy * vinv, dz = vz * vinv;
+        float Y[16];
+        float dY[16][3];
+        sh_basis(sc.sh_degree, dx, dy, dz, Y);
+        sh_basis_grad(sc.sh_degree, dx, dy, dz, dY);
+        const int K = (sc.sh_degree + 1) * (sc.sh_degree + 1);
+        float gd0 = 0.f, gd1 = 0.f, gd2 = 0.f;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            float raw = 0.5f;
+            float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+            for (int k = 0; k < K; ++k) {
+                const float co = sc.sh[(size_t)(3 * k + c) * N + i];
+                raw += Y[k] * co;
+                t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
+            }
+            const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
+            if (gc != 0.f) {
+                for (int k = 0; k < K; ++k) g.sh[(size_t)(3 * k + c) * N + i] += Y[k] * gc;
+            }
+            gd0 += gc * t0; gd1 += gc * t1; gd2 += gc * t2;
+        }
+        const float dot = gd0 * dx + gd1 * dy + gd2 * dz;
+        dmu0 += (gd0 - dx * dot) * vinv; dmu1 += (gd1 - dy * dot) * vinv; dmu2 += (gd2 - dz * dot) * vinv;
+    }
+    // ---- conic -> cov2d:  G = -Q G_Q Q with G_Q = [[ga, gb/2],[gb/2, gc]]
+    float G00, G01, G11;
+    {
+        const float ga = g2.conic[i], gb = 0.5f * g2.conic[N + i], gc = g2.conic[2 * N + i];
+        const float u00 = qa * ga + qb * gb, u01 = qa * gb + qb * gc;
+        const float u10 = qb * ga + qc * gb, u11 = qb * gb + qc * gc;
+        G00 = -(u00 * qa + u01 * qb);
+        G01 = -(u00 * qb + u01 * qc);
+        G11 = -(u10 * qb + u11 * qc);
+    }
+    // ---- cov2d = T T^T:  G_T = 2 G T
+    float GT[6];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        GT[j] = 2.f * (G00 * P.T[j] + G01 * P.T[3 + j]);
+        GT[3 + j] = 2.f * (G01 * P.T[j] + G11 * P.T[3 + j]);
+    }
+    // ---- T = J A
+    const float GJ00 = GT[0] * P.A[0] + GT[1] * P.A[1] + GT[2] * P.A[2];
+    const float GJ02 = GT[0] * P.A[6] + GT[1] * P.A[7] + GT[2] * P.A[8];
+    const float GJ11 = GT[3] * P.A[3] + GT[4] * P.A[4] + GT[5] * P.A[5];
+    const float GJ12 = GT[3] * P.A[6] + GT[4] * P.A[7] + GT[5] * P.A[8];
+    float GA[9];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        GA[j] = P.J00 * GT[j];
+        GA[3 + j] = P.J11 * GT[3 + j];
+        GA[6 + j] = P.J02 * GT[j] + P.J12 * GT[3 + j];
+    }
+    // ---- J and mean2d as functions of the camera-space position
+    float dp0, dp1, dp2;
+    {
+        const float iz = P.iz, iz2 = iz * iz;
+        const float gmx = g2.mean2d[i], gmy = g2.mean2d[N + i];
+        const float gtx = -cam.fx * iz * GJ02, gty = -cam.fy * iz * GJ12;
+        dp2 = (-cam.fx * GJ00 + cam.fx * P.tx * GJ02 - cam.fy * GJ11 + cam.fy * P.ty * GJ12) * iz2;
+        dp0 = gmx * cam.fx * iz; dp1 = gmy * cam.fy * iz;
+        dp2 -= (gmx * cam.fx * P.px + gmy * cam.fy * P.py) * iz2;
+        if (P.tx_free) { dp0 += gtx * iz; dp2 -= gtx * P.px * iz2; }
+        if (P.ty_free) { dp1 += gty * iz; dp2 -= gty * P.py * iz2; }
+    }
+    dmu0 += cam.R[0] * dp0 + cam.R[3] * dp1 + cam.R[6] * dp2;
+    dmu1 += cam.R[1] * dp0 + cam.R[4] * dp1 + cam.R[7] * dp2;
+    dmu2 += cam.R[2] * dp0 + cam.R[5] * dp1 + cam.R[8] * dp2;
+    g.mean[i] += dmu0; g.mean[N + i] += dmu1; g.mean[2 * N + i] += dmu2;
+    // ---- A = R_cam W, W = Rq diag(s)
+    float GRq[9];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        float gs = 0.f;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const float gw = cam.R[r] * GA[j] + cam.R[3 + r] * GA[3 + j] + cam.R[6 + r] * GA[6 + j];
+            gs += gw * P.Rq[3 * r + j];
+            GRq[3 * r + j] = gw * P.s[j];
+        }
+        g.log_scale[(size_t)j * N + i] += gs * P.s[j];
+    }
+    // ---- Rq as a function of the unit quaternion, then the normalisation
+    {
+        const float w = P.q[0], x = P.q[1], y = P.q[2], z = P.q[3];
+        const float* G = GRq;
+        float gq[4];
+        gq[0] = 2.f * (-z * G[1] + y * G[2] + z * G[3] - x * G[5] - y * G[6] + x * G[7]);
+        gq[1] = 2.f * (y * G[1] + z * G[2] + y * G[3] - 2.f * x * G[4] - w * G[5] + z * G[6] + w * G[7] - 2.f * x * G[8]);
+        gq[2] = 2.f * (-2.f * y * G[0] + x * G[1] + w * G[2] + x * G[3] + z * G[5] - w * G[6] + z * G[7] - 2.f * y * G[8]);
+        gq[3] = 2.f * (-2.f * z * G[0] - w * G[1] + x * G[2] + w * G[3] - 2.f * z * G[4] + y * G[5] + x * G[6] + y * G[7]);
+        const float dot = gq[0] * w + gq[1] * x + gq[2] * y + gq[3] * z;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) g.quat[(size_t)k * N + i] += (gq[k] - P.q[k] * dot) * P.qinv;
+    }
+}
+
+hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    hipLaunchKernelGGL(k_preprocess, dim3(blocks), dim3(256), 0, s, sc, cam, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
+                                 const SceneGradDev& g, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    hipLaunchKernelGGL(k_preprocess_bwd, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g);
+    return hipGetLastError();
+}
+
+}  // namespace pbdr

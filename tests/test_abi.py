@@ -1,0 +1,67 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared symbol, sizes
+workspaces sensibly and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2512_20017_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "pbdr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pbdr_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    L = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(L, n) is not None
+    assert B.pbdr_version() == 100
+
+
+def test_workspace_bytes():
+    small = B.pbdr_workspace_bytes(4096, 128, 128, 20000)
+    big = B.pbdr_workspace_bytes(1_000_000, 1920, 1080, 8_000_000)
+    assert 0 < small < big
+    assert big % 256 == 0
+    # dominated by 48 B/point + 24 B/pair
+    assert abs(big - (48e6 + 24 * 8e6)) < 0.1 * big
+    with pytest.raises(B.PbdrError):
+        B.pbdr_workspace_bytes(-1, 128, 128, 10)
+    with pytest.raises(B.PbdrError):
+        B.pbdr_workspace_bytes(10, 0, 128, 10)
+    with pytest.raises(B.PbdrError):
+        B.pbdr_workspace_bytes(10, 128, 128, 1 << 40)
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    L = B.lib()
+    cam = B.camera_struct(dict(width=64, height=64, fx=50, fy=50, cx=32, cy=32, R=[1, 0, 0, 0, 1, 0, 0, 0, 1], t=[0, 0, 3]))
+    sc = B.CScene(-5, 0, None, None, None, None, None)
+    sp = B.CSplats(-5, None, None, None, None, None, None)
+    assert L.pbdr_preprocess(C.byref(sc), C.byref(cam), C.byref(sp), None) == B.PBDR_ERR_INVALID_ARG
+    sc = B.CScene(8, 7, None, None, None, None, None)      # bad SH degree
+    sp = B.CSplats(8, None, None, None, None, None, None)
+    assert L.pbdr_preprocess(C.byref(sc), C.byref(cam), C.byref(sp), None) == B.PBDR_ERR_INVALID_ARG
+    sc = B.CScene(8, 0, 16, 16, 16, 16, 16)                  # null splat outputs
+    assert L.pbdr_preprocess(C.byref(sc), C.byref(cam), C.byref(sp), None) == B.PBDR_ERR_INVALID_ARG
+    sc = B.CScene(8, 0, 20, 16, 16, 16, 16)                  # misaligned pointer
+    sp = B.CSplats(8, 16, 16, 16, 16, 16, 16)
+    assert L.pbdr_preprocess(C.byref(sc), C.byref(cam), C.byref(sp), None) == B.PBDR_ERR_INVALID_ARG
+    bad = B.camera_struct(dict(width=64, height=64, fx=50, fy=50, cx=32, cy=32, R=[1, 0, 0, 0, 1, 0, 0, 0, 1], t=[0, 0, 3], near=0.0))
+    sc = B.CScene(8, 0, 16, 16, 16, 16, 16)
+    assert L.pbdr_preprocess(C.byref(sc), C.byref(bad), C.byref(sp), None) == B.PBDR_ERR_INVALID_ARG
+    # workspace too small / misaligned
+    bg = (C.c_float * 3)(0, 0, 0)
+    assert L.pbdr_render_fwd(C.byref(sp), C.byref(cam), bg, C.c_uint64(100), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16),
+                             C.c_void_p(256), C.c_size_t(64), None) == B.PBDR_ERR_WORKSPACE_TOO_SMALL
+    assert L.pbdr_render_fwd(C.byref(sp), C.byref(cam), bg, C.c_uint64(100), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16),
+                             C.c_void_p(272), C.c_size_t(1 << 30), None) == B.PBDR_ERR_INVALID_ARG
+    assert B.lib().pbdr_status_string(C.c_int(-2)).decode() == "workspace too small"

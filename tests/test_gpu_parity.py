@@ -1,0 +1,202 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, same seeded inputs.
+
+Staging (because fp32 and fp64 cannot agree on knife-edge integer decisions):
+  A. preprocess: GPU fp32 vs oracle fp64 with tolerances; visibility and extent exact except where the oracle flags
+     the decision as within 1e-3 of flipping.
+  B. tile lists: bit-exact, oracle binning fed with the GPU's own fp32 (mean2d, radius, depth).
+  C. compositing forward/backward: oracle fed with the GPU's fp32 splat state and the (identical) lists; image within
+     1e-4 absolute, gradients within 1e-3 relative + floor; pixels the oracle flags as fragile are excluded and counted.
+  D. splatting backward: oracle fed with the same splat-state gradient.
+  E. end to end from raw parameters on the tiny benchmark configuration.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_pipeline import GpuView
+from helpers import to_f64
+from paper_2512_20017_amd import binding as B
+from paper_2512_20017_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+BG = [0.1, 0.3, 0.2]
+IMG_ATOL = 1e-4
+GRAD_RTOL = 1e-3
+
+
+def _state64(sp):
+    return {k: sp[k].astype(np.float64) for k in ("mean2d", "conic", "opacity", "color")} | {"radius": sp["radius"]}
+
+
+def _grad_close(name, got, ref, scale_floor=1e-5):
+    """|got - ref| <= 1e-3 |ref| + floor, floor = 1e-5 x the largest reference magnitude of that attribute."""
+    ref = np.asarray(ref, dtype=np.float64); got = np.asarray(got, dtype=np.float64)
+    floor = scale_floor * max(np.abs(ref).max(), 1e-30)
+    bad = np.abs(got - ref) > GRAD_RTOL * np.abs(ref) + floor
+    assert not bad.any(), (name, int(bad.sum()), float(np.abs(got - ref).max()), float(np.abs(ref).max()))
+
+
+CASES = [
+    ("tiny_cfg1", lambda: (synth.scene_tiny(0), synth.camera_tiny())),
+    ("deg3_ragged", lambda: (synth.random_small_scene(11, 600, 3, spread=1.2, ls_mu=-2.6),
+                             synth.pinhole(200, 120, 60.0, *synth.look_at([0.4, 0.3, -3.0], [0, 0, 0], [0, 1, 0])))),
+    ("deg2_ragged", lambda: (synth.random_small_scene(12, 300, 2, spread=0.9),
+                             synth.pinhole(75, 51, 50.0, np.eye(3), [0.0, 0.1, 2.6]))),
+    ("deg1_dense", lambda: (synth.random_small_scene(13, 2000, 1, spread=0.5, ls_mu=-2.0),
+                            synth.pinhole(64, 64, 50.0, np.eye(3), [0.0, 0.0, 2.0]))),
+]
+
+
+@pytest.fixture(scope="module", params=CASES, ids=[c[0] for c in CASES])
+def case(request):
+    sc, cam = request.param[1]()
+    n = sc["mean"].shape[0]
+    scene = B.Scene.from_numpy(sc)
+    ref = oracle.preprocess(to_f64(sc), cam)
+    view = GpuView(n, cam, 1)          # capacity fixed below once the GPU's own pair count is known
+    sp = view.preprocess(scene)
+    lists = oracle.bin_sort(sp["mean2d"].astype(np.float64), sp["radius"], sp["depth"], cam["width"], cam["height"])
+    view = GpuView(n, cam, max(lists["P"], 1))
+    view.preprocess(scene)
+    return dict(sc=sc, cam=cam, scene=scene, ref=ref, view=view, sp=sp, lists=lists, n=n)
+
+
+def test_preprocess_matches_oracle(case):
+    sp, ref = case["sp"], case["ref"]
+    tie = ref["near_tie"] != 0
+    assert tie.mean() < 0.05
+    assert np.array_equal(sp["radius"][~tie], ref["radius"][~tie])
+    vis = (ref["radius"] > 0) & (sp["radius"] > 0)
+    assert vis.sum() > 0.5 * (ref["radius"] > 0).sum()
+    np.testing.assert_allclose(sp["mean2d"][vis], ref["mean2d"][vis], rtol=2e-6, atol=2e-4)
+    np.testing.assert_allclose(sp["depth"][vis], ref["depth"][vis], rtol=2e-6)
+    np.testing.assert_allclose(sp["opacity"][vis], ref["opacity"][vis], rtol=1e-5)
+    np.testing.assert_allclose(sp["color"][vis], ref["color"][vis], rtol=1e-5, atol=2e-6)
+    scale = np.abs(ref["conic"][vis]).max(axis=1, keepdims=True)
+    assert (np.abs(sp["conic"][vis] - ref["conic"][vis]) <= 1e-4 * scale).all()
+
+
+def test_tile_lists_bit_exact(case):
+    view = case["view"]
+    B.pbdr_bin_sort(view.splats, case["cam"], view.cap, view.ws)
+    got = view.lists()
+    ref = case["lists"]
+    assert got["P_raw"] == ref["P"]
+    assert np.array_equal(got["keys"], ref["keys"])
+    assert np.array_equal(got["vals"], ref["vals"])
+    assert np.array_equal(got["ranges"], ref["ranges"])
+    n_dup, over = B.pbdr_query_lists(view.ws, view.n, view.W, view.H, view.cap)
+    assert n_dup == ref["P"] and not over
+
+
+def test_composite_forward_matches_oracle(case):
+    view, cam = case["view"], case["cam"]
+    got = view.render_fwd(BG)
+    ref = oracle.render_fwd(_state64(case["sp"]), case["lists"], cam["width"], cam["height"], BG)
+    ok = ref["fragile"] == 0
+    assert (~ok).mean() < 1e-3
+    assert np.abs(got["image"] - ref["image"])[ok].max() <= IMG_ATOL
+    assert np.abs(got["final_T"] - ref["final_T"])[ok].max() <= IMG_ATOL
+    assert np.array_equal(got["last_idx"][ok], ref["last_idx"][ok])
+    assert ref["n_blend"] > 0
+    case["fwd_ref"] = ref
+
+
+def test_composite_backward_matches_oracle(case):
+    view, cam = case["view"], case["cam"]
+    W, H = cam["width"], cam["height"]
+    fwd = view.render_fwd(BG)
+    ref_f = oracle.render_fwd(_state64(case["sp"]), case["lists"], W, H, BG)
+    G = np.random.default_rng(3).normal(size=(H, W, 3)).astype(np.float32)
+    G[ref_f["fragile"] != 0] = 0.0           # knife-edge pixels carry no loss in this test
+    G[fwd["last_idx"] != ref_f["last_idx"]] = 0.0
+    got = view.render_bwd(BG, G)
+    ref = oracle.render_bwd(_state64(case["sp"]), case["lists"], W, H, BG, G.astype(np.float64))
+    vis = case["sp"]["radius"] > 0
+    for k in ("mean2d", "conic", "opacity", "color"):
+        _grad_close(k, got[k][vis], ref[k][vis])
+    assert np.abs(ref["mean2d"]).max() > 0
+
+
+def test_splatting_backward_matches_oracle(case):
+    sc, cam, n = case["sc"], case["cam"], case["n"]
+    rng = np.random.default_rng(4)
+    vis = case["sp"]["radius"] > 0
+    d = dict(mean2d=rng.normal(size=(n, 2)), conic=rng.normal(size=(n, 3)) * 10, opacity=rng.normal(size=n),
+             color=rng.normal(size=(n, 3)))
+    d = {k: v.astype(np.float32) for k, v in d.items()}
+    tie = case["ref"]["near_tie"] != 0
+    both = vis & (case["ref"]["radius"] > 0) & ~tie
+    ref = oracle.preprocess_bwd(to_f64(sc), cam, {k: v.astype(np.float64) for k, v in d.items()})
+    grads = case["scene"].zeros_like()
+    B.pbdr_preprocess_bwd(case["scene"], cam, case["view"].splats, B.SplatGrads.from_numpy(d), grads)
+    torch.cuda.synchronize()
+    got = grads.to_numpy()
+    for k in ("mean", "log_scale", "quat", "logit", "sh"):
+        _grad_close(k, got[k][both], ref[k][both], scale_floor=2e-5)
+    # culled points receive nothing
+    for k in ("mean", "log_scale", "quat", "logit", "sh"):
+        assert (got[k][~vis] == 0).all()
+
+
+def test_end_to_end_matches_oracle(case):
+    """Raw parameters -> image -> L1 loss against a seeded target -> parameter gradients, all on the GPU, against
+    the all-fp64 oracle. Pixels whose tile holds a splat with a flagged knife-edge decision are excluded."""
+    sc, cam, view, scene = case["sc"], case["cam"], case["view"], case["scene"]
+    W, H = cam["width"], cam["height"]
+    view.preprocess(scene)
+    got = view.render_fwd(BG)
+    ref = oracle.forward(to_f64(sc), cam, BG, splat_dtype=np.float64)
+    # tiles touched by near-tie splats, or where GPU and oracle lists differ (depth ties in fp32), are fragile
+    lists_g = view.lists()
+    frag = ref["fragile"] != 0
+    TX = (W + 15) // 16
+    same_lists = np.array_equal(lists_g["vals"], ref["lists"]["vals"]) and np.array_equal(lists_g["ranges"], ref["lists"]["ranges"])
+    if not same_lists:
+        for t in range(lists_g["ranges"].shape[0]):
+            a = lists_g["vals"][lists_g["ranges"][t, 0]:lists_g["ranges"][t, 1]]
+            b = ref["lists"]["vals"][ref["lists"]["ranges"][t, 0]:ref["lists"]["ranges"][t, 1]]
+            if not np.array_equal(a, b):
+                ty, tx = divmod(t, TX)
+                frag[16 * ty:16 * ty + 16, 16 * tx:16 * tx + 16] = True
+    assert frag.mean() < 0.05
+    ok = ~frag
+    assert np.abs(got["image"] - ref["image"])[ok].max() <= IMG_ATOL
+    # loss: mean L1 against a seeded target (the benchmark configuration's loss)
+    tgt = synth.target_image(0, W, H).astype(np.float64)
+    G = np.sign(ref["image"] - tgt) / (3.0 * W * H)
+    G[frag] = 0.0
+    G[np.abs(ref["image"] - tgt) < 1e-3] = 0.0   # sign() of a near-zero residual is itself a knife edge
+    if not same_lists:
+        pytest.skip("tile lists differ between fp32 and fp64 depth ordering; gradient compared in the staged tests")
+    grads = scene.zeros_like()
+    view.render_bwd(BG, G.astype(np.float32), scene=scene, grads=grads)
+    gg = grads.to_numpy()
+    rg = oracle.backward(to_f64(sc), cam, BG, ref, G)
+    for k in ("mean", "log_scale", "quat", "logit", "sh"):
+        assert np.abs(gg[k] - rg[k]).max() <= GRAD_RTOL * np.abs(rg[k]).max() + 1e-5, k   # contract as stated
+        _grad_close(k, gg[k], rg[k], scale_floor=1e-4)                                     # and scale-free
+
+
+def test_gradients_accumulate_over_views():
+    sc = synth.random_small_scene(21, 400, 2, spread=0.8)
+    cams = [synth.pinhole(96, 64, 55.0, *synth.look_at(e, [0, 0, 0], [0, 1, 0])) for e in ([0.2, 0.1, -2.5], [2.0, 0.5, -1.5])]
+    scene = B.Scene.from_numpy(sc)
+    total = scene.zeros_like()
+    singles = []
+    rng = np.random.default_rng(0)
+    for cam in cams:
+        view = GpuView(400, cam, 200000)
+        view.preprocess(scene)
+        view.render_fwd(BG)
+        G = rng.normal(size=(64, 96, 3)).astype(np.float32)
+        one = scene.zeros_like()
+        view.render_bwd(BG, G, scene=scene, grads=one)
+        view.render_bwd(BG, G, scene=scene, grads=total)
+        singles.append(one.to_numpy())
+    tot = total.to_numpy()
+    for k in ("mean", "log_scale", "quat", "logit", "sh"):
+        s = singles[0][k].astype(np.float64) + singles[1][k]
+        np.testing.assert_allclose(tot[k], s, rtol=1e-4, atol=1e-5 * np.abs(s).max())
