@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the splatting hot path on one MI355X.
+
+A step = one pass of the whole per-view path over one synthetic view, inputs resident in HBM:
+    zero the parameter-gradient buffer -> pbdr_preprocess -> pbdr_render_fwd -> pbdr_render_bwd
+on the 1M-Gaussian / SH degree 3 / 1920x1080 configuration (fwd+bwd views per second).  dL/dimage is the gradient of
+a mean-L1 loss against a seeded target, computed once from the warm-up image (the loss itself is harness, not path).
+
+Prints ONE JSON line with the contract fields plus `roofline` (dominant kernel, timed live with HIP events recorded
+on the launch stream inside the timed region) and `cpu_baseline` (the CPU oracle timed on the host cores).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# published MI355X peaks
+HBM_PEAK_GBS = 8000.0
+# fp32 vector FMA without packed math (the library is built with packed fp32 disabled):
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
+ALU_PEAK_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
+
+# algorithmic work per unit (stated in the design doc)
+FWD_FLOPS_PER_EXAMINED = 12.0    # 2 sub, 8 for the quadratic form, exp, opacity mul (+ min / compares not counted)
+FWD_FLOPS_PER_BLENDED = 9.0      # 1-alpha, T', w, 3 fma
+BWD_FLOPS_PER_EXAMINED = 12.0    # alpha recomputed
+BWD_FLOPS_PER_BLENDED = 53.0     # 44 for the per-pair gradient terms + 9 lane-sum adds
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mid", choices=["mid", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2512_20017_amd import binding as B
+    from paper_2512_20017_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+
+    if args.workload == "mid":
+        sc = synth.scene_mid(args.seed)
+        cam = synth.cameras_sphere()[0]
+        wl = "mid: 1M Gaussians, SH degree 3, 1920x1080, camera 0 of 16 on a radius-15 sphere"
+    else:
+        sc = synth.scene_tiny(args.seed)
+        cam = synth.camera_tiny()
+        wl = "tiny: 4096 Gaussians, SH degree 0, 128x128"
+    n = int(sc["mean"].shape[0])
+    W, H = cam["width"], cam["height"]
+    bg = [0.0, 0.0, 0.0]
+    scene = B.Scene.from_numpy(sc)
+    splats = B.Splats.empty(n)
+    g_splats = B.SplatGrads.empty(n)
+    grads = scene.zeros_like()
+    image = torch.empty((3, H, W), device="cuda")
+    final_T = torch.empty((H, W), device="cuda")
+    last_idx = torch.empty((H, W), dtype=torch.int32, device="cuda")
+
+    # ---- size the pair capacity from one untimed pass
+    cap = max(16 * n, 1 << 16)
+    ws = B.alloc_workspace(n, W, H, cap)
+    B.pbdr_preprocess(scene, cam, splats)
+    B.pbdr_bin_sort(splats, cam, cap, ws)
+    P, over = B.pbdr_query_lists(ws, n, W, H, cap)
+    assert not over
+    del ws
+    cap = int(P * 1.25) + 4096
+    ws = B.alloc_workspace(n, W, H, cap)
+    B.pbdr_render_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
+    torch.cuda.synchronize()
+    target = torch.from_numpy(np.ascontiguousarray(synth.target_image(args.seed, W, H).transpose(2, 0, 1))).cuda()
+    dL = (torch.sign(image - target) / float(3 * W * H)).contiguous()
+    n_vis = int((splats.radius > 0).sum().item())
+    examined, blended = B.pbdr_render_stats(cam, n, cap, ws)
+    sum_last = int(last_idx.to(torch.int64).sum().item())
+
+    def step():
+        for t in (grads.mean, grads.log_scale, grads.quat, grads.logit, grads.sh):
+            t.zero_()
+        B.pbdr_preprocess(scene, cam, splats)
+        B.pbdr_render_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
+        B.pbdr_render_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
+
+    names = B.profile_kernel_names()
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- untimed profiling pass over every kernel: which one dominates?
+    prof_steps = 3
+    B.pbdr_profile_begin((1 << len(names)) - 1, 256 * prof_steps)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    per_kernel = {}
+    for kid, name in enumerate(names):
+        ms, cnt = B.pbdr_profile_collect(kid)
+        if cnt:
+            per_kernel[name] = dict(ms_per_step=ms / prof_steps, launches_per_step=cnt / prof_steps)
+    B.pbdr_profile_end()
+    dominant = max(per_kernel, key=lambda k: per_kernel[k]["ms_per_step"])
+    dom_id = names.index(dominant)
+
+    # ---- timed region: K steps, only the dominant kernel carries events
+    B.pbdr_profile_begin(1 << dom_id, 64 * args.steps + 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_cnt = B.pbdr_profile_collect(dom_id)
+    B.pbdr_profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    views_per_s = args.steps / (t1 - t0)
+    dom_avg_ms = dom_ms / max(dom_cnt, 1)
+
+    # ---- roofline of the dominant kernel
+    K = (scene.sh_degree + 1) ** 2
+    hbm_bytes = {
+        "k_preprocess": 16.0 * n + (32.0 + 12.0 * K + 40.0) * n_vis,
+        "k_count_pack": 8.0 * n + (36.0 + 48.0) * n_vis,
+        "k_duplicate": 8.0 * n + 16.0 * n_vis + 12.0 * P,
+        "k_radix_hist": 8.0 * P,
+        "k_radix_scatter": 24.0 * P,
+        "k_tile_ranges": 8.0 * P,
+        "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K + 2 * (44.0 + 12.0 * K)) * n_vis,
+    }
+    alu_flops = {
+        "k_composite_fwd": FWD_FLOPS_PER_EXAMINED * examined + FWD_FLOPS_PER_BLENDED * blended,
+        "k_composite_bwd": BWD_FLOPS_PER_EXAMINED * sum_last + BWD_FLOPS_PER_BLENDED * blended,
+    }
+    if dominant in alu_flops:
+        ach = alu_flops[dominant] / (dom_avg_ms * 1e-3) / 1e12
+        roofline = dict(kernel=dominant, bound="alu", achieved=ach, peak=ALU_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=ach / ALU_PEAK_TFLOPS, traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt,
+                        flops_per_launch=alu_flops[dominant])
+    elif dominant in hbm_bytes:
+        ach = hbm_bytes[dominant] / (dom_avg_ms * 1e-3) / 1e9
+        roofline = dict(kernel=dominant, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=ach / HBM_PEAK_GBS, traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt,
+                        bytes_per_launch=hbm_bytes[dominant])
+    else:
+        roofline = dict(kernel=dominant, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None,
+                        traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt)
+    for name, rec in per_kernel.items():
+        t = rec["ms_per_step"] / max(rec["launches_per_step"], 1) * 1e-3
+        if name in alu_flops:
+            rec["tflops"] = alu_flops[name] / t / 1e12
+        elif name in hbm_bytes:
+            lp = rec["launches_per_step"]
+            rec["gbs"] = hbm_bytes[name] / (rec["ms_per_step"] / lp * 1e-3) / 1e9
+
+    # ---- CPU oracle on the host cores: one full view of the same workload (forward + backward)
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sp = splats.to_numpy()
+        t_c0 = time.perf_counter()
+        o_sp = oracle.preprocess(sc, cam)
+        st = {k: o_sp[k].astype(np.float32).astype(np.float64) for k in ("mean2d", "conic", "opacity", "color")}
+        st["radius"] = o_sp["radius"]
+        lists = oracle.bin_sort(st["mean2d"], st["radius"], o_sp["depth"].astype(np.float32), W, H)
+        o_f = oracle.render_fwd(st, lists, W, H, bg)
+        G = dL.permute(1, 2, 0).contiguous().cpu().numpy().astype(np.float64)
+        o_b = oracle.render_bwd(st, lists, W, H, bg, G)
+        oracle.preprocess_bwd(sc, cam, o_b)
+        t_c1 = time.perf_counter()
+        cpu = dict(value=1.0 / (t_c1 - t_c0), unit="views/s", cores=oracle.num_threads(), kind="oracle",
+                   sample="1 full view (forward + backward) of the same workload, fp64, OpenMP",
+                   seconds=t_c1 - t_c0)
+        # staged parity at full size: oracle compositing fed with the GPU's own fp32 splats
+        stg = {k: sp[k].astype(np.float64) for k in ("mean2d", "conic", "opacity", "color")}
+        stg["radius"] = sp["radius"]
+        lg = oracle.bin_sort(stg["mean2d"], stg["radius"], sp["depth"], W, H)
+        rf = oracle.render_fwd(stg, lg, W, H, bg)
+        got = image.permute(1, 2, 0).cpu().numpy()
+        ok = rf["fragile"] == 0
+        parity = dict(max_abs_image_err=float(np.abs(got - rf["image"])[ok].max()), fragile_pixels=int((~ok).sum()),
+                      pairs_oracle=int(lg["P"]), pairs_gpu=int(P), examined_oracle=int(rf["n_eval"]),
+                      examined_gpu=int(examined), blended_oracle=int(rf["n_blend"]), blended_gpu=int(blended),
+                      last_idx_mismatch=int((last_idx.cpu().numpy().astype(np.uint32) != rf["last_idx"])[ok].sum()))
+
+    out = {
+        "metric": "fwd+bwd views/sec at 1080p, 1M Gaussians" if args.workload == "mid" else "fwd+bwd views/sec",
+        "value": views_per_s, "unit": "views/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl, "n_gaussians": n, "width": W, "height": H, "sh_degree": scene.sh_degree,
+                   "visible": n_vis, "tile_pairs": int(P), "pairs_examined_fwd": int(examined),
+                   "pairs_examined_bwd": sum_last, "pairs_blended": int(blended), "seed": args.seed},
+        "mpixel_per_s": views_per_s * W * H / 1e6,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": per_kernel,
+        "parity": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

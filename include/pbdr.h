@@ -151,6 +151,24 @@ int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t 
 int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
                      uint64_t dup_capacity, void* hip_stream, uint64_t* num_dup);
 
+/* Measurement aid, not part of the hot path: counts, for the lists now in the workspace, the (pixel, splat) pairs a
+ * forward pass examines (every list entry up to and including the one that ends the pixel) and the pairs it blends.
+ * counters: device pointer to 2 uint64 {examined, blended}, overwritten. */
+int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/* Optional per-kernel timing for benchmarks, with HIP events recorded on the stream each kernel is launched on.
+ * kernel_mask: bit i enables kernel id i (ids 0 .. pbdr_profile_kernel_count()-1, names from
+ * pbdr_profile_kernel_name). At most max_records launches are timed between begin/reset and collect.
+ * collect synchronises the recorded events and returns the summed duration and number of records of one kernel id.
+ * Process-global and not thread-safe; creates HIP events (host objects), no device memory. */
+int pbdr_profile_begin(uint32_t kernel_mask, int32_t max_records);
+int pbdr_profile_collect(int32_t kernel_id, double* total_ms, int32_t* records);
+int pbdr_profile_reset(void);
+int pbdr_profile_end(void);
+const char* pbdr_profile_kernel_name(int32_t kernel_id);
+int pbdr_profile_kernel_count(void);
+
 const char* pbdr_status_string(int status);
 int pbdr_last_hip_error(void); /* hipError_t of the most recent PBDR_ERR_HIP on this thread */
 int pbdr_version(void);

@@ -84,7 +84,7 @@ def tile_rect(mx, my, radius, width, height):
     return r
 
 
-def preprocess(scene: dict, cam: dict, tau: float = 1e-3) -> dict:
+def preprocess(scene: dict, cam: dict, tau: float = 2e-5) -> dict:
     """Cull + project + colour for one view. Returns the Table 3a state plus rect, cov2d, near_tie."""
     n = int(scene["mean"].shape[0])
     deg = int(scene["sh_degree"])

@@ -24,7 +24,8 @@ PBDR_ERR_HIP = -4
 
 EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_render_fwd", "pbdr_render_bwd",
            "pbdr_preprocess_bwd", "pbdr_lists_view", "pbdr_query_lists", "pbdr_status_string", "pbdr_last_hip_error",
-           "pbdr_version")
+           "pbdr_version", "pbdr_render_stats", "pbdr_profile_begin", "pbdr_profile_collect", "pbdr_profile_reset",
+           "pbdr_profile_end", "pbdr_profile_kernel_name", "pbdr_profile_kernel_count")
 
 _f = C.POINTER(C.c_float)
 
@@ -61,6 +62,7 @@ def lib():
             raise RuntimeError(f"{LIB_PATH} not found: build it with `python paper_2512_20017_amd/build.py`")
         L = C.CDLL(LIB_PATH)
         L.pbdr_status_string.restype = C.c_char_p
+        L.pbdr_profile_kernel_name.restype = C.c_char_p
         for name in EXPORTS:
             getattr(L, name)
         _lib = L
@@ -289,3 +291,38 @@ def pbdr_lists_view(ws, n, width, height, dup_capacity):
     P = min(P_raw, max(int(dup_capacity), 1))
     return dict(P=P, P_raw=P_raw, keys=view(keys, P, np.uint64), vals=view(vals, P, np.uint32),
                 ranges=view(ranges, 2 * tiles, np.uint32).reshape(tiles, 2))
+
+
+def pbdr_render_stats(cam: dict, n, dup_capacity, ws, stream=None):
+    """(examined, blended) pair counts of a forward pass over the lists now in the workspace. Synchronises."""
+    c = camera_struct(cam)
+    counters = torch.zeros(2, dtype=torch.int64, device=ws.device)
+    _check(lib().pbdr_render_stats(C.byref(c), C.c_int32(n), C.c_uint64(dup_capacity), _dev(counters),
+                                   C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
+    torch.cuda.synchronize()
+    out = counters.cpu().numpy()
+    return int(out[0]), int(out[1])
+
+
+def profile_kernel_names():
+    L = lib()
+    return [L.pbdr_profile_kernel_name(C.c_int32(i)).decode() for i in range(int(L.pbdr_profile_kernel_count()))]
+
+
+def pbdr_profile_begin(kernel_mask: int, max_records: int) -> None:
+    _check(lib().pbdr_profile_begin(C.c_uint32(kernel_mask), C.c_int32(max_records)))
+
+
+def pbdr_profile_reset() -> None:
+    _check(lib().pbdr_profile_reset())
+
+
+def pbdr_profile_collect(kernel_id: int):
+    """(total_ms, records) for one kernel id; waits for the recorded events."""
+    ms, cnt = C.c_double(0.0), C.c_int32(0)
+    _check(lib().pbdr_profile_collect(C.c_int32(kernel_id), C.byref(ms), C.byref(cnt)))
+    return float(ms.value), int(cnt.value)
+
+
+def pbdr_profile_end() -> None:
+    _check(lib().pbdr_profile_end())

@@ -207,6 +207,16 @@ int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pb
     return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), (hipStream_t)hip_stream));
 }
 
+int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
+                      size_t workspace_bytes, void* hip_stream)
+{
+    if (!check_camera(cam) || !aligned16(counters)) return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, n, cam->width, cam->height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    return hip_result(launch_render_stats(to_dev(cam), L, (char*)workspace, counters, (hipStream_t)hip_stream));
+}
+
 int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
                     uint64_t dup_capacity, const uint64_t** keys, const uint32_t** vals, const uint32_t** ranges,
                     const uint32_t** num_dup)

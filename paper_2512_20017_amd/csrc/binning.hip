@@ -152,6 +152,7 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
                                  hipStream_t s)
 {
     const uint32_t nb = (n + kScanItems - 1) / kScanItems;
+    ProfScope prof(kKScan, s);
     if (nb > 0) hipLaunchKernelGGL(k_scan_reduce, dim3(nb), dim3(256), 0, s, in, n, partials);
     hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, partials, nb, total_out);
     if (nb > 0) hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(256), 0, s, in, out, n, partials);
@@ -215,17 +216,27 @@ hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout&
     uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
     const unsigned nblk = (unsigned)((sp.n + 255) / 256);
 
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
-                       2 * (size_t)L.tiles);
+    {
+        ProfScope prof(kKFill, s);
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
+        hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
+                           2 * (size_t)L.tiles);
+    }
     if (sp.n > 0) {
-        hipLaunchKernelGGL(k_count_pack, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, packed);
+        {
+            ProfScope prof(kKCountPack, s);
+            hipLaunchKernelGGL(k_count_pack, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, packed);
+        }
         hipError_t e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n, part, status + kStNumDup, s);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, keys0, vals0, L.cap, status);
+        {
+            ProfScope prof(kKDuplicate, s);
+            hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, keys0, vals0, L.cap, status);
+        }
         e = launch_radix_sort(L, ws, s);
         if (e != hipSuccess) return e;
         const uint64_t* sorted = reinterpret_cast<const uint64_t*>(ws + sorted_keys_off(L));
+        ProfScope prof(kKTileRanges, s);
         hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, ranges);
     }
     return hipGetLastError();

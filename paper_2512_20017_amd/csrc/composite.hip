@@ -188,6 +188,55 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     }
 }
 
+
+// Measurement aid: the forward walk with counters instead of colours. counters[0] += list entries examined per pixel
+// (up to and including the one that ends the pixel), counters[1] += pairs blended.
+__global__ __launch_bounds__(256) void k_render_stats(CamDev cam, const uint32_t* __restrict__ ranges,
+                                                      const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
+                                                      unsigned long long* __restrict__ counters)
+{
+    __shared__ float4 sA[kBatch];
+    __shared__ float4 sB[kBatch];
+    __shared__ unsigned long long sCnt[2];
+    const TileCtx c = tile_ctx(cam, ranges);
+    const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
+    float T = 1.f;
+    uint32_t examined = 0, blended = 0;
+    bool done = !c.inside;
+    if (threadIdx.x < 2) sCnt[threadIdx.x] = 0ull;
+    for (uint32_t base = c.start; base < c.end; base += kBatch) {
+        if (__syncthreads_count(!done) == 0) break;
+        const uint32_t idx = base + threadIdx.x;
+        if (idx < c.end) {
+            const float4* rec = reinterpret_cast<const float4*>(packed + vals[idx]);
+            sA[threadIdx.x] = rec[0]; sB[threadIdx.x] = rec[1];
+        }
+        __syncthreads();
+        const int cnt = (int)min((uint32_t)kBatch, c.end - base);
+        if (!done) {
+            for (int j = 0; j < cnt; ++j) {
+                const float4 a = sA[j];
+                const float4 b = sB[j];
+                const float dx = fx - a.x, dy = fy - a.y;
+                const float sigma = 0.5f * (a.z * dx * dx + b.x * dy * dy) + a.w * dx * dy;
+                ++examined;
+                if (sigma < 0.f) continue;
+                const float alpha = fminf(kAlphaMax, b.y * __expf(-sigma));
+                if (alpha < kAlphaMin) continue;
+                const float Tn = T * (1.f - alpha);
+                if (Tn < kTStop) { done = true; break; }
+                T = Tn;
+                ++blended;
+            }
+        }
+    }
+    __syncthreads();
+    atomicAdd(&sCnt[0], (unsigned long long)examined);
+    atomicAdd(&sCnt[1], (unsigned long long)blended);
+    __syncthreads();
+    if (threadIdx.x < 2 && sCnt[threadIdx.x]) atomicAdd(&counters[threadIdx.x], sCnt[threadIdx.x]);
+}
+
 __global__ __launch_bounds__(256) void k_fill_f32(float* __restrict__ p, float v, size_t count)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -200,6 +249,7 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
     const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
+    ProfScope prof(kKCompositeFwd, s);
     hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, bg[0], bg[1],
                        bg[2], image, final_T, last_idx);
     return hipGetLastError();
@@ -213,14 +263,28 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     if (n > 0) {
+        ProfScope prof(kKFill, s);
         const size_t N = (size_t)n;
         const auto zero = [&](float* p, size_t count) {
             hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, p, 0.f, count);
         };
         zero(g2.mean2d, 2 * N); zero(g2.conic, 3 * N); zero(g2.opacity, N); zero(g2.color, 3 * N);
     }
+    ProfScope prof(kKCompositeBwd, s);
     hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, bg[0], bg[1],
                        bg[2], final_T, last_idx, dL_dimage, n, g2);
+    return hipGetLastError();
+}
+
+hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s)
+{
+    const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
+    const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
+    const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
+    ProfScope prof(kKStats, s);
+    hipLaunchKernelGGL(k_fill_f32, dim3(1), dim3(256), 0, s, reinterpret_cast<float*>(counters), 0.f, (size_t)4);
+    hipLaunchKernelGGL(k_render_stats, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed,
+                       reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include "profile.h"
 
 namespace pbdr {
 
@@ -79,6 +80,8 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
 hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3],
                                 const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
                                 const SplatGradDev& g2, hipStream_t s);
+
+hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
 
 // exclusive prefix sum of n uint32 (in -> out, may alias), total written to *total_out if non-null.
 // `partials` needs ceil(n / kScanItems) + 1 uint32.

@@ -306,6 +306,7 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    ProfScope prof(kKPreprocess, s);
     hipLaunchKernelGGL(k_preprocess, dim3(blocks), dim3(256), 0, s, sc, cam, out);
     return hipGetLastError();
 }
@@ -315,6 +316,7 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    ProfScope prof(kKPreprocessBwd, s);
     hipLaunchKernelGGL(k_preprocess_bwd, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g);
     return hipGetLastError();
 }

@@ -95,9 +95,13 @@ hipError_t launch_radix_sort(const Layout& L, char* ws, hipStream_t s)
     const uint32_t nb = L.sort_blocks;
     for (int pass = 0; pass < L.sort_passes; ++pass) {
         const int src = pass & 1, dst = src ^ 1, shift = 8 * pass;
-        hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(256), 0, s, kbuf[src], status, L.cap, shift, hist, nb);
+        {
+            ProfScope prof(kKRadixHist, s);
+            hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(256), 0, s, kbuf[src], status, L.cap, shift, hist, nb);
+        }
         hipError_t e = launch_exclusive_scan(hist, hist, L.hist_len, part, nullptr, s);
         if (e != hipSuccess) return e;
+        ProfScope prof(kKRadixScatter, s);
         hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(256), 0, s, kbuf[src], vbuf[src], kbuf[dst], vbuf[dst], status,
                            L.cap, shift, hist, nb);
     }

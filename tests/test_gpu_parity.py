@@ -66,7 +66,7 @@ def case(request):
 def test_preprocess_matches_oracle(case):
     sp, ref = case["sp"], case["ref"]
     tie = ref["near_tie"] != 0
-    assert tie.mean() < 0.05
+    assert tie.mean() < 0.01
     assert np.array_equal(sp["radius"][~tie], ref["radius"][~tie])
     vis = (ref["radius"] > 0) & (sp["radius"] > 0)
     assert vis.sum() > 0.5 * (ref["radius"] > 0).sum()
@@ -96,7 +96,7 @@ def test_composite_forward_matches_oracle(case):
     got = view.render_fwd(BG)
     ref = oracle.render_fwd(_state64(case["sp"]), case["lists"], cam["width"], cam["height"], BG)
     ok = ref["fragile"] == 0
-    assert (~ok).mean() < 1e-3
+    assert (~ok).mean() < 5e-3
     assert np.abs(got["image"] - ref["image"])[ok].max() <= IMG_ATOL
     assert np.abs(got["final_T"] - ref["final_T"])[ok].max() <= IMG_ATOL
     assert np.array_equal(got["last_idx"][ok], ref["last_idx"][ok])
