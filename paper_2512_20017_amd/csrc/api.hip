@@ -25,6 +25,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
     L->sort_passes = (L->sort_bits + 7) / 8;
     L->sort_blocks = (uint32_t)((cap + kSortItems - 1) / kSortItems);
     L->hist_len = 256u * L->sort_blocks;
+    L->pstride = (L->cap + 3u) & ~3u;
     const size_t scan_max = (size_t)((uint32_t)n > L->hist_len ? (uint32_t)n : L->hist_len);
     size_t off = 0;
     L->off_status = off;    off = align256(off + kStWords * sizeof(uint32_t));
@@ -37,6 +38,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
     L->off_vals1 = off;     off = align256(off + (size_t)cap * sizeof(uint32_t));
     L->off_hist = off;      off = align256(off + (size_t)L->hist_len * sizeof(uint32_t));
     L->off_ranges = off;    off = align256(off + (size_t)L->tiles * 2 * sizeof(uint32_t));
+    L->off_partial = off;   off = align256(off + (size_t)L->pstride * 9 * sizeof(float));
     L->total = off;
     return true;
 }
@@ -201,8 +203,8 @@ int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pb
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
     const CamDev c = to_dev(cam);
-    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
-                                        (hipStream_t)hip_stream);
+    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, splats->radius, bg, final_T, last_idx, dL_dimage,
+                                        dev(g_splats), (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
     return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), (hipStream_t)hip_stream));
 }

@@ -21,7 +21,8 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, ui
                                                     Packed* __restrict__ packed)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= sp.n) return;
+    if (i > sp.n) return;
+    if (i == sp.n) { tiles_touched[i] = 0; return; }   // sentinel: the scan then leaves the pair total at offsets[n]
     const size_t N = (size_t)sp.n;
     const int r = sp.radius[i];
     uint32_t cnt = 0;
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, ui
         float4* dst = reinterpret_cast<float4*>(packed + i);
         dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
         dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
-        dst[2] = make_float4(sp.color[2 * N + i], 0.f, 0.f, 0.f);
+        dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), 0.f, 0.f);
     }
     tiles_touched[i] = cnt;
 }
@@ -225,9 +226,9 @@ hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout&
     if (sp.n > 0) {
         {
             ProfScope prof(kKCountPack, s);
-            hipLaunchKernelGGL(k_count_pack, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, packed);
+            hipLaunchKernelGGL(k_count_pack, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp, cam, offsets, packed);
         }
-        hipError_t e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n, part, status + kStNumDup, s);
+        hipError_t e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n + 1u, part, status + kStNumDup, s);
         if (e != hipSuccess) return e;
         {
             ProfScope prof(kKDuplicate, s);

@@ -2,18 +2,27 @@
 // color of each pixel front to back, blending the overlapping splats until full opacity is reached"; Alg. 1
 // lines 12 and 18).
 //
-// One workgroup (4 wavefronts of 64) per 16x16 tile; each wavefront owns an 8x8 pixel block so that a splat that
-// misses the block costs the wavefront nothing past the test. The tile's depth-sorted list is staged through LDS
-// 256 splats at a time (one 48-byte record per thread, three 16-byte loads), then every lane walks the batch with
-// LDS broadcast reads. Plain VALU work: there is no dense contraction here, so no MFMA.
+// One workgroup (4 wavefronts of 64) per 16x16 tile; each wavefront owns one 8x8 pixel quadrant. The tile's
+// depth-sorted list is staged through LDS 256 splats at a time (one 48-byte record per thread). While staging, each
+// thread works out which of the four quadrants its splat can reach at all with alpha >= 1/255 (exact minimum of
+// the quadratic form over the quadrant rectangle, taken conservatively), and the wavefronts ballot these into one
+// 256-bit mask per quadrant. A wavefront then walks only the set bits of its own mask with scalar bit scans, so a
+// splat that cannot touch the quadrant costs it nothing. The cull never changes a result: every visited
+// (pixel, splat) pair still takes the full per-pixel tests.
+//
+// The per-pair arithmetic is branch-free and in the log2 domain: alpha = min(0.99, 2^(log2 o - q(d))) with
+// q = log2(e) * sigma folded into the staged conic. Plain VALU work: no dense contraction, so no MFMA.
 #include "pbdr_internal.h"
 
 namespace pbdr {
 
 constexpr int kBatch = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLog2_255 = 7.994353436858858f;
 
 struct TileCtx {
-    int px, py;
+    int px, py;       // this lane's pixel
+    int tx0, ty0;     // tile origin in pixels
     bool inside;
     uint32_t pix;
     uint32_t start, end;
@@ -25,8 +34,9 @@ __device__ __forceinline__ TileCtx tile_ctx(const CamDev& cam, const uint32_t* _
     const int tile = blockIdx.x;
     const int ty = tile / cam.TX, tx = tile - ty * cam.TX;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    c.px = tx * kTile + (wave & 1) * 8 + (lane & 7);
-    c.py = ty * kTile + (wave >> 1) * 8 + (lane >> 3);
+    c.tx0 = tx * kTile; c.ty0 = ty * kTile;
+    c.px = c.tx0 + (wave & 1) * 8 + (lane & 7);
+    c.py = c.ty0 + (wave >> 1) * 8 + (lane >> 3);
     c.inside = c.px < cam.W && c.py < cam.H;
     c.pix = (uint32_t)c.py * (uint32_t)cam.W + (uint32_t)c.px;
     c.start = ranges[2 * tile];
@@ -34,44 +44,140 @@ __device__ __forceinline__ TileCtx tile_ctx(const CamDev& cam, const uint32_t* _
     return c;
 }
 
+// value of q(dx,dy) = A dx^2 + B dx dy + C dy^2
+__device__ __forceinline__ float qform(float A, float B, float C, float dx, float dy)
+{
+    return (A * dx + B * dy) * dx + C * dy * dy;
+}
+
+// Minimum of the positive-definite form q over the rectangle [lx,hx] x [ly,hy] (offsets from the splat centre).
+__device__ __forceinline__ float qform_min_rect(float A, float B, float C, float lx, float hx, float ly, float hy)
+{
+    if (lx <= 0.f && hx >= 0.f && ly <= 0.f && hy >= 0.f) return 0.f;
+    const float i2C = 0.5f / C, i2A = 0.5f / A;
+    float best;
+    {
+        const float dy = fminf(hy, fmaxf(ly, -B * lx * i2C));
+        best = qform(A, B, C, lx, dy);
+    }
+    {
+        const float dy = fminf(hy, fmaxf(ly, -B * hx * i2C));
+        best = fminf(best, qform(A, B, C, hx, dy));
+    }
+    {
+        const float dx = fminf(hx, fmaxf(lx, -B * ly * i2A));
+        best = fminf(best, qform(A, B, C, dx, ly));
+    }
+    {
+        const float dx = fminf(hx, fmaxf(lx, -B * hy * i2A));
+        best = fminf(best, qform(A, B, C, dx, hy));
+    }
+    return best;
+}
+
+// LDS image of one staged batch
+struct Stage {
+    float4 a[kBatch];                 // mx, my, A = log2e/2 * qa, B = log2e * qb
+    float4 b[kBatch];                 // C = log2e/2 * qc, L = log2(opacity), red, green
+    float c[kBatch];                  // blue
+    unsigned long long mask[4][4];    // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
+};
+
+// Stage list entries [first, first+count) of the tile: one per thread. Returns this thread's splat index, raw
+// conic/opacity and (mean2d, extent) for callers that need them (backward). All 256 threads must call it.
+__device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const uint32_t* __restrict__ vals,
+                                            const Packed* __restrict__ packed, uint32_t first, int count, uint32_t& id,
+                                            float4& raw, float4& geo)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool have = (int)threadIdx.x < count;
+    bool reach[4] = {false, false, false, false};
+    id = 0; raw = make_float4(0.f, 0.f, 0.f, 0.f); geo = raw;
+    if (have) {
+        id = vals[first + threadIdx.x];
+        const float4* rec = reinterpret_cast<const float4*>(packed + id);
+        const float4 r0 = rec[0], r1 = rec[1], r2 = rec[2];
+        const float mx = r0.x, my = r0.y, qa = r0.z, qb = r0.w, qc = r1.x, o = r1.y;
+        raw = make_float4(qa, qb, qc, o);
+        geo = make_float4(mx, my, r2.y, 0.f);   // r2.y carries the extent (integer bits)
+        const float A = 0.5f * kLog2e * qa, B = kLog2e * qb, C = 0.5f * kLog2e * qc;
+        const float L = __log2f(o);
+        S.a[threadIdx.x] = make_float4(mx, my, A, B);
+        S.b[threadIdx.x] = make_float4(C, L, r1.z, r1.w);
+        S.c[threadIdx.x] = r2.x;
+        // alpha >= 1/255  <=>  q(d) <= L + log2(255)
+        const float tau = L + kLog2_255;
+        const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
+        if (!(tau < -0.05f)) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float lx = (float)(t.tx0 + (q & 1) * 8) + 0.5f - mx, hx = lx + 7.f;
+                const float ly = (float)(t.ty0 + (q >> 1) * 8) + 0.5f - my, hy = ly + 7.f;
+                bool keep = true;
+                if (pd) {
+                    const float mn = qform_min_rect(A, B, C, lx, hx, ly, hy);
+                    const float mxd = fmaxf(fabsf(lx), fabsf(hx)), myd = fmaxf(fabsf(ly), fabsf(hy));
+                    const float big = A * mxd * mxd + C * myd * myd + fabsf(B) * mxd * myd;
+                    keep = !(mn > tau + 0.05f + 4e-6f * big);   // conservative: rounding can only keep more
+                }
+                reach[q] = keep;
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const unsigned long long m = __ballot(reach[q]);
+        if (lane == 0) S.mask[q][wave] = m;
+    }
+}
+
+__device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
 __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        float bg0, float bg1, float bg2, float* __restrict__ image,
                                                        float* __restrict__ final_T, uint32_t* __restrict__ last_idx)
 {
-    __shared__ float4 sA[kBatch];  // mx, my, qa, qb
-    __shared__ float4 sB[kBatch];  // qc, o, r, g
-    __shared__ float sC[kBatch];   // b
+    __shared__ Stage S;
     const TileCtx c = tile_ctx(cam, ranges);
+    const int wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     float T = 1.f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
     uint32_t last = 0;
-    bool done = !c.inside;
+    bool live = c.inside;
     for (uint32_t base = c.start; base < c.end; base += kBatch) {
-        if (__syncthreads_count(!done) == 0) break;   // also fences the previous batch's LDS reads
-        const uint32_t idx = base + threadIdx.x;
-        if (idx < c.end) {
-            const float4* rec = reinterpret_cast<const float4*>(packed + vals[idx]);
-            const float4 a = rec[0], b = rec[1], d = rec[2];
-            sA[threadIdx.x] = a; sB[threadIdx.x] = b; sC[threadIdx.x] = d.x;
-        }
-        __syncthreads();
+        if (__syncthreads_count(live) == 0) break;   // also fences the previous batch's LDS reads
         const int cnt = (int)min((uint32_t)kBatch, c.end - base);
-        if (!done) {
-            for (int j = 0; j < cnt; ++j) {
-                const float4 a = sA[j];
-                const float4 b = sB[j];
+        uint32_t id; float4 raw, geo;
+        stage_batch(S, c, vals, packed, base, cnt, id, raw, geo);
+        __syncthreads();
+        if (__ballot(live) == 0ull) continue;          // this quadrant is finished (uniform per wavefront)
+        const uint32_t pos0 = base - c.start + 1u;
+        for (int k = 0; k < 4; ++k) {
+            unsigned long long m = uniform_u64(S.mask[wave][k]);
+            while (m) {
+                const int j = k * 64 + __builtin_ctzll(m);
+                m &= m - 1ull;
+                const float4 a = S.a[j];
+                const float4 b = S.b[j];
+                const float cb = S.c[j];
                 const float dx = fx - a.x, dy = fy - a.y;
-                const float sigma = 0.5f * (a.z * dx * dx + b.x * dy * dy) + a.w * dx * dy;
-                if (sigma < 0.f) continue;
-                const float alpha = fminf(kAlphaMax, b.y * __expf(-sigma));
-                if (alpha < kAlphaMin) continue;
+                const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
+                const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
+                const bool valid = live && (q >= 0.f) && (alpha >= kAlphaMin);
                 const float Tn = T * (1.f - alpha);
-                if (Tn < kTStop) { done = true; break; }
-                const float w = alpha * T;
-                C0 += b.z * w; C1 += b.w * w; C2 += sC[j] * w;
-                T = Tn;
-                last = (base - c.start) + (uint32_t)j + 1u;
+                const bool stop = valid && (Tn < kTStop);
+                const bool blend = valid && !stop;
+                live = live && !stop;
+                const float w = blend ? alpha * T : 0.f;
+                C0 += b.z * w; C1 += b.w * w; C2 += cb * w;
+                T = blend ? Tn : T;
+                last = blend ? pos0 + (uint32_t)j : last;
             }
         }
     }
@@ -98,22 +204,30 @@ __device__ __forceinline__ float wave_sum(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// Backward. Per pixel, back to front from its last blended splat: T_k = T_{k+1} / (1 - alpha_k),
+//   dL/dalpha_k = T_k (c_k . g) - S_k / (1 - alpha_k),  S_k = sum_{i>k} w_i (c_i . g) + T_final (bg . g).
+// With ds = dL/dsigma = -alpha dL/dalpha (zero where alpha was clamped), every splat gradient is a lane sum of
+//   w g_c (3 colours)  and the six moments  ds (1, dx, dy, dx^2, dx dy, dy^2):
+//   d conic = (S3/2, S4, S5/2), d mean2d = -(qa S1 + qb S2, qc S2 + qb S1), d opacity = -S0 / o.
+//
+// No global atomics: each wavefront reduces its 64 pixels with DPP, the four quadrants of the tile meet in an LDS
+// accumulator, and the thread that staged splat j writes the tile's nine sums for it to partial[k][u], where u is
+// the pair's position in the unsorted duplicate list (offsets[id] + rank of this tile in the splat's rectangle).
+// A splat's pairs are contiguous there, so a per-splat kernel adds them up afterwards (k_gather_splat_grads).
 __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
-                                                       float bg0, float bg1, float bg2, const float* __restrict__ final_T,
-                                                       const uint32_t* __restrict__ last_idx, const float* __restrict__ dL_dimage,
-                                                       int n, SplatGradDev g2)
+                                                       const uint32_t* __restrict__ offsets, float bg0, float bg1, float bg2,
+                                                       const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
+                                                       const float* __restrict__ dL_dimage, uint32_t cap, uint32_t pstride,
+                                                       float* __restrict__ partial)
 {
-    __shared__ float4 sA[kBatch];
-    __shared__ float4 sB[kBatch];
-    __shared__ float sC[kBatch];
-    __shared__ uint32_t sId[kBatch];
+    __shared__ Stage S;
+    __shared__ float sAcc[9][kBatch];
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     const size_t HW = (size_t)cam.W * cam.H;
-    const size_t N = (size_t)n;
     float T = 1.f, g0 = 0.f, g1 = 0.f, g2c = 0.f;
     uint32_t last = 0;
     if (c.inside) {
@@ -121,9 +235,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         last = min(last_idx[c.pix], c.end - c.start);   // never walk past the tile's list, whatever the caller passed
         g0 = dL_dimage[c.pix]; g1 = dL_dimage[HW + c.pix]; g2c = dL_dimage[2 * HW + c.pix];
     }
-    // S = sum over splats behind the current one of w_i (c_i . g), plus the background term
-    float S = T * (bg0 * g0 + bg1 * g1 + bg2 * g2c);
-    // the deepest list position any pixel of the tile blended
+    float Sfx = T * (bg0 * g0 + bg1 * g1 + bg2 * g2c);
     uint32_t wmax = last;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) wmax = max(wmax, (uint32_t)__shfl_xor((int)wmax, d, 64));
@@ -131,63 +243,125 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     __syncthreads();
     const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
     if (tile_last == 0) return;
+    const int tile_x = c.tx0 / kTile, tile_y = c.ty0 / kTile;
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
         const int cnt = (int)min((uint32_t)kBatch, tile_last - boff);
+        uint32_t id; float4 raw, geo;
+        stage_batch(S, c, vals, packed, c.start + boff, cnt, id, raw, geo);
+#pragma unroll
+        for (int k = 0; k < 9; ++k) sAcc[k][threadIdx.x] = 0.f;
         __syncthreads();
-        if ((int)threadIdx.x < cnt) {
-            const uint32_t id = vals[c.start + boff + threadIdx.x];
-            const float4* rec = reinterpret_cast<const float4*>(packed + id);
-            const float4 a = rec[0], b = rec[1], d = rec[2];
-            sA[threadIdx.x] = a; sB[threadIdx.x] = b; sC[threadIdx.x] = d.x; sId[threadIdx.x] = id;
-        }
-        __syncthreads();
-        if (wmax <= boff) continue;   // nothing of this batch was blended by this wavefront (uniform per wave)
-        for (int j = cnt - 1; j >= 0; --j) {
-            const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
-            const float4 a = sA[j];
-            const float4 b = sB[j];
-            const float cb = sC[j];
-            const float dx = fx - a.x, dy = fy - a.y;
-            const float sigma = 0.5f * (a.z * dx * dx + b.x * dy * dy) + a.w * dx * dy;
-            const float gauss = __expf(-sigma);
-            const float araw = b.y * gauss;
-            const float alpha = fminf(kAlphaMax, araw);
-            const bool hit = (pos <= last) && (sigma >= 0.f) && (alpha >= kAlphaMin);
-            if (__ballot(hit) == 0ull) continue;                   // uniform per wave
-            float d_r = 0.f, d_g = 0.f, d_b = 0.f, d_o = 0.f, d_qa = 0.f, d_qb = 0.f, d_qc = 0.f, d_mx = 0.f, d_my = 0.f;
-            if (hit) {
-                const float oma = 1.f - alpha;
-                const float ioma = 1.f / oma;
-                T *= ioma;                                          // transmittance in front of this splat
-                const float w = alpha * T;
-                const float cg = b.z * g0 + b.w * g1 + cb * g2c;
-                const float dL_dalpha = T * cg - S * ioma;
-                S += w * cg;
-                d_r = w * g0; d_g = w * g1; d_b = w * g2c;
-                if (araw < kAlphaMax) {
-                    const float ds = -alpha * dL_dalpha;
-                    d_o = gauss * dL_dalpha;
-                    d_qa = 0.5f * dx * dx * ds; d_qb = dx * dy * ds; d_qc = 0.5f * dy * dy * ds;
-                    d_mx = -(a.z * dx + a.w * dy) * ds;
-                    d_my = -(b.x * dy + a.w * dx) * ds;
+        if (wmax > boff) {            // else nothing of this batch was blended by this wavefront (uniform per wave)
+            for (int k = 3; k >= 0; --k) {
+                unsigned long long m = uniform_u64(S.mask[wave][k]);
+                while (m) {
+                    const int bit = 63 - __builtin_clzll(m);
+                    m &= ~(1ull << bit);
+                    const int j = k * 64 + bit;
+                    const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
+                    const float4 a = S.a[j];
+                    const float4 b = S.b[j];
+                    const float cb = S.c[j];
+                    const float dx = fx - a.x, dy = fy - a.y;
+                    const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
+                    const float e = __builtin_amdgcn_exp2f(b.y - q);
+                    const float alpha = fminf(kAlphaMax, e);
+                    const bool hit = (pos <= last) && (q >= 0.f) && (alpha >= kAlphaMin);
+                    if (__ballot(hit) == 0ull) continue;                   // uniform per wave
+                    const float ioma = __builtin_amdgcn_rcpf(1.f - alpha);
+                    const float Tk = T * ioma;                              // transmittance in front of this splat
+                    const float w = hit ? alpha * Tk : 0.f;
+                    const float cg = b.z * g0 + b.w * g1 + cb * g2c;
+                    const float dL_dalpha = Tk * cg - Sfx * ioma;
+                    const float ds = (hit && e < kAlphaMax) ? -alpha * dL_dalpha : 0.f;
+                    T = hit ? Tk : T;
+                    Sfx += w * cg;
+                    const float dsx = ds * dx, dsy = ds * dy;
+                    const float r0 = wave_sum(w * g0), r1 = wave_sum(w * g1), r2 = wave_sum(w * g2c);
+                    const float s0 = wave_sum(ds), s1 = wave_sum(dsx), s2 = wave_sum(dsy);
+                    const float s3 = wave_sum(dsx * dx), s4 = wave_sum(dsx * dy), s5 = wave_sum(dsy * dy);
+                    if (lane < 9) {
+                        float v = r0;
+                        v = lane == 1 ? r1 : v;
+                        v = lane == 2 ? r2 : v;
+                        v = lane == 3 ? s0 : v;
+                        v = lane == 4 ? s1 : v;
+                        v = lane == 5 ? s2 : v;
+                        v = lane == 6 ? s3 : v;
+                        v = lane == 7 ? s4 : v;
+                        v = lane == 8 ? s5 : v;
+                        atomicAdd(&sAcc[lane][j], v);      // LDS float add: the four quadrants meet here
+                    }
                 }
             }
-            d_r = wave_sum(d_r); d_g = wave_sum(d_g); d_b = wave_sum(d_b); d_o = wave_sum(d_o);
-            d_qa = wave_sum(d_qa); d_qb = wave_sum(d_qb); d_qc = wave_sum(d_qc);
-            d_mx = wave_sum(d_mx); d_my = wave_sum(d_my);
-            if (lane == 0) {
-                const uint32_t id = sId[j];
-                atomicAdd(g2.color + id, d_r); atomicAdd(g2.color + N + id, d_g); atomicAdd(g2.color + 2 * N + id, d_b);
-                atomicAdd(g2.opacity + id, d_o);
-                atomicAdd(g2.conic + id, d_qa); atomicAdd(g2.conic + N + id, d_qb); atomicAdd(g2.conic + 2 * N + id, d_qc);
-                atomicAdd(g2.mean2d + id, d_mx); atomicAdd(g2.mean2d + N + id, d_my);
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < cnt) {
+            // where this (tile, splat) pair sits in the unsorted duplicate list
+            int x0, y0, x1, y1;
+            {
+                const int r = __float_as_int(geo.z);
+                const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(geo.x)));
+                const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(geo.y)));
+                x0 = min(max((ix - r) >> 4, 0), cam.TX); y0 = min(max((iy - r) >> 4, 0), cam.TY);
+                x1 = min(max((ix + r + 15) >> 4, 0), cam.TX); y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+            }
+            const uint32_t u = offsets[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
+            if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
+                const size_t Pc = (size_t)pstride;
+                const float s0 = sAcc[3][threadIdx.x], s1 = sAcc[4][threadIdx.x], s2 = sAcc[5][threadIdx.x];
+                partial[u] = -(raw.x * s1 + raw.y * s2);                 // d mean2d.x
+                partial[Pc + u] = -(raw.z * s2 + raw.y * s1);            // d mean2d.y
+                partial[2 * Pc + u] = 0.5f * sAcc[6][threadIdx.x];       // d conic a
+                partial[3 * Pc + u] = sAcc[7][threadIdx.x];              // d conic b
+                partial[4 * Pc + u] = 0.5f * sAcc[8][threadIdx.x];       // d conic c
+                partial[5 * Pc + u] = raw.w > 0.f ? -s0 / raw.w : 0.f;                     // d opacity
+                partial[6 * Pc + u] = sAcc[0][threadIdx.x];              // d colour
+                partial[7 * Pc + u] = sAcc[1][threadIdx.x];
+                partial[8 * Pc + u] = sAcc[2][threadIdx.x];
             }
         }
+        __syncthreads();   // sAcc and the stage are rewritten by the next batch
     }
 }
 
+// One thread per point: add up the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list)
+// into dL/d(splat state); points without pairs get zeros.
+__global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const int32_t* __restrict__ radius,
+                                                            const uint32_t* __restrict__ offsets,
+                                                            const float* __restrict__ partial, uint32_t cap,
+                                                            uint32_t pstride, SplatGradDev g2)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = (size_t)n, Pc = (size_t)pstride;
+    float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (radius[i] > 0) {
+        const uint32_t b = offsets[i], e = min(offsets[i + 1], cap);
+        for (uint32_t u = b; u < e; ++u) {
+#pragma unroll
+            for (int k = 0; k < 9; ++k) acc[k] += partial[k * Pc + u];
+        }
+    }
+    g2.mean2d[i] = acc[0]; g2.mean2d[N + i] = acc[1];
+    g2.conic[i] = acc[2]; g2.conic[N + i] = acc[3]; g2.conic[2 * N + i] = acc[4];
+    g2.opacity[i] = acc[5];
+    g2.color[i] = acc[6]; g2.color[N + i] = acc[7]; g2.color[2 * N + i] = acc[8];
+}
+
+// zero the first min(*count_dev, cap) entries of each of the 9 partial planes
+__global__ __launch_bounds__(256) void k_zero_partial(float* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap,
+                                                      uint32_t pstride)
+{
+    const uint32_t P = min(status[kStNumDup], cap);
+    const uint32_t i = (blockIdx.x * 256u + threadIdx.x) * 4u;
+    if (i >= P) return;                      // i + 3 < pstride always: pstride is cap rounded up to a multiple of 4
+#pragma unroll
+    for (int k = 0; k < 9; ++k)
+        *reinterpret_cast<float4*>(partial + (size_t)k * pstride + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+}
 
 // Measurement aid: the forward walk with counters instead of colours. counters[0] += list entries examined per pixel
 // (up to and including the one that ends the pixel), counters[1] += pairs blended.
@@ -255,24 +429,30 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
     return hipGetLastError();
 }
 
-hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3],
-                                const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
-                                const SplatGradDev& g2, hipStream_t s)
+hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const int32_t* radius,
+                                const float bg[3], const float* final_T, const uint32_t* last_idx,
+                                const float* dL_dimage, const SplatGradDev& g2, hipStream_t s)
 {
     const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
-    if (n > 0) {
+    const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
+    const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
+    float* partial = reinterpret_cast<float*>(ws + L.off_partial);
+    {
         ProfScope prof(kKFill, s);
-        const size_t N = (size_t)n;
-        const auto zero = [&](float* p, size_t count) {
-            hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, p, 0.f, count);
-        };
-        zero(g2.mean2d, 2 * N); zero(g2.conic, 3 * N); zero(g2.opacity, N); zero(g2.color, 3 * N);
+        hipLaunchKernelGGL(k_zero_partial, dim3((L.pstride / 4u + 255u) / 256u), dim3(256), 0, s, partial, status, L.cap, L.pstride);
     }
-    ProfScope prof(kKCompositeBwd, s);
-    hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, bg[0], bg[1],
-                       bg[2], final_T, last_idx, dL_dimage, n, g2);
+    {
+        ProfScope prof(kKCompositeBwd, s);
+        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, offsets,
+                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, L.pstride, partial);
+    }
+    if (n > 0) {
+        ProfScope prof(kKGather, s);
+        hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, radius, offsets,
+                           partial, L.cap, L.pstride, g2);
+    }
     return hipGetLastError();
 }
 

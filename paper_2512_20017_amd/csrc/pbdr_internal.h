@@ -32,7 +32,7 @@ struct CamDev {
 struct __attribute__((aligned(16))) Packed {
     float mx, my, qa, qb;   // mean2d, conic a, b
     float qc, o, r, g;      // conic c, opacity, red, green
-    float b, pad0, pad1, pad2;
+    float b, radius_bits, pad1, pad2;   // radius_bits: the integer extent, bit-cast
 };
 static_assert(sizeof(Packed) == 48, "raster record is 48 bytes");
 
@@ -63,8 +63,9 @@ struct Layout {
     int sort_bits, sort_passes;
     uint32_t sort_blocks;     // blocks of kSortItems pairs covering `cap`
     uint32_t hist_len;        // 256 * sort_blocks
+    uint32_t pstride;         // elements between the 9 planes of per-pair partial gradient sums (cap rounded up to 4)
     size_t off_status, off_packed, off_offsets, off_scan_part, off_keys0, off_keys1, off_vals0, off_vals1,
-        off_hist, off_ranges, total;
+        off_hist, off_ranges, off_partial, total;
 };
 constexpr int kSortItems = 4096;   // pairs per radix-sort block
 constexpr int kScanItems = 4096;   // elements per scan block
@@ -77,9 +78,9 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
                                 float* final_T, uint32_t* last_idx, hipStream_t s);
-hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3],
-                                const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
-                                const SplatGradDev& g2, hipStream_t s);
+hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const int32_t* radius,
+                                const float bg[3], const float* final_T, const uint32_t* last_idx,
+                                const float* dL_dimage, const SplatGradDev& g2, hipStream_t s);
 
 hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
 
