@@ -142,7 +142,7 @@ def main():
         "k_radix_hist": 8.0 * P,
         "k_radix_scatter": 24.0 * P,
         "k_tile_ranges": 8.0 * P,
-        "k_gather_splat_grads": 8.0 * n + 36.0 * P + 36.0 * n,
+        "k_gather_splat_grads": 8.0 * n + 48.0 * P + 36.0 * n,
         "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K + 2 * (44.0 + 12.0 * K)) * n_vis,
     }
     alu_flops = {

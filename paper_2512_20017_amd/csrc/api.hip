@@ -25,7 +25,6 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
     L->sort_passes = (L->sort_bits + 7) / 8;
     L->sort_blocks = (uint32_t)((cap + kSortItems - 1) / kSortItems);
     L->hist_len = 256u * L->sort_blocks;
-    L->pstride = (L->cap + 3u) & ~3u;
     const size_t scan_max = (size_t)((uint32_t)n > L->hist_len ? (uint32_t)n : L->hist_len);
     size_t off = 0;
     L->off_status = off;    off = align256(off + kStWords * sizeof(uint32_t));
@@ -38,7 +37,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
     L->off_vals1 = off;     off = align256(off + (size_t)cap * sizeof(uint32_t));
     L->off_hist = off;      off = align256(off + (size_t)L->hist_len * sizeof(uint32_t));
     L->off_ranges = off;    off = align256(off + (size_t)L->tiles * 2 * sizeof(uint32_t));
-    L->off_partial = off;   off = align256(off + (size_t)L->pstride * 9 * sizeof(float));
+    L->off_partial = off;   off = align256(off + (size_t)cap * 12 * sizeof(float));
     L->total = off;
     return true;
 }

@@ -161,30 +161,58 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
 }
 
 // One thread per point: write its (tile << 32 | depth bits, index) pairs, row-major over its tile rectangle.
+// A point with more than kDupSolo tiles is handed to its whole wavefront, 64 tiles per step.
+constexpr int kDupSolo = 8;
+
 __global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ offsets,
                                                    uint64_t* __restrict__ keys, uint32_t* __restrict__ vals, uint32_t cap,
                                                    uint32_t* __restrict__ status)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= sp.n) return;
-    const int r = sp.radius[i];
-    if (r <= 0) return;
-    const size_t N = (size_t)sp.n;
-    int x0, y0, x1, y1;
-    rect_of(cam, sp.mean2d[i], sp.mean2d[N + i], r, x0, y0, x1, y1);
-    const uint32_t bits = __float_as_uint(sp.depth[i]);
-    uint32_t at = offsets[i];
+    const int lane = threadIdx.x & 63;
+    int x0 = 0, y0 = 0, x1 = 0, y1 = 0;
+    uint32_t bits = 0, at = 0;
+    if (i < sp.n) {
+        const int r = sp.radius[i];
+        if (r > 0) {
+            rect_of(cam, sp.mean2d[i], sp.mean2d[(size_t)sp.n + i], r, x0, y0, x1, y1);
+            bits = __float_as_uint(sp.depth[i]);
+            at = offsets[i];
+        }
+    }
+    const int w = x1 - x0, cnt = w * (y1 - y0);
     bool dropped = false;
-    for (int ty = y0; ty < y1; ++ty)
-        for (int tx = x0; tx < x1; ++tx) {
-            if (at < cap) {
-                keys[at] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | bits;
-                vals[at] = (uint32_t)i;
+    const bool big = cnt > kDupSolo;
+    if (!big) {
+        for (int t = 0; t < cnt; ++t) {
+            const int ty = y0 + t / w, tx = x0 + t - (t / w) * w;
+            if (at + t < cap) {
+                keys[at + t] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | bits;
+                vals[at + t] = (uint32_t)i;
             } else {
                 dropped = true;
             }
-            ++at;
         }
+    }
+    unsigned long long todo = __ballot(big);
+    while (todo) {
+        const int src = __builtin_ctzll(todo);
+        todo &= todo - 1ull;
+        const int sx0 = __builtin_amdgcn_readlane(x0, src), sy0 = __builtin_amdgcn_readlane(y0, src);
+        const int sw = __builtin_amdgcn_readlane(w, src), scnt = __builtin_amdgcn_readlane(cnt, src);
+        const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)bits, src);
+        const uint32_t sat = (uint32_t)__builtin_amdgcn_readlane((int)at, src);
+        const uint32_t sid = (uint32_t)__builtin_amdgcn_readlane(i, src);
+        for (int t = lane; t < scnt; t += 64) {
+            const int ty = sy0 + t / sw, tx = sx0 + t - (t / sw) * sw;
+            if (sat + t < cap) {
+                keys[sat + t] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | sbits;
+                vals[sat + t] = sid;
+            } else {
+                dropped = true;
+            }
+        }
+    }
     if (dropped) status[kStOverflow] = 1u;
 }
 

@@ -204,25 +204,68 @@ __device__ __forceinline__ float wave_sum(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+template <int kCtrl>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, false));
+}
+
+// Sums eight values over each row of 16 lanes at once by recursive halving: at each of three exchange steps a lane
+// keeps half of its values and hands the other half to its partner (lane ^ 1, lane ^ 3, lane ^ 7: DPP quad
+// permutes and the half-row mirror), then one full-row mirror add finishes. 22 VALU instructions instead of 8 x 4.
+// On return the lane holds the row sum of value number 4*r1 + 2*r2 + r3, where, with b_i the bits of its lane
+// number, r1 = b0^b1, r2 = b1^b2, r3 = b2^b3 (each pairing flips exactly one of the rules it must, and none of the
+// earlier ones).
+__device__ __forceinline__ float row_sum8(const float v[8], bool r1, bool r2, bool r3)
+{
+    float a[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float keep = r1 ? v[i + 4] : v[i], send = r1 ? v[i] : v[i + 4];
+        a[i] = keep + dpp_move<0xB1>(send);        // quad_perm:[1,0,3,2]
+    }
+    float c[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const float keep = r2 ? a[i + 2] : a[i], send = r2 ? a[i] : a[i + 2];
+        c[i] = keep + dpp_move<0x1B>(send);        // quad_perm:[3,2,1,0]
+    }
+    const float keep = r3 ? c[1] : c[0], send = r3 ? c[0] : c[1];
+    float d = keep + dpp_move<0x141>(send);        // row_half_mirror
+    d += dpp_move<0x140>(d);                       // row_mirror
+    return d;
+}
+
+// inclusive row scan by shifts: lane 15 of each row ends up with the row sum
+__device__ __forceinline__ float row_sum_to_lane15(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true));
+    return v;
+}
+
 // Backward. Per pixel, back to front from its last blended splat: T_k = T_{k+1} / (1 - alpha_k),
 //   dL/dalpha_k = T_k (c_k . g) - S_k / (1 - alpha_k),  S_k = sum_{i>k} w_i (c_i . g) + T_final (bg . g).
 // With ds = dL/dsigma = -alpha dL/dalpha (zero where alpha was clamped), every splat gradient is a lane sum of
 //   w g_c (3 colours)  and the six moments  ds (1, dx, dy, dx^2, dx dy, dy^2):
 //   d conic = (S3/2, S4, S5/2), d mean2d = -(qa S1 + qb S2, qc S2 + qb S1), d opacity = -S0 / o.
 //
-// No global atomics: each wavefront reduces its 64 pixels with DPP, the four quadrants of the tile meet in an LDS
-// accumulator, and the thread that staged splat j writes the tile's nine sums for it to partial[k][u], where u is
-// the pair's position in the unsorted duplicate list (offsets[id] + rank of this tile in the splat's rectangle).
-// A splat's pairs are contiguous there, so a per-splat kernel adds them up afterwards (k_gather_splat_grads).
+// No global atomics: each wavefront reduces its rows of 16 pixels with DPP, the 16 rows of the tile meet in an LDS
+// accumulator (ds_add_f32), and the thread that staged splat j writes the tile's nine sums for it to partial[u]
+// (12 floats per pair), where u is the pair's position in the unsorted duplicate list (offsets[id] + rank of this
+// tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them up afterwards
+// (k_gather_splat_grads).
 __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        const uint32_t* __restrict__ offsets, float bg0, float bg1, float bg2,
                                                        const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
-                                                       const float* __restrict__ dL_dimage, uint32_t cap, uint32_t pstride,
-                                                       float* __restrict__ partial)
+                                                       const float* __restrict__ dL_dimage, uint32_t cap,
+                                                       float4* __restrict__ partial)
 {
     __shared__ Stage S;
-    __shared__ float sAcc[9][kBatch];
+    __shared__ float sAcc[9 * kBatch];   // [value][splat of the batch]
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -244,6 +287,10 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
     if (tile_last == 0) return;
     const int tile_x = c.tx0 / kTile, tile_y = c.ty0 / kTile;
+    // which of the eight butterfly values this lane ends up holding (see row_sum8)
+    const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
+               r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
+    const int acc_slot = ((r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0)) * kBatch;
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
@@ -251,7 +298,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         uint32_t id; float4 raw, geo;
         stage_batch(S, c, vals, packed, c.start + boff, cnt, id, raw, geo);
 #pragma unroll
-        for (int k = 0; k < 9; ++k) sAcc[k][threadIdx.x] = 0.f;
+        for (int k = 0; k < 9; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {            // else nothing of this batch was blended by this wavefront (uniform per wave)
             for (int k = 3; k >= 0; --k) {
@@ -279,21 +326,11 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                     T = hit ? Tk : T;
                     Sfx += w * cg;
                     const float dsx = ds * dx, dsy = ds * dy;
-                    const float r0 = wave_sum(w * g0), r1 = wave_sum(w * g1), r2 = wave_sum(w * g2c);
-                    const float s0 = wave_sum(ds), s1 = wave_sum(dsx), s2 = wave_sum(dsy);
-                    const float s3 = wave_sum(dsx * dx), s4 = wave_sum(dsx * dy), s5 = wave_sum(dsy * dy);
-                    if (lane < 9) {
-                        float v = r0;
-                        v = lane == 1 ? r1 : v;
-                        v = lane == 2 ? r2 : v;
-                        v = lane == 3 ? s0 : v;
-                        v = lane == 4 ? s1 : v;
-                        v = lane == 5 ? s2 : v;
-                        v = lane == 6 ? s3 : v;
-                        v = lane == 7 ? s4 : v;
-                        v = lane == 8 ? s5 : v;
-                        atomicAdd(&sAcc[lane][j], v);      // LDS float add: the four quadrants meet here
-                    }
+                    const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
+                    const float part = row_sum8(v8, r1, r2, r3);
+                    const float blue = row_sum_to_lane15(w * g2c);
+                    if ((lane & 8) == 0) atomicAdd(&sAcc[acc_slot + j], part);      // 4 rows x 8 values
+                    if ((lane & 15) == 15) atomicAdd(&sAcc[8 * kBatch + j], blue);
                 }
             }
         }
@@ -310,57 +347,73 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
             }
             const uint32_t u = offsets[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
-                const size_t Pc = (size_t)pstride;
-                const float s0 = sAcc[3][threadIdx.x], s1 = sAcc[4][threadIdx.x], s2 = sAcc[5][threadIdx.x];
-                partial[u] = -(raw.x * s1 + raw.y * s2);                 // d mean2d.x
-                partial[Pc + u] = -(raw.z * s2 + raw.y * s1);            // d mean2d.y
-                partial[2 * Pc + u] = 0.5f * sAcc[6][threadIdx.x];       // d conic a
-                partial[3 * Pc + u] = sAcc[7][threadIdx.x];              // d conic b
-                partial[4 * Pc + u] = 0.5f * sAcc[8][threadIdx.x];       // d conic c
-                partial[5 * Pc + u] = raw.w > 0.f ? -s0 / raw.w : 0.f;                     // d opacity
-                partial[6 * Pc + u] = sAcc[0][threadIdx.x];              // d colour
-                partial[7 * Pc + u] = sAcc[1][threadIdx.x];
-                partial[8 * Pc + u] = sAcc[2][threadIdx.x];
+                const float s0 = sAcc[2 * kBatch + threadIdx.x], s1 = sAcc[3 * kBatch + threadIdx.x], s2 = sAcc[4 * kBatch + threadIdx.x];
+                float4* dst = partial + (size_t)3 * u;
+                dst[0] = make_float4(-(raw.x * s1 + raw.y * s2), -(raw.z * s2 + raw.y * s1),          // d mean2d
+                                     0.5f * sAcc[5 * kBatch + threadIdx.x], sAcc[6 * kBatch + threadIdx.x]);              // d conic a, b
+                dst[1] = make_float4(0.5f * sAcc[7 * kBatch + threadIdx.x], raw.w > 0.f ? -s0 / raw.w : 0.f,    // d conic c, d opacity
+                                     sAcc[0 * kBatch + threadIdx.x], sAcc[1 * kBatch + threadIdx.x]);                     // d red, d green
+                dst[2] = make_float4(sAcc[8 * kBatch + threadIdx.x], 0.f, 0.f, 0.f);                            // d blue
             }
         }
         __syncthreads();   // sAcc and the stage are rewritten by the next batch
     }
 }
 
-// One thread per point: add up the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list)
-// into dL/d(splat state); points without pairs get zeros.
+// One thread per point: add up the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list,
+// 48 bytes each) into dL/d(splat state); points without pairs get zeros. A point with more than kGatherSolo pairs
+// is handed to its whole wavefront (64 pairs per step, then a DPP sum), so one large splat does not stall 63 lanes.
+constexpr uint32_t kGatherSolo = 8;
+
 __global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const int32_t* __restrict__ radius,
                                                             const uint32_t* __restrict__ offsets,
-                                                            const float* __restrict__ partial, uint32_t cap,
-                                                            uint32_t pstride, SplatGradDev g2)
+                                                            const float4* __restrict__ partial, uint32_t cap,
+                                                            SplatGradDev g2)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const size_t N = (size_t)n, Pc = (size_t)pstride;
+    const int lane = threadIdx.x & 63;
+    const size_t N = (size_t)n;
     float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (radius[i] > 0) {
-        const uint32_t b = offsets[i], e = min(offsets[i + 1], cap);
+    uint32_t b = 0, e = 0;
+    if (i < n && radius[i] > 0) { b = min(offsets[i], cap); e = min(offsets[i + 1], cap); }
+    const bool big = (e - b) > kGatherSolo;
+    if (!big) {
         for (uint32_t u = b; u < e; ++u) {
-#pragma unroll
-            for (int k = 0; k < 9; ++k) acc[k] += partial[k * Pc + u];
+            const float4 p0 = partial[(size_t)3 * u], p1 = partial[(size_t)3 * u + 1], p2 = partial[(size_t)3 * u + 2];
+            acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
+            acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w; acc[8] += p2.x;
         }
     }
+    unsigned long long todo = __ballot(big);
+    while (todo) {
+        const int src = __builtin_ctzll(todo);
+        todo &= todo - 1ull;
+        const uint32_t bb = (uint32_t)__builtin_amdgcn_readlane((int)b, src), ee = (uint32_t)__builtin_amdgcn_readlane((int)e, src);
+        float t[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (uint32_t u = bb + lane; u < ee; u += 64) {
+            const float4 p0 = partial[(size_t)3 * u], p1 = partial[(size_t)3 * u + 1], p2 = partial[(size_t)3 * u + 2];
+            t[0] += p0.x; t[1] += p0.y; t[2] += p0.z; t[3] += p0.w;
+            t[4] += p1.x; t[5] += p1.y; t[6] += p1.z; t[7] += p1.w; t[8] += p2.x;
+        }
+#pragma unroll
+        for (int k = 0; k < 9; ++k) {
+            const float tot = wave_sum(t[k]);
+            if (lane == src) acc[k] = tot;
+        }
+    }
+    if (i >= n) return;
     g2.mean2d[i] = acc[0]; g2.mean2d[N + i] = acc[1];
     g2.conic[i] = acc[2]; g2.conic[N + i] = acc[3]; g2.conic[2 * N + i] = acc[4];
     g2.opacity[i] = acc[5];
     g2.color[i] = acc[6]; g2.color[N + i] = acc[7]; g2.color[2 * N + i] = acc[8];
 }
 
-// zero the first min(*count_dev, cap) entries of each of the 9 partial planes
-__global__ __launch_bounds__(256) void k_zero_partial(float* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap,
-                                                      uint32_t pstride)
+// zero the partial sums of the first min(pair count, cap) pairs
+__global__ __launch_bounds__(256) void k_zero_partial(float4* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap)
 {
-    const uint32_t P = min(status[kStNumDup], cap);
-    const uint32_t i = (blockIdx.x * 256u + threadIdx.x) * 4u;
-    if (i >= P) return;                      // i + 3 < pstride always: pstride is cap rounded up to a multiple of 4
-#pragma unroll
-    for (int k = 0; k < 9; ++k)
-        *reinterpret_cast<float4*>(partial + (size_t)k * pstride + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    const size_t count = (size_t)3 * min(status[kStNumDup], cap);
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) partial[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // Measurement aid: the forward walk with counters instead of colours. counters[0] += list entries examined per pixel
@@ -438,20 +491,20 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
     const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
-    float* partial = reinterpret_cast<float*>(ws + L.off_partial);
+    float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
     {
         ProfScope prof(kKFill, s);
-        hipLaunchKernelGGL(k_zero_partial, dim3((L.pstride / 4u + 255u) / 256u), dim3(256), 0, s, partial, status, L.cap, L.pstride);
+        hipLaunchKernelGGL(k_zero_partial, dim3((unsigned)(((size_t)3 * L.cap + 255) / 256)), dim3(256), 0, s, partial, status, L.cap);
     }
     {
         ProfScope prof(kKCompositeBwd, s);
         hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, offsets,
-                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, L.pstride, partial);
+                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
         hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, radius, offsets,
-                           partial, L.cap, L.pstride, g2);
+                           partial, L.cap, g2);
     }
     return hipGetLastError();
 }

@@ -63,7 +63,6 @@ struct Layout {
     int sort_bits, sort_passes;
     uint32_t sort_blocks;     // blocks of kSortItems pairs covering `cap`
     uint32_t hist_len;        // 256 * sort_blocks
-    uint32_t pstride;         // elements between the 9 planes of per-pair partial gradient sums (cap rounded up to 4)
     size_t off_status, off_packed, off_offsets, off_scan_part, off_keys0, off_keys1, off_vals0, off_vals1,
         off_hist, off_ranges, off_partial, total;
 };
