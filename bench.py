@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
 ALU_PEAK_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
 
-# algorithmic work per unit (stated in the design doc)
+# algorithmic work per unit: flops per examined and per blended (pixel, splat) pair
 FWD_FLOPS_PER_EXAMINED = 12.0    # 2 sub, 8 for the quadratic form, exp, opacity mul (+ min / compares not counted)
 FWD_FLOPS_PER_BLENDED = 9.0      # 1-alpha, T', w, 3 fma
 BWD_FLOPS_PER_EXAMINED = 12.0    # alpha recomputed
