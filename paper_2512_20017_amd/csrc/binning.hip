@@ -160,54 +160,55 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
     return hipGetLastError();
 }
 
-// One thread per point: write its (tile << 32 | depth bits, index) pairs, row-major over its tile rectangle.
-// A point with more than kDupSolo tiles is handed to its whole wavefront, 64 tiles per step.
-constexpr int kDupSolo = 8;
-
+// Duplication: every (tile, splat) pair of a wavefront's 64 consecutive points is written by whichever lane comes
+// next, so the work is balanced whatever the mix of small and large splats. The pairs of those 64 points occupy
+// one contiguous range of the output (offsets are a prefix sum); lane l writes slots B + l, B + l + 64, ... and
+// finds the owning point of a slot by binary search over the 64 range ends kept in LDS.
+// Pair order within a point: row-major over its tile rectangle.
 __global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ offsets,
                                                    uint64_t* __restrict__ keys, uint32_t* __restrict__ vals, uint32_t cap,
                                                    uint32_t* __restrict__ status)
 {
+    __shared__ uint32_t sEnd[4][64];
     const int i = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int x0 = 0, y0 = 0, x1 = 0, y1 = 0;
     uint32_t bits = 0, at = 0;
     if (i < sp.n) {
+        at = offsets[i];
         const int r = sp.radius[i];
         if (r > 0) {
             rect_of(cam, sp.mean2d[i], sp.mean2d[(size_t)sp.n + i], r, x0, y0, x1, y1);
             bits = __float_as_uint(sp.depth[i]);
-            at = offsets[i];
         }
+    } else {
+        at = offsets[sp.n];                    // the pair total (sentinel slot of the prefix sum)
     }
-    const int w = x1 - x0, cnt = w * (y1 - y0);
+    const int w = x1 - x0;
+    const uint32_t cnt = (uint32_t)(w * (y1 - y0));
+    sEnd[wave][lane] = at + cnt;
+    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)at, 0);
+    const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)(at + cnt), 63);
+    __builtin_amdgcn_wave_barrier();
     bool dropped = false;
-    const bool big = cnt > kDupSolo;
-    if (!big) {
-        for (int t = 0; t < cnt; ++t) {
-            const int ty = y0 + t / w, tx = x0 + t - (t / w) * w;
-            if (at + t < cap) {
-                keys[at + t] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | bits;
-                vals[at + t] = (uint32_t)i;
-            } else {
-                dropped = true;
-            }
-        }
-    }
-    unsigned long long todo = __ballot(big);
-    while (todo) {
-        const int src = __builtin_ctzll(todo);
-        todo &= todo - 1ull;
-        const int sx0 = __builtin_amdgcn_readlane(x0, src), sy0 = __builtin_amdgcn_readlane(y0, src);
-        const int sw = __builtin_amdgcn_readlane(w, src), scnt = __builtin_amdgcn_readlane(cnt, src);
-        const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)bits, src);
-        const uint32_t sat = (uint32_t)__builtin_amdgcn_readlane((int)at, src);
-        const uint32_t sid = (uint32_t)__builtin_amdgcn_readlane(i, src);
-        for (int t = lane; t < scnt; t += 64) {
-            const int ty = sy0 + t / sw, tx = sx0 + t - (t / sw) * sw;
-            if (sat + t < cap) {
-                keys[sat + t] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | sbits;
-                vals[sat + t] = sid;
+    // Uniform trip count: every lane takes part in the cross-lane reads of each step (a lane that has left the loop
+    // could not be read by the others), only lanes with a slot in range store.
+    for (uint32_t base = first; base < last; base += 64) {
+        const uint32_t u = base + lane;
+        const bool mine = u < last;
+        // owner = first lane whose range end exceeds u (clamped for lanes without a slot)
+        int lo = 0;
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1)
+            if (sEnd[wave][lo + step - 1] <= u) lo += step;
+        const int ox0 = __shfl(x0, lo, 64), oy0 = __shfl(y0, lo, 64), ow = __shfl(w, lo, 64);
+        const uint32_t obits = (uint32_t)__shfl((int)bits, lo, 64), oat = (uint32_t)__shfl((int)at, lo, 64);
+        if (mine && ow > 0) {
+            const int t = (int)(u - oat);
+            const int ty = oy0 + t / ow, tx = ox0 + t - (t / ow) * ow;
+            if (u < cap) {
+                keys[u] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | obits;
+                vals[u] = (uint32_t)(blockIdx.x * 256 + wave * 64 + lo);
             } else {
                 dropped = true;
             }
@@ -224,12 +225,13 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint
 
 // One thread per sorted pair: mark where each tile's run starts and ends.
 __global__ __launch_bounds__(256) void k_tile_ranges(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ status,
-                                                     uint32_t cap, uint32_t* __restrict__ ranges)
+                                                     uint32_t cap, uint32_t ntiles, uint32_t* __restrict__ ranges)
 {
     const uint32_t P = min(status[kStNumDup], cap);
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i >= P) return;
     const uint32_t tile = (uint32_t)(keys[i] >> 32);
+    if (tile >= ntiles) return;     // cannot happen for keys written by k_duplicate; keeps the write in bounds regardless
     if (i == 0 || (uint32_t)(keys[i - 1] >> 32) != tile) ranges[2 * tile] = i;
     if (i + 1 == P || (uint32_t)(keys[i + 1] >> 32) != tile) ranges[2 * tile + 1] = i + 1;
 }
@@ -266,7 +268,7 @@ hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout&
         if (e != hipSuccess) return e;
         const uint64_t* sorted = reinterpret_cast<const uint64_t*>(ws + sorted_keys_off(L));
         ProfScope prof(kKTileRanges, s);
-        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, ranges);
+        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
     }
     return hipGetLastError();
 }

@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                                                        float4* __restrict__ partial)
 {
     __shared__ Stage S;
-    __shared__ float sAcc[9 * kBatch];   // [value][splat of the batch]
+    __shared__ float sAcc[12 * kBatch];  // [value][splat of the batch]; blue has one slot per pixel row group (8..11)
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -291,6 +291,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
                r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
     const int acc_slot = ((r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0)) * kBatch;
+    const int blue_slot = (8 + (lane >> 4)) * kBatch;
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
@@ -298,7 +299,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         uint32_t id; float4 raw, geo;
         stage_batch(S, c, vals, packed, c.start + boff, cnt, id, raw, geo);
 #pragma unroll
-        for (int k = 0; k < 9; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
+        for (int k = 0; k < 12; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {            // else nothing of this batch was blended by this wavefront (uniform per wave)
             for (int k = 3; k >= 0; --k) {
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                     const float part = row_sum8(v8, r1, r2, r3);
                     const float blue = row_sum_to_lane15(w * g2c);
                     if ((lane & 8) == 0) atomicAdd(&sAcc[acc_slot + j], part);      // 4 rows x 8 values
-                    if ((lane & 15) == 15) atomicAdd(&sAcc[8 * kBatch + j], blue);
+                    if ((lane & 15) == 15) atomicAdd(&sAcc[blue_slot + j], blue);      // one address per row group
                 }
             }
         }
@@ -353,59 +354,85 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                                      0.5f * sAcc[5 * kBatch + threadIdx.x], sAcc[6 * kBatch + threadIdx.x]);              // d conic a, b
                 dst[1] = make_float4(0.5f * sAcc[7 * kBatch + threadIdx.x], raw.w > 0.f ? -s0 / raw.w : 0.f,    // d conic c, d opacity
                                      sAcc[0 * kBatch + threadIdx.x], sAcc[1 * kBatch + threadIdx.x]);                     // d red, d green
-                dst[2] = make_float4(sAcc[8 * kBatch + threadIdx.x], 0.f, 0.f, 0.f);                            // d blue
+                dst[2] = make_float4((sAcc[8 * kBatch + threadIdx.x] + sAcc[9 * kBatch + threadIdx.x]) +
+                                     (sAcc[10 * kBatch + threadIdx.x] + sAcc[11 * kBatch + threadIdx.x]), 0.f, 0.f, 0.f);                           // d blue
             }
         }
         __syncthreads();   // sAcc and the stage are rewritten by the next batch
     }
 }
 
-// One thread per point: add up the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list,
-// 48 bytes each) into dL/d(splat state); points without pairs get zeros. A point with more than kGatherSolo pairs
-// is handed to its whole wavefront (64 pairs per step, then a DPP sum), so one large splat does not stall 63 lanes.
-constexpr uint32_t kGatherSolo = 8;
-
+// Adds up, per point, the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list, 48 bytes
+// each) into dL/d(splat state); points without pairs get zeros. A wavefront owns 64 consecutive points, whose
+// pairs form one contiguous range: its lanes stream that range 64 pairs at a time (coalesced), find each pair's
+// point by binary search over the 64 range ends in LDS, run a segmented inclusive scan over the 64 pairs (pairs of
+// one point are adjacent lanes), and the last lane of each segment adds the segment total into that point's LDS
+// accumulator - one adder per point and step, so no conflicts.
 __global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const int32_t* __restrict__ radius,
                                                             const uint32_t* __restrict__ offsets,
                                                             const float4* __restrict__ partial, uint32_t cap,
                                                             SplatGradDev g2)
 {
+    __shared__ uint32_t sEnd[4][64];
+    __shared__ float sSum[4][9][64];
     const int i = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)n;
-    float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    uint32_t b = 0, e = 0;
-    if (i < n && radius[i] > 0) { b = min(offsets[i], cap); e = min(offsets[i + 1], cap); }
-    const bool big = (e - b) > kGatherSolo;
-    if (!big) {
-        for (uint32_t u = b; u < e; ++u) {
-            const float4 p0 = partial[(size_t)3 * u], p1 = partial[(size_t)3 * u + 1], p2 = partial[(size_t)3 * u + 2];
-            acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
-            acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w; acc[8] += p2.x;
-        }
-    }
-    unsigned long long todo = __ballot(big);
-    while (todo) {
-        const int src = __builtin_ctzll(todo);
-        todo &= todo - 1ull;
-        const uint32_t bb = (uint32_t)__builtin_amdgcn_readlane((int)b, src), ee = (uint32_t)__builtin_amdgcn_readlane((int)e, src);
-        float t[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (uint32_t u = bb + lane; u < ee; u += 64) {
-            const float4 p0 = partial[(size_t)3 * u], p1 = partial[(size_t)3 * u + 1], p2 = partial[(size_t)3 * u + 2];
-            t[0] += p0.x; t[1] += p0.y; t[2] += p0.z; t[3] += p0.w;
-            t[4] += p1.x; t[5] += p1.y; t[6] += p1.z; t[7] += p1.w; t[8] += p2.x;
-        }
+    uint32_t b, e;
+    if (i < n) { b = min(offsets[i], cap); e = (radius[i] > 0) ? min(offsets[i + 1], cap) : b; }
+    else { b = min(offsets[n], cap); e = b; }
+    sEnd[wave][lane] = e;
 #pragma unroll
-        for (int k = 0; k < 9; ++k) {
-            const float tot = wave_sum(t[k]);
-            if (lane == src) acc[k] = tot;
-        }
+    for (int k = 0; k < 9; ++k) sSum[wave][k][lane] = 0.f;
+    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)b, 0);
+    const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)e, 63);
+    __builtin_amdgcn_wave_barrier();
+    // uniform trip count: every lane takes part in the cross-lane steps; the next step's loads are issued before
+    // this step's scan so that a long range is not one memory latency per 64 pairs
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 n0 = zero4, n1 = zero4, n2 = zero4;
+    if (first + lane < last) {
+        const size_t u0 = (size_t)3 * (first + lane);
+        n0 = partial[u0]; n1 = partial[u0 + 1]; n2 = partial[u0 + 2];
     }
+    for (uint32_t base = first; base < last; base += 64) {
+        const uint32_t u = base + lane;
+        const bool mine = u < last;
+        const float4 p0 = n0, p1 = n1, p2 = n2;
+        n0 = zero4; n1 = zero4; n2 = zero4;
+        if (u + 64 < last) {
+            const size_t un = (size_t)3 * (u + 64);
+            n0 = partial[un]; n1 = partial[un + 1]; n2 = partial[un + 2];
+        }
+        float v[9] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w, p2.x};
+        int owner = 0;
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1)
+            if (sEnd[wave][owner + step - 1] <= u) owner += step;
+        if (!mine) owner = 64 + lane;             // lanes past the end are segments of their own
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o2 = __shfl_up(owner, d, 64);
+            const bool same = (lane >= d) && (o2 == owner);
+#pragma unroll
+            for (int k = 0; k < 9; ++k) {
+                const float t = __shfl_up(v[k], d, 64);
+                v[k] += same ? t : 0.f;
+            }
+        }
+        const int onext = __shfl_down(owner, 1, 64);
+        if (mine && (lane == 63 || onext != owner)) {
+#pragma unroll
+            for (int k = 0; k < 9; ++k) sSum[wave][k][owner] += v[k];
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    __builtin_amdgcn_wave_barrier();
     if (i >= n) return;
-    g2.mean2d[i] = acc[0]; g2.mean2d[N + i] = acc[1];
-    g2.conic[i] = acc[2]; g2.conic[N + i] = acc[3]; g2.conic[2 * N + i] = acc[4];
-    g2.opacity[i] = acc[5];
-    g2.color[i] = acc[6]; g2.color[N + i] = acc[7]; g2.color[2 * N + i] = acc[8];
+    g2.mean2d[i] = sSum[wave][0][lane]; g2.mean2d[N + i] = sSum[wave][1][lane];
+    g2.conic[i] = sSum[wave][2][lane]; g2.conic[N + i] = sSum[wave][3][lane]; g2.conic[2 * N + i] = sSum[wave][4][lane];
+    g2.opacity[i] = sSum[wave][5][lane];
+    g2.color[i] = sSum[wave][6][lane]; g2.color[N + i] = sSum[wave][7][lane]; g2.color[2 * N + i] = sSum[wave][8][lane];
 }
 
 // zero the partial sums of the first min(pair count, cap) pairs

@@ -98,6 +98,7 @@ __device__ __forceinline__ void sh_basis(int deg, float x, float y, float z, flo
     Y[15] = -0.5900435899266435f * x * (xx - 3.f * yy);
 }
 
+template <int kDeg>
 __global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, SplatsDev out)
 {
     const int n = sc.n;
@@ -131,9 +132,10 @@ __global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, Spl
     const float vx = m0 - cam.campos[0], vy = m1 - cam.campos[1], vz = m2 - cam.campos[2];
     const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
     float Y[16];
-    sh_basis(sc.sh_degree, vx * vinv, vy * vinv, vz * vinv, Y);
-    const int K = (sc.sh_degree + 1) * (sc.sh_degree + 1);
+    sh_basis(kDeg, vx * vinv, vy * vinv, vz * vinv, Y);
+    constexpr int K = (kDeg + 1) * (kDeg + 1);
     float rgb[3] = {0.5f, 0.5f, 0.5f};
+#pragma unroll
     for (int k = 0; k < K; ++k) {
 #pragma unroll
         for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * sc.sh[(size_t)(3 * k + c) * N + i];
@@ -175,6 +177,7 @@ __device__ __forceinline__ void sh_basis_grad(int deg, float x, float y, float z
     dY[15][0] = -3.f * c3a * (xx - yy);        dY[15][1] = 6.f * c3a * x * y;
 }
 
+template <int kDeg>
 __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ radius,
                                                         SplatGradDev g2, SceneGradDev g)
 {
@@ -207,14 +210,15 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
         const float dx = vx * vinv, dy = vy * vinv, dz = vz * vinv;
         float Y[16];
         float dY[16][3];
-        sh_basis(sc.sh_degree, dx, dy, dz, Y);
-        sh_basis_grad(sc.sh_degree, dx, dy, dz, dY);
-        const int K = (sc.sh_degree + 1) * (sc.sh_degree + 1);
+        sh_basis(kDeg, dx, dy, dz, Y);
+        sh_basis_grad(kDeg, dx, dy, dz, dY);
+        constexpr int K = (kDeg + 1) * (kDeg + 1);
         float gd0 = 0.f, gd1 = 0.f, gd2 = 0.f;
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             float raw = 0.5f;
             float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+#pragma unroll
             for (int k = 0; k < K; ++k) {
                 const float co = sc.sh[(size_t)(3 * k + c) * N + i];
                 raw += Y[k] * co;
@@ -222,6 +226,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
             }
             const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
             if (gc != 0.f) {
+#pragma unroll
                 for (int k = 0; k < K; ++k) g.sh[(size_t)(3 * k + c) * N + i] += Y[k] * gc;
             }
             gd0 += gc * t0; gd1 += gc * t1; gd2 += gc * t2;
@@ -307,7 +312,12 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocess, s);
-    hipLaunchKernelGGL(k_preprocess, dim3(blocks), dim3(256), 0, s, sc, cam, out);
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL(k_preprocess<0>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        case 1: hipLaunchKernelGGL(k_preprocess<1>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        case 2: hipLaunchKernelGGL(k_preprocess<2>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        default: hipLaunchKernelGGL(k_preprocess<3>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+    }
     return hipGetLastError();
 }
 
@@ -317,7 +327,12 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    hipLaunchKernelGGL(k_preprocess_bwd, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g);
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL(k_preprocess_bwd<0>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        case 1: hipLaunchKernelGGL(k_preprocess_bwd<1>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        case 2: hipLaunchKernelGGL(k_preprocess_bwd<2>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        default: hipLaunchKernelGGL(k_preprocess_bwd<3>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+    }
     return hipGetLastError();
 }
 

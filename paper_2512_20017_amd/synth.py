@@ -69,6 +69,31 @@ def _gmm_means(rng, n, n_comp, lo, hi, sig_lo, sig_hi, z_squash=1.0):
     return (centres[comp] + noise * sig[comp][:, None]).astype(np.float32)
 
 
+def _part1by2(v):
+    """Spread the low 21 bits of v so that two zero bits separate consecutive bits."""
+    v = v.astype(np.uint64) & np.uint64(0x1FFFFF)
+    v = (v | (v << np.uint64(32))) & np.uint64(0x1F00000000FFFF)
+    v = (v | (v << np.uint64(16))) & np.uint64(0x1F0000FF0000FF)
+    v = (v | (v << np.uint64(8))) & np.uint64(0x100F00F00F00F00F)
+    v = (v | (v << np.uint64(4))) & np.uint64(0x10C30C30C30C30C3)
+    v = (v | (v << np.uint64(2))) & np.uint64(0x1249249249249249)
+    return v
+
+
+def zorder_permutation(mean):
+    """Permutation that puts points in Z-order (Morton order) of their positions, 21 bits per axis.
+    The paper keeps its point cloud in this order so that contiguous blocks of points are spatially local
+    (Sec. 4.2.1 point groups; App. D.1 "Z-order linearization")."""
+    lo = mean.min(axis=0).astype(np.float64); hi = mean.max(axis=0).astype(np.float64)
+    q = ((mean.astype(np.float64) - lo) / np.maximum(hi - lo, 1e-30) * (2 ** 21 - 1)).astype(np.uint64)
+    code = _part1by2(q[:, 0]) | (_part1by2(q[:, 1]) << np.uint64(1)) | (_part1by2(q[:, 2]) << np.uint64(2))
+    return np.argsort(code, kind="stable")
+
+
+def _reorder(scene, perm):
+    return {k: (v[perm] if isinstance(v, np.ndarray) else v) for k, v in scene.items()}
+
+
 def scene_tiny(seed=0, n=4096, sh_degree=0):
     """Config 1: means U[-1,1]^3, log-scales N(-3.5,0.3), opacity sigmoid(N(0,1)), degree-0 RGB ~ U[0,1]."""
     rng = _rng(seed, 1)
@@ -82,12 +107,14 @@ def camera_tiny(width=128, height=128):
     return pinhole(width, height, 60.0, np.eye(3), [0.0, 0.0, 3.0])
 
 
-def scene_mid(seed=0, n=1_000_000, sh_degree=3, n_comp=64):
-    """Config 2/3: 64-component mixture in a 20^3 box, log-scales N(-4,0.5), opacity sigmoid(N(0,1.5)), SH3."""
+def scene_mid(seed=0, n=1_000_000, sh_degree=3, n_comp=64, zorder=True):
+    """Config 2/3: 64-component mixture in a 20^3 box, log-scales N(-4,0.5), opacity sigmoid(N(0,1.5)), SH3.
+    Points are stored in Z-order of their positions, as the paper's system stores its point cloud."""
     rng = _rng(seed, 2)
     mean = _gmm_means(rng, n, n_comp, [-10, -10, -10], [10, 10, 10], 0.3, 2.0)
     log_scale, quat, logit, sh = _attributes(rng, n, sh_degree, -4.0, 0.5, 1.5, "dc")
-    return dict(mean=mean, log_scale=log_scale, quat=quat, logit=logit, sh=sh, sh_degree=sh_degree)
+    sc = dict(mean=mean, log_scale=log_scale, quat=quat, logit=logit, sh=sh, sh_degree=sh_degree)
+    return _reorder(sc, zorder_permutation(mean)) if zorder else sc
 
 
 def cameras_sphere(count=16, radius=15.0, width=1920, height=1080, fov_deg=60.0):
@@ -104,12 +131,13 @@ def cameras_sphere(count=16, radius=15.0, width=1920, height=1080, fov_deg=60.0)
     return cams
 
 
-def scene_large(seed=0, n=8_000_000, sh_degree=3, n_comp=512):
+def scene_large(seed=0, n=8_000_000, sh_degree=3, n_comp=512, zorder=True):
     """Config 4: one GPU's share of a city-scale scene: 512-component mixture over 200 x 200 x 30 m, z up."""
     rng = _rng(seed, 4)
     mean = _gmm_means(rng, n, n_comp, [-100, -100, 0], [100, 100, 30], 1.0, 8.0, z_squash=0.3)
     log_scale, quat, logit, sh = _attributes(rng, n, sh_degree, -4.0, 0.5, 1.5, "dc")
-    return dict(mean=mean, log_scale=log_scale, quat=quat, logit=logit, sh=sh, sh_degree=sh_degree)
+    sc = dict(mean=mean, log_scale=log_scale, quat=quat, logit=logit, sh=sh, sh_degree=sh_degree)
+    return _reorder(sc, zorder_permutation(mean)) if zorder else sc
 
 
 def cameras_street(seed=0, count=8, width=3840, height=2160, fov_deg=70.0):
