@@ -135,13 +135,14 @@ def main():
 
     # ---- roofline of the dominant kernel
     K = (scene.sh_degree + 1) ** 2
-    hbm_bytes = {
+    tile_passes = max(1, (max(1, (((W + 15) // 16) * ((H + 15) // 16) - 1).bit_length()) + 7) // 8)
+    hbm_bytes = {   # algorithmic bytes per step
         "k_preprocess": 16.0 * n + (32.0 + 12.0 * K + 40.0) * n_vis,
-        "k_count_pack": 8.0 * n + (36.0 + 48.0) * n_vis,
-        "k_duplicate": 8.0 * n + 16.0 * n_vis + 12.0 * P,
-        "k_radix_hist": 8.0 * P,
-        "k_radix_scatter": 24.0 * P,
-        "k_tile_ranges": 8.0 * P,
+        "k_count_pack": 20.0 * n + (36.0 + 48.0) * n_vis,
+        "k_duplicate": 12.0 * n + 12.0 * n_vis + 8.0 * P,
+        "k_radix_hist": 4.0 * n + 4.0 * P,
+        "k_radix_scatter": 4 * 16.0 * n + tile_passes * 16.0 * P,
+        "k_tile_ranges": 4.0 * P,
         "k_gather_splat_grads": 8.0 * n + 48.0 * P + 36.0 * n,
         "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K + 2 * (44.0 + 12.0 * K)) * n_vis,
     }
@@ -155,7 +156,7 @@ def main():
                         frac=ach / ALU_PEAK_TFLOPS, traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt,
                         flops_per_launch=alu_flops[dominant])
     elif dominant in hbm_bytes:
-        ach = hbm_bytes[dominant] / (dom_avg_ms * 1e-3) / 1e9
+        ach = hbm_bytes[dominant] / (dom_ms / args.steps * 1e-3) / 1e9
         roofline = dict(kernel=dominant, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=ach / HBM_PEAK_GBS, traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt,
                         bytes_per_launch=hbm_bytes[dominant])
@@ -163,12 +164,11 @@ def main():
         roofline = dict(kernel=dominant, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None,
                         traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt)
     for name, rec in per_kernel.items():
-        t = rec["ms_per_step"] / max(rec["launches_per_step"], 1) * 1e-3
+        t = rec["ms_per_step"] * 1e-3
         if name in alu_flops:
             rec["tflops"] = alu_flops[name] / t / 1e12
         elif name in hbm_bytes:
-            lp = rec["launches_per_step"]
-            rec["gbs"] = hbm_bytes[name] / (rec["ms_per_step"] / lp * 1e-3) / 1e9
+            rec["gbs"] = hbm_bytes[name] / t / 1e9
 
     # ---- CPU oracle on the host cores: one full view of the same workload (forward + backward)
     cpu = None

@@ -111,7 +111,8 @@ int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_
 int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream);
 
 /* The sorting half of image_render (Sec. 2.1: "sorts these view-dependent splats by their distance to the camera
- * plane"): per-splat tile count, device prefix sum, (tile << 32 | depth bits) keys, radix sort, per-tile ranges.
+ * plane"): per-splat tile count, radix sort in the order of the key (tile << 32 | depth bits) - depth digits on the
+ * splats, device prefix sum, duplication, tile digits on the pairs - and per-tile ranges.
  * Results stay in the workspace; pbdr_lists_view gives their addresses. If more than dup_capacity pairs exist the
  * excess is dropped, nothing is written out of bounds, and pbdr_query_lists reports PBDR_ERR_CAPACITY. */
 int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t dup_capacity, void* workspace,
@@ -140,10 +141,12 @@ int pbdr_preprocess_bwd(const pbdr_scene* scene, const pbdr_camera* cam, const p
 
 /* Device addresses, inside a workspace laid out for these sizes, of the results of pbdr_bin_sort / pbdr_render_fwd:
  * sorted keys [P] (tile << 32 | bits(depth)), vals [P] (point index), ranges [tiles][2] ([start,end) per tile,
- * {0,0} for an empty tile), num_dup [1] (P before clamping to dup_capacity). Any out pointer may be NULL. */
+ * {0,0} for an empty tile), num_dup [1] (P before clamping to dup_capacity). Any out pointer may be NULL.
+ * The 64-bit keys are not kept by the sort; asking for them enqueues one small kernel on hip_stream that rebuilds
+ * them into a scratch part of the workspace (valid until the next call that uses this workspace). */
 int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
-                    uint64_t dup_capacity, const uint64_t** keys, const uint32_t** vals, const uint32_t** ranges,
-                    const uint32_t** num_dup);
+                    uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
+                    const uint32_t** ranges, const uint32_t** num_dup);
 
 /* Synchronises hip_stream and reads back the number of (tile, splat) pairs found by the last pbdr_bin_sort /
  * pbdr_render_fwd on this workspace. Returns PBDR_ERR_CAPACITY if it exceeded dup_capacity (the lists were then

@@ -277,7 +277,7 @@ def pbdr_lists_view(ws, n, width, height, dup_capacity):
     """Copies the sorted lists out of the workspace (synchronises): dict(P, keys, vals, ranges) as numpy."""
     keys, vals, ranges, nd = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
     _check(lib().pbdr_lists_view(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
-                                 C.c_int32(height), C.c_uint64(dup_capacity), C.byref(keys), C.byref(vals),
+                                 C.c_int32(height), C.c_uint64(dup_capacity), _stream(None), C.byref(keys), C.byref(vals),
                                  C.byref(ranges), C.byref(nd)))
     torch.cuda.synchronize()
     base = ws.data_ptr()

@@ -14,30 +14,36 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
 {
     if (n < 0 || W <= 0 || H <= 0 || W > 65536 || H > 65536) return false;
     if (cap == 0) cap = 1;
-    if (cap > 0x7fffffffull) return false;
+    if (cap > 0x3fffffffull) return false;
     L->n = n; L->W = W; L->H = H;
     L->TX = (W + kTile - 1) / kTile; L->TY = (H + kTile - 1) / kTile;
     L->tiles = L->TX * L->TY;
     L->cap = (uint32_t)cap;
-    int tile_bits = 0;
-    while ((1 << tile_bits) < L->tiles) ++tile_bits;
-    L->sort_bits = 32 + tile_bits;
-    L->sort_passes = (L->sort_bits + 7) / 8;
-    L->sort_blocks = (uint32_t)((cap + kSortItems - 1) / kSortItems);
-    L->hist_len = 256u * L->sort_blocks;
-    const size_t scan_max = (size_t)((uint32_t)n > L->hist_len ? (uint32_t)n : L->hist_len);
+    L->tile_bits = 0;
+    while ((1 << L->tile_bits) < L->tiles) ++L->tile_bits;
+    L->tile_passes = L->tile_bits == 0 ? 1 : (L->tile_bits + 7) / 8;
+    const size_t nblk_d = ((size_t)n + kSortItems - 1) / kSortItems, nblk_t = ((size_t)cap + kSortItems - 1) / kSortItems;
     size_t off = 0;
-    L->off_status = off;    off = align256(off + kStWords * sizeof(uint32_t));
-    L->off_packed = off;    off = align256(off + (size_t)n * sizeof(Packed));
-    L->off_offsets = off;   off = align256(off + ((size_t)n + 1) * sizeof(uint32_t));
-    L->off_scan_part = off; off = align256(off + (scan_max / kScanItems + 4) * sizeof(uint32_t));
-    L->off_keys0 = off;     off = align256(off + (size_t)cap * sizeof(uint64_t));
-    L->off_keys1 = off;     off = align256(off + (size_t)cap * sizeof(uint64_t));
-    L->off_vals0 = off;     off = align256(off + (size_t)cap * sizeof(uint32_t));
-    L->off_vals1 = off;     off = align256(off + (size_t)cap * sizeof(uint32_t));
-    L->off_hist = off;      off = align256(off + (size_t)L->hist_len * sizeof(uint32_t));
-    L->off_ranges = off;    off = align256(off + (size_t)L->tiles * 2 * sizeof(uint32_t));
-    L->off_partial = off;   off = align256(off + (size_t)cap * 12 * sizeof(float));
+    const auto take = [&](size_t bytes) { const size_t at = off; off = align256(off + bytes); return at; };
+    L->off_status = take(kStWords * sizeof(uint32_t));
+    L->off_packed = take((size_t)n * sizeof(Packed));
+    L->off_touched = take((size_t)n * sizeof(uint32_t));
+    L->off_offsets = take(((size_t)n + 1) * sizeof(uint32_t));
+    L->off_slot_base = take((size_t)n * sizeof(uint32_t));
+    L->off_scan_part = take(((size_t)n / kScanItems + 8) * sizeof(uint32_t));
+    L->off_dkey0 = take((size_t)n * sizeof(uint32_t));
+    L->off_dkey1 = take((size_t)n * sizeof(uint32_t));
+    L->off_dval0 = take((size_t)n * sizeof(uint32_t));
+    L->off_dval1 = take((size_t)n * sizeof(uint32_t));
+    L->off_tkey0 = take((size_t)cap * sizeof(uint32_t));
+    L->off_tval0 = take((size_t)cap * sizeof(uint32_t));
+    L->off_tkey1 = take((size_t)cap * sizeof(uint32_t));
+    L->off_tval1 = take((size_t)cap * sizeof(uint32_t));
+    L->off_totals = take((size_t)2 * 4 * 256 * sizeof(uint32_t));   // digit totals of the depth sort, then of the tile sort
+    L->off_tile_hist = take((nblk_d > nblk_t ? nblk_d : nblk_t) * 256 * sizeof(uint32_t));
+    L->off_ranges = take((size_t)L->tiles * 2 * sizeof(uint32_t));
+    L->off_partial = take((size_t)cap * 12 * sizeof(float));
+    L->off_keys64 = take((size_t)cap * sizeof(uint64_t));
     L->total = off;
     return true;
 }
@@ -202,8 +208,8 @@ int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pb
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
     const CamDev c = to_dev(cam);
-    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, splats->radius, bg, final_T, last_idx, dL_dimage,
-                                        dev(g_splats), (hipStream_t)hip_stream);
+    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
+                                        (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
     return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), (hipStream_t)hip_stream));
 }
@@ -219,14 +225,20 @@ int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, 
 }
 
 int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
-                    uint64_t dup_capacity, const uint64_t** keys, const uint32_t** vals, const uint32_t** ranges,
-                    const uint32_t** num_dup)
+                    uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
+                    const uint32_t** ranges, const uint32_t** num_dup)
 {
     Layout L;
     const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
     char* ws = (char*)workspace;
-    if (keys) *keys = reinterpret_cast<const uint64_t*>(ws + sorted_keys_off(L));
+    if (keys) {
+        if (n > 0) {
+            const hipError_t e = launch_make_keys64(L, ws, (hipStream_t)hip_stream);
+            if (e != hipSuccess) return hip_result(e);
+        }
+        *keys = reinterpret_cast<const uint64_t*>(ws + L.off_keys64);
+    }
     if (vals) *vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     if (ranges) *ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
     if (num_dup) *num_dup = reinterpret_cast<const uint32_t*>(ws + L.off_status) + kStNumDup;
@@ -239,7 +251,7 @@ int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t
     Layout L;
     const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
-    uint32_t host[2] = {0, 0};
+    uint32_t host[4] = {0, 0, 0, 0};
     hipError_t e = hipMemcpyAsync(host, (char*)workspace + L.off_status, sizeof(host), hipMemcpyDeviceToHost,
                                   (hipStream_t)hip_stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);

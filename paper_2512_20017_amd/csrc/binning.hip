@@ -1,6 +1,12 @@
-// Tile binning: per-splat tile count + raster record, device prefix sum, key/value duplication, tile ranges.
-// These are the steps between pts_splatting and the per-pixel blend that realise "sorts these view-dependent
-// splats by their distance to the camera plane" (paper Sec. 2.1) per 16x16 tile.  All HBM-bound, integer work.
+// Tile binning: per-splat tile count + raster record, depth order of the splats, device prefix sum, key/value
+// duplication in depth order, stable sort by tile, tile ranges. These are the steps between pts_splatting and the
+// per-pixel blend that realise "sorts these view-dependent splats by their distance to the camera plane" (paper
+// Sec. 2.1) per 16x16 tile.  All HBM-bound, integer work.
+//
+// The tile lists are ordered by the 64-bit key (tile << 32 | depth bits), ties by splat index. The sort is a
+// least-significant-digit radix sort of that key whose four depth digits are sorted on the n splats, before
+// duplication (every duplicate of a splat carries the same depth bits), and whose tile digits are sorted on the P
+// pairs afterwards: the same permutation for a fraction of the traffic.
 #include "pbdr_internal.h"
 
 namespace pbdr {
@@ -16,16 +22,17 @@ __device__ __forceinline__ void rect_of(const CamDev& cam, float mx, float my, i
     y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
 }
 
-// One thread per point: number of tiles its square touches, and the 48-byte raster record.
+// One thread per point: number of tiles its square touches, the 48-byte raster record, and the (depth bits, index)
+// pair for the depth sort (culled points get the largest key and sort to the end).
 __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, uint32_t* __restrict__ tiles_touched,
-                                                    Packed* __restrict__ packed)
+                                                    Packed* __restrict__ packed, uint32_t* __restrict__ dkey,
+                                                    uint32_t* __restrict__ dval)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i > sp.n) return;
-    if (i == sp.n) { tiles_touched[i] = 0; return; }   // sentinel: the scan then leaves the pair total at offsets[n]
+    if (i >= sp.n) return;
     const size_t N = (size_t)sp.n;
     const int r = sp.radius[i];
-    uint32_t cnt = 0;
+    uint32_t cnt = 0, key = 0xFFFFFFFFu;
     if (r > 0) {
         const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
         int x0, y0, x1, y1;
@@ -34,9 +41,23 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, ui
         float4* dst = reinterpret_cast<float4*>(packed + i);
         dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
         dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
-        dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), 0.f, 0.f);
+        const float depth = sp.depth[i];
+        key = __float_as_uint(depth);
+        dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), depth, 0.f);
     }
     tiles_touched[i] = cnt;
+    dkey[i] = key;
+    dval[i] = (uint32_t)i;
+}
+
+// tile counts in depth order (rank r holds the point order[r]); slot n is the sentinel that makes the scan leave
+// the pair total at offsets[n]
+__global__ __launch_bounds__(256) void k_rank_counts(int n, const uint32_t* __restrict__ order,
+                                                     const uint32_t* __restrict__ tiles_touched, uint32_t* __restrict__ counts)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r > n) return;
+    counts[r] = (r < n) ? tiles_touched[order[r]] : 0u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -160,27 +181,28 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
     return hipGetLastError();
 }
 
-// Duplication: every (tile, splat) pair of a wavefront's 64 consecutive points is written by whichever lane comes
-// next, so the work is balanced whatever the mix of small and large splats. The pairs of those 64 points occupy
-// one contiguous range of the output (offsets are a prefix sum); lane l writes slots B + l, B + l + 64, ... and
-// finds the owning point of a slot by binary search over the 64 range ends kept in LDS.
-// Pair order within a point: row-major over its tile rectangle.
-__global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ offsets,
-                                                   uint64_t* __restrict__ keys, uint32_t* __restrict__ vals, uint32_t cap,
-                                                   uint32_t* __restrict__ status)
+// Duplication, in depth order: rank r handles point order[r]. Every (tile, splat) pair of a wavefront's 64
+// consecutive ranks is written by whichever lane comes next, so the work is balanced whatever the mix of small and
+// large splats. The pairs of those 64 ranks occupy one contiguous range of the output (offsets are a prefix sum);
+// lane l writes slots B + l, B + l + 64, ... and finds the owning rank of a slot by binary search over the 64 range
+// ends kept in LDS. Pair order within a point: row-major over its tile rectangle. Also records, per point, where
+// its pairs start (slot_base), which the backward pass uses to address its per-pair sums.
+__global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ order,
+                                                   const uint32_t* __restrict__ offsets, uint32_t* __restrict__ tkeys,
+                                                   uint32_t* __restrict__ tvals, uint32_t* __restrict__ slot_base,
+                                                   uint32_t cap, uint32_t* __restrict__ status)
 {
     __shared__ uint32_t sEnd[4][64];
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.x * 256 + threadIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int x0 = 0, y0 = 0, x1 = 0, y1 = 0;
-    uint32_t bits = 0, at = 0;
-    if (i < sp.n) {
-        at = offsets[i];
-        const int r = sp.radius[i];
-        if (r > 0) {
-            rect_of(cam, sp.mean2d[i], sp.mean2d[(size_t)sp.n + i], r, x0, y0, x1, y1);
-            bits = __float_as_uint(sp.depth[i]);
-        }
+    uint32_t at = 0, id = 0;
+    if (r < sp.n) {
+        at = offsets[r];
+        id = order[r];
+        const int rad = sp.radius[id];
+        if (rad > 0) rect_of(cam, sp.mean2d[id], sp.mean2d[(size_t)sp.n + id], rad, x0, y0, x1, y1);
+        slot_base[id] = at;
     } else {
         at = offsets[sp.n];                    // the pair total (sentinel slot of the prefix sum)
     }
@@ -202,13 +224,13 @@ __global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, con
         for (int step = 32; step >= 1; step >>= 1)
             if (sEnd[wave][lo + step - 1] <= u) lo += step;
         const int ox0 = __shfl(x0, lo, 64), oy0 = __shfl(y0, lo, 64), ow = __shfl(w, lo, 64);
-        const uint32_t obits = (uint32_t)__shfl((int)bits, lo, 64), oat = (uint32_t)__shfl((int)at, lo, 64);
+        const uint32_t oid = (uint32_t)__shfl((int)id, lo, 64), oat = (uint32_t)__shfl((int)at, lo, 64);
         if (mine && ow > 0) {
             const int t = (int)(u - oat);
             const int ty = oy0 + t / ow, tx = ox0 + t - (t / ow) * ow;
             if (u < cap) {
-                keys[u] = ((uint64_t)(uint32_t)(ty * cam.TX + tx) << 32) | obits;
-                vals[u] = (uint32_t)(blockIdx.x * 256 + wave * 64 + lo);
+                tkeys[u] = (uint32_t)(ty * cam.TX + tx);
+                tvals[u] = oid;
             } else {
                 dropped = true;
             }
@@ -224,50 +246,90 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint
 }
 
 // One thread per sorted pair: mark where each tile's run starts and ends.
-__global__ __launch_bounds__(256) void k_tile_ranges(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ status,
+__global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict__ tkeys, const uint32_t* __restrict__ status,
                                                      uint32_t cap, uint32_t ntiles, uint32_t* __restrict__ ranges)
 {
     const uint32_t P = min(status[kStNumDup], cap);
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i >= P) return;
-    const uint32_t tile = (uint32_t)(keys[i] >> 32);
+    const uint32_t tile = tkeys[i];
     if (tile >= ntiles) return;     // cannot happen for keys written by k_duplicate; keeps the write in bounds regardless
-    if (i == 0 || (uint32_t)(keys[i - 1] >> 32) != tile) ranges[2 * tile] = i;
-    if (i + 1 == P || (uint32_t)(keys[i + 1] >> 32) != tile) ranges[2 * tile + 1] = i + 1;
+    if (i == 0 || tkeys[i - 1] != tile) ranges[2 * tile] = i;
+    if (i + 1 == P || tkeys[i + 1] != tile) ranges[2 * tile + 1] = i + 1;
+}
+
+// Inspection only: the 64-bit keys (tile << 32 | depth bits) of the sorted pairs, rebuilt from the sorted tile ids
+// and the depth kept in the raster record.
+__global__ __launch_bounds__(256) void k_make_keys64(const uint32_t* __restrict__ tkeys, const uint32_t* __restrict__ tvals,
+                                                     const Packed* __restrict__ packed, const uint32_t* __restrict__ status,
+                                                     uint32_t cap, uint64_t* __restrict__ keys64)
+{
+    const uint32_t P = min(status[kStNumDup], cap);
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= P) return;
+    keys64[i] = ((uint64_t)tkeys[i] << 32) | __float_as_uint(packed[tvals[i]].depth);
+}
+
+hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s)
+{
+    const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
+    const uint32_t* tk = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
+    const uint32_t* tv = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
+    hipLaunchKernelGGL(k_make_keys64, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, tk, tv,
+                       reinterpret_cast<const Packed*>(ws + L.off_packed), status, L.cap,
+                       reinterpret_cast<uint64_t*>(ws + L.off_keys64));
+    return hipGetLastError();
 }
 
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     Packed* packed = reinterpret_cast<Packed*>(ws + L.off_packed);
+    uint32_t* touched = reinterpret_cast<uint32_t*>(ws + L.off_touched);
     uint32_t* offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
+    uint32_t* slot_base = reinterpret_cast<uint32_t*>(ws + L.off_slot_base);
     uint32_t* part = reinterpret_cast<uint32_t*>(ws + L.off_scan_part);
-    uint64_t* keys0 = reinterpret_cast<uint64_t*>(ws + L.off_keys0);
-    uint32_t* vals0 = reinterpret_cast<uint32_t*>(ws + L.off_vals0);
     uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
+    uint32_t* dk[2] = {reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dkey1)};
+    uint32_t* dv[2] = {reinterpret_cast<uint32_t*>(ws + L.off_dval0), reinterpret_cast<uint32_t*>(ws + L.off_dval1)};
+    uint32_t* tk[2] = {reinterpret_cast<uint32_t*>(ws + L.off_tkey0), reinterpret_cast<uint32_t*>(ws + L.off_tkey1)};
+    uint32_t* tv[2] = {reinterpret_cast<uint32_t*>(ws + L.off_tval0), reinterpret_cast<uint32_t*>(ws + L.off_tval1)};
+    uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
+    uint32_t* tile_hist = reinterpret_cast<uint32_t*>(ws + L.off_tile_hist);
     const unsigned nblk = (unsigned)((sp.n + 255) / 256);
-
     {
+        // status words, digit totals and tile ranges start at zero
         ProfScope prof(kKFill, s);
         hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
+        hipLaunchKernelGGL(k_fill_u32, dim3(8), dim3(256), 0, s, totals, 0u, (size_t)2048);
         hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
                            2 * (size_t)L.tiles);
     }
-    if (sp.n > 0) {
-        {
-            ProfScope prof(kKCountPack, s);
-            hipLaunchKernelGGL(k_count_pack, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp, cam, offsets, packed);
-        }
-        hipError_t e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n + 1u, part, status + kStNumDup, s);
-        if (e != hipSuccess) return e;
-        {
-            ProfScope prof(kKDuplicate, s);
-            hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, offsets, keys0, vals0, L.cap, status);
-        }
-        e = launch_radix_sort(L, ws, s);
-        if (e != hipSuccess) return e;
-        const uint64_t* sorted = reinterpret_cast<const uint64_t*>(ws + sorted_keys_off(L));
+    if (sp.n == 0) return hipGetLastError();
+    {
+        ProfScope prof(kKCountPack, s);
+        hipLaunchKernelGGL(k_count_pack, dim3(nblk), dim3(256), 0, s, sp, cam, touched, packed, dk[0], dv[0]);
+    }
+    // depth digits: sort the n splats by their 32 depth bits (4 passes, result back in buffer 0)
+    hipError_t e = launch_radix_sort32(dk, dv, nullptr, (uint32_t)sp.n, 4, totals, tile_hist, s);
+    if (e != hipSuccess) return e;
+    const uint32_t* order = dv[0];
+    {
+        ProfScope prof(kKCountPack, s);
+        hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp.n, order, touched, offsets);
+    }
+    e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n + 1u, part, status + kStNumDup, s);
+    if (e != hipSuccess) return e;
+    {
+        ProfScope prof(kKDuplicate, s);
+        hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, order, offsets, tk[0], tv[0], slot_base, L.cap, status);
+    }
+    // tile digits: stable sort of the P pairs by tile id
+    e = launch_radix_sort32(tk, tv, status + kStNumDup, L.cap, L.tile_passes, totals + 1024, tile_hist, s);
+    if (e != hipSuccess) return e;
+    {
         ProfScope prof(kKTileRanges, s);
+        const uint32_t* sorted = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
         hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
     }
     return hipGetLastError();

@@ -254,12 +254,12 @@ __device__ __forceinline__ float row_sum_to_lane15(float v)
 //
 // No global atomics: each wavefront reduces its rows of 16 pixels with DPP, the 16 rows of the tile meet in an LDS
 // accumulator (ds_add_f32), and the thread that staged splat j writes the tile's nine sums for it to partial[u]
-// (12 floats per pair), where u is the pair's position in the unsorted duplicate list (offsets[id] + rank of this
+// (12 floats per pair), where u is the pair's position in the unsorted duplicate list (slot_base[id] + rank of this
 // tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them up afterwards
 // (k_gather_splat_grads).
 __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
-                                                       const uint32_t* __restrict__ offsets, float bg0, float bg1, float bg2,
+                                                       const uint32_t* __restrict__ slot_base, float bg0, float bg1, float bg2,
                                                        const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
                                                        const float* __restrict__ dL_dimage, uint32_t cap,
                                                        float4* __restrict__ partial)
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                 x0 = min(max((ix - r) >> 4, 0), cam.TX); y0 = min(max((iy - r) >> 4, 0), cam.TY);
                 x1 = min(max((ix + r + 15) >> 4, 0), cam.TX); y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
             }
-            const uint32_t u = offsets[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
+            const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
                 const float s0 = sAcc[2 * kBatch + threadIdx.x], s1 = sAcc[3 * kBatch + threadIdx.x], s2 = sAcc[4 * kBatch + threadIdx.x];
                 float4* dst = partial + (size_t)3 * u;
@@ -363,23 +363,23 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
 }
 
 // Adds up, per point, the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list, 48 bytes
-// each) into dL/d(splat state); points without pairs get zeros. A wavefront owns 64 consecutive points, whose
+// each) into dL/d(splat state); points without pairs get zeros. A wavefront owns 64 consecutive depth ranks, whose
 // pairs form one contiguous range: its lanes stream that range 64 pairs at a time (coalesced), find each pair's
 // point by binary search over the 64 range ends in LDS, run a segmented inclusive scan over the 64 pairs (pairs of
 // one point are adjacent lanes), and the last lane of each segment adds the segment total into that point's LDS
 // accumulator - one adder per point and step, so no conflicts.
-__global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const int32_t* __restrict__ radius,
+__global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const uint32_t* __restrict__ order,
                                                             const uint32_t* __restrict__ offsets,
                                                             const float4* __restrict__ partial, uint32_t cap,
                                                             SplatGradDev g2)
 {
     __shared__ uint32_t sEnd[4][64];
     __shared__ float sSum[4][9][64];
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.x * 256 + threadIdx.x;     // rank in depth order; its pairs are [offsets[r], offsets[r+1])
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)n;
     uint32_t b, e;
-    if (i < n) { b = min(offsets[i], cap); e = (radius[i] > 0) ? min(offsets[i + 1], cap) : b; }
+    if (r < n) { b = min(offsets[r], cap); e = min(offsets[r + 1], cap); }
     else { b = min(offsets[n], cap); e = b; }
     sEnd[wave][lane] = e;
 #pragma unroll
@@ -428,7 +428,8 @@ __global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const int32_t
         __builtin_amdgcn_wave_barrier();
     }
     __builtin_amdgcn_wave_barrier();
-    if (i >= n) return;
+    if (r >= n) return;
+    const uint32_t i = order[r];
     g2.mean2d[i] = sSum[wave][0][lane]; g2.mean2d[N + i] = sSum[wave][1][lane];
     g2.conic[i] = sSum[wave][2][lane]; g2.conic[N + i] = sSum[wave][3][lane]; g2.conic[2 * N + i] = sSum[wave][4][lane];
     g2.opacity[i] = sSum[wave][5][lane];
@@ -509,14 +510,15 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
     return hipGetLastError();
 }
 
-hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const int32_t* radius,
-                                const float bg[3], const float* final_T, const uint32_t* last_idx,
-                                const float* dL_dimage, const SplatGradDev& g2, hipStream_t s)
+hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3], const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                                const SplatGradDev& g2, hipStream_t s)
 {
     const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
+    const uint32_t* slot_base = reinterpret_cast<const uint32_t*>(ws + L.off_slot_base);
+    const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_dval0);
     const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
     float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
     {
@@ -525,12 +527,12 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     }
     {
         ProfScope prof(kKCompositeBwd, s);
-        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, offsets,
+        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, slot_base,
                            bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
-        hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, radius, offsets,
+        hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, order, offsets,
                            partial, L.cap, g2);
     }
     return hipGetLastError();

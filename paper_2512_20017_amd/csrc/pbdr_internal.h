@@ -32,7 +32,7 @@ struct CamDev {
 struct __attribute__((aligned(16))) Packed {
     float mx, my, qa, qb;   // mean2d, conic a, b
     float qc, o, r, g;      // conic c, opacity, red, green
-    float b, radius_bits, pad1, pad2;   // radius_bits: the integer extent, bit-cast
+    float b, radius_bits, depth, pad2;  // radius_bits: the integer extent, bit-cast
 };
 static_assert(sizeof(Packed) == 48, "raster record is 48 bytes");
 
@@ -60,11 +60,10 @@ enum { kStNumDup = 0, kStOverflow = 1, kStWords = 64 };
 struct Layout {
     int n, W, H, TX, TY, tiles;
     uint32_t cap;
-    int sort_bits, sort_passes;
-    uint32_t sort_blocks;     // blocks of kSortItems pairs covering `cap`
-    uint32_t hist_len;        // 256 * sort_blocks
-    size_t off_status, off_packed, off_offsets, off_scan_part, off_keys0, off_keys1, off_vals0, off_vals1,
-        off_hist, off_ranges, off_partial, total;
+    int tile_bits, tile_passes;   // key bits / 8-bit passes spent on the tile id
+    size_t off_status, off_packed, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
+        off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
+        off_partial, off_keys64, total;
 };
 constexpr int kSortItems = 4096;   // pairs per radix-sort block
 constexpr int kScanItems = 4096;   // elements per scan block
@@ -77,9 +76,9 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
                                 float* final_T, uint32_t* last_idx, hipStream_t s);
-hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const int32_t* radius,
-                                const float bg[3], const float* final_T, const uint32_t* last_idx,
-                                const float* dL_dimage, const SplatGradDev& g2, hipStream_t s);
+hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3],
+                                const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                                const SplatGradDev& g2, hipStream_t s);
 
 hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
 
@@ -87,11 +86,12 @@ hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uin
 // `partials` needs ceil(n / kScanItems) + 1 uint32.
 hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* partials,
                                  uint32_t* total_out, hipStream_t s);
-// same, but the element count is min(*n_dev_items * mult, n_max) read on the device (grid sized for n_max)
-hipError_t launch_radix_sort(const Layout& L, char* ws, hipStream_t s);
+hipError_t launch_radix_sort32(uint32_t* keys[2], uint32_t* vals[2], const uint32_t* count_ptr, uint32_t count_cap,
+                               int passes, uint32_t* totals, uint32_t* tile_hist, hipStream_t s);
+hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s);
 
-// final location of the sorted lists (depends on the parity of the pass count)
-inline size_t sorted_keys_off(const Layout& L) { return (L.sort_passes & 1) ? L.off_keys1 : L.off_keys0; }
-inline size_t sorted_vals_off(const Layout& L) { return (L.sort_passes & 1) ? L.off_vals1 : L.off_vals0; }
+// final location of the sorted pair lists (depends on the parity of the tile pass count)
+inline size_t sorted_tkeys_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tkey1 : L.off_tkey0; }
+inline size_t sorted_vals_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tval1 : L.off_tval0; }
 
 }  // namespace pbdr

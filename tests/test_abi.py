@@ -31,8 +31,9 @@ def test_workspace_bytes():
     big = B.pbdr_workspace_bytes(1_000_000, 1920, 1080, 8_000_000)
     assert 0 < small < big
     assert big % 256 == 0
-    # dominated by 48 B/point + 72 B/pair (keys, values, their ping-pong copies, 48 B of partial gradient sums)
-    assert abs(big - (48e6 + 72 * 8e6)) < 0.1 * big
+    # dominated by 76 B/point (raster record, counts, offsets, depth-sort buffers) + 72 B/pair (tile keys, values,
+    # their ping-pong copies, 48 B of partial gradient sums, 8 B of inspection keys)
+    assert abs(big - (76e6 + 72 * 8e6)) < 0.1 * big
     with pytest.raises(B.PbdrError):
         B.pbdr_workspace_bytes(-1, 128, 128, 10)
     with pytest.raises(B.PbdrError):
