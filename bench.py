@@ -31,6 +31,28 @@ BWD_FLOPS_PER_EXAMINED = 12.0    # alpha recomputed
 BWD_FLOPS_PER_BLENDED = 53.0     # 44 for the per-pair gradient terms + 9 lane-sum adds
 
 
+def profiled_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE in KiB,
+    scaled by what the same counters read for a plain copy of known size); None if the summary does not cover it."""
+    path = os.path.join(ROOT, "profiles", "bench_mid_pmc_traffic.txt")
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    scale_f = scale_w = None
+    for ln in lines:
+        if ln.startswith("scale_fetch="):
+            parts = dict(kv.split("=") for kv in ln.split())
+            scale_f, scale_w = float(parts["scale_fetch"]), float(parts["scale_write"])
+    if scale_f is None:
+        return None
+    for ln in lines:
+        cols = ln.split("\t")
+        if len(cols) == 3 and cols[0].split("::")[-1].split("<")[0] == kernel:
+            return (float(cols[1]) * scale_f + float(cols[2]) * scale_w) * 1024.0
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,6 +61,8 @@ def main():
     ap.add_argument("--workload", default="mid", choices=["mid", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives are part of it); use --gpus 1",
@@ -98,6 +122,14 @@ def main():
         B.pbdr_preprocess(scene, cam, splats)
         B.pbdr_render_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
         B.pbdr_render_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
+
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     names = B.profile_kernel_names()
     for _ in range(max(args.warmup, 1)):
@@ -163,6 +195,8 @@ def main():
     else:
         roofline = dict(kernel=dominant, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None,
                         traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt)
+    if args.workload == "mid":
+        roofline["traffic"] = profiled_traffic(dominant)
     for name, rec in per_kernel.items():
         t = rec["ms_per_step"] * 1e-3
         if name in alu_flops:
