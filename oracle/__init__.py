@@ -210,3 +210,102 @@ def backward(scene: dict, cam: dict, bg, fwd: dict, dL_dimage) -> dict:
     g = preprocess_bwd(scene, cam, d_sp)
     g["d_splats"] = d_sp
     return g
+
+
+# --------------------------------------------------------------------------------------------
+# 2D Gaussian surfels. Scene: mean[n,3], tan_u[n,3], tan_v[n,3], log_scale[n,2], logit[n], sh[n,K,3].
+# Splat state (Table 3b): mean2d[n,2], T[n,9] (ray_transforms), opacity[n], color[n,3], radius[n], depth[n], normal[n,3].
+# --------------------------------------------------------------------------------------------
+def ray_uv(T, x, y):
+    Tm = _f64(T, (9,)); uv = np.zeros(2)
+    ok = lib().orc2d_ray_uv(_p(Tm, C.c_double), C.c_double(x), C.c_double(y), _p(uv, C.c_double))
+    return uv if ok else None
+
+
+def _scene2d_arrays(scene):
+    n = int(scene["mean"].shape[0]); deg = int(scene["sh_degree"]); K = (deg + 1) ** 2
+    return (n, deg, K, _f64(scene["mean"], (n, 3)), _f64(scene["tan_u"], (n, 3)), _f64(scene["tan_v"], (n, 3)),
+            _f64(scene["log_scale"], (n, 2)), _f64(scene["logit"], (n,)), _f64(scene["sh"], (n, K, 3)))
+
+
+def preprocess2d(scene: dict, cam: dict) -> dict:
+    n, deg, K, mean, tu, tv, ls, lo, sh = _scene2d_arrays(scene)
+    out = dict(mean2d=np.zeros((n, 2)), T=np.zeros((n, 9)), opacity=np.zeros(n), color=np.zeros((n, 3)),
+               radius=np.zeros(n, dtype=np.int32), depth=np.zeros(n), normal=np.zeros((n, 3)), bbox=np.zeros((n, 4)))
+    c = camera(cam)
+    lib().orc2d_preprocess(C.c_int(n), C.c_int(deg), _p(mean, C.c_double), _p(tu, C.c_double), _p(tv, C.c_double),
+                           _p(ls, C.c_double), _p(lo, C.c_double), _p(sh, C.c_double), C.byref(c),
+                           _p(out["mean2d"], C.c_double), _p(out["T"], C.c_double), _p(out["opacity"], C.c_double),
+                           _p(out["color"], C.c_double), _p(out["radius"], C.c_int32), _p(out["depth"], C.c_double),
+                           _p(out["normal"], C.c_double), _p(out["bbox"], C.c_double))
+    return out
+
+
+def render_fwd2d(splats: dict, lists: dict, width, height, bg) -> dict:
+    n = int(splats["opacity"].shape[0])
+    m2 = _f64(splats["mean2d"], (n, 2)); T = _f64(splats["T"], (n, 9)); op = _f64(splats["opacity"], (n,))
+    col = _f64(splats["color"], (n, 3)); bgv = _f64(bg, (3,))
+    vals = np.ascontiguousarray(lists["vals"], dtype=np.uint32)
+    if vals.size == 0:
+        vals = np.zeros(1, dtype=np.uint32)
+    ranges = np.ascontiguousarray(lists["ranges"], dtype=np.uint32)
+    out = dict(image=np.zeros((height, width, 3)), final_T=np.zeros((height, width)),
+               last_idx=np.zeros((height, width), dtype=np.uint32), fragile=np.zeros((height, width), dtype=np.uint8))
+    counters = np.zeros(2, dtype=np.uint64)
+    lib().orc2d_render_fwd(C.c_int(width), C.c_int(height), _p(m2, C.c_double), _p(T, C.c_double), _p(op, C.c_double),
+                           _p(col, C.c_double), _p(vals, C.c_uint32), _p(ranges, C.c_uint32), _p(bgv, C.c_double),
+                           _p(out["image"], C.c_double), _p(out["final_T"], C.c_double), _p(out["last_idx"], C.c_uint32),
+                           _p(out["fragile"], C.c_uint8), _p(counters, C.c_uint64))
+    out["n_eval"] = int(counters[0]); out["n_blend"] = int(counters[1])
+    return out
+
+
+def render_bwd2d(splats: dict, lists: dict, width, height, bg, dL_dimage) -> dict:
+    n = int(splats["opacity"].shape[0])
+    m2 = _f64(splats["mean2d"], (n, 2)); T = _f64(splats["T"], (n, 9)); op = _f64(splats["opacity"], (n,))
+    col = _f64(splats["color"], (n, 3)); bgv = _f64(bg, (3,)); g = _f64(dL_dimage, (height, width, 3))
+    vals = np.ascontiguousarray(lists["vals"], dtype=np.uint32)
+    if vals.size == 0:
+        vals = np.zeros(1, dtype=np.uint32)
+    ranges = np.ascontiguousarray(lists["ranges"], dtype=np.uint32)
+    out = dict(T=np.zeros((n, 9)), mean2d=np.zeros((n, 2)), opacity=np.zeros(n), color=np.zeros((n, 3)))
+    lib().orc2d_render_bwd(C.c_int(width), C.c_int(height), _p(m2, C.c_double), _p(T, C.c_double), _p(op, C.c_double),
+                           _p(col, C.c_double), _p(vals, C.c_uint32), _p(ranges, C.c_uint32), _p(bgv, C.c_double),
+                           _p(g, C.c_double), _p(out["T"], C.c_double), _p(out["mean2d"], C.c_double),
+                           _p(out["opacity"], C.c_double), _p(out["color"], C.c_double))
+    return out
+
+
+def preprocess_bwd2d(scene: dict, cam: dict, d_splats: dict, accumulate_into: dict = None) -> dict:
+    n, deg, K, mean, tu, tv, ls, lo, sh = _scene2d_arrays(scene)
+    dT = _f64(d_splats["T"], (n, 9)); dm = _f64(d_splats["mean2d"], (n, 2)); do = _f64(d_splats["opacity"], (n,))
+    dc = _f64(d_splats["color"], (n, 3))
+    g = accumulate_into or dict(mean=np.zeros((n, 3)), tan_u=np.zeros((n, 3)), tan_v=np.zeros((n, 3)),
+                                log_scale=np.zeros((n, 2)), logit=np.zeros(n), sh=np.zeros((n, K, 3)))
+    c = camera(cam)
+    lib().orc2d_preprocess_bwd(C.c_int(n), C.c_int(deg), _p(mean, C.c_double), _p(tu, C.c_double), _p(tv, C.c_double),
+                               _p(ls, C.c_double), _p(lo, C.c_double), _p(sh, C.c_double), C.byref(c), _p(dT, C.c_double),
+                               _p(dm, C.c_double), _p(do, C.c_double), _p(dc, C.c_double), _p(g["mean"], C.c_double),
+                               _p(g["tan_u"], C.c_double), _p(g["tan_v"], C.c_double), _p(g["log_scale"], C.c_double),
+                               _p(g["logit"], C.c_double), _p(g["sh"], C.c_double))
+    return g
+
+
+def forward2d(scene: dict, cam: dict, bg, splat_dtype=np.float32) -> dict:
+    sp = preprocess2d(scene, cam)
+    W, H = int(cam["width"]), int(cam["height"])
+    st = {k: sp[k].astype(splat_dtype).astype(np.float64) for k in ("mean2d", "T", "opacity", "color")}
+    st["radius"] = sp["radius"]
+    depth32 = sp["depth"].astype(np.float32)
+    lists = bin_sort(st["mean2d"], st["radius"], depth32, W, H)
+    out = render_fwd2d(st, lists, W, H, bg)
+    out.update(splats=sp, state=st, lists=lists, depth32=depth32)
+    return out
+
+
+def backward2d(scene: dict, cam: dict, bg, fwd: dict, dL_dimage) -> dict:
+    W, H = int(cam["width"]), int(cam["height"])
+    d_sp = render_bwd2d(fwd["state"], fwd["lists"], W, H, bg, dL_dimage)
+    g = preprocess_bwd2d(scene, cam, d_sp)
+    g["d_splats"] = d_sp
+    return g

@@ -698,3 +698,374 @@ int orc_num_threads(void)
 #endif
     return nthreads;
 }
+
+/* ====================================================================================== */
+/* 2D Gaussian surfels (the paper's 2DGS configuration: Sec. 5 "Applications", Table 3b,   */
+/* App. B: "2DGS models [the projection] more accurately").                                */
+/*                                                                                        */
+/* A point is an oriented disk: centre mean, two raw tangent vectors (a, b) made           */
+/* orthonormal by Gram-Schmidt (t_u = a/|a|, t_v = (b - (b.t_u) t_u)/|.|, n = t_u x t_v),   */
+/* two scales exp(log_scale), opacity = sigmoid(logit), SH colour as for 3D Gaussians.     */
+/* Readings (the paper gives only the state layout of Table 3b):                           */
+/*   - ray_transforms T = K [R (s_u t_u) | R (s_v t_v) | R mean + t]: maps disk            */
+/*     coordinates (u, v, 1) to homogeneous pixel coordinates;                             */
+/*   - a pixel (x, y) meets the disk plane where the two planes x and y of its ray,        */
+/*     pulled back through T, intersect: h_u = x T_2 - T_0, h_v = y T_2 - T_1 (rows of T), */
+/*     p = h_u x h_v, (u, v) = (p_0, p_1)/p_2; G = exp(-(u^2+v^2)/2);                       */
+/*   - screen-space low-pass: G^ = max(G, exp(-|pixel - mean2d|^2)) (sigma = sqrt(2)/2);    */
+/*   - alpha = min(0.99, o G^), then the same skip / stop / order rules as above;           */
+/*   - extent: exact bounding box of the perspective image of the 3-sigma disk, radius =   */
+/*     ceil of its largest reach from mean2d, at least 3 (the low-pass support); a disk     */
+/*     whose 3-sigma rim reaches the camera plane is culled; depth = z of the centre;       */
+/*   - normal = R n, turned to face the camera (output only).                               */
+/* Layouts: tan_u[n][3], tan_v[n][3], log_scale2[n][2]; T[n][9] row-major; normal[n][3].    */
+/* ====================================================================================== */
+#define ORC_FRAG_LOWPASS 16
+
+typedef struct {
+    int visible;
+    double tu[3], tv[3], nrm[3], alen, w[3], wlen, btu;
+    double su, sv, o;
+    double Hm[9], T[9];
+    double mean2d[2], bc[2], half[2];
+    int radius;
+    int32_t rect[4];
+    double ncam[3];
+    double v[3], vlen, dir[3];
+    double Y[16], dY[16][3];
+    double rgb_raw[3], rgb[3];
+} orc2d_proj;
+
+static void cross3(const double a[3], const double b[3], double c[3])
+{
+    c[0] = a[1] * b[2] - a[2] * b[1]; c[1] = a[2] * b[0] - a[0] * b[2]; c[2] = a[0] * b[1] - a[1] * b[0];
+}
+
+static void project2d_one(int sh_degree, const double mean[3], const double ta[3], const double tb[3], const double ls[2],
+                          double logit, const double* sh, const orc_camera* cam, orc2d_proj* P)
+{
+    int i, k, c;
+    const int K = (sh_degree + 1) * (sh_degree + 1);
+    double col[3][3]; /* camera-space columns of H */
+    memset(P, 0, sizeof(*P));
+    P->su = exp(ls[0]); P->sv = exp(ls[1]); P->o = 1.0 / (1.0 + exp(-logit));
+    P->alen = sqrt(ta[0] * ta[0] + ta[1] * ta[1] + ta[2] * ta[2]);
+    for (i = 0; i < 3; ++i) P->tu[i] = ta[i] / P->alen;
+    P->btu = tb[0] * P->tu[0] + tb[1] * P->tu[1] + tb[2] * P->tu[2];
+    for (i = 0; i < 3; ++i) P->w[i] = tb[i] - P->btu * P->tu[i];
+    P->wlen = sqrt(P->w[0] * P->w[0] + P->w[1] * P->w[1] + P->w[2] * P->w[2]);
+    for (i = 0; i < 3; ++i) P->tv[i] = P->w[i] / P->wlen;
+    cross3(P->tu, P->tv, P->nrm);
+    for (i = 0; i < 3; ++i) {
+        col[0][i] = P->su * (cam->R[3 * i] * P->tu[0] + cam->R[3 * i + 1] * P->tu[1] + cam->R[3 * i + 2] * P->tu[2]);
+        col[1][i] = P->sv * (cam->R[3 * i] * P->tv[0] + cam->R[3 * i + 1] * P->tv[1] + cam->R[3 * i + 2] * P->tv[2]);
+        col[2][i] = cam->R[3 * i] * mean[0] + cam->R[3 * i + 1] * mean[1] + cam->R[3 * i + 2] * mean[2] + cam->t[i];
+    }
+    for (i = 0; i < 3; ++i) for (k = 0; k < 3; ++k) P->Hm[3 * i + k] = col[k][i];
+    for (k = 0; k < 3; ++k) {
+        P->T[k] = cam->fx * P->Hm[k] + cam->cx * P->Hm[6 + k];
+        P->T[3 + k] = cam->fy * P->Hm[3 + k] + cam->cy * P->Hm[6 + k];
+        P->T[6 + k] = P->Hm[6 + k];
+    }
+    if (P->T[8] < cam->near_plane || P->T[8] > cam->far_plane) return;
+    {
+        const double a = 9.0 * (P->T[6] * P->T[6] + P->T[7] * P->T[7]) - P->T[8] * P->T[8];
+        double reach = 0.0, r;
+        if (!(a < 0.0)) return; /* the 3-sigma rim reaches the camera plane */
+        for (i = 0; i < 2; ++i) {
+            const double* Ti = P->T + 3 * i;
+            const double b = 9.0 * (Ti[0] * P->T[6] + Ti[1] * P->T[7]) - Ti[2] * P->T[8];
+            const double cc = 9.0 * (Ti[0] * Ti[0] + Ti[1] * Ti[1]) - Ti[2] * Ti[2];
+            double disc;
+            P->bc[i] = b / a;
+            disc = P->bc[i] * P->bc[i] - cc / a;
+            if (disc < 1e-4) disc = 1e-4;
+            P->half[i] = sqrt(disc);
+            P->mean2d[i] = Ti[2] / P->T[8];
+            r = fabs(P->bc[i] - P->mean2d[i]) + P->half[i];
+            if (r > reach) reach = r;
+        }
+        r = ceil(reach);
+        if (r < 3.0) r = 3.0;
+        if (!(r < (double)ORC_RADIUS_MAX)) r = (double)ORC_RADIUS_MAX;
+        P->radius = (int)r;
+    }
+    if ((double)P->radius <= cam->radius_clip) { P->radius = 0; return; }
+    orc_tile_rect(P->mean2d[0], P->mean2d[1], P->radius, cam->width, cam->height, P->rect);
+    if ((P->rect[2] - P->rect[0]) * (P->rect[3] - P->rect[1]) <= 0) { P->radius = 0; return; }
+    {
+        double dotp = 0.0;
+        for (i = 0; i < 3; ++i) {
+            P->ncam[i] = cam->R[3 * i] * P->nrm[0] + cam->R[3 * i + 1] * P->nrm[1] + cam->R[3 * i + 2] * P->nrm[2];
+            dotp += P->ncam[i] * col[2][i];
+        }
+        if (dotp > 0.0) for (i = 0; i < 3; ++i) P->ncam[i] = -P->ncam[i];
+    }
+    {
+        double campos[3];
+        for (i = 0; i < 3; ++i)
+            campos[i] = -(cam->R[i] * cam->t[0] + cam->R[3 + i] * cam->t[1] + cam->R[6 + i] * cam->t[2]);
+        for (i = 0; i < 3; ++i) P->v[i] = mean[i] - campos[i];
+        P->vlen = sqrt(P->v[0] * P->v[0] + P->v[1] * P->v[1] + P->v[2] * P->v[2]);
+        for (i = 0; i < 3; ++i) P->dir[i] = P->v[i] / P->vlen;
+        sh_eval(sh_degree, P->dir, P->Y, P->dY);
+        for (c = 0; c < 3; ++c) {
+            double acc = 0.5;
+            for (k = 0; k < K; ++k) acc += P->Y[k] * sh[3 * k + c];
+            P->rgb_raw[c] = acc;
+            P->rgb[c] = acc > 0.0 ? acc : 0.0;
+        }
+    }
+    P->visible = 1;
+}
+
+/* Table 3b state: mean2d[n][2], T[n][9] (ray_transforms), opacity[n], color[n][3], radius[n], depth[n], normal[n][3].
+ * Optional: bbox[n][4] = (centre_x, centre_y, half_x, half_y) of the 3-sigma disk's image. */
+void orc2d_preprocess(int n, int sh_degree, const double* mean, const double* tan_u, const double* tan_v,
+                      const double* log_scale2, const double* logit, const double* sh, const orc_camera* cam,
+                      double* mean2d, double* T, double* opacity, double* color, int32_t* radius, double* depth,
+                      double* normal, double* bbox)
+{
+    const int K = (sh_degree + 1) * (sh_degree + 1);
+    int i;
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < n; ++i) {
+        orc2d_proj P;
+        int k;
+        project2d_one(sh_degree, mean + 3 * i, tan_u + 3 * i, tan_v + 3 * i, log_scale2 + 2 * i, logit[i],
+                      sh + (size_t)3 * K * i, cam, &P);
+        mean2d[2 * i] = mean2d[2 * i + 1] = 0.0; opacity[i] = 0.0; depth[i] = 0.0; radius[i] = 0;
+        for (k = 0; k < 9; ++k) T[9 * i + k] = 0.0;
+        for (k = 0; k < 3; ++k) { color[3 * i + k] = 0.0; normal[3 * i + k] = 0.0; }
+        if (bbox) for (k = 0; k < 4; ++k) bbox[4 * i + k] = 0.0;
+        if (!P.visible) continue;
+        mean2d[2 * i] = P.mean2d[0]; mean2d[2 * i + 1] = P.mean2d[1];
+        for (k = 0; k < 9; ++k) T[9 * i + k] = P.T[k];
+        for (k = 0; k < 3; ++k) { color[3 * i + k] = P.rgb[k]; normal[3 * i + k] = P.ncam[k]; }
+        opacity[i] = P.o; depth[i] = P.T[8]; radius[i] = P.radius;
+        if (bbox) { bbox[4 * i] = P.bc[0]; bbox[4 * i + 1] = P.bc[1]; bbox[4 * i + 2] = P.half[0]; bbox[4 * i + 3] = P.half[1]; }
+    }
+}
+
+/* disk coordinates (u, v) where the ray of pixel position (x, y) meets the surfel's plane; returns 0 if parallel */
+int orc2d_ray_uv(const double T[9], double x, double y, double uv[2])
+{
+    double hu[3], hv[3], p[3];
+    int k;
+    for (k = 0; k < 3; ++k) { hu[k] = x * T[6 + k] - T[k]; hv[k] = y * T[6 + k] - T[3 + k]; }
+    cross3(hu, hv, p);
+    if (p[2] == 0.0) return 0;
+    uv[0] = p[0] / p[2]; uv[1] = p[1] / p[2];
+    return 1;
+}
+
+typedef struct { uint32_t pos; double alpha, Tr, ghat, u, v, g, g2; int clamped, lowpass; } orc2d_hit;
+
+static void blend_pixel2d(double px, double py, const uint32_t* list, uint32_t len, const double* mean2d, const double* Tm,
+                          const double* opacity, const double* color, const double bg[3], double rgb_out[3],
+                          double* T_out, uint32_t* last_out, uint8_t* fragile_out, uint64_t* n_eval, uint64_t* n_blend,
+                          orc2d_hit* hits, uint32_t* n_hits)
+{
+    double Tr = 1.0, C[3] = {0.0, 0.0, 0.0};
+    uint32_t last = 0, k, nh = 0;
+    uint8_t frag = 0;
+    uint64_t ev = 0;
+    for (k = 0; k < len; ++k) {
+        const uint32_t g = list[k];
+        double uv[2], G, G2, ghat, araw, alpha, Tn, dx, dy;
+        ++ev;
+        if (!orc2d_ray_uv(Tm + 9 * g, px, py, uv)) continue;
+        G = exp(-0.5 * (uv[0] * uv[0] + uv[1] * uv[1]));
+        dx = px - mean2d[2 * g]; dy = py - mean2d[2 * g + 1];
+        G2 = exp(-(dx * dx + dy * dy));
+        ghat = G > G2 ? G : G2;
+        araw = opacity[g] * ghat;
+        alpha = araw < ORC_ALPHA_MAX ? araw : ORC_ALPHA_MAX;
+        if (fabs(araw - ORC_ALPHA_MAX) < 1e-5) frag |= ORC_FRAG_ALPHA_MAX;
+        if (fabs(alpha - ORC_ALPHA_MIN) < 2e-7) frag |= ORC_FRAG_ALPHA_MIN;
+        if (alpha < ORC_ALPHA_MIN) continue;
+        if (fabs(G - G2) < 1e-6) frag |= ORC_FRAG_LOWPASS;
+        Tn = Tr * (1.0 - alpha);
+        if (fabs(Tn - ORC_T_STOP) < 1e-8) frag |= ORC_FRAG_T_STOP;
+        if (Tn < ORC_T_STOP) break;
+        C[0] += color[3 * g] * alpha * Tr; C[1] += color[3 * g + 1] * alpha * Tr; C[2] += color[3 * g + 2] * alpha * Tr;
+        if (hits) {
+            hits[nh].pos = k; hits[nh].alpha = alpha; hits[nh].Tr = Tr; hits[nh].ghat = ghat; hits[nh].u = uv[0];
+            hits[nh].v = uv[1]; hits[nh].g = G; hits[nh].g2 = G2; hits[nh].clamped = !(araw < ORC_ALPHA_MAX);
+            hits[nh].lowpass = !(G > G2);
+        }
+        ++nh;
+        Tr = Tn;
+        last = k + 1;
+    }
+    rgb_out[0] = C[0] + Tr * bg[0]; rgb_out[1] = C[1] + Tr * bg[1]; rgb_out[2] = C[2] + Tr * bg[2];
+    *T_out = Tr; *last_out = last;
+    if (fragile_out) *fragile_out = frag;
+    if (n_eval) *n_eval = ev;
+    if (n_blend) *n_blend = nh;
+    if (n_hits) *n_hits = nh;
+}
+
+void orc2d_render_fwd(int width, int height, const double* mean2d, const double* Tm, const double* opacity,
+                      const double* color, const uint32_t* vals, const uint32_t* ranges, const double bg[3],
+                      double* image, double* final_T, uint32_t* last_idx, uint8_t* fragile, uint64_t* counters)
+{
+    const int TX = (width + ORC_TILE - 1) / ORC_TILE;
+    uint64_t tot_eval = 0, tot_blend = 0;
+    int y;
+#pragma omp parallel for schedule(dynamic, 4) reduction(+ : tot_eval, tot_blend)
+    for (y = 0; y < height; ++y) {
+        int x;
+        for (x = 0; x < width; ++x) {
+            const int tile = (y / ORC_TILE) * TX + (x / ORC_TILE);
+            const uint32_t s = ranges[2 * tile], e = ranges[2 * tile + 1];
+            const size_t pix = (size_t)y * width + x;
+            uint64_t ev, nb;
+            blend_pixel2d(x + 0.5, y + 0.5, vals + s, e - s, mean2d, Tm, opacity, color, bg, image + 3 * pix, final_T + pix,
+                          last_idx + pix, fragile ? fragile + pix : NULL, &ev, &nb, NULL, NULL);
+            tot_eval += ev; tot_blend += nb;
+        }
+    }
+    if (counters) { counters[0] = tot_eval; counters[1] = tot_blend; }
+}
+
+/* gradient w.r.t. the splat state: d_T[n][9], d_mean2d[n][2] (through the low-pass branch only), d_opacity, d_color; += */
+void orc2d_render_bwd(int width, int height, const double* mean2d, const double* Tm, const double* opacity,
+                      const double* color, const uint32_t* vals, const uint32_t* ranges, const double bg[3],
+                      const double* dL_dimage, double* d_T, double* d_mean2d, double* d_opacity, double* d_color)
+{
+    const int TX = (width + ORC_TILE - 1) / ORC_TILE;
+    int y;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (y = 0; y < height; ++y) {
+        int x;
+        uint32_t cap = 0;
+        orc2d_hit* hits = NULL;
+        for (x = 0; x < width; ++x) {
+            const int tile = (y / ORC_TILE) * TX + (x / ORC_TILE);
+            const uint32_t s = ranges[2 * tile], e = ranges[2 * tile + 1];
+            const size_t pix = (size_t)y * width + x;
+            const double* g = dL_dimage + 3 * pix;
+            const double px = x + 0.5, py = y + 0.5;
+            double rgb[3], T_final, suffix;
+            uint32_t last, nh;
+            int k;
+            if (e - s > cap) { cap = e - s; free(hits); hits = (orc2d_hit*)malloc((size_t)cap * sizeof(orc2d_hit)); }
+            if (e == s) continue;
+            blend_pixel2d(px, py, vals + s, e - s, mean2d, Tm, opacity, color, bg, rgb, &T_final, &last, NULL, NULL, NULL,
+                          hits, &nh);
+            suffix = T_final * (bg[0] * g[0] + bg[1] * g[1] + bg[2] * g[2]);
+            for (k = (int)nh - 1; k >= 0; --k) {
+                const uint32_t gi = vals[s + hits[k].pos];
+                const double alpha = hits[k].alpha, Tr = hits[k].Tr, w = alpha * Tr;
+                const double cg = color[3 * gi] * g[0] + color[3 * gi + 1] * g[1] + color[3 * gi + 2] * g[2];
+                const double dL_dalpha = Tr * cg - suffix / (1.0 - alpha);
+                int c;
+                for (c = 0; c < 3; ++c) {
+#pragma omp atomic
+                    d_color[3 * gi + c] += w * g[c];
+                }
+                if (!hits[k].clamped) {
+                    const double dL_dghat = opacity[gi] * dL_dalpha;
+#pragma omp atomic
+                    d_opacity[gi] += hits[k].ghat * dL_dalpha;
+                    if (hits[k].lowpass) {
+                        const double dx = px - mean2d[2 * gi], dy = py - mean2d[2 * gi + 1];
+                        /* G2 = exp(-(dx^2+dy^2)), dx = px - mx */
+#pragma omp atomic
+                        d_mean2d[2 * gi] += dL_dghat * hits[k].g2 * 2.0 * dx;
+#pragma omp atomic
+                        d_mean2d[2 * gi + 1] += dL_dghat * hits[k].g2 * 2.0 * dy;
+                    } else {
+                        const double* Tg = Tm + 9 * gi;
+                        const double du = -hits[k].u * hits[k].g * dL_dghat, dv = -hits[k].v * hits[k].g * dL_dghat;
+                        double hu[3], hv[3], p[3], dp[3], dhu[3], dhv[3];
+                        int q;
+                        for (q = 0; q < 3; ++q) { hu[q] = px * Tg[6 + q] - Tg[q]; hv[q] = py * Tg[6 + q] - Tg[3 + q]; }
+                        cross3(hu, hv, p);
+                        dp[0] = du / p[2]; dp[1] = dv / p[2]; dp[2] = -(du * p[0] + dv * p[1]) / (p[2] * p[2]);
+                        cross3(hv, dp, dhu);   /* p = hu x hv  =>  dL/dhu = hv x dL/dp */
+                        cross3(dp, hu, dhv);   /*                  dL/dhv = dL/dp x hu */
+                        for (q = 0; q < 3; ++q) {
+#pragma omp atomic
+                            d_T[9 * gi + q] += -dhu[q];
+#pragma omp atomic
+                            d_T[9 * gi + 3 + q] += -dhv[q];
+#pragma omp atomic
+                            d_T[9 * gi + 6 + q] += px * dhu[q] + py * dhv[q];
+                        }
+                    }
+                }
+                suffix += w * cg;
+            }
+        }
+        free(hits);
+    }
+}
+
+/* chain rule from (d_T, d_mean2d, d_opacity, d_color) to the raw surfel parameters; accumulated (+=) */
+void orc2d_preprocess_bwd(int n, int sh_degree, const double* mean, const double* tan_u, const double* tan_v,
+                          const double* log_scale2, const double* logit, const double* sh, const orc_camera* cam,
+                          const double* d_T, const double* d_mean2d, const double* d_opacity, const double* d_color,
+                          double* g_mean, double* g_tan_u, double* g_tan_v, double* g_log_scale2, double* g_logit,
+                          double* g_sh)
+{
+    const int K = (sh_degree + 1) * (sh_degree + 1);
+    int idx;
+#pragma omp parallel for schedule(static)
+    for (idx = 0; idx < n; ++idx) {
+        orc2d_proj P;
+        double GT[9], GH[9], gcol[3][3], dmu[3] = {0, 0, 0}, gtu[3], gtv[3], gx[3], gw[3], gb[3], ga[3];
+        int i, k, c;
+        project2d_one(sh_degree, mean + 3 * idx, tan_u + 3 * idx, tan_v + 3 * idx, log_scale2 + 2 * idx, logit[idx],
+                      sh + (size_t)3 * K * idx, cam, &P);
+        if (!P.visible) continue;
+        g_logit[idx] += d_opacity[idx] * P.o * (1.0 - P.o);
+        {
+            double ddir[3] = {0, 0, 0}, dot;
+            for (c = 0; c < 3; ++c) {
+                const double gc = P.rgb_raw[c] > 0.0 ? d_color[3 * idx + c] : 0.0;
+                for (k = 0; k < K; ++k) {
+                    g_sh[(size_t)3 * K * idx + 3 * k + c] += P.Y[k] * gc;
+                    for (i = 0; i < 3; ++i) ddir[i] += gc * P.dY[k][i] * sh[(size_t)3 * K * idx + 3 * k + c];
+                }
+            }
+            dot = ddir[0] * P.dir[0] + ddir[1] * P.dir[1] + ddir[2] * P.dir[2];
+            for (i = 0; i < 3; ++i) dmu[i] += (ddir[i] - P.dir[i] * dot) / P.vlen;
+        }
+        for (k = 0; k < 9; ++k) GT[k] = d_T[9 * idx + k];
+        /* mean2d_i = T_i2 / T_22 */
+        GT[2] += d_mean2d[2 * idx] / P.T[8];
+        GT[5] += d_mean2d[2 * idx + 1] / P.T[8];
+        GT[8] += -(d_mean2d[2 * idx] * P.T[2] + d_mean2d[2 * idx + 1] * P.T[5]) / (P.T[8] * P.T[8]);
+        /* T0 = fx H0 + cx H2, T1 = fy H1 + cy H2, T2 = H2 (rows) */
+        for (k = 0; k < 3; ++k) {
+            GH[k] = cam->fx * GT[k];
+            GH[3 + k] = cam->fy * GT[3 + k];
+            GH[6 + k] = cam->cx * GT[k] + cam->cy * GT[3 + k] + GT[6 + k];
+        }
+        /* columns of H: R (su tu), R (sv tv), R mean + t  ->  world-space gradients of the three column vectors */
+        for (k = 0; k < 3; ++k)
+            for (i = 0; i < 3; ++i)
+                gcol[k][i] = cam->R[i] * GH[k] + cam->R[3 + i] * GH[3 + k] + cam->R[6 + i] * GH[6 + k];
+        for (i = 0; i < 3; ++i) dmu[i] += gcol[2][i];
+        for (i = 0; i < 3; ++i) g_mean[3 * idx + i] += dmu[i];
+        g_log_scale2[2 * idx] += P.su * (gcol[0][0] * P.tu[0] + gcol[0][1] * P.tu[1] + gcol[0][2] * P.tu[2]);
+        g_log_scale2[2 * idx + 1] += P.sv * (gcol[1][0] * P.tv[0] + gcol[1][1] * P.tv[1] + gcol[1][2] * P.tv[2]);
+        for (i = 0; i < 3; ++i) { gtu[i] = P.su * gcol[0][i]; gtv[i] = P.sv * gcol[1][i]; }
+        /* Gram-Schmidt: tv = w/|w|, w = b - (b.tu) tu, tu = a/|a| */
+        {
+            double dot = gtv[0] * P.tv[0] + gtv[1] * P.tv[1] + gtv[2] * P.tv[2], wtu, gbtu;
+            for (i = 0; i < 3; ++i) gw[i] = (gtv[i] - P.tv[i] * dot) / P.wlen;
+            wtu = gw[0] * P.tu[0] + gw[1] * P.tu[1] + gw[2] * P.tu[2];
+            gbtu = -wtu;                                  /* d/d(b.tu) */
+            for (i = 0; i < 3; ++i) {
+                gb[i] = gw[i] + gbtu * P.tu[i];
+                gx[i] = gtu[i] - P.btu * gw[i] + gbtu * tan_v[3 * idx + i];   /* total gradient w.r.t. tu */
+            }
+            dot = gx[0] * P.tu[0] + gx[1] * P.tu[1] + gx[2] * P.tu[2];
+            for (i = 0; i < 3; ++i) ga[i] = (gx[i] - P.tu[i] * dot) / P.alen;
+        }
+        for (i = 0; i < 3; ++i) { g_tan_u[3 * idx + i] += ga[i]; g_tan_v[3 * idx + i] += gb[i]; }
+    }
+}

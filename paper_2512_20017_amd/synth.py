@@ -153,6 +153,32 @@ def cameras_street(seed=0, count=8, width=3840, height=2160, fov_deg=70.0):
     return cams
 
 
+def scene_surfels(seed=0, n=1_000_000, sh_degree=3, n_comp=64, zorder=True):
+    """Config 5: 2D Gaussian disks. Means as the mid scene; two raw tangent vectors ~ N(0,1)^3 (orthonormalised by the
+    renderer, normal = their cross product); two log-scales N(-4,0.5); opacity sigmoid(N(0,1)); SH degree 3."""
+    rng = _rng(seed, 6)
+    mean = _gmm_means(rng, n, n_comp, [-10, -10, -10], [10, 10, 10], 0.3, 2.0)
+    log_scale3, _, logit, sh = _attributes(rng, n, sh_degree, -4.0, 0.5, 1.0, "dc")
+    tan_u = rng.normal(0.0, 1.0, size=(n, 3)).astype(np.float32)
+    tan_v = rng.normal(0.0, 1.0, size=(n, 3)).astype(np.float32)
+    sc = dict(mean=mean, tan_u=tan_u, tan_v=tan_v, log_scale=np.ascontiguousarray(log_scale3[:, :2]), logit=logit, sh=sh,
+              sh_degree=sh_degree)
+    return _reorder(sc, zorder_permutation(mean)) if zorder else sc
+
+
+def random_small_surfels(seed, n, sh_degree, spread=0.6, ls_mu=-2.0, ls_sigma=0.4):
+    """Small random surfel scene for parity sweeps and finite differences."""
+    rng = _rng(seed, 10)
+    mean = rng.uniform(-spread, spread, size=(n, 3)).astype(np.float32)
+    log_scale3, _, logit, sh = _attributes(rng, n, sh_degree, ls_mu, ls_sigma, 1.0, "rgb")
+    if sh_degree > 0:
+        sh[:, 1:, :] *= 4.0
+    tan_u = rng.normal(0.0, 1.0, size=(n, 3)).astype(np.float32)
+    tan_v = rng.normal(0.0, 1.0, size=(n, 3)).astype(np.float32)
+    return dict(mean=mean, tan_u=tan_u, tan_v=tan_v, log_scale=np.ascontiguousarray(log_scale3[:, :2]), logit=logit, sh=sh,
+                sh_degree=sh_degree)
+
+
 def target_image(seed, width, height):
     """Seeded U[0,1] ground-truth stand-in, [H,W,3] float32."""
     return _rng(seed, 7).uniform(0.0, 1.0, size=(height, width, 3)).astype(np.float32)

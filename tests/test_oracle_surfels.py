@@ -1,0 +1,171 @@
+"""Pins of the CPU oracle's 2D Gaussian surfel path (no GPU): geometry of the ray-disk intersection and of the
+extent against brute force, a head-on closed form, invariants, and finite differences of the whole path."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import simple_camera
+from paper_2512_20017_amd import synth
+
+BG = np.array([0.2, 0.5, 0.3])
+
+
+def _f64(sc):
+    return {k: (np.asarray(v, dtype=np.float64).copy() if isinstance(v, np.ndarray) else v) for k, v in sc.items()}
+
+
+def _frame(a, b):
+    """Orthonormal (t_u, t_v) spanning (a, b) with t_u along a: QR with positive diagonal (library routine)."""
+    q, r = np.linalg.qr(np.stack([a, b], 1))
+    q = q * np.sign(np.diag(r))
+    return q[:, 0], q[:, 1]
+
+
+def _scene(seed, n=24, deg=0):
+    return _f64(synth.random_small_surfels(seed, n, deg)), synth.pinhole(80, 56, 55.0, *synth.look_at([0.3, 0.2, -2.4], [0, 0, 0], [0, 1, 0]))
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_ray_hits_the_disk_point_that_projects_to_the_pixel(seed):
+    sc, cam = _scene(seed)
+    sp = oracle.preprocess2d(sc, cam)
+    rng = np.random.default_rng(seed)
+    R, t = np.asarray(cam["R"]), np.asarray(cam["t"])
+    checked = 0
+    for i in np.nonzero(sp["radius"] > 0)[0]:
+        tu, tv = _frame(sc["tan_u"][i], sc["tan_v"][i])
+        su, sv = np.exp(sc["log_scale"][i])
+        for _ in range(4):
+            u, v = rng.uniform(-2.5, 2.5, 2)
+            P = sc["mean"][i] + su * u * tu + sv * v * tv
+            pc = R @ P + t
+            x, y = cam["fx"] * pc[0] / pc[2] + cam["cx"], cam["fy"] * pc[1] / pc[2] + cam["cy"]
+            uv = oracle.ray_uv(sp["T"][i], x, y)
+            np.testing.assert_allclose(uv, [u, v], rtol=1e-8, atol=1e-8)
+            checked += 1
+        # centre and depth
+        pc = R @ sc["mean"][i] + t
+        np.testing.assert_allclose(sp["mean2d"][i], [cam["fx"] * pc[0] / pc[2] + cam["cx"], cam["fy"] * pc[1] / pc[2] + cam["cy"]], rtol=1e-12)
+        np.testing.assert_allclose(sp["depth"][i], pc[2], rtol=1e-13)
+        # normal: unit, orthogonal to both tangents, facing the camera
+        ncam = sp["normal"][i]
+        assert abs(np.linalg.norm(ncam) - 1) < 1e-12 and abs(ncam @ (R @ tu)) < 1e-12 and abs(ncam @ (R @ tv)) < 1e-12
+        assert ncam @ pc <= 0
+    assert checked >= 40
+
+
+def test_extent_is_the_bounding_box_of_the_projected_three_sigma_rim():
+    sc, cam = _scene(2, n=32)
+    sp = oracle.preprocess2d(sc, cam)
+    R, t = np.asarray(cam["R"]), np.asarray(cam["t"])
+    th = np.linspace(0, 2 * np.pi, 20001)
+    seen = 0
+    for i in np.nonzero(sp["radius"] > 0)[0]:
+        tu, tv = _frame(sc["tan_u"][i], sc["tan_v"][i])
+        su, sv = np.exp(sc["log_scale"][i])
+        P = sc["mean"][i] + 3 * su * np.cos(th)[:, None] * tu + 3 * sv * np.sin(th)[:, None] * tv
+        pc = P @ R.T + t
+        x = cam["fx"] * pc[:, 0] / pc[:, 2] + cam["cx"]; y = cam["fy"] * pc[:, 1] / pc[:, 2] + cam["cy"]
+        cx, cy, hx, hy = sp["bbox"][i]
+        np.testing.assert_allclose([x.min(), x.max(), y.min(), y.max()], [cx - hx, cx + hx, cy - hy, cy + hy], atol=2e-6 * max(hx, hy, 1))
+        reach = max(abs(cx - sp["mean2d"][i, 0]) + hx, abs(cy - sp["mean2d"][i, 1]) + hy)
+        assert sp["radius"][i] == max(3, math.ceil(reach))
+        seen += 1
+    assert seen >= 20
+
+
+def test_head_on_disk_closed_form():
+    W = H = 64; f = 50.0; z = 4.0; su, sv = 0.9, 0.6; logit = 0.4; rgb = np.array([0.9, 0.5, 0.2])
+    sh = np.zeros((1, 1, 3)); sh[0, 0] = (rgb - 0.5) / 0.28209479177387814
+    sc = dict(mean=np.zeros((1, 3)), tan_u=np.array([[2.0, 0, 0]]), tan_v=np.array([[0.3, 1.5, 0]]), log_scale=np.log([[su, sv]]),
+              logit=np.array([logit]), sh=sh, sh_degree=0)
+    cam = simple_camera(W, H, f, z)
+    out = oracle.forward2d(sc, cam, BG, splat_dtype=np.float64)
+    assert out["splats"]["radius"][0] >= 32
+    o = 1 / (1 + math.exp(-logit))
+    ys, xs = np.mgrid[0:H, 0:W]
+    dx, dy = xs + 0.5 - W / 2, ys + 0.5 - H / 2
+    G = np.exp(-0.5 * ((dx * z / (f * su)) ** 2 + (dy * z / (f * sv)) ** 2))
+    ghat = np.maximum(G, np.exp(-(dx * dx + dy * dy)))
+    alpha = np.minimum(0.99, o * ghat); alpha = np.where(alpha < 1 / 255, 0.0, alpha)
+    np.testing.assert_allclose(out["image"], alpha[..., None] * rgb + (1 - alpha)[..., None] * BG, atol=1e-13)
+    np.testing.assert_allclose(out["final_T"], 1 - alpha, atol=1e-13)
+    assert (alpha == 0).any() and (alpha > 0).any()
+
+
+def test_low_pass_keeps_a_tiny_or_edge_on_disk_visible():
+    cam = simple_camera(32, 32, 40.0, 3.0)
+    sh = np.zeros((1, 1, 3)); sh[0, 0] = 1.0
+    tiny = dict(mean=np.array([[0.0125 * 3 / 40 * 40, 0.0, 0.0]]), tan_u=np.array([[1.0, 0, 0]]), tan_v=np.array([[0, 1.0, 0]]),
+                log_scale=np.log([[1e-4, 1e-4]]), logit=np.array([2.0]), sh=sh, sh_degree=0)
+    out = oracle.forward2d(tiny, cam, [0, 0, 0], splat_dtype=np.float64)
+    assert out["splats"]["radius"][0] == 3
+    o = 1 / (1 + math.exp(-2.0))
+    mx, my = out["splats"]["mean2d"][0]
+    d2 = (16.5 - mx) ** 2 + (16.5 - my) ** 2
+    np.testing.assert_allclose(out["final_T"][16, 16], 1 - o * math.exp(-d2), rtol=1e-12)
+    # a disk whose 3-sigma rim reaches the camera plane is culled
+    big = dict(tiny, log_scale=np.log([[5.0, 5.0]]), tan_u=np.array([[0.0, 0, 1.0]]), tan_v=np.array([[0, 1.0, 0]]))
+    assert oracle.preprocess2d(big, cam)["radius"][0] == 0
+
+
+@pytest.mark.parametrize("seed", [0, 3])
+def test_white_furnace(seed):
+    sc, cam = _scene(seed, n=48)
+    f = oracle.forward2d(sc, cam, [1, 1, 1])
+    st = dict(f["state"]); st["color"] = np.ones_like(st["color"])
+    out = oracle.render_fwd2d(st, f["lists"], cam["width"], cam["height"], [1.0, 1.0, 1.0])
+    np.testing.assert_allclose(out["image"], 1.0, atol=1e-13)
+    assert out["n_blend"] > 500 and (out["final_T"] >= 1e-4).all()
+
+
+def _fd(sc, cam, seed, eps=1e-6, rtol=3e-5, min_checked=0.6):
+    W, H = cam["width"], cam["height"]
+    G = np.random.default_rng(seed).normal(size=(H, W, 3))
+
+    def run():
+        f = oracle.forward2d(sc, cam, BG, splat_dtype=np.float64)
+        sig = (f["splats"]["radius"].tobytes(), f["lists"]["vals"].tobytes(), f["lists"]["ranges"].tobytes(),
+               f["last_idx"].tobytes(), (f["splats"]["color"] > 0).tobytes())
+        return float((f["image"] * G).sum()), sig, f
+    L0, sig0, f0 = run()
+    assert (f0["fragile"] == 0).all()
+    g = oracle.backward2d(sc, cam, BG, f0, G)
+    checked = total = 0
+    for name in ("mean", "tan_u", "tan_v", "log_scale", "logit", "sh"):
+        a = sc[name]
+        scale = max(np.abs(g[name]).max(), 1e-12)
+        for idx in np.ndindex(a.shape):
+            total += 1
+            old = a[idx]
+            a[idx] = old + eps; Lp, sp, fp = run()
+            a[idx] = old - eps; Lm, sm, fm = run()
+            a[idx] = old
+            if sp != sig0 or sm != sig0 or fp["fragile"].any() or fm["fragile"].any():
+                continue
+            checked += 1
+            assert abs((Lp - Lm) / (2 * eps) - g[name][idx]) <= rtol * scale + 1e-9, (name, idx)
+    assert checked >= min_checked * total, (checked, total)
+    return g, f0
+
+
+@pytest.mark.parametrize("seed,deg", [(0, 2), (1, 0), (4, 3)])
+def test_finite_differences(seed, deg):
+    sc = _f64(synth.random_small_surfels(seed, 8, deg))
+    cam = synth.pinhole(32, 32, 50.0, *synth.look_at([0.4, -0.3, -2.2], [0, 0, 0], [0, 1, 0]))
+    cam["cx"] += 0.8
+    g, f = _fd(sc, cam, seed)
+    assert f["n_blend"] > 300
+    for k in ("mean", "tan_u", "tan_v", "log_scale", "logit", "sh"):
+        assert np.abs(g[k]).max() > 0
+
+
+def test_finite_differences_low_pass_branch():
+    """Very thin disks: most blended pixels take the screen-space low-pass branch, whose gradient flows through mean2d."""
+    sc = _f64(synth.random_small_surfels(5, 6, 0, spread=0.4, ls_mu=-6.0, ls_sigma=0.1))
+    sc["logit"][:] = 1.0
+    cam = synth.pinhole(32, 32, 50.0, np.eye(3), [0.0, 0.0, 2.0])
+    g, f = _fd(sc, cam, 7, min_checked=0.5)
+    assert np.abs(g["d_splats"]["mean2d"]).max() > 0 and f["n_blend"] > 20
