@@ -160,6 +160,91 @@ int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t
 int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------------------------
+ * 2D Gaussian surfels: the same three calls for the paper's 2DGS configuration (Sec. 5 "Applications"; per-view
+ * state of Table 3b, 20 floats; App. B notes that 2DGS projects more accurately than the affine approximation).
+ * The paper gives only the state layout; this library's readings, which the CPU oracle states too:
+ *   - a point is a disk: centre, two raw tangent vectors made orthonormal by Gram-Schmidt (t_u = a/|a|, t_v = the
+ *     normalised part of b orthogonal to t_u), scales exp(log_scale) along them, opacity, SH colour;
+ *   - ray_transform T = K [R s_u t_u | R s_v t_v | R mean + t] (row-major 3x3) maps disk coordinates (u, v, 1) to
+ *     homogeneous pixels; a pixel (x, y) meets the disk plane at (u, v) = (p_0, p_1) / p_2, p = h_u x h_v,
+ *     h_u = x T_2 - T_0, h_v = y T_2 - T_1 (rows of T); G = exp(-(u^2 + v^2) / 2);
+ *   - screen-space low-pass G^ = max(G, exp(-|pixel - mean2d|^2)); alpha = min(0.99, o G^); a pair with p_2 = 0 is
+ *     skipped; skip / stop / order rules as for 3D Gaussians;
+ *   - extent = max(3, ceil(largest reach, from mean2d, of the exact bounding box of the 3-sigma rim's perspective
+ *     image)); a disk whose 3-sigma rim reaches the camera plane is culled; depth = camera-space z of the centre;
+ *   - normal = R (t_u x t_v), turned to face the camera (an output; carries no gradient).
+ * Workspaces are laid out differently from the 3D calls: size them with pbdr2d_workspace_bytes and inspect them with
+ * pbdr2d_lists_view. pbdr_query_lists does not apply; read num_dup through pbdr2d_lists_view. */
+typedef struct pbdr2d_scene {
+    int32_t n;
+    int32_t sh_degree;
+    const float* mean;          /* [3][n] */
+    const float* tan_u;         /* [3][n] raw first tangent, any non-zero length */
+    const float* tan_v;         /* [3][n] raw second tangent, not parallel to tan_u */
+    const float* log_scale;     /* [2][n] */
+    const float* opacity_logit; /* [n] */
+    const float* sh;            /* [K][3][n] */
+} pbdr2d_scene;
+
+typedef struct pbdr2d_scene_grads { /* accumulated (+=) */
+    int32_t n;
+    int32_t sh_degree;
+    float* mean;
+    float* tan_u;
+    float* tan_v;
+    float* log_scale;
+    float* opacity_logit;
+    float* sh;
+} pbdr2d_scene_grads;
+
+/* Per-view surfel state: the 20 floats per point of Table 3b (radius counted as one). radius == 0 = culled. */
+typedef struct pbdr2d_splats {
+    int32_t n;
+    float* mean2d;        /* [2][n] */
+    float* ray_transform; /* [9][n] T row-major: plane k holds T[k/3][k%3] */
+    float* opacity;       /* [n] */
+    float* color;         /* [3][n] */
+    int32_t* radius;      /* [n] */
+    float* depth;         /* [n] */
+    float* normal;        /* [3][n] camera-space unit normal facing the camera */
+} pbdr2d_splats;
+
+typedef struct pbdr2d_splat_grads { /* overwritten */
+    int32_t n;
+    float* mean2d;        /* [2][n] through the low-pass term only */
+    float* ray_transform; /* [9][n] */
+    float* opacity;       /* [n] */
+    float* color;         /* [3][n] */
+} pbdr2d_splat_grads;
+
+int pbdr2d_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes);
+
+/* pts_culling + pts_splatting for surfels (Sec. 3.1; state of Table 3b). Writes all of `out`. */
+int pbdr2d_preprocess(const pbdr2d_scene* scene, const pbdr_camera* cam, pbdr2d_splats* out, void* hip_stream);
+
+/* image_render forward for surfels: binning and sorting exactly as pbdr_bin_sort (Sec. 2.1), then per-tile
+ * front-to-back compositing with one ray-disk intersection per (pixel, splat) pair. Outputs as pbdr_render_fwd. */
+int pbdr2d_render_fwd(const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
+                      float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+/* image_render.backward then pts_splatting.backward for surfels (Alg. 1 lines 17-18, 22-24); arguments and the
+ * scene/grads NULL rule as pbdr_render_bwd. */
+int pbdr2d_render_bwd(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3],
+                      uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                      pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+/* pts_splatting.backward alone for surfels; accumulates into grads. */
+int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr2d_splats* splats,
+                          const pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* hip_stream);
+
+/* As pbdr_lists_view, for a workspace used by pbdr2d_render_fwd. */
+int pbdr2d_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                      uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
+                      const uint32_t** ranges, const uint32_t** num_dup);
+
 /* Optional per-kernel timing for benchmarks, with HIP events recorded on the stream each kernel is launched on.
  * kernel_mask: bit i enables kernel id i (ids 0 .. pbdr_profile_kernel_count()-1, names from
  * pbdr_profile_kernel_name). At most max_records launches are timed between begin/reset and collect.

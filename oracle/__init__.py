@@ -228,16 +228,18 @@ def _scene2d_arrays(scene):
             _f64(scene["log_scale"], (n, 2)), _f64(scene["logit"], (n,)), _f64(scene["sh"], (n, K, 3)))
 
 
-def preprocess2d(scene: dict, cam: dict) -> dict:
+def preprocess2d(scene: dict, cam: dict, tau: float = 2e-5) -> dict:
     n, deg, K, mean, tu, tv, ls, lo, sh = _scene2d_arrays(scene)
     out = dict(mean2d=np.zeros((n, 2)), T=np.zeros((n, 9)), opacity=np.zeros(n), color=np.zeros((n, 3)),
-               radius=np.zeros(n, dtype=np.int32), depth=np.zeros(n), normal=np.zeros((n, 3)), bbox=np.zeros((n, 4)))
+               radius=np.zeros(n, dtype=np.int32), depth=np.zeros(n), normal=np.zeros((n, 3)), bbox=np.zeros((n, 4)),
+               near_tie=np.zeros(n, dtype=np.uint8))
     c = camera(cam)
     lib().orc2d_preprocess(C.c_int(n), C.c_int(deg), _p(mean, C.c_double), _p(tu, C.c_double), _p(tv, C.c_double),
                            _p(ls, C.c_double), _p(lo, C.c_double), _p(sh, C.c_double), C.byref(c),
                            _p(out["mean2d"], C.c_double), _p(out["T"], C.c_double), _p(out["opacity"], C.c_double),
                            _p(out["color"], C.c_double), _p(out["radius"], C.c_int32), _p(out["depth"], C.c_double),
-                           _p(out["normal"], C.c_double), _p(out["bbox"], C.c_double))
+                           _p(out["normal"], C.c_double), _p(out["bbox"], C.c_double), _p(out["near_tie"], C.c_uint8),
+                           C.c_double(tau))
     return out
 
 

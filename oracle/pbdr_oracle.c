@@ -728,6 +728,7 @@ typedef struct {
     double su, sv, o;
     double Hm[9], T[9];
     double mean2d[2], bc[2], half[2];
+    double arim, reach; /* rim-vs-camera-plane discriminant and largest reach of the bounding box (set when in depth range) */
     int radius;
     int32_t rect[4];
     double ncam[3];
@@ -771,6 +772,7 @@ static void project2d_one(int sh_degree, const double mean[3], const double ta[3
     {
         const double a = 9.0 * (P->T[6] * P->T[6] + P->T[7] * P->T[7]) - P->T[8] * P->T[8];
         double reach = 0.0, r;
+        P->arim = a;
         if (!(a < 0.0)) return; /* the 3-sigma rim reaches the camera plane */
         for (i = 0; i < 2; ++i) {
             const double* Ti = P->T + 3 * i;
@@ -785,6 +787,7 @@ static void project2d_one(int sh_degree, const double mean[3], const double ta[3
             r = fabs(P->bc[i] - P->mean2d[i]) + P->half[i];
             if (r > reach) reach = r;
         }
+        P->reach = reach;
         r = ceil(reach);
         if (r < 3.0) r = 3.0;
         if (!(r < (double)ORC_RADIUS_MAX)) r = (double)ORC_RADIUS_MAX;
@@ -820,11 +823,13 @@ static void project2d_one(int sh_degree, const double mean[3], const double ta[3
 }
 
 /* Table 3b state: mean2d[n][2], T[n][9] (ray_transforms), opacity[n], color[n][3], radius[n], depth[n], normal[n][3].
- * Optional: bbox[n][4] = (centre_x, centre_y, half_x, half_y) of the 3-sigma disk's image. */
+ * Optional: bbox[n][4] = (centre_x, centre_y, half_x, half_y) of the 3-sigma disk's image; near_tie[n] = 1 where an
+ * integer decision (a cull test, the extent's ceil, the tile rectangle) is within `tau` of flipping, or where the rim
+ * comes so close to the camera plane that the extent is ill-conditioned, so an fp32 evaluation may differ. */
 void orc2d_preprocess(int n, int sh_degree, const double* mean, const double* tan_u, const double* tan_v,
                       const double* log_scale2, const double* logit, const double* sh, const orc_camera* cam,
                       double* mean2d, double* T, double* opacity, double* color, int32_t* radius, double* depth,
-                      double* normal, double* bbox)
+                      double* normal, double* bbox, uint8_t* near_tie, double tau)
 {
     const int K = (sh_degree + 1) * (sh_degree + 1);
     int i;
@@ -838,6 +843,30 @@ void orc2d_preprocess(int n, int sh_degree, const double* mean, const double* ta
         for (k = 0; k < 9; ++k) T[9 * i + k] = 0.0;
         for (k = 0; k < 3; ++k) { color[3 * i + k] = 0.0; normal[3 * i + k] = 0.0; }
         if (bbox) for (k = 0; k < 4; ++k) bbox[4 * i + k] = 0.0;
+        if (near_tie) {
+            int flag = 0;
+            const double z = P.T[8];
+            if (fabs(z - cam->near_plane) < tau * fabs(z) || fabs(z - cam->far_plane) < tau * fabs(z)) flag = 1;
+            if (z >= cam->near_plane && z <= cam->far_plane) {
+                if (fabs(P.arim) < 0.02 * z * z) flag = 1;
+                if (P.arim < 0.0) {
+                    int32_t ra[4], rb[4];
+                    double elo = P.reach * (1.0 - tau) - tau, ehi = P.reach * (1.0 + tau) + tau;
+                    int rlo, rhi;
+                    if (fabs(P.reach - floor(P.reach + 0.5)) < tau * (1.0 + P.reach)) flag = 1;
+                    if (elo < 3.0) elo = 3.0;
+                    if (ehi < 3.0) ehi = 3.0;
+                    rlo = (int)ceil(elo); rhi = (int)ceil(ehi);
+                    if (((double)rlo <= cam->radius_clip) != ((double)rhi <= cam->radius_clip)) flag = 1;
+                    orc_tile_rect(P.mean2d[0] - tau * (1.0 + fabs(P.mean2d[0])), P.mean2d[1] - tau * (1.0 + fabs(P.mean2d[1])),
+                                  P.radius > 0 ? P.radius : rhi, cam->width, cam->height, ra);
+                    orc_tile_rect(P.mean2d[0] + tau * (1.0 + fabs(P.mean2d[0])), P.mean2d[1] + tau * (1.0 + fabs(P.mean2d[1])),
+                                  P.radius > 0 ? P.radius : rhi, cam->width, cam->height, rb);
+                    for (k = 0; k < 4; ++k) if (ra[k] != rb[k]) flag = 1;
+                }
+            }
+            near_tie[i] = (uint8_t)flag;
+        }
         if (!P.visible) continue;
         mean2d[2 * i] = P.mean2d[0]; mean2d[2 * i + 1] = P.mean2d[1];
         for (k = 0; k < 9; ++k) T[9 * i + k] = P.T[k];

@@ -25,7 +25,9 @@ PBDR_ERR_HIP = -4
 EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_render_fwd", "pbdr_render_bwd",
            "pbdr_preprocess_bwd", "pbdr_lists_view", "pbdr_query_lists", "pbdr_status_string", "pbdr_last_hip_error",
            "pbdr_version", "pbdr_render_stats", "pbdr_profile_begin", "pbdr_profile_collect", "pbdr_profile_reset",
-           "pbdr_profile_end", "pbdr_profile_kernel_name", "pbdr_profile_kernel_count")
+           "pbdr_profile_end", "pbdr_profile_kernel_name", "pbdr_profile_kernel_count",
+           "pbdr2d_workspace_bytes", "pbdr2d_preprocess", "pbdr2d_render_fwd", "pbdr2d_render_bwd", "pbdr2d_preprocess_bwd",
+           "pbdr2d_lists_view")
 
 _f = C.POINTER(C.c_float)
 
@@ -48,6 +50,21 @@ class CSplats(C.Structure):
 
 class CSplatGrads(C.Structure):
     _fields_ = [("n", C.c_int32), ("mean2d", C.c_void_p), ("conic", C.c_void_p), ("opacity", C.c_void_p),
+                ("color", C.c_void_p)]
+
+
+class CScene2D(C.Structure):
+    _fields_ = [("n", C.c_int32), ("sh_degree", C.c_int32), ("mean", C.c_void_p), ("tan_u", C.c_void_p),
+                ("tan_v", C.c_void_p), ("log_scale", C.c_void_p), ("opacity_logit", C.c_void_p), ("sh", C.c_void_p)]
+
+
+class CSplats2D(C.Structure):
+    _fields_ = [("n", C.c_int32), ("mean2d", C.c_void_p), ("ray_transform", C.c_void_p), ("opacity", C.c_void_p),
+                ("color", C.c_void_p), ("radius", C.c_void_p), ("depth", C.c_void_p), ("normal", C.c_void_p)]
+
+
+class CSplatGrads2D(C.Structure):
+    _fields_ = [("n", C.c_int32), ("mean2d", C.c_void_p), ("ray_transform", C.c_void_p), ("opacity", C.c_void_p),
                 ("color", C.c_void_p)]
 
 
@@ -273,12 +290,12 @@ def pbdr_query_lists(ws, n, width, height, dup_capacity, stream=None):
     return int(out.value), st == PBDR_ERR_CAPACITY
 
 
-def pbdr_lists_view(ws, n, width, height, dup_capacity):
+def pbdr_lists_view(ws, n, width, height, dup_capacity, _entry="pbdr_lists_view"):
     """Copies the sorted lists out of the workspace (synchronises): dict(P, keys, vals, ranges) as numpy."""
     keys, vals, ranges, nd = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
-    _check(lib().pbdr_lists_view(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
-                                 C.c_int32(height), C.c_uint64(dup_capacity), _stream(None), C.byref(keys), C.byref(vals),
-                                 C.byref(ranges), C.byref(nd)))
+    _check(getattr(lib(), _entry)(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
+                                  C.c_int32(height), C.c_uint64(dup_capacity), _stream(None), C.byref(keys), C.byref(vals),
+                                  C.byref(ranges), C.byref(nd)))
     torch.cuda.synchronize()
     base = ws.data_ptr()
     host = ws.cpu().numpy()
@@ -326,3 +343,158 @@ def pbdr_profile_collect(kernel_id: int):
 
 def pbdr_profile_end() -> None:
     _check(lib().pbdr_profile_end())
+
+
+# ---------------------------------------------------------------------------------------------- 2D Gaussian surfels
+@dataclass
+class Scene2D:
+    """Surfel parameters on the device: mean[3,n], tan_u[3,n], tan_v[3,n], log_scale[2,n], logit[n], sh[K,3,n]."""
+    n: int
+    sh_degree: int
+    mean: torch.Tensor
+    tan_u: torch.Tensor
+    tan_v: torch.Tensor
+    log_scale: torch.Tensor
+    logit: torch.Tensor
+    sh: torch.Tensor
+
+    @staticmethod
+    def from_numpy(sc: dict, device="cuda") -> "Scene2D":
+        def up(a, perm):
+            return torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=np.float32).transpose(perm))).to(device)
+        n = int(sc["mean"].shape[0])
+        return Scene2D(n, int(sc["sh_degree"]), up(sc["mean"], (1, 0)), up(sc["tan_u"], (1, 0)), up(sc["tan_v"], (1, 0)),
+                       up(sc["log_scale"], (1, 0)),
+                       torch.from_numpy(np.ascontiguousarray(sc["logit"], dtype=np.float32)).to(device), up(sc["sh"], (1, 2, 0)))
+
+    def zeros_like(self) -> "Scene2D":
+        return Scene2D(self.n, self.sh_degree, torch.zeros_like(self.mean), torch.zeros_like(self.tan_u),
+                       torch.zeros_like(self.tan_v), torch.zeros_like(self.log_scale), torch.zeros_like(self.logit),
+                       torch.zeros_like(self.sh))
+
+    def to_numpy(self) -> dict:
+        return dict(mean=self.mean.cpu().numpy().T.copy(), tan_u=self.tan_u.cpu().numpy().T.copy(),
+                    tan_v=self.tan_v.cpu().numpy().T.copy(), log_scale=self.log_scale.cpu().numpy().T.copy(),
+                    logit=self.logit.cpu().numpy().copy(), sh=self.sh.cpu().numpy().transpose(2, 0, 1).copy(),
+                    sh_degree=self.sh_degree)
+
+    def struct(self) -> CScene2D:
+        return CScene2D(self.n, self.sh_degree, _dev(self.mean), _dev(self.tan_u), _dev(self.tan_v), _dev(self.log_scale),
+                        _dev(self.logit), _dev(self.sh))
+
+
+@dataclass
+class Splats2D:
+    """Per-view surfel state (Table 3b), SoA planes; T is the 3x3 ray transform, row-major over its 9 planes."""
+    n: int
+    mean2d: torch.Tensor
+    T: torch.Tensor
+    opacity: torch.Tensor
+    color: torch.Tensor
+    radius: torch.Tensor
+    depth: torch.Tensor
+    normal: torch.Tensor
+
+    @staticmethod
+    def empty(n, device="cuda") -> "Splats2D":
+        f = dict(dtype=torch.float32, device=device)
+        return Splats2D(n, torch.empty((2, n), **f), torch.empty((9, n), **f), torch.empty(n, **f), torch.empty((3, n), **f),
+                        torch.empty(n, dtype=torch.int32, device=device), torch.empty(n, **f), torch.empty((3, n), **f))
+
+    @staticmethod
+    def from_numpy(st: dict, device="cuda") -> "Splats2D":
+        def up(a, dt=np.float32):
+            a = np.asarray(a, dtype=dt)
+            return torch.from_numpy(np.ascontiguousarray(a.T if a.ndim == 2 else a)).to(device)
+        n = int(np.asarray(st["opacity"]).shape[0])
+        normal = st["normal"] if "normal" in st else np.zeros((n, 3))
+        return Splats2D(n, up(st["mean2d"]), up(st["T"]), up(st["opacity"]), up(st["color"]), up(st["radius"], np.int32),
+                        up(st["depth"]), up(normal))
+
+    def to_numpy(self) -> dict:
+        return dict(mean2d=self.mean2d.cpu().numpy().T.copy(), T=self.T.cpu().numpy().T.copy(),
+                    opacity=self.opacity.cpu().numpy().copy(), color=self.color.cpu().numpy().T.copy(),
+                    radius=self.radius.cpu().numpy().copy(), depth=self.depth.cpu().numpy().copy(),
+                    normal=self.normal.cpu().numpy().T.copy())
+
+    def struct(self) -> CSplats2D:
+        return CSplats2D(self.n, _dev(self.mean2d), _dev(self.T), _dev(self.opacity), _dev(self.color), _dev(self.radius),
+                         _dev(self.depth), _dev(self.normal))
+
+
+@dataclass
+class SplatGrads2D:
+    n: int
+    mean2d: torch.Tensor
+    T: torch.Tensor
+    opacity: torch.Tensor
+    color: torch.Tensor
+
+    @staticmethod
+    def empty(n, device="cuda") -> "SplatGrads2D":
+        f = dict(dtype=torch.float32, device=device)
+        return SplatGrads2D(n, torch.empty((2, n), **f), torch.empty((9, n), **f), torch.empty(n, **f), torch.empty((3, n), **f))
+
+    @staticmethod
+    def from_numpy(d: dict, device="cuda") -> "SplatGrads2D":
+        def up(a):
+            a = np.asarray(a, dtype=np.float32)
+            return torch.from_numpy(np.ascontiguousarray(a.T if a.ndim == 2 else a)).to(device)
+        n = int(np.asarray(d["opacity"]).shape[0])
+        return SplatGrads2D(n, up(d["mean2d"]), up(d["T"]), up(d["opacity"]), up(d["color"]))
+
+    def to_numpy(self) -> dict:
+        return dict(mean2d=self.mean2d.cpu().numpy().T.copy(), T=self.T.cpu().numpy().T.copy(),
+                    opacity=self.opacity.cpu().numpy().copy(), color=self.color.cpu().numpy().T.copy())
+
+    def struct(self) -> CSplatGrads2D:
+        return CSplatGrads2D(self.n, _dev(self.mean2d), _dev(self.T), _dev(self.opacity), _dev(self.color))
+
+
+def pbdr2d_workspace_bytes(n, width, height, dup_capacity) -> int:
+    out = C.c_size_t(0)
+    _check(lib().pbdr2d_workspace_bytes(C.c_int32(n), C.c_int32(width), C.c_int32(height), C.c_uint64(dup_capacity),
+                                        C.byref(out)))
+    return int(out.value)
+
+
+def alloc_workspace2d(n, width, height, dup_capacity, device="cuda") -> torch.Tensor:
+    nbytes = pbdr2d_workspace_bytes(n, width, height, dup_capacity)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws[off:off + nbytes]
+
+
+def pbdr2d_preprocess(scene: Scene2D, cam: dict, out: Splats2D, stream=None) -> None:
+    s, c, o = scene.struct(), camera_struct(cam), out.struct()
+    _check(lib().pbdr2d_preprocess(C.byref(s), C.byref(c), C.byref(o), _stream(stream)))
+
+
+def pbdr2d_render_fwd(splats: Splats2D, cam: dict, bg, dup_capacity: int, image, final_T, last_idx, ws, stream=None) -> None:
+    s, c = splats.struct(), camera_struct(cam)
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    _check(lib().pbdr2d_render_fwd(C.byref(s), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(image), _dev(final_T),
+                                   _dev(last_idx), C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def pbdr2d_render_bwd(scene, splats: Splats2D, cam: dict, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
+                      g_splats: SplatGrads2D, grads, ws, stream=None) -> None:
+    sp, c, g2 = splats.struct(), camera_struct(cam), g_splats.struct()
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    if scene is not None:
+        sc, g = scene.struct(), grads.struct()
+        psc, pg = C.byref(sc), C.byref(g)
+    else:
+        psc, pg = None, None
+    _check(lib().pbdr2d_render_bwd(psc, C.byref(sp), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(final_T), _dev(last_idx),
+                                   _dev(dL_dimage), C.byref(g2), pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
+                                   _stream(stream)))
+
+
+def pbdr2d_preprocess_bwd(scene: Scene2D, cam: dict, splats: Splats2D, g_splats: SplatGrads2D, grads: Scene2D, stream=None) -> None:
+    sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct()
+    _check(lib().pbdr2d_preprocess_bwd(C.byref(sc), C.byref(c), C.byref(sp), C.byref(g2), C.byref(g), _stream(stream)))
+
+
+def pbdr2d_lists_view(ws, n, width, height, dup_capacity):
+    return pbdr_lists_view(ws, n, width, height, dup_capacity, _entry="pbdr2d_lists_view")

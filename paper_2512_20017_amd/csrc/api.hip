@@ -10,12 +10,15 @@ static thread_local int g_last_hip_error = 0;
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
+bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
 {
     if (n < 0 || W <= 0 || H <= 0 || W > 65536 || H > 65536) return false;
     if (cap == 0) cap = 1;
     if (cap > 0x3fffffffull) return false;
     L->n = n; L->W = W; L->H = H;
+    L->variant = variant;
+    L->record_bytes = variant == kVariant2D ? 64 : sizeof(Packed);
+    L->partial_vec4 = variant == kVariant2D ? 4 : 3;
     L->TX = (W + kTile - 1) / kTile; L->TY = (H + kTile - 1) / kTile;
     L->tiles = L->TX * L->TY;
     L->cap = (uint32_t)cap;
@@ -26,7 +29,8 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
     size_t off = 0;
     const auto take = [&](size_t bytes) { const size_t at = off; off = align256(off + bytes); return at; };
     L->off_status = take(kStWords * sizeof(uint32_t));
-    L->off_packed = take((size_t)n * sizeof(Packed));
+    L->off_packed = take((size_t)n * L->record_bytes);
+    L->off_depth_bits = take((size_t)n * sizeof(uint32_t));
     L->off_touched = take((size_t)n * sizeof(uint32_t));
     L->off_offsets = take(((size_t)n + 1) * sizeof(uint32_t));
     L->off_slot_base = take((size_t)n * sizeof(uint32_t));
@@ -42,7 +46,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, Layout* L)
     L->off_totals = take((size_t)2 * 4 * 256 * sizeof(uint32_t));   // digit totals of the depth sort, then of the tile sort
     L->off_tile_hist = take((nblk_d > nblk_t ? nblk_d : nblk_t) * 256 * sizeof(uint32_t));
     L->off_ranges = take((size_t)L->tiles * 2 * sizeof(uint32_t));
-    L->off_partial = take((size_t)cap * 12 * sizeof(float));
+    L->off_partial = take((size_t)cap * L->partial_vec4 * 4 * sizeof(float));
     L->off_keys64 = take((size_t)cap * sizeof(uint64_t));
     L->total = off;
     return true;
@@ -108,6 +112,44 @@ static SceneGradDev dev(const pbdr_scene_grads* g) { return SceneGradDev{g->mean
 static SplatsDev dev(const pbdr_splats* s) { return SplatsDev{s->n, s->mean2d, s->conic, s->opacity, s->color, s->radius, s->depth}; }
 static SplatGradDev dev(const pbdr_splat_grads* g) { return SplatGradDev{g->mean2d, g->conic, g->opacity, g->color}; }
 
+static bool check_scene2d(const pbdr2d_scene* sc)
+{
+    if (!sc || sc->n < 0 || sc->sh_degree < 0 || sc->sh_degree > 3) return false;
+    if (sc->n == 0) return true;
+    return aligned16(sc->mean) && aligned16(sc->tan_u) && aligned16(sc->tan_v) && aligned16(sc->log_scale) &&
+           aligned16(sc->opacity_logit) && aligned16(sc->sh);
+}
+static bool check_scene2d_grads(const pbdr2d_scene_grads* g, const pbdr2d_scene* sc)
+{
+    if (!g || g->n != sc->n || g->sh_degree != sc->sh_degree) return false;
+    if (g->n == 0) return true;
+    return aligned16(g->mean) && aligned16(g->tan_u) && aligned16(g->tan_v) && aligned16(g->log_scale) &&
+           aligned16(g->opacity_logit) && aligned16(g->sh);
+}
+static bool check_splats2d(const pbdr2d_splats* sp)
+{
+    if (!sp || sp->n < 0) return false;
+    if (sp->n == 0) return true;
+    return aligned16(sp->mean2d) && aligned16(sp->ray_transform) && aligned16(sp->opacity) && aligned16(sp->color) &&
+           aligned16(sp->radius) && aligned16(sp->depth) && aligned16(sp->normal);
+}
+static bool check_splat2d_grads(const pbdr2d_splat_grads* g, int n)
+{
+    if (!g || g->n != n) return false;
+    if (n == 0) return true;
+    return aligned16(g->mean2d) && aligned16(g->ray_transform) && aligned16(g->opacity) && aligned16(g->color);
+}
+static Scene2DDev dev(const pbdr2d_scene* s)
+{
+    return Scene2DDev{s->n, s->sh_degree, s->mean, s->tan_u, s->tan_v, s->log_scale, s->opacity_logit, s->sh};
+}
+static Scene2DGradDev dev(const pbdr2d_scene_grads* g) { return Scene2DGradDev{g->mean, g->tan_u, g->tan_v, g->log_scale, g->opacity_logit, g->sh}; }
+static Splats2DDev dev(const pbdr2d_splats* s)
+{
+    return Splats2DDev{s->n, s->mean2d, s->ray_transform, s->opacity, s->color, s->radius, s->depth, s->normal};
+}
+static Splat2DGradDev dev(const pbdr2d_splat_grads* g) { return Splat2DGradDev{g->mean2d, g->ray_transform, g->opacity, g->color}; }
+
 static int hip_result(hipError_t e)
 {
     if (e == hipSuccess) return PBDR_OK;
@@ -115,9 +157,9 @@ static int hip_result(hipError_t e)
     return PBDR_ERR_HIP;
 }
 
-static int workspace_ok(void* ws, size_t bytes, int n, int W, int H, uint64_t cap, Layout* L)
+static int workspace_ok(void* ws, size_t bytes, int n, int W, int H, uint64_t cap, Layout* L, int variant = kVariant3D)
 {
-    if (!make_layout(n, W, H, cap, L)) return PBDR_ERR_INVALID_ARG;
+    if (!make_layout(n, W, H, cap, variant, L)) return PBDR_ERR_INVALID_ARG;
     if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return PBDR_ERR_INVALID_ARG;
     if (bytes < L->total) return PBDR_ERR_WORKSPACE_TOO_SMALL;
     return PBDR_OK;
@@ -148,7 +190,7 @@ const char* pbdr_status_string(int status)
 int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes)
 {
     Layout L;
-    if (!out_bytes || !make_layout(n, width, height, dup_capacity, &L)) return PBDR_ERR_INVALID_ARG;
+    if (!out_bytes || !make_layout(n, width, height, dup_capacity, kVariant3D, &L)) return PBDR_ERR_INVALID_ARG;
     *out_bytes = L.total;
     return PBDR_OK;
 }
@@ -224,12 +266,12 @@ int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, 
     return hip_result(launch_render_stats(to_dev(cam), L, (char*)workspace, counters, (hipStream_t)hip_stream));
 }
 
-int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
-                    uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
-                    const uint32_t** ranges, const uint32_t** num_dup)
+static int lists_view(int variant, void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                      uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
+                      const uint32_t** ranges, const uint32_t** num_dup)
 {
     Layout L;
-    const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L);
+    const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L, variant);
     if (st != PBDR_OK) return st;
     char* ws = (char*)workspace;
     if (keys) {
@@ -243,6 +285,78 @@ int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t 
     if (ranges) *ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
     if (num_dup) *num_dup = reinterpret_cast<const uint32_t*>(ws + L.off_status) + kStNumDup;
     return PBDR_OK;
+}
+
+int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                    uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
+                    const uint32_t** ranges, const uint32_t** num_dup)
+{
+    return lists_view(kVariant3D, workspace, workspace_bytes, n, width, height, dup_capacity, hip_stream, keys, vals, ranges, num_dup);
+}
+
+int pbdr2d_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                      uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
+                      const uint32_t** ranges, const uint32_t** num_dup)
+{
+    return lists_view(kVariant2D, workspace, workspace_bytes, n, width, height, dup_capacity, hip_stream, keys, vals, ranges, num_dup);
+}
+
+int pbdr2d_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes)
+{
+    Layout L;
+    if (!out_bytes || !make_layout(n, width, height, dup_capacity, kVariant2D, &L)) return PBDR_ERR_INVALID_ARG;
+    *out_bytes = L.total;
+    return PBDR_OK;
+}
+
+int pbdr2d_preprocess(const pbdr2d_scene* scene, const pbdr_camera* cam, pbdr2d_splats* out, void* hip_stream)
+{
+    if (!check_scene2d(scene) || !check_camera(cam) || !check_splats2d(out) || out->n != scene->n) return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_preprocess2d(dev(scene), to_dev(cam), dev(out), (hipStream_t)hip_stream));
+}
+
+int pbdr2d_render_fwd(const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
+                      float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
+                      void* hip_stream)
+{
+    if (!check_splats2d(splats) || !check_camera(cam) || !bg || !aligned16(image) || !aligned16(final_T) || !aligned16(last_idx))
+        return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L, kVariant2D);
+    if (st != PBDR_OK) return st;
+    const CamDev c = to_dev(cam);
+    hipError_t e = launch_bin_sort2d(dev(splats), c, L, (char*)workspace, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_result(e);
+    return hip_result(launch_composite2d_fwd(c, L, (char*)workspace, bg, image, final_T, last_idx, (hipStream_t)hip_stream));
+}
+
+int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr2d_splats* splats,
+                          const pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* hip_stream)
+{
+    if (!check_scene2d(scene) || !check_camera(cam) || !check_splats2d(splats) || splats->n != scene->n ||
+        !check_splat2d_grads(g_splats, scene->n) || !check_scene2d_grads(grads, scene))
+        return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_preprocess2d_bwd(dev(scene), to_dev(cam), dev(splats), dev(g_splats), dev(grads), (hipStream_t)hip_stream));
+}
+
+int pbdr2d_render_bwd(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3],
+                      uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
+                      pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes,
+                      void* hip_stream)
+{
+    if (!check_splats2d(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) ||
+        !aligned16(dL_dimage) || !check_splat2d_grads(g_splats, splats->n))
+        return PBDR_ERR_INVALID_ARG;
+    if ((scene == nullptr) != (grads == nullptr)) return PBDR_ERR_INVALID_ARG;
+    if (scene && (!check_scene2d(scene) || scene->n != splats->n || !check_scene2d_grads(grads, scene))) return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L, kVariant2D);
+    if (st != PBDR_OK) return st;
+    const CamDev c = to_dev(cam);
+    hipError_t e = launch_composite2d_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
+                                          (hipStream_t)hip_stream);
+    if (e != hipSuccess || !scene) return hip_result(e);
+    return hip_result(launch_preprocess2d_bwd(dev(scene), c, dev(splats), dev(g_splats), dev(grads), (hipStream_t)hip_stream));
 }
 
 int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,

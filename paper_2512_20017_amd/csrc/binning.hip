@@ -26,7 +26,7 @@ __device__ __forceinline__ void rect_of(const CamDev& cam, float mx, float my, i
 // pair for the depth sort (culled points get the largest key and sort to the end).
 __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, uint32_t* __restrict__ tiles_touched,
                                                     Packed* __restrict__ packed, uint32_t* __restrict__ dkey,
-                                                    uint32_t* __restrict__ dval)
+                                                    uint32_t* __restrict__ dval, uint32_t* __restrict__ depth_bits)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= sp.n) return;
@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, ui
     tiles_touched[i] = cnt;
     dkey[i] = key;
     dval[i] = (uint32_t)i;
+    depth_bits[i] = key;
 }
 
 // tile counts in depth order (rank r holds the point order[r]); slot n is the sentinel that makes the scan leave
@@ -187,7 +188,7 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
 // lane l writes slots B + l, B + l + 64, ... and finds the owning rank of a slot by binary search over the 64 range
 // ends kept in LDS. Pair order within a point: row-major over its tile rectangle. Also records, per point, where
 // its pairs start (slot_base), which the backward pass uses to address its per-pair sums.
-__global__ __launch_bounds__(256) void k_duplicate(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ order,
+__global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, const uint32_t* __restrict__ order,
                                                    const uint32_t* __restrict__ offsets, uint32_t* __restrict__ tkeys,
                                                    uint32_t* __restrict__ tvals, uint32_t* __restrict__ slot_base,
                                                    uint32_t cap, uint32_t* __restrict__ status)
@@ -259,15 +260,15 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict_
 }
 
 // Inspection only: the 64-bit keys (tile << 32 | depth bits) of the sorted pairs, rebuilt from the sorted tile ids
-// and the depth kept in the raster record.
+// and the per-point depth bits.
 __global__ __launch_bounds__(256) void k_make_keys64(const uint32_t* __restrict__ tkeys, const uint32_t* __restrict__ tvals,
-                                                     const Packed* __restrict__ packed, const uint32_t* __restrict__ status,
+                                                     const uint32_t* __restrict__ depth_bits, const uint32_t* __restrict__ status,
                                                      uint32_t cap, uint64_t* __restrict__ keys64)
 {
     const uint32_t P = min(status[kStNumDup], cap);
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i >= P) return;
-    keys64[i] = ((uint64_t)tkeys[i] << 32) | __float_as_uint(packed[tvals[i]].depth);
+    keys64[i] = ((uint64_t)tkeys[i] << 32) | depth_bits[tvals[i]];
 }
 
 hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s)
@@ -276,15 +277,42 @@ hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s)
     const uint32_t* tk = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
     const uint32_t* tv = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     hipLaunchKernelGGL(k_make_keys64, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, tk, tv,
-                       reinterpret_cast<const Packed*>(ws + L.off_packed), status, L.cap,
+                       reinterpret_cast<const uint32_t*>(ws + L.off_depth_bits), status, L.cap,
                        reinterpret_cast<uint64_t*>(ws + L.off_keys64));
     return hipGetLastError();
 }
 
-hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
+hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
 {
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
-    Packed* packed = reinterpret_cast<Packed*>(ws + L.off_packed);
+    uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
+    uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
+    // status words, digit totals and tile ranges start at zero
+    ProfScope prof(kKFill, s);
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
+    hipLaunchKernelGGL(k_fill_u32, dim3(8), dim3(256), 0, s, totals, 0u, (size_t)2048);
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
+                       2 * (size_t)L.tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
+{
+    if (sp.n == 0) return hipSuccess;
+    ProfScope prof(kKCountPack, s);
+    hipLaunchKernelGGL(k_count_pack, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
+                       reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed*>(ws + L.off_packed),
+                       reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
+                       reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
+    return hipGetLastError();
+}
+
+// Everything after the per-point counts and (depth bits, index) pairs are in place: depth order, prefix sum,
+// duplication, tile sort, tile ranges.
+hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
+{
+    if (sp.n == 0) return hipSuccess;
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     uint32_t* touched = reinterpret_cast<uint32_t*>(ws + L.off_touched);
     uint32_t* offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
     uint32_t* slot_base = reinterpret_cast<uint32_t*>(ws + L.off_slot_base);
@@ -297,19 +325,6 @@ hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout&
     uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
     uint32_t* tile_hist = reinterpret_cast<uint32_t*>(ws + L.off_tile_hist);
     const unsigned nblk = (unsigned)((sp.n + 255) / 256);
-    {
-        // status words, digit totals and tile ranges start at zero
-        ProfScope prof(kKFill, s);
-        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
-        hipLaunchKernelGGL(k_fill_u32, dim3(8), dim3(256), 0, s, totals, 0u, (size_t)2048);
-        hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
-                           2 * (size_t)L.tiles);
-    }
-    if (sp.n == 0) return hipGetLastError();
-    {
-        ProfScope prof(kKCountPack, s);
-        hipLaunchKernelGGL(k_count_pack, dim3(nblk), dim3(256), 0, s, sp, cam, touched, packed, dk[0], dv[0]);
-    }
     // depth digits: sort the n splats by their 32 depth bits (4 passes, result back in buffer 0)
     hipError_t e = launch_radix_sort32(dk, dv, nullptr, (uint32_t)sp.n, 4, totals, tile_hist, s);
     if (e != hipSuccess) return e;
@@ -333,6 +348,15 @@ hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout&
         hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
+{
+    hipError_t e = launch_bin_begin(L, ws, s);
+    if (e != hipSuccess) return e;
+    e = launch_count_pack(sp, cam, L, ws, s);
+    if (e != hipSuccess) return e;
+    return launch_bin_finish(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
 }
 
 }  // namespace pbdr

@@ -53,26 +53,58 @@ struct SplatGradDev {
     float *mean2d, *conic, *opacity, *color;
 };
 
+// 2D Gaussian surfels: raw parameters, per-view state (Table 3b of the paper) and their gradients
+struct Scene2DDev {
+    int n, sh_degree;
+    const float *mean, *tan_u, *tan_v, *log_scale, *logit, *sh;
+};
+struct Scene2DGradDev {
+    float *mean, *tan_u, *tan_v, *log_scale, *logit, *sh;
+};
+struct Splats2DDev {
+    int n;
+    float *mean2d, *T, *opacity, *color;
+    int32_t* radius;
+    float *depth, *normal;
+};
+struct Splat2DGradDev {
+    float *mean2d, *T, *opacity, *color;
+};
+
 // Status words at the head of the workspace.
 enum { kStNumDup = 0, kStOverflow = 1, kStWords = 64 };
 
 // Workspace layout for (n, W, H, capacity). All offsets are multiples of 256 bytes.
+enum Variant { kVariant3D = 0, kVariant2D = 1 };   // 3D Gaussians / 2D Gaussian surfels
+
 struct Layout {
     int n, W, H, TX, TY, tiles;
+    int variant;
+    size_t record_bytes;      // raster record per point: 48 (3D) or 64 (2D)
+    int partial_vec4;         // float4s of partial gradient sums per pair: 3 (3D) or 4 (2D)
     uint32_t cap;
     int tile_bits, tile_passes;   // key bits / 8-bit passes spent on the tile id
-    size_t off_status, off_packed, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
+    size_t off_status, off_packed, off_depth_bits, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
         off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
         off_partial, off_keys64, total;
 };
 constexpr int kSortItems = 4096;   // pairs per radix-sort block
 constexpr int kScanItems = 4096;   // elements per scan block
-bool make_layout(int n, int W, int H, uint64_t cap, Layout* L);
+bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L);
 
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
 hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, hipStream_t s);
 hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
                                  const SceneGradDev& g, hipStream_t s);
+// what binning needs of a splat state, whatever the variant
+struct BinInput {
+    int n;
+    const float* mean2d;      // [2][n]
+    const int32_t* radius;    // [n]
+};
+hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s);                       // zero status / totals / ranges
+hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
+hipError_t launch_bin_finish(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
                                 float* final_T, uint32_t* last_idx, hipStream_t s);
@@ -89,6 +121,16 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
 hipError_t launch_radix_sort32(uint32_t* keys[2], uint32_t* vals[2], const uint32_t* count_ptr, uint32_t count_cap,
                                int passes, uint32_t* totals, uint32_t* tile_hist, hipStream_t s);
 hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s);
+
+// 2D Gaussian surfel variant (workspace laid out with kVariant2D)
+hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& out, hipStream_t s);
+hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
+                                   const Scene2DGradDev& g, hipStream_t s);
+hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
+hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
+                                  float* final_T, uint32_t* last_idx, hipStream_t s);
+hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3], const float* final_T,
+                                  const uint32_t* last_idx, const float* dL_dimage, const Splat2DGradDev& g2, hipStream_t s);
 
 // final location of the sorted pair lists (depends on the parity of the tile pass count)
 inline size_t sorted_tkeys_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tkey1 : L.off_tkey0; }

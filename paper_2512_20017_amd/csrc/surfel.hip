@@ -1,0 +1,735 @@
+// 2D Gaussian surfels (the paper's 2DGS configuration: Sec. 5 "Applications"; Table 3b state of 20 floats; App. B
+// "2DGS models [the projection] more accurately"): per-point projection and its derivative, raster record, and the
+// per-tile compositing kernels with a ray-disk intersection per (pixel, splat) pair instead of a projected conic.
+//
+// A point is an oriented disk: centre, two raw tangent vectors made orthonormal by Gram-Schmidt, two scales, opacity,
+// SH colour. ray_transform T = K [R s_u t_u | R s_v t_v | R mean + t] maps disk coordinates (u, v, 1) to homogeneous
+// pixels. A pixel's ray meets the disk plane at (u, v) = (p_0, p_1) / p_2 with p = h_u x h_v, h_u = x T_2 - T_0,
+// h_v = y T_2 - T_1 (rows of T); G = exp(-(u^2+v^2)/2), low-pass G^ = max(G, exp(-|pixel - mean2d|^2)),
+// alpha = min(0.99, o G^); skip / stop / order rules as for 3D Gaussians.
+//
+// fp32 care: x T_2 - T_0 subtracts numbers of size (pixel x depth) to leave one of size (offset x depth). The raster
+// record therefore stores rows centred on the projected centre, T_0' = T_0 - mx T_2 and T_1' = T_1 - my T_2 (one fused
+// multiply-add each, so exactly rounded), and the kernels use h_u = dx T_2 - T_0' with dx = x - mx. The same value of
+// mx is used on both sides, so this is the same number as x T_2 - T_0, without the cancellation.
+#include "composite_common.h"
+
+namespace pbdr {
+
+// 64-byte raster record
+struct __attribute__((aligned(16))) Packed2D {
+    float t0x, t0y, t1x, t1y;      // centred rows T_0', T_1' (first two components)
+    float t2x, t2y, t2z, o;        // T_2, opacity
+    float mx, my, r, g;            // mean2d, red, green
+    float b, radius_bits, t0z, t1z;  // blue, integer extent (bit-cast), third components of the centred rows (rounding residue)
+};
+static_assert(sizeof(Packed2D) == 64, "surfel raster record is 64 bytes");
+
+__device__ __forceinline__ void sh_basis2(int deg, float x, float y, float z, float Y[16])
+{
+    Y[0] = 0.28209479177387814f;
+    if (deg < 1) return;
+    Y[1] = -0.4886025119029199f * y; Y[2] = 0.4886025119029199f * z; Y[3] = -0.4886025119029199f * x;
+    if (deg < 2) return;
+    const float xx = x * x, yy = y * y, zz = z * z;
+    Y[4] = 1.0925484305920792f * x * y;
+    Y[5] = -1.0925484305920792f * y * z;
+    Y[6] = 0.31539156525252005f * (2.f * zz - xx - yy);
+    Y[7] = -1.0925484305920792f * x * z;
+    Y[8] = 0.5462742152960396f * (xx - yy);
+    if (deg < 3) return;
+    Y[9] = -0.5900435899266435f * y * (3.f * xx - yy);
+    Y[10] = 2.890611442640554f * x * y * z;
+    Y[11] = -0.4570457994644658f * y * (4.f * zz - xx - yy);
+    Y[12] = 0.3731763325901154f * z * (2.f * zz - 3.f * xx - 3.f * yy);
+    Y[13] = -0.4570457994644658f * x * (4.f * zz - xx - yy);
+    Y[14] = 1.445305721320277f * z * (xx - yy);
+    Y[15] = -0.5900435899266435f * x * (xx - 3.f * yy);
+}
+
+__device__ __forceinline__ void sh_basis_grad2(int deg, float x, float y, float z, float dY[16][3])
+{
+#pragma unroll
+    for (int k = 0; k < 16; ++k) dY[k][0] = dY[k][1] = dY[k][2] = 0.f;
+    if (deg < 1) return;
+    const float c1 = 0.4886025119029199f;
+    dY[1][1] = -c1; dY[2][2] = c1; dY[3][0] = -c1;
+    if (deg < 2) return;
+    const float c2a = 1.0925484305920792f, c2b = 0.31539156525252005f, c2c = 0.5462742152960396f;
+    dY[4][0] = c2a * y; dY[4][1] = c2a * x;
+    dY[5][1] = -c2a * z; dY[5][2] = -c2a * y;
+    dY[6][0] = -2.f * c2b * x; dY[6][1] = -2.f * c2b * y; dY[6][2] = 4.f * c2b * z;
+    dY[7][0] = -c2a * z; dY[7][2] = -c2a * x;
+    dY[8][0] = 2.f * c2c * x; dY[8][1] = -2.f * c2c * y;
+    if (deg < 3) return;
+    const float c3a = 0.5900435899266435f, c3b = 2.890611442640554f, c3c = 0.4570457994644658f,
+                c3d = 0.3731763325901154f, c3e = 1.445305721320277f;
+    const float xx = x * x, yy = y * y, zz = z * z;
+    dY[9][0] = -6.f * c3a * x * y;             dY[9][1] = -3.f * c3a * (xx - yy);
+    dY[10][0] = c3b * y * z;                   dY[10][1] = c3b * x * z;                  dY[10][2] = c3b * x * y;
+    dY[11][0] = 2.f * c3c * x * y;             dY[11][1] = -c3c * (4.f * zz - xx - 3.f * yy); dY[11][2] = -8.f * c3c * y * z;
+    dY[12][0] = -6.f * c3d * x * z;            dY[12][1] = -6.f * c3d * y * z;           dY[12][2] = 3.f * c3d * (2.f * zz - xx - yy);
+    dY[13][0] = -c3c * (4.f * zz - 3.f * xx - yy); dY[13][1] = 2.f * c3c * x * y;        dY[13][2] = -8.f * c3c * x * z;
+    dY[14][0] = 2.f * c3e * x * z;             dY[14][1] = -2.f * c3e * y * z;           dY[14][2] = c3e * (xx - yy);
+    dY[15][0] = -3.f * c3a * (xx - yy);        dY[15][1] = 6.f * c3a * x * y;
+}
+
+struct Frame2D {
+    float tu[3], tv[3], w[3], ainv, winv, btu, su, sv;
+    float H[9];   // row-major; columns R s_u t_u, R s_v t_v, R mean + t
+};
+
+__device__ __forceinline__ void surfel_frame(const CamDev& cam, const float m[3], const float a[3], const float b[3],
+                                             float ls0, float ls1, Frame2D& F)
+{
+    F.su = expf(ls0); F.sv = expf(ls1);
+    F.ainv = 1.0f / sqrtf(a[0] * a[0] + a[1] * a[1] + a[2] * a[2]);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) F.tu[i] = a[i] * F.ainv;
+    F.btu = b[0] * F.tu[0] + b[1] * F.tu[1] + b[2] * F.tu[2];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) F.w[i] = b[i] - F.btu * F.tu[i];
+    F.winv = 1.0f / sqrtf(F.w[0] * F.w[0] + F.w[1] * F.w[1] + F.w[2] * F.w[2]);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) F.tv[i] = F.w[i] * F.winv;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        F.H[3 * i] = F.su * (cam.R[3 * i] * F.tu[0] + cam.R[3 * i + 1] * F.tu[1] + cam.R[3 * i + 2] * F.tu[2]);
+        F.H[3 * i + 1] = F.sv * (cam.R[3 * i] * F.tv[0] + cam.R[3 * i + 1] * F.tv[1] + cam.R[3 * i + 2] * F.tv[2]);
+        F.H[3 * i + 2] = cam.R[3 * i] * m[0] + cam.R[3 * i + 1] * m[1] + cam.R[3 * i + 2] * m[2] + cam.t[i];
+    }
+}
+
+template <int kDeg>
+__global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam, Splats2DDev out)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = (size_t)n;
+    const float m[3] = {sc.mean[i], sc.mean[N + i], sc.mean[2 * N + i]};
+    const float pz = cam.R[6] * m[0] + cam.R[7] * m[1] + cam.R[8] * m[2] + cam.t[2];
+    if (!(pz >= cam.near_p && pz <= cam.far_p)) { out.radius[i] = 0; return; }
+    const float a[3] = {sc.tan_u[i], sc.tan_u[N + i], sc.tan_u[2 * N + i]};
+    const float b[3] = {sc.tan_v[i], sc.tan_v[N + i], sc.tan_v[2 * N + i]};
+    Frame2D F;
+    surfel_frame(cam, m, a, b, sc.log_scale[i], sc.log_scale[N + i], F);
+    float T[9];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        T[k] = cam.fx * F.H[k] + cam.cx * F.H[6 + k];
+        T[3 + k] = cam.fy * F.H[3 + k] + cam.cy * F.H[6 + k];
+        T[6 + k] = F.H[6 + k];
+    }
+    const float aa = 9.f * (T[6] * T[6] + T[7] * T[7]) - T[8] * T[8];
+    if (!(aa < 0.f)) { out.radius[i] = 0; return; }
+    const float iz = 1.0f / T[8];
+    // projected centre, formed from the camera-space columns so that cx, cy do not cancel
+    const float mx = cam.fx * F.H[2] * iz + cam.cx, my = cam.fy * F.H[5] * iz + cam.cy;
+    float reach = 0.f;
+    {
+        // Bounding box of the perspective image of the 3-sigma rim, in coordinates centred on the projected centre:
+        // rows U_i = f_i (H_i - (H_i2 / H_22) H_2), whose third components vanish, so neither the principal point nor
+        // the centre's own pixel coordinate enters (no cancellation of large numbers).
+        const float ia = 1.0f / (9.f * (F.H[6] * F.H[6] + F.H[7] * F.H[7]) - F.H[8] * F.H[8]);
+        const float f2[2] = {cam.fx, cam.fy};
+#pragma unroll
+        for (int ax = 0; ax < 2; ++ax) {
+            const float* Hi = F.H + 3 * ax;
+            const float sl = Hi[2] * iz;
+            const float u0 = f2[ax] * (Hi[0] - sl * F.H[6]), u1 = f2[ax] * (Hi[1] - sl * F.H[7]);
+            const float bb = 9.f * (u0 * F.H[6] + u1 * F.H[7]);
+            const float cc = 9.f * (u0 * u0 + u1 * u1);
+            const float c0 = bb * ia;
+            const float half = sqrtf(fmaxf(1e-4f, c0 * c0 - cc * ia));
+            reach = fmaxf(reach, fabsf(c0) + half);
+        }
+    }
+    float ext = fmaxf(3.f, ceilf(reach));
+    const int r = (ext < (float)kRadiusMax) ? (int)ext : kRadiusMax;
+    if ((float)r <= cam.radius_clip) { out.radius[i] = 0; return; }
+    {
+        const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
+        const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
+        const int x0 = min(max((ix - r) >> 4, 0), cam.TX), y0 = min(max((iy - r) >> 4, 0), cam.TY);
+        const int x1 = min(max((ix + r + 15) >> 4, 0), cam.TX), y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+        if ((x1 - x0) * (y1 - y0) <= 0) { out.radius[i] = 0; return; }
+    }
+    const float vx = m[0] - cam.campos[0], vy = m[1] - cam.campos[1], vz = m[2] - cam.campos[2];
+    const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
+    float Y[16];
+    sh_basis2(kDeg, vx * vinv, vy * vinv, vz * vinv, Y);
+    constexpr int K = (kDeg + 1) * (kDeg + 1);
+    float rgb[3] = {0.5f, 0.5f, 0.5f};
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * sc.sh[(size_t)(3 * k + c) * N + i];
+    }
+    // normal = R (t_u x t_v), turned towards the camera
+    float nw[3] = {F.tu[1] * F.tv[2] - F.tu[2] * F.tv[1], F.tu[2] * F.tv[0] - F.tu[0] * F.tv[2], F.tu[0] * F.tv[1] - F.tu[1] * F.tv[0]};
+    float nc[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) nc[k] = cam.R[3 * k] * nw[0] + cam.R[3 * k + 1] * nw[1] + cam.R[3 * k + 2] * nw[2];
+    const float facing = nc[0] * F.H[2] + nc[1] * F.H[5] + nc[2] * F.H[8];
+    const float sgn = facing > 0.f ? -1.f : 1.f;
+    out.mean2d[i] = mx; out.mean2d[N + i] = my;
+#pragma unroll
+    for (int k = 0; k < 9; ++k) out.T[(size_t)k * N + i] = T[k];
+    out.opacity[i] = 1.0f / (1.0f + expf(-sc.logit[i]));
+#pragma unroll
+    for (int c = 0; c < 3; ++c) { out.color[(size_t)c * N + i] = fmaxf(rgb[c], 0.f); out.normal[(size_t)c * N + i] = sgn * nc[c]; }
+    out.radius[i] = r;
+    out.depth[i] = T[8];
+}
+
+template <int kDeg>
+__global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev cam, const int32_t* __restrict__ radius,
+                                                          const float* __restrict__ Tst, Splat2DGradDev g2, Scene2DGradDev g)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    if (radius[i] <= 0) return;
+    const size_t N = (size_t)n;
+    const float m[3] = {sc.mean[i], sc.mean[N + i], sc.mean[2 * N + i]};
+    const float a[3] = {sc.tan_u[i], sc.tan_u[N + i], sc.tan_u[2 * N + i]};
+    const float b[3] = {sc.tan_v[i], sc.tan_v[N + i], sc.tan_v[2 * N + i]};
+    Frame2D F;
+    surfel_frame(cam, m, a, b, sc.log_scale[i], sc.log_scale[N + i], F);
+    {
+        const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
+        g.logit[i] += g2.opacity[i] * o * (1.f - o);
+    }
+    float dmu[3] = {0.f, 0.f, 0.f};
+    {
+        const float vx = m[0] - cam.campos[0], vy = m[1] - cam.campos[1], vz = m[2] - cam.campos[2];
+        const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
+        const float dx = vx * vinv, dy = vy * vinv, dz = vz * vinv;
+        float Y[16];
+        float dY[16][3];
+        sh_basis2(kDeg, dx, dy, dz, Y);
+        sh_basis_grad2(kDeg, dx, dy, dz, dY);
+        constexpr int K = (kDeg + 1) * (kDeg + 1);
+        float gd0 = 0.f, gd1 = 0.f, gd2 = 0.f;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            float raw = 0.5f, t0 = 0.f, t1 = 0.f, t2 = 0.f;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const float co = sc.sh[(size_t)(3 * k + c) * N + i];
+                raw += Y[k] * co;
+                t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
+            }
+            const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
+            if (gc != 0.f) {
+#pragma unroll
+                for (int k = 0; k < K; ++k) g.sh[(size_t)(3 * k + c) * N + i] += Y[k] * gc;
+            }
+            gd0 += gc * t0; gd1 += gc * t1; gd2 += gc * t2;
+        }
+        const float dot = gd0 * dx + gd1 * dy + gd2 * dz;
+        dmu[0] += (gd0 - dx * dot) * vinv; dmu[1] += (gd1 - dy * dot) * vinv; dmu[2] += (gd2 - dz * dot) * vinv;
+    }
+    // gradient w.r.t. the stored transform, plus mean2d_i = T_i2 / T_22
+    float GT[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) GT[k] = g2.T[(size_t)k * N + i];
+    {
+        const float T02 = Tst[2 * N + i], T12 = Tst[5 * N + i], T22 = Tst[8 * N + i];
+        const float iz = 1.0f / T22, gmx = g2.mean2d[i], gmy = g2.mean2d[N + i];
+        GT[2] += gmx * iz; GT[5] += gmy * iz;
+        GT[8] -= (gmx * T02 + gmy * T12) * iz * iz;
+    }
+    float GH[9];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        GH[k] = cam.fx * GT[k];
+        GH[3 + k] = cam.fy * GT[3 + k];
+        GH[6 + k] = cam.cx * GT[k] + cam.cy * GT[3 + k] + GT[6 + k];
+    }
+    float gcol[3][3];   // world-space gradients of the three column vectors
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+#pragma unroll
+        for (int r = 0; r < 3; ++r) gcol[k][r] = cam.R[r] * GH[k] + cam.R[3 + r] * GH[3 + k] + cam.R[6 + r] * GH[6 + k];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) g.mean[(size_t)r * N + i] += dmu[r] + gcol[2][r];
+    g.log_scale[i] += F.su * (gcol[0][0] * F.tu[0] + gcol[0][1] * F.tu[1] + gcol[0][2] * F.tu[2]);
+    g.log_scale[N + i] += F.sv * (gcol[1][0] * F.tv[0] + gcol[1][1] * F.tv[1] + gcol[1][2] * F.tv[2]);
+    {
+        float gtu[3], gtv[3], gw[3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) { gtu[r] = F.su * gcol[0][r]; gtv[r] = F.sv * gcol[1][r]; }
+        float dot = gtv[0] * F.tv[0] + gtv[1] * F.tv[1] + gtv[2] * F.tv[2];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) gw[r] = (gtv[r] - F.tv[r] * dot) * F.winv;
+        const float gbtu = -(gw[0] * F.tu[0] + gw[1] * F.tu[1] + gw[2] * F.tu[2]);
+        float gx[3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            g.tan_v[(size_t)r * N + i] += gw[r] + gbtu * F.tu[r];
+            gx[r] = gtu[r] - F.btu * gw[r] + gbtu * b[r];
+        }
+        dot = gx[0] * F.tu[0] + gx[1] * F.tu[1] + gx[2] * F.tu[2];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) g.tan_u[(size_t)r * N + i] += (gx[r] - F.tu[r] * dot) * F.ainv;
+    }
+}
+
+// One thread per point: tile count, 64-byte raster record with centred rows, (depth bits, index) for the depth sort.
+__global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam, uint32_t* __restrict__ tiles_touched,
+                                                      Packed2D* __restrict__ packed, uint32_t* __restrict__ dkey,
+                                                      uint32_t* __restrict__ dval, uint32_t* __restrict__ depth_bits)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sp.n) return;
+    const size_t N = (size_t)sp.n;
+    const int r = sp.radius[i];
+    uint32_t cnt = 0, key = 0xFFFFFFFFu;
+    if (r > 0) {
+        const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
+        const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
+        const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
+        const int x0 = min(max((ix - r) >> 4, 0), cam.TX), y0 = min(max((iy - r) >> 4, 0), cam.TY);
+        const int x1 = min(max((ix + r + 15) >> 4, 0), cam.TX), y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+        cnt = (uint32_t)((x1 - x0) * (y1 - y0));
+        const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
+        float4* dst = reinterpret_cast<float4*>(packed + i);
+        dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
+                             fmaf(-my, t2y, sp.T[4 * N + i]));
+        dst[1] = make_float4(t2x, t2y, t2z, sp.opacity[i]);
+        dst[2] = make_float4(mx, my, sp.color[i], sp.color[N + i]);
+        dst[3] = make_float4(sp.color[2 * N + i], __int_as_float(r), fmaf(-mx, t2z, sp.T[2 * N + i]), fmaf(-my, t2z, sp.T[5 * N + i]));
+        key = __float_as_uint(sp.depth[i]);
+    }
+    tiles_touched[i] = cnt;
+    dkey[i] = key;
+    dval[i] = (uint32_t)i;
+    depth_bits[i] = key;
+}
+
+// LDS image of one staged batch of surfels
+struct Stage2D {
+    float4 a[kBatch];   // t0x, t0y, t1x, t1y
+    float4 b[kBatch];   // t2x, t2y, t2z, log2(opacity)
+    float4 c[kBatch];   // mx, my, red, green
+    float4 d[kBatch];   // blue, t0z, t1z, -
+    unsigned long long mask[4][4];
+};
+
+// Stage list entries [first, first+count): one per thread. A quadrant is kept for a splat if the bounding box of the
+// image of the disk rim where alpha falls to 1/255 (rho^2 = 2 ln(255 o)), or the low-pass support around the centre,
+// meets the quadrant's pixel centres; taken conservatively. All 256 threads must call it.
+__device__ __forceinline__ void stage_batch2d(Stage2D& S, const TileCtx& t, const uint32_t* __restrict__ vals,
+                                              const Packed2D* __restrict__ packed, uint32_t first, int count, uint32_t& id,
+                                              float4& r0, float4& r1, float4& r2, float4& r3)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool have = (int)threadIdx.x < count;
+    bool reach[4] = {false, false, false, false};
+    id = 0;
+    r0 = r1 = r2 = r3 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (have) {
+        id = vals[first + threadIdx.x];
+        const float4* rec = reinterpret_cast<const float4*>(packed + id);
+        r0 = rec[0]; r1 = rec[1]; r2 = rec[2]; r3 = rec[3];
+        const float L = __log2f(r1.w);
+        S.a[threadIdx.x] = r0;
+        S.b[threadIdx.x] = make_float4(r1.x, r1.y, r1.z, L);
+        S.c[threadIdx.x] = r2;
+        S.d[threadIdx.x] = make_float4(r3.x, r3.z, r3.w, 0.f);
+        const float tau = (L + kLog2_255) * 0.6931471805599453f;      // ln(255 o): alpha >= 1/255 <=> -ln G^ <= tau
+        if (!(tau < -0.02f)) {
+            const float rho2 = 2.f * fmaxf(tau, 0.f) + 0.05f;          // rim of the disk part, with margin
+            const float lp = sqrtf(fmaxf(tau, 0.f)) + 0.05f;           // radius of the low-pass part, with margin
+            // image of the rim u^2 + v^2 = rho2, relative to the projected centre: rows T_0', T_1', T_2
+            const float aa = rho2 * (r1.x * r1.x + r1.y * r1.y) - r1.z * r1.z;
+            float lo[2] = {-lp, -lp}, hi[2] = {lp, lp};
+            const bool bounded = aa < -0.02f * r1.z * r1.z;   // else the rim at this level comes (almost) to the camera plane: keep all
+            if (bounded) {
+                const float ia = 1.0f / aa;
+                const float bx = rho2 * (r0.x * r1.x + r0.y * r1.y) - r3.z * r1.z, by = rho2 * (r0.z * r1.x + r0.w * r1.y) - r3.w * r1.z;
+                const float cx = rho2 * (r0.x * r0.x + r0.y * r0.y) - r3.z * r3.z, cy = rho2 * (r0.z * r0.z + r0.w * r0.w) - r3.w * r3.w;
+                const float c0x = bx * ia, c0y = by * ia;
+                const float hx = sqrtf(fmaxf(0.f, c0x * c0x - cx * ia)) * 1.001f + 0.01f;
+                const float hy = sqrtf(fmaxf(0.f, c0y * c0y - cy * ia)) * 1.001f + 0.01f;
+                lo[0] = fminf(lo[0], c0x - hx); hi[0] = fmaxf(hi[0], c0x + hx);
+                lo[1] = fminf(lo[1], c0y - hy); hi[1] = fmaxf(hi[1], c0y + hy);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float qx0 = (float)(t.tx0 + (q & 1) * 8) + 0.5f - r2.x, qy0 = (float)(t.ty0 + (q >> 1) * 8) + 0.5f - r2.y;
+                // keep unless the box lies wholly outside the quadrant's span of pixel centres (NaN keeps)
+                const bool out = (hi[0] < qx0) || (lo[0] > qx0 + 7.f) || (hi[1] < qy0) || (lo[1] > qy0 + 7.f);
+                reach[q] = !bounded || !out;
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const unsigned long long m = __ballot(reach[q]);
+        if (lane == 0) S.mask[q][wave] = m;
+    }
+}
+
+// per-pair evaluation shared by forward and backward: exponent of G^ in log2 units and the pieces the backward needs
+struct Pair2D {
+    float dx, dy, hu0, hu1, hu2, hv0, hv1, hv2, p2, ip2, u, v, e1, e2;
+};
+
+__device__ __forceinline__ void eval_pair2d(const float4& a, const float4& b, const float4& c, const float4& d, float fx, float fy,
+                                            Pair2D& E)
+{
+    E.dx = fx - c.x; E.dy = fy - c.y;
+    E.hu0 = E.dx * b.x - a.x; E.hu1 = E.dx * b.y - a.y; E.hu2 = E.dx * b.z - d.y;
+    E.hv0 = E.dy * b.x - a.z; E.hv1 = E.dy * b.y - a.w; E.hv2 = E.dy * b.z - d.z;
+    const float p0 = E.hu1 * E.hv2 - E.hu2 * E.hv1;
+    const float p1 = E.hu2 * E.hv0 - E.hu0 * E.hv2;
+    E.p2 = E.hu0 * E.hv1 - E.hu1 * E.hv0;
+    E.ip2 = __builtin_amdgcn_rcpf(E.p2);
+    E.u = p0 * E.ip2; E.v = p1 * E.ip2;
+    E.e1 = (-0.5f * kLog2e) * (E.u * E.u + E.v * E.v);
+    E.e2 = -kLog2e * (E.dx * E.dx + E.dy * E.dy);
+}
+
+__global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint32_t* __restrict__ ranges,
+                                                         const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
+                                                         float bg0, float bg1, float bg2, float* __restrict__ image,
+                                                         float* __restrict__ final_T, uint32_t* __restrict__ last_idx)
+{
+    __shared__ Stage2D S;
+    const TileCtx c = tile_ctx(cam, ranges);
+    const int wave = threadIdx.x >> 6;
+    const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
+    float T = 1.f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
+    uint32_t last = 0;
+    bool live = c.inside;
+    for (uint32_t base = c.start; base < c.end; base += kBatch) {
+        if (__syncthreads_count(live) == 0) break;
+        const int cnt = (int)min((uint32_t)kBatch, c.end - base);
+        uint32_t id; float4 r0, r1, r2, r3;
+        stage_batch2d(S, c, vals, packed, base, cnt, id, r0, r1, r2, r3);
+        __syncthreads();
+        if (__ballot(live) == 0ull) continue;
+        const uint32_t pos0 = base - c.start + 1u;
+        for (int k = 0; k < 4; ++k) {
+            unsigned long long m = uniform_u64(S.mask[wave][k]);
+            while (m) {
+                const int j = k * 64 + __builtin_ctzll(m);
+                m &= m - 1ull;
+                const float4 a = S.a[j], b = S.b[j], cc = S.c[j], dd = S.d[j];
+                const float blue = dd.x;
+                Pair2D E;
+                eval_pair2d(a, b, cc, dd, fx, fy, E);
+                const float ex = (E.p2 != 0.f) ? fmaxf(E.e1, E.e2) : -1e30f;
+                const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.w + ex));
+                const bool valid = live && (E.p2 != 0.f) && (alpha >= kAlphaMin);
+                const float Tn = T * (1.f - alpha);
+                const bool stop = valid && (Tn < kTStop);
+                const bool blend = valid && !stop;
+                live = live && !stop;
+                const float w = blend ? alpha * T : 0.f;
+                C0 += cc.z * w; C1 += cc.w * w; C2 += blue * w;
+                T = blend ? Tn : T;
+                last = blend ? pos0 + (uint32_t)j : last;
+            }
+        }
+    }
+    if (c.inside) {
+        const size_t HW = (size_t)cam.W * cam.H;
+        image[c.pix] = C0 + T * bg0;
+        image[HW + c.pix] = C1 + T * bg1;
+        image[2 * HW + c.pix] = C2 + T * bg2;
+        final_T[c.pix] = T;
+        last_idx[c.pix] = last;
+    }
+}
+
+// Backward. With dp = dL/dp for p = h_u x h_v (three numbers per pair), the gradient of the transform is a lane sum of
+// the moments S0 = sum dp, Sx = sum dx dp, Sy = sum dy dp (dx, dy from the projected centre):
+//   sum dL/dh_u = T_2 x Sy - T_1' x S0,   sum dL/dh_v = Sx x T_2 - S0 x T_0',
+//   dT_0 = -sum dL/dh_u, dT_1 = -sum dL/dh_v, dT_2 = mx sum dL/dh_u + my sum dL/dh_v - T_1' x Sx - Sy x T_0'.
+// Together with 3 colour sums, d opacity and the 2 low-pass sums for mean2d: 15 sums per splat, through two row
+// butterflies, an LDS accumulator for the tile and one 64-byte record per (tile, splat) pair.
+__global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
+                                                         const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
+                                                         const uint32_t* __restrict__ slot_base, float bg0, float bg1, float bg2,
+                                                         const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
+                                                         const float* __restrict__ dL_dimage, uint32_t cap,
+                                                         float4* __restrict__ partial)
+{
+    __shared__ Stage2D S;
+    __shared__ float sAcc[16 * kBatch];
+    __shared__ uint32_t sMax[4];
+    const TileCtx c = tile_ctx(cam, ranges);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
+    const size_t HW = (size_t)cam.W * cam.H;
+    float T = 1.f, g0 = 0.f, g1 = 0.f, g2c = 0.f;
+    uint32_t last = 0;
+    if (c.inside) {
+        T = final_T[c.pix];
+        last = min(last_idx[c.pix], c.end - c.start);
+        g0 = dL_dimage[c.pix]; g1 = dL_dimage[HW + c.pix]; g2c = dL_dimage[2 * HW + c.pix];
+    }
+    float Sfx = T * (bg0 * g0 + bg1 * g1 + bg2 * g2c);
+    uint32_t wmax = last;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) wmax = max(wmax, (uint32_t)__shfl_xor((int)wmax, d, 64));
+    if (lane == 0) sMax[wave] = wmax;
+    __syncthreads();
+    const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
+    if (tile_last == 0) return;
+    const int tile_x = c.tx0 / kTile, tile_y = c.ty0 / kTile;
+    const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
+               r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
+    const int acc_slot = ((r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0)) * kBatch;
+    const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
+    for (int bi = nbatch - 1; bi >= 0; --bi) {
+        const uint32_t boff = (uint32_t)bi * kBatch;
+        const int cnt = (int)min((uint32_t)kBatch, tile_last - boff);
+        uint32_t id; float4 q0, q1, q2, q3;
+        stage_batch2d(S, c, vals, packed, c.start + boff, cnt, id, q0, q1, q2, q3);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
+        __syncthreads();
+        if (wmax > boff) {
+            for (int k = 3; k >= 0; --k) {
+                unsigned long long m = uniform_u64(S.mask[wave][k]);
+                while (m) {
+                    const int bit = 63 - __builtin_clzll(m);
+                    m &= ~(1ull << bit);
+                    const int j = k * 64 + bit;
+                    const uint32_t pos = boff + (uint32_t)j + 1u;
+                    const float4 a = S.a[j], b = S.b[j], cc = S.c[j], dd = S.d[j];
+                    const float blue = dd.x;
+                    Pair2D E;
+                    eval_pair2d(a, b, cc, dd, fx, fy, E);
+                    const bool disk = E.e1 > E.e2;                         // which part of the max is active (false for NaN)
+                    const float ex = disk ? E.e1 : E.e2;
+                    const float gh = __builtin_amdgcn_exp2f(ex);           // G^
+                    const float araw = __builtin_amdgcn_exp2f(b.w + ex);   // o G^
+                    const float alpha = fminf(kAlphaMax, araw);
+                    const bool hit = (pos <= last) && (E.p2 != 0.f) && (alpha >= kAlphaMin);
+                    if (__ballot(hit) == 0ull) continue;
+                    const float ioma = __builtin_amdgcn_rcpf(1.f - alpha);
+                    const float Tk = T * ioma;
+                    const float w = hit ? alpha * Tk : 0.f;
+                    const float cg = cc.z * g0 + cc.w * g1 + blue * g2c;
+                    const float dL_dalpha = Tk * cg - Sfx * ioma;
+                    const float da = (hit && araw < kAlphaMax) ? dL_dalpha : 0.f;     // zero where alpha was clamped
+                    T = hit ? Tk : T;
+                    Sfx += w * cg;
+                    const float d_o = gh * da;
+                    const float dgh = araw * da;                             // o G^ dL/dalpha (zero unless hit)
+                    // disk part: dL/du = -u G o dL/dalpha; low-pass part: dL/dmx = 2 dx G2 o dL/dalpha.
+                    // u, v, 1/p2 are finite wherever the disk part is the active one; elsewhere they are replaced by 0
+                    // so that no 0 * inf reaches the sums.
+                    const float us = disk ? E.u : 0.f, vs = disk ? E.v : 0.f, ips = disk ? E.ip2 : 0.f;
+                    const float du = -us * dgh, dv = -vs * dgh;
+                    const float dmx = disk ? 0.f : 2.f * E.dx * dgh, dmy = disk ? 0.f : 2.f * E.dy * dgh;
+                    const float dp0 = du * ips, dp1 = dv * ips, dp2 = -(du * us + dv * vs) * ips;
+                    const float va[8] = {dp0, dp1, dp2, E.dx * dp0, E.dx * dp1, E.dx * dp2, E.dy * dp0, E.dy * dp1};
+                    const float vb[8] = {E.dy * dp2, w * g0, w * g1, w * g2c, d_o, dmx, dmy, 0.f};
+                    const float pa = row_sum8(va, r1, r2, r3);
+                    const float pb = row_sum8(vb, r1, r2, r3);
+                    if ((lane & 8) == 0) {
+                        atomicAdd(&sAcc[acc_slot + j], pa);
+                        atomicAdd(&sAcc[8 * kBatch + acc_slot + j], pb);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < cnt) {
+            int x0, y0, x1, y1;
+            {
+                const int r = __float_as_int(q3.y);
+                const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(q2.x)));
+                const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(q2.y)));
+                x0 = min(max((ix - r) >> 4, 0), cam.TX); y0 = min(max((iy - r) >> 4, 0), cam.TY);
+                x1 = min(max((ix + r + 15) >> 4, 0), cam.TX); y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+            }
+            const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
+            if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
+                const int t = threadIdx.x;
+                const float s0[3] = {sAcc[0 * kBatch + t], sAcc[1 * kBatch + t], sAcc[2 * kBatch + t]};
+                const float sx[3] = {sAcc[3 * kBatch + t], sAcc[4 * kBatch + t], sAcc[5 * kBatch + t]};
+                const float sy[3] = {sAcc[6 * kBatch + t], sAcc[7 * kBatch + t], sAcc[8 * kBatch + t]};
+                const float t0[3] = {q0.x, q0.y, q3.z}, t1[3] = {q0.z, q0.w, q3.w}, t2[3] = {q1.x, q1.y, q1.z};
+                const float mx = q2.x, my = q2.y;
+                float dhu[3], dhv[3], ex[3];
+                // sum dL/dh_u = T2 x Sy - T1' x S0
+                dhu[0] = (t2[1] * sy[2] - t2[2] * sy[1]) - (t1[1] * s0[2] - t1[2] * s0[1]);
+                dhu[1] = (t2[2] * sy[0] - t2[0] * sy[2]) - (t1[2] * s0[0] - t1[0] * s0[2]);
+                dhu[2] = (t2[0] * sy[1] - t2[1] * sy[0]) - (t1[0] * s0[1] - t1[1] * s0[0]);
+                // sum dL/dh_v = Sx x T2 - S0 x T0'
+                dhv[0] = (sx[1] * t2[2] - sx[2] * t2[1]) - (s0[1] * t0[2] - s0[2] * t0[1]);
+                dhv[1] = (sx[2] * t2[0] - sx[0] * t2[2]) - (s0[2] * t0[0] - s0[0] * t0[2]);
+                dhv[2] = (sx[0] * t2[1] - sx[1] * t2[0]) - (s0[0] * t0[1] - s0[1] * t0[0]);
+                // - T1' x Sx - Sy x T0'
+                ex[0] = -(t1[1] * sx[2] - t1[2] * sx[1]) - (sy[1] * t0[2] - sy[2] * t0[1]);
+                ex[1] = -(t1[2] * sx[0] - t1[0] * sx[2]) - (sy[2] * t0[0] - sy[0] * t0[2]);
+                ex[2] = -(t1[0] * sx[1] - t1[1] * sx[0]) - (sy[0] * t0[1] - sy[1] * t0[0]);
+                float4* dst = partial + (size_t)4 * u;
+                dst[0] = make_float4(-dhu[0], -dhu[1], -dhu[2], -dhv[0]);                                     // dT0, dT1.x
+                dst[1] = make_float4(-dhv[1], -dhv[2], mx * dhu[0] + my * dhv[0] + ex[0], mx * dhu[1] + my * dhv[1] + ex[1]);
+                dst[2] = make_float4(mx * dhu[2] + my * dhv[2] + ex[2], sAcc[13 * kBatch + t], sAcc[14 * kBatch + t],   // dT2.z, d mean2d
+                                     sAcc[12 * kBatch + t]);                                                          // d opacity
+                dst[3] = make_float4(sAcc[9 * kBatch + t], sAcc[10 * kBatch + t], sAcc[11 * kBatch + t], 0.f);        // d colour
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Per point (in depth-rank order): add up the 64-byte partial records of its pairs; see the 3D variant for the scheme.
+__global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restrict__ order, const uint32_t* __restrict__ offsets,
+                                                  const float4* __restrict__ partial, uint32_t cap, Splat2DGradDev g2)
+{
+    __shared__ uint32_t sEnd[4][64];
+    __shared__ float sSum[4][16][64];
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t N = (size_t)n;
+    uint32_t b, e;
+    if (r < n) { b = min(offsets[r], cap); e = min(offsets[r + 1], cap); }
+    else { b = min(offsets[n], cap); e = b; }
+    sEnd[wave][lane] = e;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) sSum[wave][k][lane] = 0.f;
+    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)b, 0);
+    const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)e, 63);
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t base = first; base < last; base += 64) {      // uniform trip count: all lanes join the cross-lane steps
+        const uint32_t u = base + lane;
+        const bool mine = u < last;
+        float v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = 0.f;
+        if (mine) {
+            const float4 p0 = partial[(size_t)4 * u], p1 = partial[(size_t)4 * u + 1], p2 = partial[(size_t)4 * u + 2],
+                         p3 = partial[(size_t)4 * u + 3];
+            v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+            v[8] = p2.x; v[9] = p2.y; v[10] = p2.z; v[11] = p2.w; v[12] = p3.x; v[13] = p3.y; v[14] = p3.z;
+        }
+        int owner = 0;
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1)
+            if (sEnd[wave][owner + step - 1] <= u) owner += step;
+        if (!mine) owner = 64 + lane;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o2 = __shfl_up(owner, d, 64);
+            const bool same = (lane >= d) && (o2 == owner);
+#pragma unroll
+            for (int k = 0; k < 15; ++k) {
+                const float t = __shfl_up(v[k], d, 64);
+                v[k] += same ? t : 0.f;
+            }
+        }
+        const int onext = __shfl_down(owner, 1, 64);
+        if (mine && (lane == 63 || onext != owner)) {
+#pragma unroll
+            for (int k = 0; k < 15; ++k) sSum[wave][k][owner] += v[k];
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (r >= n) return;
+    const uint32_t i = order[r];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) g2.T[(size_t)k * N + i] = sSum[wave][k][lane];
+    g2.mean2d[i] = sSum[wave][9][lane]; g2.mean2d[N + i] = sSum[wave][10][lane];
+    g2.opacity[i] = sSum[wave][11][lane];
+    g2.color[i] = sSum[wave][12][lane]; g2.color[N + i] = sSum[wave][13][lane]; g2.color[2 * N + i] = sSum[wave][14][lane];
+}
+
+__global__ __launch_bounds__(256) void k_zero_partial2d(float4* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap)
+{
+    const size_t count = (size_t)4 * min(status[kStNumDup], cap);
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) partial[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ---------------------------------------------------------------------------------------------------- launchers
+hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& out, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    ProfScope prof(kKPreprocess, s);
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL(k_preprocess2d<0>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        case 1: hipLaunchKernelGGL(k_preprocess2d<1>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        case 2: hipLaunchKernelGGL(k_preprocess2d<2>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        default: hipLaunchKernelGGL(k_preprocess2d<3>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
+                                   const Scene2DGradDev& g, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    ProfScope prof(kKPreprocessBwd, s);
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL(k_preprocess2d_bwd<0>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        case 1: hipLaunchKernelGGL(k_preprocess2d_bwd<1>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        case 2: hipLaunchKernelGGL(k_preprocess2d_bwd<2>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        default: hipLaunchKernelGGL(k_preprocess2d_bwd<3>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
+{
+    hipError_t e = launch_bin_begin(L, ws, s);
+    if (e != hipSuccess) return e;
+    if (sp.n > 0) {
+        ProfScope prof(kKCountPack, s);
+        hipLaunchKernelGGL(k_count_pack2d, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
+                           reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed2D*>(ws + L.off_packed),
+                           reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
+                           reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
+    }
+    return launch_bin_finish(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
+}
+
+hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
+                                  float* final_T, uint32_t* last_idx, hipStream_t s)
+{
+    ProfScope prof(kKCompositeFwd, s);
+    hipLaunchKernelGGL(k_composite2d_fwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam,
+                       reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
+                       reinterpret_cast<const Packed2D*>(ws + L.off_packed), bg[0], bg[1], bg[2], image, final_T, last_idx);
+    return hipGetLastError();
+}
+
+hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3], const float* final_T,
+                                  const uint32_t* last_idx, const float* dL_dimage, const Splat2DGradDev& g2, hipStream_t s)
+{
+    const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
+    float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
+    {
+        ProfScope prof(kKFill, s);
+        hipLaunchKernelGGL(k_zero_partial2d, dim3((unsigned)(((size_t)4 * L.cap + 255) / 256)), dim3(256), 0, s, partial, status, L.cap);
+    }
+    {
+        ProfScope prof(kKCompositeBwd, s);
+        hipLaunchKernelGGL(k_composite2d_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam,
+                           reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
+                           reinterpret_cast<const Packed2D*>(ws + L.off_packed), reinterpret_cast<const uint32_t*>(ws + L.off_slot_base),
+                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
+    }
+    if (n > 0) {
+        ProfScope prof(kKGather, s);
+        hipLaunchKernelGGL(k_gather2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
+                           reinterpret_cast<const uint32_t*>(ws + L.off_dval0), reinterpret_cast<const uint32_t*>(ws + L.off_offsets),
+                           partial, L.cap, g2);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pbdr

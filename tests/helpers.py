@@ -24,8 +24,9 @@ def one_point_scene(mean, log_scale, quat, logit, rgb=None, sh=None, sh_degree=0
 
 def to_f64(scene):
     out = dict(scene)
-    for k in ("mean", "log_scale", "quat", "logit", "sh"):
-        out[k] = np.asarray(scene[k], dtype=np.float64).copy()
+    for k in ("mean", "log_scale", "quat", "tan_u", "tan_v", "logit", "sh"):
+        if k in scene:
+            out[k] = np.asarray(scene[k], dtype=np.float64).copy()
     return out
 
 

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "pbdr.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pbdr_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(pbdr(?:2d)?_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -34,6 +34,9 @@ def test_workspace_bytes():
     # dominated by 76 B/point (raster record, counts, offsets, depth-sort buffers) + 72 B/pair (tile keys, values,
     # their ping-pong copies, 48 B of partial gradient sums, 8 B of inspection keys)
     assert abs(big - (76e6 + 72 * 8e6)) < 0.1 * big
+    # surfels: 16 B more per point (64-byte raster record) and per pair (64 B of partial sums)
+    big2 = B.pbdr2d_workspace_bytes(1_000_000, 1920, 1080, 8_000_000)
+    assert abs((big2 - big) - (16e6 + 16 * 8e6)) < 1e5
     with pytest.raises(B.PbdrError):
         B.pbdr_workspace_bytes(-1, 128, 128, 10)
     with pytest.raises(B.PbdrError):
