@@ -175,11 +175,11 @@ def test_d_splatting_backward(case):
     both = (sp["radius"] > 0) & (case["ref"]["radius"] > 0) & (case["ref"]["near_tie"] == 0)
     for k in PARAM_KEYS:
         _grad_close(k, got[k][both], ref[k][both], floor_scale=3e-5)
-    # accumulation: a second backward doubles the parameter gradient
+    # accumulation: a second backward doubles the parameter gradient (up to the order of the in-tile float sums)
     view.render_bwd(BG, G, scene=scene, grads=grads)
     got2 = grads.to_numpy()
     for k in PARAM_KEYS:
-        np.testing.assert_allclose(got2[k], 2.0 * got[k], rtol=1e-6, atol=1e-30)
+        np.testing.assert_allclose(got2[k], 2.0 * got[k], rtol=1e-4, atol=1e-5 * np.abs(got[k]).max())
 
 
 def test_edge_empty_and_all_culled():
