@@ -71,7 +71,9 @@ def _grad_close(name, got, ref, floor_scale=1e-5, allow_frac=0.0):
     assert bad.mean() <= allow_frac, (name, int(bad.sum()), float(np.abs(got - ref).max()), float(np.abs(ref).max()))
 
 
-def _check_preprocess(sp, ref, cam, max_tie=0.01):
+def _check_preprocess(sp, ref, cam, sc, max_tie=0.01):
+    # S: magnitude of the world coordinates entering p = R x + t (fp32 leaves ~4e-7 S absolute error in p)
+    S = float(np.abs(sc["mean"]).max() + np.abs(cam["t"]).max())
     tie = ref["near_tie"] != 0
     assert tie.mean() < max_tie
     assert np.array_equal(sp["radius"][~tie], ref["radius"][~tie])
@@ -80,15 +82,24 @@ def _check_preprocess(sp, ref, cam, max_tie=0.01):
         f = max(cam["fx"], cam["fy"])
         z = ref["depth"][vis]
         # the centre comes through p = R x + t and a perspective divide, the transform through products with f and c
-        m_tol = 1e-4 + 3e-7 * np.abs(ref["mean2d"][vis]) + 4e-6 * f / z[:, None]
-        assert (np.abs(sp["mean2d"][vis] - ref["mean2d"][vis]) <= m_tol).all()
-        scale = np.abs(ref["T"][vis]).reshape(-1, 3, 3).max(axis=2, keepdims=True)     # per row of T
-        t_tol = (3e-6 * scale + 1e-6 * f) * np.ones((1, 1, 3))
-        assert (np.abs(sp["T"][vis].reshape(-1, 3, 3) - ref["T"][vis].reshape(-1, 3, 3)) <= t_tol).all()
+        slope = np.abs(ref["mean2d"][vis] - np.array([cam["cx"], cam["cy"]])) / f
+        m_tol = 1e-4 + 3e-7 * np.abs(ref["mean2d"][vis]) + 4e-7 * S * f * (1.0 + slope) / z[:, None]
+        m_err = np.abs(sp["mean2d"][vis] - ref["mean2d"][vis])
+        assert (m_err <= m_tol).all(), (int((m_err > m_tol).sum()), float(m_err.max()))
+        # rows of T are sums of products of size (f + c) x |p|; compare against the row's size and that floor
+        scale = np.abs(ref["T"][vis]).reshape(-1, 3, 3).max(axis=2, keepdims=True)
+        t_tol = (3e-6 * scale + 6e-7 * (f + max(cam["cx"], cam["cy"])) * S) * np.ones((1, 1, 3))
+        t_tol[:, 2, :] = 3e-6 * scale[:, 2, :] + 6e-7 * S
+        t_err = np.abs(sp["T"][vis].reshape(-1, 3, 3) - ref["T"][vis].reshape(-1, 3, 3))
+        assert (t_err <= t_tol).all(), (int((t_err > t_tol).sum()), float(t_err.max()))
         np.testing.assert_allclose(sp["opacity"][vis], ref["opacity"][vis], rtol=2e-6, atol=1e-7)
         np.testing.assert_allclose(sp["color"][vis], ref["color"][vis], rtol=2e-5, atol=4e-6)
-        np.testing.assert_allclose(sp["depth"][vis], ref["depth"][vis], rtol=2e-6, atol=2e-6)
-        np.testing.assert_allclose(sp["normal"][vis], ref["normal"][vis], rtol=0, atol=5e-6)
+        np.testing.assert_allclose(sp["depth"][vis], ref["depth"][vis], rtol=2e-6, atol=2e-6 + 6e-7 * S)
+        # Gram-Schmidt loses accuracy as the raw tangents approach parallel: error ~ eps / sin(angle between them)
+        a, b = np.asarray(sc["tan_u"], dtype=np.float64)[vis], np.asarray(sc["tan_v"], dtype=np.float64)[vis]
+        sin = np.linalg.norm(np.cross(a, b), axis=1) / (np.linalg.norm(a, axis=1) * np.linalg.norm(b, axis=1))
+        n_err = np.abs(sp["normal"][vis] - ref["normal"][vis]).max(axis=1)
+        assert (n_err <= 2e-6 / sin).all(), float((n_err * sin).max())
     return tie, vis
 
 
@@ -121,7 +132,7 @@ def case(request):
 
 
 def test_a_preprocess(case):
-    _check_preprocess(case["sp"], case["ref"], case["cam"], max_tie=0.02)
+    _check_preprocess(case["sp"], case["ref"], case["cam"], case["sc"], max_tie=0.02)
     assert (case["sp"]["radius"] > 0).sum() > 0.3 * case["n"]
 
 
@@ -235,7 +246,7 @@ def test_e_full_size_view():
     sp = view.preprocess(scene)
     sc64 = to_f64(sc)
     ref = oracle.preprocess2d(sc64, cam)
-    tie, vis = _check_preprocess(sp, ref, cam)
+    tie, vis = _check_preprocess(sp, ref, cam, sc)
     lists = oracle.bin_sort(sp["mean2d"].astype(np.float64), sp["radius"], sp["depth"], W, H)
     assert lists["P"] <= cap
     got = view.render_fwd([0.0, 0.0, 0.0])
