@@ -29,6 +29,10 @@ FWD_FLOPS_PER_EXAMINED = 12.0    # 2 sub, 8 for the quadratic form, exp, opacity
 FWD_FLOPS_PER_BLENDED = 9.0      # 1-alpha, T', w, 3 fma
 BWD_FLOPS_PER_EXAMINED = 12.0    # alpha recomputed
 BWD_FLOPS_PER_BLENDED = 53.0     # 44 for the per-pair gradient terms + 9 lane-sum adds
+# surfels: 2 sub, 12 for h_u and h_v, 9 for the cross product, reciprocal, 2 for (u, v), 4 + 3 for the two exponents,
+# max, opacity add, exp2
+FWD2D_FLOPS_PER_EXAMINED = 36.0
+BWD2D_FLOPS_PER_BLENDED = 55.0   # 40 for the per-pair gradient terms and moments + 15 lane-sum adds
 
 
 def profiled_traffic(kernel):
@@ -58,7 +62,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="mid", choices=["mid", "tiny"])
+    ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "surfels"],
+                    help="mid = the headline configuration; surfels = the same with 2D Gaussian disks (not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -83,45 +88,60 @@ def main():
         sc = synth.scene_mid(args.seed)
         cam = synth.cameras_sphere()[0]
         wl = "mid: 1M Gaussians, SH degree 3, 1920x1080, camera 0 of 16 on a radius-15 sphere"
+    elif args.workload == "surfels":
+        sc = synth.scene_surfels(args.seed)
+        cam = synth.cameras_sphere()[0]
+        wl = "surfels: 1M 2D Gaussian disks, SH degree 3, 1920x1080, camera 0 of 16 on a radius-15 sphere"
     else:
         sc = synth.scene_tiny(args.seed)
         cam = synth.camera_tiny()
         wl = "tiny: 4096 Gaussians, SH degree 0, 128x128"
+    surfels = args.workload == "surfels"
     n = int(sc["mean"].shape[0])
     W, H = cam["width"], cam["height"]
     bg = [0.0, 0.0, 0.0]
-    scene = B.Scene.from_numpy(sc)
-    splats = B.Splats.empty(n)
-    g_splats = B.SplatGrads.empty(n)
+    if surfels:
+        scene = B.Scene2D.from_numpy(sc)
+        splats = B.Splats2D.empty(n)
+        g_splats = B.SplatGrads2D.empty(n)
+        alloc_ws, f_pre, f_fwd, f_bwd, f_stats = (B.alloc_workspace2d, B.pbdr2d_preprocess, B.pbdr2d_render_fwd,
+                                                  B.pbdr2d_render_bwd, B.pbdr2d_render_stats)
+    else:
+        scene = B.Scene.from_numpy(sc)
+        splats = B.Splats.empty(n)
+        g_splats = B.SplatGrads.empty(n)
+        alloc_ws, f_pre, f_fwd, f_bwd, f_stats = (B.alloc_workspace, B.pbdr_preprocess, B.pbdr_render_fwd,
+                                                  B.pbdr_render_bwd, B.pbdr_render_stats)
     grads = scene.zeros_like()
+    grad_tensors = [v for v in vars(grads).values() if isinstance(v, torch.Tensor)]
     image = torch.empty((3, H, W), device="cuda")
     final_T = torch.empty((H, W), device="cuda")
     last_idx = torch.empty((H, W), dtype=torch.int32, device="cuda")
 
     # ---- size the pair capacity from one untimed pass
     cap = max(16 * n, 1 << 16)
-    ws = B.alloc_workspace(n, W, H, cap)
-    B.pbdr_preprocess(scene, cam, splats)
-    B.pbdr_bin_sort(splats, cam, cap, ws)
+    ws = alloc_ws(n, W, H, cap)
+    f_pre(scene, cam, splats)
+    f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
     P, over = B.pbdr_query_lists(ws, n, W, H, cap)
     assert not over
     del ws
     cap = int(P * 1.25) + 4096
-    ws = B.alloc_workspace(n, W, H, cap)
-    B.pbdr_render_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
+    ws = alloc_ws(n, W, H, cap)
+    f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
     torch.cuda.synchronize()
     target = torch.from_numpy(np.ascontiguousarray(synth.target_image(args.seed, W, H).transpose(2, 0, 1))).cuda()
     dL = (torch.sign(image - target) / float(3 * W * H)).contiguous()
     n_vis = int((splats.radius > 0).sum().item())
-    examined, blended = B.pbdr_render_stats(cam, n, cap, ws)
+    examined, blended = f_stats(cam, n, cap, ws)
     sum_last = int(last_idx.to(torch.int64).sum().item())
 
     def step():
-        for t in (grads.mean, grads.log_scale, grads.quat, grads.logit, grads.sh):
+        for t in grad_tensors:
             t.zero_()
-        B.pbdr_preprocess(scene, cam, splats)
-        B.pbdr_render_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
-        B.pbdr_render_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
+        f_pre(scene, cam, splats)
+        f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
+        f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
 
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
@@ -182,6 +202,12 @@ def main():
         "k_composite_fwd": FWD_FLOPS_PER_EXAMINED * examined + FWD_FLOPS_PER_BLENDED * blended,
         "k_composite_bwd": BWD_FLOPS_PER_EXAMINED * sum_last + BWD_FLOPS_PER_BLENDED * blended,
     }
+    if surfels:   # same kernel ids, the surfel kernels behind them; only the compositing figures are stated
+        hbm_bytes = {}
+        alu_flops = {
+            "k_composite_fwd": FWD2D_FLOPS_PER_EXAMINED * examined + FWD_FLOPS_PER_BLENDED * blended,
+            "k_composite_bwd": FWD2D_FLOPS_PER_EXAMINED * sum_last + BWD2D_FLOPS_PER_BLENDED * blended,
+        }
     if dominant in alu_flops:
         ach = alu_flops[dominant] / (dom_avg_ms * 1e-3) / 1e12
         roofline = dict(kernel=dominant, bound="alu", achieved=ach, peak=ALU_PEAK_TFLOPS, unit="TFLOP/s",
@@ -210,24 +236,28 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         sp = splats.to_numpy()
+        keys = ("mean2d", "T", "opacity", "color") if surfels else ("mean2d", "conic", "opacity", "color")
+        o_pre, o_fwd, o_bwd, o_pbwd = ((oracle.preprocess2d, oracle.render_fwd2d, oracle.render_bwd2d, oracle.preprocess_bwd2d)
+                                       if surfels else
+                                       (oracle.preprocess, oracle.render_fwd, oracle.render_bwd, oracle.preprocess_bwd))
         t_c0 = time.perf_counter()
-        o_sp = oracle.preprocess(sc, cam)
-        st = {k: o_sp[k].astype(np.float32).astype(np.float64) for k in ("mean2d", "conic", "opacity", "color")}
+        o_sp = o_pre(sc, cam)
+        st = {k: o_sp[k].astype(np.float32).astype(np.float64) for k in keys}
         st["radius"] = o_sp["radius"]
         lists = oracle.bin_sort(st["mean2d"], st["radius"], o_sp["depth"].astype(np.float32), W, H)
-        o_f = oracle.render_fwd(st, lists, W, H, bg)
+        o_f = o_fwd(st, lists, W, H, bg)
         G = dL.permute(1, 2, 0).contiguous().cpu().numpy().astype(np.float64)
-        o_b = oracle.render_bwd(st, lists, W, H, bg, G)
-        oracle.preprocess_bwd(sc, cam, o_b)
+        o_b = o_bwd(st, lists, W, H, bg, G)
+        o_pbwd(sc, cam, o_b)
         t_c1 = time.perf_counter()
         cpu = dict(value=1.0 / (t_c1 - t_c0), unit="views/s", cores=oracle.num_threads(), kind="oracle",
                    sample="1 full view (forward + backward) of the same workload, fp64, OpenMP",
                    seconds=t_c1 - t_c0)
         # staged parity at full size: oracle compositing fed with the GPU's own fp32 splats
-        stg = {k: sp[k].astype(np.float64) for k in ("mean2d", "conic", "opacity", "color")}
+        stg = {k: sp[k].astype(np.float64) for k in keys}
         stg["radius"] = sp["radius"]
         lg = oracle.bin_sort(stg["mean2d"], stg["radius"], sp["depth"], W, H)
-        rf = oracle.render_fwd(stg, lg, W, H, bg)
+        rf = o_fwd(stg, lg, W, H, bg)
         got = image.permute(1, 2, 0).cpu().numpy()
         ok = rf["fragile"] == 0
         parity = dict(max_abs_image_err=float(np.abs(got - rf["image"])[ok].max()), fragile_pixels=int((~ok).sum()),
@@ -236,7 +266,8 @@ def main():
                       last_idx_mismatch=int((last_idx.cpu().numpy().astype(np.uint32) != rf["last_idx"])[ok].sum()))
 
     out = {
-        "metric": "fwd+bwd views/sec at 1080p, 1M Gaussians" if args.workload == "mid" else "fwd+bwd views/sec",
+        "metric": {"mid": "fwd+bwd views/sec at 1080p, 1M Gaussians",
+                   "surfels": "fwd+bwd views/sec at 1080p, 1M 2D Gaussian surfels"}.get(args.workload, "fwd+bwd views/sec"),
         "value": views_per_s, "unit": "views/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",

@@ -175,7 +175,7 @@ int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, 
  *     image)); a disk whose 3-sigma rim reaches the camera plane is culled; depth = camera-space z of the centre;
  *   - normal = R (t_u x t_v), turned to face the camera (an output; carries no gradient).
  * Workspaces are laid out differently from the 3D calls: size them with pbdr2d_workspace_bytes and inspect them with
- * pbdr2d_lists_view. pbdr_query_lists does not apply; read num_dup through pbdr2d_lists_view. */
+ * pbdr2d_lists_view. pbdr_query_lists serves both kinds of workspace (the pair count sits at the same place). */
 typedef struct pbdr2d_scene {
     int32_t n;
     int32_t sh_degree;
@@ -244,6 +244,10 @@ int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, con
 int pbdr2d_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
                       uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
                       const uint32_t** ranges, const uint32_t** num_dup);
+
+/* As pbdr_render_stats, for a workspace used by pbdr2d_render_fwd. */
+int pbdr2d_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
 
 /* Optional per-kernel timing for benchmarks, with HIP events recorded on the stream each kernel is launched on.
  * kernel_mask: bit i enables kernel id i (ids 0 .. pbdr_profile_kernel_count()-1, names from

@@ -27,7 +27,7 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr_version", "pbdr_render_stats", "pbdr_profile_begin", "pbdr_profile_collect", "pbdr_profile_reset",
            "pbdr_profile_end", "pbdr_profile_kernel_name", "pbdr_profile_kernel_count",
            "pbdr2d_workspace_bytes", "pbdr2d_preprocess", "pbdr2d_render_fwd", "pbdr2d_render_bwd", "pbdr2d_preprocess_bwd",
-           "pbdr2d_lists_view")
+           "pbdr2d_lists_view", "pbdr2d_render_stats")
 
 _f = C.POINTER(C.c_float)
 
@@ -310,11 +310,11 @@ def pbdr_lists_view(ws, n, width, height, dup_capacity, _entry="pbdr_lists_view"
                 ranges=view(ranges, 2 * tiles, np.uint32).reshape(tiles, 2))
 
 
-def pbdr_render_stats(cam: dict, n, dup_capacity, ws, stream=None):
+def pbdr_render_stats(cam: dict, n, dup_capacity, ws, stream=None, _entry="pbdr_render_stats"):
     """(examined, blended) pair counts of a forward pass over the lists now in the workspace. Synchronises."""
     c = camera_struct(cam)
     counters = torch.zeros(2, dtype=torch.int64, device=ws.device)
-    _check(lib().pbdr_render_stats(C.byref(c), C.c_int32(n), C.c_uint64(dup_capacity), _dev(counters),
+    _check(getattr(lib(), _entry)(C.byref(c), C.c_int32(n), C.c_uint64(dup_capacity), _dev(counters),
                                    C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
     torch.cuda.synchronize()
     out = counters.cpu().numpy()
@@ -498,3 +498,7 @@ def pbdr2d_preprocess_bwd(scene: Scene2D, cam: dict, splats: Splats2D, g_splats:
 
 def pbdr2d_lists_view(ws, n, width, height, dup_capacity):
     return pbdr_lists_view(ws, n, width, height, dup_capacity, _entry="pbdr2d_lists_view")
+
+
+def pbdr2d_render_stats(cam: dict, n, dup_capacity, ws, stream=None):
+    return pbdr_render_stats(cam, n, dup_capacity, ws, stream, _entry="pbdr2d_render_stats")

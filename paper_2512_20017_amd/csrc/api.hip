@@ -330,6 +330,16 @@ int pbdr2d_render_fwd(const pbdr2d_splats* splats, const pbdr_camera* cam, const
     return hip_result(launch_composite2d_fwd(c, L, (char*)workspace, bg, image, final_T, last_idx, (hipStream_t)hip_stream));
 }
 
+int pbdr2d_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
+                        size_t workspace_bytes, void* hip_stream)
+{
+    if (!check_camera(cam) || !aligned16(counters)) return PBDR_ERR_INVALID_ARG;
+    Layout L;
+    const int st = workspace_ok(workspace, workspace_bytes, n, cam->width, cam->height, dup_capacity, &L, kVariant2D);
+    if (st != PBDR_OK) return st;
+    return hip_result(launch_render_stats2d(to_dev(cam), L, (char*)workspace, counters, (hipStream_t)hip_stream));
+}
+
 int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr2d_splats* splats,
                           const pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* hip_stream)
 {

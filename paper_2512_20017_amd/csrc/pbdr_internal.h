@@ -132,6 +132,8 @@ hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, 
 hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3], const float* final_T,
                                   const uint32_t* last_idx, const float* dL_dimage, const Splat2DGradDev& g2, hipStream_t s);
 
+hipError_t launch_render_stats2d(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
+
 // final location of the sorted pair lists (depends on the parity of the tile pass count)
 inline size_t sorted_tkeys_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tkey1 : L.off_tkey0; }
 inline size_t sorted_vals_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tval1 : L.off_tval0; }

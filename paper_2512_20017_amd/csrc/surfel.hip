@@ -646,6 +646,57 @@ __global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restr
     g2.color[i] = sSum[wave][12][lane]; g2.color[N + i] = sSum[wave][13][lane]; g2.color[2 * N + i] = sSum[wave][14][lane];
 }
 
+// Measurement aid: the forward walk with counters instead of colours (see the 3D variant).
+__global__ __launch_bounds__(256) void k_render_stats2d(CamDev cam, const uint32_t* __restrict__ ranges,
+                                                        const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
+                                                        unsigned long long* __restrict__ counters)
+{
+    __shared__ float4 sR[4][kBatch];
+    __shared__ unsigned long long sCnt[2];
+    const TileCtx c = tile_ctx(cam, ranges);
+    const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
+    float T = 1.f;
+    uint32_t examined = 0, blended = 0;
+    bool done = !c.inside;
+    if (threadIdx.x < 2) sCnt[threadIdx.x] = 0ull;
+    for (uint32_t base = c.start; base < c.end; base += kBatch) {
+        if (__syncthreads_count(!done) == 0) break;
+        const uint32_t idx = base + threadIdx.x;
+        if (idx < c.end) {
+            const float4* rec = reinterpret_cast<const float4*>(packed + vals[idx]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) sR[k][threadIdx.x] = rec[k];
+        }
+        __syncthreads();
+        const int cnt = (int)min((uint32_t)kBatch, c.end - base);
+        if (!done) {
+            for (int j = 0; j < cnt; ++j) {
+                const float4 a = sR[0][j], b = sR[1][j], cc = sR[2][j], r3 = sR[3][j];
+                Pair2D E;
+                eval_pair2d(a, b, cc, make_float4(r3.x, r3.z, r3.w, 0.f), fx, fy, E);
+                ++examined;
+                if (E.p2 == 0.f) continue;
+                const float alpha = fminf(kAlphaMax, b.w * __builtin_amdgcn_exp2f(fmaxf(E.e1, E.e2)));
+                if (!(alpha >= kAlphaMin)) continue;
+                const float Tn = T * (1.f - alpha);
+                if (Tn < kTStop) { done = true; break; }
+                T = Tn;
+                ++blended;
+            }
+        }
+    }
+    __syncthreads();
+    atomicAdd(&sCnt[0], (unsigned long long)examined);
+    atomicAdd(&sCnt[1], (unsigned long long)blended);
+    __syncthreads();
+    if (threadIdx.x < 2 && sCnt[threadIdx.x]) atomicAdd(&counters[threadIdx.x], sCnt[threadIdx.x]);
+}
+
+__global__ __launch_bounds__(64) void k_zero_counters2d(unsigned long long* __restrict__ counters)
+{
+    if (threadIdx.x < 2) counters[threadIdx.x] = 0ull;
+}
+
 __global__ __launch_bounds__(256) void k_zero_partial2d(float4* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap)
 {
     const size_t count = (size_t)4 * min(status[kStNumDup], cap);
@@ -729,6 +780,16 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
                            reinterpret_cast<const uint32_t*>(ws + L.off_dval0), reinterpret_cast<const uint32_t*>(ws + L.off_offsets),
                            partial, L.cap, g2);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_render_stats2d(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s)
+{
+    ProfScope prof(kKStats, s);
+    hipLaunchKernelGGL(k_zero_counters2d, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned long long*>(counters));
+    hipLaunchKernelGGL(k_render_stats2d, dim3((unsigned)L.tiles), dim3(256), 0, s, cam,
+                       reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
+                       reinterpret_cast<const Packed2D*>(ws + L.off_packed), reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
 }
 
