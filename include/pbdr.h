@@ -93,7 +93,8 @@ typedef struct pbdr_splats {
     float* depth;    /* [n] camera-space z */
 } pbdr_splats;
 
-/* Gradient w.r.t. the differentiable part of pbdr_splats (what Alg. 1 line 19-20 sends back). Overwritten. */
+/* Gradient w.r.t. the differentiable part of pbdr_splats (what Alg. 1 line 19-20 sends back). Overwritten for every
+ * point with radius > 0; entries of culled points are left untouched (nothing reads them). */
 typedef struct pbdr_splat_grads {
     int32_t n;
     float* mean2d;  /* [2][n] */
@@ -210,7 +211,7 @@ typedef struct pbdr2d_splats {
     float* normal;        /* [3][n] camera-space unit normal facing the camera */
 } pbdr2d_splats;
 
-typedef struct pbdr2d_splat_grads { /* overwritten */
+typedef struct pbdr2d_splat_grads { /* overwritten for points with radius > 0, untouched for culled points */
     int32_t n;
     float* mean2d;        /* [2][n] through the low-pass term only */
     float* ray_transform; /* [9][n] */

@@ -31,6 +31,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->off_status = take(kStWords * sizeof(uint32_t));
     L->off_packed = take((size_t)n * L->record_bytes);
     L->off_depth_bits = take((size_t)n * sizeof(uint32_t));
+    L->off_vis_block = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
     L->off_touched = take((size_t)n * sizeof(uint32_t));
     L->off_offsets = take(((size_t)n + 1) * sizeof(uint32_t));
     L->off_slot_base = take((size_t)n * sizeof(uint32_t));

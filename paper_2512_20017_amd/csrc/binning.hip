@@ -22,43 +22,60 @@ __device__ __forceinline__ void rect_of(const CamDev& cam, float mx, float my, i
     y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
 }
 
-// One thread per point: number of tiles its square touches, the 48-byte raster record, and the (depth bits, index)
-// pair for the depth sort (culled points get the largest key and sort to the end).
-__global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, uint32_t* __restrict__ tiles_touched,
-                                                    Packed* __restrict__ packed, uint32_t* __restrict__ dkey,
-                                                    uint32_t* __restrict__ dval, uint32_t* __restrict__ depth_bits)
+// Number of visible points (radius > 0) in each block of 256 consecutive points.
+__global__ __launch_bounds__(256) void k_count_visible(int n, const int32_t* __restrict__ radius, uint32_t* __restrict__ vis_block)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= sp.n) return;
+    const int c = __syncthreads_count(i < n && radius[i] > 0);
+    if (threadIdx.x == 0) vis_block[blockIdx.x] = (uint32_t)c;
+}
+
+// One thread per point. A visible point gets: the number of tiles its square touches, the 48-byte raster record,
+// and a slot in the compact list of visible points, kept in ascending point order (the block's first slot comes from
+// the scanned block counts, the slot within the block from ballots), where its (depth bits, index) pair for the depth
+// sort goes. Culled points cost one 4-byte read and nothing downstream.
+__global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ vis_block,
+                                                    uint32_t* __restrict__ tiles_touched, Packed* __restrict__ packed,
+                                                    uint32_t* __restrict__ dkey, uint32_t* __restrict__ dval,
+                                                    uint32_t* __restrict__ depth_bits)
+{
+    __shared__ uint32_t sWave[4];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)sp.n;
-    const int r = sp.radius[i];
-    uint32_t cnt = 0, key = 0xFFFFFFFFu;
-    if (r > 0) {
-        const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-        int x0, y0, x1, y1;
-        rect_of(cam, mx, my, r, x0, y0, x1, y1);
-        cnt = (uint32_t)((x1 - x0) * (y1 - y0));
-        float4* dst = reinterpret_cast<float4*>(packed + i);
-        dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
-        dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
-        const float depth = sp.depth[i];
-        key = __float_as_uint(depth);
-        dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), depth, 0.f);
-    }
-    tiles_touched[i] = cnt;
-    dkey[i] = key;
-    dval[i] = (uint32_t)i;
+    const int r = (i < sp.n) ? sp.radius[i] : 0;
+    const bool vis = r > 0;
+    const unsigned long long m = __ballot(vis);
+    if (lane == 0) sWave[wave] = (uint32_t)__popcll(m);
+    __syncthreads();
+    if (!vis) return;
+    uint32_t slot = vis_block[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+#pragma unroll
+    for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
+    const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
+    int x0, y0, x1, y1;
+    rect_of(cam, mx, my, r, x0, y0, x1, y1);
+    float4* dst = reinterpret_cast<float4*>(packed + i);
+    dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
+    dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
+    const float depth = sp.depth[i];
+    const uint32_t key = __float_as_uint(depth);
+    dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), depth, 0.f);
+    tiles_touched[i] = (uint32_t)((x1 - x0) * (y1 - y0));
+    dkey[slot] = key;
+    dval[slot] = (uint32_t)i;
     depth_bits[i] = key;
 }
 
-// tile counts in depth order (rank r holds the point order[r]); slot n is the sentinel that makes the scan leave
-// the pair total at offsets[n]
-__global__ __launch_bounds__(256) void k_rank_counts(int n, const uint32_t* __restrict__ order,
+// tile counts in depth order (rank r < m holds the visible point order[r]); ranks m..n get 0, and slot n is the
+// sentinel that makes the scan leave the pair total at offsets[n]
+__global__ __launch_bounds__(256) void k_rank_counts(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
                                                      const uint32_t* __restrict__ tiles_touched, uint32_t* __restrict__ counts)
 {
     const int r = blockIdx.x * 256 + threadIdx.x;
     if (r > n) return;
-    counts[r] = (r < n) ? tiles_touched[order[r]] : 0u;
+    const uint32_t m = min(status[kStNumVis], (uint32_t)n);
+    counts[r] = ((uint32_t)r < m) ? tiles_touched[order[r]] : 0u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -198,7 +215,8 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int x0 = 0, y0 = 0, x1 = 0, y1 = 0;
     uint32_t at = 0, id = 0;
-    if (r < sp.n) {
+    const uint32_t m = min(status[kStNumVis], (uint32_t)sp.n);     // ranks below m hold visible points
+    if ((uint32_t)r < m) {
         at = offsets[r];
         id = order[r];
         const int rad = sp.radius[id];
@@ -296,12 +314,27 @@ hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
     return hipGetLastError();
 }
 
+// visible points per block of 256, scanned in place; leaves the visible count in the status words
+hipError_t launch_count_visible(int n, const int32_t* radius, const Layout& L, char* ws, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    uint32_t* vis_block = reinterpret_cast<uint32_t*>(ws + L.off_vis_block);
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    ProfScope prof(kKCountPack, s);
+    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, n, radius, vis_block);
+    hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, vis_block, nb, status + kStNumVis);
+    return hipGetLastError();
+}
+
 hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     if (sp.n == 0) return hipSuccess;
+    hipError_t e = launch_count_visible(sp.n, sp.radius, L, ws, s);
+    if (e != hipSuccess) return e;
     ProfScope prof(kKCountPack, s);
     hipLaunchKernelGGL(k_count_pack, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
-                       reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed*>(ws + L.off_packed),
+                       reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed*>(ws + L.off_packed),
                        reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
                        reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
     return hipGetLastError();
@@ -325,13 +358,13 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
     uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
     uint32_t* tile_hist = reinterpret_cast<uint32_t*>(ws + L.off_tile_hist);
     const unsigned nblk = (unsigned)((sp.n + 255) / 256);
-    // depth digits: sort the n splats by their 32 depth bits (4 passes, result back in buffer 0)
-    hipError_t e = launch_radix_sort32(dk, dv, nullptr, (uint32_t)sp.n, 4, totals, tile_hist, s);
+    // depth digits: sort the visible splats by their 32 depth bits (4 passes, result back in buffer 0)
+    hipError_t e = launch_radix_sort32(dk, dv, status + kStNumVis, (uint32_t)sp.n, 4, totals, tile_hist, s);
     if (e != hipSuccess) return e;
     const uint32_t* order = dv[0];
     {
         ProfScope prof(kKCountPack, s);
-        hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp.n, order, touched, offsets);
+        hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp.n, status, order, touched, offsets);
     }
     e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n + 1u, part, status + kStNumDup, s);
     if (e != hipSuccess) return e;

@@ -273,18 +273,21 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
 }
 
 // Adds up, per point, the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list, 48 bytes
-// each) into dL/d(splat state); points without pairs get zeros. A wavefront owns 64 consecutive depth ranks, whose
+// each) into dL/d(splat state) of the visible points; culled points are not written. A wavefront owns 64 consecutive depth ranks, whose
 // pairs form one contiguous range: its lanes stream that range 64 pairs at a time (coalesced), find each pair's
 // point by binary search over the 64 range ends in LDS, run a segmented inclusive scan over the 64 pairs (pairs of
 // one point are adjacent lanes), and the last lane of each segment adds the segment total into that point's LDS
 // accumulator - one adder per point and step, so no conflicts.
-__global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const uint32_t* __restrict__ order,
+__global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const uint32_t* __restrict__ status,
+                                                            const uint32_t* __restrict__ order,
                                                             const uint32_t* __restrict__ offsets,
                                                             const float4* __restrict__ partial, uint32_t cap,
                                                             SplatGradDev g2)
 {
     __shared__ uint32_t sEnd[4][64];
     __shared__ float sSum[4][9][64];
+    const uint32_t m = min(status[kStNumVis], (uint32_t)n);     // ranks below m hold the visible points
+    if ((uint32_t)(blockIdx.x * 256) >= m) return;
     const int r = blockIdx.x * 256 + threadIdx.x;     // rank in depth order; its pairs are [offsets[r], offsets[r+1])
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)n;
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const uint32_
         __builtin_amdgcn_wave_barrier();
     }
     __builtin_amdgcn_wave_barrier();
-    if (r >= n) return;
+    if ((uint32_t)r >= m) return;
     const uint32_t i = order[r];
     g2.mean2d[i] = sSum[wave][0][lane]; g2.mean2d[N + i] = sSum[wave][1][lane];
     g2.conic[i] = sSum[wave][2][lane]; g2.conic[N + i] = sSum[wave][3][lane]; g2.conic[2 * N + i] = sSum[wave][4][lane];
@@ -442,7 +445,7 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
-        hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, order, offsets,
+        hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status, order, offsets,
                            partial, L.cap, g2);
     }
     return hipGetLastError();

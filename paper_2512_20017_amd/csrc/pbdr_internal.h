@@ -72,7 +72,7 @@ struct Splat2DGradDev {
 };
 
 // Status words at the head of the workspace.
-enum { kStNumDup = 0, kStOverflow = 1, kStWords = 64 };
+enum { kStNumDup = 0, kStOverflow = 1, kStNumVis = 2, kStWords = 64 };   // pair count, overflow flag, visible-point count
 
 // Workspace layout for (n, W, H, capacity). All offsets are multiples of 256 bytes.
 enum Variant { kVariant3D = 0, kVariant2D = 1 };   // 3D Gaussians / 2D Gaussian surfels
@@ -84,7 +84,7 @@ struct Layout {
     int partial_vec4;         // float4s of partial gradient sums per pair: 3 (3D) or 4 (2D)
     uint32_t cap;
     int tile_bits, tile_passes;   // key bits / 8-bit passes spent on the tile id
-    size_t off_status, off_packed, off_depth_bits, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
+    size_t off_status, off_packed, off_depth_bits, off_vis_block, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
         off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
         off_partial, off_keys64, total;
 };
@@ -103,6 +103,7 @@ struct BinInput {
     const int32_t* radius;    // [n]
 };
 hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s);                       // zero status / totals / ranges
+hipError_t launch_count_visible(int n, const int32_t* radius, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_finish(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);

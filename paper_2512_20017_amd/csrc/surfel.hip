@@ -277,35 +277,42 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     }
 }
 
-// One thread per point: tile count, 64-byte raster record with centred rows, (depth bits, index) for the depth sort.
-__global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam, uint32_t* __restrict__ tiles_touched,
-                                                      Packed2D* __restrict__ packed, uint32_t* __restrict__ dkey,
-                                                      uint32_t* __restrict__ dval, uint32_t* __restrict__ depth_bits)
+// One thread per point; a visible point gets its tile count, the 64-byte raster record with centred rows, and its
+// (depth bits, index) pair in the compact, index-ordered list of visible points (see the 3D variant).
+__global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam, const uint32_t* __restrict__ vis_block,
+                                                      uint32_t* __restrict__ tiles_touched, Packed2D* __restrict__ packed,
+                                                      uint32_t* __restrict__ dkey, uint32_t* __restrict__ dval,
+                                                      uint32_t* __restrict__ depth_bits)
 {
+    __shared__ uint32_t sWave[4];
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= sp.n) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)sp.n;
-    const int r = sp.radius[i];
-    uint32_t cnt = 0, key = 0xFFFFFFFFu;
-    if (r > 0) {
-        const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-        const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
-        const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
-        const int x0 = min(max((ix - r) >> 4, 0), cam.TX), y0 = min(max((iy - r) >> 4, 0), cam.TY);
-        const int x1 = min(max((ix + r + 15) >> 4, 0), cam.TX), y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
-        cnt = (uint32_t)((x1 - x0) * (y1 - y0));
-        const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
-        float4* dst = reinterpret_cast<float4*>(packed + i);
-        dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
-                             fmaf(-my, t2y, sp.T[4 * N + i]));
-        dst[1] = make_float4(t2x, t2y, t2z, sp.opacity[i]);
-        dst[2] = make_float4(mx, my, sp.color[i], sp.color[N + i]);
-        dst[3] = make_float4(sp.color[2 * N + i], __int_as_float(r), fmaf(-mx, t2z, sp.T[2 * N + i]), fmaf(-my, t2z, sp.T[5 * N + i]));
-        key = __float_as_uint(sp.depth[i]);
-    }
-    tiles_touched[i] = cnt;
-    dkey[i] = key;
-    dval[i] = (uint32_t)i;
+    const int r = (i < sp.n) ? sp.radius[i] : 0;
+    const bool vis = r > 0;
+    const unsigned long long m = __ballot(vis);
+    if (lane == 0) sWave[wave] = (uint32_t)__popcll(m);
+    __syncthreads();
+    if (!vis) return;
+    uint32_t slot = vis_block[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+#pragma unroll
+    for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
+    const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
+    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
+    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
+    const int x0 = min(max((ix - r) >> 4, 0), cam.TX), y0 = min(max((iy - r) >> 4, 0), cam.TY);
+    const int x1 = min(max((ix + r + 15) >> 4, 0), cam.TX), y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+    const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
+    float4* dst = reinterpret_cast<float4*>(packed + i);
+    dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
+                         fmaf(-my, t2y, sp.T[4 * N + i]));
+    dst[1] = make_float4(t2x, t2y, t2z, sp.opacity[i]);
+    dst[2] = make_float4(mx, my, sp.color[i], sp.color[N + i]);
+    dst[3] = make_float4(sp.color[2 * N + i], __int_as_float(r), fmaf(-mx, t2z, sp.T[2 * N + i]), fmaf(-my, t2z, sp.T[5 * N + i]));
+    const uint32_t key = __float_as_uint(sp.depth[i]);
+    tiles_touched[i] = (uint32_t)((x1 - x0) * (y1 - y0));
+    dkey[slot] = key;
+    dval[slot] = (uint32_t)i;
     depth_bits[i] = key;
 }
 
@@ -585,9 +592,12 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
 }
 
 // Per point (in depth-rank order): add up the 64-byte partial records of its pairs; see the 3D variant for the scheme.
-__global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restrict__ order, const uint32_t* __restrict__ offsets,
-                                                  const float4* __restrict__ partial, uint32_t cap, Splat2DGradDev g2)
+__global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
+                                                  const uint32_t* __restrict__ offsets, const float4* __restrict__ partial,
+                                                  uint32_t cap, Splat2DGradDev g2)
 {
+    const uint32_t m = min(status[kStNumVis], (uint32_t)n);     // ranks below m hold the visible points
+    if ((uint32_t)(blockIdx.x * 256) >= m) return;
     __shared__ uint32_t sEnd[4][64];
     __shared__ float sSum[4][16][64];
     const int r = blockIdx.x * 256 + threadIdx.x;
@@ -637,7 +647,7 @@ __global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restr
         __builtin_amdgcn_wave_barrier();
     }
     __builtin_amdgcn_wave_barrier();
-    if (r >= n) return;
+    if ((uint32_t)r >= m) return;
     const uint32_t i = order[r];
 #pragma unroll
     for (int k = 0; k < 9; ++k) g2.T[(size_t)k * N + i] = sSum[wave][k][lane];
@@ -739,9 +749,11 @@ hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Lay
     hipError_t e = launch_bin_begin(L, ws, s);
     if (e != hipSuccess) return e;
     if (sp.n > 0) {
+        e = launch_count_visible(sp.n, sp.radius, L, ws, s);
+        if (e != hipSuccess) return e;
         ProfScope prof(kKCountPack, s);
         hipLaunchKernelGGL(k_count_pack2d, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
-                           reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed2D*>(ws + L.off_packed),
+                           reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed2D*>(ws + L.off_packed),
                            reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
                            reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
     }
@@ -776,7 +788,7 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
-        hipLaunchKernelGGL(k_gather2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
+        hipLaunchKernelGGL(k_gather2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status,
                            reinterpret_cast<const uint32_t*>(ws + L.off_dval0), reinterpret_cast<const uint32_t*>(ws + L.off_offsets),
                            partial, L.cap, g2);
     }
