@@ -47,6 +47,8 @@ __device__ __forceinline__ float qform_min_rect(float A, float B, float C, float
     return best;
 }
 
+constexpr int kAccStride = 9;    // floats between the LDS accumulators of consecutive splats of a batch (odd)
+
 // LDS image of one staged batch
 struct Stage {
     float4 a[kBatch];                 // mx, my, A = log2e/2 * qa, B = log2e * qb
@@ -175,7 +177,8 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                                                        float4* __restrict__ partial)
 {
     __shared__ Stage S;
-    __shared__ float sAcc[12 * kBatch];  // [value][splat of the batch]; blue has one slot per pixel row group (8..11)
+    // [splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are conflict-free)
+    __shared__ float sAcc[kAccStride * kBatch];
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -200,8 +203,13 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     // which of the eight butterfly values this lane ends up holding (see row_sum8)
     const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
                r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
-    const int acc_slot = ((r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0)) * kBatch;
-    const int blue_slot = (8 + (lane >> 4)) * kBatch;
+    // One LDS add per visit, by nine lanes. After the row butterfly lanes 0-7 of each row carry the eight values
+    // and lane 15 the row's blue sum; the four rows are then added lane by lane into row 3. (LDS float adds cost
+    // LDS time per active lane and per address clash, and the LDS pipe, not the VALU, bounded this kernel when all
+    // four rows issued their own adds.)
+    const bool blue_lane = (lane & 15) == 15;
+    const bool add_lane = lane >= 48 && (blue_lane || (lane & 8) == 0);
+    const int acc_slot = blue_lane ? 8 : (r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0);
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
@@ -209,7 +217,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         uint32_t id; float4 raw, geo;
         stage_batch(S, c, vals, packed, c.start + boff, cnt, id, raw, geo);
 #pragma unroll
-        for (int k = 0; k < 12; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
+        for (int k = 0; k < kAccStride; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {            // else nothing of this batch was blended by this wavefront (uniform per wave)
             for (int k = 3; k >= 0; --k) {
@@ -240,8 +248,8 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                     const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
                     const float part = row_sum8(v8, r1, r2, r3);
                     const float blue = row_sum_to_lane15(w * g2c);
-                    if ((lane & 8) == 0) atomicAdd(&sAcc[acc_slot + j], part);      // 4 rows x 8 values
-                    if ((lane & 15) == 15) atomicAdd(&sAcc[blue_slot + j], blue);      // one address per row group
+                    const float tot = rows_sum_to_row3(blue_lane ? blue : part);
+                    if (add_lane) atomicAdd(&sAcc[kAccStride * j + acc_slot], tot);
                 }
             }
         }
@@ -258,14 +266,14 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
             }
             const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
-                const float s0 = sAcc[2 * kBatch + threadIdx.x], s1 = sAcc[3 * kBatch + threadIdx.x], s2 = sAcc[4 * kBatch + threadIdx.x];
+                const float* acc = sAcc + kAccStride * threadIdx.x;
+                const float s0 = acc[2], s1 = acc[3], s2 = acc[4];
                 float4* dst = partial + (size_t)3 * u;
                 dst[0] = make_float4(-(raw.x * s1 + raw.y * s2), -(raw.z * s2 + raw.y * s1),          // d mean2d
-                                     0.5f * sAcc[5 * kBatch + threadIdx.x], sAcc[6 * kBatch + threadIdx.x]);              // d conic a, b
-                dst[1] = make_float4(0.5f * sAcc[7 * kBatch + threadIdx.x], raw.w > 0.f ? -s0 / raw.w : 0.f,    // d conic c, d opacity
-                                     sAcc[0 * kBatch + threadIdx.x], sAcc[1 * kBatch + threadIdx.x]);                     // d red, d green
-                dst[2] = make_float4((sAcc[8 * kBatch + threadIdx.x] + sAcc[9 * kBatch + threadIdx.x]) +
-                                     (sAcc[10 * kBatch + threadIdx.x] + sAcc[11 * kBatch + threadIdx.x]), 0.f, 0.f, 0.f);                           // d blue
+                                     0.5f * acc[5], acc[6]);                                         // d conic a, b
+                dst[1] = make_float4(0.5f * acc[7], raw.w > 0.f ? -s0 / raw.w : 0.f,                   // d conic c, d opacity
+                                     acc[0], acc[1]);                                                 // d red, d green
+                dst[2] = make_float4(acc[8], 0.f, 0.f, 0.f);                                          // d blue
             }
         }
         __syncthreads();   // sAcc and the stage are rewritten by the next batch

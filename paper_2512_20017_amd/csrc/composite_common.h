@@ -84,6 +84,18 @@ __device__ __forceinline__ float row_sum8(const float v[8], bool r1, bool r2, bo
     return d;
 }
 
+// Adds the four rows of 16 lanes of a wavefront lane by lane; the total is valid in lanes 48..63 only.
+// v_permlane16_swap / v_permlane32_swap (gfx950) exchange odd rows (the upper half) of their first operand with even
+// rows (the lower half) of the second: with both operands equal, rows 1 and 3 receive rows 0 and 2, then the upper
+// half receives the lower half. Only the first result of each builtin is used.
+__device__ __forceinline__ float rows_sum_to_row3(float v)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    const float s = v + __builtin_bit_cast(float, __builtin_amdgcn_permlane16_swap(u, u, false, false)[0]);
+    const unsigned us = __builtin_bit_cast(unsigned, s);
+    return s + __builtin_bit_cast(float, __builtin_amdgcn_permlane32_swap(us, us, false, false)[0]);
+}
+
 // inclusive row scan by shifts: lane 15 of each row ends up with the row sum
 __device__ __forceinline__ float row_sum_to_lane15(float v)
 {

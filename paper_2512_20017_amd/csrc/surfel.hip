@@ -316,6 +316,8 @@ __global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam
     depth_bits[i] = key;
 }
 
+constexpr int kAccStride2D = 17;   // floats between the LDS accumulators of consecutive surfels of a batch (odd)
+
 // LDS image of one staged batch of surfels
 struct Stage2D {
     float4 a[kBatch];   // t0x, t0y, t1x, t1y
@@ -467,7 +469,9 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                                                          float4* __restrict__ partial)
 {
     __shared__ Stage2D S;
-    __shared__ float sAcc[16 * kBatch];
+    // [splat of the batch][value], 17 floats apart (odd: the adds of one visit and the per-thread reads at the end of
+    // a batch spread over the LDS banks)
+    __shared__ float sAcc[kAccStride2D * kBatch];
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -491,7 +495,7 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
     const int tile_x = c.tx0 / kTile, tile_y = c.ty0 / kTile;
     const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
                r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
-    const int acc_slot = ((r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0)) * kBatch;
+    const int acc_slot = ((lane & 8) ? 8 : 0) + (r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0);
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;
@@ -499,7 +503,7 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
         uint32_t id; float4 q0, q1, q2, q3;
         stage_batch2d(S, c, vals, packed, c.start + boff, cnt, id, q0, q1, q2, q3);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
+        for (int k = 0; k < kAccStride2D; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {
             for (int k = 3; k >= 0; --k) {
@@ -541,10 +545,10 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                     const float vb[8] = {E.dy * dp2, w * g0, w * g1, w * g2c, d_o, dmx, dmy, 0.f};
                     const float pa = row_sum8(va, r1, r2, r3);
                     const float pb = row_sum8(vb, r1, r2, r3);
-                    if ((lane & 8) == 0) {
-                        atomicAdd(&sAcc[acc_slot + j], pa);
-                        atomicAdd(&sAcc[8 * kBatch + acc_slot + j], pb);
-                    }
+                    // lanes 0-7 of a row keep the first eight sums, lanes 8-15 (mirror copies) take the second eight;
+                    // the four rows are added lane by lane into row 3, whose 16 lanes issue the one LDS add
+                    const float tot = rows_sum_to_row3((lane & 8) ? pb : pa);
+                    if (lane >= 48) atomicAdd(&sAcc[kAccStride2D * j + acc_slot], tot);
                 }
             }
         }
@@ -560,10 +564,10 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
             }
             const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
-                const int t = threadIdx.x;
-                const float s0[3] = {sAcc[0 * kBatch + t], sAcc[1 * kBatch + t], sAcc[2 * kBatch + t]};
-                const float sx[3] = {sAcc[3 * kBatch + t], sAcc[4 * kBatch + t], sAcc[5 * kBatch + t]};
-                const float sy[3] = {sAcc[6 * kBatch + t], sAcc[7 * kBatch + t], sAcc[8 * kBatch + t]};
+                const float* acc = sAcc + kAccStride2D * threadIdx.x;
+                const float s0[3] = {acc[0], acc[1], acc[2]};
+                const float sx[3] = {acc[3], acc[4], acc[5]};
+                const float sy[3] = {acc[6], acc[7], acc[8]};
                 const float t0[3] = {q0.x, q0.y, q3.z}, t1[3] = {q0.z, q0.w, q3.w}, t2[3] = {q1.x, q1.y, q1.z};
                 const float mx = q2.x, my = q2.y;
                 float dhu[3], dhv[3], ex[3];
@@ -582,9 +586,9 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                 float4* dst = partial + (size_t)4 * u;
                 dst[0] = make_float4(-dhu[0], -dhu[1], -dhu[2], -dhv[0]);                                     // dT0, dT1.x
                 dst[1] = make_float4(-dhv[1], -dhv[2], mx * dhu[0] + my * dhv[0] + ex[0], mx * dhu[1] + my * dhv[1] + ex[1]);
-                dst[2] = make_float4(mx * dhu[2] + my * dhv[2] + ex[2], sAcc[13 * kBatch + t], sAcc[14 * kBatch + t],   // dT2.z, d mean2d
-                                     sAcc[12 * kBatch + t]);                                                          // d opacity
-                dst[3] = make_float4(sAcc[9 * kBatch + t], sAcc[10 * kBatch + t], sAcc[11 * kBatch + t], 0.f);        // d colour
+                dst[2] = make_float4(mx * dhu[2] + my * dhv[2] + ex[2], acc[13], acc[14],   // dT2.z, d mean2d
+                                     acc[12]);                                                          // d opacity
+                dst[3] = make_float4(acc[9], acc[10], acc[11], 0.f);        // d colour
             }
         }
         __syncthreads();
