@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "surfels", "large"],
                     help="mid = the headline configuration; surfels = the same with 2D Gaussian disks (not the headline metric)")
+    ap.add_argument("--group-size", type=int, default=0,
+                    help="if > 0: preprocess with point-group frustum culling at this group size (3D Gaussian workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -116,6 +118,15 @@ def main():
         g_splats = B.SplatGrads.empty(n)
         alloc_ws, f_pre, f_fwd, f_bwd, f_stats = (B.alloc_workspace, B.pbdr_preprocess, B.pbdr_render_fwd,
                                                   B.pbdr_render_bwd, B.pbdr_render_stats)
+    kept_groups = None
+    if args.group_size > 0 and not surfels:
+        ng = B.pbdr_group_count(n, args.group_size)
+        g_bounds = torch.empty((7, max(ng, 1)), dtype=torch.float32, device="cuda")
+        g_keep = torch.empty(max(ng, 1), dtype=torch.uint8, device="cuda")
+        B.pbdr_group_bounds(scene, args.group_size, g_bounds)       # once per cloud, outside the step
+
+        def f_pre(scene_, cam_, splats_):
+            B.pbdr_preprocess_grouped(scene_, cam_, args.group_size, g_bounds, g_keep, splats_)
     grads = scene.zeros_like()
     grad_tensors = [v for v in vars(grads).values() if isinstance(v, torch.Tensor)]
     image = torch.empty((3, H, W), device="cuda")
@@ -137,6 +148,8 @@ def main():
     target = torch.from_numpy(np.ascontiguousarray(synth.target_image(args.seed, W, H).transpose(2, 0, 1))).cuda()
     dL = (torch.sign(image - target) / float(3 * W * H)).contiguous()
     n_vis = int((splats.radius > 0).sum().item())
+    if args.group_size > 0 and not surfels:
+        kept_groups = float(g_keep[:ng].float().mean().item())
     examined, blended = f_stats(cam, n, cap, ws)
     sum_last = int(last_idx.to(torch.int64).sum().item())
 
@@ -278,7 +291,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl, "n_gaussians": n, "width": W, "height": H, "sh_degree": scene.sh_degree,
                    "visible": n_vis, "tile_pairs": int(P), "pairs_examined_fwd": int(examined),
-                   "pairs_examined_bwd": sum_last, "pairs_blended": int(blended), "seed": args.seed},
+                   "pairs_examined_bwd": sum_last, "pairs_blended": int(blended), "seed": args.seed,
+                   "group_size": args.group_size, "groups_kept": kept_groups},
         "mpixel_per_s": views_per_s * W * H / 1e6,
         "roofline": roofline,
         "cpu_baseline": cpu,

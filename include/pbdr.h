@@ -111,6 +111,22 @@ int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_
  * cull, covariance projection, conic, extent, off-screen and radius_clip cull, SH colour. Writes all of `out`. */
 int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream);
 
+/* Point-group frustum culling (App. D.1; the groups are those of Sec. 4.2.1: runs of group_size consecutive points of
+ * a cloud stored in Z-order, so that a group is spatially compact). group_size: a multiple of 256 in [256, 2^20].
+ * pbdr_group_count returns ceil(n / group_size), or a negative status.
+ * pbdr_group_bounds: once per cloud (again whenever means or scales have changed): bounds [7][n_groups] (device) =
+ * planes min x, min y, min z, max x, max y, max z of the group's centres and the group's largest scale.
+ * pbdr_preprocess_grouped = pbdr_preprocess preceded by one test per group: keep [n_groups] (device, uint8, written)
+ * is 0 for a group whose box shows that each of its points would be culled for this view (behind the near plane,
+ * beyond the far plane, or off screen by more than any member's extent); such groups cost 4 bytes written per point
+ * and no parameter read. The paper tests the eight box corners against the frustum; here the test is conservative
+ * with respect to the per-point culls, so `out` is identical to what pbdr_preprocess writes (radius == 0 for every
+ * point of a dropped group). */
+int pbdr_group_count(int32_t n, int32_t group_size);
+int pbdr_group_bounds(const pbdr_scene* scene, int32_t group_size, float* bounds, void* hip_stream);
+int pbdr_preprocess_grouped(const pbdr_scene* scene, const pbdr_camera* cam, int32_t group_size, const float* bounds,
+                            uint8_t* keep, pbdr_splats* out, void* hip_stream);
+
 /* The sorting half of image_render (Sec. 2.1: "sorts these view-dependent splats by their distance to the camera
  * plane"): per-splat tile count, radix sort in the order of the key (tile << 32 | depth bits) - depth digits on the
  * splats, device prefix sum, duplication, tile digits on the pairs - and per-tile ranges.

@@ -311,3 +311,44 @@ def backward2d(scene: dict, cam: dict, bg, fwd: dict, dL_dimage) -> dict:
     g = preprocess_bwd2d(scene, cam, d_sp)
     g["d_splats"] = d_sp
     return g
+
+
+# ---------------------------------------------------------------------------------------- point-group frustum culling
+def _scene_arrays(scene):
+    n = int(scene["mean"].shape[0]); deg = int(scene["sh_degree"]); K = (deg + 1) ** 2
+    return (n, deg, K, _f64(scene["mean"], (n, 3)), _f64(scene["log_scale"], (n, 3)), _f64(scene["quat"], (n, 4)),
+            _f64(scene["logit"], (n,)), _f64(scene["sh"], (n, K, 3)))
+
+
+def group_bounds(scene: dict, group_size: int) -> np.ndarray:
+    """[ceil(n/G), 7] = (min xyz, max xyz, largest scale) per group of G consecutive points."""
+    n, deg, K, mean, ls, q, lo, sh = _scene_arrays(scene)
+    ng = (n + group_size - 1) // group_size
+    out = np.zeros((max(ng, 1), 7))
+    lib().orc_group_bounds(C.c_int(n), C.c_int(group_size), _p(mean, C.c_double), _p(ls, C.c_double), _p(out, C.c_double))
+    return out[:ng]
+
+
+def group_cull(bounds: np.ndarray, cam: dict, tau: float = 1e-4) -> dict:
+    b = np.ascontiguousarray(bounds, dtype=np.float64)
+    ng = int(b.shape[0])
+    out = dict(keep=np.zeros(max(ng, 1), dtype=np.uint8), near_tie=np.zeros(max(ng, 1), dtype=np.uint8))
+    c = camera(cam)
+    lib().orc_group_cull(C.c_int(ng), _p(b, C.c_double), C.byref(c), _p(out["keep"], C.c_uint8),
+                         _p(out["near_tie"], C.c_uint8), C.c_double(tau))
+    return {k: v[:ng] for k, v in out.items()}
+
+
+def preprocess_grouped(scene: dict, cam: dict, group_size: int) -> dict:
+    n, deg, K, mean, ls, q, lo, sh = _scene_arrays(scene)
+    ng = (n + group_size - 1) // group_size
+    out = dict(mean2d=np.zeros((n, 2)), conic=np.zeros((n, 3)), opacity=np.zeros(n), color=np.zeros((n, 3)),
+               radius=np.zeros(n, dtype=np.int32), depth=np.zeros(n), keep=np.zeros(max(ng, 1), dtype=np.uint8))
+    c = camera(cam)
+    lib().orc_preprocess_grouped(C.c_int(n), C.c_int(deg), C.c_int(group_size), _p(mean, C.c_double), _p(ls, C.c_double),
+                                 _p(q, C.c_double), _p(lo, C.c_double), _p(sh, C.c_double), C.byref(c),
+                                 _p(out["mean2d"], C.c_double), _p(out["conic"], C.c_double), _p(out["opacity"], C.c_double),
+                                 _p(out["color"], C.c_double), _p(out["radius"], C.c_int32), _p(out["depth"], C.c_double),
+                                 _p(out["keep"], C.c_uint8))
+    out["keep"] = out["keep"][:ng]
+    return out

@@ -700,6 +700,132 @@ int orc_num_threads(void)
 }
 
 /* ====================================================================================== */
+/* Point-group frustum culling (App. D.1; Sec. 4.2.1 for the Z-order and the group size).   */
+/*                                                                                        */
+/* Points stored in Z-order are cut into groups of G consecutive points; each group keeps   */
+/* an axis-aligned box around its centres and its largest scale. Per view, a whole group   */
+/* is dropped when its box shows that every point in it would be culled anyway, so the      */
+/* per-point work is spent on in-frustum groups only.                                      */
+/* Reading: the paper tests the 8 box corners against the frustum; a box can meet the       */
+/* frustum with no corner inside, and splats have an extent, so that test can drop          */
+/* visible points. Here the test is made conservative with respect to THIS file's           */
+/* per-point culls, so that grouped and ungrouped preprocessing give identical results.     */
+/* With p = R c + t a corner in camera space, a group is dropped if                         */
+/*   every corner has p_z < near, or every corner has p_z > far, or                         */
+/*   for one of the four image sides every corner lies beyond that side's plane pushed      */
+/*   out by the largest extent a member can have. A member at depth z has extent            */
+/*     ceil(3 sqrt(lambda)) <= k1 s_max / z + k0,                                           */
+/*     k1 = 3 sqrt(F2),  F2 = fx^2 (1 + lim_x^2) + fy^2 (1 + lim_y^2)  (Frobenius norm of    */
+/*     the clamped Jacobian times z),  k0 = 3 sqrt(0.3 + sqrt(0.1)) + 1  (blur, the floor    */
+/*     under the root of the eigenvalue formula, the ceil),                                 */
+/*   and its tile rectangle is empty on the right if mean2d_x - extent >= 16 TX + 1, on      */
+/*   the left if mean2d_x + extent < 0 (same in y). Multiplied by z > 0 these are linear     */
+/*   in p, e.g. right:  fx p_x - (16 TX + 1 + k0 - cx) p_z - k1 s_max >= 0,                  */
+/*   so they hold throughout the box if they hold at its corners; members behind the        */
+/*   camera are culled by the near test whatever the planes say.                            */
+/* bounds[g] = (min x, min y, min z, max x, max y, max z, s_max).                          */
+/* ====================================================================================== */
+void orc_group_bounds(int n, int group_size, const double* mean, const double* log_scale, double* bounds)
+{
+    const int ng = (n + group_size - 1) / group_size;
+    int g;
+#pragma omp parallel for schedule(static)
+    for (g = 0; g < ng; ++g) {
+        const int lo = g * group_size, hi = (lo + group_size < n) ? lo + group_size : n;
+        double* b = bounds + 7 * g;
+        int i, k;
+        for (k = 0; k < 3; ++k) { b[k] = mean[3 * lo + k]; b[3 + k] = mean[3 * lo + k]; }
+        b[6] = 0.0;
+        for (i = lo; i < hi; ++i) {
+            for (k = 0; k < 3; ++k) {
+                const double v = mean[3 * i + k], sc = exp(log_scale[3 * i + k]);
+                if (v < b[k]) b[k] = v;
+                if (v > b[3 + k]) b[3 + k] = v;
+                if (sc > b[6]) b[6] = sc;
+            }
+        }
+    }
+}
+
+/* The rule. Every comparison is moved by eps times the sum of the magnitudes of its terms: towards keeping for
+ * eps > 0, towards dropping for eps < 0 (used to flag decisions that rounding could flip). */
+static int group_keep(const double* b, const orc_camera* cam, double eps)
+{
+    const int TX = (cam->width + ORC_TILE - 1) / ORC_TILE, TY = (cam->height + ORC_TILE - 1) / ORC_TILE;
+    const double lim_x = ORC_GUARD * (0.5 * cam->width) / cam->fx, lim_y = ORC_GUARD * (0.5 * cam->height) / cam->fy;
+    const double F2 = cam->fx * cam->fx * (1.0 + lim_x * lim_x) + cam->fy * cam->fy * (1.0 + lim_y * lim_y);
+    const double k1 = 3.0 * sqrt(F2), k0 = 3.0 * sqrt(ORC_BLUR + sqrt(ORC_EIG_FLOOR)) + 1.0;
+    /* side planes as (coefficient of p_x, of p_y, of p_z): right, left, bottom, top */
+    const double side[4][3] = {{cam->fx, 0.0, -(16.0 * TX + 1.0 + k0 - cam->cx)}, {-cam->fx, 0.0, -(cam->cx + k0)},
+                               {0.0, cam->fy, -(16.0 * TY + 1.0 + k0 - cam->cy)}, {0.0, -cam->fy, -(cam->cy + k0)}};
+    double p[8][3], mag[8][3];
+    int k, i, j, behind = 1, beyond = 1;
+    for (k = 0; k < 8; ++k) {
+        const double c[3] = {b[(k & 1) ? 3 : 0], b[(k & 2) ? 4 : 1], b[(k & 4) ? 5 : 2]};
+        for (i = 0; i < 3; ++i) {
+            p[k][i] = cam->t[i]; mag[k][i] = fabs(cam->t[i]);
+            for (j = 0; j < 3; ++j) { p[k][i] += cam->R[3 * i + j] * c[j]; mag[k][i] += fabs(cam->R[3 * i + j] * c[j]); }
+        }
+        if (!(p[k][2] + eps * mag[k][2] < cam->near_plane)) behind = 0;
+        if (!(p[k][2] - eps * mag[k][2] > cam->far_plane)) beyond = 0;
+    }
+    if (behind || beyond) return 0;
+    for (i = 0; i < 4; ++i) {
+        int outside = 1;
+        for (k = 0; k < 8 && outside; ++k) {
+            const double f = side[i][0] * p[k][0] + side[i][1] * p[k][1] + side[i][2] * p[k][2] - k1 * b[6];
+            const double m = fabs(side[i][0]) * mag[k][0] + fabs(side[i][1]) * mag[k][1] + fabs(side[i][2]) * mag[k][2] + k1 * b[6];
+            if (!(f - eps * m > 0.0)) outside = 0;
+        }
+        if (outside) return 0;
+    }
+    return 1;
+}
+
+/* keep[g] = 0 if group g is dropped for this view. near_tie[g] (optional) = 1 if moving the thresholds by +-tau flips it. */
+void orc_group_cull(int n_groups, const double* bounds, const orc_camera* cam, uint8_t* keep, uint8_t* near_tie, double tau)
+{
+    int g;
+#pragma omp parallel for schedule(static)
+    for (g = 0; g < n_groups; ++g) {
+        keep[g] = (uint8_t)group_keep(bounds + 7 * g, cam, 0.0);
+        if (near_tie) near_tie[g] = (uint8_t)(group_keep(bounds + 7 * g, cam, tau) != group_keep(bounds + 7 * g, cam, -tau));
+    }
+}
+
+/* orc_preprocess restricted to the groups that survive orc_group_cull: the state of Table 3a, culled groups zeroed */
+void orc_preprocess_grouped(int n, int sh_degree, int group_size, const double* mean, const double* log_scale,
+                            const double* quat, const double* logit, const double* sh, const orc_camera* cam,
+                            double* mean2d, double* conic, double* opacity, double* color, int32_t* radius, double* depth,
+                            uint8_t* keep_out)
+{
+    const int K = (sh_degree + 1) * (sh_degree + 1);
+    const int ng = (n + group_size - 1) / group_size;
+    double* bounds = (double*)malloc((size_t)(ng > 0 ? ng : 1) * 7 * sizeof(double));
+    uint8_t* keep = (uint8_t*)malloc((size_t)(ng > 0 ? ng : 1));
+    int i;
+    orc_group_bounds(n, group_size, mean, log_scale, bounds);
+    orc_group_cull(ng, bounds, cam, keep, NULL, 0.0);
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < n; ++i) {
+        orc_proj P;
+        int k;
+        mean2d[2 * i] = mean2d[2 * i + 1] = 0.0;
+        conic[3 * i] = conic[3 * i + 1] = conic[3 * i + 2] = 0.0;
+        opacity[i] = 0.0; depth[i] = 0.0; radius[i] = 0;
+        color[3 * i] = color[3 * i + 1] = color[3 * i + 2] = 0.0;
+        if (!keep[i / group_size]) continue;
+        project_one(sh_degree, mean + 3 * i, log_scale + 3 * i, quat + 4 * i, logit[i], sh + (size_t)3 * K * i, cam, &P);
+        if (!P.visible) continue;
+        mean2d[2 * i] = P.mean2d[0]; mean2d[2 * i + 1] = P.mean2d[1];
+        for (k = 0; k < 3; ++k) { conic[3 * i + k] = P.conic[k]; color[3 * i + k] = P.rgb[k]; }
+        opacity[i] = P.o; depth[i] = P.p[2]; radius[i] = P.radius;
+    }
+    if (keep_out) memcpy(keep_out, keep, (size_t)ng);
+    free(bounds); free(keep);
+}
+
+/* ====================================================================================== */
 /* 2D Gaussian surfels (the paper's 2DGS configuration: Sec. 5 "Applications", Table 3b,   */
 /* App. B: "2DGS models [the projection] more accurately").                                */
 /*                                                                                        */

@@ -27,7 +27,7 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr_version", "pbdr_render_stats", "pbdr_profile_begin", "pbdr_profile_collect", "pbdr_profile_reset",
            "pbdr_profile_end", "pbdr_profile_kernel_name", "pbdr_profile_kernel_count",
            "pbdr2d_workspace_bytes", "pbdr2d_preprocess", "pbdr2d_render_fwd", "pbdr2d_render_bwd", "pbdr2d_preprocess_bwd",
-           "pbdr2d_lists_view", "pbdr2d_render_stats")
+           "pbdr2d_lists_view", "pbdr2d_render_stats", "pbdr_group_count", "pbdr_group_bounds", "pbdr_preprocess_grouped")
 
 _f = C.POINTER(C.c_float)
 
@@ -245,6 +245,27 @@ def alloc_workspace(n, width, height, dup_capacity, device="cuda") -> torch.Tens
 def pbdr_preprocess(scene: Scene, cam: dict, out: Splats, stream=None) -> None:
     s, c, o = scene.struct(), camera_struct(cam), out.struct()
     _check(lib().pbdr_preprocess(C.byref(s), C.byref(c), C.byref(o), _stream(stream)))
+
+
+def pbdr_group_count(n: int, group_size: int) -> int:
+    ng = int(lib().pbdr_group_count(C.c_int32(n), C.c_int32(group_size)))
+    if ng < 0:
+        raise PbdrError(ng)
+    return ng
+
+
+def pbdr_group_bounds(scene: Scene, group_size: int, bounds: torch.Tensor, stream=None) -> None:
+    """bounds: float32 [7, n_groups] on the device."""
+    s = scene.struct()
+    _check(lib().pbdr_group_bounds(C.byref(s), C.c_int32(group_size), _dev(bounds), _stream(stream)))
+
+
+def pbdr_preprocess_grouped(scene: Scene, cam: dict, group_size: int, bounds: torch.Tensor, keep: torch.Tensor,
+                            out: Splats, stream=None) -> None:
+    """keep: uint8 [n_groups] on the device, written."""
+    s, c, o = scene.struct(), camera_struct(cam), out.struct()
+    _check(lib().pbdr_preprocess_grouped(C.byref(s), C.byref(c), C.c_int32(group_size), _dev(bounds), _dev(keep),
+                                         C.byref(o), _stream(stream)))
 
 
 def pbdr_bin_sort(splats: Splats, cam: dict, dup_capacity: int, ws: torch.Tensor, stream=None) -> None:

@@ -199,7 +199,39 @@ int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_
 int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream)
 {
     if (!check_scene(scene) || !check_camera(cam) || !check_splats(out) || out->n != scene->n) return PBDR_ERR_INVALID_ARG;
-    return hip_result(launch_preprocess(dev(scene), to_dev(cam), dev(out), (hipStream_t)hip_stream));
+    return hip_result(launch_preprocess(dev(scene), to_dev(cam), dev(out), nullptr, 0, (hipStream_t)hip_stream));
+}
+
+static bool check_group_size(int32_t group_size)
+{
+    return group_size >= 256 && group_size <= (1 << 20) && (group_size % 256) == 0;
+}
+
+int pbdr_group_count(int32_t n, int32_t group_size)
+{
+    if (n < 0 || !check_group_size(group_size)) return PBDR_ERR_INVALID_ARG;
+    return (int)(((int64_t)n + group_size - 1) / group_size);
+}
+
+int pbdr_group_bounds(const pbdr_scene* scene, int32_t group_size, float* bounds, void* hip_stream)
+{
+    if (!check_scene(scene) || !check_group_size(group_size)) return PBDR_ERR_INVALID_ARG;
+    if (scene->n > 0 && !aligned16(bounds)) return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_group_bounds(dev(scene), group_size, bounds, (hipStream_t)hip_stream));
+}
+
+int pbdr_preprocess_grouped(const pbdr_scene* scene, const pbdr_camera* cam, int32_t group_size, const float* bounds,
+                            uint8_t* keep, pbdr_splats* out, void* hip_stream)
+{
+    if (!check_scene(scene) || !check_camera(cam) || !check_splats(out) || out->n != scene->n || !check_group_size(group_size))
+        return PBDR_ERR_INVALID_ARG;
+    if (scene->n == 0) return PBDR_OK;
+    if (!aligned16(bounds) || !aligned16(keep)) return PBDR_ERR_INVALID_ARG;
+    const CamDev c = to_dev(cam);
+    const int ng = (int)(((int64_t)scene->n + group_size - 1) / group_size);
+    const hipError_t e = launch_group_cull(c, ng, bounds, keep, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_result(e);
+    return hip_result(launch_preprocess(dev(scene), c, dev(out), keep, group_size, (hipStream_t)hip_stream));
 }
 
 int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t dup_capacity, void* workspace,

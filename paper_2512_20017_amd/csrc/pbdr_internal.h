@@ -93,7 +93,11 @@ constexpr int kScanItems = 4096;   // elements per scan block
 bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L);
 
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
-hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, hipStream_t s);
+// keep == nullptr: every point is tested; else keep[point / group_size] == 0 skips the point (group_size % 256 == 0)
+hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, const uint8_t* keep,
+                             int group_size, hipStream_t s);
+hipError_t launch_group_bounds(const SceneDev& sc, int group_size, float* bounds, hipStream_t s);
+hipError_t launch_group_cull(const CamDev& cam, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
 hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
                                  const SceneGradDev& g, hipStream_t s);
 // what binning needs of a splat state, whatever the variant

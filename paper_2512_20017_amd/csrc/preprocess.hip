@@ -98,12 +98,16 @@ __device__ __forceinline__ void sh_basis(int deg, float x, float y, float z, flo
     Y[15] = -0.5900435899266435f * x * (xx - 3.f * yy);
 }
 
+// keep / blocks_per_group: optional point-group culling (App. D.1). keep[g] == 0 means every point of group g is
+// known to be culled for this view; the workgroup then only marks its 256 points culled and reads no parameter.
 template <int kDeg>
-__global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, SplatsDev out)
+__global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, SplatsDev out, const uint8_t* __restrict__ keep,
+                                                    int blocks_per_group)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
+    if (keep != nullptr && keep[blockIdx.x / blocks_per_group] == 0) { out.radius[i] = 0; return; }
     const size_t N = (size_t)n;
     const float m0 = sc.mean[i], m1 = sc.mean[N + i], m2 = sc.mean[2 * N + i];
     Proj P;
@@ -307,16 +311,18 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     }
 }
 
-hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, hipStream_t s)
+hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, const uint8_t* keep,
+                             int group_size, hipStream_t s)
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    const int bpg = keep ? group_size / 256 : 1;
     ProfScope prof(kKPreprocess, s);
     switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL(k_preprocess<0>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
-        case 1: hipLaunchKernelGGL(k_preprocess<1>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
-        case 2: hipLaunchKernelGGL(k_preprocess<2>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
-        default: hipLaunchKernelGGL(k_preprocess<3>, dim3(blocks), dim3(256), 0, s, sc, cam, out); break;
+        case 0: hipLaunchKernelGGL(k_preprocess<0>, dim3(blocks), dim3(256), 0, s, sc, cam, out, keep, bpg); break;
+        case 1: hipLaunchKernelGGL(k_preprocess<1>, dim3(blocks), dim3(256), 0, s, sc, cam, out, keep, bpg); break;
+        case 2: hipLaunchKernelGGL(k_preprocess<2>, dim3(blocks), dim3(256), 0, s, sc, cam, out, keep, bpg); break;
+        default: hipLaunchKernelGGL(k_preprocess<3>, dim3(blocks), dim3(256), 0, s, sc, cam, out, keep, bpg); break;
     }
     return hipGetLastError();
 }
