@@ -127,6 +127,31 @@ int pbdr_group_bounds(const pbdr_scene* scene, int32_t group_size, float* bounds
 int pbdr_preprocess_grouped(const pbdr_scene* scene, const pbdr_camera* cam, int32_t group_size, const float* bounds,
                             uint8_t* keep, pbdr_splats* out, void* hip_stream);
 
+/* Image patches (Sec. 4.2.2: the unit of rendering work is an H/p x W/p patch of an image, p = 2..8; App. D.2: the
+ * rendering kernels are restricted to the patch). A patch is the pixel rectangle [x0, x1) x [y0, y1) of the camera's
+ * image, any size and position inside it. The *_patch calls do what their whole-image namesakes do for those pixels
+ * only: tiles stay aligned to the image's own 16 x 16 grid and only tiles that meet the patch are listed, sorted and
+ * composited, so image / final_T / last_idx - here [3][h][w], [h][w], [h][w] with w = x1 - x0, h = y1 - y0 - hold
+ * exactly the values the whole-image render has at those pixels, and dL_dimage is [3][h][w]. pbdr_preprocess_patch
+ * additionally culls points whose tile rectangle misses the patch (radius = 0), which is what makes a patch cheaper
+ * than the image; the other fields of a visible point do not depend on the patch. The workspace is sized for the
+ * whole image (pbdr_workspace_bytes with the camera's width and height); pbdr_lists_view then shows tile ids
+ * relative to the patch's tile grid (its first tile is 0, row length = tiles across the patch). The three calls of
+ * one patch must be given the same patch. pbdr_preprocess_bwd serves patches unchanged. */
+typedef struct pbdr_patch {
+    int32_t x0, y0, x1, y1;
+} pbdr_patch;
+
+int pbdr_preprocess_patch(const pbdr_scene* scene, const pbdr_camera* cam, const pbdr_patch* patch, pbdr_splats* out,
+                          void* hip_stream);
+int pbdr_render_fwd_patch(const pbdr_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                          uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+int pbdr_render_bwd_patch(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam,
+                          const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                          const uint32_t* last_idx, const float* dL_dimage, pbdr_splat_grads* g_splats,
+                          pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* The sorting half of image_render (Sec. 2.1: "sorts these view-dependent splats by their distance to the camera
  * plane"): per-splat tile count, radix sort in the order of the key (tile << 32 | depth bits) - depth digits on the
  * splats, device prefix sum, duplication, tile digits on the pairs - and per-tile ranges.
@@ -256,6 +281,18 @@ int pbdr2d_render_bwd(const pbdr2d_scene* scene, const pbdr2d_splats* splats, co
 /* pts_splatting.backward alone for surfels; accumulates into grads. */
 int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr2d_splats* splats,
                           const pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* hip_stream);
+
+/* Image patches for surfels: as pbdr_preprocess_patch / pbdr_render_fwd_patch / pbdr_render_bwd_patch (App. D.2 restricts
+ * the kernels of every evaluated algorithm to a patch); workspace sized by pbdr2d_workspace_bytes for the whole image. */
+int pbdr2d_preprocess_patch(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr_patch* patch, pbdr2d_splats* out,
+                            void* hip_stream);
+int pbdr2d_render_fwd_patch(const pbdr2d_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                            uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                            size_t workspace_bytes, void* hip_stream);
+int pbdr2d_render_bwd_patch(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam,
+                            const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                            const uint32_t* last_idx, const float* dL_dimage, pbdr2d_splat_grads* g_splats,
+                            pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* As pbdr_lists_view, for a workspace used by pbdr2d_render_fwd. */
 int pbdr2d_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,

@@ -27,7 +27,9 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr_version", "pbdr_render_stats", "pbdr_profile_begin", "pbdr_profile_collect", "pbdr_profile_reset",
            "pbdr_profile_end", "pbdr_profile_kernel_name", "pbdr_profile_kernel_count",
            "pbdr2d_workspace_bytes", "pbdr2d_preprocess", "pbdr2d_render_fwd", "pbdr2d_render_bwd", "pbdr2d_preprocess_bwd",
-           "pbdr2d_lists_view", "pbdr2d_render_stats", "pbdr_group_count", "pbdr_group_bounds", "pbdr_preprocess_grouped")
+           "pbdr2d_lists_view", "pbdr2d_render_stats", "pbdr_group_count", "pbdr_group_bounds", "pbdr_preprocess_grouped",
+           "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
+           "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch")
 
 _f = C.POINTER(C.c_float)
 
@@ -41,6 +43,10 @@ class CCamera(C.Structure):
     _fields_ = [("width", C.c_int32), ("height", C.c_int32), ("fx", C.c_float), ("fy", C.c_float), ("cx", C.c_float),
                 ("cy", C.c_float), ("R", C.c_float * 9), ("t", C.c_float * 3), ("near_plane", C.c_float),
                 ("far_plane", C.c_float), ("radius_clip", C.c_float)]
+
+
+class CPatch(C.Structure):
+    _fields_ = [("x0", C.c_int32), ("y0", C.c_int32), ("x1", C.c_int32), ("y1", C.c_int32)]
 
 
 class CSplats(C.Structure):
@@ -296,6 +302,40 @@ def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, fin
                                  _stream(stream)))
 
 
+def _patch(patch) -> CPatch:
+    x0, y0, x1, y1 = (int(v) for v in patch)
+    return CPatch(x0, y0, x1, y1)
+
+
+def pbdr_preprocess_patch(scene: Scene, cam: dict, patch, out: Splats, stream=None) -> None:
+    """patch = (x0, y0, x1, y1): the pixel rectangle [x0, x1) x [y0, y1) of the camera's image."""
+    s, c, p, o = scene.struct(), camera_struct(cam), _patch(patch), out.struct()
+    _check(lib().pbdr_preprocess_patch(C.byref(s), C.byref(c), C.byref(p), C.byref(o), _stream(stream)))
+
+
+def pbdr_render_fwd_patch(splats: Splats, cam: dict, patch, bg, dup_capacity: int, image, final_T, last_idx, ws,
+                          stream=None) -> None:
+    s, c, p = splats.struct(), camera_struct(cam), _patch(patch)
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    _check(lib().pbdr_render_fwd_patch(C.byref(s), C.byref(c), C.byref(p), bgv, C.c_uint64(dup_capacity), _dev(image),
+                                       _dev(final_T), _dev(last_idx), C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
+                                       _stream(stream)))
+
+
+def pbdr_render_bwd_patch(scene, splats: Splats, cam: dict, patch, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
+                          g_splats: SplatGrads, grads, ws, stream=None) -> None:
+    sp, c, p, g2 = splats.struct(), camera_struct(cam), _patch(patch), g_splats.struct()
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    if scene is not None:
+        sc, g = scene.struct(), grads.struct()
+        psc, pg = C.byref(sc), C.byref(g)
+    else:
+        psc, pg = None, None
+    _check(lib().pbdr_render_bwd_patch(psc, C.byref(sp), C.byref(c), C.byref(p), bgv, C.c_uint64(dup_capacity),
+                                       _dev(final_T), _dev(last_idx), _dev(dL_dimage), C.byref(g2), pg,
+                                       C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
+
+
 def pbdr_preprocess_bwd(scene: Scene, cam: dict, splats: Splats, g_splats: SplatGrads, grads: Scene, stream=None) -> None:
     sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct()
     _check(lib().pbdr_preprocess_bwd(C.byref(sc), C.byref(c), C.byref(sp), C.byref(g2), C.byref(g), _stream(stream)))
@@ -510,6 +550,34 @@ def pbdr2d_render_bwd(scene, splats: Splats2D, cam: dict, bg, dup_capacity: int,
     _check(lib().pbdr2d_render_bwd(psc, C.byref(sp), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(final_T), _dev(last_idx),
                                    _dev(dL_dimage), C.byref(g2), pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
                                    _stream(stream)))
+
+
+def pbdr2d_preprocess_patch(scene: Scene2D, cam: dict, patch, out: Splats2D, stream=None) -> None:
+    s, c, p, o = scene.struct(), camera_struct(cam), _patch(patch), out.struct()
+    _check(lib().pbdr2d_preprocess_patch(C.byref(s), C.byref(c), C.byref(p), C.byref(o), _stream(stream)))
+
+
+def pbdr2d_render_fwd_patch(splats: Splats2D, cam: dict, patch, bg, dup_capacity: int, image, final_T, last_idx, ws,
+                            stream=None) -> None:
+    s, c, p = splats.struct(), camera_struct(cam), _patch(patch)
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    _check(lib().pbdr2d_render_fwd_patch(C.byref(s), C.byref(c), C.byref(p), bgv, C.c_uint64(dup_capacity), _dev(image),
+                                         _dev(final_T), _dev(last_idx), C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
+                                         _stream(stream)))
+
+
+def pbdr2d_render_bwd_patch(scene, splats: Splats2D, cam: dict, patch, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
+                            g_splats: SplatGrads2D, grads, ws, stream=None) -> None:
+    sp, c, p, g2 = splats.struct(), camera_struct(cam), _patch(patch), g_splats.struct()
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    if scene is not None:
+        sc, g = scene.struct(), grads.struct()
+        psc, pg = C.byref(sc), C.byref(g)
+    else:
+        psc, pg = None, None
+    _check(lib().pbdr2d_render_bwd_patch(psc, C.byref(sp), C.byref(c), C.byref(p), bgv, C.c_uint64(dup_capacity),
+                                         _dev(final_T), _dev(last_idx), _dev(dL_dimage), C.byref(g2), pg,
+                                         C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
 
 
 def pbdr2d_preprocess_bwd(scene: Scene2D, cam: dict, splats: Splats2D, g_splats: SplatGrads2D, grads: Scene2D, stream=None) -> None:

@@ -66,11 +66,21 @@ static bool check_camera(const pbdr_camera* cam)
     return std::isfinite(cam->cx) && std::isfinite(cam->cy);
 }
 
-static CamDev to_dev(const pbdr_camera* cam)
+static bool check_patch(const pbdr_camera* cam, const pbdr_patch* p)
+{
+    return p && p->x0 >= 0 && p->y0 >= 0 && p->x0 < p->x1 && p->y0 < p->y1 && p->x1 <= cam->width && p->y1 <= cam->height;
+}
+
+// patch == nullptr: the whole image
+static CamDev to_dev(const pbdr_camera* cam, const pbdr_patch* patch = nullptr)
 {
     CamDev c;
-    c.W = cam->width; c.H = cam->height;
-    c.TX = (cam->width + kTile - 1) / kTile; c.TY = (cam->height + kTile - 1) / kTile;
+    const pbdr_patch whole = {0, 0, cam->width, cam->height};
+    const pbdr_patch& r = patch ? *patch : whole;
+    c.W = r.x1 - r.x0; c.H = r.y1 - r.y0;
+    c.rx0 = r.x0; c.ry0 = r.y0; c.rx1 = r.x1; c.ry1 = r.y1;
+    c.otx = r.x0 / kTile; c.oty = r.y0 / kTile;
+    c.TX = (r.x1 + kTile - 1) / kTile - c.otx; c.TY = (r.y1 + kTile - 1) / kTile - c.oty;
     c.fx = cam->fx; c.fy = cam->fy; c.cx = cam->cx; c.cy = cam->cy;
     for (int i = 0; i < 9; ++i) c.R[i] = cam->R[i];
     for (int i = 0; i < 3; ++i) c.t[i] = cam->t[i];
@@ -196,10 +206,24 @@ int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_
     return PBDR_OK;
 }
 
-int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream)
+static int preprocess_impl(const pbdr_scene* scene, const pbdr_camera* cam, const pbdr_patch* patch, pbdr_splats* out,
+                           void* hip_stream)
 {
     if (!check_scene(scene) || !check_camera(cam) || !check_splats(out) || out->n != scene->n) return PBDR_ERR_INVALID_ARG;
-    return hip_result(launch_preprocess(dev(scene), to_dev(cam), dev(out), nullptr, 0, (hipStream_t)hip_stream));
+    if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_preprocess(dev(scene), to_dev(cam, patch), dev(out), nullptr, 0, (hipStream_t)hip_stream));
+}
+
+int pbdr_preprocess(const pbdr_scene* scene, const pbdr_camera* cam, pbdr_splats* out, void* hip_stream)
+{
+    return preprocess_impl(scene, cam, nullptr, out, hip_stream);
+}
+
+int pbdr_preprocess_patch(const pbdr_scene* scene, const pbdr_camera* cam, const pbdr_patch* patch, pbdr_splats* out,
+                          void* hip_stream)
+{
+    if (!patch) return PBDR_ERR_INVALID_ARG;
+    return preprocess_impl(scene, cam, patch, out, hip_stream);
 }
 
 static bool check_group_size(int32_t group_size)
@@ -244,16 +268,36 @@ int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t du
     return hip_result(launch_bin_sort(dev(splats), to_dev(cam), L, (char*)workspace, (hipStream_t)hip_stream));
 }
 
+static int render_fwd_impl(const pbdr_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                           uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
 int pbdr_render_fwd(const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
                     float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
                     void* hip_stream)
 {
+    return render_fwd_impl(splats, cam, nullptr, bg, dup_capacity, image, final_T, last_idx, workspace, workspace_bytes, hip_stream);
+}
+
+int pbdr_render_fwd_patch(const pbdr_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                          uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                          size_t workspace_bytes, void* hip_stream)
+{
+    if (!patch) return PBDR_ERR_INVALID_ARG;
+    return render_fwd_impl(splats, cam, patch, bg, dup_capacity, image, final_T, last_idx, workspace, workspace_bytes, hip_stream);
+}
+
+static int render_fwd_impl(const pbdr_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                           uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                           size_t workspace_bytes, void* hip_stream)
+{
     if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(image) || !aligned16(final_T) || !aligned16(last_idx))
         return PBDR_ERR_INVALID_ARG;
+    if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
     Layout L;
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
-    const CamDev c = to_dev(cam);
+    const CamDev c = to_dev(cam, patch);
     hipError_t e = launch_bin_sort(dev(splats), c, L, (char*)workspace, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_result(e);
     return hip_result(launch_composite_fwd(c, L, (char*)workspace, bg, image, final_T, last_idx, (hipStream_t)hip_stream));
@@ -269,20 +313,45 @@ int pbdr_preprocess_bwd(const pbdr_scene* scene, const pbdr_camera* cam, const p
                                             (hipStream_t)hip_stream));
 }
 
+static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam,
+                           const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                           const uint32_t* last_idx, const float* dL_dimage, pbdr_splat_grads* g_splats,
+                           pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3],
                     uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
                     pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes,
                     void* hip_stream)
 {
+    return render_bwd_impl(scene, splats, cam, nullptr, bg, dup_capacity, final_T, last_idx, dL_dimage, g_splats, grads,
+                           workspace, workspace_bytes, hip_stream);
+}
+
+int pbdr_render_bwd_patch(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam,
+                          const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                          const uint32_t* last_idx, const float* dL_dimage, pbdr_splat_grads* g_splats,
+                          pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!patch) return PBDR_ERR_INVALID_ARG;
+    return render_bwd_impl(scene, splats, cam, patch, bg, dup_capacity, final_T, last_idx, dL_dimage, g_splats, grads,
+                           workspace, workspace_bytes, hip_stream);
+}
+
+static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam,
+                           const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                           const uint32_t* last_idx, const float* dL_dimage, pbdr_splat_grads* g_splats,
+                           pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
     if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) ||
         !aligned16(dL_dimage) || !check_splat_grads(g_splats, splats->n))
         return PBDR_ERR_INVALID_ARG;
+    if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
     if ((scene == nullptr) != (grads == nullptr)) return PBDR_ERR_INVALID_ARG;
     if (scene && (!check_scene(scene) || scene->n != splats->n || !check_scene_grads(grads, scene))) return PBDR_ERR_INVALID_ARG;
     Layout L;
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
-    const CamDev c = to_dev(cam);
+    const CamDev c = to_dev(cam, patch);
     hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
                                         (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
@@ -342,22 +411,56 @@ int pbdr2d_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t du
     return PBDR_OK;
 }
 
-int pbdr2d_preprocess(const pbdr2d_scene* scene, const pbdr_camera* cam, pbdr2d_splats* out, void* hip_stream)
+static int preprocess2d_impl(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr_patch* patch, pbdr2d_splats* out,
+                             void* hip_stream)
 {
     if (!check_scene2d(scene) || !check_camera(cam) || !check_splats2d(out) || out->n != scene->n) return PBDR_ERR_INVALID_ARG;
-    return hip_result(launch_preprocess2d(dev(scene), to_dev(cam), dev(out), (hipStream_t)hip_stream));
+    if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_preprocess2d(dev(scene), to_dev(cam, patch), dev(out), (hipStream_t)hip_stream));
 }
+
+int pbdr2d_preprocess(const pbdr2d_scene* scene, const pbdr_camera* cam, pbdr2d_splats* out, void* hip_stream)
+{
+    return preprocess2d_impl(scene, cam, nullptr, out, hip_stream);
+}
+
+int pbdr2d_preprocess_patch(const pbdr2d_scene* scene, const pbdr_camera* cam, const pbdr_patch* patch, pbdr2d_splats* out,
+                            void* hip_stream)
+{
+    if (!patch) return PBDR_ERR_INVALID_ARG;
+    return preprocess2d_impl(scene, cam, patch, out, hip_stream);
+}
+
+static int render2d_fwd_impl(const pbdr2d_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                             uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
 
 int pbdr2d_render_fwd(const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
                       float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
                       void* hip_stream)
 {
+    return render2d_fwd_impl(splats, cam, nullptr, bg, dup_capacity, image, final_T, last_idx, workspace, workspace_bytes, hip_stream);
+}
+
+int pbdr2d_render_fwd_patch(const pbdr2d_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                            uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                            size_t workspace_bytes, void* hip_stream)
+{
+    if (!patch) return PBDR_ERR_INVALID_ARG;
+    return render2d_fwd_impl(splats, cam, patch, bg, dup_capacity, image, final_T, last_idx, workspace, workspace_bytes, hip_stream);
+}
+
+static int render2d_fwd_impl(const pbdr2d_splats* splats, const pbdr_camera* cam, const pbdr_patch* patch, const float bg[3],
+                             uint64_t dup_capacity, float* image, float* final_T, uint32_t* last_idx, void* workspace,
+                             size_t workspace_bytes, void* hip_stream)
+{
     if (!check_splats2d(splats) || !check_camera(cam) || !bg || !aligned16(image) || !aligned16(final_T) || !aligned16(last_idx))
         return PBDR_ERR_INVALID_ARG;
+    if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
     Layout L;
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L, kVariant2D);
     if (st != PBDR_OK) return st;
-    const CamDev c = to_dev(cam);
+    const CamDev c = to_dev(cam, patch);
     hipError_t e = launch_bin_sort2d(dev(splats), c, L, (char*)workspace, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_result(e);
     return hip_result(launch_composite2d_fwd(c, L, (char*)workspace, bg, image, final_T, last_idx, (hipStream_t)hip_stream));
@@ -382,20 +485,45 @@ int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, con
     return hip_result(launch_preprocess2d_bwd(dev(scene), to_dev(cam), dev(splats), dev(g_splats), dev(grads), (hipStream_t)hip_stream));
 }
 
+static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam,
+                             const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                             const uint32_t* last_idx, const float* dL_dimage, pbdr2d_splat_grads* g_splats,
+                             pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 int pbdr2d_render_bwd(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3],
                       uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
                       pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes,
                       void* hip_stream)
 {
+    return render2d_bwd_impl(scene, splats, cam, nullptr, bg, dup_capacity, final_T, last_idx, dL_dimage, g_splats, grads,
+                             workspace, workspace_bytes, hip_stream);
+}
+
+int pbdr2d_render_bwd_patch(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam,
+                            const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                            const uint32_t* last_idx, const float* dL_dimage, pbdr2d_splat_grads* g_splats,
+                            pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!patch) return PBDR_ERR_INVALID_ARG;
+    return render2d_bwd_impl(scene, splats, cam, patch, bg, dup_capacity, final_T, last_idx, dL_dimage, g_splats, grads,
+                             workspace, workspace_bytes, hip_stream);
+}
+
+static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam,
+                             const pbdr_patch* patch, const float bg[3], uint64_t dup_capacity, const float* final_T,
+                             const uint32_t* last_idx, const float* dL_dimage, pbdr2d_splat_grads* g_splats,
+                             pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
     if (!check_splats2d(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) ||
         !aligned16(dL_dimage) || !check_splat2d_grads(g_splats, splats->n))
         return PBDR_ERR_INVALID_ARG;
+    if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
     if ((scene == nullptr) != (grads == nullptr)) return PBDR_ERR_INVALID_ARG;
     if (scene && (!check_scene2d(scene) || scene->n != splats->n || !check_scene2d_grads(grads, scene))) return PBDR_ERR_INVALID_ARG;
     Layout L;
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L, kVariant2D);
     if (st != PBDR_OK) return st;
-    const CamDev c = to_dev(cam);
+    const CamDev c = to_dev(cam, patch);
     hipError_t e = launch_composite2d_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
                                           (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);

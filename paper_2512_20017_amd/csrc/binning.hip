@@ -11,17 +11,6 @@
 
 namespace pbdr {
 
-__device__ __forceinline__ void rect_of(const CamDev& cam, float mx, float my, int r, int& x0, int& y0, int& x1, int& y1)
-{
-    // floor((m - r)/16) == (floor(m) - r) >> 4 because r and 16 are integers: exact in integer arithmetic
-    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
-    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
-    x0 = min(max((ix - r) >> 4, 0), cam.TX);
-    y0 = min(max((iy - r) >> 4, 0), cam.TY);
-    x1 = min(max((ix + r + 15) >> 4, 0), cam.TX);
-    y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
-}
-
 // Number of visible points (radius > 0) in each block of 256 consecutive points.
 __global__ __launch_bounds__(256) void k_count_visible(int n, const int32_t* __restrict__ radius, uint32_t* __restrict__ vis_block)
 {
@@ -54,7 +43,7 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, co
     for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
     const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
     int x0, y0, x1, y1;
-    rect_of(cam, mx, my, r, x0, y0, x1, y1);
+    tile_rect(cam, mx, my, r, x0, y0, x1, y1);
     float4* dst = reinterpret_cast<float4*>(packed + i);
     dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
     dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
@@ -220,7 +209,7 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
         at = offsets[r];
         id = order[r];
         const int rad = sp.radius[id];
-        if (rad > 0) rect_of(cam, sp.mean2d[id], sp.mean2d[(size_t)sp.n + id], rad, x0, y0, x1, y1);
+        if (rad > 0) tile_rect(cam, sp.mean2d[id], sp.mean2d[(size_t)sp.n + id], rad, x0, y0, x1, y1);
         slot_base[id] = at;
     } else {
         at = offsets[sp.n];                    // the pair total (sentinel slot of the prefix sum)

@@ -50,10 +50,13 @@ __device__ __forceinline__ float qform_min_rect(float A, float B, float C, float
 constexpr int kAccStride = 9;    // floats between the LDS accumulators of consecutive splats of a batch (odd)
 
 // LDS image of one staged batch
+struct StageRec {                     // 48 bytes: one LDS address register serves all three reads of a visit
+    float4 a;                         // mx, my, A = log2e/2 * qa, B = log2e * qb
+    float4 b;                         // C = log2e/2 * qc, L = log2(opacity), red, green
+    float c, pad[3];                  // blue
+};
 struct Stage {
-    float4 a[kBatch];                 // mx, my, A = log2e/2 * qa, B = log2e * qb
-    float4 b[kBatch];                 // C = log2e/2 * qc, L = log2(opacity), red, green
-    float c[kBatch];                  // blue
+    StageRec rec[kBatch];
     unsigned long long mask[4][4];    // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
 };
 
@@ -76,9 +79,9 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
         geo = make_float4(mx, my, r2.y, 0.f);   // r2.y carries the extent (integer bits)
         const float A = 0.5f * kLog2e * qa, B = kLog2e * qb, C = 0.5f * kLog2e * qc;
         const float L = __log2f(o);
-        S.a[threadIdx.x] = make_float4(mx, my, A, B);
-        S.b[threadIdx.x] = make_float4(C, L, r1.z, r1.w);
-        S.c[threadIdx.x] = r2.x;
+        S.rec[threadIdx.x].a = make_float4(mx, my, A, B);
+        S.rec[threadIdx.x].b = make_float4(C, L, r1.z, r1.w);
+        S.rec[threadIdx.x].c = r2.x;
         // alpha >= 1/255  <=>  q(d) <= L + log2(255)
         const float tau = L + kLog2_255;
         const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
@@ -130,9 +133,9 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
             while (m) {
                 const int j = k * 64 + __builtin_ctzll(m);
                 m &= m - 1ull;
-                const float4 a = S.a[j];
-                const float4 b = S.b[j];
-                const float cb = S.c[j];
+                const float4 a = S.rec[j].a;
+                const float4 b = S.rec[j].b;
+                const float cb = S.rec[j].c;
                 const float dx = fx - a.x, dy = fy - a.y;
                 const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                 const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
@@ -199,17 +202,15 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     __syncthreads();
     const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
     if (tile_last == 0) return;
-    const int tile_x = c.tx0 / kTile, tile_y = c.ty0 / kTile;
-    // which of the eight butterfly values this lane ends up holding (see row_sum8)
-    const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
-               r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
-    // One LDS add per visit, by nine lanes. After the row butterfly lanes 0-7 of each row carry the eight values
-    // and lane 15 the row's blue sum; the four rows are then added lane by lane into row 3. (LDS float adds cost
-    // LDS time per active lane and per address clash, and the LDS pipe, not the VALU, bounded this kernel when all
-    // four rows issued their own adds.)
+    const int tile_x = c.tix, tile_y = c.tiy;
+    // One LDS add per visit, by nine lanes. After the row butterfly (row_sum8) lanes 2k and 2k+1 of each row carry
+    // value k and lane 15 is given the row's blue sum; the four rows are then added lane by lane into row 3, whose
+    // even lanes and lane 63 add. (LDS float adds cost LDS time per active lane and per address clash, and the LDS
+    // pipe, not the VALU, bounded this kernel when all four rows issued their own adds.)
+    const bool bit1 = (lane & 2) != 0;
     const bool blue_lane = (lane & 15) == 15;
-    const bool add_lane = lane >= 48 && (blue_lane || (lane & 8) == 0);
-    const int acc_slot = blue_lane ? 8 : (r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0);
+    const bool add_lane = lane >= 48 && (blue_lane || (lane & 1) == 0);
+    const int acc_slot = blue_lane ? 8 : (lane >> 1) & 7;
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
@@ -227,9 +228,9 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                     m &= ~(1ull << bit);
                     const int j = k * 64 + bit;
                     const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
-                    const float4 a = S.a[j];
-                    const float4 b = S.b[j];
-                    const float cb = S.c[j];
+                    const float4 a = S.rec[j].a;
+                    const float4 b = S.rec[j].b;
+                    const float cb = S.rec[j].c;
                     const float dx = fx - a.x, dy = fy - a.y;
                     const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                     const float e = __builtin_amdgcn_exp2f(b.y - q);
@@ -246,10 +247,12 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                     Sfx += w * cg;
                     const float dsx = ds * dx, dsy = ds * dy;
                     const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
-                    const float part = row_sum8(v8, r1, r2, r3);
+                    const float part = row_sum8(v8, bit1);
                     const float blue = row_sum_to_lane15(w * g2c);
                     const float tot = rows_sum_to_row3(blue_lane ? blue : part);
-                    if (add_lane) atomicAdd(&sAcc[kAccStride * j + acc_slot], tot);
+                    int acc_base = kAccStride * j;
+                    asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (else a quarter-rate VALU mad)
+                    if (add_lane) atomicAdd(&sAcc[acc_base + acc_slot], tot);
                 }
             }
         }
@@ -257,13 +260,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         if ((int)threadIdx.x < cnt) {
             // where this (tile, splat) pair sits in the unsorted duplicate list
             int x0, y0, x1, y1;
-            {
-                const int r = __float_as_int(geo.z);
-                const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(geo.x)));
-                const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(geo.y)));
-                x0 = min(max((ix - r) >> 4, 0), cam.TX); y0 = min(max((iy - r) >> 4, 0), cam.TY);
-                x1 = min(max((ix + r + 15) >> 4, 0), cam.TX); y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
-            }
+            tile_rect(cam, geo.x, geo.y, __float_as_int(geo.z), x0, y0, x1, y1);
             const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
                 const float* acc = sAcc + kAccStride * threadIdx.x;
@@ -426,7 +423,7 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     ProfScope prof(kKCompositeFwd, s);
-    hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, bg[0], bg[1],
+    hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed, bg[0], bg[1],
                        bg[2], image, final_T, last_idx);
     return hipGetLastError();
 }
@@ -448,7 +445,7 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     }
     {
         ProfScope prof(kKCompositeBwd, s);
-        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed, slot_base,
+        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed, slot_base,
                            bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
     }
     if (n > 0) {
@@ -466,7 +463,7 @@ hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uin
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     ProfScope prof(kKStats, s);
     hipLaunchKernelGGL(k_fill_f32, dim3(1), dim3(256), 0, s, reinterpret_cast<float*>(counters), 0.f, (size_t)4);
-    hipLaunchKernelGGL(k_render_stats, dim3((unsigned)L.tiles), dim3(256), 0, s, cam, ranges, vals, packed,
+    hipLaunchKernelGGL(k_render_stats, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed,
                        reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
 }

@@ -9,10 +9,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2_255 = 7.994353436858858f;
 
 struct TileCtx {
-    int px, py;       // this lane's pixel
-    int tx0, ty0;     // tile origin in pixels
-    bool inside;
-    uint32_t pix;
+    int px, py;       // this lane's pixel (image coordinates)
+    int tx0, ty0;     // tile origin in pixels (image coordinates)
+    int tix, tiy;     // tile coordinates within the call's tile grid
+    bool inside;      // the pixel belongs to the rendered patch
+    uint32_t pix;     // its index in the output buffers
     uint32_t start, end;
 };
 
@@ -22,11 +23,12 @@ __device__ __forceinline__ TileCtx tile_ctx(const CamDev& cam, const uint32_t* _
     const int tile = blockIdx.x;
     const int ty = tile / cam.TX, tx = tile - ty * cam.TX;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    c.tx0 = tx * kTile; c.ty0 = ty * kTile;
+    c.tix = tx; c.tiy = ty;
+    c.tx0 = (cam.otx + tx) * kTile; c.ty0 = (cam.oty + ty) * kTile;
     c.px = c.tx0 + (wave & 1) * 8 + (lane & 7);
     c.py = c.ty0 + (wave >> 1) * 8 + (lane >> 3);
-    c.inside = c.px < cam.W && c.py < cam.H;
-    c.pix = (uint32_t)c.py * (uint32_t)cam.W + (uint32_t)c.px;
+    c.inside = c.px >= cam.rx0 && c.px < cam.rx1 && c.py >= cam.ry0 && c.py < cam.ry1;
+    c.pix = (uint32_t)(c.py - cam.ry0) * (uint32_t)cam.W + (uint32_t)(c.px - cam.rx0);
     c.start = ranges[2 * tile];
     c.end = ranges[2 * tile + 1];
     return c;
@@ -59,35 +61,49 @@ __device__ __forceinline__ float dpp_move(float v)
 }
 
 // Sums eight values over each row of 16 lanes at once by recursive halving: at each of three exchange steps a lane
-// keeps half of its values and hands the other half to its partner (lane ^ 1, lane ^ 3, lane ^ 7: DPP quad
-// permutes and the half-row mirror), then one full-row mirror add finishes. 22 VALU instructions instead of 8 x 4.
-// On return the lane holds the row sum of value number 4*r1 + 2*r2 + r3, where, with b_i the bits of its lane
-// number, r1 = b0^b1, r2 = b1^b2, r3 = b2^b3 (each pairing flips exactly one of the rules it must, and none of the
-// earlier ones).
-__device__ __forceinline__ float row_sum8(const float v[8], bool r1, bool r2, bool r3)
+// keeps half of its values and adds its partner's copy of that half, then one more pairing finishes.
+//   step 1: partner lane ^ 8 (row_ror:8);           lanes with bit 3 clear keep values 0..3, the others 4..7
+//   step 2: partner lane ^ 7 (row_half_mirror);     lanes with bit 2 clear keep the first two of those, the others the rest
+//   step 3: partner lane ^ 3 (quad_perm [3,2,1,0]); lanes with bit 1 clear keep the first of those two
+//   last  : partner lane ^ 1 (quad_perm [1,0,3,2]); plain add
+// Each partner differs from the lane in exactly the bit that decides the step and in none of the bits that decided
+// earlier steps, so both hold the same values. Bits 3 and 2 are the quad a lane sits in, which is what a DPP bank
+// mask selects: steps 1 and 2 are two masked adds per output and no select (written as assembly because the compiler
+// has no form for a masked DPP write; the s_nop's cover the VALU-write -> DPP-read wait states inside and on both
+// sides of the block). 16 VALU instructions instead of 8 x 4. Every lane of the wavefront must be active.
+// On return the lane holds the row sum of value number (lane >> 1) & 7; lanes 2k and 2k+1 hold the same number.
+__device__ __forceinline__ float row_sum8(const float v[8], bool bit1)
 {
-    float a[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float keep = r1 ? v[i + 4] : v[i], send = r1 ? v[i] : v[i + 4];
-        a[i] = keep + dpp_move<0xB1>(send);        // quad_perm:[1,0,3,2]
-    }
-    float c[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const float keep = r2 ? a[i + 2] : a[i], send = r2 ? a[i] : a[i + 2];
-        c[i] = keep + dpp_move<0x1B>(send);        // quad_perm:[3,2,1,0]
-    }
-    const float keep = r3 ? c[1] : c[0], send = r3 ? c[0] : c[1];
-    float d = keep + dpp_move<0x141>(send);        // row_half_mirror
-    d += dpp_move<0x140>(d);                       // row_mirror
+    float a[4], c[2];
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %6, %6 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %1, %7, %7 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %2, %8, %8 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %3, %9, %9 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %0, %10, %10 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %1, %11, %11 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %2, %12, %12 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %3, %13, %13 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %4, %0, %0 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %5, %1, %1 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %4, %2, %2 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %5, %3, %3 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "s_nop 1"
+        : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(c[0]), "=&v"(c[1])
+        : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]));
+    const float keep = bit1 ? c[1] : c[0], send = bit1 ? c[0] : c[1];
+    float d = keep + dpp_move<0x1B>(send);         // quad_perm:[3,2,1,0]
+    d += dpp_move<0xB1>(d);                        // quad_perm:[1,0,3,2]
     return d;
 }
 
 // Adds the four rows of 16 lanes of a wavefront lane by lane; the total is valid in lanes 48..63 only.
 // v_permlane16_swap / v_permlane32_swap (gfx950) exchange odd rows (the upper half) of their first operand with even
 // rows (the lower half) of the second: with both operands equal, rows 1 and 3 receive rows 0 and 2, then the upper
-// half receives the lower half. Only the first result of each builtin is used.
+// half receives the lower half. Only the first result of each builtin is used (this compiler hands back the first
+// register for both results of the builtin).
 __device__ __forceinline__ float rows_sum_to_row3(float v)
 {
     const unsigned u = __builtin_bit_cast(unsigned, v);

@@ -71,8 +71,8 @@ __global__ __launch_bounds__(256) void k_group_cull(CamDev cam, int n_groups, co
     const float k0 = (3.0f * sqrtf(kBlur + sqrtf(kEigFloor)) + 1.0f) * 1.00001f;
     // (coefficient of p_x or p_y, coefficient of p_z) of the four side planes: right, left, bottom, top
     const float cxy[4] = {cam.fx, -cam.fx, cam.fy, -cam.fy};
-    const float cz[4] = {-(16.0f * (float)cam.TX + 1.0f + k0 - cam.cx), -(cam.cx + k0),
-                         -(16.0f * (float)cam.TY + 1.0f + k0 - cam.cy), -(cam.cy + k0)};
+    const float cz[4] = {-(16.0f * (float)(cam.otx + cam.TX) + 1.0f + k0 - cam.cx), -(cam.cx - 16.0f * (float)cam.otx + k0),
+                         -(16.0f * (float)(cam.oty + cam.TY) + 1.0f + k0 - cam.cy), -(cam.cy - 16.0f * (float)cam.oty + k0)};
     bool behind = true, beyond = true;
     bool outside[4] = {true, true, true, true};
 #pragma unroll

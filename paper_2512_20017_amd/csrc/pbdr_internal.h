@@ -18,8 +18,13 @@ constexpr int kRadiusMax = 1 << 20;
 constexpr float kPixMax = 1073741824.0f;
 
 // Camera as the kernels see it (passed by value as a kernel argument -> lives in SGPRs).
+// A call may render one rectangular patch of the image (App. D.2 of the paper): W, H are then the patch's size (the
+// size of the output buffers), [rx0, rx1) x [ry0, ry1) its pixels in image coordinates, and TX x TY the part of the
+// image's tile grid that meets it, starting at tile (otx, oty). Tiles stay aligned to the image's own 16 x 16 grid, so
+// a patch holds exactly the pixels the whole-image render would give. Whole image: otx = oty = 0, patch = image.
 struct CamDev {
     int W, H, TX, TY;
+    int otx, oty, rx0, ry0, rx1, ry1;
     float fx, fy, cx, cy;
     float R[9];
     float t[3];
@@ -27,6 +32,18 @@ struct CamDev {
     float near_p, far_p, radius_clip;
     float lim_x, lim_y;
 };
+
+// Tile rectangle [x0, x1) x [y0, y1) of a splat, in tiles of the call's grid: floor((m -+ r) / 16) evaluated as integer
+// floor-division of floor(m) -+ r (the same number, exact), clamped to the grid.
+__device__ __forceinline__ void tile_rect(const CamDev& cam, float mx, float my, int r, int& x0, int& y0, int& x1, int& y1)
+{
+    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
+    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
+    x0 = min(max(((ix - r) >> 4) - cam.otx, 0), cam.TX);
+    y0 = min(max(((iy - r) >> 4) - cam.oty, 0), cam.TY);
+    x1 = min(max(((ix + r + 15) >> 4) - cam.otx, 0), cam.TX);
+    y1 = min(max(((iy + r + 15) >> 4) - cam.oty, 0), cam.TY);
+}
 
 // Raster record: everything the compositing kernels need about one splat, gathered with three 16-byte loads.
 struct __attribute__((aligned(16))) Packed {

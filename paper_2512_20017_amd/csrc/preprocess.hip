@@ -65,16 +65,6 @@ __device__ __forceinline__ void project_cov(const CamDev& cam, const float ls[3]
     P.det = (xx * xx + xy * xy + xz * xz) + kBlur * (a0 + c0) + kBlur * kBlur;
 }
 
-__device__ __forceinline__ void tile_rect(const CamDev& cam, float mx, float my, int r, int& x0, int& y0, int& x1, int& y1)
-{
-    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
-    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
-    x0 = min(max((ix - r) >> 4, 0), cam.TX);
-    y0 = min(max((iy - r) >> 4, 0), cam.TY);
-    x1 = min(max((ix + r + 15) >> 4, 0), cam.TX);
-    y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
-}
-
 // Real SH basis, index l*l+l+m, Condon-Shortley phase kept (so l=1 is (-y, z, -x)).
 __device__ __forceinline__ void sh_basis(int deg, float x, float y, float z, float Y[16])
 {

@@ -149,10 +149,8 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     const int r = (ext < (float)kRadiusMax) ? (int)ext : kRadiusMax;
     if ((float)r <= cam.radius_clip) { out.radius[i] = 0; return; }
     {
-        const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
-        const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
-        const int x0 = min(max((ix - r) >> 4, 0), cam.TX), y0 = min(max((iy - r) >> 4, 0), cam.TY);
-        const int x1 = min(max((ix + r + 15) >> 4, 0), cam.TX), y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+        int x0, y0, x1, y1;
+        tile_rect(cam, mx, my, r, x0, y0, x1, y1);
         if ((x1 - x0) * (y1 - y0) <= 0) { out.radius[i] = 0; return; }
     }
     const float vx = m[0] - cam.campos[0], vy = m[1] - cam.campos[1], vz = m[2] - cam.campos[2];
@@ -298,10 +296,8 @@ __global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam
 #pragma unroll
     for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
     const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-    const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(mx)));
-    const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(my)));
-    const int x0 = min(max((ix - r) >> 4, 0), cam.TX), y0 = min(max((iy - r) >> 4, 0), cam.TY);
-    const int x1 = min(max((ix + r + 15) >> 4, 0), cam.TX), y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
+    int x0, y0, x1, y1;
+    tile_rect(cam, mx, my, r, x0, y0, x1, y1);
     const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
     float4* dst = reinterpret_cast<float4*>(packed + i);
     dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
@@ -492,10 +488,9 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
     __syncthreads();
     const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
     if (tile_last == 0) return;
-    const int tile_x = c.tx0 / kTile, tile_y = c.ty0 / kTile;
-    const bool r1 = ((lane ^ (lane >> 1)) & 1) != 0, r2 = (((lane >> 1) ^ (lane >> 2)) & 1) != 0,
-               r3 = (((lane >> 2) ^ (lane >> 3)) & 1) != 0;
-    const int acc_slot = ((lane & 8) ? 8 : 0) + (r1 ? 4 : 0) + (r2 ? 2 : 0) + (r3 ? 1 : 0);
+    const int tile_x = c.tix, tile_y = c.tiy;
+    const bool bit1 = (lane & 2) != 0;
+    const int acc_slot = ((lane & 1) ? 8 : 0) + ((lane >> 1) & 7);     // see row_sum8: odd lanes take the second eight sums
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBatch;
@@ -543,11 +538,11 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                     const float dp0 = du * ips, dp1 = dv * ips, dp2 = -(du * us + dv * vs) * ips;
                     const float va[8] = {dp0, dp1, dp2, E.dx * dp0, E.dx * dp1, E.dx * dp2, E.dy * dp0, E.dy * dp1};
                     const float vb[8] = {E.dy * dp2, w * g0, w * g1, w * g2c, d_o, dmx, dmy, 0.f};
-                    const float pa = row_sum8(va, r1, r2, r3);
-                    const float pb = row_sum8(vb, r1, r2, r3);
-                    // lanes 0-7 of a row keep the first eight sums, lanes 8-15 (mirror copies) take the second eight;
+                    const float pa = row_sum8(va, bit1);
+                    const float pb = row_sum8(vb, bit1);
+                    // even lanes of a row keep the first eight sums, odd lanes (their copies) take the second eight;
                     // the four rows are added lane by lane into row 3, whose 16 lanes issue the one LDS add
-                    const float tot = rows_sum_to_row3((lane & 8) ? pb : pa);
+                    const float tot = rows_sum_to_row3((lane & 1) ? pb : pa);
                     if (lane >= 48) atomicAdd(&sAcc[kAccStride2D * j + acc_slot], tot);
                 }
             }
@@ -555,13 +550,7 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
         __syncthreads();
         if ((int)threadIdx.x < cnt) {
             int x0, y0, x1, y1;
-            {
-                const int r = __float_as_int(q3.y);
-                const int ix = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(q2.x)));
-                const int iy = (int)fminf(kPixMax, fmaxf(-kPixMax, floorf(q2.y)));
-                x0 = min(max((ix - r) >> 4, 0), cam.TX); y0 = min(max((iy - r) >> 4, 0), cam.TY);
-                x1 = min(max((ix + r + 15) >> 4, 0), cam.TX); y1 = min(max((iy + r + 15) >> 4, 0), cam.TY);
-            }
+            tile_rect(cam, q2.x, q2.y, __float_as_int(q3.y), x0, y0, x1, y1);
             const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
                 const float* acc = sAcc + kAccStride2D * threadIdx.x;
@@ -768,7 +757,7 @@ hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, 
                                   float* final_T, uint32_t* last_idx, hipStream_t s)
 {
     ProfScope prof(kKCompositeFwd, s);
-    hipLaunchKernelGGL(k_composite2d_fwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam,
+    hipLaunchKernelGGL(k_composite2d_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,
                        reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
                        reinterpret_cast<const Packed2D*>(ws + L.off_packed), bg[0], bg[1], bg[2], image, final_T, last_idx);
     return hipGetLastError();
@@ -785,7 +774,7 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
     }
     {
         ProfScope prof(kKCompositeBwd, s);
-        hipLaunchKernelGGL(k_composite2d_bwd, dim3((unsigned)L.tiles), dim3(256), 0, s, cam,
+        hipLaunchKernelGGL(k_composite2d_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,
                            reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
                            reinterpret_cast<const Packed2D*>(ws + L.off_packed), reinterpret_cast<const uint32_t*>(ws + L.off_slot_base),
                            bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
@@ -803,7 +792,7 @@ hipError_t launch_render_stats2d(const CamDev& cam, const Layout& L, char* ws, u
 {
     ProfScope prof(kKStats, s);
     hipLaunchKernelGGL(k_zero_counters2d, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned long long*>(counters));
-    hipLaunchKernelGGL(k_render_stats2d, dim3((unsigned)L.tiles), dim3(256), 0, s, cam,
+    hipLaunchKernelGGL(k_render_stats2d, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,
                        reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
                        reinterpret_cast<const Packed2D*>(ws + L.off_packed), reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
