@@ -352,3 +352,30 @@ def preprocess_grouped(scene: dict, cam: dict, group_size: int) -> dict:
                                  _p(out["keep"], C.c_uint8))
     out["keep"] = out["keep"][:ng]
     return out
+
+
+# ---------------------------------------------------------------------------------------- loss and optimizer step
+# Alg. 1 line 13 (loss_fn), line 16 (loss_fn.backward) and line 27 (AdamUpdate). The paper names the steps only; the
+# benchmark configurations fix the loss (mean L1 against the target image) and App. E.1 says the optimizer is the
+# "selective" Adam: the textbook update (Kingma & Ba, with bias correction) applied to the points that were visible
+# in the batch, every other point - parameter and both moments - left exactly as it was. Plain numpy, fp64.
+def l1_loss(image, target):
+    """image, target [H,W,3]. Returns (mean |image - target|, dL/dimage = sign(image - target) / (3 H W))."""
+    a = np.asarray(image, dtype=np.float64); b = np.asarray(target, dtype=np.float64)
+    d = a - b
+    return float(np.abs(d).mean()), np.sign(d) / d.size
+
+
+def adam_selective(param, grad, exp_avg, exp_avg_sq, visible, lr, beta1, beta2, eps, step):
+    """One Adam step on the rows i with visible[i] != 0 of param [n, ...]; returns new (param, exp_avg, exp_avg_sq).
+    step = 1 for the first update (bias corrections 1 - beta^step)."""
+    p = np.array(param, dtype=np.float64); g = np.asarray(grad, dtype=np.float64)
+    m = np.array(exp_avg, dtype=np.float64); v = np.array(exp_avg_sq, dtype=np.float64)
+    rows = np.nonzero(np.asarray(visible) != 0)[0]
+    for i in rows:
+        m[i] = beta1 * m[i] + (1.0 - beta1) * g[i]
+        v[i] = beta2 * v[i] + (1.0 - beta2) * g[i] * g[i]
+        m_hat = m[i] / (1.0 - beta1 ** step)
+        v_hat = v[i] / (1.0 - beta2 ** step)
+        p[i] = p[i] - lr * m_hat / (np.sqrt(v_hat) + eps)
+    return p, m, v
