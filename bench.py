@@ -66,6 +66,9 @@ def main():
                     help="mid = the headline configuration; surfels = the same with 2D Gaussian disks (not the headline metric)")
     ap.add_argument("--group-size", type=int, default=0,
                     help="if > 0: preprocess with point-group frustum culling at this group size (3D Gaussian workloads)")
+    ap.add_argument("--train-step", action="store_true",
+                    help="time a whole training iteration instead (Alg. 1 on one GPU: splat, render, L1 loss, backward, "
+                         "selective Adam with the gradient zeroed in the same pass); not the headline metric")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -160,6 +163,29 @@ def main():
         f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
         f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
 
+    if args.train_step:
+        args.no_cpu_baseline = True      # the parameters move: the oracle legs below describe the fixed scene only
+        assert not surfels, "--train-step is wired for the 3D Gaussian workloads"
+        m1, m2 = scene.zeros_like(), scene.zeros_like()
+        visible = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        lrs = dict(mean=1.6e-4, log_scale=5e-3, quat=1e-3, logit=5e-2, sh=2.5e-3)
+        it = [0]
+
+        def step():   # noqa: F811  (the gradient buffer is zero on entry: zeroed once above, then by every Adam pass)
+            it[0] += 1
+            visible.zero_()
+            f_pre(scene, cam, splats)
+            B.pbdr_mark_visible(splats.radius, visible)
+            f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
+            B.pbdr_l1_loss(image, target, loss, dL)
+            f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
+            for k, lr in lrs.items():
+                B.pbdr_adam_selective(getattr(scene, k), getattr(grads, k), getattr(m1, k), getattr(m2, k), visible,
+                                      lr, 0.9, 0.999, 1e-15, it[0], zero_grad=True)
+        for t in grad_tensors:
+            t.zero_()
+
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -214,6 +240,8 @@ def main():
         "k_tile_ranges": 4.0 * P,
         "k_gather_splat_grads": 8.0 * n + 48.0 * P + 36.0 * n,
         "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K + 2 * (44.0 + 12.0 * K)) * n_vis,
+        "k_l1_loss": 36.0 * W * H,                                        # two reads, one write per value
+        "k_adam_selective": (11 + 3 * K) * (1.0 * n + 32.0 * n_vis),      # mask byte per point and plane; 4 reads + 4 writes
     }
     alu_flops = {
         "k_composite_fwd": FWD_FLOPS_PER_EXAMINED * examined + FWD_FLOPS_PER_BLENDED * blended,
@@ -283,7 +311,8 @@ def main():
                       last_idx_mismatch=int((last_idx.cpu().numpy().astype(np.uint32) != rf["last_idx"])[ok].sum()))
 
     out = {
-        "metric": {"mid": "fwd+bwd views/sec at 1080p, 1M Gaussians",
+        "metric": "training iterations/sec (splat, render, L1 loss, backward, selective Adam), one view" if args.train_step else
+                  {"mid": "fwd+bwd views/sec at 1080p, 1M Gaussians",
                    "surfels": "fwd+bwd views/sec at 1080p, 1M 2D Gaussian surfels",
                    "large": "fwd+bwd views/sec at 4K, 8M Gaussians, street view"}.get(args.workload, "fwd+bwd views/sec"),
         "value": views_per_s, "unit": "views/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

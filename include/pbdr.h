@@ -303,6 +303,37 @@ int pbdr2d_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_
 int pbdr2d_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------------------------
+ * The two steps of a training iteration around the rasterizer (Alg. 1): loss and parameter update. The paper names
+ * them only (loss_fn, loss_fn.backward, AdamUpdate; App. E.1: the "selective" Adam); the readings here, stated by the
+ * CPU oracle too: mean-L1 loss against the target image (what the benchmark configurations use), and the textbook
+ * Adam update with bias correction applied to the points that were visible in the batch, every other point's
+ * parameter and moments left untouched.
+ *
+ * pbdr_l1_loss (Alg. 1 lines 13 and 16, one pass): *loss += mean |image - target| over the 3 x H x W values (device
+ * float, accumulated like line 14's loss_total; the caller zeroes it), dL_dimage = sign(image - target) / (3 H W),
+ * zero where they are equal. image, target, dL_dimage: [3][H][W]. For a patch pass the patch's width and height.
+ *
+ * pbdr_mark_visible: visible[i] = 1 where radius[i] > 0, other entries kept: called once per view of a batch on a
+ * zeroed uint8 [n], it leaves the union of the points the batch's views use.
+ *
+ * pbdr_adam_selective (Alg. 1 line 27) on one attribute tensor of `planes` planes, [planes][n]: for each point i with
+ * visible[i] != 0 and each plane,  m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ * param -= lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps);  step counts from 1. If zero_grad != 0 the
+ * gradient entries that were consumed are set to zero (Alg. 1 line 21 for the next iteration: entries of invisible
+ * points are zero already, nothing accumulated into them). A point that is not visible costs one byte read. */
+typedef struct pbdr_adam_config {
+    float lr, beta1, beta2, eps;
+    int32_t step;
+    int32_t zero_grad;
+} pbdr_adam_config;
+
+int pbdr_l1_loss(int32_t width, int32_t height, const float* image, const float* target, float* loss, float* dL_dimage,
+                 void* hip_stream);
+int pbdr_mark_visible(int32_t n, const int32_t* radius, uint8_t* visible, void* hip_stream);
+int pbdr_adam_selective(int32_t n, int32_t planes, float* param, float* grad, float* exp_avg, float* exp_avg_sq,
+                        const uint8_t* visible, const pbdr_adam_config* cfg, void* hip_stream);
+
 /* Optional per-kernel timing for benchmarks, with HIP events recorded on the stream each kernel is launched on.
  * kernel_mask: bit i enables kernel id i (ids 0 .. pbdr_profile_kernel_count()-1, names from
  * pbdr_profile_kernel_name). At most max_records launches are timed between begin/reset and collect.

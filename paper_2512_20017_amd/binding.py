@@ -29,7 +29,8 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr2d_workspace_bytes", "pbdr2d_preprocess", "pbdr2d_render_fwd", "pbdr2d_render_bwd", "pbdr2d_preprocess_bwd",
            "pbdr2d_lists_view", "pbdr2d_render_stats", "pbdr_group_count", "pbdr_group_bounds", "pbdr_preprocess_grouped",
            "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
-           "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch")
+           "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch",
+           "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective")
 
 _f = C.POINTER(C.c_float)
 
@@ -47,6 +48,11 @@ class CCamera(C.Structure):
 
 class CPatch(C.Structure):
     _fields_ = [("x0", C.c_int32), ("y0", C.c_int32), ("x1", C.c_int32), ("y1", C.c_int32)]
+
+
+class CAdamConfig(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_int32),
+                ("zero_grad", C.c_int32)]
 
 
 class CSplats(C.Structure):
@@ -300,6 +306,26 @@ def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, fin
     _check(lib().pbdr_render_bwd(psc, C.byref(sp), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(final_T), _dev(last_idx),
                                  _dev(dL_dimage), C.byref(g2), pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
                                  _stream(stream)))
+
+
+def pbdr_l1_loss(image: torch.Tensor, target: torch.Tensor, loss: torch.Tensor, dL_dimage: torch.Tensor, stream=None) -> None:
+    """image, target, dL_dimage [3, H, W]; loss: float32 device scalar, accumulated."""
+    _, H, W = image.shape
+    _check(lib().pbdr_l1_loss(C.c_int32(W), C.c_int32(H), _dev(image), _dev(target), _dev(loss), _dev(dL_dimage), _stream(stream)))
+
+
+def pbdr_mark_visible(radius: torch.Tensor, visible: torch.Tensor, stream=None) -> None:
+    _check(lib().pbdr_mark_visible(C.c_int32(radius.numel()), _dev(radius), _dev(visible), _stream(stream)))
+
+
+def pbdr_adam_selective(param, grad, exp_avg, exp_avg_sq, visible, lr, beta1, beta2, eps, step, zero_grad=False,
+                        stream=None) -> None:
+    """One attribute tensor [planes, n] (or [n]); visible uint8 [n]."""
+    n = int(param.shape[-1])
+    planes = int(param.numel() // n) if n else 0
+    cfg = CAdamConfig(float(lr), float(beta1), float(beta2), float(eps), int(step), int(bool(zero_grad)))
+    _check(lib().pbdr_adam_selective(C.c_int32(n), C.c_int32(planes), _dev(param), _dev(grad), _dev(exp_avg), _dev(exp_avg_sq),
+                                     _dev(visible), C.byref(cfg), _stream(stream)))
 
 
 def _patch(patch) -> CPatch:

@@ -530,6 +530,36 @@ static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* spl
     return hip_result(launch_preprocess2d_bwd(dev(scene), c, dev(splats), dev(g_splats), dev(grads), (hipStream_t)hip_stream));
 }
 
+int pbdr_l1_loss(int32_t width, int32_t height, const float* image, const float* target, float* loss, float* dL_dimage,
+                 void* hip_stream)
+{
+    if (width <= 0 || height <= 0 || width > 65536 || height > 65536) return PBDR_ERR_INVALID_ARG;
+    if (!aligned16(image) || !aligned16(target) || !aligned16(dL_dimage) || loss == nullptr || (reinterpret_cast<uintptr_t>(loss) & 3u))
+        return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_l1_loss(width, height, image, target, loss, dL_dimage, (hipStream_t)hip_stream));
+}
+
+int pbdr_mark_visible(int32_t n, const int32_t* radius, uint8_t* visible, void* hip_stream)
+{
+    if (n < 0) return PBDR_ERR_INVALID_ARG;
+    if (n > 0 && (!aligned16(radius) || !aligned16(visible))) return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_mark_visible(n, radius, visible, (hipStream_t)hip_stream));
+}
+
+int pbdr_adam_selective(int32_t n, int32_t planes, float* param, float* grad, float* exp_avg, float* exp_avg_sq,
+                        const uint8_t* visible, const pbdr_adam_config* cfg, void* hip_stream)
+{
+    if (n < 0 || planes < 0 || planes > 65535 || !cfg) return PBDR_ERR_INVALID_ARG;
+    if (!(cfg->lr >= 0.f) || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f) ||
+        !(cfg->eps > 0.f) || cfg->step < 1)
+        return PBDR_ERR_INVALID_ARG;
+    if (n > 0 && planes > 0 &&
+        (!aligned16(param) || !aligned16(grad) || !aligned16(exp_avg) || !aligned16(exp_avg_sq) || !aligned16(visible)))
+        return PBDR_ERR_INVALID_ARG;
+    return hip_result(launch_adam_selective(n, planes, param, grad, exp_avg, exp_avg_sq, visible, cfg->lr, cfg->beta1,
+                                            cfg->beta2, cfg->eps, cfg->step, cfg->zero_grad, (hipStream_t)hip_stream));
+}
+
 int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
                      uint64_t dup_capacity, void* hip_stream, uint64_t* num_dup)
 {

@@ -156,6 +156,13 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
 
 hipError_t launch_render_stats2d(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
 
+// loss and optimizer step (Alg. 1 lines 13, 16, 27)
+hipError_t launch_l1_loss(int W, int H, const float* image, const float* target, float* loss, float* dL, hipStream_t s);
+hipError_t launch_mark_visible(int n, const int32_t* radius, uint8_t* visible, hipStream_t s);
+hipError_t launch_adam_selective(int n, int planes, float* param, float* grad, float* exp_avg, float* exp_avg_sq,
+                                 const uint8_t* visible, float lr, float beta1, float beta2, float eps, int step,
+                                 int zero_grad, hipStream_t s);
+
 // final location of the sorted pair lists (depends on the parity of the tile pass count)
 inline size_t sorted_tkeys_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tkey1 : L.off_tkey0; }
 inline size_t sorted_vals_off(const Layout& L) { return (L.tile_passes & 1) ? L.off_tval1 : L.off_tval0; }
