@@ -94,7 +94,8 @@ typedef struct pbdr_splats {
 } pbdr_splats;
 
 /* Gradient w.r.t. the differentiable part of pbdr_splats (what Alg. 1 line 19-20 sends back). Overwritten for every
- * point with radius > 0; entries of culled points are left untouched (nothing reads them). */
+ * point that binning lists: radius > 0 and a tile rectangle that is not empty, which is every point with radius > 0
+ * of a state written by pbdr_preprocess. Entries of other points are left untouched (nothing reads them). */
 typedef struct pbdr_splat_grads {
     int32_t n;
     float* mean2d;  /* [2][n] */

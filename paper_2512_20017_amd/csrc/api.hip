@@ -49,6 +49,9 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->off_ranges = take((size_t)L->tiles * 2 * sizeof(uint32_t));
     L->off_partial = take((size_t)cap * L->partial_vec4 * 4 * sizeof(float));
     L->off_keys64 = take((size_t)cap * sizeof(uint64_t));
+    L->off_chunk_rank = take(((size_t)cap / 256 + 2) * sizeof(uint32_t));         // see pair_reduce.h
+    L->off_carry = take(((size_t)cap / 256 + 2) * 36 * sizeof(float));
+    L->off_grad_rec = take((size_t)n * L->partial_vec4 * 4 * sizeof(float));      // per-point gradient records, by point index
     L->total = off;
     return true;
 }

@@ -8,14 +8,29 @@
 // duplication (every duplicate of a splat carries the same depth bits), and whose tile digits are sorted on the P
 // pairs afterwards: the same permutation for a fraction of the traffic.
 #include "pbdr_internal.h"
+#include "pair_reduce.h"
 
 namespace pbdr {
 
-// Number of visible points (radius > 0) in each block of 256 consecutive points.
-__global__ __launch_bounds__(256) void k_count_visible(int n, const int32_t* __restrict__ radius, uint32_t* __restrict__ vis_block)
+// Tiles touched by every point (0 for culled points) and, per block of 256 consecutive points, the number of points
+// that touch at least one tile: those are the points binning lists ("visible" below). A state made by the
+// preprocessing calls has radius == 0 for every point without a tile; a caller-made state with radius > 0 and an
+// empty tile rectangle is treated as culled here, so every listed point owns at least one pair.
+__global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, uint32_t* __restrict__ tiles_touched,
+                                                       uint32_t* __restrict__ vis_block)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    const int c = __syncthreads_count(i < n && radius[i] > 0);
+    uint32_t t = 0;
+    if (i < in.n) {
+        const int r = in.radius[i];
+        if (r > 0) {
+            int x0, y0, x1, y1;
+            tile_rect(cam, in.mean2d[i], in.mean2d[(size_t)in.n + i], r, x0, y0, x1, y1);
+            t = (uint32_t)(max(x1 - x0, 0) * max(y1 - y0, 0));
+        }
+        tiles_touched[i] = t;
+    }
+    const int c = __syncthreads_count(t > 0);
     if (threadIdx.x == 0) vis_block[blockIdx.x] = (uint32_t)c;
 }
 
@@ -24,7 +39,7 @@ __global__ __launch_bounds__(256) void k_count_visible(int n, const int32_t* __r
 // the scanned block counts, the slot within the block from ballots), where its (depth bits, index) pair for the depth
 // sort goes. Culled points cost one 4-byte read and nothing downstream.
 __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ vis_block,
-                                                    uint32_t* __restrict__ tiles_touched, Packed* __restrict__ packed,
+                                                    const uint32_t* __restrict__ tiles_touched, Packed* __restrict__ packed,
                                                     uint32_t* __restrict__ dkey, uint32_t* __restrict__ dval,
                                                     uint32_t* __restrict__ depth_bits)
 {
@@ -32,8 +47,7 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, co
     const int i = blockIdx.x * 256 + threadIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)sp.n;
-    const int r = (i < sp.n) ? sp.radius[i] : 0;
-    const bool vis = r > 0;
+    const bool vis = (i < sp.n) && tiles_touched[i] > 0;
     const unsigned long long m = __ballot(vis);
     if (lane == 0) sWave[wave] = (uint32_t)__popcll(m);
     __syncthreads();
@@ -41,16 +55,14 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, co
     uint32_t slot = vis_block[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
 #pragma unroll
     for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
+    const int r = sp.radius[i];
     const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-    int x0, y0, x1, y1;
-    tile_rect(cam, mx, my, r, x0, y0, x1, y1);
     float4* dst = reinterpret_cast<float4*>(packed + i);
     dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
     dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
     const float depth = sp.depth[i];
     const uint32_t key = __float_as_uint(depth);
     dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), depth, 0.f);
-    tiles_touched[i] = (uint32_t)((x1 - x0) * (y1 - y0));
     dkey[slot] = key;
     dval[slot] = (uint32_t)i;
     depth_bits[i] = key;
@@ -247,6 +259,16 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
     if (dropped) status[kStOverflow] = 1u;
 }
 
+__global__ __launch_bounds__(256) void k_chunk_ranks(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ offsets,
+                                                     uint32_t cap, uint32_t* __restrict__ chunk_rank)
+{
+    const uint32_t r = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t m = min(status[kStNumVis], (uint32_t)n);
+    if (r >= m) return;
+    const uint32_t at = min(offsets[r], cap), end = min(offsets[r + 1], cap);
+    for (uint32_t c = (at + kChunkPairs - 1) / kChunkPairs; (uint64_t)c * kChunkPairs < end; ++c) chunk_rank[c] = r;
+}
+
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, size_t count)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -304,14 +326,15 @@ hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
 }
 
 // visible points per block of 256, scanned in place; leaves the visible count in the status words
-hipError_t launch_count_visible(int n, const int32_t* radius, const Layout& L, char* ws, hipStream_t s)
+hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
+    const int n = in.n;
     if (n == 0) return hipSuccess;
     uint32_t* vis_block = reinterpret_cast<uint32_t*>(ws + L.off_vis_block);
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     const unsigned nb = (unsigned)((n + 255) / 256);
     ProfScope prof(kKCountPack, s);
-    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, n, radius, vis_block);
+    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), vis_block);
     hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, vis_block, nb, status + kStNumVis);
     return hipGetLastError();
 }
@@ -319,11 +342,11 @@ hipError_t launch_count_visible(int n, const int32_t* radius, const Layout& L, c
 hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     if (sp.n == 0) return hipSuccess;
-    hipError_t e = launch_count_visible(sp.n, sp.radius, L, ws, s);
+    hipError_t e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
     if (e != hipSuccess) return e;
     ProfScope prof(kKCountPack, s);
     hipLaunchKernelGGL(k_count_pack, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
-                       reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed*>(ws + L.off_packed),
+                       reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<const uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed*>(ws + L.off_packed),
                        reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
                        reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
     return hipGetLastError();

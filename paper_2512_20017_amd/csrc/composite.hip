@@ -13,6 +13,7 @@
 // The per-pair arithmetic is branch-free and in the log2 domain: alpha = min(0.99, 2^(log2 o - q(d))) with
 // q = log2(e) * sigma folded into the staged conic. Plain VALU work: no dense contraction, so no MFMA.
 #include "composite_common.h"
+#include "pair_reduce.h"
 
 namespace pbdr {
 
@@ -278,80 +279,54 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
 }
 
 // Adds up, per point, the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list, 48 bytes
-// each) into dL/d(splat state) of the visible points; culled points are not written. A wavefront owns 64 consecutive depth ranks, whose
-// pairs form one contiguous range: its lanes stream that range 64 pairs at a time (coalesced), find each pair's
-// point by binary search over the 64 range ends in LDS, run a segmented inclusive scan over the 64 pairs (pairs of
-// one point are adjacent lanes), and the last lane of each segment adds the segment total into that point's LDS
-// accumulator - one adder per point and step, so no conflicts.
+// each) into dL/d(splat state) of the visible points; culled points are not written. Balanced by pairs: see
+// pair_reduce.h.
+// The sums are first stored as one 48-byte record per point, by point index (ranks are in depth order, points in
+// storage order: nine 4-byte stores per point into nine planes would touch nine cache lines where this touches one),
+// then a streaming kernel over all points copies the records of listed points into the planes of the splat-state
+// gradient.
+struct StoreSplatGrad {
+    float4* rec;
+    const uint32_t* order;
+    __device__ __forceinline__ void operator()(uint32_t rank, const float (&v)[9]) const
+    {
+        float4* dst = rec + (size_t)3 * order[rank];
+        dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+        dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+        dst[2] = make_float4(v[8], 0.f, 0.f, 0.f);
+    }
+};
+
 __global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const uint32_t* __restrict__ status,
                                                             const uint32_t* __restrict__ order,
                                                             const uint32_t* __restrict__ offsets,
+                                                            const uint32_t* __restrict__ chunk_rank,
                                                             const float4* __restrict__ partial, uint32_t cap,
-                                                            SplatGradDev g2)
+                                                            float* __restrict__ carry, float4* __restrict__ rec)
 {
     __shared__ uint32_t sEnd[4][64];
-    __shared__ float sSum[4][9][64];
-    const uint32_t m = min(status[kStNumVis], (uint32_t)n);     // ranks below m hold the visible points
-    if ((uint32_t)(blockIdx.x * 256) >= m) return;
-    const int r = blockIdx.x * 256 + threadIdx.x;     // rank in depth order; its pairs are [offsets[r], offsets[r+1])
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t w = blockIdx.x * 4u + (threadIdx.x >> 6);
+    gather_wave<3, 9>(w, n, status, offsets, chunk_rank, partial, cap, carry, sEnd[threadIdx.x >> 6], StoreSplatGrad{rec, order});
+}
+
+__global__ __launch_bounds__(256) void k_gather_fixup(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
+                                                      uint32_t cap, const float* __restrict__ carry, float4* __restrict__ rec)
+{
+    gather_fixup<9>(blockIdx.x * 256u + threadIdx.x, status, cap, carry, StoreSplatGrad{rec, order});
+}
+
+// records -> planes, for the points binning listed (tiles_touched > 0)
+__global__ __launch_bounds__(256) void k_grad_records_to_planes(int n, const uint32_t* __restrict__ tiles_touched,
+                                                                const float4* __restrict__ rec, SplatGradDev g2)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n || tiles_touched[i] == 0) return;
     const size_t N = (size_t)n;
-    uint32_t b, e;
-    if (r < n) { b = min(offsets[r], cap); e = min(offsets[r + 1], cap); }
-    else { b = min(offsets[n], cap); e = b; }
-    sEnd[wave][lane] = e;
-#pragma unroll
-    for (int k = 0; k < 9; ++k) sSum[wave][k][lane] = 0.f;
-    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)b, 0);
-    const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)e, 63);
-    __builtin_amdgcn_wave_barrier();
-    // uniform trip count: every lane takes part in the cross-lane steps; the next step's loads are issued before
-    // this step's scan so that a long range is not one memory latency per 64 pairs
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 n0 = zero4, n1 = zero4, n2 = zero4;
-    if (first + lane < last) {
-        const size_t u0 = (size_t)3 * (first + lane);
-        n0 = partial[u0]; n1 = partial[u0 + 1]; n2 = partial[u0 + 2];
-    }
-    for (uint32_t base = first; base < last; base += 64) {
-        const uint32_t u = base + lane;
-        const bool mine = u < last;
-        const float4 p0 = n0, p1 = n1, p2 = n2;
-        n0 = zero4; n1 = zero4; n2 = zero4;
-        if (u + 64 < last) {
-            const size_t un = (size_t)3 * (u + 64);
-            n0 = partial[un]; n1 = partial[un + 1]; n2 = partial[un + 2];
-        }
-        float v[9] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w, p2.x};
-        int owner = 0;
-#pragma unroll
-        for (int step = 32; step >= 1; step >>= 1)
-            if (sEnd[wave][owner + step - 1] <= u) owner += step;
-        if (!mine) owner = 64 + lane;             // lanes past the end are segments of their own
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int o2 = __shfl_up(owner, d, 64);
-            const bool same = (lane >= d) && (o2 == owner);
-#pragma unroll
-            for (int k = 0; k < 9; ++k) {
-                const float t = __shfl_up(v[k], d, 64);
-                v[k] += same ? t : 0.f;
-            }
-        }
-        const int onext = __shfl_down(owner, 1, 64);
-        if (mine && (lane == 63 || onext != owner)) {
-#pragma unroll
-            for (int k = 0; k < 9; ++k) sSum[wave][k][owner] += v[k];
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-    __builtin_amdgcn_wave_barrier();
-    if ((uint32_t)r >= m) return;
-    const uint32_t i = order[r];
-    g2.mean2d[i] = sSum[wave][0][lane]; g2.mean2d[N + i] = sSum[wave][1][lane];
-    g2.conic[i] = sSum[wave][2][lane]; g2.conic[N + i] = sSum[wave][3][lane]; g2.conic[2 * N + i] = sSum[wave][4][lane];
-    g2.opacity[i] = sSum[wave][5][lane];
-    g2.color[i] = sSum[wave][6][lane]; g2.color[N + i] = sSum[wave][7][lane]; g2.color[2 * N + i] = sSum[wave][8][lane];
+    const float4 a = rec[(size_t)3 * i], b = rec[(size_t)3 * i + 1], c = rec[(size_t)3 * i + 2];
+    g2.mean2d[i] = a.x; g2.mean2d[N + i] = a.y;
+    g2.conic[i] = a.z; g2.conic[N + i] = a.w; g2.conic[2 * N + i] = b.x;
+    g2.opacity[i] = b.y;
+    g2.color[i] = b.z; g2.color[N + i] = b.w; g2.color[2 * N + i] = c.x;
 }
 
 // zero the partial sums of the first min(pair count, cap) pairs
@@ -450,8 +425,16 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
-        hipLaunchKernelGGL(k_gather_splat_grads, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status, order, offsets,
-                           partial, L.cap, g2);
+        uint32_t* chunk_rank = reinterpret_cast<uint32_t*>(ws + L.off_chunk_rank);
+        float* carry = reinterpret_cast<float*>(ws + L.off_carry);
+        const unsigned nwave = (unsigned)((L.cap + kChunkPairs - 1) / kChunkPairs);
+        hipLaunchKernelGGL(k_chunk_ranks, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status, offsets, L.cap, chunk_rank);
+        float4* rec = reinterpret_cast<float4*>(ws + L.off_grad_rec);
+        hipLaunchKernelGGL(k_gather_splat_grads, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank,
+                           partial, L.cap, carry, rec);
+        hipLaunchKernelGGL(k_gather_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
+        hipLaunchKernelGGL(k_grad_records_to_planes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
+                           reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
     }
     return hipGetLastError();
 }

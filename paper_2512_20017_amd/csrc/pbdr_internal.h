@@ -103,7 +103,7 @@ struct Layout {
     int tile_bits, tile_passes;   // key bits / 8-bit passes spent on the tile id
     size_t off_status, off_packed, off_depth_bits, off_vis_block, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
         off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
-        off_partial, off_keys64, total;
+        off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, total;
 };
 constexpr int kSortItems = 4096;   // pairs per radix-sort block
 constexpr int kScanItems = 4096;   // elements per scan block
@@ -124,7 +124,7 @@ struct BinInput {
     const int32_t* radius;    // [n]
 };
 hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s);                       // zero status / totals / ranges
-hipError_t launch_count_visible(int n, const int32_t* radius, const Layout& L, char* ws, hipStream_t s);
+hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_finish(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);

@@ -13,6 +13,7 @@
 // multiply-add each, so exactly rounded), and the kernels use h_u = dx T_2 - T_0' with dx = x - mx. The same value of
 // mx is used on both sides, so this is the same number as x T_2 - T_0, without the cancellation.
 #include "composite_common.h"
+#include "pair_reduce.h"
 
 namespace pbdr {
 
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
 // One thread per point; a visible point gets its tile count, the 64-byte raster record with centred rows, and its
 // (depth bits, index) pair in the compact, index-ordered list of visible points (see the 3D variant).
 __global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam, const uint32_t* __restrict__ vis_block,
-                                                      uint32_t* __restrict__ tiles_touched, Packed2D* __restrict__ packed,
+                                                      const uint32_t* __restrict__ tiles_touched, Packed2D* __restrict__ packed,
                                                       uint32_t* __restrict__ dkey, uint32_t* __restrict__ dval,
                                                       uint32_t* __restrict__ depth_bits)
 {
@@ -286,8 +287,7 @@ __global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam
     const int i = blockIdx.x * 256 + threadIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)sp.n;
-    const int r = (i < sp.n) ? sp.radius[i] : 0;
-    const bool vis = r > 0;
+    const bool vis = (i < sp.n) && tiles_touched[i] > 0;
     const unsigned long long m = __ballot(vis);
     if (lane == 0) sWave[wave] = (uint32_t)__popcll(m);
     __syncthreads();
@@ -295,9 +295,8 @@ __global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam
     uint32_t slot = vis_block[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
 #pragma unroll
     for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
+    const int r = sp.radius[i];
     const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-    int x0, y0, x1, y1;
-    tile_rect(cam, mx, my, r, x0, y0, x1, y1);
     const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
     float4* dst = reinterpret_cast<float4*>(packed + i);
     dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
@@ -306,7 +305,6 @@ __global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam
     dst[2] = make_float4(mx, my, sp.color[i], sp.color[N + i]);
     dst[3] = make_float4(sp.color[2 * N + i], __int_as_float(r), fmaf(-mx, t2z, sp.T[2 * N + i]), fmaf(-my, t2z, sp.T[5 * N + i]));
     const uint32_t key = __float_as_uint(sp.depth[i]);
-    tiles_touched[i] = (uint32_t)((x1 - x0) * (y1 - y0));
     dkey[slot] = key;
     dval[slot] = (uint32_t)i;
     depth_bits[i] = key;
@@ -584,69 +582,49 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
     }
 }
 
-// Per point (in depth-rank order): add up the 64-byte partial records of its pairs; see the 3D variant for the scheme.
-__global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
-                                                  const uint32_t* __restrict__ offsets, const float4* __restrict__ partial,
-                                                  uint32_t cap, Splat2DGradDev g2)
-{
-    const uint32_t m = min(status[kStNumVis], (uint32_t)n);     // ranks below m hold the visible points
-    if ((uint32_t)(blockIdx.x * 256) >= m) return;
-    __shared__ uint32_t sEnd[4][64];
-    __shared__ float sSum[4][16][64];
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const size_t N = (size_t)n;
-    uint32_t b, e;
-    if (r < n) { b = min(offsets[r], cap); e = min(offsets[r + 1], cap); }
-    else { b = min(offsets[n], cap); e = b; }
-    sEnd[wave][lane] = e;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) sSum[wave][k][lane] = 0.f;
-    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)b, 0);
-    const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)e, 63);
-    __builtin_amdgcn_wave_barrier();
-    for (uint32_t base = first; base < last; base += 64) {      // uniform trip count: all lanes join the cross-lane steps
-        const uint32_t u = base + lane;
-        const bool mine = u < last;
-        float v[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = 0.f;
-        if (mine) {
-            const float4 p0 = partial[(size_t)4 * u], p1 = partial[(size_t)4 * u + 1], p2 = partial[(size_t)4 * u + 2],
-                         p3 = partial[(size_t)4 * u + 3];
-            v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
-            v[8] = p2.x; v[9] = p2.y; v[10] = p2.z; v[11] = p2.w; v[12] = p3.x; v[13] = p3.y; v[14] = p3.z;
-        }
-        int owner = 0;
-#pragma unroll
-        for (int step = 32; step >= 1; step >>= 1)
-            if (sEnd[wave][owner + step - 1] <= u) owner += step;
-        if (!mine) owner = 64 + lane;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int o2 = __shfl_up(owner, d, 64);
-            const bool same = (lane >= d) && (o2 == owner);
-#pragma unroll
-            for (int k = 0; k < 15; ++k) {
-                const float t = __shfl_up(v[k], d, 64);
-                v[k] += same ? t : 0.f;
-            }
-        }
-        const int onext = __shfl_down(owner, 1, 64);
-        if (mine && (lane == 63 || onext != owner)) {
-#pragma unroll
-            for (int k = 0; k < 15; ++k) sSum[wave][k][owner] += v[k];
-        }
-        __builtin_amdgcn_wave_barrier();
+// Per point: add up the 64-byte partial records of its pairs (balanced by pairs, see pair_reduce.h).
+struct StoreSplat2DGrad {      // one 64-byte record per point, by point index (see the 3D variant)
+    float4* rec;
+    const uint32_t* order;
+    __device__ __forceinline__ void operator()(uint32_t rank, const float (&v)[15]) const
+    {
+        float4* dst = rec + (size_t)4 * order[rank];
+        dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+        dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+        dst[2] = make_float4(v[8], v[9], v[10], v[11]);
+        dst[3] = make_float4(v[12], v[13], v[14], 0.f);
     }
-    __builtin_amdgcn_wave_barrier();
-    if ((uint32_t)r >= m) return;
-    const uint32_t i = order[r];
+};
+
+__global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
+                                                  const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ chunk_rank,
+                                                  const float4* __restrict__ partial, uint32_t cap, float* __restrict__ carry,
+                                                  float4* __restrict__ rec)
+{
+    __shared__ uint32_t sEnd[4][64];
+    const uint32_t w = blockIdx.x * 4u + (threadIdx.x >> 6);
+    gather_wave<4, 15>(w, n, status, offsets, chunk_rank, partial, cap, carry, sEnd[threadIdx.x >> 6], StoreSplat2DGrad{rec, order});
+}
+
+__global__ __launch_bounds__(256) void k_gather2d_fixup(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
+                                                        uint32_t cap, const float* __restrict__ carry, float4* __restrict__ rec)
+{
+    gather_fixup<15>(blockIdx.x * 256u + threadIdx.x, status, cap, carry, StoreSplat2DGrad{rec, order});
+}
+
+__global__ __launch_bounds__(256) void k_grad_records_to_planes2d(int n, const uint32_t* __restrict__ tiles_touched,
+                                                                  const float4* __restrict__ rec, Splat2DGradDev g2)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n || tiles_touched[i] == 0) return;
+    const size_t N = (size_t)n;
+    const float4 a = rec[(size_t)4 * i], b = rec[(size_t)4 * i + 1], c = rec[(size_t)4 * i + 2], d = rec[(size_t)4 * i + 3];
+    const float v[15] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w, c.x, c.y, c.z, c.w, d.x, d.y, d.z};
 #pragma unroll
-    for (int k = 0; k < 9; ++k) g2.T[(size_t)k * N + i] = sSum[wave][k][lane];
-    g2.mean2d[i] = sSum[wave][9][lane]; g2.mean2d[N + i] = sSum[wave][10][lane];
-    g2.opacity[i] = sSum[wave][11][lane];
-    g2.color[i] = sSum[wave][12][lane]; g2.color[N + i] = sSum[wave][13][lane]; g2.color[2 * N + i] = sSum[wave][14][lane];
+    for (int k = 0; k < 9; ++k) g2.T[(size_t)k * N + i] = v[k];
+    g2.mean2d[i] = v[9]; g2.mean2d[N + i] = v[10];
+    g2.opacity[i] = v[11];
+    g2.color[i] = v[12]; g2.color[N + i] = v[13]; g2.color[2 * N + i] = v[14];
 }
 
 // Measurement aid: the forward walk with counters instead of colours (see the 3D variant).
@@ -742,11 +720,11 @@ hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Lay
     hipError_t e = launch_bin_begin(L, ws, s);
     if (e != hipSuccess) return e;
     if (sp.n > 0) {
-        e = launch_count_visible(sp.n, sp.radius, L, ws, s);
+        e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
         if (e != hipSuccess) return e;
         ProfScope prof(kKCountPack, s);
         hipLaunchKernelGGL(k_count_pack2d, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
-                           reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed2D*>(ws + L.off_packed),
+                           reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<const uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed2D*>(ws + L.off_packed),
                            reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
                            reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
     }
@@ -781,9 +759,18 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
-        hipLaunchKernelGGL(k_gather2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status,
-                           reinterpret_cast<const uint32_t*>(ws + L.off_dval0), reinterpret_cast<const uint32_t*>(ws + L.off_offsets),
-                           partial, L.cap, g2);
+        const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_dval0);
+        const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
+        uint32_t* chunk_rank = reinterpret_cast<uint32_t*>(ws + L.off_chunk_rank);
+        float* carry = reinterpret_cast<float*>(ws + L.off_carry);
+        const unsigned nwave = (unsigned)((L.cap + kChunkPairs - 1) / kChunkPairs);
+        hipLaunchKernelGGL(k_chunk_ranks, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status, offsets, L.cap, chunk_rank);
+        float4* rec = reinterpret_cast<float4*>(ws + L.off_grad_rec);
+        hipLaunchKernelGGL(k_gather2d, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank, partial,
+                           L.cap, carry, rec);
+        hipLaunchKernelGGL(k_gather2d_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
+        hipLaunchKernelGGL(k_grad_records_to_planes2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
+                           reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
     }
     return hipGetLastError();
 }

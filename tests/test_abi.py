@@ -31,12 +31,13 @@ def test_workspace_bytes():
     big = B.pbdr_workspace_bytes(1_000_000, 1920, 1080, 8_000_000)
     assert 0 < small < big
     assert big % 256 == 0
-    # dominated by 76 B/point (raster record, counts, offsets, depth-sort buffers) + 72 B/pair (tile keys, values,
-    # their ping-pong copies, 48 B of partial gradient sums, 8 B of inspection keys)
-    assert abs(big - (76e6 + 72 * 8e6)) < 0.1 * big
-    # surfels: 16 B more per point (64-byte raster record) and per pair (64 B of partial sums)
+    # dominated by 124 B/point (raster record, counts, offsets, depth-sort buffers, 48-byte gradient record) +
+    # 72.6 B/pair (tile keys, values, their ping-pong copies, 48 B of partial gradient sums, 8 B of inspection keys,
+    # per-256-pair chunk data)
+    assert abs(big - (124e6 + 72.6 * 8e6)) < 0.1 * big
+    # surfels: 32 B more per point (64-byte raster and gradient records) and 16 B more per pair (64 B of partial sums)
     big2 = B.pbdr2d_workspace_bytes(1_000_000, 1920, 1080, 8_000_000)
-    assert abs((big2 - big) - (16e6 + 16 * 8e6)) < 1e5
+    assert abs((big2 - big) - (32e6 + 16 * 8e6)) < 1e5
     with pytest.raises(B.PbdrError):
         B.pbdr_workspace_bytes(-1, 128, 128, 10)
     with pytest.raises(B.PbdrError):
