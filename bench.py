@@ -131,7 +131,8 @@ def main():
         def f_pre(scene_, cam_, splats_):
             B.pbdr_preprocess_grouped(scene_, cam_, args.group_size, g_bounds, g_keep, splats_)
     grads = scene.zeros_like()
-    grad_tensors = [v for v in vars(grads).values() if isinstance(v, torch.Tensor)]
+    # one fill per step where the gradient buffer is one allocation
+    grad_tensors = [grads.flat] if hasattr(grads, "flat") else [v for v in vars(grads).values() if isinstance(v, torch.Tensor)]
     image = torch.empty((3, H, W), device="cuda")
     final_T = torch.empty((H, W), device="cuda")
     last_idx = torch.empty((H, W), dtype=torch.int32, device="cuda")

@@ -157,8 +157,18 @@ class Scene:
                      up(sc["sh"], (1, 2, 0)))
 
     def zeros_like(self) -> "Scene":
-        return Scene(self.n, self.sh_degree, torch.zeros_like(self.mean), torch.zeros_like(self.log_scale),
-                     torch.zeros_like(self.quat), torch.zeros_like(self.logit), torch.zeros_like(self.sh))
+        """Same shapes, zero-filled, carved out of ONE allocation (kept as `.flat`) so that a gradient buffer is cleared
+        with a single fill; every attribute starts on a 16-byte boundary."""
+        parts = [self.mean, self.log_scale, self.quat, self.logit, self.sh]
+        sizes = [(t.numel() + 3) // 4 * 4 for t in parts]
+        flat = torch.zeros(sum(sizes), dtype=torch.float32, device=self.mean.device)
+        views, at = [], 0
+        for t, sz in zip(parts, sizes):
+            views.append(flat[at:at + t.numel()].view(t.shape))
+            at += sz
+        out = Scene(self.n, self.sh_degree, *views)
+        out.flat = flat
+        return out
 
     def to_numpy(self) -> dict:
         return dict(mean=self.mean.cpu().numpy().T.copy(), log_scale=self.log_scale.cpu().numpy().T.copy(),

@@ -24,7 +24,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->cap = (uint32_t)cap;
     L->tile_bits = 0;
     while ((1 << L->tile_bits) < L->tiles) ++L->tile_bits;
-    L->tile_passes = L->tile_bits == 0 ? 1 : (L->tile_bits + 7) / 8;
+    L->tile_passes = radix_pass_count(L->tile_bits);
     const size_t nblk_d = ((size_t)n + kSortItems - 1) / kSortItems, nblk_t = ((size_t)cap + kSortItems - 1) / kSortItems;
     size_t off = 0;
     const auto take = [&](size_t bytes) { const size_t at = off; off = align256(off + bytes); return at; };
@@ -44,8 +44,11 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->off_tval0 = take((size_t)cap * sizeof(uint32_t));
     L->off_tkey1 = take((size_t)cap * sizeof(uint32_t));
     L->off_tval1 = take((size_t)cap * sizeof(uint32_t));
-    L->off_totals = take((size_t)2 * 4 * 256 * sizeof(uint32_t));   // digit totals of the depth sort, then of the tile sort
-    L->off_tile_hist = take((nblk_d > nblk_t ? nblk_d : nblk_t) * 256 * sizeof(uint32_t));
+    L->off_totals = take((size_t)2 * kRadixMaxBins * sizeof(uint32_t));   // digit totals of the depth sort, then of the tile sort
+    {
+        const size_t hd = nblk_d * kRadixMaxBins, ht = nblk_t * kRadixMaxBins;
+        L->off_tile_hist = take((hd > ht ? hd : ht) * sizeof(uint32_t));
+    }
     L->off_ranges = take((size_t)L->tiles * 2 * sizeof(uint32_t));
     L->off_partial = take((size_t)cap * L->partial_vec4 * 4 * sizeof(float));
     L->off_keys64 = take((size_t)cap * sizeof(uint64_t));

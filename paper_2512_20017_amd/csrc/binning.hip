@@ -209,7 +209,7 @@ hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, 
 __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, const uint32_t* __restrict__ order,
                                                    const uint32_t* __restrict__ offsets, uint32_t* __restrict__ tkeys,
                                                    uint32_t* __restrict__ tvals, uint32_t* __restrict__ slot_base,
-                                                   uint32_t cap, uint32_t* __restrict__ status)
+                                                   uint32_t* __restrict__ chunk_rank, uint32_t cap, uint32_t* __restrict__ status)
 {
     __shared__ uint32_t sEnd[4][64];
     const int r = blockIdx.x * 256 + threadIdx.x;
@@ -228,6 +228,10 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
     }
     const int w = x1 - x0;
     const uint32_t cnt = (uint32_t)(w * (y1 - y0));
+    if ((uint32_t)r < m) {   // which rank owns every 256th pair (for the pair-balanced gather of the backward pass)
+        const uint32_t end = min(at + cnt, cap);
+        for (uint32_t c = (at + kChunkPairs - 1) / kChunkPairs; (uint64_t)c * kChunkPairs < end; ++c) chunk_rank[c] = (uint32_t)r;
+    }
     sEnd[wave][lane] = at + cnt;
     const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)at, 0);
     const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)(at + cnt), 63);
@@ -259,14 +263,11 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
     if (dropped) status[kStOverflow] = 1u;
 }
 
-__global__ __launch_bounds__(256) void k_chunk_ranks(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ offsets,
-                                                     uint32_t cap, uint32_t* __restrict__ chunk_rank)
+__global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, size_t nranges)
 {
-    const uint32_t r = blockIdx.x * 256u + threadIdx.x;
-    const uint32_t m = min(status[kStNumVis], (uint32_t)n);
-    if (r >= m) return;
-    const uint32_t at = min(offsets[r], cap), end = min(offsets[r + 1], cap);
-    for (uint32_t c = (at + kChunkPairs - 1) / kChunkPairs; (uint64_t)c * kChunkPairs < end; ++c) chunk_rank[c] = r;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < (size_t)kStWords) status[i] = 0u;
+    if (i < nranges) ranges[i] = 0u;
 }
 
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, size_t count)
@@ -316,11 +317,10 @@ hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
     uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
-    // status words, digit totals and tile ranges start at zero
+    // status words and tile ranges start at zero (one launch)
+    (void)totals;
     ProfScope prof(kKFill, s);
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(256), 0, s, status, 0u, (size_t)kStWords);
-    hipLaunchKernelGGL(k_fill_u32, dim3(8), dim3(256), 0, s, totals, 0u, (size_t)2048);
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, ranges, 0u,
+    hipLaunchKernelGGL(k_bin_begin, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, status, ranges,
                        2 * (size_t)L.tiles);
     return hipGetLastError();
 }
@@ -370,10 +370,10 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
     uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
     uint32_t* tile_hist = reinterpret_cast<uint32_t*>(ws + L.off_tile_hist);
     const unsigned nblk = (unsigned)((sp.n + 255) / 256);
-    // depth digits: sort the visible splats by their 32 depth bits (4 passes, result back in buffer 0)
-    hipError_t e = launch_radix_sort32(dk, dv, status + kStNumVis, (uint32_t)sp.n, 4, totals, tile_hist, s);
+    // depth digits: sort the visible splats by their 32 depth bits (four passes, result back in the "0" buffers)
+    hipError_t e = launch_radix_sort32(dk, dv, status + kStNumVis, (uint32_t)sp.n, 32, totals, tile_hist, s);
     if (e != hipSuccess) return e;
-    const uint32_t* order = dv[0];
+    const uint32_t* order = dv[radix_pass_count(32) & 1];
     {
         ProfScope prof(kKCountPack, s);
         hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp.n, status, order, touched, offsets);
@@ -382,10 +382,11 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
     if (e != hipSuccess) return e;
     {
         ProfScope prof(kKDuplicate, s);
-        hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, order, offsets, tk[0], tv[0], slot_base, L.cap, status);
+        hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, order, offsets, tk[0], tv[0], slot_base,
+                           reinterpret_cast<uint32_t*>(ws + L.off_chunk_rank), L.cap, status);
     }
     // tile digits: stable sort of the P pairs by tile id
-    e = launch_radix_sort32(tk, tv, status + kStNumDup, L.cap, L.tile_passes, totals + 1024, tile_hist, s);
+    e = launch_radix_sort32(tk, tv, status + kStNumDup, L.cap, L.tile_bits, totals + kRadixMaxBins, tile_hist, s);
     if (e != hipSuccess) return e;
     {
         ProfScope prof(kKTileRanges, s);

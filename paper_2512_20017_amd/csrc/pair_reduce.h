@@ -20,9 +20,8 @@ constexpr int kChunkPairs = 256;   // pairs per wavefront
 constexpr int kCarryFloats = 36;
 enum { kCarryHasLeft = 1, kCarryLeftThrough = 2, kCarryHasRight = 4 };
 
-// chunk_rank[c] = depth rank that owns pair c * 256 (one thread per rank; a rank writes one entry per 256 pairs it spans)
-__global__ __launch_bounds__(256) void k_chunk_ranks(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ offsets,
-                                                     uint32_t cap, uint32_t* __restrict__ chunk_rank);
+// chunk_rank[c] = depth rank that owns pair c * 256; written by the duplication kernel (a rank writes one entry per 256
+// pairs it spans).
 
 template <int kCtrl>
 __device__ __forceinline__ float dpp_shift0(float v)    // shifted-in lanes read 0

@@ -100,12 +100,14 @@ struct Layout {
     size_t record_bytes;      // raster record per point: 48 (3D) or 64 (2D)
     int partial_vec4;         // float4s of partial gradient sums per pair: 3 (3D) or 4 (2D)
     uint32_t cap;
-    int tile_bits, tile_passes;   // key bits / 8-bit passes spent on the tile id
+    int tile_bits, tile_passes;   // key bits / radix passes spent on the tile id
     size_t off_status, off_packed, off_depth_bits, off_vis_block, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
         off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
         off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, total;
 };
-constexpr int kSortItems = 4096;   // pairs per radix-sort block
+constexpr int kSortItems = 2048;   // pairs per radix-sort block
+constexpr int kRadixMaxBins = 256;   // widest digit: 8 bits
+int radix_pass_count(int key_bits);  // passes launch_radix_sort32 takes for this many key bits
 constexpr int kScanItems = 4096;   // elements per scan block
 bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L);
 
@@ -141,7 +143,7 @@ hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uin
 hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* partials,
                                  uint32_t* total_out, hipStream_t s);
 hipError_t launch_radix_sort32(uint32_t* keys[2], uint32_t* vals[2], const uint32_t* count_ptr, uint32_t count_cap,
-                               int passes, uint32_t* totals, uint32_t* tile_hist, hipStream_t s);
+                               int key_bits, uint32_t* totals, uint32_t* tile_hist, hipStream_t s);
 hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s);
 
 // 2D Gaussian surfel variant (workspace laid out with kVariant2D)

@@ -761,10 +761,9 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
         ProfScope prof(kKGather, s);
         const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_dval0);
         const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
-        uint32_t* chunk_rank = reinterpret_cast<uint32_t*>(ws + L.off_chunk_rank);
+        const uint32_t* chunk_rank = reinterpret_cast<const uint32_t*>(ws + L.off_chunk_rank);
         float* carry = reinterpret_cast<float*>(ws + L.off_carry);
         const unsigned nwave = (unsigned)((L.cap + kChunkPairs - 1) / kChunkPairs);
-        hipLaunchKernelGGL(k_chunk_ranks, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, status, offsets, L.cap, chunk_rank);
         float4* rec = reinterpret_cast<float4*>(ws + L.off_grad_rec);
         hipLaunchKernelGGL(k_gather2d, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank, partial,
                            L.cap, carry, rec);
