@@ -2,7 +2,8 @@
 """Benchmark of the splatting hot path on one MI355X.
 
 A step = one pass of the whole per-view path over one synthetic view, inputs resident in HBM:
-    zero the parameter-gradient buffer -> pbdr_preprocess -> pbdr_render_fwd -> pbdr_render_bwd
+    pbdr_preprocess -> pbdr_render_fwd -> pbdr_render_bwd (which, as the first view of its batch, also zeroes the
+    parameter-gradient entries of points the view does not use; --separate-zero does that with a fill of its own)
 on the 1M-Gaussian / SH degree 3 / 1920x1080 configuration (fwd+bwd views per second).  dL/dimage is the gradient of
 a mean-L1 loss against a seeded target, computed once from the warm-up image (the loss itself is harness, not path).
 
@@ -69,6 +70,9 @@ def main():
     ap.add_argument("--train-step", action="store_true",
                     help="time a whole training iteration instead (Alg. 1 on one GPU: splat, render, L1 loss, backward, "
                          "selective Adam with the gradient zeroed in the same pass); not the headline metric")
+    ap.add_argument("--separate-zero", action="store_true",
+                    help="clear the gradient buffer with a separate fill each step and accumulate into it, instead of "
+                         "letting the backward call write it as the first view of its batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -158,11 +162,15 @@ def main():
     sum_last = int(last_idx.to(torch.int64).sum().item())
 
     def step():
-        for t in grad_tensors:
-            t.zero_()
+        # One view per step: the backward call is the first view of its batch, so it also does the zeroing of the
+        # gradient buffer (it writes every entry of every point: the view's gradient, or zero). --separate-zero clears
+        # the buffer with a fill of its own first and accumulates, which leaves the same numbers.
+        if args.separate_zero:
+            for t in grad_tensors:
+                t.zero_()
         f_pre(scene, cam, splats)
         f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
-        f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
+        f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws, first_view=not args.separate_zero)
 
     if args.train_step:
         args.no_cpu_baseline = True      # the parameters move: the oracle legs below describe the fixed scene only

@@ -59,7 +59,11 @@ typedef struct pbdr_scene {
 } pbdr_scene;
 
 /* Gradient w.r.t. pbdr_scene, same layout. pbdr_render_bwd / pbdr_preprocess_bwd ACCUMULATE (+=) into it,
- * which is how Alg. 1 lines 22-24 sum the views of a batch; the caller zeroes it once per batch. */
+ * which is how Alg. 1 lines 22-24 sum the views of a batch; the caller zeroes it once per batch (line 21).
+ * first_view != 0 folds that zeroing into the call for the first view of a batch: the buffer's previous contents
+ * are ignored and every entry of every point is written - the view's gradient, or zero for points it does not use -
+ * which leaves what zeroing and then accumulating leaves (up to the rounding of the last multiply-add), without the
+ * extra pass over 236 bytes per point. */
 typedef struct pbdr_scene_grads {
     int32_t n;
     int32_t sh_degree;
@@ -68,6 +72,7 @@ typedef struct pbdr_scene_grads {
     float* quat;
     float* opacity_logit;
     float* sh;
+    int32_t first_view;
 } pbdr_scene_grads;
 
 /* Pinhole view. World -> camera: p = R x + t, R row-major; camera axes +x right, +y down, +z forward.
@@ -230,7 +235,7 @@ typedef struct pbdr2d_scene {
     const float* sh;            /* [K][3][n] */
 } pbdr2d_scene;
 
-typedef struct pbdr2d_scene_grads { /* accumulated (+=) */
+typedef struct pbdr2d_scene_grads { /* accumulated (+=); first_view as in pbdr_scene_grads */
     int32_t n;
     int32_t sh_degree;
     float* mean;
@@ -239,6 +244,7 @@ typedef struct pbdr2d_scene_grads { /* accumulated (+=) */
     float* log_scale;
     float* opacity_logit;
     float* sh;
+    int32_t first_view;
 } pbdr2d_scene_grads;
 
 /* Per-view surfel state: the 20 floats per point of Table 3b (radius counted as one). radius == 0 = culled. */

@@ -36,8 +36,9 @@ _f = C.POINTER(C.c_float)
 
 
 class CScene(C.Structure):
+    # also used for pbdr_scene_grads, which has the same layout plus the trailing first_view flag
     _fields_ = [("n", C.c_int32), ("sh_degree", C.c_int32), ("mean", C.c_void_p), ("log_scale", C.c_void_p),
-                ("quat", C.c_void_p), ("opacity_logit", C.c_void_p), ("sh", C.c_void_p)]
+                ("quat", C.c_void_p), ("opacity_logit", C.c_void_p), ("sh", C.c_void_p), ("first_view", C.c_int32)]
 
 
 class CCamera(C.Structure):
@@ -67,7 +68,8 @@ class CSplatGrads(C.Structure):
 
 class CScene2D(C.Structure):
     _fields_ = [("n", C.c_int32), ("sh_degree", C.c_int32), ("mean", C.c_void_p), ("tan_u", C.c_void_p),
-                ("tan_v", C.c_void_p), ("log_scale", C.c_void_p), ("opacity_logit", C.c_void_p), ("sh", C.c_void_p)]
+                ("tan_v", C.c_void_p), ("log_scale", C.c_void_p), ("opacity_logit", C.c_void_p), ("sh", C.c_void_p),
+                ("first_view", C.c_int32)]
 
 
 class CSplats2D(C.Structure):
@@ -175,9 +177,9 @@ class Scene:
                     quat=self.quat.cpu().numpy().T.copy(), logit=self.logit.cpu().numpy().copy(),
                     sh=self.sh.cpu().numpy().transpose(2, 0, 1).copy(), sh_degree=self.sh_degree)
 
-    def struct(self) -> CScene:
+    def struct(self, first_view=False) -> CScene:
         return CScene(self.n, self.sh_degree, _dev(self.mean), _dev(self.log_scale), _dev(self.quat), _dev(self.logit),
-                      _dev(self.sh))
+                      _dev(self.sh), int(bool(first_view)))
 
 
 @dataclass
@@ -304,12 +306,13 @@ def pbdr_render_fwd(splats: Splats, cam: dict, bg, dup_capacity: int, image, fin
 
 
 def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
-                    g_splats: SplatGrads, grads, ws, stream=None) -> None:
-    """scene/grads: both Scene (gradient accumulated into grads) or both None (stop at g_splats)."""
+                    g_splats: SplatGrads, grads, ws, stream=None, first_view=False) -> None:
+    """scene/grads: both Scene (gradient accumulated into grads) or both None (stop at g_splats). first_view: write
+    instead of accumulating, zeros for points the view does not use (the first view of a batch, buffer not cleared)."""
     sp, c, g2 = splats.struct(), camera_struct(cam), g_splats.struct()
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
-        sc, g = scene.struct(), grads.struct()
+        sc, g = scene.struct(), grads.struct(first_view)
         psc, pg = C.byref(sc), C.byref(g)
     else:
         psc, pg = None, None
@@ -359,11 +362,11 @@ def pbdr_render_fwd_patch(splats: Splats, cam: dict, patch, bg, dup_capacity: in
 
 
 def pbdr_render_bwd_patch(scene, splats: Splats, cam: dict, patch, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
-                          g_splats: SplatGrads, grads, ws, stream=None) -> None:
+                          g_splats: SplatGrads, grads, ws, stream=None, first_view=False) -> None:
     sp, c, p, g2 = splats.struct(), camera_struct(cam), _patch(patch), g_splats.struct()
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
-        sc, g = scene.struct(), grads.struct()
+        sc, g = scene.struct(), grads.struct(first_view)
         psc, pg = C.byref(sc), C.byref(g)
     else:
         psc, pg = None, None
@@ -372,8 +375,8 @@ def pbdr_render_bwd_patch(scene, splats: Splats, cam: dict, patch, bg, dup_capac
                                        C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
 
 
-def pbdr_preprocess_bwd(scene: Scene, cam: dict, splats: Splats, g_splats: SplatGrads, grads: Scene, stream=None) -> None:
-    sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct()
+def pbdr_preprocess_bwd(scene: Scene, cam: dict, splats: Splats, g_splats: SplatGrads, grads: Scene, stream=None, first_view=False) -> None:
+    sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct(first_view)
     _check(lib().pbdr_preprocess_bwd(C.byref(sc), C.byref(c), C.byref(sp), C.byref(g2), C.byref(g), _stream(stream)))
 
 
@@ -475,9 +478,9 @@ class Scene2D:
                     logit=self.logit.cpu().numpy().copy(), sh=self.sh.cpu().numpy().transpose(2, 0, 1).copy(),
                     sh_degree=self.sh_degree)
 
-    def struct(self) -> CScene2D:
+    def struct(self, first_view=False) -> CScene2D:
         return CScene2D(self.n, self.sh_degree, _dev(self.mean), _dev(self.tan_u), _dev(self.tan_v), _dev(self.log_scale),
-                        _dev(self.logit), _dev(self.sh))
+                        _dev(self.logit), _dev(self.sh), int(bool(first_view)))
 
 
 @dataclass
@@ -575,11 +578,11 @@ def pbdr2d_render_fwd(splats: Splats2D, cam: dict, bg, dup_capacity: int, image,
 
 
 def pbdr2d_render_bwd(scene, splats: Splats2D, cam: dict, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
-                      g_splats: SplatGrads2D, grads, ws, stream=None) -> None:
+                      g_splats: SplatGrads2D, grads, ws, stream=None, first_view=False) -> None:
     sp, c, g2 = splats.struct(), camera_struct(cam), g_splats.struct()
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
-        sc, g = scene.struct(), grads.struct()
+        sc, g = scene.struct(), grads.struct(first_view)
         psc, pg = C.byref(sc), C.byref(g)
     else:
         psc, pg = None, None
@@ -603,11 +606,11 @@ def pbdr2d_render_fwd_patch(splats: Splats2D, cam: dict, patch, bg, dup_capacity
 
 
 def pbdr2d_render_bwd_patch(scene, splats: Splats2D, cam: dict, patch, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
-                            g_splats: SplatGrads2D, grads, ws, stream=None) -> None:
+                            g_splats: SplatGrads2D, grads, ws, stream=None, first_view=False) -> None:
     sp, c, p, g2 = splats.struct(), camera_struct(cam), _patch(patch), g_splats.struct()
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
-        sc, g = scene.struct(), grads.struct()
+        sc, g = scene.struct(), grads.struct(first_view)
         psc, pg = C.byref(sc), C.byref(g)
     else:
         psc, pg = None, None
@@ -616,8 +619,8 @@ def pbdr2d_render_bwd_patch(scene, splats: Splats2D, cam: dict, patch, bg, dup_c
                                          C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
 
 
-def pbdr2d_preprocess_bwd(scene: Scene2D, cam: dict, splats: Splats2D, g_splats: SplatGrads2D, grads: Scene2D, stream=None) -> None:
-    sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct()
+def pbdr2d_preprocess_bwd(scene: Scene2D, cam: dict, splats: Splats2D, g_splats: SplatGrads2D, grads: Scene2D, stream=None, first_view=False) -> None:
+    sc, c, sp, g2, g = scene.struct(), camera_struct(cam), splats.struct(), g_splats.struct(), grads.struct(first_view)
     _check(lib().pbdr2d_preprocess_bwd(C.byref(sc), C.byref(c), C.byref(sp), C.byref(g2), C.byref(g), _stream(stream)))
 
 

@@ -316,7 +316,7 @@ int pbdr_preprocess_bwd(const pbdr_scene* scene, const pbdr_camera* cam, const p
         !check_splat_grads(g_splats, scene->n) || !check_scene_grads(grads, scene))
         return PBDR_ERR_INVALID_ARG;
     return hip_result(launch_preprocess_bwd(dev(scene), to_dev(cam), splats->radius, dev(g_splats), dev(grads),
-                                            (hipStream_t)hip_stream));
+                                            grads->first_view != 0, (hipStream_t)hip_stream));
 }
 
 static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam,
@@ -361,7 +361,8 @@ static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, c
     hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
                                         (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
-    return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), (hipStream_t)hip_stream));
+    return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), grads->first_view != 0,
+                                            (hipStream_t)hip_stream));
 }
 
 int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
@@ -488,7 +489,8 @@ int pbdr2d_preprocess_bwd(const pbdr2d_scene* scene, const pbdr_camera* cam, con
     if (!check_scene2d(scene) || !check_camera(cam) || !check_splats2d(splats) || splats->n != scene->n ||
         !check_splat2d_grads(g_splats, scene->n) || !check_scene2d_grads(grads, scene))
         return PBDR_ERR_INVALID_ARG;
-    return hip_result(launch_preprocess2d_bwd(dev(scene), to_dev(cam), dev(splats), dev(g_splats), dev(grads), (hipStream_t)hip_stream));
+    return hip_result(launch_preprocess2d_bwd(dev(scene), to_dev(cam), dev(splats), dev(g_splats), dev(grads), grads->first_view != 0,
+                                              (hipStream_t)hip_stream));
 }
 
 static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam,
@@ -533,7 +535,8 @@ static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* spl
     hipError_t e = launch_composite2d_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
                                           (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
-    return hip_result(launch_preprocess2d_bwd(dev(scene), c, dev(splats), dev(g_splats), dev(grads), (hipStream_t)hip_stream));
+    return hip_result(launch_preprocess2d_bwd(dev(scene), c, dev(splats), dev(g_splats), dev(grads), grads->first_view != 0,
+                                              (hipStream_t)hip_stream));
 }
 
 int pbdr_l1_loss(int32_t width, int32_t height, const float* image, const float* target, float* loss, float* dL_dimage,

@@ -45,6 +45,14 @@ __device__ __forceinline__ void tile_rect(const CamDev& cam, float mx, float my,
     y1 = min(max(((iy + r + 15) >> 4) - cam.oty, 0), cam.TY);
 }
 
+// Gradient write-out of the splatting backward: "+=" into the caller's buffer (Alg. 1 lines 22-24), or a plain store
+// for the first view of a batch, which folds the zero-initialisation of line 21 into it.
+template <bool kFirst>
+__device__ __forceinline__ void grad_out(float* __restrict__ p, float v)
+{
+    if (kFirst) *p = v; else *p += v;
+}
+
 // Raster record: everything the compositing kernels need about one splat, gathered with three 16-byte loads.
 struct __attribute__((aligned(16))) Packed {
     float mx, my, qa, qb;   // mean2d, conic a, b
@@ -118,7 +126,7 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
 hipError_t launch_group_bounds(const SceneDev& sc, int group_size, float* bounds, hipStream_t s);
 hipError_t launch_group_cull(const CamDev& cam, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
 hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
-                                 const SceneGradDev& g, hipStream_t s);
+                                 const SceneGradDev& g, bool first_view, hipStream_t s);
 // what binning needs of a splat state, whatever the variant
 struct BinInput {
     int n;
@@ -149,7 +157,7 @@ hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s);
 // 2D Gaussian surfel variant (workspace laid out with kVariant2D)
 hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& out, hipStream_t s);
 hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
-                                   const Scene2DGradDev& g, hipStream_t s);
+                                   const Scene2DGradDev& g, bool first_view, hipStream_t s);
 hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
                                   float* final_T, uint32_t* last_idx, hipStream_t s);

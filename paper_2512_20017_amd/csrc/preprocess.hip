@@ -171,15 +171,29 @@ __device__ __forceinline__ void sh_basis_grad(int deg, float x, float y, float z
     dY[15][0] = -3.f * c3a * (xx - yy);        dY[15][1] = 6.f * c3a * x * y;
 }
 
-template <int kDeg>
+// kFirst: the first view of a batch. The gradient buffer is then written, not added to, and points this view does not
+// use get zeros, so the caller need not clear the buffer beforehand.
+template <int kDeg, bool kFirst>
 __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ radius,
                                                         SplatGradDev g2, SceneGradDev g)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    if (radius[i] <= 0) return;
     const size_t N = (size_t)n;
+    if (radius[i] <= 0) {
+        if (kFirst) {
+            constexpr int K0 = (kDeg + 1) * (kDeg + 1);
+#pragma unroll
+            for (int k = 0; k < 3; ++k) { g.mean[(size_t)k * N + i] = 0.f; g.log_scale[(size_t)k * N + i] = 0.f; }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) g.quat[(size_t)k * N + i] = 0.f;
+            g.logit[i] = 0.f;
+#pragma unroll
+            for (int k = 0; k < 3 * K0; ++k) g.sh[(size_t)k * N + i] = 0.f;
+        }
+        return;
+    }
     const float m0 = sc.mean[i], m1 = sc.mean[N + i], m2 = sc.mean[2 * N + i];
     Proj P;
     P.px = cam.R[0] * m0 + cam.R[1] * m1 + cam.R[2] * m2 + cam.t[0];
@@ -194,7 +208,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     // ---- opacity
     {
         const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
-        g.logit[i] += g2.opacity[i] * o * (1.f - o);
+        grad_out<kFirst>(&g.logit[i], g2.opacity[i] * o * (1.f - o));
     }
     float dmu0 = 0.f, dmu1 = 0.f, dmu2 = 0.f;
     // ---- colour: SH coefficients and the view direction
@@ -219,9 +233,9 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
                 t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
             }
             const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
-            if (gc != 0.f) {
+            if (kFirst || gc != 0.f) {
 #pragma unroll
-                for (int k = 0; k < K; ++k) g.sh[(size_t)(3 * k + c) * N + i] += Y[k] * gc;
+                for (int k = 0; k < K; ++k) grad_out<kFirst>(&g.sh[(size_t)(3 * k + c) * N + i], Y[k] * gc);
             }
             gd0 += gc * t0; gd1 += gc * t1; gd2 += gc * t2;
         }
@@ -272,7 +286,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     dmu0 += cam.R[0] * dp0 + cam.R[3] * dp1 + cam.R[6] * dp2;
     dmu1 += cam.R[1] * dp0 + cam.R[4] * dp1 + cam.R[7] * dp2;
     dmu2 += cam.R[2] * dp0 + cam.R[5] * dp1 + cam.R[8] * dp2;
-    g.mean[i] += dmu0; g.mean[N + i] += dmu1; g.mean[2 * N + i] += dmu2;
+    grad_out<kFirst>(&g.mean[i], dmu0); grad_out<kFirst>(&g.mean[N + i], dmu1); grad_out<kFirst>(&g.mean[2 * N + i], dmu2);
     // ---- A = R_cam W, W = Rq diag(s)
     float GRq[9];
 #pragma unroll
@@ -284,7 +298,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
             gs += gw * P.Rq[3 * r + j];
             GRq[3 * r + j] = gw * P.s[j];
         }
-        g.log_scale[(size_t)j * N + i] += gs * P.s[j];
+        grad_out<kFirst>(&g.log_scale[(size_t)j * N + i], gs * P.s[j]);
     }
     // ---- Rq as a function of the unit quaternion, then the normalisation
     {
@@ -297,7 +311,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
         gq[3] = 2.f * (-2.f * z * G[0] - w * G[1] + x * G[2] + w * G[3] - 2.f * z * G[4] + y * G[5] + x * G[6] + y * G[7]);
         const float dot = gq[0] * w + gq[1] * x + gq[2] * y + gq[3] * z;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) g.quat[(size_t)k * N + i] += (gq[k] - P.q[k] * dot) * P.qinv;
+        for (int k = 0; k < 4; ++k) grad_out<kFirst>(&g.quat[(size_t)k * N + i], (gq[k] - P.q[k] * dot) * P.qinv);
     }
 }
 
@@ -317,18 +331,26 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
     return hipGetLastError();
 }
 
+template <bool kFirst>
+static void launch_preprocess_bwd_t(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
+                                    const SceneGradDev& g, unsigned blocks, hipStream_t s)
+{
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL((k_preprocess_bwd<0, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess_bwd<1, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess_bwd<2, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        default: hipLaunchKernelGGL((k_preprocess_bwd<3, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+    }
+}
+
 hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
-                                 const SceneGradDev& g, hipStream_t s)
+                                 const SceneGradDev& g, bool first_view, hipStream_t s)
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL(k_preprocess_bwd<0>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-        case 1: hipLaunchKernelGGL(k_preprocess_bwd<1>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-        case 2: hipLaunchKernelGGL(k_preprocess_bwd<2>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-        default: hipLaunchKernelGGL(k_preprocess_bwd<3>, dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-    }
+    if (first_view) launch_preprocess_bwd_t<true>(sc, cam, radius, g2, g, blocks, s);
+    else launch_preprocess_bwd_t<false>(sc, cam, radius, g2, g, blocks, s);
     return hipGetLastError();
 }
 

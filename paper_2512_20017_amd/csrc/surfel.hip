@@ -182,15 +182,26 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     out.depth[i] = T[8];
 }
 
-template <int kDeg>
+template <int kDeg, bool kFirst>      // kFirst: see the 3D variant
 __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev cam, const int32_t* __restrict__ radius,
                                                           const float* __restrict__ Tst, Splat2DGradDev g2, Scene2DGradDev g)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    if (radius[i] <= 0) return;
     const size_t N = (size_t)n;
+    if (radius[i] <= 0) {
+        if (kFirst) {
+            constexpr int K0 = (kDeg + 1) * (kDeg + 1);
+#pragma unroll
+            for (int k = 0; k < 3; ++k) { g.mean[(size_t)k * N + i] = 0.f; g.tan_u[(size_t)k * N + i] = 0.f; g.tan_v[(size_t)k * N + i] = 0.f; }
+            g.log_scale[i] = 0.f; g.log_scale[N + i] = 0.f;
+            g.logit[i] = 0.f;
+#pragma unroll
+            for (int k = 0; k < 3 * K0; ++k) g.sh[(size_t)k * N + i] = 0.f;
+        }
+        return;
+    }
     const float m[3] = {sc.mean[i], sc.mean[N + i], sc.mean[2 * N + i]};
     const float a[3] = {sc.tan_u[i], sc.tan_u[N + i], sc.tan_u[2 * N + i]};
     const float b[3] = {sc.tan_v[i], sc.tan_v[N + i], sc.tan_v[2 * N + i]};
@@ -198,7 +209,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     surfel_frame(cam, m, a, b, sc.log_scale[i], sc.log_scale[N + i], F);
     {
         const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
-        g.logit[i] += g2.opacity[i] * o * (1.f - o);
+        grad_out<kFirst>(&g.logit[i], g2.opacity[i] * o * (1.f - o));
     }
     float dmu[3] = {0.f, 0.f, 0.f};
     {
@@ -221,9 +232,9 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
                 t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
             }
             const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
-            if (gc != 0.f) {
+            if (kFirst || gc != 0.f) {
 #pragma unroll
-                for (int k = 0; k < K; ++k) g.sh[(size_t)(3 * k + c) * N + i] += Y[k] * gc;
+                for (int k = 0; k < K; ++k) grad_out<kFirst>(&g.sh[(size_t)(3 * k + c) * N + i], Y[k] * gc);
             }
             gd0 += gc * t0; gd1 += gc * t1; gd2 += gc * t2;
         }
@@ -253,9 +264,9 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
 #pragma unroll
         for (int r = 0; r < 3; ++r) gcol[k][r] = cam.R[r] * GH[k] + cam.R[3 + r] * GH[3 + k] + cam.R[6 + r] * GH[6 + k];
 #pragma unroll
-    for (int r = 0; r < 3; ++r) g.mean[(size_t)r * N + i] += dmu[r] + gcol[2][r];
-    g.log_scale[i] += F.su * (gcol[0][0] * F.tu[0] + gcol[0][1] * F.tu[1] + gcol[0][2] * F.tu[2]);
-    g.log_scale[N + i] += F.sv * (gcol[1][0] * F.tv[0] + gcol[1][1] * F.tv[1] + gcol[1][2] * F.tv[2]);
+    for (int r = 0; r < 3; ++r) grad_out<kFirst>(&g.mean[(size_t)r * N + i], dmu[r] + gcol[2][r]);
+    grad_out<kFirst>(&g.log_scale[i], F.su * (gcol[0][0] * F.tu[0] + gcol[0][1] * F.tu[1] + gcol[0][2] * F.tu[2]));
+    grad_out<kFirst>(&g.log_scale[N + i], F.sv * (gcol[1][0] * F.tv[0] + gcol[1][1] * F.tv[1] + gcol[1][2] * F.tv[2]));
     {
         float gtu[3], gtv[3], gw[3];
 #pragma unroll
@@ -267,12 +278,12 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
         float gx[3];
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
-            g.tan_v[(size_t)r * N + i] += gw[r] + gbtu * F.tu[r];
+            grad_out<kFirst>(&g.tan_v[(size_t)r * N + i], gw[r] + gbtu * F.tu[r]);
             gx[r] = gtu[r] - F.btu * gw[r] + gbtu * b[r];
         }
         dot = gx[0] * F.tu[0] + gx[1] * F.tu[1] + gx[2] * F.tu[2];
 #pragma unroll
-        for (int r = 0; r < 3; ++r) g.tan_u[(size_t)r * N + i] += (gx[r] - F.tu[r] * dot) * F.ainv;
+        for (int r = 0; r < 3; ++r) grad_out<kFirst>(&g.tan_u[(size_t)r * N + i], (gx[r] - F.tu[r] * dot) * F.ainv);
     }
 }
 
@@ -700,18 +711,26 @@ hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Sp
     return hipGetLastError();
 }
 
+template <bool kFirst>
+static void launch_preprocess2d_bwd_t(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
+                                      const Scene2DGradDev& g, unsigned blocks, hipStream_t s)
+{
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL((k_preprocess2d_bwd<0, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess2d_bwd<1, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess2d_bwd<2, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        default: hipLaunchKernelGGL((k_preprocess2d_bwd<3, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+    }
+}
+
 hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
-                                   const Scene2DGradDev& g, hipStream_t s)
+                                   const Scene2DGradDev& g, bool first_view, hipStream_t s)
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL(k_preprocess2d_bwd<0>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-        case 1: hipLaunchKernelGGL(k_preprocess2d_bwd<1>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-        case 2: hipLaunchKernelGGL(k_preprocess2d_bwd<2>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-        default: hipLaunchKernelGGL(k_preprocess2d_bwd<3>, dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-    }
+    if (first_view) launch_preprocess2d_bwd_t<true>(sc, cam, sp, g2, g, blocks, s);
+    else launch_preprocess2d_bwd_t<false>(sc, cam, sp, g2, g, blocks, s);
     return hipGetLastError();
 }
 

@@ -14,7 +14,7 @@ import pytest
 import torch
 
 import oracle
-from gpu_pipeline import GpuView
+from gpu_pipeline import GpuView, to_chw_dev
 from helpers import to_f64
 from paper_2512_20017_amd import binding as B
 from paper_2512_20017_amd import synth
@@ -200,3 +200,36 @@ def test_gradients_accumulate_over_views():
     for k in ("mean", "log_scale", "quat", "logit", "sh"):
         s = singles[0][k].astype(np.float64) + singles[1][k]
         np.testing.assert_allclose(tot[k], s, rtol=1e-4, atol=1e-5 * np.abs(s).max())
+
+
+@pytest.mark.parametrize("deg", [0, 3])
+def test_first_view_writes_what_zero_then_accumulate_leaves(deg):
+    """pbdr_scene_grads.first_view folds Alg. 1 line 21 (zero the buffer) into the first view's backward call: whatever
+    the buffer held, it ends up holding what clearing it and accumulating leaves (to the last bit or two: the compiler
+    contracts the final multiply-add differently in the two variants), exact zeros for the points this view does not
+    use; a second view then accumulates on top as before."""
+    sc = synth.random_small_scene(31 + deg, 500, deg, spread=1.2)           # wide: part of the cloud is off screen
+    cams = [synth.pinhole(96, 64, 45.0, *synth.look_at(e, [0, 0, 0], [0, 1, 0])) for e in ([0.2, 0.1, -2.5], [2.0, 0.5, -1.5])]
+    scene = B.Scene.from_numpy(sc)
+    rng = np.random.default_rng(1)
+    ref = scene.zeros_like()
+    got = scene.zeros_like()
+    got.flat.fill_(float("nan"))                                            # stale contents must not matter
+    for ci, cam in enumerate(cams):
+        view = GpuView(500, cam, 200000)
+        sp = view.preprocess(scene)
+        assert 0 < (sp["radius"] > 0).sum() < 500
+        view.render_fwd(BG)
+        G = rng.normal(size=(64, 96, 3)).astype(np.float32)
+        view.render_bwd(BG, G, scene=scene, grads=ref)
+        g = to_chw_dev(G)
+        B.pbdr_render_bwd(scene, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, g, view.g_splats, got, view.ws,
+                          first_view=(ci == 0))
+        torch.cuda.synchronize()
+        a, b = got.to_numpy(), ref.to_numpy()
+        unused = sp["radius"] <= 0
+        for k in ("mean", "log_scale", "quat", "logit", "sh"):
+            assert np.isfinite(a[k]).all(), (ci, k)
+            np.testing.assert_allclose(a[k], b[k], rtol=4e-6, atol=1e-6 * np.abs(b[k]).max())
+            if ci == 0:
+                assert not a[k][unused].any(), k

@@ -274,3 +274,29 @@ def test_e_full_size_view():
     both = vis & ~tie
     for k in PARAM_KEYS:
         _grad_close(k, got_g[k][both], ref_g[k][both], floor_scale=3e-5, allow_frac=1e-5)
+
+
+def test_first_view_writes_what_zero_then_accumulate_leaves():
+    """Surfel twin of the 3D test: first_view stores instead of accumulating and zeroes the points the view skips."""
+    sc = synth.random_small_surfels(41, 400, 2, spread=1.2)
+    cam = synth.pinhole(96, 64, 45.0, *synth.look_at([0.3, 0.1, -2.5], [0, 0, 0], [0, 1, 0]))
+    scene = B.Scene2D.from_numpy(sc)
+    view = SurfelView(400, cam, 200000)
+    sp = view.preprocess(scene)
+    assert 0 < (sp["radius"] > 0).sum() < 400
+    view.render_fwd(BG)
+    G = np.random.default_rng(2).normal(size=(64, 96, 3)).astype(np.float32)
+    ref = scene.zeros_like()
+    view.render_bwd(BG, G, scene=scene, grads=ref)
+    got = scene.zeros_like()
+    for t in (got.mean, got.tan_u, got.tan_v, got.log_scale, got.logit, got.sh):
+        t.fill_(float("nan"))
+    B.pbdr2d_render_bwd(scene, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, to_chw_dev(G), view.g_splats, got,
+                        view.ws, first_view=True)
+    torch.cuda.synchronize()
+    a, b = got.to_numpy(), ref.to_numpy()
+    unused = sp["radius"] <= 0
+    for k in PARAM_KEYS:
+        assert np.isfinite(a[k]).all(), k
+        np.testing.assert_allclose(a[k], b[k], rtol=4e-6, atol=1e-6 * np.abs(b[k]).max())
+        assert not a[k][unused].any(), k
