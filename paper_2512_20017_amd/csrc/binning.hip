@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
 __global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, size_t nranges)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < (size_t)kStWords) status[i] = 0u;
+    if (i < (size_t)kStCleared) status[i] = 0u;
     if (i < nranges) ranges[i] = 0u;
 }
 

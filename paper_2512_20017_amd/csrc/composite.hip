@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                                                        const uint32_t* __restrict__ slot_base, float bg0, float bg1, float bg2,
                                                        const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
                                                        const float* __restrict__ dL_dimage, uint32_t cap,
-                                                       float4* __restrict__ partial)
+                                                       const uint32_t* __restrict__ status, float4* __restrict__ partial)
 {
     __shared__ Stage S;
     // [splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are conflict-free)
@@ -188,6 +188,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     const size_t HW = (size_t)cam.W * cam.H;
+    const uint32_t epoch = status[kStEpoch];
     float T = 1.f, g0 = 0.f, g1 = 0.f, g2c = 0.f;
     uint32_t last = 0;
     if (c.inside) {
@@ -271,7 +272,8 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                                      0.5f * acc[5], acc[6]);                                         // d conic a, b
                 dst[1] = make_float4(0.5f * acc[7], raw.w > 0.f ? -s0 / raw.w : 0.f,                   // d conic c, d opacity
                                      acc[0], acc[1]);                                                 // d red, d green
-                dst[2] = make_float4(acc[8], 0.f, 0.f, 0.f);                                          // d blue
+                // d blue, then the stamp that tells the gather this record belongs to this backward call
+                dst[2] = make_float4(acc[8], 0.f, __uint_as_float(epoch), __uint_as_float(~epoch));
             }
         }
         __syncthreads();   // sAcc and the stage are rewritten by the next batch
@@ -306,13 +308,15 @@ __global__ __launch_bounds__(256) void k_gather_splat_grads(int n, const uint32_
 {
     __shared__ uint32_t sEnd[4][64];
     const uint32_t w = blockIdx.x * 4u + (threadIdx.x >> 6);
-    gather_wave<3, 9>(w, n, status, offsets, chunk_rank, partial, cap, carry, sEnd[threadIdx.x >> 6], StoreSplatGrad{rec, order});
+    gather_wave<3, 9, true>(w, n, status, offsets, chunk_rank, partial, cap, carry, sEnd[threadIdx.x >> 6], StoreSplatGrad{rec, order});
 }
 
-__global__ __launch_bounds__(256) void k_gather_fixup(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
+// also closes the backward call's epoch: the next call stamps its records with a new number
+__global__ __launch_bounds__(256) void k_gather_fixup(int n, uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
                                                       uint32_t cap, const float* __restrict__ carry, float4* __restrict__ rec)
 {
     gather_fixup<9>(blockIdx.x * 256u + threadIdx.x, status, cap, carry, StoreSplatGrad{rec, order});
+    if (blockIdx.x == 0 && threadIdx.x == 0) status[kStEpoch] = status[kStEpoch] + 1u;
 }
 
 // records -> planes, for the points binning listed (tiles_touched > 0)
@@ -327,14 +331,6 @@ __global__ __launch_bounds__(256) void k_grad_records_to_planes(int n, const uin
     g2.conic[i] = a.z; g2.conic[N + i] = a.w; g2.conic[2 * N + i] = b.x;
     g2.opacity[i] = b.y;
     g2.color[i] = b.z; g2.color[N + i] = b.w; g2.color[2 * N + i] = c.x;
-}
-
-// zero the partial sums of the first min(pair count, cap) pairs
-__global__ __launch_bounds__(256) void k_zero_partial(float4* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap)
-{
-    const size_t count = (size_t)3 * min(status[kStNumDup], cap);
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < count) partial[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // Measurement aid: the forward walk with counters instead of colours. counters[0] += list entries examined per pixel
@@ -412,16 +408,12 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
     const uint32_t* slot_base = reinterpret_cast<const uint32_t*>(ws + L.off_slot_base);
     const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_dval0);
-    const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
-    {
-        ProfScope prof(kKFill, s);
-        hipLaunchKernelGGL(k_zero_partial, dim3((unsigned)(((size_t)3 * L.cap + 255) / 256)), dim3(256), 0, s, partial, status, L.cap);
-    }
     {
         ProfScope prof(kKCompositeBwd, s);
         hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed, slot_base,
-                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
+                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, status, partial);
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);

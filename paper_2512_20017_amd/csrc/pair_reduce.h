@@ -74,7 +74,10 @@ __device__ __forceinline__ void seg_scan_sorted(float (&v)[kVals], int owner)
 
 // One wavefront's 256 pairs. kVec4 float4 per record, of which the first kVals floats are summed. `store(rank, v)`
 // writes a finished sum for depth rank `rank`. sEnd: 64 words of LDS private to the wavefront.
-template <int kVec4, int kVals, class Store>
+// kTagged: the last two words of a record carry (epoch, ~epoch) of the backward call that wrote it; a record with any
+// other tag was not written by this call (its pair lies beyond the last splat its tile blended) and counts as zero.
+// That replaces clearing all records before every backward pass.
+template <int kVec4, int kVals, bool kTagged, class Store>
 __device__ __forceinline__ void gather_wave(uint32_t w, int n, const uint32_t* __restrict__ status,
                                             const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ chunk_rank,
                                             const float4* __restrict__ partial, uint32_t cap, float* __restrict__ carry,
@@ -83,6 +86,7 @@ __device__ __forceinline__ void gather_wave(uint32_t w, int n, const uint32_t* _
     const int lane = threadIdx.x & 63;
     const uint32_t Pc = min(status[kStNumDup], cap);
     const uint32_t m = min(status[kStNumVis], (uint32_t)n);
+    const uint32_t epoch = status[kStEpoch];
     const uint32_t wbeg = w * (uint32_t)kChunkPairs;
     if (wbeg >= Pc) return;
     const uint32_t wend = min(wbeg + (uint32_t)kChunkPairs, Pc);
@@ -106,10 +110,12 @@ __device__ __forceinline__ void gather_wave(uint32_t w, int n, const uint32_t* _
             float4 rec[kVec4];
 #pragma unroll
             for (int q = 0; q < kVec4; ++q) rec[q] = partial[(size_t)kVec4 * u + q];
+            const bool written = !kTagged || (__float_as_uint(rec[kVec4 - 1].z) == epoch && __float_as_uint(rec[kVec4 - 1].w) == ~epoch);
 #pragma unroll
             for (int k = 0; k < kVals; ++k) {
                 const float4 r = rec[k >> 2];
-                v[k] = (k & 3) == 0 ? r.x : (k & 3) == 1 ? r.y : (k & 3) == 2 ? r.z : r.w;
+                const float x = (k & 3) == 0 ? r.x : (k & 3) == 1 ? r.y : (k & 3) == 2 ? r.z : r.w;
+                v[k] = written ? x : 0.f;
             }
         }
         {   // range ends of ranks r_cur .. r_cur + 63

@@ -97,7 +97,9 @@ struct Splat2DGradDev {
 };
 
 // Status words at the head of the workspace.
-enum { kStNumDup = 0, kStOverflow = 1, kStNumVis = 2, kStWords = 64 };   // pair count, overflow flag, visible-point count
+// pair count, overflow flag, visible-point count: cleared by every binning. kStEpoch is never cleared: a counter that
+// the backward pass bumps once per call and stamps into the per-pair records it writes (see k_composite_bwd).
+enum { kStNumDup = 0, kStOverflow = 1, kStNumVis = 2, kStCleared = 32, kStEpoch = 32, kStWords = 64 };
 
 // Workspace layout for (n, W, H, capacity). All offsets are multiples of 256 bytes.
 enum Variant { kVariant3D = 0, kVariant2D = 1 };   // 3D Gaussians / 2D Gaussian surfels

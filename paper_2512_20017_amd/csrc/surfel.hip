@@ -614,7 +614,7 @@ __global__ __launch_bounds__(256) void k_gather2d(int n, const uint32_t* __restr
 {
     __shared__ uint32_t sEnd[4][64];
     const uint32_t w = blockIdx.x * 4u + (threadIdx.x >> 6);
-    gather_wave<4, 15>(w, n, status, offsets, chunk_rank, partial, cap, carry, sEnd[threadIdx.x >> 6], StoreSplat2DGrad{rec, order});
+    gather_wave<4, 15, false>(w, n, status, offsets, chunk_rank, partial, cap, carry, sEnd[threadIdx.x >> 6], StoreSplat2DGrad{rec, order});
 }
 
 __global__ __launch_bounds__(256) void k_gather2d_fixup(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,

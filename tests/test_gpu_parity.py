@@ -233,3 +233,37 @@ def test_first_view_writes_what_zero_then_accumulate_leaves(deg):
             np.testing.assert_allclose(a[k], b[k], rtol=4e-6, atol=1e-6 * np.abs(b[k]).max())
             if ci == 0:
                 assert not a[k][unused].any(), k
+
+
+def test_backward_ignores_per_pair_records_of_earlier_calls():
+    """The backward pass does not clear its per-pair records; each call stamps the ones it writes. A call on the same
+    forward pass that walks nothing (last_idx = 0 everywhere) must give exact zeros for every listed point, whatever an
+    earlier call left behind, and the original inputs must then give the original answer again (to fp32 summation
+    order: the four wavefronts of a tile add into LDS in no fixed order)."""
+    sc = synth.random_small_scene(51, 600, 1, spread=0.7)
+    cam = synth.pinhole(96, 80, 55.0, np.eye(3), [0.0, 0.0, 2.4])
+    scene = B.Scene.from_numpy(sc)
+    view = GpuView(600, cam, 200000)
+    sp = view.preprocess(scene)
+    view.render_fwd(BG)
+    vis = sp["radius"] > 0
+    G = np.random.default_rng(3).normal(size=(80, 96, 3)).astype(np.float32)
+    full = view.render_bwd(BG, G)
+    assert np.abs(full["color"][vis]).max() > 0
+    keep_last = view.last_idx.clone()
+    view.last_idx.zero_()
+    none = view.render_bwd(BG, G)
+    for k in ("mean2d", "conic", "opacity", "color"):
+        assert not none[k][vis].any(), k
+    # only the left half of the image walks its lists: points whose tiles all lie in the right half get exact zeros
+    view.last_idx.copy_(keep_last)
+    view.last_idx[:, 48:] = 0
+    left = view.render_bwd(BG, G)
+    right_only = vis & (np.floor(sp["mean2d"][:, 0]) - sp["radius"] >= 48)
+    assert right_only.sum() > 5
+    for k in ("mean2d", "conic", "opacity", "color"):
+        assert not left[k][right_only].any(), k
+    view.last_idx.copy_(keep_last)
+    again = view.render_bwd(BG, G)
+    for k in ("mean2d", "conic", "opacity", "color"):
+        np.testing.assert_allclose(again[k][vis], full[k][vis], rtol=1e-4, atol=1e-5 * np.abs(full[k][vis]).max())
