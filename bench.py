@@ -248,7 +248,9 @@ def main():
         "k_radix_scatter": 4 * 16.0 * n + tile_passes * 16.0 * P,
         "k_tile_ranges": 4.0 * P,
         "k_gather_splat_grads": 8.0 * n + 48.0 * P + 36.0 * n,
-        "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K + 2 * (44.0 + 12.0 * K)) * n_vis,
+        # accumulate: read + write of the visible points' gradient entries; first view: one write of every point's
+        "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K) * n_vis
+                            + ((44.0 + 12.0 * K) * 2 * n_vis if args.separate_zero else (44.0 + 12.0 * K) * n),
         "k_l1_loss": 36.0 * W * H,                                        # two reads, one write per value
         "k_adam_selective": (11 + 3 * K) * (1.0 * n + 32.0 * n_vis),      # mask byte per point and plane; 4 reads + 4 writes
     }
