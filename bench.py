@@ -58,6 +58,104 @@ def profiled_traffic(kernel):
     return None
 
 
+def run_batched(args):
+    """Not the headline metric: the B views of a batch of the mid scene, preprocessing and its backward done for the
+    whole batch in one pass each (pbdr_preprocess_batch, pbdr_preprocess_bwd_batch), next to the same work done with
+    the per-view calls. One step = one batch; value = views per second."""
+    import torch
+
+    from paper_2512_20017_amd import binding as B
+    from paper_2512_20017_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+    nb = args.batch_views
+    sc = synth.scene_mid(args.seed)
+    cams = synth.cameras_sphere()[:nb]
+    n = int(sc["mean"].shape[0])
+    W, H = cams[0]["width"], cams[0]["height"]
+    bg = [0.0, 0.0, 0.0]
+    scene = B.Scene.from_numpy(sc)
+    splats = [B.Splats.empty(n) for _ in cams]
+    g_splats = [B.SplatGrads.empty(n) for _ in cams]
+    grads = scene.zeros_like()
+    image = torch.empty((3, H, W), device="cuda")
+    final_T = torch.empty((H, W), device="cuda")
+    last_idx = torch.empty((H, W), dtype=torch.int32, device="cuda")
+    group = args.group_size
+    bounds = keep = None
+    if group > 0:
+        ng = B.pbdr_group_count(n, group)
+        bounds = torch.empty((7, ng), dtype=torch.float32, device="cuda")
+        keep = torch.empty((nb, ng), dtype=torch.uint8, device="cuda")
+        keep1 = torch.empty(ng, dtype=torch.uint8, device="cuda")
+        B.pbdr_group_bounds(scene, group, bounds)
+    # pair capacity: the largest view's count
+    cap = max(min(16 * n, 32_000_000), 1 << 16)
+    ws = B.alloc_workspace(n, W, H, cap)
+    B.pbdr_preprocess_batch(scene, cams, splats, group, bounds, keep)
+    pairs = []
+    for v, cam in enumerate(cams):
+        B.pbdr_render_fwd(splats[v], cam, bg, cap, image, final_T, last_idx, ws)
+        P, over = B.pbdr_query_lists(ws, n, W, H, cap)
+        assert not over
+        pairs.append(P)
+    del ws
+    cap = int(max(pairs) * 1.25) + 4096
+    ws = B.alloc_workspace(n, W, H, cap)
+    dL = torch.full((3, H, W), 1.0 / float(3 * W * H), device="cuda")
+    dL[:, ::2, 1::2] *= -1.0
+
+    def step_batch():
+        B.pbdr_preprocess_batch(scene, cams, splats, group, bounds, keep)
+        for v, cam in enumerate(cams):
+            B.pbdr_render_fwd(splats[v], cam, bg, cap, image, final_T, last_idx, ws)
+            B.pbdr_render_bwd(None, splats[v], cam, bg, cap, final_T, last_idx, dL, g_splats[v], None, ws)
+        B.pbdr_preprocess_bwd_batch(scene, cams, splats, g_splats, grads, first_view=True)
+
+    def step_per_view():
+        for v, cam in enumerate(cams):
+            if group > 0:
+                B.pbdr_preprocess_grouped(scene, cam, group, bounds, keep1, splats[v])
+            else:
+                B.pbdr_preprocess(scene, cam, splats[v])
+            B.pbdr_render_fwd(splats[v], cam, bg, cap, image, final_T, last_idx, ws)
+            B.pbdr_render_bwd(scene, splats[v], cam, bg, cap, final_T, last_idx, dL, g_splats[v], grads, ws, first_view=(v == 0))
+
+    names = B.profile_kernel_names()
+    out = {}
+    for label, step in (("batch_calls", step_batch), ("per_view_calls", step_per_view)):
+        for _ in range(max(args.warmup, 1)):
+            step()
+        torch.cuda.synchronize()
+        B.pbdr_profile_begin((1 << len(names)) - 1, 64 * nb * 2)
+        step()
+        torch.cuda.synchronize()
+        kern = {}
+        for kid, name in enumerate(names):
+            ms, cnt = B.pbdr_profile_collect(kid)
+            if cnt:
+                kern[name] = dict(ms_per_batch=ms, launches=cnt)
+        B.pbdr_profile_end()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        out[label] = dict(views_per_s=nb * args.steps / (t1 - t0), ms_per_batch=(t1 - t0) * 1e3 / args.steps,
+                          kernels={k: kern[k] for k in ("k_preprocess", "k_preprocess_bwd", "k_group_cull") if k in kern})
+    print(json.dumps({
+        "metric": "fwd+bwd views/sec at 1080p, 1M Gaussians, batch of views (not the headline)",
+        "value": out["batch_calls"]["views_per_s"], "unit": "views/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": out["batch_calls"]["ms_per_batch"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"batched: the mid scene from cameras 0..{nb - 1} of 16, 1920x1080", "views_per_batch": nb,
+                   "group_size": group, "pairs_min": min(pairs), "pairs_max": max(pairs)},
+        "batch_calls": out["batch_calls"], "per_view_calls": out["per_view_calls"]}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +165,9 @@ def main():
                     help="mid = the headline configuration; surfels = the same with 2D Gaussian disks (not the headline metric)")
     ap.add_argument("--group-size", type=int, default=0,
                     help="if > 0: preprocess with point-group frustum culling at this group size (3D Gaussian workloads)")
+    ap.add_argument("--batch-views", type=int, default=0,
+                    help="if > 0: time a batch of this many views (at most 16) of the mid scene with the batched "
+                         "preprocessing calls, next to the per-view calls; not the headline metric")
     ap.add_argument("--train-step", action="store_true",
                     help="time a whole training iteration instead (Alg. 1 on one GPU: splat, render, L1 loss, backward, "
                          "selective Adam with the gradient zeroed in the same pass); not the headline metric")
@@ -82,6 +183,13 @@ def main():
         print("bench.py: this build runs on one GPU only (no sharding or collectives are part of it); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.batch_views > 0:
+        assert args.batch_views <= 16 and args.workload == "mid"
+        if args.steps == 50:
+            args.steps = 10
+        run_batched(args)
+        return
 
     import numpy as np
     import torch

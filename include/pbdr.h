@@ -133,6 +133,24 @@ int pbdr_group_bounds(const pbdr_scene* scene, int32_t group_size, float* bounds
 int pbdr_preprocess_grouped(const pbdr_scene* scene, const pbdr_camera* cam, int32_t group_size, const float* bounds,
                             uint8_t* keep, pbdr_splats* out, void* hip_stream);
 
+/* The views of a batch in one pass over the points (App. D.1: view-by-view preprocessing reads the cloud once per
+ * view, O(batch x points); Alg. 1 lines 2-4 for every view of the batch, lines 21-24 for their gradients).
+ * num_views in [1, PBDR_MAX_BATCH_VIEWS]; `cams`, `outs`, `splats`, `g_splats` are host arrays of num_views structs
+ * (the pointers inside them are device pointers, every n equal to scene->n).
+ * pbdr_preprocess_batch: outs[v] receives exactly what pbdr_preprocess(scene, &cams[v], &outs[v]) writes; every
+ * parameter of a point is read at most once for the whole batch. group_size == 0: no group test (bounds and keep are
+ * ignored). Otherwise bounds is what pbdr_group_bounds wrote and keep [num_views][n_groups] (device, uint8) receives
+ * the per-view flags of pbdr_preprocess_grouped; a group that no view keeps costs no parameter read.
+ * pbdr_preprocess_bwd_batch: grads (+)= sum over v of what pbdr_preprocess_bwd(scene, &cams[v], &splats[v],
+ * &g_splats[v], grads) adds, the views added in index order before the buffer is touched once (a store when
+ * grads->first_view != 0, else one "+="). Of splats[v] only radius is read. Equal to the view-by-view sequence up to
+ * the rounding of fused multiply-adds. */
+#define PBDR_MAX_BATCH_VIEWS 16
+int pbdr_preprocess_batch(const pbdr_scene* scene, int32_t num_views, const pbdr_camera* cams, const pbdr_splats* outs,
+                          int32_t group_size, const float* bounds, uint8_t* keep, void* hip_stream);
+int pbdr_preprocess_bwd_batch(const pbdr_scene* scene, int32_t num_views, const pbdr_camera* cams, const pbdr_splats* splats,
+                              const pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* hip_stream);
+
 /* Image patches (Sec. 4.2.2: the unit of rendering work is an H/p x W/p patch of an image, p = 2..8; App. D.2: the
  * rendering kernels are restricted to the patch). A patch is the pixel rectangle [x0, x1) x [y0, y1) of the camera's
  * image, any size and position inside it. The *_patch calls do what their whole-image namesakes do for those pixels

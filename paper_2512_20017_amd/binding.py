@@ -30,7 +30,7 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr2d_lists_view", "pbdr2d_render_stats", "pbdr_group_count", "pbdr_group_bounds", "pbdr_preprocess_grouped",
            "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
            "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch",
-           "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective")
+           "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective", "pbdr_preprocess_batch", "pbdr_preprocess_bwd_batch")
 
 _f = C.POINTER(C.c_float)
 
@@ -290,6 +290,29 @@ def pbdr_preprocess_grouped(scene: Scene, cam: dict, group_size: int, bounds: to
     s, c, o = scene.struct(), camera_struct(cam), out.struct()
     _check(lib().pbdr_preprocess_grouped(C.byref(s), C.byref(c), C.c_int32(group_size), _dev(bounds), _dev(keep),
                                          C.byref(o), _stream(stream)))
+
+
+def pbdr_preprocess_batch(scene: Scene, cams, outs, group_size: int = 0, bounds=None, keep=None, stream=None) -> None:
+    """cams: list of camera dicts; outs: list of Splats, one per view. With group_size != 0: bounds float32 [7, n_groups]
+    and keep uint8 [len(cams), n_groups] on the device (keep is written)."""
+    s = scene.struct()
+    cs = (CCamera * len(cams))(*[camera_struct(c) for c in cams])
+    structs = [o.struct() for o in outs]
+    os_ = (type(structs[0]) * len(outs))(*structs)
+    _check(lib().pbdr_preprocess_batch(C.byref(s), C.c_int32(len(cams)), cs, os_, C.c_int32(group_size),
+                                       _dev(bounds) if bounds is not None else None,
+                                       _dev(keep) if keep is not None else None, _stream(stream)))
+
+
+def pbdr_preprocess_bwd_batch(scene: Scene, cams, splats, g_splats, grads: Scene, stream=None, first_view=False) -> None:
+    """cams / splats / g_splats: lists with one entry per view."""
+    sc, g = scene.struct(), grads.struct(first_view)
+    cs = (CCamera * len(cams))(*[camera_struct(c) for c in cams])
+    sps = [x.struct() for x in splats]
+    g2s = [x.struct() for x in g_splats]
+    sp_arr = (type(sps[0]) * len(sps))(*sps)
+    g2_arr = (type(g2s[0]) * len(g2s))(*g2s)
+    _check(lib().pbdr_preprocess_bwd_batch(C.byref(sc), C.c_int32(len(cams)), cs, sp_arr, g2_arr, C.byref(g), _stream(stream)))
 
 
 def pbdr_bin_sort(splats: Splats, cam: dict, dup_capacity: int, ws: torch.Tensor, stream=None) -> None:

@@ -264,6 +264,53 @@ int pbdr_preprocess_grouped(const pbdr_scene* scene, const pbdr_camera* cam, int
     return hip_result(launch_preprocess(dev(scene), c, dev(out), keep, group_size, (hipStream_t)hip_stream));
 }
 
+int pbdr_preprocess_batch(const pbdr_scene* scene, int32_t num_views, const pbdr_camera* cams, const pbdr_splats* outs,
+                          int32_t group_size, const float* bounds, uint8_t* keep, void* hip_stream)
+{
+    if (!check_scene(scene) || num_views < 1 || num_views > PBDR_MAX_BATCH_VIEWS || !cams || !outs) return PBDR_ERR_INVALID_ARG;
+    if (group_size != 0 && !check_group_size(group_size)) return PBDR_ERR_INVALID_ARG;
+    BatchCams bc;
+    BatchSplats bs;
+    bc.count = num_views;
+    for (int v = 0; v < num_views; ++v) {
+        if (!check_camera(&cams[v]) || !check_splats(&outs[v]) || outs[v].n != scene->n) return PBDR_ERR_INVALID_ARG;
+        bc.cam[v] = to_dev(&cams[v]);
+        bs.view[v] = dev(&outs[v]);
+    }
+    for (int v = num_views; v < kMaxBatchViews; ++v) { bc.cam[v] = bc.cam[0]; bs.view[v] = bs.view[0]; }
+    if (scene->n == 0) return PBDR_OK;
+    const uint8_t* use_keep = nullptr;
+    if (group_size != 0) {
+        if (!aligned16(bounds) || !aligned16(keep)) return PBDR_ERR_INVALID_ARG;
+        const int ng = (int)(((int64_t)scene->n + group_size - 1) / group_size);
+        const hipError_t e = launch_group_cull_batch(bc, ng, bounds, keep, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return hip_result(e);
+        use_keep = keep;
+    }
+    return hip_result(launch_preprocess_batch(dev(scene), bc, bs, use_keep, group_size, (hipStream_t)hip_stream));
+}
+
+int pbdr_preprocess_bwd_batch(const pbdr_scene* scene, int32_t num_views, const pbdr_camera* cams, const pbdr_splats* splats,
+                              const pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* hip_stream)
+{
+    if (!check_scene(scene) || num_views < 1 || num_views > PBDR_MAX_BATCH_VIEWS || !cams || !splats || !g_splats ||
+        !check_scene_grads(grads, scene))
+        return PBDR_ERR_INVALID_ARG;
+    BatchCams bc;
+    BatchSplatGrads bg;
+    bc.count = num_views;
+    for (int v = 0; v < num_views; ++v) {
+        if (!check_camera(&cams[v]) || !check_splats(&splats[v]) || splats[v].n != scene->n ||
+            !check_splat_grads(&g_splats[v], scene->n))
+            return PBDR_ERR_INVALID_ARG;
+        bc.cam[v] = to_dev(&cams[v]);
+        bg.radius[v] = splats[v].radius;
+        bg.grad[v] = dev(&g_splats[v]);
+    }
+    for (int v = num_views; v < kMaxBatchViews; ++v) { bc.cam[v] = bc.cam[0]; bg.radius[v] = bg.radius[0]; bg.grad[v] = bg.grad[0]; }
+    return hip_result(launch_preprocess_bwd_batch(dev(scene), bc, bg, dev(grads), grads->first_view != 0, (hipStream_t)hip_stream));
+}
+
 int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t dup_capacity, void* workspace,
                   size_t workspace_bytes, void* hip_stream)
 {

@@ -57,11 +57,8 @@ __global__ __launch_bounds__(256) void k_group_bounds(SceneDev sc, int group_siz
 // floor and ceil), and its tile rectangle is empty on the right if mean2d_x - extent >= 16 TX + 1, on the left if
 // mean2d_x + extent < 0; times z > 0 these are linear in the camera-space position, so corners decide for the box.
 // Each comparison carries 4e-6 of the sum of the magnitudes of its terms as margin towards keeping.
-__global__ __launch_bounds__(256) void k_group_cull(CamDev cam, int n_groups, const float* __restrict__ bounds,
-                                                    uint8_t* __restrict__ keep)
+__device__ __forceinline__ uint8_t group_keep(const CamDev& cam, int g, int n_groups, const float* __restrict__ bounds)
 {
-    const int g = blockIdx.x * 256 + threadIdx.x;
-    if (g >= n_groups) return;
     float b[7];
 #pragma unroll
     for (int k = 0; k < 7; ++k) b[k] = bounds[(size_t)k * n_groups + g];
@@ -96,7 +93,25 @@ __global__ __launch_bounds__(256) void k_group_cull(CamDev cam, int n_groups, co
         }
     }
     const bool drop = behind || beyond || outside[0] || outside[1] || outside[2] || outside[3];
-    keep[g] = drop ? 0 : 1;
+    return drop ? 0 : 1;
+}
+
+__global__ __launch_bounds__(256) void k_group_cull(CamDev cam, int n_groups, const float* __restrict__ bounds,
+                                                    uint8_t* __restrict__ keep)
+{
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= n_groups) return;
+    keep[g] = group_keep(cam, g, n_groups, bounds);
+}
+
+// the same test for every view of a batch: blockIdx.y = view, keep is [views][groups]
+__global__ __launch_bounds__(256) void k_group_cull_batch(BatchCams cams, int n_groups, const float* __restrict__ bounds,
+                                                          uint8_t* __restrict__ keep)
+{
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= n_groups) return;
+    const int v = blockIdx.y;
+    keep[(size_t)v * n_groups + g] = group_keep(cams.cam[v], g, n_groups, bounds);
 }
 
 hipError_t launch_group_bounds(const SceneDev& sc, int group_size, float* bounds, hipStream_t s)
@@ -112,6 +127,15 @@ hipError_t launch_group_cull(const CamDev& cam, int n_groups, const float* bound
     if (n_groups == 0) return hipSuccess;
     ProfScope prof(kKGroupCull, s);
     hipLaunchKernelGGL(k_group_cull, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, s, cam, n_groups, bounds, keep);
+    return hipGetLastError();
+}
+
+hipError_t launch_group_cull_batch(const BatchCams& cams, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s)
+{
+    if (n_groups == 0 || cams.count == 0) return hipSuccess;
+    ProfScope prof(kKGroupCull, s);
+    hipLaunchKernelGGL(k_group_cull_batch, dim3((unsigned)((n_groups + 255) / 256), (unsigned)cams.count), dim3(256), 0, s, cams,
+                       n_groups, bounds, keep);
     return hipGetLastError();
 }
 

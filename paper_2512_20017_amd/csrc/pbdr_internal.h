@@ -78,6 +78,21 @@ struct SplatGradDev {
     float *mean2d, *conic, *opacity, *color;
 };
 
+// Up to kMaxBatchViews views handed to one launch by value (kernel arguments): cameras, the splat states to write,
+// the radii and splat-state gradients to read.
+constexpr int kMaxBatchViews = 16;
+struct BatchCams {
+    int count;
+    CamDev cam[kMaxBatchViews];
+};
+struct BatchSplats {
+    SplatsDev view[kMaxBatchViews];
+};
+struct BatchSplatGrads {
+    const int32_t* radius[kMaxBatchViews];
+    SplatGradDev grad[kMaxBatchViews];
+};
+
 // 2D Gaussian surfels: raw parameters, per-view state (Table 3b of the paper) and their gradients
 struct Scene2DDev {
     int n, sh_degree;
@@ -127,6 +142,11 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
                              int group_size, hipStream_t s);
 hipError_t launch_group_bounds(const SceneDev& sc, int group_size, float* bounds, hipStream_t s);
 hipError_t launch_group_cull(const CamDev& cam, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
+hipError_t launch_group_cull_batch(const BatchCams& cams, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
+hipError_t launch_preprocess_batch(const SceneDev& sc, const BatchCams& cams, const BatchSplats& outs, const uint8_t* keep,
+                                   int group_size, hipStream_t s);
+hipError_t launch_preprocess_bwd_batch(const SceneDev& sc, const BatchCams& cams, const BatchSplatGrads& in, const SceneGradDev& g,
+                                       bool first_view, hipStream_t s);
 hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
                                  const SceneGradDev& g, bool first_view, hipStream_t s);
 // what binning needs of a splat state, whatever the variant

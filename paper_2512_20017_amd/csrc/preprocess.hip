@@ -6,6 +6,13 @@
 // HBM-bound: 236 B read + 44 B written per surviving point, 12 B + 4 B per point culled by depth.
 #include "pbdr_internal.h"
 
+// No fused multiply-adds formed by the compiler in this file. Which products get fused into which sums depends on how
+// the surrounding code is laid out (what shares a basic block after inlining, hoisting and unrolling), so the one-view
+// and the batched kernels, which run the same per-point functions inside different loops, would otherwise differ in
+// the last bit here and there, and with them, rarely, an extent or a cull decision. With contraction off every
+// operation rounds as written and the variants agree bit for bit. These kernels wait on memory, not on the ALU.
+#pragma clang fp contract(off)
+
 namespace pbdr {
 
 struct Proj {
@@ -88,26 +95,81 @@ __device__ __forceinline__ void sh_basis(int deg, float x, float y, float z, flo
     Y[15] = -0.5900435899266435f * x * (xx - 3.f * yy);
 }
 
-// keep / blocks_per_group: optional point-group culling (App. D.1). keep[g] == 0 means every point of group g is
-// known to be culled for this view; the workgroup then only marks its 256 points culled and reads no parameter.
+// Where a point's raw parameters come from. The per-view work asks for them in the order it needs them - centre,
+// then shape (scales, rotation) once the depth test is passed, then appearance (SH coefficients, opacity) once the
+// point is known to be visible - so that culled points cost 12 bytes.
+// DirectSrc reads every value from memory where it is used (one view per launch). CachedSrc keeps what it has read
+// in registers, for launches that take a point through several views.
 template <int kDeg>
-__global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, SplatsDev out, const uint8_t* __restrict__ keep,
-                                                    int blocks_per_group)
+struct DirectSrc {
+    const SceneDev& sc;
+    int i;
+    size_t N;
+    float m[3], ls[3], qr[4];
+    __device__ __forceinline__ DirectSrc(const SceneDev& sc_, int i_) : sc(sc_), i(i_), N((size_t)sc_.n)
+    {
+        m[0] = sc.mean[i]; m[1] = sc.mean[N + i]; m[2] = sc.mean[2 * N + i];
+    }
+    __device__ __forceinline__ void need_shape()
+    {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) ls[k] = sc.log_scale[(size_t)k * N + i];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) qr[k] = sc.quat[(size_t)k * N + i];
+    }
+    __device__ __forceinline__ void need_appearance() {}
+    __device__ __forceinline__ float sh(int j) const { return sc.sh[(size_t)j * N + i]; }
+    __device__ __forceinline__ float logit() const { return sc.logit[i]; }
+};
+
+template <int kDeg>
+struct CachedSrc {
+    static constexpr int K3 = 3 * (kDeg + 1) * (kDeg + 1);
+    const SceneDev& sc;
+    int i;
+    size_t N;
+    float m[3], ls[3], qr[4];
+    float shv[K3], lg;
+    bool has_shape, has_app;
+    __device__ __forceinline__ CachedSrc(const SceneDev& sc_, int i_) : sc(sc_), i(i_), N((size_t)sc_.n), has_shape(false), has_app(false)
+    {
+        m[0] = sc.mean[i]; m[1] = sc.mean[N + i]; m[2] = sc.mean[2 * N + i];
+    }
+    __device__ __forceinline__ void need_shape()
+    {
+        if (has_shape) return;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) ls[k] = sc.log_scale[(size_t)k * N + i];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) qr[k] = sc.quat[(size_t)k * N + i];
+        has_shape = true;
+    }
+    __device__ __forceinline__ void need_appearance()
+    {
+        if (has_app) return;
+#pragma unroll
+        for (int j = 0; j < K3; ++j) shv[j] = sc.sh[(size_t)j * N + i];
+        lg = sc.logit[i];
+        has_app = true;
+    }
+    __device__ __forceinline__ float sh(int j) const { return shv[j]; }
+    __device__ __forceinline__ float logit() const { return lg; }
+};
+
+// One point through one view: cull, project, colour; writes the view's splat state (radius 0 for a culled point).
+template <int kDeg, class Src>
+__device__ __forceinline__ void preprocess_point(const CamDev& cam, Src& src, const SplatsDev& out)
 {
-    const int n = sc.n;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    if (keep != nullptr && keep[blockIdx.x / blocks_per_group] == 0) { out.radius[i] = 0; return; }
-    const size_t N = (size_t)n;
-    const float m0 = sc.mean[i], m1 = sc.mean[N + i], m2 = sc.mean[2 * N + i];
+    const int i = src.i;
+    const size_t N = src.N;
+    const float m0 = src.m[0], m1 = src.m[1], m2 = src.m[2];
     Proj P;
     P.px = cam.R[0] * m0 + cam.R[1] * m1 + cam.R[2] * m2 + cam.t[0];
     P.py = cam.R[3] * m0 + cam.R[4] * m1 + cam.R[5] * m2 + cam.t[1];
     P.pz = cam.R[6] * m0 + cam.R[7] * m1 + cam.R[8] * m2 + cam.t[2];
     if (!(P.pz >= cam.near_p && P.pz <= cam.far_p)) { out.radius[i] = 0; return; }
-    const float ls[3] = {sc.log_scale[i], sc.log_scale[N + i], sc.log_scale[2 * N + i]};
-    const float qr[4] = {sc.quat[i], sc.quat[N + i], sc.quat[2 * N + i], sc.quat[3 * N + i]};
-    project_cov(cam, ls, qr, P);
+    src.need_shape();
+    project_cov(cam, src.ls, src.qr, P);
     if (!(P.det > 0.f)) { out.radius[i] = 0; return; }
     const float idet = 1.0f / P.det;
     const float mx = cam.fx * P.px * P.iz + cam.cx;
@@ -123,6 +185,7 @@ __global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, Spl
     tile_rect(cam, mx, my, r, x0, y0, x1, y1);
     if ((x1 - x0) * (y1 - y0) <= 0) { out.radius[i] = 0; return; }
     // colour
+    src.need_appearance();
     const float vx = m0 - cam.campos[0], vy = m1 - cam.campos[1], vz = m2 - cam.campos[2];
     const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
     float Y[16];
@@ -132,15 +195,46 @@ __global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, Spl
 #pragma unroll
     for (int k = 0; k < K; ++k) {
 #pragma unroll
-        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * sc.sh[(size_t)(3 * k + c) * N + i];
+        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * src.sh(3 * k + c);
     }
-    const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
+    const float o = 1.0f / (1.0f + expf(-src.logit()));
     out.mean2d[i] = mx; out.mean2d[N + i] = my;
     out.conic[i] = P.c * idet; out.conic[N + i] = -P.b * idet; out.conic[2 * N + i] = P.a * idet;
     out.opacity[i] = o;
     out.color[i] = fmaxf(rgb[0], 0.f); out.color[N + i] = fmaxf(rgb[1], 0.f); out.color[2 * N + i] = fmaxf(rgb[2], 0.f);
     out.radius[i] = r;
     out.depth[i] = P.pz;
+}
+
+// keep / blocks_per_group: optional point-group culling (App. D.1). keep[g] == 0 means every point of group g is
+// known to be culled for this view; the workgroup then only marks its 256 points culled and reads no parameter.
+template <int kDeg>
+__global__ __launch_bounds__(256) void k_preprocess(SceneDev sc, CamDev cam, SplatsDev out, const uint8_t* __restrict__ keep,
+                                                    int blocks_per_group)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sc.n) return;
+    if (keep != nullptr && keep[blockIdx.x / blocks_per_group] == 0) { out.radius[i] = 0; return; }
+    DirectSrc<kDeg> src(sc, i);
+    preprocess_point<kDeg>(cam, src, out);
+}
+
+// All views of a batch in one pass over the points (App. D.1: view-by-view preprocessing reads the cloud once per
+// view, O(batch x points)). A thread takes its point through every view and reads each parameter at most once; the
+// per-view arithmetic is preprocess_point, so each view's splat state is what k_preprocess writes for it.
+// keep: [views][groups] flags of the group test, or null.
+template <int kDeg>
+__global__ __launch_bounds__(256) void k_preprocess_batch(SceneDev sc, BatchCams cams, BatchSplats outs,
+                                                          const uint8_t* __restrict__ keep, int blocks_per_group, int n_groups)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sc.n) return;
+    const int g = blockIdx.x / blocks_per_group;
+    CachedSrc<kDeg> src(sc, i);
+    for (int v = 0; v < cams.count; ++v) {
+        if (keep != nullptr && keep[(size_t)v * n_groups + g] == 0) { outs.view[v].radius[i] = 0; continue; }
+        preprocess_point<kDeg>(cams.cam[v], src, outs.view[v]);
+    }
 }
 
 // d(colour)/d(direction): partial derivatives of the SH polynomials contracted with the coefficients.
@@ -171,44 +265,74 @@ __device__ __forceinline__ void sh_basis_grad(int deg, float x, float y, float z
     dY[15][0] = -3.f * c3a * (xx - yy);        dY[15][1] = 6.f * c3a * x * y;
 }
 
-// kFirst: the first view of a batch. The gradient buffer is then written, not added to, and points this view does not
-// use get zeros, so the caller need not clear the buffer beforehand.
-template <int kDeg, bool kFirst>
-__global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ radius,
-                                                        SplatGradDev g2, SceneGradDev g)
-{
-    const int n = sc.n;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const size_t N = (size_t)n;
-    if (radius[i] <= 0) {
-        if (kFirst) {
-            constexpr int K0 = (kDeg + 1) * (kDeg + 1);
-#pragma unroll
-            for (int k = 0; k < 3; ++k) { g.mean[(size_t)k * N + i] = 0.f; g.log_scale[(size_t)k * N + i] = 0.f; }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) g.quat[(size_t)k * N + i] = 0.f;
-            g.logit[i] = 0.f;
-#pragma unroll
-            for (int k = 0; k < 3 * K0; ++k) g.sh[(size_t)k * N + i] = 0.f;
-        }
-        return;
+// dL/d(splat state) of one point in one view
+struct SplatGradIn {
+    float mean2d[2], conic[3], opacity, color[3];
+    __device__ __forceinline__ void load(const SplatGradDev& g2, int i, size_t N)
+    {
+        mean2d[0] = g2.mean2d[i]; mean2d[1] = g2.mean2d[N + i];
+        conic[0] = g2.conic[i]; conic[1] = g2.conic[N + i]; conic[2] = g2.conic[2 * N + i];
+        opacity = g2.opacity[i];
+        color[0] = g2.color[i]; color[1] = g2.color[N + i]; color[2] = g2.color[2 * N + i];
     }
-    const float m0 = sc.mean[i], m1 = sc.mean[N + i], m2 = sc.mean[2 * N + i];
+};
+
+// Where the parameter gradients of a point go. MemSink puts each value into the caller's buffer as it is produced
+// (one view per launch): "+=" (Alg. 1 lines 22-24), or a plain store for the first view of a batch, which folds the
+// zero-initialisation of line 21 into it. RegSink adds the views of a batch up in registers first.
+template <int kDeg, bool kFirst>
+struct MemSink {
+    const SceneGradDev& g;
+    int i;
+    size_t N;
+    static constexpr bool kSkipZeroChannel = !kFirst;     // adding zeros to sixteen planes is sixteen wasted updates
+    __device__ __forceinline__ void logit(float v) { grad_out<kFirst>(&g.logit[i], v); }
+    __device__ __forceinline__ void sh(int j, float v) { grad_out<kFirst>(&g.sh[(size_t)j * N + i], v); }
+    __device__ __forceinline__ void mean(int k, float v) { grad_out<kFirst>(&g.mean[(size_t)k * N + i], v); }
+    __device__ __forceinline__ void log_scale(int k, float v) { grad_out<kFirst>(&g.log_scale[(size_t)k * N + i], v); }
+    __device__ __forceinline__ void quat(int k, float v) { grad_out<kFirst>(&g.quat[(size_t)k * N + i], v); }
+};
+
+template <int kDeg>
+struct RegSink {
+    static constexpr int K3 = 3 * (kDeg + 1) * (kDeg + 1);
+    static constexpr bool kSkipZeroChannel = true;
+    float a_logit, a_sh[K3], a_mean[3], a_ls[3], a_quat[4];
+    __device__ __forceinline__ RegSink()
+    {
+        a_logit = 0.f;
+#pragma unroll
+        for (int j = 0; j < K3; ++j) a_sh[j] = 0.f;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) { a_mean[k] = 0.f; a_ls[k] = 0.f; }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a_quat[k] = 0.f;
+    }
+    __device__ __forceinline__ void logit(float v) { a_logit += v; }
+    __device__ __forceinline__ void sh(int j, float v) { a_sh[j] += v; }
+    __device__ __forceinline__ void mean(int k, float v) { a_mean[k] += v; }
+    __device__ __forceinline__ void log_scale(int k, float v) { a_ls[k] += v; }
+    __device__ __forceinline__ void quat(int k, float v) { a_quat[k] += v; }
+};
+
+// Derivative of preprocess_point for a point that the view uses (radius > 0): dL/d(splat state) -> dL/d(parameters).
+// src must hold shape and appearance.
+template <int kDeg, class Src, class Sink>
+__device__ __forceinline__ void preprocess_point_bwd(const CamDev& cam, const Src& src, const SplatGradIn& in, Sink& sink)
+{
+    const float m0 = src.m[0], m1 = src.m[1], m2 = src.m[2];
     Proj P;
     P.px = cam.R[0] * m0 + cam.R[1] * m1 + cam.R[2] * m2 + cam.t[0];
     P.py = cam.R[3] * m0 + cam.R[4] * m1 + cam.R[5] * m2 + cam.t[1];
     P.pz = cam.R[6] * m0 + cam.R[7] * m1 + cam.R[8] * m2 + cam.t[2];
-    const float ls[3] = {sc.log_scale[i], sc.log_scale[N + i], sc.log_scale[2 * N + i]};
-    const float qr[4] = {sc.quat[i], sc.quat[N + i], sc.quat[2 * N + i], sc.quat[3 * N + i]};
-    project_cov(cam, ls, qr, P);
+    project_cov(cam, src.ls, src.qr, P);
     const float idet = 1.0f / P.det;
     const float qa = P.c * idet, qb = -P.b * idet, qc = P.a * idet;
 
     // ---- opacity
     {
-        const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
-        grad_out<kFirst>(&g.logit[i], g2.opacity[i] * o * (1.f - o));
+        const float o = 1.0f / (1.0f + expf(-src.logit()));
+        sink.logit(in.opacity * o * (1.f - o));
     }
     float dmu0 = 0.f, dmu1 = 0.f, dmu2 = 0.f;
     // ---- colour: SH coefficients and the view direction
@@ -228,14 +352,14 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
             float t0 = 0.f, t1 = 0.f, t2 = 0.f;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                const float co = sc.sh[(size_t)(3 * k + c) * N + i];
+                const float co = src.sh(3 * k + c);
                 raw += Y[k] * co;
                 t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
             }
-            const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
-            if (kFirst || gc != 0.f) {
+            const float gc = raw > 0.f ? in.color[c] : 0.f;
+            if (!Sink::kSkipZeroChannel || gc != 0.f) {
 #pragma unroll
-                for (int k = 0; k < K; ++k) grad_out<kFirst>(&g.sh[(size_t)(3 * k + c) * N + i], Y[k] * gc);
+                for (int k = 0; k < K; ++k) sink.sh(3 * k + c, Y[k] * gc);
             }
             gd0 += gc * t0; gd1 += gc * t1; gd2 += gc * t2;
         }
@@ -245,7 +369,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     // ---- conic -> cov2d:  G = -Q G_Q Q with G_Q = [[ga, gb/2],[gb/2, gc]]
     float G00, G01, G11;
     {
-        const float ga = g2.conic[i], gb = 0.5f * g2.conic[N + i], gc = g2.conic[2 * N + i];
+        const float ga = in.conic[0], gb = 0.5f * in.conic[1], gc = in.conic[2];
         const float u00 = qa * ga + qb * gb, u01 = qa * gb + qb * gc;
         const float u10 = qb * ga + qc * gb, u11 = qb * gb + qc * gc;
         G00 = -(u00 * qa + u01 * qb);
@@ -275,7 +399,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     float dp0, dp1, dp2;
     {
         const float iz = P.iz, iz2 = iz * iz;
-        const float gmx = g2.mean2d[i], gmy = g2.mean2d[N + i];
+        const float gmx = in.mean2d[0], gmy = in.mean2d[1];
         const float gtx = -cam.fx * iz * GJ02, gty = -cam.fy * iz * GJ12;
         dp2 = (-cam.fx * GJ00 + cam.fx * P.tx * GJ02 - cam.fy * GJ11 + cam.fy * P.ty * GJ12) * iz2;
         dp0 = gmx * cam.fx * iz; dp1 = gmy * cam.fy * iz;
@@ -286,7 +410,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     dmu0 += cam.R[0] * dp0 + cam.R[3] * dp1 + cam.R[6] * dp2;
     dmu1 += cam.R[1] * dp0 + cam.R[4] * dp1 + cam.R[7] * dp2;
     dmu2 += cam.R[2] * dp0 + cam.R[5] * dp1 + cam.R[8] * dp2;
-    grad_out<kFirst>(&g.mean[i], dmu0); grad_out<kFirst>(&g.mean[N + i], dmu1); grad_out<kFirst>(&g.mean[2 * N + i], dmu2);
+    sink.mean(0, dmu0); sink.mean(1, dmu1); sink.mean(2, dmu2);
     // ---- A = R_cam W, W = Rq diag(s)
     float GRq[9];
 #pragma unroll
@@ -298,7 +422,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
             gs += gw * P.Rq[3 * r + j];
             GRq[3 * r + j] = gw * P.s[j];
         }
-        grad_out<kFirst>(&g.log_scale[(size_t)j * N + i], gs * P.s[j]);
+        sink.log_scale(j, gs * P.s[j]);
     }
     // ---- Rq as a function of the unit quaternion, then the normalisation
     {
@@ -311,8 +435,85 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
         gq[3] = 2.f * (-2.f * z * G[0] - w * G[1] + x * G[2] + w * G[3] - 2.f * z * G[4] + y * G[5] + x * G[6] + y * G[7]);
         const float dot = gq[0] * w + gq[1] * x + gq[2] * y + gq[3] * z;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) grad_out<kFirst>(&g.quat[(size_t)k * N + i], (gq[k] - P.q[k] * dot) * P.qinv);
+        for (int k = 0; k < 4; ++k) sink.quat(k, (gq[k] - P.q[k] * dot) * P.qinv);
     }
+}
+
+// zeros for a point no view of the batch uses, when the buffer is written rather than added to
+template <int kDeg>
+__device__ __forceinline__ void zero_point_grads(const SceneGradDev& g, int i, size_t N)
+{
+    constexpr int K0 = (kDeg + 1) * (kDeg + 1);
+#pragma unroll
+    for (int k = 0; k < 3; ++k) { g.mean[(size_t)k * N + i] = 0.f; g.log_scale[(size_t)k * N + i] = 0.f; }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) g.quat[(size_t)k * N + i] = 0.f;
+    g.logit[i] = 0.f;
+#pragma unroll
+    for (int k = 0; k < 3 * K0; ++k) g.sh[(size_t)k * N + i] = 0.f;
+}
+
+// kFirst: the first view of a batch. The gradient buffer is then written, not added to, and points this view does not
+// use get zeros, so the caller need not clear the buffer beforehand.
+template <int kDeg, bool kFirst>
+__global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ radius,
+                                                        SplatGradDev g2, SceneGradDev g)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = (size_t)n;
+    if (radius[i] <= 0) {
+        if (kFirst) zero_point_grads<kDeg>(g, i, N);
+        return;
+    }
+    DirectSrc<kDeg> src(sc, i);
+    src.need_shape();
+    SplatGradIn in;
+    in.load(g2, i, N);
+    MemSink<kDeg, kFirst> sink{g, i, N};
+    preprocess_point_bwd<kDeg>(cam, src, in, sink);
+}
+
+// The views of a batch in one pass over the points (Alg. 1 lines 21-24: the gradients of the batch's views are summed
+// into one buffer). A thread reads its point's parameters once, runs the per-view derivative for every view that uses
+// the point, adds the results up in registers in view order and touches the gradient buffer once: a store (kFirst) or
+// one "+=". View by view the same work reads the parameters and reads and writes the 236-byte gradient row once per
+// view.
+template <int kDeg, bool kFirst>
+__global__ __launch_bounds__(256) void k_preprocess_bwd_batch(SceneDev sc, BatchCams cams, BatchSplatGrads in_all, SceneGradDev g)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = (size_t)n;
+    uint32_t used = 0u;
+    for (int v = 0; v < cams.count; ++v) used |= (in_all.radius[v][i] > 0 ? 1u : 0u) << v;
+    if (used == 0u) {
+        if (kFirst) zero_point_grads<kDeg>(g, i, N);
+        return;
+    }
+    CachedSrc<kDeg> src(sc, i);
+    src.need_shape();
+    src.need_appearance();
+    RegSink<kDeg> acc;
+    for (int v = 0; v < cams.count; ++v) {
+        if (!((used >> v) & 1u)) continue;
+        SplatGradIn in;
+        in.load(in_all.grad[v], i, N);
+        preprocess_point_bwd<kDeg>(cams.cam[v], src, in, acc);
+    }
+    constexpr int K3 = 3 * (kDeg + 1) * (kDeg + 1);
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        grad_out<kFirst>(&g.mean[(size_t)k * N + i], acc.a_mean[k]);
+        grad_out<kFirst>(&g.log_scale[(size_t)k * N + i], acc.a_ls[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) grad_out<kFirst>(&g.quat[(size_t)k * N + i], acc.a_quat[k]);
+    grad_out<kFirst>(&g.logit[i], acc.a_logit);
+#pragma unroll
+    for (int j = 0; j < K3; ++j) grad_out<kFirst>(&g.sh[(size_t)j * N + i], acc.a_sh[j]);
 }
 
 hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, const uint8_t* keep,
@@ -351,6 +552,46 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
     ProfScope prof(kKPreprocessBwd, s);
     if (first_view) launch_preprocess_bwd_t<true>(sc, cam, radius, g2, g, blocks, s);
     else launch_preprocess_bwd_t<false>(sc, cam, radius, g2, g, blocks, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_preprocess_batch(const SceneDev& sc, const BatchCams& cams, const BatchSplats& outs, const uint8_t* keep,
+                                   int group_size, hipStream_t s)
+{
+    if (sc.n == 0 || cams.count == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    const int bpg = keep ? group_size / 256 : 1;
+    const int ng = keep ? (sc.n + group_size - 1) / group_size : 0;
+    ProfScope prof(kKPreprocess, s);
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL(k_preprocess_batch<0>, dim3(blocks), dim3(256), 0, s, sc, cams, outs, keep, bpg, ng); break;
+        case 1: hipLaunchKernelGGL(k_preprocess_batch<1>, dim3(blocks), dim3(256), 0, s, sc, cams, outs, keep, bpg, ng); break;
+        case 2: hipLaunchKernelGGL(k_preprocess_batch<2>, dim3(blocks), dim3(256), 0, s, sc, cams, outs, keep, bpg, ng); break;
+        default: hipLaunchKernelGGL(k_preprocess_batch<3>, dim3(blocks), dim3(256), 0, s, sc, cams, outs, keep, bpg, ng); break;
+    }
+    return hipGetLastError();
+}
+
+template <bool kFirst>
+static void launch_preprocess_bwd_batch_t(const SceneDev& sc, const BatchCams& cams, const BatchSplatGrads& in, const SceneGradDev& g,
+                                          unsigned blocks, hipStream_t s)
+{
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL((k_preprocess_bwd_batch<0, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cams, in, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess_bwd_batch<1, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cams, in, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess_bwd_batch<2, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cams, in, g); break;
+        default: hipLaunchKernelGGL((k_preprocess_bwd_batch<3, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cams, in, g); break;
+    }
+}
+
+hipError_t launch_preprocess_bwd_batch(const SceneDev& sc, const BatchCams& cams, const BatchSplatGrads& in, const SceneGradDev& g,
+                                       bool first_view, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    ProfScope prof(kKPreprocessBwd, s);
+    if (first_view) launch_preprocess_bwd_batch_t<true>(sc, cams, in, g, blocks, s);
+    else launch_preprocess_bwd_batch_t<false>(sc, cams, in, g, blocks, s);
     return hipGetLastError();
 }
 
