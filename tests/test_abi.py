@@ -70,3 +70,55 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.pbdr_render_fwd(C.byref(sp), C.byref(cam), bg, C.c_uint64(100), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16),
                              C.c_void_p(272), C.c_size_t(1 << 30), None) == B.PBDR_ERR_INVALID_ARG
     assert B.lib().pbdr_status_string(C.c_int(-2)).decode() == "workspace too small"
+
+
+def _table3():
+    """{'3dgs': [(name, elems), ...], '2dgs': [...]} from the fixture that restates the paper's Table 3."""
+    out, cur = {}, None
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "table3_state_layout.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("["):
+            cur = line.strip("[]")
+            out[cur] = []
+        else:
+            name, k = line.split()
+            out[cur].append((name, int(k)))
+    return out
+
+
+def _struct_fields(header_text, struct):
+    """[(field, elements per point)] of a state struct of the header, from its '[k][n]' / '[n]' layout comments."""
+    body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (struct, struct), header_text, re.S).group(1)
+    fields = []
+    for m in re.finditer(r"\*\s*(\w+);\s*/\*\s*\[(\d+)\]\[n\]|\*\s*(\w+);\s*/\*\s*\[n\]", body):
+        fields.append((m.group(1), int(m.group(2))) if m.group(1) else (m.group(3), 1))
+    return fields
+
+
+def test_state_layout_is_table_3():
+    """The per-view state that crosses the boundary is the paper's Table 3, field by field: same order, same element
+    counts, 11 and 20 elements per point; the oracle's arrays have the same widths."""
+    t3 = _table3()
+    text = open(os.path.join(ROOT, "include", "pbdr.h")).read()
+    for key, struct in (("3dgs", "pbdr_splats"), ("2dgs", "pbdr2d_splats")):
+        rows = t3[key]
+        assert rows[-1][0] == "total" and rows[-1][1] == sum(k for _, k in rows[:-1])
+        fields = _struct_fields(text, struct)
+        assert [k for _, k in fields] == [k for _, k in rows[:-1]], (struct, fields)
+        # names agree up to the plural and the underscore style
+        for (f, _), (r, _) in zip(fields, rows[:-1]):
+            assert f.replace("_", "")[:4] == r.replace("_", "")[:4], (f, r)
+    assert t3["3dgs"][-1][1] * 4 == 44 and t3["2dgs"][-1][1] * 4 == 80
+
+    import numpy as np
+    import oracle
+    from paper_2512_20017_amd import synth
+    sc, cam = synth.scene_tiny(0), synth.camera_tiny()
+    sp = oracle.preprocess({k: (v.astype(np.float64) if isinstance(v, np.ndarray) else v) for k, v in sc.items()}, cam)
+    widths = dict(mean2d=2, conic=3, opacity=1, color=3, radius=1, depth=1)
+    for (name, k), (field, w) in zip(t3["3dgs"][:-1], widths.items()):
+        assert k == w
+        arr = np.asarray(sp[field])
+        assert (arr.shape[1] if arr.ndim == 2 else 1) == k, field
