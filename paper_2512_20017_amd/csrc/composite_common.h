@@ -99,26 +99,30 @@ __device__ __forceinline__ float row_sum8(const float v[8], bool bit1)
     return d;
 }
 
-// Adds the four rows of 16 lanes of a wavefront lane by lane; the total is valid in lanes 48..63 only.
-// v_permlane16_swap / v_permlane32_swap (gfx950) exchange odd rows (the upper half) of their first operand with even
-// rows (the lower half) of the second: with both operands equal, rows 1 and 3 receive rows 0 and 2, then the upper
-// half receives the lower half. Only the first result of each builtin is used (this compiler hands back the first
-// register for both results of the builtin).
+// Adds the four rows of 16 lanes of a wavefront lane by lane; every row ends up with the total.
+// v_permlane16_swap (gfx950) exchanges the odd rows of its first operand with the even rows of its second, in both
+// registers: from two copies of v = [r0 r1 r2 r3] it leaves [r0 r0 r2 r2] and [r1 r1 r3 r3], whose sum holds r0 + r1 in
+// rows 0, 1 and r2 + r3 in rows 2, 3. v_permlane32_swap does the same with the halves of the wavefront. Written as
+// assembly because both registers are results (the compiler's builtin hands back only one of them correctly); the
+// s_nop covers the wait states between a VALU write of an operand and the swap.
 __device__ __forceinline__ float rows_sum_to_row3(float v)
 {
-    const unsigned u = __builtin_bit_cast(unsigned, v);
-    const float s = v + __builtin_bit_cast(float, __builtin_amdgcn_permlane16_swap(u, u, false, false)[0]);
-    const unsigned us = __builtin_bit_cast(unsigned, s);
-    return s + __builtin_bit_cast(float, __builtin_amdgcn_permlane32_swap(us, us, false, false)[0]);
+    float a = v, b = v;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    const float s = a + b;
+    a = s; b = s;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
 }
 
-// inclusive row scan by shifts: lane 15 of each row ends up with the row sum
+// sum over each row of 16 lanes, left in every lane of the row: partners lane ^ 1, ^ 2, ^ 7 (within eight), ^ 15
 __device__ __forceinline__ float row_sum_to_lane15(float v)
 {
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true));
+    asm volatile("" : "+v"(v));   // keeps a product that feeds v from being fused into the first add (which would cost the DPP form)
+    v += dpp_move<0xB1>(v);    // quad_perm:[1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm:[2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    v += dpp_move<0x140>(v);   // row_mirror
     return v;
 }
 
