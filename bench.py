@@ -170,7 +170,8 @@ def main():
                          "preprocessing calls, next to the per-view calls; not the headline metric")
     ap.add_argument("--train-step", action="store_true",
                     help="time a whole training iteration instead (Alg. 1 on one GPU: splat, render, L1 loss, backward, "
-                         "selective Adam with the gradient zeroed in the same pass); not the headline metric")
+                         "selective Adam; with --separate-zero the Adam pass also zeroes the consumed gradient entries and the "
+                         "backward accumulates); not the headline metric")
     ap.add_argument("--separate-zero", action="store_true",
                     help="clear the gradient buffer with a separate fill each step and accumulate into it, instead of "
                          "letting the backward call write it as the first view of its batch")
@@ -289,17 +290,17 @@ def main():
         lrs = dict(mean=1.6e-4, log_scale=5e-3, quat=1e-3, logit=5e-2, sh=2.5e-3)
         it = [0]
 
-        def step():   # noqa: F811  (the gradient buffer is zero on entry: zeroed once above, then by every Adam pass)
+        def step():   # noqa: F811  (one view per iteration: its backward call writes the whole gradient buffer)
             it[0] += 1
             visible.zero_()
             f_pre(scene, cam, splats)
             B.pbdr_mark_visible(splats.radius, visible)
             f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
             B.pbdr_l1_loss(image, target, loss, dL)
-            f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws)
+            f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws, first_view=not args.separate_zero)
             for k, lr in lrs.items():
                 B.pbdr_adam_selective(getattr(scene, k), getattr(grads, k), getattr(m1, k), getattr(m2, k), visible,
-                                      lr, 0.9, 0.999, 1e-15, it[0], zero_grad=True)
+                                      lr, 0.9, 0.999, 1e-15, it[0], zero_grad=args.separate_zero)
         for t in grad_tensors:
             t.zero_()
 
