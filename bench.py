@@ -143,7 +143,7 @@ def run_batched(args):
             else:
                 B.pbdr_preprocess(scene, cam, splats[v])
             B.pbdr_render_fwd(splats[v], cam, bg, cap, image, final_T, last_idx, ws)
-            B.pbdr_render_bwd(scene, splats[v], cam, bg, cap, final_T, last_idx, dL, g_splats[v], grads, ws, first_view=(v == 0))
+            B.pbdr_render_bwd(scene, splats[v], cam, bg, cap, final_T, last_idx, dL, None, grads, ws, first_view=(v == 0))
 
     names = B.profile_kernel_names()
     out = {}
@@ -201,6 +201,8 @@ def main():
                     help="after the timed region, also time the same step with this many views in flight on separate "
                          "streams (reported as `overlapped`, not as `value`); 1 = skip. With --batch-views: the streams "
                          "the views of a batch are rendered on")
+    ap.add_argument("--splat-grads", action="store_true",
+                    help="have pbdr_render_bwd also write dL/d(splat state) out (nine planes), which the step itself does not need")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -296,6 +298,9 @@ def main():
     examined, blended = f_stats(cam, n, cap, ws)
     sum_last = int(last_idx.to(torch.int64).sum().item())
 
+    # the step's output is dL/d(parameters); the 3D call then need not write dL/d(splat state) out (--splat-grads: do)
+    g_out = g_splats if (surfels or args.splat_grads) else None
+
     def step():
         # One view per step: the backward call is the first view of its batch, so it also does the zeroing of the
         # gradient buffer (it writes every entry of every point: the view's gradient, or zero). --separate-zero clears
@@ -305,7 +310,7 @@ def main():
                 t.zero_()
         f_pre(scene, cam, splats)
         f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
-        f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws, first_view=not args.separate_zero)
+        f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_out, grads, ws, first_view=not args.separate_zero)
 
     if args.train_step:
         args.no_cpu_baseline = True      # the parameters move: the oracle legs below describe the fixed scene only
@@ -323,7 +328,7 @@ def main():
             B.pbdr_mark_visible(splats.radius, visible)
             f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
             B.pbdr_l1_loss(image, target, loss, dL)
-            f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, grads, ws, first_view=not args.separate_zero)
+            f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_out, grads, ws, first_view=not args.separate_zero)
             for k, lr in lrs.items():
                 B.pbdr_adam_selective(getattr(scene, k), getattr(grads, k), getattr(m1, k), getattr(m2, k), visible,
                                       lr, 0.9, 0.999, 1e-15, it[0], zero_grad=args.separate_zero)
@@ -473,7 +478,8 @@ def main():
             with torch.cuda.stream(c["stream"]):
                 f_pre(scene, cam, c["splats"])
                 f_fwd(c["splats"], cam, bg, cap, c["image"], c["final_T"], c["last_idx"], c["ws"])
-                f_bwd(scene, c["splats"], cam, bg, cap, c["final_T"], c["last_idx"], dL, c["g2"], c["grads"], c["ws"], first_view=True)
+                f_bwd(scene, c["splats"], cam, bg, cap, c["final_T"], c["last_idx"], dL, c["g2"] if args.splat_grads else None,
+                      c["grads"], c["ws"], first_view=True)
 
         for i in range(2 * args.streams):
             step_on(ctxs[i % args.streams])

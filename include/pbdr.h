@@ -194,7 +194,9 @@ int pbdr_render_fwd(const pbdr_splats* splats, const pbdr_camera* cam, const flo
 /* image_render.backward then pts_splatting.backward (Alg. 1 lines 17-18 and 22-24). Needs the workspace exactly
  * as pbdr_render_fwd left it for the same splats, camera and dup_capacity. dL_dimage [3][H][W]. g_splats is overwritten with
  * dL/d(splat state). If scene and grads are both non-NULL the parameter gradient is then ACCUMULATED into grads;
- * if both are NULL the call stops after g_splats (the point where the paper's system exchanges gradients). */
+ * if both are NULL the call stops after g_splats (the point where the paper's system exchanges gradients).
+ * g_splats may be NULL when scene and grads are given: the splat-state gradient then stays in the workspace (one
+ * 48-byte record per point) and the second half reads it there, which saves writing and re-reading its nine planes. */
 int pbdr_render_bwd(const pbdr_scene* scene, const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3],
                     uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
                     pbdr_splat_grads* g_splats, pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes,

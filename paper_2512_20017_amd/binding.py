@@ -332,7 +332,8 @@ def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, fin
                     g_splats: SplatGrads, grads, ws, stream=None, first_view=False) -> None:
     """scene/grads: both Scene (gradient accumulated into grads) or both None (stop at g_splats). first_view: write
     instead of accumulating, zeros for points the view does not use (the first view of a batch, buffer not cleared)."""
-    sp, c, g2 = splats.struct(), camera_struct(cam), g_splats.struct()
+    sp, c = splats.struct(), camera_struct(cam)
+    g2 = g_splats.struct() if g_splats is not None else None      # None (with scene/grads given): no splat-state gradient output
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
         sc, g = scene.struct(), grads.struct(first_view)
@@ -340,8 +341,8 @@ def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, fin
     else:
         psc, pg = None, None
     _check(lib().pbdr_render_bwd(psc, C.byref(sp), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(final_T), _dev(last_idx),
-                                 _dev(dL_dimage), C.byref(g2), pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
-                                 _stream(stream)))
+                                 _dev(dL_dimage), C.byref(g2) if g2 is not None else None, pg, C.c_void_p(ws.data_ptr()),
+                                 C.c_size_t(ws.numel()), _stream(stream)))
 
 
 def pbdr_l1_loss(image: torch.Tensor, target: torch.Tensor, loss: torch.Tensor, dL_dimage: torch.Tensor, stream=None) -> None:

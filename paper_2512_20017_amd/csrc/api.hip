@@ -395,9 +395,9 @@ static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, c
                            const uint32_t* last_idx, const float* dL_dimage, pbdr_splat_grads* g_splats,
                            pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) ||
-        !aligned16(dL_dimage) || !check_splat_grads(g_splats, splats->n))
+    if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) || !aligned16(dL_dimage))
         return PBDR_ERR_INVALID_ARG;
+    if (g_splats ? !check_splat_grads(g_splats, splats->n) : scene == nullptr) return PBDR_ERR_INVALID_ARG;
     if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
     if ((scene == nullptr) != (grads == nullptr)) return PBDR_ERR_INVALID_ARG;
     if (scene && (!check_scene(scene) || scene->n != splats->n || !check_scene_grads(grads, scene))) return PBDR_ERR_INVALID_ARG;
@@ -405,10 +405,14 @@ static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, c
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L);
     if (st != PBDR_OK) return st;
     const CamDev c = to_dev(cam, patch);
-    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
-                                        (hipStream_t)hip_stream);
+    const SplatGradDev g2 = g_splats ? dev(g_splats) : SplatGradDev{nullptr, nullptr, nullptr, nullptr};
+    hipError_t e = launch_composite_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, g2, (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
-    return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, dev(g_splats), dev(grads), grads->first_view != 0,
+    if (!g_splats)      // no splat-state gradient asked for: the splatting backward reads the workspace's per-point records
+        return hip_result(launch_preprocess_bwd_records(dev(scene), c, reinterpret_cast<const uint32_t*>((char*)workspace + L.off_touched),
+                                                        reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec), dev(grads),
+                                                        grads->first_view != 0, (hipStream_t)hip_stream));
+    return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, g2, dev(grads), grads->first_view != 0,
                                             (hipStream_t)hip_stream));
 }
 

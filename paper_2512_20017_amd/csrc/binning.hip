@@ -17,9 +17,14 @@ namespace pbdr {
 // preprocessing calls has radius == 0 for every point without a tile; a caller-made state with radius > 0 and an
 // empty tile rectangle is treated as culled here, so every listed point owns at least one pair.
 __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, uint32_t* __restrict__ tiles_touched,
-                                                       uint32_t* __restrict__ vis_block)
+                                                       uint32_t* __restrict__ vis_block, uint32_t* __restrict__ status,
+                                                       uint32_t* __restrict__ ranges, uint32_t nranges)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
+    // first launch of a binning call: the status words and the tile ranges start at zero (every later kernel of the call
+    // comes after this one on the stream)
+    if (i < kStCleared) status[i] = 0u;
+    for (uint32_t k = (uint32_t)i; k < nranges; k += gridDim.x * 256u) ranges[k] = 0u;
     uint32_t t = 0;
     if (i < in.n) {
         const int r = in.radius[i];
@@ -325,7 +330,8 @@ hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
     return hipGetLastError();
 }
 
-// visible points per block of 256, scanned in place; leaves the visible count in the status words
+// visible points per block of 256, scanned in place; leaves the visible count in the status words. Also the call's
+// first launch: clears the status words and the tile ranges.
 hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     const int n = in.n;
@@ -334,7 +340,8 @@ hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Lay
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     const unsigned nb = (unsigned)((n + 255) / 256);
     ProfScope prof(kKCountPack, s);
-    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), vis_block);
+    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), vis_block,
+                       status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
     hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, vis_block, nb, status + kStNumVis);
     return hipGetLastError();
 }
@@ -398,9 +405,8 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
 
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
-    hipError_t e = launch_bin_begin(L, ws, s);
-    if (e != hipSuccess) return e;
-    e = launch_count_pack(sp, cam, L, ws, s);
+    if (sp.n == 0) return launch_bin_begin(L, ws, s);      // nothing to count: only the cleared status words and ranges
+    hipError_t e = launch_count_pack(sp, cam, L, ws, s);
     if (e != hipSuccess) return e;
     return launch_bin_finish(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
 }

@@ -424,8 +424,9 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
         hipLaunchKernelGGL(k_gather_splat_grads, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank,
                            partial, L.cap, carry, rec);
         hipLaunchKernelGGL(k_gather_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
-        hipLaunchKernelGGL(k_grad_records_to_planes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
-                           reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
+        if (g2.mean2d != nullptr)       // else the caller goes on from the records (launch_preprocess_bwd_records)
+            hipLaunchKernelGGL(k_grad_records_to_planes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
+                               reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
     }
     return hipGetLastError();
 }

@@ -142,6 +142,8 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
                              int group_size, hipStream_t s);
 hipError_t launch_group_bounds(const SceneDev& sc, int group_size, float* bounds, hipStream_t s);
 hipError_t launch_group_cull(const CamDev& cam, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
+hipError_t launch_preprocess_bwd_records(const SceneDev& sc, const CamDev& cam, const uint32_t* tiles_touched, const float4* rec,
+                                         const SceneGradDev& g, bool first_view, hipStream_t s);
 hipError_t launch_group_cull_batch(const BatchCams& cams, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
 hipError_t launch_preprocess_batch(const SceneDev& sc, const BatchCams& cams, const BatchSplats& outs, const uint8_t* keep,
                                    int group_size, hipStream_t s);

@@ -275,6 +275,15 @@ struct SplatGradIn {
         opacity = g2.opacity[i];
         color[0] = g2.color[i]; color[1] = g2.color[N + i]; color[2] = g2.color[2 * N + i];
     }
+    // from the 48-byte per-point record the gather of the compositing backward leaves in the workspace
+    __device__ __forceinline__ void load_record(const float4* __restrict__ rec, int i)
+    {
+        const float4 a = rec[(size_t)3 * i], b = rec[(size_t)3 * i + 1], c = rec[(size_t)3 * i + 2];
+        mean2d[0] = a.x; mean2d[1] = a.y;
+        conic[0] = a.z; conic[1] = a.w; conic[2] = b.x;
+        opacity = b.y;
+        color[0] = b.z; color[1] = b.w; color[2] = c.x;
+    }
 };
 
 // Where the parameter gradients of a point go. MemSink puts each value into the caller's buffer as it is produced
@@ -455,22 +464,26 @@ __device__ __forceinline__ void zero_point_grads(const SceneGradDev& g, int i, s
 
 // kFirst: the first view of a batch. The gradient buffer is then written, not added to, and points this view does not
 // use get zeros, so the caller need not clear the buffer beforehand.
-template <int kDeg, bool kFirst>
-__global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ radius,
-                                                        SplatGradDev g2, SceneGradDev g)
+// kFromRecords: the splat-state gradient comes straight from the per-point records of the compositing backward
+// (`rec`), and the points to work on are those binning listed (`used` = tiles touched); otherwise from the planes of
+// g2, for the points with radius > 0 (`used` = radius).
+template <int kDeg, bool kFirst, bool kFromRecords>
+__global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ used,
+                                                        SplatGradDev g2, const float4* __restrict__ rec, SceneGradDev g)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     const size_t N = (size_t)n;
-    if (radius[i] <= 0) {
+    if (used[i] <= 0) {
         if (kFirst) zero_point_grads<kDeg>(g, i, N);
         return;
     }
     DirectSrc<kDeg> src(sc, i);
     src.need_shape();
     SplatGradIn in;
-    in.load(g2, i, N);
+    if (kFromRecords) in.load_record(rec, i);
+    else in.load(g2, i, N);
     MemSink<kDeg, kFirst> sink{g, i, N};
     preprocess_point_bwd<kDeg>(cam, src, in, sink);
 }
@@ -532,15 +545,15 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
     return hipGetLastError();
 }
 
-template <bool kFirst>
-static void launch_preprocess_bwd_t(const SceneDev& sc, const CamDev& cam, const int32_t* radius, const SplatGradDev& g2,
-                                    const SceneGradDev& g, unsigned blocks, hipStream_t s)
+template <bool kFirst, bool kFromRecords>
+static void launch_preprocess_bwd_t(const SceneDev& sc, const CamDev& cam, const int32_t* used, const SplatGradDev& g2,
+                                    const float4* rec, const SceneGradDev& g, unsigned blocks, hipStream_t s)
 {
     switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL((k_preprocess_bwd<0, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-        case 1: hipLaunchKernelGGL((k_preprocess_bwd<1, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-        case 2: hipLaunchKernelGGL((k_preprocess_bwd<2, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
-        default: hipLaunchKernelGGL((k_preprocess_bwd<3, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, radius, g2, g); break;
+        case 0: hipLaunchKernelGGL((k_preprocess_bwd<0, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess_bwd<1, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess_bwd<2, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
+        default: hipLaunchKernelGGL((k_preprocess_bwd<3, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
     }
 }
 
@@ -550,8 +563,22 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    if (first_view) launch_preprocess_bwd_t<true>(sc, cam, radius, g2, g, blocks, s);
-    else launch_preprocess_bwd_t<false>(sc, cam, radius, g2, g, blocks, s);
+    if (first_view) launch_preprocess_bwd_t<true, false>(sc, cam, radius, g2, nullptr, g, blocks, s);
+    else launch_preprocess_bwd_t<false, false>(sc, cam, radius, g2, nullptr, g, blocks, s);
+    return hipGetLastError();
+}
+
+// the same from the per-point gradient records in the workspace (see k_preprocess_bwd)
+hipError_t launch_preprocess_bwd_records(const SceneDev& sc, const CamDev& cam, const uint32_t* tiles_touched, const float4* rec,
+                                         const SceneGradDev& g, bool first_view, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    const int32_t* used = reinterpret_cast<const int32_t*>(tiles_touched);     // counts are far below 2^31
+    const SplatGradDev none{nullptr, nullptr, nullptr, nullptr};
+    ProfScope prof(kKPreprocessBwd, s);
+    if (first_view) launch_preprocess_bwd_t<true, true>(sc, cam, used, none, rec, g, blocks, s);
+    else launch_preprocess_bwd_t<false, true>(sc, cam, used, none, rec, g, blocks, s);
     return hipGetLastError();
 }
 

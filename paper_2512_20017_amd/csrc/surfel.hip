@@ -736,9 +736,9 @@ hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, cons
 
 hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
-    hipError_t e = launch_bin_begin(L, ws, s);
-    if (e != hipSuccess) return e;
-    if (sp.n > 0) {
+    if (sp.n == 0) return launch_bin_begin(L, ws, s);      // nothing to count: only the cleared status words and ranges
+    hipError_t e = hipSuccess;
+    {
         e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
         if (e != hipSuccess) return e;
         ProfScope prof(kKCountPack, s);

@@ -267,3 +267,31 @@ def test_backward_ignores_per_pair_records_of_earlier_calls():
     again = view.render_bwd(BG, G)
     for k in ("mean2d", "conic", "opacity", "color"):
         np.testing.assert_allclose(again[k][vis], full[k][vis], rtol=1e-4, atol=1e-5 * np.abs(full[k][vis]).max())
+
+
+@pytest.mark.parametrize("first", [True, False])
+def test_backward_without_splat_gradient_output(case, first):
+    """pbdr_render_bwd with g_splats = NULL: the splat-state gradient stays in the workspace's per-point records and the
+    splatting backward reads it there. Same parameter gradient as with the output (to the rounding of the compositing
+    kernel's LDS adds, whose order is not fixed), both as a store and as an accumulation; NULL without a scene is an
+    error."""
+    view, cam, scene = case["view"], case["cam"], case["scene"]
+    W, H = cam["width"], cam["height"]
+    view.preprocess(scene)
+    view.render_fwd(BG)
+    G = to_chw_dev(np.random.default_rng(6).normal(size=(H, W, 3)).astype(np.float32))
+    start = torch.from_numpy(np.random.default_rng(7).normal(size=scene.zeros_like().flat.shape).astype(np.float32)).cuda()
+    out = []
+    for g2 in (view.g_splats, None):
+        grads = scene.zeros_like()
+        grads.flat.copy_(start)
+        B.pbdr_render_bwd(scene, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, G, g2, grads, view.ws,
+                          first_view=first)
+        torch.cuda.synchronize()
+        out.append(grads.to_numpy())
+    for k in ("mean", "log_scale", "quat", "logit", "sh"):
+        scale = np.abs(out[0][k]).max()
+        assert scale > 0
+        np.testing.assert_allclose(out[1][k], out[0][k], rtol=1e-4, atol=1e-5 * scale, err_msg=k)
+    with pytest.raises(B.PbdrError):
+        B.pbdr_render_bwd(None, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, G, None, None, view.ws)
