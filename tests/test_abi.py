@@ -72,6 +72,38 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert B.lib().pbdr_status_string(C.c_int(-2)).decode() == "workspace too small"
 
 
+def test_batch_calls_reject_bad_arguments_on_the_host():
+    L = B.lib()
+    cam = dict(width=64, height=64, fx=50, fy=50, cx=32, cy=32, R=[1, 0, 0, 0, 1, 0, 0, 0, 1], t=[0, 0, 3])
+    sc = B.CScene(8, 0, 16, 16, 16, 16, 16)
+    grads = B.CScene(8, 0, 16, 16, 16, 16, 16, 0)
+
+    def arrays(count, n=8):
+        cams = (B.CCamera * count)(*[B.camera_struct(cam) for _ in range(count)])
+        sps = (B.CSplats * count)(*[B.CSplats(n, 16, 16, 16, 16, 16, 16) for _ in range(count)])
+        g2s = (B.CSplatGrads * count)(*[B.CSplatGrads(n, 16, 16, 16, 16) for _ in range(count)])
+        return cams, sps, g2s
+
+    cams, sps, g2s = arrays(17)
+    for count in (0, -1, 17):          # 1 .. PBDR_MAX_BATCH_VIEWS views
+        assert L.pbdr_preprocess_batch(C.byref(sc), C.c_int32(count), cams, sps, C.c_int32(0), None, None, None) == B.PBDR_ERR_INVALID_ARG
+        assert L.pbdr_preprocess_bwd_batch(C.byref(sc), C.c_int32(count), cams, sps, g2s, C.byref(grads), None) == B.PBDR_ERR_INVALID_ARG
+    cams, sps, g2s = arrays(2)
+    assert L.pbdr_preprocess_batch(C.byref(sc), C.c_int32(2), None, sps, C.c_int32(0), None, None, None) == B.PBDR_ERR_INVALID_ARG
+    assert L.pbdr_preprocess_batch(C.byref(sc), C.c_int32(2), cams, sps, C.c_int32(300), None, None, None) == B.PBDR_ERR_INVALID_ARG
+    # group test asked for, but no bounds / keep
+    assert L.pbdr_preprocess_batch(C.byref(sc), C.c_int32(2), cams, sps, C.c_int32(256), None, None, None) == B.PBDR_ERR_INVALID_ARG
+    _, odd, _ = arrays(2, n=9)         # a view whose arrays are sized for another cloud
+    assert L.pbdr_preprocess_batch(C.byref(sc), C.c_int32(2), cams, odd, C.c_int32(0), None, None, None) == B.PBDR_ERR_INVALID_ARG
+    assert L.pbdr_preprocess_bwd_batch(C.byref(sc), C.c_int32(2), cams, sps, g2s, None, None) == B.PBDR_ERR_INVALID_ARG
+    # pbdr_render_bwd: no splat-state gradient output only together with a scene
+    bg = (C.c_float * 3)(0, 0, 0)
+    sp = B.CSplats(8, 16, 16, 16, 16, 16, 16)
+    c1 = B.camera_struct(cam)
+    assert L.pbdr_render_bwd(None, C.byref(sp), C.byref(c1), bg, C.c_uint64(100), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16),
+                             None, None, C.c_void_p(256), C.c_size_t(1 << 30), None) == B.PBDR_ERR_INVALID_ARG
+
+
 def _table3():
     """{'3dgs': [(name, elems), ...], '2dgs': [...]} from the fixture that restates the paper's Table 3."""
     out, cur = {}, None
