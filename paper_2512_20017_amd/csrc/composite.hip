@@ -24,28 +24,17 @@ __device__ __forceinline__ float qform(float A, float B, float C, float dx, floa
 }
 
 // Minimum of the positive-definite form q over the rectangle [lx,hx] x [ly,hy] (offsets from the splat centre).
+// With (xs, ys) the point of the rectangle nearest the centre coordinate by coordinate, the minimum lies on the
+// segment x = xs or on the segment y = ys of the rectangle: q is convex with its minimum 0 at the centre, so from the
+// minimiser a step towards the centre must leave the rectangle, which makes x = xs or y = ys there (and if the centre
+// is inside, both segments pass through it). Two one-dimensional minimisations instead of one per edge.
 __device__ __forceinline__ float qform_min_rect(float A, float B, float C, float lx, float hx, float ly, float hy)
 {
-    if (lx <= 0.f && hx >= 0.f && ly <= 0.f && hy >= 0.f) return 0.f;
+    const float xs = fminf(hx, fmaxf(lx, 0.f)), ys = fminf(hy, fmaxf(ly, 0.f));
     const float i2C = 0.5f / C, i2A = 0.5f / A;
-    float best;
-    {
-        const float dy = fminf(hy, fmaxf(ly, -B * lx * i2C));
-        best = qform(A, B, C, lx, dy);
-    }
-    {
-        const float dy = fminf(hy, fmaxf(ly, -B * hx * i2C));
-        best = fminf(best, qform(A, B, C, hx, dy));
-    }
-    {
-        const float dx = fminf(hx, fmaxf(lx, -B * ly * i2A));
-        best = fminf(best, qform(A, B, C, dx, ly));
-    }
-    {
-        const float dx = fminf(hx, fmaxf(lx, -B * hy * i2A));
-        best = fminf(best, qform(A, B, C, dx, hy));
-    }
-    return best;
+    const float yv = fminf(hy, fmaxf(ly, -B * xs * i2C));
+    const float xh = fminf(hx, fmaxf(lx, -B * ys * i2A));
+    return fminf(qform(A, B, C, xs, yv), qform(A, B, C, xh, ys));
 }
 
 constexpr int kAccStride = 9;    // floats between the LDS accumulators of consecutive splats of a batch (odd)
@@ -63,9 +52,12 @@ struct Stage {
 
 // Stage list entries [first, first+count) of the tile: one per thread. Returns this thread's splat index, raw
 // conic/opacity and (mean2d, extent) for callers that need them (backward). All 256 threads must call it.
+// reach: one byte per list position, bit q = "this splat can reach quadrant q". The forward pass works the bits out
+// and stores them (kReuse = false); the backward pass, which walks a prefix of the same lists, reads them back.
+template <bool kReuse>
 __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const uint32_t* __restrict__ vals,
-                                            const Packed* __restrict__ packed, uint32_t first, int count, uint32_t& id,
-                                            float4& raw, float4& geo)
+                                            const Packed* __restrict__ packed, uint8_t* __restrict__ reach_bits, uint32_t first,
+                                            int count, uint32_t& id, float4& raw, float4& geo)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool have = (int)threadIdx.x < count;
@@ -83,23 +75,30 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
         S.rec[threadIdx.x].a = make_float4(mx, my, A, B);
         S.rec[threadIdx.x].b = make_float4(C, L, r1.z, r1.w);
         S.rec[threadIdx.x].c = r2.x;
-        // alpha >= 1/255  <=>  q(d) <= L + log2(255)
-        const float tau = L + kLog2_255;
-        const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
-        if (!(tau < -0.05f)) {
+        if (kReuse) {
+            const uint32_t bits = reach_bits[first + threadIdx.x];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float lx = (float)(t.tx0 + (q & 1) * 8) + 0.5f - mx, hx = lx + 7.f;
-                const float ly = (float)(t.ty0 + (q >> 1) * 8) + 0.5f - my, hy = ly + 7.f;
-                bool keep = true;
-                if (pd) {
-                    const float mn = qform_min_rect(A, B, C, lx, hx, ly, hy);
-                    const float mxd = fmaxf(fabsf(lx), fabsf(hx)), myd = fmaxf(fabsf(ly), fabsf(hy));
-                    const float big = A * mxd * mxd + C * myd * myd + fabsf(B) * mxd * myd;
-                    keep = !(mn > tau + 0.05f + 4e-6f * big);   // conservative: rounding can only keep more
+            for (int q = 0; q < 4; ++q) reach[q] = ((bits >> q) & 1u) != 0;
+        } else {
+            // alpha >= 1/255  <=>  q(d) <= L + log2(255)
+            const float tau = L + kLog2_255;
+            const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
+            if (!(tau < -0.05f)) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float lx = (float)(t.tx0 + (q & 1) * 8) + 0.5f - mx, hx = lx + 7.f;
+                    const float ly = (float)(t.ty0 + (q >> 1) * 8) + 0.5f - my, hy = ly + 7.f;
+                    bool keep = true;
+                    if (pd) {
+                        const float mn = qform_min_rect(A, B, C, lx, hx, ly, hy);
+                        const float mxd = fmaxf(fabsf(lx), fabsf(hx)), myd = fmaxf(fabsf(ly), fabsf(hy));
+                        const float big = A * mxd * mxd + C * myd * myd + fabsf(B) * mxd * myd;
+                        keep = !(mn > tau + 0.05f + 4e-6f * big);   // conservative: rounding can only keep more
+                    }
+                    reach[q] = keep;
                 }
-                reach[q] = keep;
             }
+            reach_bits[first + threadIdx.x] = (uint8_t)((reach[0] ? 1u : 0u) | (reach[1] ? 2u : 0u) | (reach[2] ? 4u : 0u) | (reach[3] ? 8u : 0u));
         }
     }
 #pragma unroll
@@ -111,8 +110,9 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
 
 __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
-                                                       float bg0, float bg1, float bg2, float* __restrict__ image,
-                                                       float* __restrict__ final_T, uint32_t* __restrict__ last_idx)
+                                                       uint8_t* __restrict__ reach_bits, float bg0, float bg1, float bg2,
+                                                       float* __restrict__ image, float* __restrict__ final_T,
+                                                       uint32_t* __restrict__ last_idx)
 {
     __shared__ Stage S;
     const TileCtx c = tile_ctx(cam, ranges);
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
         if (__syncthreads_count(live) == 0) break;   // also fences the previous batch's LDS reads
         const int cnt = (int)min((uint32_t)kBatch, c.end - base);
         uint32_t id; float4 raw, geo;
-        stage_batch(S, c, vals, packed, base, cnt, id, raw, geo);
+        stage_batch<false>(S, c, vals, packed, reach_bits, base, cnt, id, raw, geo);
         __syncthreads();
         if (__ballot(live) == 0ull) continue;          // this quadrant is finished (uniform per wavefront)
         const uint32_t pos0 = base - c.start + 1u;
@@ -175,8 +175,9 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
 // (k_gather_splat_grads).
 __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
-                                                       const uint32_t* __restrict__ slot_base, float bg0, float bg1, float bg2,
-                                                       const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
+                                                       uint8_t* __restrict__ reach_bits, const uint32_t* __restrict__ slot_base,
+                                                       float bg0, float bg1, float bg2, const float* __restrict__ final_T,
+                                                       const uint32_t* __restrict__ last_idx,
                                                        const float* __restrict__ dL_dimage, uint32_t cap,
                                                        const uint32_t* __restrict__ status, float4* __restrict__ partial)
 {
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
         const int cnt = (int)min((uint32_t)kBatch, tile_last - boff);
         uint32_t id; float4 raw, geo;
-        stage_batch(S, c, vals, packed, c.start + boff, cnt, id, raw, geo);
+        stage_batch<true>(S, c, vals, packed, reach_bits, c.start + boff, cnt, id, raw, geo);
 #pragma unroll
         for (int k = 0; k < kAccStride; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
         __syncthreads();
@@ -394,8 +395,8 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     ProfScope prof(kKCompositeFwd, s);
-    hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed, bg[0], bg[1],
-                       bg[2], image, final_T, last_idx);
+    hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed,
+                       reinterpret_cast<uint8_t*>(ws + L.off_reach), bg[0], bg[1], bg[2], image, final_T, last_idx);
     return hipGetLastError();
 }
 
@@ -412,8 +413,9 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
     {
         ProfScope prof(kKCompositeBwd, s);
-        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed, slot_base,
-                           bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, status, partial);
+        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed,
+                           reinterpret_cast<uint8_t*>(ws + L.off_reach), slot_base, bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage,
+                           L.cap, status, partial);
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
