@@ -275,12 +275,6 @@ __global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status
     if (i < nranges) ranges[i] = 0u;
 }
 
-__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, size_t count)
-{
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < count) p[i] = v;
-}
-
 // One thread per sorted pair: mark where each tile's run starts and ends.
 __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict__ tkeys, const uint32_t* __restrict__ status,
                                                      uint32_t cap, uint32_t ntiles, uint32_t* __restrict__ ranges)
@@ -320,10 +314,8 @@ hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s)
 hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
 {
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
-    uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
     uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
     // status words and tile ranges start at zero (one launch)
-    (void)totals;
     ProfScope prof(kKFill, s);
     hipLaunchKernelGGL(k_bin_begin, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, status, ranges,
                        2 * (size_t)L.tiles);

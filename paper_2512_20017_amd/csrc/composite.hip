@@ -141,11 +141,12 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
                 const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                 const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
                 const bool valid = live && (q >= 0.f) && (alpha >= kAlphaMin);
-                const float Tn = T * (1.f - alpha);
+                const float aT = alpha * T;
+                const float Tn = T - aT;            // T (1 - alpha), with the product the weight needs anyway
                 const bool stop = valid && (Tn < kTStop);
                 const bool blend = valid && !stop;
                 live = live && !stop;
-                const float w = blend ? alpha * T : 0.f;
+                const float w = blend ? aT : 0.f;
                 C0 += b.z * w; C1 += b.w * w; C2 += cb * w;
                 T = blend ? Tn : T;
                 last = blend ? pos0 + (uint32_t)j : last;
@@ -207,8 +208,8 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     if (tile_last == 0) return;
     const int tile_x = c.tix, tile_y = c.tiy;
     // One LDS add per visit, by nine lanes. After the row butterfly (row_sum8) lanes 2k and 2k+1 of each row carry
-    // value k and lane 15 is given the row's blue sum; the four rows are then added lane by lane into row 3, whose
-    // even lanes and lane 63 add. (LDS float adds cost LDS time per active lane and per address clash, and the LDS
+    // value k and lane 15 is given the row's blue sum; the four rows are then added lane by lane (every row ends up
+    // with the total) and the even lanes of the last row and lane 63 add. (LDS float adds cost LDS time per active lane and per address clash, and the LDS
     // pipe, not the VALU, bounded this kernel when all four rows issued their own adds.)
     const bool bit1 = (lane & 2) != 0;
     const bool blue_lane = (lane & 15) == 15;
@@ -251,8 +252,8 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                     const float dsx = ds * dx, dsy = ds * dy;
                     const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
                     const float part = row_sum8(v8, bit1);
-                    const float blue = row_sum_to_lane15(w * g2c);
-                    const float tot = rows_sum_to_row3(blue_lane ? blue : part);
+                    const float blue = row_sum16(w * g2c);
+                    const float tot = sum_rows(blue_lane ? blue : part);
                     int acc_base = kAccStride * j;
                     asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (else a quarter-rate VALU mad)
                     if (add_lane) atomicAdd(&sAcc[acc_base + acc_slot], tot);
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(256) void k_render_stats(CamDev cam, const uint32_t
                 if (sigma < 0.f) continue;
                 const float alpha = fminf(kAlphaMax, b.y * __expf(-sigma));
                 if (alpha < kAlphaMin) continue;
-                const float Tn = T * (1.f - alpha);
+                const float Tn = T - alpha * T;     // as the forward kernel forms it
                 if (Tn < kTStop) { done = true; break; }
                 T = Tn;
                 ++blended;

@@ -41,19 +41,6 @@ __device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v)
     return ((unsigned long long)hi << 32) | lo;
 }
 
-// Sum over the 64 lanes of a wavefront with DPP row shifts and row broadcasts (no LDS traffic); the total ends
-// up in lane 63 and is returned in every lane through a readlane.
-__device__ __forceinline__ float wave_sum(float v)
-{
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true));  // row_shr:1
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true));  // row_shr:2
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true));  // row_shr:4
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true));  // row_shr:8
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xa, 0xf, false)); // row_bcast:15
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xc, 0xf, false)); // row_bcast:31
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-
 template <int kCtrl>
 __device__ __forceinline__ float dpp_move(float v)
 {
@@ -105,7 +92,7 @@ __device__ __forceinline__ float row_sum8(const float v[8], bool bit1)
 // rows 0, 1 and r2 + r3 in rows 2, 3. v_permlane32_swap does the same with the halves of the wavefront. Written as
 // assembly because both registers are results (the compiler's builtin hands back only one of them correctly); the
 // s_nop covers the wait states between a VALU write of an operand and the swap.
-__device__ __forceinline__ float rows_sum_to_row3(float v)
+__device__ __forceinline__ float sum_rows(float v)
 {
     float a = v, b = v;
     asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
@@ -116,7 +103,7 @@ __device__ __forceinline__ float rows_sum_to_row3(float v)
 }
 
 // sum over each row of 16 lanes, left in every lane of the row: partners lane ^ 1, ^ 2, ^ 7 (within eight), ^ 15
-__device__ __forceinline__ float row_sum_to_lane15(float v)
+__device__ __forceinline__ float row_sum16(float v)
 {
     asm volatile("" : "+v"(v));   // keeps a product that feeds v from being fused into the first add (which would cost the DPP form)
     v += dpp_move<0xB1>(v);    // quad_perm:[1,0,3,2]

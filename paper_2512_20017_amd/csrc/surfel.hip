@@ -439,11 +439,12 @@ __global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint3
                 const float ex = (E.p2 != 0.f) ? fmaxf(E.e1, E.e2) : -1e30f;
                 const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.w + ex));
                 const bool valid = live && (E.p2 != 0.f) && (alpha >= kAlphaMin);
-                const float Tn = T * (1.f - alpha);
+                const float aT = alpha * T;
+                const float Tn = T - aT;            // T (1 - alpha), with the product the weight needs anyway
                 const bool stop = valid && (Tn < kTStop);
                 const bool blend = valid && !stop;
                 live = live && !stop;
-                const float w = blend ? alpha * T : 0.f;
+                const float w = blend ? aT : 0.f;
                 C0 += cc.z * w; C1 += cc.w * w; C2 += blue * w;
                 T = blend ? Tn : T;
                 last = blend ? pos0 + (uint32_t)j : last;
@@ -550,8 +551,8 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                     const float pa = row_sum8(va, bit1);
                     const float pb = row_sum8(vb, bit1);
                     // even lanes of a row keep the first eight sums, odd lanes (their copies) take the second eight;
-                    // the four rows are added lane by lane into row 3, whose 16 lanes issue the one LDS add
-                    const float tot = rows_sum_to_row3((lane & 1) ? pb : pa);
+                    // the four rows are added lane by lane, and the 16 lanes of the last row issue the one LDS add
+                    const float tot = sum_rows((lane & 1) ? pb : pa);
                     if (lane >= 48) atomicAdd(&sAcc[kAccStride2D * j + acc_slot], tot);
                 }
             }
@@ -670,7 +671,7 @@ __global__ __launch_bounds__(256) void k_render_stats2d(CamDev cam, const uint32
                 if (E.p2 == 0.f) continue;
                 const float alpha = fminf(kAlphaMax, b.w * __builtin_amdgcn_exp2f(fmaxf(E.e1, E.e2)));
                 if (!(alpha >= kAlphaMin)) continue;
-                const float Tn = T * (1.f - alpha);
+                const float Tn = T - alpha * T;     // as the forward kernel forms it
                 if (Tn < kTStop) { done = true; break; }
                 T = Tn;
                 ++blended;
