@@ -194,6 +194,9 @@ def main():
                     help="time a whole training iteration instead (Alg. 1 on one GPU: splat, render, L1 loss, backward, "
                          "selective Adam; with --separate-zero the Adam pass also zeroes the consumed gradient entries and the "
                          "backward accumulates); not the headline metric")
+    ap.add_argument("--unfused-adam", action="store_true",
+                    help="with --train-step: splatting backward into the gradient buffer, then pbdr_adam_selective per "
+                         "attribute, instead of the one-pass pbdr_preprocess_bwd_batch_adam")
     ap.add_argument("--separate-zero", action="store_true",
                     help="clear the gradient buffer with a separate fill each step and accumulate into it, instead of "
                          "letting the backward call write it as the first view of its batch")
@@ -323,11 +326,18 @@ def main():
 
         def step():   # noqa: F811  (one view per iteration: its backward call writes the whole gradient buffer)
             it[0] += 1
-            visible.zero_()
             f_pre(scene, cam, splats)
-            B.pbdr_mark_visible(splats.radius, visible)
+            if args.unfused_adam:
+                visible.zero_()
+                B.pbdr_mark_visible(splats.radius, visible)
             f_fwd(splats, cam, bg, cap, image, final_T, last_idx, ws)
             B.pbdr_l1_loss(image, target, loss, dL)
+            if not args.unfused_adam:
+                # compositing backward stops at dL/d(splat state); the splatting backward and the Adam step are one pass
+                f_bwd(None, splats, cam, bg, cap, final_T, last_idx, dL, g_splats, None, ws)
+                B.pbdr_preprocess_bwd_batch_adam(scene, [cam], [splats], [g_splats], m1, m2, list(lrs.values()), 0.9, 0.999,
+                                                 1e-15, it[0])
+                return
             f_bwd(scene, splats, cam, bg, cap, final_T, last_idx, dL, g_out, grads, ws, first_view=not args.separate_zero)
             for k, lr in lrs.items():
                 B.pbdr_adam_selective(getattr(scene, k), getattr(grads, k), getattr(m1, k), getattr(m2, k), visible,

@@ -361,6 +361,16 @@ int pbdr_mark_visible(int32_t n, const int32_t* radius, uint8_t* visible, void* 
 int pbdr_adam_selective(int32_t n, int32_t planes, float* param, float* grad, float* exp_avg, float* exp_avg_sq,
                         const uint8_t* visible, const pbdr_adam_config* cfg, void* hip_stream);
 
+/* pts_splatting.backward for the views of a batch and the optimizer step in one pass over the points (Alg. 1 lines
+ * 21-27): exactly what pbdr_preprocess_bwd_batch with first_view = 1, pbdr_mark_visible once per view and
+ * pbdr_adam_selective once per attribute do, bit for bit, without the parameter gradient going through memory.
+ * The arrays `scene` points to are UPDATED IN PLACE for the points at least one view uses (radius > 0); exp_avg and
+ * exp_avg_sq are the two Adam moments, laid out like the scene (their first_view field is ignored). lr[5]: learning
+ * rates of mean, log_scale, quat, opacity_logit, sh. Of cfg, beta1, beta2, eps and step are used. */
+int pbdr_preprocess_bwd_batch_adam(const pbdr_scene* scene, int32_t num_views, const pbdr_camera* cams, const pbdr_splats* splats,
+                                   const pbdr_splat_grads* g_splats, pbdr_scene_grads* exp_avg, pbdr_scene_grads* exp_avg_sq,
+                                   const float lr[5], const pbdr_adam_config* cfg, void* hip_stream);
+
 /* Optional per-kernel timing for benchmarks, with HIP events recorded on the stream each kernel is launched on.
  * kernel_mask: bit i enables kernel id i (ids 0 .. pbdr_profile_kernel_count()-1, names from
  * pbdr_profile_kernel_name). At most max_records launches are timed between begin/reset and collect.

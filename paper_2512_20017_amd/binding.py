@@ -30,7 +30,8 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr2d_lists_view", "pbdr2d_render_stats", "pbdr_group_count", "pbdr_group_bounds", "pbdr_preprocess_grouped",
            "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
            "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch",
-           "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective", "pbdr_preprocess_batch", "pbdr_preprocess_bwd_batch")
+           "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective", "pbdr_preprocess_batch", "pbdr_preprocess_bwd_batch",
+           "pbdr_preprocess_bwd_batch_adam")
 
 _f = C.POINTER(C.c_float)
 
@@ -313,6 +314,21 @@ def pbdr_preprocess_bwd_batch(scene: Scene, cams, splats, g_splats, grads: Scene
     sp_arr = (type(sps[0]) * len(sps))(*sps)
     g2_arr = (type(g2s[0]) * len(g2s))(*g2s)
     _check(lib().pbdr_preprocess_bwd_batch(C.byref(sc), C.c_int32(len(cams)), cs, sp_arr, g2_arr, C.byref(g), _stream(stream)))
+
+
+def pbdr_preprocess_bwd_batch_adam(scene: Scene, cams, splats, g_splats, exp_avg: Scene, exp_avg_sq: Scene, lrs, beta1, beta2, eps,
+                                   step: int, stream=None) -> None:
+    """lrs: learning rates of (mean, log_scale, quat, logit, sh). Updates the scene's tensors and both moments in place."""
+    sc, m, v = scene.struct(), exp_avg.struct(), exp_avg_sq.struct()
+    cs = (CCamera * len(cams))(*[camera_struct(c) for c in cams])
+    sps = [x.struct() for x in splats]
+    g2s = [x.struct() for x in g_splats]
+    sp_arr = (type(sps[0]) * len(sps))(*sps)
+    g2_arr = (type(g2s[0]) * len(g2s))(*g2s)
+    lr = (C.c_float * 5)(*[float(x) for x in lrs])
+    cfg = CAdamConfig(0.0, float(beta1), float(beta2), float(eps), int(step), 0)
+    _check(lib().pbdr_preprocess_bwd_batch_adam(C.byref(sc), C.c_int32(len(cams)), cs, sp_arr, g2_arr, C.byref(m), C.byref(v), lr,
+                                                C.byref(cfg), _stream(stream)))
 
 
 def pbdr_bin_sort(splats: Splats, cam: dict, dup_capacity: int, ws: torch.Tensor, stream=None) -> None:

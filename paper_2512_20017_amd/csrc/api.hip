@@ -621,6 +621,38 @@ int pbdr_adam_selective(int32_t n, int32_t planes, float* param, float* grad, fl
                                             cfg->beta2, cfg->eps, cfg->step, cfg->zero_grad, (hipStream_t)hip_stream));
 }
 
+int pbdr_preprocess_bwd_batch_adam(const pbdr_scene* scene, int32_t num_views, const pbdr_camera* cams, const pbdr_splats* splats,
+                                   const pbdr_splat_grads* g_splats, pbdr_scene_grads* exp_avg, pbdr_scene_grads* exp_avg_sq,
+                                   const float lr[5], const pbdr_adam_config* cfg, void* hip_stream)
+{
+    if (!check_scene(scene) || num_views < 1 || num_views > PBDR_MAX_BATCH_VIEWS || !cams || !splats || !g_splats || !lr || !cfg ||
+        !check_scene_grads(exp_avg, scene) || !check_scene_grads(exp_avg_sq, scene))
+        return PBDR_ERR_INVALID_ARG;
+    if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f) || !(cfg->eps > 0.f) || cfg->step < 1)
+        return PBDR_ERR_INVALID_ARG;
+    BatchCams bc;
+    BatchSplatGrads bg;
+    BatchAdam opt;
+    bc.count = num_views;
+    for (int v = 0; v < num_views; ++v) {
+        if (!check_camera(&cams[v]) || !check_splats(&splats[v]) || splats[v].n != scene->n ||
+            !check_splat_grads(&g_splats[v], scene->n))
+            return PBDR_ERR_INVALID_ARG;
+        bc.cam[v] = to_dev(&cams[v]);
+        bg.radius[v] = splats[v].radius;
+        bg.grad[v] = dev(&g_splats[v]);
+    }
+    for (int v = num_views; v < kMaxBatchViews; ++v) { bc.cam[v] = bc.cam[0]; bg.radius[v] = bg.radius[0]; bg.grad[v] = bg.grad[0]; }
+    for (int a = 0; a < 5; ++a) {
+        if (!(lr[a] >= 0.f)) return PBDR_ERR_INVALID_ARG;
+        opt.attr[a] = make_adam(lr[a], cfg->beta1, cfg->beta2, cfg->eps, cfg->step, 0);
+    }
+    const SceneGradDev m = dev(exp_avg), v2 = dev(exp_avg_sq);
+    opt.m_mean = m.mean; opt.m_log_scale = m.log_scale; opt.m_quat = m.quat; opt.m_logit = m.logit; opt.m_sh = m.sh;
+    opt.v_mean = v2.mean; opt.v_log_scale = v2.log_scale; opt.v_quat = v2.quat; opt.v_logit = v2.logit; opt.v_sh = v2.sh;
+    return hip_result(launch_preprocess_bwd_batch_adam(dev(scene), bc, bg, opt, (hipStream_t)hip_stream));
+}
+
 int pbdr_query_lists(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
                      uint64_t dup_capacity, void* hip_stream, uint64_t* num_dup)
 {

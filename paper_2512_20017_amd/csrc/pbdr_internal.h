@@ -191,6 +191,31 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
 hipError_t launch_render_stats2d(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
 
 // loss and optimizer step (Alg. 1 lines 13, 16, 27)
+// Adam with bias correction for one value (Alg. 1 line 27). The constants are formed on the host in double.
+struct AdamDev {
+    float beta1, beta2, one_m_beta1, one_m_beta2;
+    float step_size;      // lr / (1 - beta1^t)
+    float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^t)
+    float eps;
+    int zero_grad;
+};
+AdamDev make_adam(float lr, float beta1, float beta2, float eps, int step, int zero_grad);
+
+__device__ __forceinline__ void adam_one(const AdamDev& c, float& p, float g, float& m, float& v)
+{
+#pragma clang fp contract(off)      // the same roundings wherever this is inlined (see preprocess.hip)
+    m = c.beta1 * m + c.one_m_beta1 * g;
+    v = c.beta2 * v + c.one_m_beta2 * g * g;
+    p -= c.step_size * m / (sqrtf(v) * c.inv_sqrt_bc2 + c.eps);
+}
+
+struct BatchAdam {          // one AdamDev per attribute: mean, log_scale, quat, opacity logit, SH
+    AdamDev attr[5];
+    float *m_mean, *m_log_scale, *m_quat, *m_logit, *m_sh;
+    float *v_mean, *v_log_scale, *v_quat, *v_logit, *v_sh;
+};
+hipError_t launch_preprocess_bwd_batch_adam(const SceneDev& sc, const BatchCams& cams, const BatchSplatGrads& in, const BatchAdam& opt,
+                                            hipStream_t s);
 hipError_t launch_l1_loss(int W, int H, const float* image, const float* target, float* loss, float* dL, hipStream_t s);
 hipError_t launch_mark_visible(int n, const int32_t* radius, uint8_t* visible, hipStream_t s);
 hipError_t launch_adam_selective(int n, int planes, float* param, float* grad, float* exp_avg, float* exp_avg_sq,

@@ -529,6 +529,61 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd_batch(SceneDev sc, Batch
     for (int j = 0; j < K3; ++j) grad_out<kFirst>(&g.sh[(size_t)j * N + i], acc.a_sh[j]);
 }
 
+// The same, with the optimizer step in the same pass (Alg. 1 lines 21-27 for one batch): the summed gradient of a point
+// never leaves the registers; the thread updates the point's 11 + 3K parameters and both Adam moments in place. Points no
+// view of the batch uses are left alone (the "selective" Adam of App. E.1: the union of the views' visible points).
+template <int kDeg>
+__global__ __launch_bounds__(256) void k_preprocess_bwd_batch_adam(SceneDev sc, BatchCams cams, BatchSplatGrads in_all, BatchAdam opt)
+{
+    const int n = sc.n;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = (size_t)n;
+    uint32_t used = 0u;
+    for (int v = 0; v < cams.count; ++v) used |= (in_all.radius[v][i] > 0 ? 1u : 0u) << v;
+    if (used == 0u) return;
+    CachedSrc<kDeg> src(sc, i);
+    src.need_shape();
+    src.need_appearance();
+    RegSink<kDeg> acc;
+    for (int v = 0; v < cams.count; ++v) {
+        if (!((used >> v) & 1u)) continue;
+        SplatGradIn in;
+        in.load(in_all.grad[v], i, N);
+        preprocess_point_bwd<kDeg>(cams.cam[v], src, in, acc);
+    }
+    constexpr int K3 = 3 * (kDeg + 1) * (kDeg + 1);
+    // parameter planes are written through the scene's own pointers
+    float* p_mean = const_cast<float*>(sc.mean);
+    float* p_ls = const_cast<float*>(sc.log_scale);
+    float* p_quat = const_cast<float*>(sc.quat);
+    float* p_logit = const_cast<float*>(sc.logit);
+    float* p_sh = const_cast<float*>(sc.sh);
+    // Entries are taken in runs of up to 16: all moments of a run are asked for before the first is used, so the run
+    // costs one memory round trip and not one per entry.
+    auto run = [&](int attr, float* param, float* mom1, float* mom2, const float* value, const float* grad, int first, int count) {
+        float m[16], v2[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < count) { const size_t at = (size_t)(first + k) * N + i; m[k] = mom1[at]; v2[k] = mom2[at]; }
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < count) {
+                const size_t at = (size_t)(first + k) * N + i;
+                float p = value[first + k];
+                adam_one(opt.attr[attr], p, grad[first + k], m[k], v2[k]);
+                param[at] = p; mom1[at] = m[k]; mom2[at] = v2[k];
+            }
+    };
+    run(0, p_mean, opt.m_mean, opt.v_mean, src.m, acc.a_mean, 0, 3);
+    run(1, p_ls, opt.m_log_scale, opt.v_log_scale, src.ls, acc.a_ls, 0, 3);
+    run(2, p_quat, opt.m_quat, opt.v_quat, src.qr, acc.a_quat, 0, 4);
+    run(3, p_logit, opt.m_logit, opt.v_logit, &src.lg, &acc.a_logit, 0, 1);
+#pragma unroll
+    for (int j0 = 0; j0 < K3; j0 += 16) run(4, p_sh, opt.m_sh, opt.v_sh, src.shv, acc.a_sh, j0, (K3 - j0 < 16) ? K3 - j0 : 16);
+}
+
+
 hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const SplatsDev& out, const uint8_t* keep,
                              int group_size, hipStream_t s)
 {
@@ -619,6 +674,21 @@ hipError_t launch_preprocess_bwd_batch(const SceneDev& sc, const BatchCams& cams
     ProfScope prof(kKPreprocessBwd, s);
     if (first_view) launch_preprocess_bwd_batch_t<true>(sc, cams, in, g, blocks, s);
     else launch_preprocess_bwd_batch_t<false>(sc, cams, in, g, blocks, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_preprocess_bwd_batch_adam(const SceneDev& sc, const BatchCams& cams, const BatchSplatGrads& in, const BatchAdam& opt,
+                                            hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    ProfScope prof(kKPreprocessBwd, s);
+    switch (sc.sh_degree) {
+        case 0: hipLaunchKernelGGL(k_preprocess_bwd_batch_adam<0>, dim3(blocks), dim3(256), 0, s, sc, cams, in, opt); break;
+        case 1: hipLaunchKernelGGL(k_preprocess_bwd_batch_adam<1>, dim3(blocks), dim3(256), 0, s, sc, cams, in, opt); break;
+        case 2: hipLaunchKernelGGL(k_preprocess_bwd_batch_adam<2>, dim3(blocks), dim3(256), 0, s, sc, cams, in, opt); break;
+        default: hipLaunchKernelGGL(k_preprocess_bwd_batch_adam<3>, dim3(blocks), dim3(256), 0, s, sc, cams, in, opt); break;
+    }
     return hipGetLastError();
 }
 

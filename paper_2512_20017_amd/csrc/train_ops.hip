@@ -50,21 +50,6 @@ __global__ __launch_bounds__(256) void k_mark_visible(int n, const int32_t* __re
     if (i < n && radius[i] > 0) visible[i] = 1;
 }
 
-struct AdamDev {
-    float beta1, beta2, one_m_beta1, one_m_beta2;
-    float step_size;      // lr / (1 - beta1^t)
-    float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^t)
-    float eps;
-    int zero_grad;
-};
-
-__device__ __forceinline__ void adam_one(const AdamDev& c, float& p, float g, float& m, float& v)
-{
-    m = c.beta1 * m + c.one_m_beta1 * g;
-    v = c.beta2 * v + c.one_m_beta2 * g * g;
-    p -= c.step_size * m / (sqrtf(v) * c.inv_sqrt_bc2 + c.eps);
-}
-
 // blockIdx.y = plane of the [planes][n] tensors; a lane owns four consecutive points (n % 4 == 0 here).
 // A lane none of whose points is visible reads four mask bytes and nothing else.
 __global__ __launch_bounds__(256) void k_adam_selective_vec(int n, float* __restrict__ param, float* __restrict__ grad,
@@ -111,6 +96,18 @@ __global__ __launch_bounds__(256) void k_adam_selective(int n, float* __restrict
     if (c.zero_grad) grad[at] = 0.f;
 }
 
+AdamDev make_adam(float lr, float beta1, float beta2, float eps, int step, int zero_grad)
+{
+    AdamDev c;
+    c.beta1 = beta1; c.beta2 = beta2;
+    c.one_m_beta1 = (float)(1.0 - (double)beta1); c.one_m_beta2 = (float)(1.0 - (double)beta2);
+    const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
+    c.step_size = (float)((double)lr / bc1);
+    c.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    c.eps = eps; c.zero_grad = zero_grad;
+    return c;
+}
+
 hipError_t launch_l1_loss(int W, int H, const float* image, const float* target, float* loss, float* dL, hipStream_t s)
 {
     const size_t count = (size_t)3 * W * H;
@@ -134,13 +131,7 @@ hipError_t launch_adam_selective(int n, int planes, float* param, float* grad, f
                                  int zero_grad, hipStream_t s)
 {
     if (n == 0 || planes == 0) return hipSuccess;
-    AdamDev c;
-    c.beta1 = beta1; c.beta2 = beta2;
-    c.one_m_beta1 = (float)(1.0 - (double)beta1); c.one_m_beta2 = (float)(1.0 - (double)beta2);
-    const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
-    c.step_size = (float)((double)lr / bc1);
-    c.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
-    c.eps = eps; c.zero_grad = zero_grad;
+    const AdamDev c = make_adam(lr, beta1, beta2, eps, step, zero_grad);
     ProfScope prof(kKAdam, s);
     if ((n & 3) == 0)
         hipLaunchKernelGGL(k_adam_selective_vec, dim3((unsigned)((n / 4 + 255) / 256), (unsigned)planes), dim3(256), 0, s, n, param,

@@ -144,3 +144,69 @@ def test_training_iteration_full_size():
         assert np.array_equal(got[vis == 0], P0[vis == 0])
         assert not g.any().item()
         assert (np.abs(got - P0)[vis != 0].max() > 0.5 * lr)       # the step really moved the visible points
+
+
+@pytest.mark.parametrize("deg,n,views", [(1, 1500, 1), (3, 2500, 4), (0, 777, 16)])
+def test_fused_batch_backward_and_adam_is_the_unfused_sequence(deg, n, views):
+    """pbdr_preprocess_bwd_batch_adam against pbdr_preprocess_bwd_batch (first view) + pbdr_mark_visible per view +
+    pbdr_adam_selective per attribute: parameters and both moments bit for bit, over two consecutive steps; points no
+    view uses keep their parameters and moments."""
+    sc = synth.random_small_scene(40 + deg, n, deg, spread=1.3, ls_mu=-2.8)
+    cams = []
+    for k in range(views):
+        a = 2 * np.pi * k / views + 0.2
+        cams.append(synth.pinhole(160, 96, 55.0, *synth.look_at([3 * np.cos(a), 0.3, 3 * np.sin(a)], [0, 0, 0], [0, 1, 0])))
+    rng = np.random.default_rng(12)
+    lrs = (1.6e-4, 5e-3, 1e-3, 5e-2, 2.5e-3)
+    names = ("mean", "log_scale", "quat", "logit", "sh")
+
+    def fresh():
+        scene = B.Scene.from_numpy(sc)
+        m, v = scene.zeros_like(), scene.zeros_like()
+        m.flat.copy_(torch.from_numpy(np.random.default_rng(1).normal(size=m.flat.shape).astype(np.float32) * 1e-3).cuda())
+        v.flat.copy_(torch.from_numpy(np.random.default_rng(2).uniform(size=v.flat.shape).astype(np.float32) * 1e-4).cuda())
+        return scene, m, v
+
+    s_ref, m_ref, v_ref = fresh()
+    s_got, m_got, v_got = fresh()
+    start = s_ref.to_numpy()
+    used_any = np.zeros(n, dtype=bool)
+    for step in (1, 2):
+        g2_np = []
+        for _ in cams:
+            d = dict(mean2d=rng.normal(size=(n, 2)), conic=rng.normal(size=(n, 3)) * 10, opacity=rng.normal(size=n),
+                     color=rng.normal(size=(n, 3)))
+            g2_np.append({k: x.astype(np.float32) for k, x in d.items()})
+        # unfused
+        splats = []
+        visible = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        for cam in cams:
+            sp = B.Splats.empty(n)
+            B.pbdr_preprocess(s_ref, cam, sp)
+            B.pbdr_mark_visible(sp.radius, visible)
+            splats.append(sp)
+        g2s = [B.SplatGrads.from_numpy(d) for d in g2_np]
+        grads = s_ref.zeros_like()
+        grads.flat.fill_(float("nan"))
+        B.pbdr_preprocess_bwd_batch(s_ref, cams, splats, g2s, grads, first_view=True)
+        for k, lr in zip(names, lrs):
+            B.pbdr_adam_selective(getattr(s_ref, k), getattr(grads, k), getattr(m_ref, k), getattr(v_ref, k), visible, lr, 0.9, 0.999,
+                                  1e-15, step)
+        used_any |= visible.cpu().numpy() != 0
+        # fused (its own preprocessing: its parameters must follow the same trajectory)
+        splats2 = []
+        for cam in cams:
+            sp = B.Splats.empty(n)
+            B.pbdr_preprocess(s_got, cam, sp)
+            splats2.append(sp)
+        B.pbdr_preprocess_bwd_batch_adam(s_got, cams, splats2, g2s, m_got, v_got, lrs, 0.9, 0.999, 1e-15, step)
+        torch.cuda.synchronize()
+        for k in names:
+            assert torch.equal(getattr(s_got, k), getattr(s_ref, k)), (step, k)
+            assert torch.equal(getattr(m_got, k), getattr(m_ref, k)), (step, k)
+            assert torch.equal(getattr(v_got, k), getattr(v_ref, k)), (step, k)
+    assert 0 < used_any.sum() < n
+    end = s_got.to_numpy()
+    for k in names:
+        assert np.array_equal(end[k][~used_any], start[k][~used_any]), k
+        assert not np.array_equal(end[k][used_any], start[k][used_any]), k
