@@ -425,7 +425,11 @@ static void blend_pixel(double px, double py, const uint32_t* list, uint32_t len
         const double sigma = 0.5 * (conic[3 * g] * dx * dx + conic[3 * g + 2] * dy * dy) + conic[3 * g + 1] * dx * dy;
         double gauss, araw, alpha, Tn;
         ++ev;
-        if (fabs(sigma) < 1e-6) frag |= ORC_FRAG_SIGMA;
+        /* the sign decision below is within fp32 rounding of flipping: the error of sigma evaluated in fp32 grows
+         * with the size of its three terms, which matters for conics close to degenerate (terms that cancel) */
+        if (fabs(sigma) < 1e-6 + 4e-7 * (0.5 * (fabs(conic[3 * g]) * dx * dx + fabs(conic[3 * g + 2]) * dy * dy) +
+                                         fabs(conic[3 * g + 1] * dx * dy)))
+            frag |= ORC_FRAG_SIGMA;
         if (sigma < 0.0) continue;
         gauss = exp(-sigma);
         araw = opacity[g] * gauss;
