@@ -15,6 +15,8 @@
 #include "composite_common.h"
 #include "pair_reduce.h"
 
+#include <type_traits>
+
 namespace pbdr {
 
 // value of q(dx,dy) = A dx^2 + B dx dy + C dy^2
@@ -48,12 +50,15 @@ struct StageRec {                     // 48 bytes: one LDS address register serv
 struct Stage {
     StageRec rec[kBatch];
     unsigned long long mask[4][4];    // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
+    uint32_t definite[4];             // [staging wavefront]: all of its splats have a positive-definite conic, with margin
 };
 
 // Stage list entries [first, first+count) of the tile: one per thread. Returns this thread's splat index, raw
 // conic/opacity and (mean2d, extent) for callers that need them (backward). All 256 threads must call it.
-// reach: one byte per list position, bit q = "this splat can reach quadrant q". The forward pass works the bits out
-// and stores them (kReuse = false); the backward pass, which walks a prefix of the same lists, reads them back.
+// reach: one byte per list position, bit q = "this splat can reach quadrant q", bit 4 = "its conic is positive
+// definite with a margin that rounding cannot bridge" (then the quadratic form is never negative and the per-pixel
+// sign test can be left out for the batch, see walk loops). The forward pass works the bits out and stores them
+// (kReuse = false); the backward pass, which walks a prefix of the same lists, reads them back.
 template <bool kReuse>
 __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const uint32_t* __restrict__ vals,
                                             const Packed* __restrict__ packed, uint8_t* __restrict__ reach_bits, uint32_t first,
@@ -62,6 +67,7 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool have = (int)threadIdx.x < count;
     bool reach[4] = {false, false, false, false};
+    bool definite = true;
     id = 0; raw = make_float4(0.f, 0.f, 0.f, 0.f); geo = raw;
     if (have) {
         id = vals[first + threadIdx.x];
@@ -79,10 +85,12 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
             const uint32_t bits = reach_bits[first + threadIdx.x];
 #pragma unroll
             for (int q = 0; q < 4; ++q) reach[q] = ((bits >> q) & 1u) != 0;
+            definite = ((bits >> 4) & 1u) != 0;
         } else {
             // alpha >= 1/255  <=>  q(d) <= L + log2(255)
             const float tau = L + kLog2_255;
             const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
+            definite = (A > 0.f) && (C > 0.f) && (4.f * A * C > 1.00001f * (B * B));
             if (!(tau < -0.05f)) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -98,7 +106,8 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
                     reach[q] = keep;
                 }
             }
-            reach_bits[first + threadIdx.x] = (uint8_t)((reach[0] ? 1u : 0u) | (reach[1] ? 2u : 0u) | (reach[2] ? 4u : 0u) | (reach[3] ? 8u : 0u));
+            reach_bits[first + threadIdx.x] = (uint8_t)((reach[0] ? 1u : 0u) | (reach[1] ? 2u : 0u) | (reach[2] ? 4u : 0u) |
+                                                        (reach[3] ? 8u : 0u) | (definite ? 16u : 0u));
         }
     }
 #pragma unroll
@@ -106,6 +115,8 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
         const unsigned long long m = __ballot(reach[q]);
         if (lane == 0) S.mask[q][wave] = m;
     }
+    const unsigned long long dm = __ballot(definite);
+    if (lane == 0) S.definite[wave] = (dm == ~0ull) ? 1u : 0u;
 }
 
 __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges,
@@ -129,29 +140,36 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
         __syncthreads();
         if (__ballot(live) == 0ull) continue;          // this quadrant is finished (uniform per wavefront)
         const uint32_t pos0 = base - c.start + 1u;
-        for (int k = 0; k < 4; ++k) {
-            unsigned long long m = uniform_u64(S.mask[wave][k]);
-            while (m) {
-                const int j = k * 64 + __builtin_ctzll(m);
-                m &= m - 1ull;
-                const float4 a = S.rec[j].a;
-                const float4 b = S.rec[j].b;
-                const float cb = S.rec[j].c;
-                const float dx = fx - a.x, dy = fy - a.y;
-                const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
-                const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
-                const bool valid = live && (q >= 0.f) && (alpha >= kAlphaMin);
-                const float aT = alpha * T;
-                const float Tn = T - aT;            // T (1 - alpha), with the product the weight needs anyway
-                const bool stop = valid && (Tn < kTStop);
-                const bool blend = valid && !stop;
-                live = live && !stop;
-                const float w = blend ? aT : 0.f;
-                C0 += b.z * w; C1 += b.w * w; C2 += cb * w;
-                T = blend ? Tn : T;
-                last = blend ? pos0 + (uint32_t)j : last;
+        // kSign: keep the "quadratic form < 0 -> skip" test per pixel; not needed when every splat of the batch has a
+        // positive-definite conic (every state that pbdr_preprocess writes)
+        auto walk = [&](auto sign_test) {
+            constexpr bool kSign = decltype(sign_test)::value;
+            for (int k = 0; k < 4; ++k) {
+                unsigned long long m = uniform_u64(S.mask[wave][k]);
+                while (m) {
+                    const int j = k * 64 + __builtin_ctzll(m);
+                    m &= m - 1ull;
+                    const float4 a = S.rec[j].a;
+                    const float4 b = S.rec[j].b;
+                    const float cb = S.rec[j].c;
+                    const float dx = fx - a.x, dy = fy - a.y;
+                    const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
+                    const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
+                    const bool valid = live && (!kSign || q >= 0.f) && (alpha >= kAlphaMin);
+                    const float aT = alpha * T;
+                    const float Tn = T - aT;            // T (1 - alpha), with the product the weight needs anyway
+                    const bool stop = valid && (Tn < kTStop);
+                    const bool blend = valid && !stop;
+                    live = live && !stop;
+                    const float w = blend ? aT : 0.f;
+                    C0 += b.z * w; C1 += b.w * w; C2 += cb * w;
+                    T = blend ? Tn : T;
+                    last = blend ? pos0 + (uint32_t)j : last;
+                }
             }
-        }
+        };
+        if (S.definite[0] & S.definite[1] & S.definite[2] & S.definite[3]) walk(std::false_type{});
+        else walk(std::true_type{});
     }
     if (c.inside) {
         const size_t HW = (size_t)cam.W * cam.H;
@@ -225,40 +243,47 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
         for (int k = 0; k < kAccStride; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {            // else nothing of this batch was blended by this wavefront (uniform per wave)
-            for (int k = 3; k >= 0; --k) {
-                unsigned long long m = uniform_u64(S.mask[wave][k]);
-                while (m) {
-                    const int bit = 63 - __builtin_clzll(m);
-                    m &= ~(1ull << bit);
-                    const int j = k * 64 + bit;
-                    const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
-                    const float4 a = S.rec[j].a;
-                    const float4 b = S.rec[j].b;
-                    const float cb = S.rec[j].c;
-                    const float dx = fx - a.x, dy = fy - a.y;
-                    const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
-                    const float e = __builtin_amdgcn_exp2f(b.y - q);
-                    const float alpha = fminf(kAlphaMax, e);
-                    const bool hit = (pos <= last) && (q >= 0.f) && (alpha >= kAlphaMin);
-                    if (__ballot(hit) == 0ull) continue;                   // uniform per wave
-                    const float ioma = __builtin_amdgcn_rcpf(1.f - alpha);
-                    const float Tk = T * ioma;                              // transmittance in front of this splat
-                    const float w = hit ? alpha * Tk : 0.f;
-                    const float cg = b.z * g0 + b.w * g1 + cb * g2c;
-                    const float dL_dalpha = Tk * cg - Sfx * ioma;
-                    const float ds = (hit && e < kAlphaMax) ? -alpha * dL_dalpha : 0.f;
-                    T = hit ? Tk : T;
-                    Sfx += w * cg;
-                    const float dsx = ds * dx, dsy = ds * dy;
-                    const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
-                    const float part = row_sum8(v8, bit1);
-                    const float blue = row_sum16(w * g2c);
-                    const float tot = sum_rows(blue_lane ? blue : part);
-                    int acc_base = kAccStride * j;
-                    asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (else a quarter-rate VALU mad)
-                    if (add_lane) atomicAdd(&sAcc[acc_base + acc_slot], tot);
+            // kSign: as in the forward kernel, the per-pixel sign test of the quadratic form is only kept for batches that
+            // hold a splat whose conic is not safely positive definite
+            auto walk = [&](auto sign_test) {
+                constexpr bool kSign = decltype(sign_test)::value;
+                for (int k = 3; k >= 0; --k) {
+                    unsigned long long m = uniform_u64(S.mask[wave][k]);
+                    while (m) {
+                        const int bit = 63 - __builtin_clzll(m);
+                        m &= ~(1ull << bit);
+                        const int j = k * 64 + bit;
+                        const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
+                        const float4 a = S.rec[j].a;
+                        const float4 b = S.rec[j].b;
+                        const float cb = S.rec[j].c;
+                        const float dx = fx - a.x, dy = fy - a.y;
+                        const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
+                        const float e = __builtin_amdgcn_exp2f(b.y - q);
+                        const float alpha = fminf(kAlphaMax, e);
+                        const bool hit = (pos <= last) && (!kSign || q >= 0.f) && (alpha >= kAlphaMin);
+                        if (__ballot(hit) == 0ull) continue;                   // uniform per wave
+                        const float ioma = __builtin_amdgcn_rcpf(1.f - alpha);
+                        const float Tk = T * ioma;                              // transmittance in front of this splat
+                        const float w = hit ? alpha * Tk : 0.f;
+                        const float cg = b.z * g0 + b.w * g1 + cb * g2c;
+                        const float dL_dalpha = Tk * cg - Sfx * ioma;
+                        const float ds = (hit && e < kAlphaMax) ? -alpha * dL_dalpha : 0.f;
+                        T = hit ? Tk : T;
+                        Sfx += w * cg;
+                        const float dsx = ds * dx, dsy = ds * dy;
+                        const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
+                        const float part = row_sum8(v8, bit1);
+                        const float blue = row_sum16(w * g2c);
+                        const float tot = sum_rows(blue_lane ? blue : part);
+                        int acc_base = kAccStride * j;
+                        asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (else a quarter-rate VALU mad)
+                        if (add_lane) atomicAdd(&sAcc[acc_base + acc_slot], tot);
+                    }
                 }
-            }
+            };
+            if (S.definite[0] & S.definite[1] & S.definite[2] & S.definite[3]) walk(std::false_type{});
+            else walk(std::true_type{});
         }
         __syncthreads();
         if ((int)threadIdx.x < cnt) {

@@ -120,3 +120,46 @@ def test_large_radius_covers_whole_image():
     sp64 = {k: np.asarray(st[k], dtype=np.float32).astype(np.float64) for k in ("mean2d", "conic", "opacity", "color")}
     r = oracle.render_fwd(sp64, ref, w, h, [0, 0, 0])
     assert np.abs(out["image"] - r["image"]).max() < 1e-5
+
+
+def test_caller_supplied_conics_that_are_not_positive_definite():
+    """pbdr_render_fwd / pbdr_render_bwd accept any splat state. A conic that is not positive definite makes the
+    quadratic form negative on part of the image, where the rule is "skip" (no blend); the compositing kernels leave that
+    test out only for batches whose conics are all safely positive definite, so a scene that mixes indefinite,
+    near-degenerate and ordinary conics over several staging batches exercises both loops, forward and backward."""
+    rng = np.random.default_rng(17)
+    w, h, n = 96, 80, 900                                   # ~40 splats per tile on average, several batches of 256 in the busy ones
+    st = dict(mean2d=np.stack([rng.uniform(0, w, n), rng.uniform(0, h, n)], 1).astype(np.float32),
+              conic=np.zeros((n, 3), dtype=np.float32), opacity=rng.uniform(0.05, 0.6, n).astype(np.float32),
+              color=rng.uniform(0, 1, (n, 3)).astype(np.float32), radius=rng.integers(4, 40, n).astype(np.int32))
+    a = rng.uniform(0.01, 0.08, n); c = rng.uniform(0.01, 0.08, n)
+    b = rng.uniform(-0.9, 0.9, n) * np.sqrt(a * c)          # positive definite ...
+    kind = rng.integers(0, 4, n)
+    b[kind == 1] = (1.5 * np.sqrt(a * c) * rng.choice([-1, 1], n))[kind == 1]                  # ... indefinite ...
+    b[kind == 2] = (np.sqrt(a * c) * (1 - 1e-7) * rng.choice([-1, 1], n))[kind == 2]            # ... within rounding of degenerate
+    st["conic"] = np.stack([a, b, c], 1).astype(np.float32)
+    st["mean2d"][:300] = rng.uniform(30, 50, (300, 2)).astype(np.float32)                     # a crowd, so that lists exceed one batch
+    depth = rng.uniform(0.5, 20, n).astype(np.float32)
+    got_l, ref_l, view = _lists_case(st, depth, w, h)
+    assert np.array_equal(got_l["vals"], ref_l["vals"])
+    assert (ref_l["ranges"][:, 1] - ref_l["ranges"][:, 0]).max() > 256
+    bg = [0.1, 0.2, 0.3]
+    got = view.render_fwd(bg)
+    st64 = {k: np.asarray(v, dtype=np.float32).astype(np.float64) for k, v in st.items() if k != "radius"} | {"radius": st["radius"]}
+    ref = oracle.render_fwd(st64, ref_l, w, h, bg)
+    ok = ref["fragile"] == 0
+    assert ok.mean() > 0.95
+    assert np.abs(got["image"] - ref["image"])[ok].max() <= 1e-4
+    assert np.array_equal(got["last_idx"][ok], ref["last_idx"][ok])
+    G = rng.normal(size=(h, w, 3)).astype(np.float32)
+    G[~ok] = 0.0
+    G[got["last_idx"] != ref["last_idx"]] = 0.0
+    g = view.render_bwd(bg, G)
+    rg = oracle.render_bwd(st64, ref_l, w, h, bg, G.astype(np.float64))
+    for k in ("mean2d", "conic", "opacity", "color"):
+        r_ = np.asarray(rg[k]); d = np.abs(g[k] - r_)
+        floor = 1e-5 * max(np.abs(r_).max(), 1e-30)
+        bad = d > 1e-3 * np.abs(r_) + floor
+        # a pixel that sits within rounding of sigma = 0 of an indefinite splat is flagged fragile and carries no loss;
+        # what is left must agree
+        assert bad.mean() < 2e-3, (k, int(bad.sum()), float(d.max()))
