@@ -345,6 +345,21 @@ def main():
         for t in grad_tensors:
             t.zero_()
 
+    # a plain device copy as the yardstick for the HBM-bound kernels: 256 MiB read + 256 MiB written, timed with events
+    copy_gbs = None
+    if not args.train_step:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -522,6 +537,7 @@ def main():
                    "pairs_examined_bwd": sum_last, "pairs_blended": int(blended), "seed": args.seed,
                    "group_size": args.group_size, "groups_kept": kept_groups},
         "mpixel_per_s": views_per_s * W * H / 1e6,
+        "device_copy_gbs": copy_gbs,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": per_kernel,
