@@ -403,7 +403,8 @@ def pbdr_render_fwd_patch(splats: Splats, cam: dict, patch, bg, dup_capacity: in
 
 def pbdr_render_bwd_patch(scene, splats: Splats, cam: dict, patch, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
                           g_splats: SplatGrads, grads, ws, stream=None, first_view=False) -> None:
-    sp, c, p, g2 = splats.struct(), camera_struct(cam), _patch(patch), g_splats.struct()
+    sp, c, p = splats.struct(), camera_struct(cam), _patch(patch)
+    g2 = g_splats.struct() if g_splats is not None else None
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
         sc, g = scene.struct(), grads.struct(first_view)
@@ -411,7 +412,7 @@ def pbdr_render_bwd_patch(scene, splats: Splats, cam: dict, patch, bg, dup_capac
     else:
         psc, pg = None, None
     _check(lib().pbdr_render_bwd_patch(psc, C.byref(sp), C.byref(c), C.byref(p), bgv, C.c_uint64(dup_capacity),
-                                       _dev(final_T), _dev(last_idx), _dev(dL_dimage), C.byref(g2), pg,
+                                       _dev(final_T), _dev(last_idx), _dev(dL_dimage), C.byref(g2) if g2 is not None else None, pg,
                                        C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
 
 

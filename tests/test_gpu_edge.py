@@ -87,6 +87,11 @@ def test_zero_points():
     assert (out["image"][..., 0] == 1).all() and (out["image"][..., 2] == 0.5).all()
     grads = scene.zeros_like()
     view.render_bwd([1.0, 0.0, 0.5], np.ones((32, 32, 3), dtype=np.float32), scene=scene, grads=grads)
+    # the same without a splat-state gradient output, and the batched calls on an empty cloud
+    G = torch.ones((3, 32, 32), device="cuda")
+    B.pbdr_render_bwd(scene, view.splats, cam, [1.0, 0.0, 0.5], view.cap, view.final_T, view.last_idx, G, None, grads, view.ws,
+                      first_view=True)
+    torch.cuda.synchronize()
 
 
 def test_capacity_overflow_is_reported_and_in_bounds():

@@ -103,7 +103,7 @@ def test_patches_small(seed, W, H, deg):
     G = rng.normal(size=(H, W, 3)).astype(np.float32)
     G[~ok] = 0.0
     patches = _partition(W, H, 2) + _partition(W, H, 3) + [(17, 5, 18, 6), (W - 40, H - 33, W, H), (0, 0, W, H)]
-    acc = {2: scene.zeros_like(), 3: scene.zeros_like()}
+    acc = {2: scene.zeros_like(), 3: scene.zeros_like(), "2, no splat-gradient output": scene.zeros_like()}
     for pi, patch in enumerate(patches):
         x0, y0, x1, y1 = patch
         splats, sp, final_T, last_idx, vis = _render_patch(scene, full, patch, ws)
@@ -113,6 +113,9 @@ def test_patches_small(seed, W, H, deg):
         grads = acc[2] if pi < 4 else (acc[3] if pi < 13 else scene.zeros_like())
         B.pbdr_render_bwd_patch(scene, splats, cam, patch, BG, cap, final_T, last_idx,
                                 to_chw_dev(G[y0:y1, x0:x1]), g_sp, grads, ws)
+        if pi < 4:      # the 2 x 2 partition once more, the splat-state gradient left in the workspace
+            B.pbdr_render_bwd_patch(scene, splats, cam, patch, BG, cap, final_T, last_idx, to_chw_dev(G[y0:y1, x0:x1]), None,
+                                    acc["2, no splat-gradient output"], ws)
         torch.cuda.synchronize()
         got = g_sp.to_numpy()
         for k in ("mean2d", "conic", "opacity", "color"):
@@ -125,7 +128,7 @@ def test_patches_small(seed, W, H, deg):
     B.pbdr_render_bwd(scene, full.splats, cam, BG, cap, full.final_T, full.last_idx, to_chw_dev(G), g_sp, whole, full.ws)
     torch.cuda.synchronize()
     ref = whole.to_numpy()
-    for p in (2, 3):
+    for p in acc:
         got = acc[p].to_numpy()
         for k in ("mean", "log_scale", "quat", "logit", "sh"):
             _close(k, got[k], ref[k], rtol=1e-3, floor=2e-5)
