@@ -355,7 +355,7 @@ def preprocess_grouped(scene: dict, cam: dict, group_size: int) -> dict:
 
 
 # ---------------------------------------------------------------------------------------- loss and optimizer step
-# Alg. 1 line 13 (loss_fn), line 16 (loss_fn.backward) and line 27 (AdamUpdate). The paper names the steps only; the
+# Alg. 1's loss_fn, loss_fn.backward and AdamUpdate steps. The paper names the steps only; the
 # benchmark configurations fix the loss (mean L1 against the target image) and App. E.1 says the optimizer is the
 # "selective" Adam: the textbook update (Kingma & Ba, with bias correction) applied to the points that were visible
 # in the batch, every other point - parameter and both moments - left exactly as it was. Plain numpy, fp64.

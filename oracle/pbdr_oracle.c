@@ -284,7 +284,7 @@ static void project_one(int sh_degree, const double mean[3], const double log_sc
 }
 
 /*
- * pts_culling + pts_splatting for one view (Sec. 3.1; Alg. 1 lines 2-4): fills the
+ * pts_culling + pts_splatting for one view (Sec. 3.1; Alg. 1's culling and splatting steps): fills the
  * Table 3a state. A culled point gets radius 0 and zeros elsewhere.
  * Optional outputs (may be NULL): rect[n][4]; cov2d[n][3] = (a,b,c) incl. blur;
  * near_tie[n] = 1 where an integer decision (extent ceil, tile rectangle, a cull
@@ -510,7 +510,7 @@ void orc_render_fwd_global(int width, int height, int n_order, const uint32_t* o
 }
 
 /*
- * image_render.backward (Alg. 1 line 18): gradient of L w.r.t. the splat state given
+ * image_render.backward (Alg. 1): gradient of L w.r.t. the splat state given
  * dL/dimage [H][W][3]. Outputs are ACCUMULATED (+=): d_mean2d[n][2], d_conic[n][3],
  * d_opacity[n], d_color[n][3]. The forward blend is recomputed per pixel and the suffix
  * sums are formed directly (no divide-back recurrence).
@@ -576,7 +576,7 @@ void orc_render_bwd(int width, int height, const double* mean2d, const double* c
 }
 
 /*
- * pts_splatting.backward (Alg. 1 lines 22-24): chain rule from the splat-state gradient to
+ * pts_splatting.backward (Alg. 1, the step that sums the views' gradients): chain rule from the splat-state gradient to
  * the raw point parameters, ACCUMULATED (+=) into g_mean[n][3], g_log_scale[n][3],
  * g_quat[n][4], g_logit[n], g_sh[n][K][3]. Depth and radius carry no gradient.
  */
