@@ -21,7 +21,20 @@ def build(verbose: bool = False, extra=()) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+    build_ubench(verbose)
     return LIB
+
+
+def build_ubench(verbose: bool = False) -> str:
+    """The instruction-issue micro-benchmark behind the ALU roofline figures (a stand-alone program, not in the library)."""
+    src = os.path.join(HERE, "ubench", "valu_issue.hip")
+    exe = os.path.join(HERE, "ubench", "valu_issue.bin")
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", exe, src]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return exe
 
 
 if __name__ == "__main__":
