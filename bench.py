@@ -208,6 +208,7 @@ def main():
     ap.add_argument("--splat-grads", action="store_true",
                     help="have pbdr_render_bwd also write dL/d(splat state) out (nine planes), which the step itself does not need")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the leg that replays the step from a HIP graph")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (a kernel of known traffic, to scale rocprofv3 byte counters)")
@@ -525,6 +526,28 @@ def main():
                           max_gradient_diff_rel_to_max=gdiff)
         del ctxs
 
+    # ---- the same step recorded once into a HIP graph and replayed (not `value`): the calls are kernel launches on the
+    # caller's stream and nothing else, so the step can be captured; one graph launch then stands for its ~45 launches
+    graph_replay = None
+    if not args.no_graph and not args.train_step:
+        graph = torch.cuda.CUDAGraph()
+        before = grads.flat.clone() if hasattr(grads, "flat") else None
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(max(args.warmup, 1)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        graph_replay = dict(views_per_s=args.steps / (t1 - t0), ms_per_step=(t1 - t0) * 1e3 / args.steps)
+        if before is not None:
+            gscale = float(before.abs().max().item())
+            graph_replay["max_gradient_diff_rel_to_max"] = float((grads.flat - before).abs().max().item()) / max(gscale, 1e-30)
+        del graph
+
     out = {
         "metric": "training iterations/sec (splat, render, L1 loss, backward, selective Adam), one view" if args.train_step else
                   {"mid": "fwd+bwd views/sec at 1080p, 1M Gaussians",
@@ -544,6 +567,7 @@ def main():
         "kernels": per_kernel,
         "parity": parity,
         "overlapped": overlapped,
+        "graph_replay": graph_replay,
     }
     print(json.dumps(out))
 
