@@ -216,6 +216,15 @@ int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t 
                     uint64_t dup_capacity, void* hip_stream, const uint64_t** keys, const uint32_t** vals,
                     const uint32_t** ranges, const uint32_t** num_dup);
 
+/* Device address, inside a workspace laid out for these sizes, of the order in which the compositing kernels of the
+ * last pbdr_bin_sort / pbdr_render_fwd (surfel_workspace == 0) or pbdr2d_render_fwd (!= 0) take the tiles:
+ * tile_order [tiles of the call's grid], a permutation of the tile ids as pbdr_lists_view shows them. An
+ * implementation detail with no effect on any result (Sec. 2.1 composites every tile independently of the others):
+ * tiles with longer lists come first, in classes of list length L, two per octave of L + 1 (class = 2 floor(log2(L + 1))
+ * + the next lower bit of L + 1, classes of 2^19.5 and more merged), and within a class in ascending id. */
+int pbdr_tile_order_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                         uint64_t dup_capacity, int32_t surfel_workspace, const uint32_t** tile_order);
+
 /* Synchronises hip_stream and reads back the number of (tile, splat) pairs found by the last pbdr_bin_sort /
  * pbdr_render_fwd on this workspace. Returns PBDR_ERR_CAPACITY if it exceeded dup_capacity (the lists were then
  * truncated), else PBDR_OK. Optional: callers that know a safe capacity never need to call it. */

@@ -31,7 +31,7 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
            "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch",
            "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective", "pbdr_preprocess_batch", "pbdr_preprocess_bwd_batch",
-           "pbdr_preprocess_bwd_batch_adam")
+           "pbdr_preprocess_bwd_batch_adam", "pbdr_tile_order_view")
 
 _f = C.POINTER(C.c_float)
 
@@ -449,6 +449,16 @@ def pbdr_lists_view(ws, n, width, height, dup_capacity, _entry="pbdr_lists_view"
     P = min(P_raw, max(int(dup_capacity), 1))
     return dict(P=P, P_raw=P_raw, keys=view(keys, P, np.uint64), vals=view(vals, P, np.uint32),
                 ranges=view(ranges, 2 * tiles, np.uint32).reshape(tiles, 2))
+
+
+def pbdr_tile_order_view(ws, n, width, height, dup_capacity, tiles, surfels=False):
+    """Copies out (synchronises) the order in which the compositing kernels take the `tiles` tiles of the last call's grid."""
+    ptr = C.c_void_p()
+    _check(lib().pbdr_tile_order_view(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
+                                      C.c_int32(height), C.c_uint64(dup_capacity), C.c_int32(int(bool(surfels))), C.byref(ptr)))
+    torch.cuda.synchronize()
+    off = ptr.value - ws.data_ptr()
+    return ws[off:off + 4 * tiles].cpu().numpy().view(np.uint32).copy()
 
 
 def pbdr_render_stats(cam: dict, n, dup_capacity, ws, stream=None, _entry="pbdr_render_stats"):

@@ -56,6 +56,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->off_carry = take(((size_t)cap / 256 + 2) * 36 * sizeof(float));
     L->off_grad_rec = take((size_t)n * L->partial_vec4 * 4 * sizeof(float));      // per-point gradient records, by point index
     L->off_reach = take((size_t)cap);      // per sorted pair: which quadrants of its tile the splat reaches (forward -> backward)
+    L->off_tile_order = take((size_t)L->tiles * sizeof(uint32_t));   // tiles in the order the compositing kernels take them
     L->total = off;
     return true;
 }
@@ -445,6 +446,17 @@ static int lists_view(int variant, void* workspace, size_t workspace_bytes, int3
     if (vals) *vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     if (ranges) *ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
     if (num_dup) *num_dup = reinterpret_cast<const uint32_t*>(ws + L.off_status) + kStNumDup;
+    return PBDR_OK;
+}
+
+int pbdr_tile_order_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                         uint64_t dup_capacity, int32_t surfel_workspace, const uint32_t** tile_order)
+{
+    Layout L;
+    if (!tile_order) return PBDR_ERR_INVALID_ARG;
+    const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L, surfel_workspace ? kVariant2D : kVariant3D);
+    if (st != PBDR_OK) return st;
+    *tile_order = reinterpret_cast<const uint32_t*>((char*)workspace + L.off_tile_order);
     return PBDR_OK;
 }
 

@@ -268,11 +268,13 @@ __global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, cons
     if (dropped) status[kStOverflow] = 1u;
 }
 
-__global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, size_t nranges)
+__global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, size_t nranges,
+                                                   uint32_t* __restrict__ tile_order)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i < (size_t)kStCleared) status[i] = 0u;
     if (i < nranges) ranges[i] = 0u;
+    if (2 * i < nranges) tile_order[i] = (uint32_t)i;      // no lists: any order will do
 }
 
 // One thread per sorted pair: mark where each tile's run starts and ends.
@@ -286,6 +288,104 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict_
     if (tile >= ntiles) return;     // cannot happen for keys written by k_duplicate; keeps the write in bounds regardless
     if (i == 0 || tkeys[i - 1] != tile) ranges[2 * tile] = i;
     if (i + 1 == P || tkeys[i + 1] != tile) ranges[2 * tile + 1] = i + 1;
+}
+
+// The order in which the compositing kernels take the tiles: longest lists first. Workgroups start in index order and a
+// tile's cost grows with its list, so in image order a launch ends on whatever long tiles happen to come late, with
+// most of the chip idle. Tiles are put in classes of list length, two per octave (class 0 = longest); within a class
+// they keep the image order, so neighbours in the order are still neighbours in the image and share splat records in L2.
+// That is a stable counting sort on the class, done by one workgroup: wavefront w owns a contiguous run of tiles and
+// takes it 64 at a time. A lane finds the lanes of its class from six ballots, one per bit of the class, with no loop
+// over the classes present: the kernel runs on one compute unit, so its instruction count is its duration.
+constexpr int kOrderClasses = 40;           // < 63; class 63 stands for "no tile"
+constexpr uint32_t kOrderRounds = 8;        // rounds of 64 tiles whose ranges are loaded together (one trip to memory, not eight)
+
+__device__ __forceinline__ uint32_t order_class(uint32_t len)
+{
+    const uint32_t x = len + 1u;
+    const int e = 31 - __clz((int)x);
+    const uint32_t half = e > 0 ? (x >> (e - 1)) & 1u : 0u;
+    return (uint32_t)(kOrderClasses - 1) - min(2u * (uint32_t)e + half, (uint32_t)(kOrderClasses - 1));
+}
+
+// classes of the tiles tb + 64 k + lane, k = 0 .. kOrderRounds - 1, of the run that ends at t1
+__device__ __forceinline__ void order_classes(const uint2* __restrict__ range2, uint32_t tb, uint32_t t1, uint32_t lane,
+                                              uint32_t (&cls)[kOrderRounds])
+{
+    uint2 r[kOrderRounds];
+#pragma unroll
+    for (uint32_t k = 0; k < kOrderRounds; ++k) {
+        const uint32_t t = tb + k * 64u + lane;
+        r[k] = t < t1 ? range2[t] : make_uint2(0u, 0u);
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < kOrderRounds; ++k) cls[k] = tb + k * 64u + lane < t1 ? order_class(r[k].y - r[k].x) : 63u;
+}
+
+// the lanes of the wavefront whose class equals this lane's
+__device__ __forceinline__ uint64_t lanes_of_my_class(uint32_t cls)
+{
+    uint64_t same = ~0ull;
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        const bool bit = ((cls >> b) & 1u) != 0u;
+        const uint64_t set = __ballot(bit);
+        same &= bit ? set : ~set;
+    }
+    return same;
+}
+
+__global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict__ ranges, uint32_t ntiles, uint32_t* __restrict__ tile_order)
+{
+    __shared__ uint32_t count[64 * 16];      // [class][wavefront]: tiles, then where the wavefront's next tile of the class goes
+    const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+    const uint32_t per_wave = ((ntiles + 1023u) / 1024u) * 64u;
+    const uint32_t t0 = w * per_wave, t1 = min(ntiles, t0 + per_wave);
+    const uint64_t below = (1ull << lane) - 1ull;
+    const uint2* range2 = reinterpret_cast<const uint2*>(ranges);
+
+    count[threadIdx.x] = 0u;
+    __syncthreads();
+    for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
+        uint32_t cls[kOrderRounds];
+        order_classes(range2, tb, t1, lane, cls);
+#pragma unroll
+        for (uint32_t k = 0; k < kOrderRounds; ++k) {
+            const uint64_t same = lanes_of_my_class(cls[k]);
+            if ((same & below) == 0ull && cls[k] != 63u) count[cls[k] * 16u + w] += (uint32_t)__popcll(same);      // first lane of its class
+        }
+    }
+    __syncthreads();
+    if (w == 0) {      // exclusive prefix sums over (class, wavefront), classes 0 .. kOrderClasses - 1: 10 consecutive entries per lane
+        constexpr int kPer = kOrderClasses * 16 / 64;
+        uint32_t v[kPer], sum = 0;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) { v[k] = count[lane * kPer + k]; sum += v[k]; }
+        uint32_t incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t up = __shfl_up(incl, d);
+            if (lane >= (uint32_t)d) incl += up;
+        }
+        uint32_t at = incl - sum;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) { count[lane * kPer + k] = at; at += v[k]; }
+    }
+    __syncthreads();
+    for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
+        uint32_t cls[kOrderRounds];
+        order_classes(range2, tb, t1, lane, cls);
+#pragma unroll
+        for (uint32_t k = 0; k < kOrderRounds; ++k) {
+            const uint64_t same = lanes_of_my_class(cls[k]);
+            const uint32_t slot = cls[k] * 16u + w;
+            const uint32_t at = count[slot];      // every lane of the class reads it before its first lane moves it on
+            if (cls[k] != 63u) {
+                tile_order[at + (uint32_t)__popcll(same & below)] = tb + k * 64u + lane;
+                if ((same & below) == 0ull) count[slot] = at + (uint32_t)__popcll(same);
+            }
+        }
+    }
 }
 
 // Inspection only: the 64-bit keys (tile << 32 | depth bits) of the sorted pairs, rebuilt from the sorted tile ids
@@ -318,7 +418,7 @@ hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
     // status words and tile ranges start at zero (one launch)
     ProfScope prof(kKFill, s);
     hipLaunchKernelGGL(k_bin_begin, dim3((unsigned)((2 * (size_t)L.tiles + 255) / 256)), dim3(256), 0, s, status, ranges,
-                       2 * (size_t)L.tiles);
+                       2 * (size_t)L.tiles, reinterpret_cast<uint32_t*>(ws + L.off_tile_order));
     return hipGetLastError();
 }
 
@@ -391,6 +491,9 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
         ProfScope prof(kKTileRanges, s);
         const uint32_t* sorted = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
         hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
+        // the call's tile grid (a patch covers fewer tiles than the image the workspace is sized for)
+        hipLaunchKernelGGL(k_tile_order, dim3(1), dim3(1024), 0, s, ranges, (uint32_t)(cam.TX * cam.TY),
+                           reinterpret_cast<uint32_t*>(ws + L.off_tile_order));
     }
     return hipGetLastError();
 }

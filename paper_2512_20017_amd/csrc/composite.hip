@@ -119,14 +119,14 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
     if (lane == 0) S.definite[wave] = (dm == ~0ull) ? 1u : 0u;
 }
 
-__global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges,
+__global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        uint8_t* __restrict__ reach_bits, float bg0, float bg1, float bg2,
                                                        float* __restrict__ image, float* __restrict__ final_T,
                                                        uint32_t* __restrict__ last_idx)
 {
     __shared__ Stage S;
-    const TileCtx c = tile_ctx(cam, ranges);
+    const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     float T = 1.f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
 // (12 floats per pair), where u is the pair's position in the unsorted duplicate list (slot_base[id] + rank of this
 // tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them up afterwards
 // (k_gather_splat_grads).
-__global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
+__global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        uint8_t* __restrict__ reach_bits, const uint32_t* __restrict__ slot_base,
                                                        float bg0, float bg1, float bg2, const float* __restrict__ final_T,
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     // [splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are conflict-free)
     __shared__ float sAcc[kAccStride * kBatch];
     __shared__ uint32_t sMax[4];
-    const TileCtx c = tile_ctx(cam, ranges);
+    const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     const size_t HW = (size_t)cam.W * cam.H;
@@ -385,14 +385,14 @@ __global__ __launch_bounds__(256) void k_grad_records_to_planes(int n, const uin
 
 // Measurement aid: the forward walk with counters instead of colours. counters[0] += list entries examined per pixel
 // (up to and including the one that ends the pixel), counters[1] += pairs blended.
-__global__ __launch_bounds__(256) void k_render_stats(CamDev cam, const uint32_t* __restrict__ ranges,
+__global__ __launch_bounds__(256) void k_render_stats(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                       const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                       unsigned long long* __restrict__ counters)
 {
     __shared__ float4 sA[kBatch];
     __shared__ float4 sB[kBatch];
     __shared__ unsigned long long sCnt[2];
-    const TileCtx c = tile_ctx(cam, ranges);
+    const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     float T = 1.f;
     uint32_t examined = 0, blended = 0;
@@ -441,10 +441,11 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
                                 float* final_T, uint32_t* last_idx, hipStream_t s)
 {
     const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
+    const uint32_t* tile_order = reinterpret_cast<const uint32_t*>(ws + L.off_tile_order);
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     ProfScope prof(kKCompositeFwd, s);
-    hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed,
+    hipLaunchKernelGGL(k_composite_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, tile_order, vals, packed,
                        reinterpret_cast<uint8_t*>(ws + L.off_reach), bg[0], bg[1], bg[2], image, final_T, last_idx);
     return hipGetLastError();
 }
@@ -453,6 +454,7 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
                                 const SplatGradDev& g2, hipStream_t s)
 {
     const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
+    const uint32_t* tile_order = reinterpret_cast<const uint32_t*>(ws + L.off_tile_order);
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
@@ -462,7 +464,7 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
     {
         ProfScope prof(kKCompositeBwd, s);
-        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed,
+        hipLaunchKernelGGL(k_composite_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, tile_order, vals, packed,
                            reinterpret_cast<uint8_t*>(ws + L.off_reach), slot_base, bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage,
                            L.cap, status, partial);
     }
@@ -485,11 +487,12 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
 hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s)
 {
     const uint32_t* ranges = reinterpret_cast<const uint32_t*>(ws + L.off_ranges);
+    const uint32_t* tile_order = reinterpret_cast<const uint32_t*>(ws + L.off_tile_order);
     const uint32_t* vals = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     ProfScope prof(kKStats, s);
     hipLaunchKernelGGL(k_fill_f32, dim3(1), dim3(256), 0, s, reinterpret_cast<float*>(counters), 0.f, (size_t)4);
-    hipLaunchKernelGGL(k_render_stats, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, vals, packed,
+    hipLaunchKernelGGL(k_render_stats, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam, ranges, tile_order, vals, packed,
                        reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
 }

@@ -17,10 +17,13 @@ struct TileCtx {
     uint32_t start, end;
 };
 
-__device__ __forceinline__ TileCtx tile_ctx(const CamDev& cam, const uint32_t* __restrict__ ranges)
+// Workgroup b takes tile tile_order[b]: the hardware starts workgroups in index order, and the order array lists the
+// tiles with the longest lists first (k_tile_order), so the launch does not end on a few long tiles with the chip idle.
+__device__ __forceinline__ TileCtx tile_ctx(const CamDev& cam, const uint32_t* __restrict__ ranges,
+                                            const uint32_t* __restrict__ tile_order)
 {
     TileCtx c;
-    const int tile = blockIdx.x;
+    const int tile = (int)tile_order[blockIdx.x];
     const int ty = tile / cam.TX, tx = tile - ty * cam.TX;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     c.tix = tx; c.tiy = ty;

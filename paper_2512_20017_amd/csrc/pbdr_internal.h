@@ -128,7 +128,7 @@ struct Layout {
     int tile_bits, tile_passes;   // key bits / radix passes spent on the tile id
     size_t off_status, off_packed, off_depth_bits, off_vis_block, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
         off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
-        off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, off_reach, total;
+        off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, off_reach, off_tile_order, total;
 };
 constexpr int kSortItems = 2048;   // pairs per radix-sort block
 constexpr int kRadixMaxBins = 256;   // widest digit: 8 bits

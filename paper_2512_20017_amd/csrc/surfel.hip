@@ -407,13 +407,13 @@ __device__ __forceinline__ void eval_pair2d(const float4& a, const float4& b, co
     E.e2 = -kLog2e * (E.dx * E.dx + E.dy * E.dy);
 }
 
-__global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint32_t* __restrict__ ranges,
+__global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                          const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
                                                          float bg0, float bg1, float bg2, float* __restrict__ image,
                                                          float* __restrict__ final_T, uint32_t* __restrict__ last_idx)
 {
     __shared__ Stage2D S;
-    const TileCtx c = tile_ctx(cam, ranges);
+    const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     float T = 1.f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
@@ -467,7 +467,7 @@ __global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint3
 //   dT_0 = -sum dL/dh_u, dT_1 = -sum dL/dh_v, dT_2 = mx sum dL/dh_u + my sum dL/dh_v - T_1' x Sx - Sy x T_0'.
 // Together with 3 colour sums, d opacity and the 2 low-pass sums for mean2d: 15 sums per splat, through two row
 // butterflies, an LDS accumulator for the tile and one 64-byte record per (tile, splat) pair.
-__global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint32_t* __restrict__ ranges,
+__global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                          const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
                                                          const uint32_t* __restrict__ slot_base, float bg0, float bg1, float bg2,
                                                          const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
@@ -479,7 +479,7 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
     // a batch spread over the LDS banks)
     __shared__ float sAcc[kAccStride2D * kBatch];
     __shared__ uint32_t sMax[4];
-    const TileCtx c = tile_ctx(cam, ranges);
+    const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     const size_t HW = (size_t)cam.W * cam.H;
@@ -640,13 +640,13 @@ __global__ __launch_bounds__(256) void k_grad_records_to_planes2d(int n, const u
 }
 
 // Measurement aid: the forward walk with counters instead of colours (see the 3D variant).
-__global__ __launch_bounds__(256) void k_render_stats2d(CamDev cam, const uint32_t* __restrict__ ranges,
+__global__ __launch_bounds__(256) void k_render_stats2d(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                         const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
                                                         unsigned long long* __restrict__ counters)
 {
     __shared__ float4 sR[4][kBatch];
     __shared__ unsigned long long sCnt[2];
-    const TileCtx c = tile_ctx(cam, ranges);
+    const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     float T = 1.f;
     uint32_t examined = 0, blended = 0;
@@ -756,7 +756,8 @@ hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, 
 {
     ProfScope prof(kKCompositeFwd, s);
     hipLaunchKernelGGL(k_composite2d_fwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,
-                       reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
+                       reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + L.off_tile_order),
+                       reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
                        reinterpret_cast<const Packed2D*>(ws + L.off_packed), bg[0], bg[1], bg[2], image, final_T, last_idx);
     return hipGetLastError();
 }
@@ -773,7 +774,8 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
     {
         ProfScope prof(kKCompositeBwd, s);
         hipLaunchKernelGGL(k_composite2d_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,
-                           reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
+                           reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + L.off_tile_order),
+                       reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
                            reinterpret_cast<const Packed2D*>(ws + L.off_packed), reinterpret_cast<const uint32_t*>(ws + L.off_slot_base),
                            bg[0], bg[1], bg[2], final_T, last_idx, dL_dimage, L.cap, partial);
     }
@@ -799,7 +801,8 @@ hipError_t launch_render_stats2d(const CamDev& cam, const Layout& L, char* ws, u
     ProfScope prof(kKStats, s);
     hipLaunchKernelGGL(k_zero_counters2d, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned long long*>(counters));
     hipLaunchKernelGGL(k_render_stats2d, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,
-                       reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
+                       reinterpret_cast<const uint32_t*>(ws + L.off_ranges), reinterpret_cast<const uint32_t*>(ws + L.off_tile_order),
+                       reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L)),
                        reinterpret_cast<const Packed2D*>(ws + L.off_packed), reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
 }
