@@ -346,8 +346,8 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
 
     count[threadIdx.x] = 0u;
     __syncthreads();
+    uint32_t cls[kOrderRounds];
     for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
-        uint32_t cls[kOrderRounds];
         order_classes(range2, tb, t1, lane, cls);
 #pragma unroll
         for (uint32_t k = 0; k < kOrderRounds; ++k) {
@@ -373,8 +373,7 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
     }
     __syncthreads();
     for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
-        uint32_t cls[kOrderRounds];
-        order_classes(range2, tb, t1, lane, cls);
+        if (per_wave > kOrderRounds * 64u) order_classes(range2, tb, t1, lane, cls);      // else still there from the counting pass
 #pragma unroll
         for (uint32_t k = 0; k < kOrderRounds; ++k) {
             const uint64_t same = lanes_of_my_class(cls[k]);
