@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
 #pragma unroll
     for (int k = 0; k < K; ++k) {
 #pragma unroll
-        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * sc.sh[(size_t)(3 * k + c) * N + i];
+        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * __builtin_nontemporal_load(&sc.sh[(size_t)(3 * k + c) * N + i]);
     }
     // normal = R (t_u x t_v), turned towards the camera
     float nw[3] = {F.tu[1] * F.tv[2] - F.tu[2] * F.tv[1], F.tu[2] * F.tv[0] - F.tu[0] * F.tv[2], F.tu[0] * F.tv[1] - F.tu[1] * F.tv[0]};
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     out.mean2d[i] = mx; out.mean2d[N + i] = my;
 #pragma unroll
     for (int k = 0; k < 9; ++k) out.T[(size_t)k * N + i] = T[k];
-    out.opacity[i] = 1.0f / (1.0f + expf(-sc.logit[i]));
+    out.opacity[i] = 1.0f / (1.0f + expf(-__builtin_nontemporal_load(&sc.logit[i])));
 #pragma unroll
     for (int c = 0; c < 3; ++c) { out.color[(size_t)c * N + i] = fmaxf(rgb[c], 0.f); out.normal[(size_t)c * N + i] = sgn * nc[c]; }
     out.radius[i] = r;
@@ -193,12 +193,17 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     if (radius[i] <= 0) {
         if (kFirst) {
             constexpr int K0 = (kDeg + 1) * (kDeg + 1);
+            // zeros and SH / opacity reads: non-temporal, as in the 3D kernels (see preprocess.hip)
 #pragma unroll
-            for (int k = 0; k < 3; ++k) { g.mean[(size_t)k * N + i] = 0.f; g.tan_u[(size_t)k * N + i] = 0.f; g.tan_v[(size_t)k * N + i] = 0.f; }
-            g.log_scale[i] = 0.f; g.log_scale[N + i] = 0.f;
-            g.logit[i] = 0.f;
+            for (int k = 0; k < 3; ++k) {
+                __builtin_nontemporal_store(0.f, &g.mean[(size_t)k * N + i]);
+                __builtin_nontemporal_store(0.f, &g.tan_u[(size_t)k * N + i]);
+                __builtin_nontemporal_store(0.f, &g.tan_v[(size_t)k * N + i]);
+            }
+            __builtin_nontemporal_store(0.f, &g.log_scale[i]); __builtin_nontemporal_store(0.f, &g.log_scale[N + i]);
+            __builtin_nontemporal_store(0.f, &g.logit[i]);
 #pragma unroll
-            for (int k = 0; k < 3 * K0; ++k) g.sh[(size_t)k * N + i] = 0.f;
+            for (int k = 0; k < 3 * K0; ++k) __builtin_nontemporal_store(0.f, &g.sh[(size_t)k * N + i]);
         }
         return;
     }
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     Frame2D F;
     surfel_frame(cam, m, a, b, sc.log_scale[i], sc.log_scale[N + i], F);
     {
-        const float o = 1.0f / (1.0f + expf(-sc.logit[i]));
+        const float o = 1.0f / (1.0f + expf(-__builtin_nontemporal_load(&sc.logit[i])));
         grad_out<kFirst>(&g.logit[i], g2.opacity[i] * o * (1.f - o));
     }
     float dmu[3] = {0.f, 0.f, 0.f};
@@ -227,7 +232,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
             float raw = 0.5f, t0 = 0.f, t1 = 0.f, t2 = 0.f;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                const float co = sc.sh[(size_t)(3 * k + c) * N + i];
+                const float co = __builtin_nontemporal_load(&sc.sh[(size_t)(3 * k + c) * N + i]);
                 raw += Y[k] * co;
                 t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
             }
