@@ -2,7 +2,9 @@
 // are made of. Prints (1) the rate of independent plain v_fma_f32 (the fp32 vector peak that is reachable without packed
 // math) and (2) the issue cost, in cycles per SIMD at the nominal 2.4 GHz, of a plain add, a DPP add, v_exp_f32,
 // v_rcp_f32, a select and the two row-swap instructions, each measured as "two instructions per trip, one of them a
-// plain op of known cost". Results are meaningless numerically (the asm strings ignore DPP wait states on purpose:
+// plain op of known cost", and (3) the rate at which one compute unit's LDS returns reads of 4, 8 and 16 bytes per lane,
+// all lanes reading the same address (how the compositing kernels read a staged splat) and every lane its own.
+// Results are meaningless numerically (the asm strings ignore DPP wait states on purpose:
 // only the issue rate is measured) and nothing is read back but one float per lane.
 #include <hip/hip_runtime.h>
 
@@ -42,6 +44,28 @@ __global__ __launch_bounds__(256) void k_pair(float* out, int iters)
         }
     }
     out[blockIdx.x * 256 + threadIdx.x] = a + b + c + d;
+}
+
+// kBytes per lane per read; kSame: every lane of a wavefront reads the same address
+template <int kBytes, bool kSame>
+__global__ __launch_bounds__(256) void k_lds_read(float* out, int iters)
+{
+    __shared__ float4 buf[1024];
+    for (int i = threadIdx.x; i < 1024; i += 256) buf[i] = make_float4((float)i, 1.f, 2.f, 3.f);
+    __syncthreads();
+    float acc = 0.f;
+    const unsigned addr = kSame ? (threadIdx.x >> 6) * 64u : threadIdx.x * 16u;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned a = addr + ((i * 8 + u) & 63) * 48u;      // byte address inside buf (the kernel's only LDS array)
+            if (kBytes == 16) { float4 v; asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(4)" : "=v"(v) : "v"(a) : "memory"); acc += v.x; }
+            if (kBytes == 8) { float2 v; asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(4)" : "=v"(v) : "v"(a) : "memory"); acc += v.x; }
+            if (kBytes == 4) { float v; asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(4)" : "=v"(v) : "v"(a) : "memory"); acc += v; }
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)");
+    out[blockIdx.x * 256 + threadIdx.x] = acc + buf[threadIdx.x].y;
 }
 
 template <class F>
@@ -88,6 +112,18 @@ int main()
     for (int m = 0; m < 7; ++m) {
         const double both = ms[m] * 1e-3 * kClock / per_simd * 2.0;   // cycles per pair
         std::printf("%-24s %.2f cycles per wavefront instruction per SIMD\n", names[m], m == 0 ? plain : both - plain);
+    }
+    {   // LDS reads: 8 workgroups of 4 wavefronts per compute unit, up to 4 reads in flight per wavefront
+        const char* lnames[4] = {"ds_read_b32, same address", "ds_read_b64, same address", "ds_read_b128, same address", "ds_read_b128, own address"};
+        float lms[4];
+        const int liters = 2000;
+        if (timed([&](int w) { hipLaunchKernelGGL((k_lds_read<4, true>), dim3(nb), dim3(256), 0, 0, out, w ? w : liters); }, &lms[0])) return 1;
+        if (timed([&](int w) { hipLaunchKernelGGL((k_lds_read<8, true>), dim3(nb), dim3(256), 0, 0, out, w ? w : liters); }, &lms[1])) return 1;
+        if (timed([&](int w) { hipLaunchKernelGGL((k_lds_read<16, true>), dim3(nb), dim3(256), 0, 0, out, w ? w : liters); }, &lms[2])) return 1;
+        if (timed([&](int w) { hipLaunchKernelGGL((k_lds_read<16, false>), dim3(nb), dim3(256), 0, 0, out, w ? w : liters); }, &lms[3])) return 1;
+        const double per_cu = (double)nb * 4 / kCus * liters * 8;      // wavefront reads per compute unit
+        for (int m = 0; m < 4; ++m)
+            std::printf("%-28s %.2f cycles per wavefront read per compute unit\n", lnames[m], lms[m] * 1e-3 * kClock / per_cu);
     }
     CHECK(hipFree(out));
     return 0;
