@@ -277,17 +277,30 @@ __global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status
     if (2 * i < nranges) tile_order[i] = (uint32_t)i;      // no lists: any order will do
 }
 
-// One thread per sorted pair: mark where each tile's run starts and ends.
+// Four consecutive sorted pairs per thread: mark where each tile's run starts and ends.
 __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict__ tkeys, const uint32_t* __restrict__ status,
                                                      uint32_t cap, uint32_t ntiles, uint32_t* __restrict__ ranges)
 {
     const uint32_t P = min(status[kStNumDup], cap);
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= P) return;
-    const uint32_t tile = tkeys[i];
-    if (tile >= ntiles) return;     // cannot happen for keys written by k_duplicate; keeps the write in bounds regardless
-    if (i == 0 || tkeys[i - 1] != tile) ranges[2 * tile] = i;
-    if (i + 1 == P || tkeys[i + 1] != tile) ranges[2 * tile + 1] = i + 1;
+    const uint32_t i0 = (blockIdx.x * 256u + threadIdx.x) * 4u;
+    if (i0 >= P) return;
+    uint32_t t[6];      // the pair before, the four of this thread, the pair after
+    if (i0 + 4u <= P) {
+        const uint4 v = *reinterpret_cast<const uint4*>(tkeys + i0);
+        t[1] = v.x; t[2] = v.y; t[3] = v.z; t[4] = v.w;
+    } else {
+#pragma unroll
+        for (uint32_t k = 0; k < 4u; ++k) t[1 + k] = i0 + k < P ? tkeys[i0 + k] : 0xffffffffu;
+    }
+    t[0] = i0 > 0u ? tkeys[i0 - 1u] : 0xffffffffu;
+    t[5] = i0 + 4u < P ? tkeys[i0 + 4u] : 0xffffffffu;
+#pragma unroll
+    for (uint32_t k = 0; k < 4u; ++k) {
+        const uint32_t i = i0 + k, tile = t[1 + k];
+        if (i >= P || tile >= ntiles) continue;     // tile >= ntiles cannot happen for keys written by k_duplicate; keeps the writes in bounds regardless
+        if (i == 0u || t[k] != tile) ranges[2 * tile] = i;
+        if (i + 1u == P || t[2 + k] != tile) ranges[2 * tile + 1] = i + 1u;
+    }
 }
 
 // The order in which the compositing kernels take the tiles: longest lists first. Workgroups start in index order and a
@@ -489,7 +502,7 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
     {
         ProfScope prof(kKTileRanges, s);
         const uint32_t* sorted = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
-        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
+        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 1023u) / 1024u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
         // the call's tile grid (a patch covers fewer tiles than the image the workspace is sized for)
         hipLaunchKernelGGL(k_tile_order, dim3(1), dim3(1024), 0, s, ranges, (uint32_t)(cam.TX * cam.TY),
                            reinterpret_cast<uint32_t*>(ws + L.off_tile_order));
