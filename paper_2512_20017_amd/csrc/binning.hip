@@ -78,10 +78,24 @@ __global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, co
 __global__ __launch_bounds__(256) void k_rank_counts(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
                                                      const uint32_t* __restrict__ tiles_touched, uint32_t* __restrict__ counts)
 {
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    if (r > n) return;
+    // four consecutive ranks per thread (offsets, counts and order start on 16-byte boundaries)
+    const uint32_t r0 = (blockIdx.x * 256u + threadIdx.x) * 4u;
+    if (r0 > (uint32_t)n) return;
     const uint32_t m = min(status[kStNumVis], (uint32_t)n);
-    counts[r] = ((uint32_t)r < m) ? tiles_touched[order[r]] : 0u;
+    uint32_t c[4] = {0u, 0u, 0u, 0u};
+    if (r0 + 4u <= m) {
+        const uint4 o = *reinterpret_cast<const uint4*>(order + r0);
+        c[0] = tiles_touched[o.x]; c[1] = tiles_touched[o.y]; c[2] = tiles_touched[o.z]; c[3] = tiles_touched[o.w];
+    } else {
+#pragma unroll
+        for (uint32_t k = 0; k < 4u; ++k) if (r0 + k < m) c[k] = tiles_touched[order[r0 + k]];
+    }
+    if (r0 + 4u <= (uint32_t)n + 1u) {
+        *reinterpret_cast<uint4*>(counts + r0) = make_uint4(c[0], c[1], c[2], c[3]);
+    } else {
+#pragma unroll
+        for (uint32_t k = 0; k < 4u; ++k) if (r0 + k <= (uint32_t)n) counts[r0 + k] = c[k];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -487,7 +501,7 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
     const uint32_t* order = dv[radix_pass_count(32) & 1];
     {
         ProfScope prof(kKCountPack, s);
-        hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 256 + 1)), dim3(256), 0, s, sp.n, status, order, touched, offsets);
+        hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 1024 + 1)), dim3(256), 0, s, sp.n, status, order, touched, offsets);
     }
     e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n + 1u, part, status + kStNumDup, s);
     if (e != hipSuccess) return e;
