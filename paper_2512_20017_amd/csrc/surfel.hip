@@ -432,27 +432,49 @@ __global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint3
         __syncthreads();
         if (__ballot(live) == 0ull) continue;
         const uint32_t pos0 = base - c.start + 1u;
+        // alpha of one visit: everything that does not depend on the pixel's running state
+        auto eval = [&](int j, float& alpha, bool& ok, float& r, float& g, float& bl) {
+            const float4 a = S.a[j], b = S.b[j], cc = S.c[j], dd = S.d[j];
+            bl = dd.x; r = cc.z; g = cc.w;
+            Pair2D E;
+            eval_pair2d(a, b, cc, dd, fx, fy, E);
+            const float ex = (E.p2 != 0.f) ? fmaxf(E.e1, E.e2) : -1e30f;
+            alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.w + ex));
+            ok = (E.p2 != 0.f) && (alpha >= kAlphaMin);
+        };
+        auto blend_one = [&](int j, float alpha, bool ok, float r, float g, float bl) {
+            const bool valid = live && ok;
+            const float aT = alpha * T;
+            const float Tn = T - aT;            // T (1 - alpha), with the product the weight needs anyway
+            const bool stop = valid && (Tn < kTStop);
+            const bool blend = valid && !stop;
+            live = live && !stop;
+            const float w = blend ? aT : 0.f;
+            C0 += r * w; C1 += g * w; C2 += bl * w;
+            T = blend ? Tn : T;
+            last = blend ? pos0 + (uint32_t)j : last;
+        };
         for (int k = 0; k < 4; ++k) {
             unsigned long long m = uniform_u64(S.mask[wave][k]);
-            while (m) {
-                const int j = k * 64 + __builtin_ctzll(m);
+            // two visits per trip while there are two (independent alphas, blends in list order), as in the 3D kernel
+            while (m & (m - 1ull)) {
+                const int j0 = k * 64 + __builtin_ctzll(m);
                 m &= m - 1ull;
-                const float4 a = S.a[j], b = S.b[j], cc = S.c[j], dd = S.d[j];
-                const float blue = dd.x;
-                Pair2D E;
-                eval_pair2d(a, b, cc, dd, fx, fy, E);
-                const float ex = (E.p2 != 0.f) ? fmaxf(E.e1, E.e2) : -1e30f;
-                const float alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.w + ex));
-                const bool valid = live && (E.p2 != 0.f) && (alpha >= kAlphaMin);
-                const float aT = alpha * T;
-                const float Tn = T - aT;            // T (1 - alpha), with the product the weight needs anyway
-                const bool stop = valid && (Tn < kTStop);
-                const bool blend = valid && !stop;
-                live = live && !stop;
-                const float w = blend ? aT : 0.f;
-                C0 += cc.z * w; C1 += cc.w * w; C2 += blue * w;
-                T = blend ? Tn : T;
-                last = blend ? pos0 + (uint32_t)j : last;
+                const int j1 = k * 64 + __builtin_ctzll(m);
+                m &= m - 1ull;
+                float al0, red0, grn0, blu0, al1, red1, grn1, blu1;
+                bool ok0, ok1;
+                eval(j0, al0, ok0, red0, grn0, blu0);
+                eval(j1, al1, ok1, red1, grn1, blu1);
+                blend_one(j0, al0, ok0, red0, grn0, blu0);
+                blend_one(j1, al1, ok1, red1, grn1, blu1);
+            }
+            if (m) {
+                const int j0 = k * 64 + __builtin_ctzll(m);
+                float al0, red0, grn0, blu0;
+                bool ok0;
+                eval(j0, al0, ok0, red0, grn0, blu0);
+                blend_one(j0, al0, ok0, red0, grn0, blu0);
             }
         }
     }
