@@ -580,7 +580,9 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                     // even lanes of a row keep the first eight sums, odd lanes (their copies) take the second eight;
                     // the four rows are added lane by lane, and the 16 lanes of the last row issue the one LDS add
                     const float tot = sum_rows((lane & 1) ? pb : pa);
-                    if (lane >= 48) atomicAdd(&sAcc[kAccStride2D * j + acc_slot], tot);
+                    int acc_base = kAccStride2D * j;
+                    asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (as in the 3D kernel)
+                    if (lane >= 48) atomicAdd(&sAcc[acc_base + acc_slot], tot);
                 }
             }
         }
