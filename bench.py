@@ -304,7 +304,7 @@ def main():
     sum_last = int(last_idx.to(torch.int64).sum().item())
 
     # the step's output is dL/d(parameters); the 3D call then need not write dL/d(splat state) out (--splat-grads: do)
-    g_out = g_splats if (surfels or args.splat_grads) else None
+    g_out = g_splats if args.splat_grads else None
 
     def step():
         # One view per step: the backward call is the first view of its batch, so it also does the zeroing of the

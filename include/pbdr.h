@@ -308,7 +308,7 @@ int pbdr2d_render_fwd(const pbdr2d_splats* splats, const pbdr_camera* cam, const
                       void* hip_stream);
 
 /* image_render.backward then pts_splatting.backward for surfels (Alg. 1 lines 17-18, 22-24); arguments and the
- * scene/grads NULL rule as pbdr_render_bwd. */
+ * scene/grads NULL rule and the g_splats NULL rule (64-byte records here) as pbdr_render_bwd. */
 int pbdr2d_render_bwd(const pbdr2d_scene* scene, const pbdr2d_splats* splats, const pbdr_camera* cam, const float bg[3],
                       uint64_t dup_capacity, const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
                       pbdr2d_splat_grads* g_splats, pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes,

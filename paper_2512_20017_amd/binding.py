@@ -630,7 +630,8 @@ def pbdr2d_render_fwd(splats: Splats2D, cam: dict, bg, dup_capacity: int, image,
 
 def pbdr2d_render_bwd(scene, splats: Splats2D, cam: dict, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
                       g_splats: SplatGrads2D, grads, ws, stream=None, first_view=False) -> None:
-    sp, c, g2 = splats.struct(), camera_struct(cam), g_splats.struct()
+    sp, c = splats.struct(), camera_struct(cam)
+    g2 = g_splats.struct() if g_splats is not None else None      # None (with scene/grads given): no splat-state gradient output
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
         sc, g = scene.struct(), grads.struct(first_view)
@@ -638,7 +639,7 @@ def pbdr2d_render_bwd(scene, splats: Splats2D, cam: dict, bg, dup_capacity: int,
     else:
         psc, pg = None, None
     _check(lib().pbdr2d_render_bwd(psc, C.byref(sp), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(final_T), _dev(last_idx),
-                                   _dev(dL_dimage), C.byref(g2), pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
+                                   _dev(dL_dimage), C.byref(g2) if g2 is not None else None, pg, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()),
                                    _stream(stream)))
 
 
@@ -658,7 +659,8 @@ def pbdr2d_render_fwd_patch(splats: Splats2D, cam: dict, patch, bg, dup_capacity
 
 def pbdr2d_render_bwd_patch(scene, splats: Splats2D, cam: dict, patch, bg, dup_capacity: int, final_T, last_idx, dL_dimage,
                             g_splats: SplatGrads2D, grads, ws, stream=None, first_view=False) -> None:
-    sp, c, p, g2 = splats.struct(), camera_struct(cam), _patch(patch), g_splats.struct()
+    sp, c, p = splats.struct(), camera_struct(cam), _patch(patch)
+    g2 = g_splats.struct() if g_splats is not None else None
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     if scene is not None:
         sc, g = scene.struct(), grads.struct(first_view)
@@ -666,7 +668,7 @@ def pbdr2d_render_bwd_patch(scene, splats: Splats2D, cam: dict, patch, bg, dup_c
     else:
         psc, pg = None, None
     _check(lib().pbdr2d_render_bwd_patch(psc, C.byref(sp), C.byref(c), C.byref(p), bgv, C.c_uint64(dup_capacity),
-                                         _dev(final_T), _dev(last_idx), _dev(dL_dimage), C.byref(g2), pg,
+                                         _dev(final_T), _dev(last_idx), _dev(dL_dimage), C.byref(g2) if g2 is not None else None, pg,
                                          C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
 
 

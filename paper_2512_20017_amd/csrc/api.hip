@@ -586,9 +586,9 @@ static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* spl
                              const uint32_t* last_idx, const float* dL_dimage, pbdr2d_splat_grads* g_splats,
                              pbdr2d_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!check_splats2d(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) ||
-        !aligned16(dL_dimage) || !check_splat2d_grads(g_splats, splats->n))
+    if (!check_splats2d(splats) || !check_camera(cam) || !bg || !aligned16(final_T) || !aligned16(last_idx) || !aligned16(dL_dimage))
         return PBDR_ERR_INVALID_ARG;
+    if (g_splats ? !check_splat2d_grads(g_splats, splats->n) : scene == nullptr) return PBDR_ERR_INVALID_ARG;
     if (patch && !check_patch(cam, patch)) return PBDR_ERR_INVALID_ARG;
     if ((scene == nullptr) != (grads == nullptr)) return PBDR_ERR_INVALID_ARG;
     if (scene && (!check_scene2d(scene) || scene->n != splats->n || !check_scene2d_grads(grads, scene))) return PBDR_ERR_INVALID_ARG;
@@ -596,9 +596,15 @@ static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* spl
     const int st = workspace_ok(workspace, workspace_bytes, splats->n, cam->width, cam->height, dup_capacity, &L, kVariant2D);
     if (st != PBDR_OK) return st;
     const CamDev c = to_dev(cam, patch);
-    hipError_t e = launch_composite2d_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, dev(g_splats),
+    const Splat2DGradDev g2 = g_splats ? dev(g_splats) : Splat2DGradDev{nullptr, nullptr, nullptr, nullptr};
+    hipError_t e = launch_composite2d_bwd(c, L, (char*)workspace, splats->n, bg, final_T, last_idx, dL_dimage, g2,
                                           (hipStream_t)hip_stream);
     if (e != hipSuccess || !scene) return hip_result(e);
+    if (!g_splats)      // no splat-state gradient asked for: the splatting backward reads the workspace's per-point records
+        return hip_result(launch_preprocess2d_bwd_records(dev(scene), c, dev(splats),
+                                                          reinterpret_cast<const uint32_t*>((char*)workspace + L.off_touched),
+                                                          reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec), dev(grads),
+                                                          grads->first_view != 0, (hipStream_t)hip_stream));
     return hip_result(launch_preprocess2d_bwd(dev(scene), c, dev(splats), dev(g_splats), dev(grads), grads->first_view != 0,
                                               (hipStream_t)hip_stream));
 }

@@ -182,6 +182,8 @@ hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& out, hipStream_t s);
 hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
                                    const Scene2DGradDev& g, bool first_view, hipStream_t s);
+hipError_t launch_preprocess2d_bwd_records(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const uint32_t* tiles_touched,
+                                           const float4* rec, const Scene2DGradDev& g, bool first_view, hipStream_t s);
 hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
                                   float* final_T, uint32_t* last_idx, hipStream_t s);

@@ -182,9 +182,12 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     out.depth[i] = T[8];
 }
 
-template <int kDeg, bool kFirst>      // kFirst: see the 3D variant
+// kFirst, kFromRecords: see the 3D variant. With kFromRecords the splat-state gradient of a point is the 64-byte record
+// the gather of the compositing backward left in the workspace (`rec`), and `radius` is the tiles-touched count.
+template <int kDeg, bool kFirst, bool kFromRecords>
 __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev cam, const int32_t* __restrict__ radius,
-                                                          const float* __restrict__ Tst, Splat2DGradDev g2, Scene2DGradDev g)
+                                                          const float* __restrict__ Tst, Splat2DGradDev g2,
+                                                          const float4* __restrict__ rec, Scene2DGradDev g)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -207,6 +210,20 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
         }
         return;
     }
+    // dL/d(splat state): T (nine), mean2d (two), opacity, colour (three), in the record's order
+    float gs[15];
+    if (kFromRecords) {
+        const float4 ra = rec[(size_t)4 * i], rb = rec[(size_t)4 * i + 1], rc = rec[(size_t)4 * i + 2], rd = rec[(size_t)4 * i + 3];
+        const float v[15] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w, rc.x, rc.y, rc.z, rc.w, rd.x, rd.y, rd.z};
+#pragma unroll
+        for (int k = 0; k < 15; ++k) gs[k] = v[k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < 9; ++k) gs[k] = g2.T[(size_t)k * N + i];
+        gs[9] = g2.mean2d[i]; gs[10] = g2.mean2d[N + i];
+        gs[11] = g2.opacity[i];
+        gs[12] = g2.color[i]; gs[13] = g2.color[N + i]; gs[14] = g2.color[2 * N + i];
+    }
     const float m[3] = {sc.mean[i], sc.mean[N + i], sc.mean[2 * N + i]};
     const float a[3] = {sc.tan_u[i], sc.tan_u[N + i], sc.tan_u[2 * N + i]};
     const float b[3] = {sc.tan_v[i], sc.tan_v[N + i], sc.tan_v[2 * N + i]};
@@ -214,7 +231,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     surfel_frame(cam, m, a, b, sc.log_scale[i], sc.log_scale[N + i], F);
     {
         const float o = 1.0f / (1.0f + expf(-__builtin_nontemporal_load(&sc.logit[i])));
-        grad_out<kFirst>(&g.logit[i], g2.opacity[i] * o * (1.f - o));
+        grad_out<kFirst>(&g.logit[i], gs[11] * o * (1.f - o));
     }
     float dmu[3] = {0.f, 0.f, 0.f};
     {
@@ -236,7 +253,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
                 raw += Y[k] * co;
                 t0 += dY[k][0] * co; t1 += dY[k][1] * co; t2 += dY[k][2] * co;
             }
-            const float gc = raw > 0.f ? g2.color[(size_t)c * N + i] : 0.f;
+            const float gc = raw > 0.f ? gs[12 + c] : 0.f;
             if (kFirst || gc != 0.f) {
 #pragma unroll
                 for (int k = 0; k < K; ++k) grad_out<kFirst>(&g.sh[(size_t)(3 * k + c) * N + i], Y[k] * gc);
@@ -249,10 +266,10 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     // gradient w.r.t. the stored transform, plus mean2d_i = T_i2 / T_22
     float GT[9];
 #pragma unroll
-    for (int k = 0; k < 9; ++k) GT[k] = g2.T[(size_t)k * N + i];
+    for (int k = 0; k < 9; ++k) GT[k] = gs[k];
     {
         const float T02 = Tst[2 * N + i], T12 = Tst[5 * N + i], T22 = Tst[8 * N + i];
-        const float iz = 1.0f / T22, gmx = g2.mean2d[i], gmy = g2.mean2d[N + i];
+        const float iz = 1.0f / T22, gmx = gs[9], gmy = gs[10];
         GT[2] += gmx * iz; GT[5] += gmy * iz;
         GT[8] -= (gmx * T02 + gmy * T12) * iz * iz;
     }
@@ -741,15 +758,15 @@ hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Sp
     return hipGetLastError();
 }
 
-template <bool kFirst>
-static void launch_preprocess2d_bwd_t(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
-                                      const Scene2DGradDev& g, unsigned blocks, hipStream_t s)
+template <bool kFirst, bool kFromRecords>
+static void launch_preprocess2d_bwd_t(const Scene2DDev& sc, const CamDev& cam, const int32_t* used, const float* Tst,
+                                      const Splat2DGradDev& g2, const float4* rec, const Scene2DGradDev& g, unsigned blocks, hipStream_t s)
 {
     switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL((k_preprocess2d_bwd<0, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-        case 1: hipLaunchKernelGGL((k_preprocess2d_bwd<1, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-        case 2: hipLaunchKernelGGL((k_preprocess2d_bwd<2, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
-        default: hipLaunchKernelGGL((k_preprocess2d_bwd<3, kFirst>), dim3(blocks), dim3(256), 0, s, sc, cam, sp.radius, sp.T, g2, g); break;
+        case 0: hipLaunchKernelGGL((k_preprocess2d_bwd<0, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess2d_bwd<1, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess2d_bwd<2, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
+        default: hipLaunchKernelGGL((k_preprocess2d_bwd<3, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
     }
 }
 
@@ -759,8 +776,22 @@ hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, cons
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    if (first_view) launch_preprocess2d_bwd_t<true>(sc, cam, sp, g2, g, blocks, s);
-    else launch_preprocess2d_bwd_t<false>(sc, cam, sp, g2, g, blocks, s);
+    if (first_view) launch_preprocess2d_bwd_t<true, false>(sc, cam, sp.radius, sp.T, g2, nullptr, g, blocks, s);
+    else launch_preprocess2d_bwd_t<false, false>(sc, cam, sp.radius, sp.T, g2, nullptr, g, blocks, s);
+    return hipGetLastError();
+}
+
+// the same from the per-point gradient records in the workspace (see k_preprocess2d_bwd)
+hipError_t launch_preprocess2d_bwd_records(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const uint32_t* tiles_touched,
+                                           const float4* rec, const Scene2DGradDev& g, bool first_view, hipStream_t s)
+{
+    if (sc.n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((sc.n + 255) / 256);
+    const int32_t* used = reinterpret_cast<const int32_t*>(tiles_touched);     // counts are far below 2^31
+    const Splat2DGradDev none{nullptr, nullptr, nullptr, nullptr};
+    ProfScope prof(kKPreprocessBwd, s);
+    if (first_view) launch_preprocess2d_bwd_t<true, true>(sc, cam, used, sp.T, none, rec, g, blocks, s);
+    else launch_preprocess2d_bwd_t<false, true>(sc, cam, used, sp.T, none, rec, g, blocks, s);
     return hipGetLastError();
 }
 
@@ -819,8 +850,9 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
         hipLaunchKernelGGL(k_gather2d, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank, partial,
                            L.cap, carry, rec);
         hipLaunchKernelGGL(k_gather2d_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
-        hipLaunchKernelGGL(k_grad_records_to_planes2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
-                           reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
+        if (g2.mean2d != nullptr)       // else the caller goes on from the records (launch_preprocess2d_bwd_records)
+            hipLaunchKernelGGL(k_grad_records_to_planes2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
+                               reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
     }
     return hipGetLastError();
 }

@@ -300,3 +300,53 @@ def test_first_view_writes_what_zero_then_accumulate_leaves():
         assert np.isfinite(a[k]).all(), k
         np.testing.assert_allclose(a[k], b[k], rtol=4e-6, atol=1e-6 * np.abs(b[k]).max())
         assert not a[k][unused].any(), k
+
+
+def test_backward_without_splat_gradient_output():
+    """g_splats = NULL with a scene: the splatting backward reads the per-point records in the workspace instead of the
+    planes; the parameter gradient is the one the two-step path gives (same values and formulas; the two compositing runs
+    differ by the rounding of their LDS adds and the two kernel variants by the compiler's choice of fused multiply-adds:
+    4e-6 relative, as between the store and accumulate variants), as a store and as an accumulation, for the whole image
+    and for a patch."""
+    sc = synth.random_small_surfels(43, 3000, 2, spread=1.2)
+    cam = synth.pinhole(160, 96, 50.0, *synth.look_at([0.3, 0.1, -2.5], [0, 0, 0], [0, 1, 0]))
+    scene = B.Scene2D.from_numpy(sc)
+    view = SurfelView(3000, cam, 400000)
+    sp = view.preprocess(scene)
+    assert 0 < (sp["radius"] > 0).sum() < 3000
+    view.render_fwd(BG)
+    G = to_chw_dev(np.random.default_rng(3).normal(size=(96, 160, 3)).astype(np.float32))
+    for first in (True, False):
+        ref, got = scene.zeros_like(), scene.zeros_like()
+        if not first:
+            for t in (ref, got):
+                t.mean.fill_(0.25); t.sh.fill_(-0.5)
+        B.pbdr2d_render_bwd(scene, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, G, view.g_splats, ref, view.ws,
+                            first_view=first)
+        B.pbdr2d_render_bwd(scene, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, G, None, got, view.ws,
+                            first_view=first)
+        torch.cuda.synchronize()
+        a, b = got.to_numpy(), ref.to_numpy()
+        for k in PARAM_KEYS:
+            np.testing.assert_allclose(a[k], b[k], rtol=4e-6, atol=1e-6 * np.abs(b[k]).max(), err_msg=f"{k} {first}")
+            assert np.array_equal(a[k] == 0, b[k] == 0) or first is False, k      # the same points get exact zeros
+        assert np.abs(b["mean"]).max() > 0
+    # a patch
+    patch = (37, 10, 140, 81)
+    w, h = patch[2] - patch[0], patch[3] - patch[1]
+    splats = B.Splats2D.empty(3000)
+    B.pbdr2d_preprocess_patch(scene, cam, patch, splats)
+    image = torch.empty((3, h, w), device="cuda"); T = torch.empty((h, w), device="cuda")
+    last = torch.empty((h, w), dtype=torch.int32, device="cuda")
+    B.pbdr2d_render_fwd_patch(splats, cam, patch, BG, view.cap, image, T, last, view.ws)
+    Gp = G[:, patch[1]:patch[3], patch[0]:patch[2]].contiguous()
+    ref, got = scene.zeros_like(), scene.zeros_like()
+    B.pbdr2d_render_bwd_patch(scene, splats, cam, patch, BG, view.cap, T, last, Gp, view.g_splats, ref, view.ws, first_view=True)
+    B.pbdr2d_render_bwd_patch(scene, splats, cam, patch, BG, view.cap, T, last, Gp, None, got, view.ws, first_view=True)
+    torch.cuda.synchronize()
+    a, b = got.to_numpy(), ref.to_numpy()
+    for k in PARAM_KEYS:
+        np.testing.assert_allclose(a[k], b[k], rtol=4e-6, atol=1e-6 * np.abs(b[k]).max(), err_msg=k)
+    # no output at all is still an error
+    with pytest.raises(B.PbdrError):
+        B.pbdr2d_render_bwd(None, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, G, None, None, view.ws)
