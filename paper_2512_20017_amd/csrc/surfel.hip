@@ -541,8 +541,24 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
     if (lane == 0) sMax[wave] = wmax;
     __syncthreads();
     const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
-    if (tile_last == 0) return;
     const int tile_x = c.tix, tile_y = c.tiy;
+    // The pairs behind the last splat any pixel of the tile blended are never staged; the gather adds up the records of
+    // all pairs, so theirs are written as zeros here (every pair is in exactly one tile's list: each record is written
+    // exactly once per call, here or at the end of its batch, and no fill of the whole array is needed beforehand).
+    for (uint32_t p = tile_last + threadIdx.x; p < c.end - c.start; p += 256u) {
+        const uint32_t idz = vals[c.start + p];
+        const float4* rz = reinterpret_cast<const float4*>(packed + idz);
+        const float4 z2 = rz[2], z3 = rz[3];
+        int x0, y0, x1, y1;
+        tile_rect(cam, z2.x, z2.y, __float_as_int(z3.y), x0, y0, x1, y1);
+        const uint32_t u = slot_base[idz] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
+        if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
+            float4* dst = partial + (size_t)4 * u;
+            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+            dst[0] = zero; dst[1] = zero; dst[2] = zero; dst[3] = zero;
+        }
+    }
+    if (tile_last == 0) return;
     const bool bit1 = (lane & 2) != 0;
     const int acc_slot = ((lane & 1) ? 8 : 0) + ((lane >> 1) & 7);     // see row_sum8: odd lanes take the second eight sums
     const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
@@ -736,13 +752,6 @@ __global__ __launch_bounds__(64) void k_zero_counters2d(unsigned long long* __re
     if (threadIdx.x < 2) counters[threadIdx.x] = 0ull;
 }
 
-__global__ __launch_bounds__(256) void k_zero_partial2d(float4* __restrict__ partial, const uint32_t* __restrict__ status, uint32_t cap)
-{
-    const size_t count = (size_t)4 * min(status[kStNumDup], cap);
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < count) partial[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-}
-
 // ---------------------------------------------------------------------------------------------------- launchers
 hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& out, hipStream_t s)
 {
@@ -827,10 +836,6 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
 {
     const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
     float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
-    {
-        ProfScope prof(kKFill, s);
-        hipLaunchKernelGGL(k_zero_partial2d, dim3((unsigned)(((size_t)4 * L.cap + 255) / 256)), dim3(256), 0, s, partial, status, L.cap);
-    }
     {
         ProfScope prof(kKCompositeBwd, s);
         hipLaunchKernelGGL(k_composite2d_bwd, dim3((unsigned)(cam.TX * cam.TY)), dim3(256), 0, s, cam,

@@ -350,3 +350,40 @@ def test_backward_without_splat_gradient_output():
     # no output at all is still an error
     with pytest.raises(B.PbdrError):
         B.pbdr2d_render_bwd(None, view.splats, cam, BG, view.cap, view.final_T, view.last_idx, G, None, None, view.ws)
+
+
+def test_backward_writes_every_per_pair_record_itself():
+    """The backward pass needs no cleared workspace: records of pairs that lie behind the last splat their tile blended are
+    written as zeros by the compositing kernel. A dense scene (most lists end early on transmittance) is rendered with
+    the whole workspace poisoned with NaN bit patterns before the forward pass; the gradient equals that of a clean run."""
+    sc = synth.random_small_surfels(47, 6000, 1, spread=0.5, ls_mu=-1.6)     # large, overlapping disks
+    sc["logit"] = np.full(6000, 4.0, dtype=np.float32)                       # nearly opaque: pixels saturate early
+    cam = synth.pinhole(160, 96, 50.0, *synth.look_at([0.2, 0.1, -2.5], [0, 0, 0], [0, 1, 0]))
+    scene = B.Scene2D.from_numpy(sc)
+    G = np.random.default_rng(9).normal(size=(96, 160, 3)).astype(np.float32)
+    out = []
+    for poison in (False, True):
+        view = SurfelView(6000, cam, 600000)
+        view.ws.fill_(0xFF if poison else 0)
+        vis = view.preprocess(scene)["radius"] > 0
+        fw = view.render_fwd(BG)
+        lists = view.lists()
+        grads = scene.zeros_like()
+        g2 = view.render_bwd(BG, G, scene=scene, grads=grads)
+        out.append((g2, grads.to_numpy(), fw, lists))
+    (g2a, ga, fwa, la), (g2b, gb, fwb, lb) = out
+    # the case is what it claims: many pairs lie behind the last blended splat of their tile
+    tiles = la["ranges"]
+    walked = 0
+    last = fwa["last_idx"]
+    for t in range(tiles.shape[0]):
+        ty, tx = divmod(t, 10)
+        walked += int(last[ty * 16:(ty + 1) * 16, tx * 16:(tx + 1) * 16].max())
+    assert walked < 0.8 * la["P"], (walked, la["P"])
+    assert np.array_equal(fwa["image"], fwb["image"])
+    for k in g2a:      # the splat-state gradient is written for the listed points only
+        assert np.isfinite(g2b[k][vis]).all(), k
+        np.testing.assert_allclose(g2b[k][vis], g2a[k][vis], rtol=1e-5, atol=1e-6 * np.abs(g2a[k][vis]).max(), err_msg=k)
+    for k in PARAM_KEYS:
+        assert np.isfinite(gb[k]).all(), k
+        np.testing.assert_allclose(gb[k], ga[k], rtol=1e-5, atol=1e-6 * np.abs(ga[k]).max(), err_msg=k)
