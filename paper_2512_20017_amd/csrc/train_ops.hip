@@ -114,6 +114,9 @@ hipError_t launch_l1_loss(int W, int H, const float* image, const float* target,
     const size_t nvec = count / 4;
     unsigned blocks = (unsigned)((nvec + 256 * 4 - 1) / (256 * 4));     // four float4 per lane
     if (blocks < 1) blocks = 1;
+    // every workgroup ends in one float atomic on the same word, and those serialise: at 1080p 1,519 workgroups (four
+    // float4 per lane) took 31 us, 512 (grid-stride) take 20; 256 are too few wavefronts to stream at full rate (26 us)
+    if (blocks > 512) blocks = 512;
     ProfScope prof(kKLoss, s);
     hipLaunchKernelGGL(k_l1_loss, dim3(blocks), dim3(256), 0, s, image, target, count, (float)(1.0 / (double)count), loss, dL);
     return hipGetLastError();
