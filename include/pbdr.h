@@ -44,7 +44,8 @@ typedef enum pbdr_status {
     PBDR_ERR_INVALID_ARG = -1,         /* null / misaligned pointer, n < 0, sh_degree outside 0..3, bad image size */
     PBDR_ERR_WORKSPACE_TOO_SMALL = -2, /* workspace smaller than pbdr_workspace_bytes() for these sizes */
     PBDR_ERR_CAPACITY = -3,            /* more (tile, splat) pairs than dup_capacity (reported by pbdr_query_lists) */
-    PBDR_ERR_HIP = -4                  /* a HIP call failed; see pbdr_last_hip_error() */
+    PBDR_ERR_HIP = -4,                 /* a HIP call failed; see pbdr_last_hip_error() */
+    PBDR_ERR_STATIC_LIMIT = -5         /* pbdr_render_fwd_static: more points or a larger image than its fixed scratch serves */
 } pbdr_status;
 
 /* Point cloud shard ("model state", Sec. 3.1; 3DGS attributes Sec. 2.1 / 3.2): 59 floats per point at degree 3. */
@@ -190,6 +191,25 @@ int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t du
 int pbdr_render_fwd(const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3], uint64_t dup_capacity,
                     float* image, float* final_T, uint32_t* last_idx, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
+
+/* pbdr_render_fwd for callers that cannot allocate device memory at all (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels in the same order, with the workspace taken from a fixed
+ * array of PBDR_STATIC_SCRATCH_BYTES that lives in the library's device image (each GPU the library runs on holds its
+ * own copy until the process ends) instead of from the caller. The call allocates and frees nothing; its first use on
+ * a device only looks up that device's address of the array. Limits: splats->n <= PBDR_STATIC_MAX_POINTS, width and
+ * height <= PBDR_STATIC_MAX_SIDE, at most PBDR_STATIC_MAX_PAIRS (tile, splat) pairs (the dup_capacity of the call; the
+ * excess is dropped as pbdr_render_fwd drops it). Larger n or image: PBDR_ERR_STATIC_LIMIT, nothing enqueued.
+ * image, final_T, last_idx as pbdr_render_fwd, bit for bit what it writes for dup_capacity = PBDR_STATIC_MAX_PAIRS.
+ * pair_count: device pointer to one uint32 that receives the number of pairs found (before clamping; a value above
+ * PBDR_STATIC_MAX_PAIRS means the lists were truncated), or NULL. Rendering only: the lists stay in the library's
+ * array, there is no matching backward call. Every call on one GPU uses that GPU's one array, whatever its stream:
+ * calls that may overlap in time on one GPU race with each other - order them on one stream or with events. */
+#define PBDR_STATIC_MAX_POINTS 16384
+#define PBDR_STATIC_MAX_SIDE 512
+#define PBDR_STATIC_MAX_PAIRS 262144
+#define PBDR_STATIC_SCRATCH_BYTES (24u << 20)
+int pbdr_render_fwd_static(const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3], float* image,
+                           float* final_T, uint32_t* last_idx, uint32_t* pair_count, void* hip_stream);
 
 /* image_render.backward then pts_splatting.backward (Alg. 1 lines 17-18 and 22-24). Needs the workspace exactly
  * as pbdr_render_fwd left it for the same splats, camera and dup_capacity. dL_dimage [3][H][W]. g_splats is overwritten with

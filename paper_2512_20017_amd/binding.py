@@ -21,6 +21,11 @@ PBDR_ERR_INVALID_ARG = -1
 PBDR_ERR_WORKSPACE_TOO_SMALL = -2
 PBDR_ERR_CAPACITY = -3
 PBDR_ERR_HIP = -4
+PBDR_ERR_STATIC_LIMIT = -5
+PBDR_STATIC_MAX_POINTS = 16384
+PBDR_STATIC_MAX_SIDE = 512
+PBDR_STATIC_MAX_PAIRS = 262144
+PBDR_STATIC_SCRATCH_BYTES = 24 << 20
 
 EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_render_fwd", "pbdr_render_bwd",
            "pbdr_preprocess_bwd", "pbdr_lists_view", "pbdr_query_lists", "pbdr_status_string", "pbdr_last_hip_error",
@@ -31,7 +36,7 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
            "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch",
            "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective", "pbdr_preprocess_batch", "pbdr_preprocess_bwd_batch",
-           "pbdr_preprocess_bwd_batch_adam", "pbdr_tile_order_view")
+           "pbdr_preprocess_bwd_batch_adam", "pbdr_tile_order_view", "pbdr_render_fwd_static")
 
 _f = C.POINTER(C.c_float)
 
@@ -342,6 +347,14 @@ def pbdr_render_fwd(splats: Splats, cam: dict, bg, dup_capacity: int, image, fin
     bgv = (C.c_float * 3)(*[float(x) for x in bg])
     _check(lib().pbdr_render_fwd(C.byref(s), C.byref(c), bgv, C.c_uint64(dup_capacity), _dev(image), _dev(final_T),
                                  _dev(last_idx), C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def pbdr_render_fwd_static(splats: Splats, cam: dict, bg, image, final_T, last_idx, pair_count=None, stream=None) -> None:
+    """pbdr_render_fwd on the library's own fixed scratch array (no workspace argument); pair_count: uint32 tensor [1] or None."""
+    s, c = splats.struct(), camera_struct(cam)
+    bgv = (C.c_float * 3)(*[float(x) for x in bg])
+    _check(lib().pbdr_render_fwd_static(C.byref(s), C.byref(c), bgv, _dev(image), _dev(final_T), _dev(last_idx),
+                                        _dev(pair_count), _stream(stream)))
 
 
 def pbdr_render_bwd(scene, splats: Splats, cam: dict, bg, dup_capacity: int, final_T, last_idx, dL_dimage,

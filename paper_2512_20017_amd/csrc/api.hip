@@ -3,8 +3,40 @@
 #include "pbdr_internal.h"
 
 #include <cmath>
+#include <mutex>
 
 namespace pbdr {
+
+// Workspace of pbdr_render_fwd_static: part of the library's device image, one copy per GPU. Host code never uses this
+// name as an address; static_scratch() asks the runtime where the current device keeps its copy.
+static __device__ __align__(256) unsigned char scratch[PBDR_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];      // per device, filled on first use
+static std::mutex g_scratch_mutex;
+
+static hipError_t static_scratch(void** out)
+{
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 255u) != 0) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
+__global__ void k_copy_word(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
+}
 
 static thread_local int g_last_hip_error = 0;
 
@@ -202,6 +234,7 @@ const char* pbdr_status_string(int status)
         case PBDR_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case PBDR_ERR_CAPACITY: return "more (tile, splat) pairs than dup_capacity";
         case PBDR_ERR_HIP: return "HIP error";
+        case PBDR_ERR_STATIC_LIMIT: return "more points or a larger image than the static scratch buffer serves";
         default: return "unknown status";
     }
 }
@@ -356,6 +389,32 @@ static int render_fwd_impl(const pbdr_splats* splats, const pbdr_camera* cam, co
     hipError_t e = launch_bin_sort(dev(splats), c, L, (char*)workspace, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_result(e);
     return hip_result(launch_composite_fwd(c, L, (char*)workspace, bg, image, final_T, last_idx, (hipStream_t)hip_stream));
+}
+
+int pbdr_render_fwd_static(const pbdr_splats* splats, const pbdr_camera* cam, const float bg[3], float* image,
+                           float* final_T, uint32_t* last_idx, uint32_t* pair_count, void* hip_stream)
+{
+    if (!check_splats(splats) || !check_camera(cam) || !bg || !aligned16(image) || !aligned16(final_T) || !aligned16(last_idx))
+        return PBDR_ERR_INVALID_ARG;
+    if (pair_count && (reinterpret_cast<uintptr_t>(pair_count) & 3u)) return PBDR_ERR_INVALID_ARG;
+    if (splats->n > PBDR_STATIC_MAX_POINTS || cam->width > PBDR_STATIC_MAX_SIDE || cam->height > PBDR_STATIC_MAX_SIDE)
+        return PBDR_ERR_STATIC_LIMIT;
+    Layout L;
+    if (!make_layout(splats->n, cam->width, cam->height, PBDR_STATIC_MAX_PAIRS, kVariant3D, &L)) return PBDR_ERR_INVALID_ARG;
+    if (L.total > (size_t)PBDR_STATIC_SCRATCH_BYTES) return PBDR_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return hip_result(e);
+    // nothing of the array needs clearing here: binning's first kernel zeroes the status words and the tile ranges,
+    // and every other part is written by this call before this call reads it
+    const CamDev c = to_dev(cam);
+    e = launch_bin_sort(dev(splats), c, L, (char*)ws, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_result(e);
+    e = launch_composite_fwd(c, L, (char*)ws, bg, image, final_T, last_idx, (hipStream_t)hip_stream);
+    if (e != hipSuccess || !pair_count) return hip_result(e);
+    hipLaunchKernelGGL(k_copy_word, dim3(1), dim3(64), 0, (hipStream_t)hip_stream,
+                       reinterpret_cast<const uint32_t*>((char*)ws + L.off_status) + kStNumDup, pair_count);
+    return hip_result(hipGetLastError());
 }
 
 int pbdr_preprocess_bwd(const pbdr_scene* scene, const pbdr_camera* cam, const pbdr_splats* splats,

@@ -7,6 +7,7 @@ import re
 import pytest
 
 from paper_2512_20017_amd import binding as B
+from paper_2512_20017_amd import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -154,3 +155,21 @@ def test_state_layout_is_table_3():
         assert k == w
         arr = np.asarray(sp[field])
         assert (arr.shape[1] if arr.ndim == 2 else 1) == k, field
+
+
+def test_static_scratch_limits_and_arguments():
+    L = B.lib()
+    cam_ok = B.camera_struct(synth.camera_tiny(64, 64))
+    cam_big = B.camera_struct(synth.camera_tiny(B.PBDR_STATIC_MAX_SIDE + 16, 64))
+    bg = (C.c_float * 3)(0, 0, 0)
+    sp_big = B.CSplats(B.PBDR_STATIC_MAX_POINTS + 1, 16, 16, 16, 16, 16, 16)
+    sp_ok = B.CSplats(8, 16, 16, 16, 16, 16, 16)
+    args = (C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), None, None)
+    assert L.pbdr_render_fwd_static(C.byref(sp_big), C.byref(cam_ok), bg, *args) == B.PBDR_ERR_STATIC_LIMIT
+    assert L.pbdr_render_fwd_static(C.byref(sp_ok), C.byref(cam_big), bg, *args) == B.PBDR_ERR_STATIC_LIMIT
+    assert L.pbdr_render_fwd_static(C.byref(sp_ok), C.byref(cam_ok), bg, C.c_void_p(0), C.c_void_p(16), C.c_void_p(16), None,
+                                    None) == B.PBDR_ERR_INVALID_ARG
+    assert "static scratch" in L.pbdr_status_string(C.c_int(B.PBDR_ERR_STATIC_LIMIT)).decode()
+    # the largest admitted sizes fit the array
+    assert B.pbdr_workspace_bytes(B.PBDR_STATIC_MAX_POINTS, B.PBDR_STATIC_MAX_SIDE, B.PBDR_STATIC_MAX_SIDE,
+                                  B.PBDR_STATIC_MAX_PAIRS) <= B.PBDR_STATIC_SCRATCH_BYTES
