@@ -100,8 +100,10 @@ typedef struct pbdr_splats {
 } pbdr_splats;
 
 /* Gradient w.r.t. the differentiable part of pbdr_splats (what Alg. 1 line 19-20 sends back). Overwritten for every
- * point that binning lists: radius > 0 and a tile rectangle that is not empty, which is every point with radius > 0
- * of a state written by pbdr_preprocess. Entries of other points are left untouched (nothing reads them). */
+ * point that binning lists: radius > 0 and a tile rectangle that meets the rendered image or patch (every point with
+ * radius > 0 of a state written by the matching preprocessing call). Entries of other points are left untouched, and
+ * the second half of pbdr_render_bwd does not read them: such points receive no parameter gradient (zeros with
+ * first_view). pbdr_preprocess_bwd on its own selects by splats->radius > 0 and reads g_splats of all those points. */
 typedef struct pbdr_splat_grads {
     int32_t n;
     float* mean2d;  /* [2][n] */

@@ -435,7 +435,13 @@ static void blend_pixel(double px, double py, const uint32_t* list, uint32_t len
         araw = opacity[g] * gauss;
         alpha = araw < ORC_ALPHA_MAX ? araw : ORC_ALPHA_MAX;
         if (fabs(araw - ORC_ALPHA_MAX) < 1e-5) frag |= ORC_FRAG_ALPHA_MAX;
-        if (fabs(alpha - ORC_ALPHA_MIN) < 2e-7) frag |= ORC_FRAG_ALPHA_MIN;
+        /* the skip decision is within fp32 rounding of flipping. An fp32 evaluation of alpha = o exp(-sigma) carries a
+         * relative error of at most about 1e-6 (logarithm of o, exponential, the final product) + 2.5e-7 x the size of
+         * sigma's three terms (a few roundings of each); the flag is raised within twice that of the threshold */
+        if (fabs(alpha - ORC_ALPHA_MIN) <
+            ORC_ALPHA_MIN * (2e-6 + 5e-7 * (0.5 * (fabs(conic[3 * g]) * dx * dx + fabs(conic[3 * g + 2]) * dy * dy) +
+                                            fabs(conic[3 * g + 1] * dx * dy))))
+            frag |= ORC_FRAG_ALPHA_MIN;
         if (alpha < ORC_ALPHA_MIN) continue;
         Tn = T * (1.0 - alpha);
         if (fabs(Tn - ORC_T_STOP) < 1e-8) frag |= ORC_FRAG_T_STOP;
@@ -851,6 +857,7 @@ void orc_preprocess_grouped(int n, int sh_degree, int group_size, const double* 
 /* Layouts: tan_u[n][3], tan_v[n][3], log_scale2[n][2]; T[n][9] row-major; normal[n][3].    */
 /* ====================================================================================== */
 #define ORC_FRAG_LOWPASS 16
+#define ORC_FRAG_GRAZING 32
 
 typedef struct {
     int visible;
@@ -1006,6 +1013,21 @@ void orc2d_preprocess(int n, int sh_degree, const double* mean, const double* ta
     }
 }
 
+/* How ill-conditioned the ray-disk intersection of pixel position (x, y) is: |h_u| |h_v| / |h_u x h_v| (>= 1). The
+ * cross product p = h_u x h_v cancels when the disk is seen nearly edge-on from this pixel (h_u and h_v nearly
+ * parallel); (u, v) = (p_0, p_1) / p_2 evaluated in fp32 then carries about 2.5e-7 x this number of relative error. */
+static double ray_uv_condition(const double T[9], double x, double y)
+{
+    double hu[3], hv[3], p[3], nu, nv, np_;
+    int k;
+    for (k = 0; k < 3; ++k) { hu[k] = x * T[6 + k] - T[k]; hv[k] = y * T[6 + k] - T[3 + k]; }
+    cross3(hu, hv, p);
+    nu = sqrt(hu[0] * hu[0] + hu[1] * hu[1] + hu[2] * hu[2]);
+    nv = sqrt(hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2]);
+    np_ = sqrt(p[0] * p[0] + p[1] * p[1] + p[2] * p[2]);
+    return np_ > 0.0 ? nu * nv / np_ : 1e300;
+}
+
 /* disk coordinates (u, v) where the ray of pixel position (x, y) meets the surfel's plane; returns 0 if parallel */
 int orc2d_ray_uv(const double T[9], double x, double y, double uv[2])
 {
@@ -1042,6 +1064,17 @@ static void blend_pixel2d(double px, double py, const uint32_t* list, uint32_t l
         alpha = araw < ORC_ALPHA_MAX ? araw : ORC_ALPHA_MAX;
         if (fabs(araw - ORC_ALPHA_MAX) < 1e-5) frag |= ORC_FRAG_ALPHA_MAX;
         if (fabs(alpha - ORC_ALPHA_MIN) < 2e-7) frag |= ORC_FRAG_ALPHA_MIN;
+        /* a disk seen nearly edge-on from this pixel: an fp32 evaluation of (u, v) is off by `rel`, relatively, so G by
+         * the factor exp(+- rel (u^2 + v^2)). If that exceeds 1.25e-4 (the gradient tolerance is 1e-3) and the pair is
+         * blended, or would be with G at the upper end of that range, the pixel's result is not pinned by fp32 */
+        {
+            const double rel = 2.5e-7 * ray_uv_condition(Tm + 9 * g, px, py);
+            if (rel > 1.25e-4) {
+                const double r2 = uv[0] * uv[0] + uv[1] * uv[1];
+                const double Gup = exp(-0.5 * r2 * (1.0 - (rel < 0.5 ? 2.0 * rel : 1.0)));
+                if (opacity[g] * (Gup > G2 ? Gup : G2) >= ORC_ALPHA_MIN) frag |= ORC_FRAG_GRAZING;
+            }
+        }
         if (alpha < ORC_ALPHA_MIN) continue;
         if (fabs(G - G2) < 1e-6) frag |= ORC_FRAG_LOWPASS;
         Tn = Tr * (1.0 - alpha);

@@ -473,8 +473,11 @@ static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, c
         return hip_result(launch_preprocess_bwd_records(dev(scene), c, reinterpret_cast<const uint32_t*>((char*)workspace + L.off_touched),
                                                         reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec), dev(grads),
                                                         grads->first_view != 0, (hipStream_t)hip_stream));
-    return hip_result(launch_preprocess_bwd(dev(scene), c, splats->radius, g2, dev(grads), grads->first_view != 0,
-                                            (hipStream_t)hip_stream));
+    // g_splats holds this call's values for exactly the points binning listed (tile count > 0), so those, not
+    // radius > 0, are the points the second half may read: a whole-image state rendered through a patch, or a
+    // caller-made state with an empty tile rectangle, has radius > 0 points that were never listed
+    return hip_result(launch_preprocess_bwd(dev(scene), c, reinterpret_cast<const int32_t*>((char*)workspace + L.off_touched), g2,
+                                            dev(grads), grads->first_view != 0, (hipStream_t)hip_stream));
 }
 
 int pbdr_render_stats(const pbdr_camera* cam, int32_t n, uint64_t dup_capacity, uint64_t* counters, void* workspace,
@@ -664,7 +667,9 @@ static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* spl
                                                           reinterpret_cast<const uint32_t*>((char*)workspace + L.off_touched),
                                                           reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec), dev(grads),
                                                           grads->first_view != 0, (hipStream_t)hip_stream));
-    return hip_result(launch_preprocess2d_bwd(dev(scene), c, dev(splats), dev(g_splats), dev(grads), grads->first_view != 0,
+    Splats2DDev listed = dev(splats);      // as in the 3D call: the points binning listed are the ones g_splats was written for
+    listed.radius = reinterpret_cast<int32_t*>((char*)workspace + L.off_touched);
+    return hip_result(launch_preprocess2d_bwd(dev(scene), c, listed, dev(g_splats), dev(grads), grads->first_view != 0,
                                               (hipStream_t)hip_stream));
 }
 

@@ -41,3 +41,26 @@ def splat_state(mean2d, conic, opacity, color, radius):
 
 def tiles_xy(width, height):
     return (width + TILE - 1) // TILE, (height + TILE - 1) // TILE
+
+
+GRAD_RTOL = 1e-3      # gradients: 1e-3 relative ...
+GRAD_FLOOR = 1e-5     # ... + 1e-5 of the largest reference magnitude of the attribute
+IMG_ATOL = 1e-4       # image and final_T: absolute
+
+
+def grad_close(name, got, ref, report=True):
+    """Every element: |got - ref| <= 1e-3 |ref| + 1e-5 max|ref| (max over the compared elements of the attribute).
+    No element is exempt here: a caller may leave elements out only on the strength of a flag the oracle raised.
+    Prints the worst error over its tolerance, so that the headroom is on record."""
+    ref = np.asarray(ref, dtype=np.float64); got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    err = np.abs(got - ref)
+    tol = GRAD_RTOL * np.abs(ref) + GRAD_FLOOR * max(float(np.abs(ref).max()), 1e-30)
+    worst = float((err / tol).max())
+    if report:
+        print(f"[parity] {name}: worst |err|/tol = {worst:.3f} over {ref.size} elements (max|ref| = {float(np.abs(ref).max()):.3e})")
+    bad = err > tol
+    assert not bad.any(), (name, int(bad.sum()), ref.size, worst, float(err.max()), float(np.abs(ref).max()))
+    return worst

@@ -5,6 +5,7 @@ import torch
 
 import oracle
 from gpu_pipeline import GpuView
+from helpers import grad_close
 from paper_2512_20017_amd import binding as B
 from paper_2512_20017_amd import synth
 
@@ -162,9 +163,6 @@ def test_caller_supplied_conics_that_are_not_positive_definite():
     g = view.render_bwd(bg, G)
     rg = oracle.render_bwd(st64, ref_l, w, h, bg, G.astype(np.float64))
     for k in ("mean2d", "conic", "opacity", "color"):
-        r_ = np.asarray(rg[k]); d = np.abs(g[k] - r_)
-        floor = 1e-5 * max(np.abs(r_).max(), 1e-30)
-        bad = d > 1e-3 * np.abs(r_) + floor
         # a pixel that sits within rounding of sigma = 0 of an indefinite splat is flagged fragile and carries no loss;
         # what is left must agree
-        assert bad.mean() < 2e-3, (k, int(bad.sum()), float(d.max()))
+        grad_close("indefinite conics " + k, g[k], rg[k])

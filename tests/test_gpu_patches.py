@@ -13,6 +13,7 @@ import torch
 
 import oracle
 from gpu_pipeline import to_chw_dev, to_hwc
+from helpers import IMG_ATOL, grad_close
 from paper_2512_20017_amd import binding as B
 from paper_2512_20017_amd import synth
 
@@ -78,13 +79,6 @@ def _render_patch(scene, full, patch, ws):
     return splats, sp, final_T, last_idx, want
 
 
-def _close(name, got, ref, rtol=1e-3, floor=1e-5):
-    ref = np.asarray(ref, dtype=np.float64); got = np.asarray(got, dtype=np.float64)
-    tol = rtol * np.abs(ref) + floor * max(np.abs(ref).max(), 1e-30)
-    bad = np.abs(got - ref) > tol
-    assert bad.mean() < 1e-5, (name, int(bad.sum()), float(np.abs(got - ref).max()), float(np.abs(ref).max()))
-
-
 @pytest.mark.parametrize("seed,W,H,deg", [(0, 200, 120, 1), (1, 97, 83, 0), (2, 160, 160, 3)])
 def test_patches_small(seed, W, H, deg):
     sc = synth.random_small_scene(seed, 300, deg)
@@ -99,6 +93,11 @@ def test_patches_small(seed, W, H, deg):
     lists = oracle.bin_sort(st["mean2d"], st["radius"], full.sp["depth"], W, H)
     ref_f = oracle.render_fwd(st, lists, W, H, BG)
     ok = ref_f["fragile"] == 0
+    # the whole-image render the patches are cropped from, against the oracle (the crops themselves are bit-exact)
+    whole_img = full.image.permute(1, 2, 0).cpu().numpy()
+    assert np.abs(whole_img - ref_f["image"])[ok].max() <= IMG_ATOL
+    assert np.abs(full.final_T.cpu().numpy() - ref_f["final_T"])[ok].max() <= IMG_ATOL
+    assert np.array_equal(full.last_idx.cpu().numpy().astype(np.uint32)[ok], ref_f["last_idx"][ok])
     rng = np.random.default_rng(seed)
     G = rng.normal(size=(H, W, 3)).astype(np.float32)
     G[~ok] = 0.0
@@ -119,7 +118,7 @@ def test_patches_small(seed, W, H, deg):
         torch.cuda.synchronize()
         got = g_sp.to_numpy()
         for k in ("mean2d", "conic", "opacity", "color"):
-            _close(k, got[k][vis], ref_b[k][vis])
+            grad_close(f"patch {pi} composite bwd {k}", got[k][vis], ref_b[k][vis], report=(pi == 0))
             hidden = (full.sp["radius"] > 0) & ~vis          # visible in the image, not in the patch: no gradient
             assert not np.abs(ref_b[k][hidden]).any()
     # Alg. 1 lines 22-24 over the patches of a partition = the whole image
@@ -131,7 +130,7 @@ def test_patches_small(seed, W, H, deg):
     for p in acc:
         got = acc[p].to_numpy()
         for k in ("mean", "log_scale", "quat", "logit", "sh"):
-            _close(k, got[k], ref[k], rtol=1e-3, floor=2e-5)
+            grad_close(f"patches summed {k}", got[k], ref[k])
 
 
 def test_invalid_patches():
@@ -181,6 +180,8 @@ def test_surfel_patches(seed, W, H, deg):
     lists = oracle.bin_sort(st["mean2d"], st["radius"], fsp["depth"], W, H)
     ref_f = oracle.render_fwd2d(st, lists, W, H, BG)
     ok = ref_f["fragile"] == 0
+    assert np.abs(to_hwc(image) - ref_f["image"])[ok].max() <= IMG_ATOL      # what the patches are crops of
+    assert np.array_equal(last_idx.cpu().numpy().astype(np.uint32)[ok], ref_f["last_idx"][ok])
     G = np.random.default_rng(seed).normal(size=(H, W, 3)).astype(np.float32)
     G[~ok] = 0.0
     ws = B.alloc_workspace2d(n, W, H, cap)
@@ -210,13 +211,66 @@ def test_surfel_patches(seed, W, H, deg):
         torch.cuda.synchronize()
         got = g_sp.to_numpy()
         for k in ("mean2d", "opacity", "color"):
-            _close(k, got[k][vis], ref_b[k][vis])
+            grad_close(f"surfel patch {patch} composite bwd {k}", got[k][vis], ref_b[k][vis], report=False)
         for row in range(3):      # the rows of T differ by the focal length in magnitude
-            _close("T%d" % row, got["T"][vis][:, 3 * row:3 * row + 3], ref_b["T"][vis][:, 3 * row:3 * row + 3])
+            grad_close(f"surfel patch {patch} T{row}", got["T"][vis][:, 3 * row:3 * row + 3], ref_b["T"][vis][:, 3 * row:3 * row + 3],
+                       report=False)
     whole = scene.zeros_like()
     g_sp = B.SplatGrads2D.empty(n)
     B.pbdr2d_render_bwd(scene, full_sp, cam, BG, cap, final_T, last_idx, to_chw_dev(G), g_sp, whole, full_ws)
     torch.cuda.synchronize()
     ref, got = whole.to_numpy(), acc.to_numpy()
     for k in ("mean", "tan_u", "tan_v", "log_scale", "logit", "sh"):
-        _close(k, got[k], ref[k], rtol=1e-3, floor=2e-5)
+        grad_close(f"patches summed {k}", got[k], ref[k])
+
+
+@pytest.mark.parametrize("surfels", [False, True])
+def test_whole_image_state_through_a_patch_ignores_unlisted_splat_gradients(surfels):
+    """A state written by the whole-image preprocessing call has radius > 0 for points whose tiles miss the patch.
+    Binning for the patch never lists them, so their g_splats entries are not written by the backward; the parameter
+    gradient must not depend on what those entries held (here: NaN), and must equal the one from the patch's own state."""
+    W, H, n, cap = 240, 180, 600, 1 << 18
+    patch = (100, 70, 130, 90)
+    x0, y0, x1, y1 = patch
+    cam = synth.pinhole(W, H, 55.0, np.eye(3), [0.03, -0.02, 2.4])
+    if surfels:
+        sc = synth.random_small_surfels(7, n, 2, spread=1.0, ls_mu=-3.2); scene = B.Scene2D.from_numpy(sc)
+        mk_sp, mk_g, alloc = B.Splats2D.empty, B.SplatGrads2D.empty, B.alloc_workspace2d
+        pre, pre_p, fwd_p, bwd_p = B.pbdr2d_preprocess, B.pbdr2d_preprocess_patch, B.pbdr2d_render_fwd_patch, B.pbdr2d_render_bwd_patch
+        keys, state_keys = ("mean", "tan_u", "tan_v", "log_scale", "logit", "sh"), ("mean2d", "T", "opacity", "color")
+    else:
+        sc = synth.random_small_scene(7, n, 2, spread=1.0, ls_mu=-3.4); scene = B.Scene.from_numpy(sc)
+        mk_sp, mk_g, alloc = B.Splats.empty, B.SplatGrads.empty, B.alloc_workspace
+        pre, pre_p, fwd_p, bwd_p = B.pbdr_preprocess, B.pbdr_preprocess_patch, B.pbdr_render_fwd_patch, B.pbdr_render_bwd_patch
+        keys, state_keys = ("mean", "log_scale", "quat", "logit", "sh"), ("mean2d", "conic", "opacity", "color")
+    G = to_chw_dev(np.random.default_rng(1).normal(size=(y1 - y0, x1 - x0, 3)).astype(np.float32))
+    results = []
+    for whole_state in (False, True):
+        sp = mk_sp(n)
+        if whole_state:
+            pre(scene, cam, sp)
+        else:
+            pre_p(scene, cam, patch, sp)
+        ws = alloc(n, W, H, cap)
+        image = torch.empty((3, y1 - y0, x1 - x0), device="cuda"); fT = torch.empty((y1 - y0, x1 - x0), device="cuda")
+        li = torch.empty((y1 - y0, x1 - x0), dtype=torch.int32, device="cuda")
+        fwd_p(sp, cam, patch, BG, cap, image, fT, li, ws)
+        g_sp = mk_g(n)
+        for k in state_keys:
+            getattr(g_sp, "T" if k == "T" else k).fill_(float("nan"))
+        grads = scene.zeros_like()
+        for k in keys:
+            getattr(grads, k).fill_(float("nan"))          # first_view: every entry is written
+        bwd_p(scene, sp, cam, patch, BG, cap, fT, li, G, g_sp, grads, ws, first_view=True)
+        torch.cuda.synchronize()
+        results.append((sp.to_numpy()["radius"] > 0, image.clone(), grads.to_numpy(), g_sp.to_numpy()))
+    (vis_p, img_p, g_p, _), (vis_w, img_w, g_w, gsp_w) = results
+    assert (vis_w & ~vis_p).sum() > 10                      # points the patch does not list although radius > 0
+    assert torch.equal(img_p, img_w)
+    for k in keys:
+        assert np.isfinite(g_w[k]).all(), k
+        # (not bit for bit: the order of a tile's four wavefronts' adds into the shared accumulators is not fixed)
+        np.testing.assert_allclose(g_w[k], g_p[k], rtol=1e-5, atol=1e-6 * np.abs(g_p[k]).max(), err_msg=k)
+        assert not g_w[k][~vis_p].any(), k                  # no gradient for points the patch does not use
+    for k in state_keys:                                    # unlisted points: left untouched, as the header says
+        assert np.isnan(gsp_w[k][vis_w & ~vis_p]).all() and np.isfinite(gsp_w[k][vis_p]).all(), k

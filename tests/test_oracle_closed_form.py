@@ -163,3 +163,54 @@ def test_near_far_and_radius_clip_cull():
     # a splat wholly off-screen is culled
     off, _ = _single(mean=(40.0, 0, 0))
     assert oracle.preprocess(off, cam)["radius"][0] == 0
+
+
+def test_skip_flag_covers_float32_evaluations_of_alpha():
+    """The width of the 'within rounding of the 1/255 threshold' flag is derived from fp32 arithmetic (about 1e-6 of
+    relative error from log / exp / product, 2.5e-7 per unit of sigma's terms, doubled). Here: one splat per tile, its
+    opacity chosen so that one pixel of the tile lands within a few 1e-6 (relative) of the threshold; alpha of that
+    pixel is then evaluated in float32 in two ways (o exp(-sigma), and 2^(log2 o - sigma log2 e) with pre-scaled conic).
+    Wherever either float32 decision differs from the oracle's, the oracle must have flagged the pixel; and the flag
+    must not be so wide that it swallows samples 1e-4 away."""
+    rng = np.random.default_rng(5)
+    tx = ty = 64
+    w, h = 16 * tx, 16 * ty
+    n = tx * ty
+    cx = (np.arange(n) % tx) * 16 + rng.uniform(2, 14, n)
+    cy = (np.arange(n) // tx) * 16 + rng.uniform(2, 14, n)
+    a = rng.uniform(0.02, 0.6, n); c = rng.uniform(0.02, 0.6, n); b = rng.uniform(-0.9, 0.9, n) * np.sqrt(a * c)
+    px = (np.arange(n) % tx) * 16 + rng.integers(0, 16, n) + 0.5
+    py = (np.arange(n) // tx) * 16 + rng.integers(0, 16, n) + 0.5
+    mean2d = np.stack([cx, cy], 1).astype(np.float32).astype(np.float64)
+    conic = np.stack([a, b, c], 1).astype(np.float32).astype(np.float64)
+    dx, dy = px - mean2d[:, 0], py - mean2d[:, 1]
+    sigma = 0.5 * (conic[:, 0] * dx * dx + conic[:, 2] * dy * dy) + conic[:, 1] * dx * dy
+    keep = sigma < 5.0                                     # so that the opacity below stays under 1
+    delta = rng.uniform(-4e-6, 4e-6, n)
+    delta[::7] = rng.choice([-1e-4, 1e-4], len(delta[::7]))   # some samples clearly off the threshold
+    o = np.where(keep, np.exp(sigma) / 255.0 * (1.0 + delta), 0.5).astype(np.float32).astype(np.float64)
+    st = splat_state(mean2d, conic, o, np.ones((n, 3)), np.full(n, 7))
+    # the radius keeps every splat inside its own tile's 3 x 3 neighbourhood; only the designated pixel is looked at
+    lists = oracle.bin_sort(st["mean2d"], st["radius"], np.ones(n, dtype=np.float32), w, h)
+    out = oracle.render_fwd(st, lists, w, h, (0, 0, 0))
+    iy, ix = (py - 0.5).astype(int), (px - 0.5).astype(int)
+    # float32 evaluations (this test's own restatement of the blend rule of Sec. 2.1 in single precision)
+    f = np.float32
+    m32, q32, o32 = mean2d.astype(f), conic.astype(f), o.astype(f)
+    dx32, dy32 = px.astype(f) - m32[:, 0], py.astype(f) - m32[:, 1]
+    s32 = f(0.5) * (q32[:, 0] * dx32 * dx32 + q32[:, 2] * dy32 * dy32) + q32[:, 1] * dx32 * dy32
+    alpha_a = np.minimum(f(0.99), o32 * np.exp(-s32))
+    l2e = f(1.4426950408889634)
+    A, Bq, Cq = f(0.5) * l2e * q32[:, 0], l2e * q32[:, 1], f(0.5) * l2e * q32[:, 2]
+    alpha_b = np.minimum(f(0.99), np.exp2(np.log2(o32) - ((A * dx32 + Bq * dy32) * dx32 + Cq * dy32 * dy32)))
+    thr = f(1.0 / 255.0)
+    # the designated pixel sees only its own tile's splats; its own is the one whose index is the tile's
+    alpha64 = np.minimum(0.99, o * np.exp(-sigma))
+    dec64 = alpha64 >= 1.0 / 255.0
+    flagged = (out["fragile"][iy, ix] & 1) != 0
+    differs = keep & (((alpha_a >= thr) != dec64) | ((alpha_b >= thr) != dec64))
+    assert differs.sum() > 20                               # the sample does reach the knife edge
+    assert flagged[differs].all()
+    far = keep & (np.abs(delta) > 5e-5)
+    alone = np.array([(lists["ranges"][t, 1] - lists["ranges"][t, 0]) == 1 for t in range(n)])
+    assert far.sum() > 100 and not flagged[far & alone].any()

@@ -169,3 +169,51 @@ def test_finite_differences_low_pass_branch():
     cam = synth.pinhole(32, 32, 50.0, np.eye(3), [0.0, 0.0, 2.0])
     g, f = _fd(sc, cam, 7, min_checked=0.5)
     assert np.abs(g["d_splats"]["mean2d"]).max() > 0 and f["n_blend"] > 20
+
+
+def test_grazing_flag_marks_pixels_whose_ray_disk_intersection_is_ill_conditioned():
+    """A disk seen nearly edge-on from a pixel makes h_u and h_v nearly parallel; (u, v) in single precision then loses
+    as many digits as |h_u||h_v| / |h_u x h_v| has. The oracle flags such pixels (flag 32) when the pair can blend, and
+    only those: a float32 evaluation of (u, v) agrees with the oracle's to 1e-3 wherever the flag is not set."""
+    cam = simple_camera(64, 64, 60.0, 3.0)
+    n = 2
+    # first disk faces the camera. The second one's plane nearly contains the camera centre C = (0, 0, -3): it is spanned
+    # by an oblique in-image direction and a direction 2e-4 rad off the line from C to the disk centre, which projects
+    # onto pixel centre (36.5, 32.5); the line of slope 2/3 through it passes through a pixel centre every 3 columns
+    C3 = np.array([0.0, 0.0, -3.0])
+    M = np.array([(36.5 - 32.0) / 60.0 * 3.0, (32.5 - 32.0) / 60.0 * 3.0, 0.0])
+    tu = np.array([12.0, 8.0, 0.0]) / math.hypot(12.0, 8.0)
+    view = (M - C3) / np.linalg.norm(M - C3)
+    off = np.cross(tu, view); off /= np.linalg.norm(off)
+    sc = dict(mean=np.array([[0.0, 0.0, 0.0], M]), tan_u=np.array([[1.0, 0.0, 0.0], tu]),
+              tan_v=np.array([[0.0, 1.0, 0.0], view + 2e-4 * off]),
+              log_scale=np.log(np.array([[0.2, 0.2], [0.3, 0.3]])), logit=np.array([2.0, 2.0]),
+              sh=np.zeros((n, 1, 3)), sh_degree=0)
+    sp = oracle.preprocess2d(sc, cam)
+    assert (sp["radius"] > 0).all()
+    st = {k: sp[k] for k in ("mean2d", "T", "opacity", "color")} | {"radius": sp["radius"]}
+    lists = oracle.bin_sort(st["mean2d"], st["radius"], sp["depth"].astype(np.float32), 64, 64)
+    out = oracle.render_fwd2d(st, lists, 64, 64, BG)
+    graz = (out["fragile"] & 32) != 0
+    assert graz[32, 36] and graz[30, 33] and graz[34, 39] and 5 <= graz.sum() <= 20      # pixels the sliver passes through
+    # float32 re-evaluation of the intersection for every pixel and both disks (this test's own statement of it)
+    f = np.float32
+    ys, xs = np.mgrid[0:64, 0:64]
+    worst_unflagged = 0.0
+    for i in range(n):
+        T64 = sp["T"][i]; T32 = T64.astype(f)
+        for (yy, xx) in zip(ys.ravel(), xs.ravel()):
+            x, y = xx + 0.5, yy + 0.5
+            uv = oracle.ray_uv(T64, x, y)
+            hu = (f(x) * T32[6:9] - T32[0:3]).astype(f); hv = (f(y) * T32[6:9] - T32[3:6]).astype(f)
+            p = np.cross(hu, hv).astype(f)
+            if uv is None or p[2] == 0 or (uv[0] ** 2 + uv[1] ** 2) > 11.0:
+                continue
+            err = max(abs(float(p[0] / p[2]) - uv[0]), abs(float(p[1] / p[2]) - uv[1])) / max(1.0, math.hypot(*uv))
+            if not graz[yy, xx]:
+                worst_unflagged = max(worst_unflagged, err)
+    assert worst_unflagged < 1e-3
+    # the facing disk alone raises nothing
+    one = {k: v[:1] for k, v in st.items()}
+    l1 = oracle.bin_sort(one["mean2d"], one["radius"], sp["depth"][:1].astype(np.float32), 64, 64)
+    assert not (oracle.render_fwd2d(one, l1, 64, 64, BG)["fragile"] & 32).any()
