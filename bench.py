@@ -409,11 +409,12 @@ def main():
     tile_passes = max(1, (max(1, (((W + 15) // 16) * ((H + 15) // 16) - 1).bit_length()) + 7) // 8)
     hbm_bytes = {   # algorithmic bytes per step
         "k_preprocess": 16.0 * n + (32.0 + 12.0 * K + 40.0) * n_vis,
-        "k_count_pack": 20.0 * n + (36.0 + 48.0) * n_vis,
-        "k_duplicate": 12.0 * n + 12.0 * n_vis + 8.0 * P,
-        "k_radix_hist": 4.0 * n + 4.0 * P,
-        "k_radix_scatter": 4 * 16.0 * n + tile_passes * 16.0 * P,
+        "k_count_visible": 8.0 * n + 8.0 * n_vis,
+        "k_pack_dup": 4.0 * n + (44.0 + 64.0) * n_vis + 8.0 * P,
+        "k_radix_hist": tile_passes * 4.0 * P,
+        "k_radix_scatter": tile_passes * 16.0 * P,
         "k_tile_ranges": 4.0 * P,
+        "k_tile_depth_sort": 12.0 * P,
         "k_gather_splat_grads": 8.0 * n + 48.0 * P + 36.0 * n,
         # accumulate: read + write of the visible points' gradient entries; first view: one write of every point's
         "k_preprocess_bwd": 4.0 * n + (36.0 + 32.0 + 12.0 * K) * n_vis

@@ -57,30 +57,24 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->tile_bits = 0;
     while ((1 << L->tile_bits) < L->tiles) ++L->tile_bits;
     L->tile_passes = radix_pass_count(L->tile_bits);
-    const size_t nblk_d = ((size_t)n + kSortItems - 1) / kSortItems, nblk_t = ((size_t)cap + kSortItems - 1) / kSortItems;
+    const size_t nblk_t = ((size_t)cap + kSortItems - 1) / kSortItems;
     size_t off = 0;
     const auto take = [&](size_t bytes) { const size_t at = off; off = align256(off + bytes); return at; };
     L->off_status = take(kStWords * sizeof(uint32_t));
     L->off_packed = take((size_t)n * L->record_bytes);
     L->off_depth_bits = take((size_t)n * sizeof(uint32_t));
-    L->off_vis_block = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
+    L->off_blk_vis = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
+    L->off_blk_pairs = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
     L->off_touched = take((size_t)n * sizeof(uint32_t));
     L->off_offsets = take(((size_t)n + 1) * sizeof(uint32_t));
     L->off_slot_base = take((size_t)n * sizeof(uint32_t));
-    L->off_scan_part = take(((size_t)n / kScanItems + 8) * sizeof(uint32_t));
-    L->off_dkey0 = take((size_t)n * sizeof(uint32_t));
-    L->off_dkey1 = take((size_t)n * sizeof(uint32_t));
-    L->off_dval0 = take((size_t)n * sizeof(uint32_t));
-    L->off_dval1 = take((size_t)n * sizeof(uint32_t));
+    L->off_order = take((size_t)n * sizeof(uint32_t));       // listed points in index order ("rank" -> point)
     L->off_tkey0 = take((size_t)cap * sizeof(uint32_t));
     L->off_tval0 = take((size_t)cap * sizeof(uint32_t));
     L->off_tkey1 = take((size_t)cap * sizeof(uint32_t));
     L->off_tval1 = take((size_t)cap * sizeof(uint32_t));
-    L->off_totals = take((size_t)2 * kRadixMaxBins * sizeof(uint32_t));   // digit totals of the depth sort, then of the tile sort
-    {
-        const size_t hd = nblk_d * kRadixMaxBins, ht = nblk_t * kRadixMaxBins;
-        L->off_tile_hist = take((hd > ht ? hd : ht) * sizeof(uint32_t));
-    }
+    L->off_totals = take((size_t)kRadixMaxBins * sizeof(uint32_t));      // digit totals of a pass of the tile sort
+    L->off_tile_hist = take(nblk_t * kRadixMaxBins * sizeof(uint32_t));
     L->off_ranges = take((size_t)L->tiles * 2 * sizeof(uint32_t));
     L->off_partial = take((size_t)cap * L->partial_vec4 * 4 * sizeof(float));
     L->off_keys64 = take((size_t)cap * sizeof(uint64_t));

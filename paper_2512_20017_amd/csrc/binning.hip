@@ -1,26 +1,30 @@
-// Tile binning: per-splat tile count + raster record, depth order of the splats, device prefix sum, key/value
-// duplication in depth order, stable sort by tile, tile ranges. These are the steps between pts_splatting and the
+// Tile binning: per-splat tile count + raster record, device prefix sums, key/value duplication in index order, stable
+// sort by tile, tile ranges, depth order inside each tile's list. These are the steps between pts_splatting and the
 // per-pixel blend that realise "sorts these view-dependent splats by their distance to the camera plane" (paper
-// Sec. 2.1) per 16x16 tile.  All HBM-bound, integer work.
+// Sec. 2.1) per 16x16 tile.  All HBM- or latency-bound integer work.
 //
-// The tile lists are ordered by the 64-bit key (tile << 32 | depth bits), ties by splat index. The sort is a
-// least-significant-digit radix sort of that key whose four depth digits are sorted on the n splats, before
-// duplication (every duplicate of a splat carries the same depth bits), and whose tile digits are sorted on the P
-// pairs afterwards: the same permutation for a fraction of the traffic.
+// The tile lists are ordered by the 64-bit key (tile << 32 | depth bits), ties by splat index. That order is made in
+// two halves: the (tile, point) pairs are emitted in point-index order and sorted stably by tile id (two radix passes
+// over the P pairs), which leaves every tile's list in index order; one workgroup per tile then sorts its list stably
+// by the 32 depth bits (k_tile_depth_sort, radix_sort.hip: in LDS for lists up to 2048 entries). The same permutation
+// as a six-pass radix sort of P 64-bit keys, in a third of the launches of the earlier scheme (depth digits sorted on
+// the points before duplication: twelve launches for 0.5 M keys, every one of them at the latency floor).
 #include "pbdr_internal.h"
-#include "pair_reduce.h"
+#include "binning_common.h"
 
 namespace pbdr {
 
 // Tiles touched by every point (0 for culled points) and, per block of 256 consecutive points, the number of points
-// that touch at least one tile: those are the points binning lists ("visible" below). A state made by the
-// preprocessing calls has radius == 0 for every point without a tile; a caller-made state with radius > 0 and an
-// empty tile rectangle is treated as culled here, so every listed point owns at least one pair.
+// that touch at least one tile - those are the points binning lists ("visible" below) - and the number of their pairs.
+// A state made by the preprocessing calls has radius == 0 for every point without a tile; a caller-made state with
+// radius > 0 and an empty tile rectangle is treated as culled here, so every listed point owns at least one pair.
 __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, uint32_t* __restrict__ tiles_touched,
-                                                       uint32_t* __restrict__ vis_block, uint32_t* __restrict__ status,
-                                                       uint32_t* __restrict__ ranges, uint32_t nranges)
+                                                       uint32_t* __restrict__ blk_vis, uint32_t* __restrict__ blk_pairs,
+                                                       uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, uint32_t nranges)
 {
+    __shared__ uint32_t sPairs[4];
     const int i = blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // first launch of a binning call: the status words and the tile ranges start at zero (every later kernel of the call
     // comes after this one on the stream)
     if (i < kStCleared) status[i] = 0u;
@@ -31,255 +35,74 @@ __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, 
         if (r > 0) {
             int x0, y0, x1, y1;
             tile_rect(cam, in.mean2d[i], in.mean2d[(size_t)in.n + i], r, x0, y0, x1, y1);
-            t = (uint32_t)(max(x1 - x0, 0) * max(y1 - y0, 0));
+            t = (uint32_t)(max(x1 - x0, 0) * max(y1 - y0, 0));       // <= 2^24: the grid has at most 4096 x 4096 tiles
         }
         tiles_touched[i] = t;
     }
+    const uint32_t inc = wave_inclusive_scan_sat(t);
+    if (lane == 63) sPairs[wave] = inc;
     const int c = __syncthreads_count(t > 0);
-    if (threadIdx.x == 0) vis_block[blockIdx.x] = (uint32_t)c;
+    if (threadIdx.x == 0) {
+        blk_vis[blockIdx.x] = (uint32_t)c;
+        blk_pairs[blockIdx.x] = sat_add(sat_add(sPairs[0], sPairs[1]), sat_add(sPairs[2], sPairs[3]));
+    }
 }
 
-// One thread per point. A visible point gets: the number of tiles its square touches, the 48-byte raster record,
-// and a slot in the compact list of visible points, kept in ascending point order (the block's first slot comes from
-// the scanned block counts, the slot within the block from ballots), where its (depth bits, index) pair for the depth
-// sort goes. Culled points cost one 4-byte read and nothing downstream.
-__global__ __launch_bounds__(256) void k_count_pack(SplatsDev sp, CamDev cam, const uint32_t* __restrict__ vis_block,
-                                                    const uint32_t* __restrict__ tiles_touched, Packed* __restrict__ packed,
-                                                    uint32_t* __restrict__ dkey, uint32_t* __restrict__ dval,
-                                                    uint32_t* __restrict__ depth_bits)
+// One workgroup: exclusive prefix sums, in place, of the per-block counts of listed points and of pairs (the latter
+// saturating). Leaves the totals in the status words and the pair total behind the last rank's offset.
+__global__ __launch_bounds__(1024) void k_scan_blocks(uint32_t* __restrict__ blk_vis, uint32_t* __restrict__ blk_pairs, uint32_t nb,
+                                                      uint32_t* __restrict__ status, uint32_t* __restrict__ offsets, uint32_t n)
 {
-    __shared__ uint32_t sWave[4];
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    __shared__ uint32_t sV[16], sP[16];
+    __shared__ uint32_t carry_v, carry_p;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const size_t N = (size_t)sp.n;
-    const bool vis = (i < sp.n) && tiles_touched[i] > 0;
-    const unsigned long long m = __ballot(vis);
-    if (lane == 0) sWave[wave] = (uint32_t)__popcll(m);
-    __syncthreads();
-    if (!vis) return;
-    uint32_t slot = vis_block[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-#pragma unroll
-    for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
-    const int r = sp.radius[i];
-    const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-    float4* dst = reinterpret_cast<float4*>(packed + i);
-    dst[0] = make_float4(mx, my, sp.conic[i], sp.conic[N + i]);
-    dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
-    const float depth = sp.depth[i];
-    const uint32_t key = __float_as_uint(depth);
-    dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(r), depth, 0.f);
-    dkey[slot] = key;
-    dval[slot] = (uint32_t)i;
-    depth_bits[i] = key;
-}
-
-// tile counts in depth order (rank r < m holds the visible point order[r]); ranks m..n get 0, and slot n is the
-// sentinel that makes the scan leave the pair total at offsets[n]
-__global__ __launch_bounds__(256) void k_rank_counts(int n, const uint32_t* __restrict__ status, const uint32_t* __restrict__ order,
-                                                     const uint32_t* __restrict__ tiles_touched, uint32_t* __restrict__ counts)
-{
-    // four consecutive ranks per thread (offsets, counts and order start on 16-byte boundaries)
-    const uint32_t r0 = (blockIdx.x * 256u + threadIdx.x) * 4u;
-    if (r0 > (uint32_t)n) return;
-    const uint32_t m = min(status[kStNumVis], (uint32_t)n);
-    uint32_t c[4] = {0u, 0u, 0u, 0u};
-    if (r0 + 4u <= m) {
-        const uint4 o = *reinterpret_cast<const uint4*>(order + r0);
-        c[0] = tiles_touched[o.x]; c[1] = tiles_touched[o.y]; c[2] = tiles_touched[o.z]; c[3] = tiles_touched[o.w];
-    } else {
-#pragma unroll
-        for (uint32_t k = 0; k < 4u; ++k) if (r0 + k < m) c[k] = tiles_touched[order[r0 + k]];
-    }
-    if (r0 + 4u <= (uint32_t)n + 1u) {
-        *reinterpret_cast<uint4*>(counts + r0) = make_uint4(c[0], c[1], c[2], c[3]);
-    } else {
-#pragma unroll
-        for (uint32_t k = 0; k < 4u; ++k) if (r0 + k <= (uint32_t)n) counts[r0 + k] = c[k];
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Exclusive prefix sum over uint32: reduce per 4096-element block, scan the block sums in one
-// workgroup, rescan each block with its offset. No inter-workgroup waiting.
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
-{
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t t = __shfl_up(v, d, 64);
-        if (lane >= d) v += t;
-    }
-    return v;
-}
-
-// exclusive scan of one value per thread across a 256-thread block; returns the block total through `total`
-__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* lds_wave /*[4]*/, uint32_t& total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t inc = wave_inclusive_scan(v);
-    if (lane == 63) lds_wave[wave] = inc;
-    __syncthreads();
-    uint32_t base = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        const uint32_t t = lds_wave[w];
-        if (w < wave) base += t;
-    }
-    total = lds_wave[0] + lds_wave[1] + lds_wave[2] + lds_wave[3];
-    __syncthreads();
-    return base + inc - v;
-}
-
-constexpr int kScanPerThread = kScanItems / 256;  // 16
-
-__global__ __launch_bounds__(256) void k_scan_reduce(const uint32_t* __restrict__ in, uint32_t n, uint32_t* __restrict__ partials)
-{
-    __shared__ uint32_t lds[4];
-    const uint32_t base = blockIdx.x * (uint32_t)kScanItems + threadIdx.x * kScanPerThread;
-    uint32_t s = 0;
-    if (base + kScanPerThread <= n) {
-        const uint4* p = reinterpret_cast<const uint4*>(in + base);
-#pragma unroll
-        for (int k = 0; k < kScanPerThread / 4; ++k) { const uint4 v = p[k]; s += v.x + v.y + v.z + v.w; }
-    } else {
-        for (int k = 0; k < kScanPerThread; ++k) if (base + k < n) s += in[base + k];
-    }
-    uint32_t total;
-    (void)block_exclusive_scan_256(s, lds, total);
-    if (threadIdx.x == 0) partials[blockIdx.x] = total;
-}
-
-// one workgroup of 1024 threads scans the `nb` block sums in place (exclusive); writes the grand total
-__global__ __launch_bounds__(1024) void k_scan_partials(uint32_t* __restrict__ partials, uint32_t nb, uint32_t* __restrict__ total_out)
-{
-    __shared__ uint32_t lds[16];
-    __shared__ uint32_t carry_s;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) carry_s = 0;
+    if (threadIdx.x == 0) { carry_v = 0; carry_p = 0; }
     __syncthreads();
     for (uint32_t start = 0; start < nb; start += 1024) {
         const uint32_t idx = start + threadIdx.x;
-        const uint32_t v = idx < nb ? partials[idx] : 0u;
-        const uint32_t inc = wave_inclusive_scan(v);
-        if (lane == 63) lds[wave] = inc;
-        __syncthreads();
-        uint32_t base = carry_s, chunk = 0;
+        const uint32_t v = idx < nb ? blk_vis[idx] : 0u, p = idx < nb ? blk_pairs[idx] : 0u;
+        uint32_t iv = v, ip = p;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) { const uint32_t t = lds[w]; if (w < wave) base += t; chunk += t; }
-        if (idx < nb) partials[idx] = base + inc - v;
-        __syncthreads();
-        if (threadIdx.x == 0) carry_s += chunk;
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) { partials[nb] = carry_s; if (total_out) *total_out = carry_s; }
-}
-
-// `in` and `out` may be the same array: every thread reads its 16 elements before it writes them
-__global__ __launch_bounds__(256) void k_scan_apply(const uint32_t* in, uint32_t* out, uint32_t n,
-                                                    const uint32_t* __restrict__ partials)
-{
-    __shared__ uint32_t lds[4];
-    const uint32_t base = blockIdx.x * (uint32_t)kScanItems + threadIdx.x * kScanPerThread;
-    uint32_t v[kScanPerThread];
-    const bool full = base + kScanPerThread <= n;
-    if (full) {
-        const uint4* p = reinterpret_cast<const uint4*>(in + base);
-#pragma unroll
-        for (int k = 0; k < kScanPerThread / 4; ++k) { const uint4 t = p[k]; v[4 * k] = t.x; v[4 * k + 1] = t.y; v[4 * k + 2] = t.z; v[4 * k + 3] = t.w; }
-    } else {
-#pragma unroll
-        for (int k = 0; k < kScanPerThread; ++k) v[k] = (base + k < n) ? in[base + k] : 0u;
-    }
-    uint32_t s = 0;
-#pragma unroll
-    for (int k = 0; k < kScanPerThread; ++k) s += v[k];
-    uint32_t total;
-    uint32_t run = block_exclusive_scan_256(s, lds, total) + partials[blockIdx.x];
-#pragma unroll
-    for (int k = 0; k < kScanPerThread; ++k) { const uint32_t t = v[k]; v[k] = run; run += t; }
-    if (full) {
-        uint4* q = reinterpret_cast<uint4*>(out + base);
-#pragma unroll
-        for (int k = 0; k < kScanPerThread / 4; ++k) q[k] = make_uint4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
-    } else {
-#pragma unroll
-        for (int k = 0; k < kScanPerThread; ++k) if (base + k < n) out[base + k] = v[k];
-    }
-}
-
-hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* partials, uint32_t* total_out,
-                                 hipStream_t s)
-{
-    const uint32_t nb = (n + kScanItems - 1) / kScanItems;
-    ProfScope prof(kKScan, s);
-    if (nb > 0) hipLaunchKernelGGL(k_scan_reduce, dim3(nb), dim3(256), 0, s, in, n, partials);
-    hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, partials, nb, total_out);
-    if (nb > 0) hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(256), 0, s, in, out, n, partials);
-    return hipGetLastError();
-}
-
-// Duplication, in depth order: rank r handles point order[r]. Every (tile, splat) pair of a wavefront's 64
-// consecutive ranks is written by whichever lane comes next, so the work is balanced whatever the mix of small and
-// large splats. The pairs of those 64 ranks occupy one contiguous range of the output (offsets are a prefix sum);
-// lane l writes slots B + l, B + l + 64, ... and finds the owning rank of a slot by binary search over the 64 range
-// ends kept in LDS. Pair order within a point: row-major over its tile rectangle. Also records, per point, where
-// its pairs start (slot_base), which the backward pass uses to address its per-pair sums.
-__global__ __launch_bounds__(256) void k_duplicate(BinInput sp, CamDev cam, const uint32_t* __restrict__ order,
-                                                   const uint32_t* __restrict__ offsets, uint32_t* __restrict__ tkeys,
-                                                   uint32_t* __restrict__ tvals, uint32_t* __restrict__ slot_base,
-                                                   uint32_t* __restrict__ chunk_rank, uint32_t cap, uint32_t* __restrict__ status)
-{
-    __shared__ uint32_t sEnd[4][64];
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int x0 = 0, y0 = 0, x1 = 0, y1 = 0;
-    uint32_t at = 0, id = 0;
-    const uint32_t m = min(status[kStNumVis], (uint32_t)sp.n);     // ranks below m hold visible points
-    if ((uint32_t)r < m) {
-        at = offsets[r];
-        id = order[r];
-        const int rad = sp.radius[id];
-        if (rad > 0) tile_rect(cam, sp.mean2d[id], sp.mean2d[(size_t)sp.n + id], rad, x0, y0, x1, y1);
-        slot_base[id] = at;
-    } else {
-        at = offsets[sp.n];                    // the pair total (sentinel slot of the prefix sum)
-    }
-    const int w = x1 - x0;
-    const uint32_t cnt = (uint32_t)(w * (y1 - y0));
-    if ((uint32_t)r < m) {   // which rank owns every 256th pair (for the pair-balanced gather of the backward pass)
-        const uint32_t end = min(at + cnt, cap);
-        for (uint32_t c = (at + kChunkPairs - 1) / kChunkPairs; (uint64_t)c * kChunkPairs < end; ++c) chunk_rank[c] = (uint32_t)r;
-    }
-    sEnd[wave][lane] = at + cnt;
-    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)at, 0);
-    const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)(at + cnt), 63);
-    __builtin_amdgcn_wave_barrier();
-    bool dropped = false;
-    // Uniform trip count: every lane takes part in the cross-lane reads of each step (a lane that has left the loop
-    // could not be read by the others), only lanes with a slot in range store.
-    for (uint32_t base = first; base < last; base += 64) {
-        const uint32_t u = base + lane;
-        const bool mine = u < last;
-        // owner = first lane whose range end exceeds u (clamped for lanes without a slot)
-        int lo = 0;
-#pragma unroll
-        for (int step = 32; step >= 1; step >>= 1)
-            if (sEnd[wave][lo + step - 1] <= u) lo += step;
-        const int ox0 = __shfl(x0, lo, 64), oy0 = __shfl(y0, lo, 64), ow = __shfl(w, lo, 64);
-        const uint32_t oid = (uint32_t)__shfl((int)id, lo, 64), oat = (uint32_t)__shfl((int)at, lo, 64);
-        if (mine && ow > 0) {
-            const int t = (int)(u - oat);
-            const int ty = oy0 + t / ow, tx = ox0 + t - (t / ow) * ow;
-            if (u < cap) {
-                tkeys[u] = (uint32_t)(ty * cam.TX + tx);
-                tvals[u] = oid;
-            } else {
-                dropped = true;
-            }
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t tv = __shfl_up(iv, d, 64), tp = __shfl_up(ip, d, 64);
+            if (lane >= d) { iv += tv; ip = sat_add(ip, tp); }
         }
+        if (lane == 63) { sV[wave] = iv; sP[wave] = ip; }
+        __syncthreads();
+        uint32_t bv = carry_v, bp = carry_p, cv = 0, cp = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const uint32_t tv = sV[w], tp = sP[w];
+            if (w < wave) { bv += tv; bp = sat_add(bp, tp); }
+            cv += tv; cp = sat_add(cp, tp);
+        }
+        const uint32_t ep = __shfl_up(ip, 1, 64);      // exclusive within the wavefront = the lane below's inclusive sum
+        if (idx < nb) {
+            blk_vis[idx] = bv + iv - v;
+            blk_pairs[idx] = sat_add(bp, lane == 0 ? 0u : ep);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) { carry_v += cv; carry_p = sat_add(carry_p, cp); }
+        __syncthreads();
     }
-    if (dropped) status[kStOverflow] = 1u;
+    if (threadIdx.x == 0) {
+        const uint32_t m = min(carry_v, n);
+        status[kStNumVis] = m;
+        status[kStNumDup] = carry_p;
+        offsets[m] = carry_p;
+    }
+}
+
+// 3D Gaussians: the 48-byte raster record of a listed point (see binning_common.h for the rest of the block's work).
+__global__ __launch_bounds__(256) void k_pack_dup(SplatsDev sp, CamDev cam, BinArrays A, Packed* __restrict__ packed)
+{
+    const size_t N = (size_t)sp.n;
+    pack_dup_block(BinInput{sp.n, sp.mean2d, sp.radius}, cam, A, sp.depth, [&](int i) {
+        float4* dst = reinterpret_cast<float4*>(packed + i);
+        dst[0] = make_float4(sp.mean2d[i], sp.mean2d[N + i], sp.conic[i], sp.conic[N + i]);
+        dst[1] = make_float4(sp.conic[2 * N + i], sp.opacity[i], sp.color[i], sp.color[N + i]);
+        dst[2] = make_float4(sp.color[2 * N + i], __int_as_float(sp.radius[i]), sp.depth[i], 0.f);
+    });
 }
 
 __global__ __launch_bounds__(256) void k_bin_begin(uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, size_t nranges,
@@ -326,6 +149,9 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict_
 // over the classes present: the kernel runs on one compute unit, so its instruction count is its duration.
 constexpr int kOrderClasses = 40;           // < 63; class 63 stands for "no tile"
 constexpr uint32_t kOrderRounds = 8;        // rounds of 64 tiles whose ranges are loaded together (one trip to memory, not eight)
+// lists of 511 entries or more are sorted by a whole workgroup (radix_sort.hip: kWaveListMax - 1); length + 1 < 512 =
+// 2^9 means a class code of at most 2 * 8 + 1
+constexpr uint32_t kFirstSmallClass = (uint32_t)(kOrderClasses - 1) - 17u;
 
 __device__ __forceinline__ uint32_t order_class(uint32_t len)
 {
@@ -362,7 +188,8 @@ __device__ __forceinline__ uint64_t lanes_of_my_class(uint32_t cls)
     return same;
 }
 
-__global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict__ ranges, uint32_t ntiles, uint32_t* __restrict__ tile_order)
+__global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict__ ranges, uint32_t ntiles, uint32_t* __restrict__ tile_order,
+                                                     uint32_t* __restrict__ status)
 {
     __shared__ uint32_t count[64 * 16];      // [class][wavefront]: tiles, then where the wavefront's next tile of the class goes
     const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
@@ -399,6 +226,10 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
         for (int k = 0; k < kPer; ++k) { count[lane * kPer + k] = at; at += v[k]; }
     }
     __syncthreads();
+    // how many tiles hold 511 entries or more: they come first in the order, and the depth sort gives each a whole
+    // workgroup (the classes are cut at powers of two of length + 1, so this is where a class starts)
+    if (threadIdx.x == 0) status[kStNumBig] = count[kFirstSmallClass * 16u];
+    __syncthreads();
     for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
         if (per_wave > kOrderRounds * 64u) order_classes(range2, tb, t1, lane, cls);      // else still there from the counting pass
 #pragma unroll
@@ -414,26 +245,21 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
     }
 }
 
-// Inspection only: the 64-bit keys (tile << 32 | depth bits) of the sorted pairs, rebuilt from the sorted tile ids
-// and the per-point depth bits.
-__global__ __launch_bounds__(256) void k_make_keys64(const uint32_t* __restrict__ tkeys, const uint32_t* __restrict__ tvals,
-                                                     const uint32_t* __restrict__ depth_bits, const uint32_t* __restrict__ status,
-                                                     uint32_t cap, uint64_t* __restrict__ keys64)
+// Inspection only: the 64-bit keys (tile << 32 | depth bits) of the sorted pairs, rebuilt from the tile ranges, the
+// sorted point indices and the per-point depth bits. One workgroup per tile.
+__global__ __launch_bounds__(256) void k_make_keys64(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tvals,
+                                                     const uint32_t* __restrict__ depth_bits, uint32_t cap, uint64_t* __restrict__ keys64)
 {
-    const uint32_t P = min(status[kStNumDup], cap);
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= P) return;
-    keys64[i] = ((uint64_t)tkeys[i] << 32) | depth_bits[tvals[i]];
+    const uint32_t tile = blockIdx.x;
+    const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
+    for (uint32_t i = s + threadIdx.x; i < e; i += 256u) keys64[i] = ((uint64_t)tile << 32) | depth_bits[tvals[i]];
 }
 
 hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s)
 {
-    const uint32_t* status = reinterpret_cast<const uint32_t*>(ws + L.off_status);
-    const uint32_t* tk = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
     const uint32_t* tv = reinterpret_cast<const uint32_t*>(ws + sorted_vals_off(L));
-    hipLaunchKernelGGL(k_make_keys64, dim3((L.cap + 255u) / 256u), dim3(256), 0, s, tk, tv,
-                       reinterpret_cast<const uint32_t*>(ws + L.off_depth_bits), status, L.cap,
-                       reinterpret_cast<uint64_t*>(ws + L.off_keys64));
+    hipLaunchKernelGGL(k_make_keys64, dim3((unsigned)L.tiles), dim3(256), 0, s, reinterpret_cast<const uint32_t*>(ws + L.off_ranges), tv,
+                       reinterpret_cast<const uint32_t*>(ws + L.off_depth_bits), L.cap, reinterpret_cast<uint64_t*>(ws + L.off_keys64));
     return hipGetLastError();
 }
 
@@ -448,87 +274,82 @@ hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s)
     return hipGetLastError();
 }
 
-// visible points per block of 256, scanned in place; leaves the visible count in the status words. Also the call's
-// first launch: clears the status words and the tile ranges.
+BinArrays bin_arrays(const Layout& L, char* ws)
+{
+    BinArrays A;
+    A.touched = reinterpret_cast<const uint32_t*>(ws + L.off_touched);
+    A.blk_vis = reinterpret_cast<const uint32_t*>(ws + L.off_blk_vis);
+    A.blk_pairs = reinterpret_cast<const uint32_t*>(ws + L.off_blk_pairs);
+    A.order = reinterpret_cast<uint32_t*>(ws + L.off_order);
+    A.offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
+    A.slot_base = reinterpret_cast<uint32_t*>(ws + L.off_slot_base);
+    A.depth_bits = reinterpret_cast<uint32_t*>(ws + L.off_depth_bits);
+    A.tkeys = reinterpret_cast<uint32_t*>(ws + L.off_tkey0);
+    A.tvals = reinterpret_cast<uint32_t*>(ws + L.off_tval0);
+    A.chunk_rank = reinterpret_cast<uint32_t*>(ws + L.off_chunk_rank);
+    A.cap = L.cap;
+    A.status = reinterpret_cast<uint32_t*>(ws + L.off_status);
+    return A;
+}
+
+// Tiles per point, listed points and pairs per block of 256 points and their prefix sums; leaves the listed count and the
+// pair total in the status words. Also the call's first launch: clears the status words and the tile ranges.
 hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     const int n = in.n;
     if (n == 0) return hipSuccess;
-    uint32_t* vis_block = reinterpret_cast<uint32_t*>(ws + L.off_vis_block);
+    uint32_t* blk_vis = reinterpret_cast<uint32_t*>(ws + L.off_blk_vis);
+    uint32_t* blk_pairs = reinterpret_cast<uint32_t*>(ws + L.off_blk_pairs);
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     const unsigned nb = (unsigned)((n + 255) / 256);
     ProfScope prof(kKCountPack, s);
-    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), vis_block,
-                       status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
-    hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, s, vis_block, nb, status + kStNumVis);
+    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), blk_vis,
+                       blk_pairs, status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, s, blk_vis, blk_pairs, nb, status,
+                       reinterpret_cast<uint32_t*>(ws + L.off_offsets), (uint32_t)n);
     return hipGetLastError();
 }
 
-hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
-{
-    if (sp.n == 0) return hipSuccess;
-    hipError_t e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
-    if (e != hipSuccess) return e;
-    ProfScope prof(kKCountPack, s);
-    hipLaunchKernelGGL(k_count_pack, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
-                       reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<const uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed*>(ws + L.off_packed),
-                       reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
-                       reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
-    return hipGetLastError();
-}
-
-// Everything after the per-point counts and (depth bits, index) pairs are in place: depth order, prefix sum,
-// duplication, tile sort, tile ranges.
+// Everything after the pairs are in place (in point order): stable sort by tile, tile ranges, the order in which the
+// compositing kernels take the tiles, depth order inside every tile's list.
 hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     if (sp.n == 0) return hipSuccess;
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
-    uint32_t* touched = reinterpret_cast<uint32_t*>(ws + L.off_touched);
-    uint32_t* offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
-    uint32_t* slot_base = reinterpret_cast<uint32_t*>(ws + L.off_slot_base);
-    uint32_t* part = reinterpret_cast<uint32_t*>(ws + L.off_scan_part);
     uint32_t* ranges = reinterpret_cast<uint32_t*>(ws + L.off_ranges);
-    uint32_t* dk[2] = {reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dkey1)};
-    uint32_t* dv[2] = {reinterpret_cast<uint32_t*>(ws + L.off_dval0), reinterpret_cast<uint32_t*>(ws + L.off_dval1)};
     uint32_t* tk[2] = {reinterpret_cast<uint32_t*>(ws + L.off_tkey0), reinterpret_cast<uint32_t*>(ws + L.off_tkey1)};
     uint32_t* tv[2] = {reinterpret_cast<uint32_t*>(ws + L.off_tval0), reinterpret_cast<uint32_t*>(ws + L.off_tval1)};
     uint32_t* totals = reinterpret_cast<uint32_t*>(ws + L.off_totals);
     uint32_t* tile_hist = reinterpret_cast<uint32_t*>(ws + L.off_tile_hist);
-    const unsigned nblk = (unsigned)((sp.n + 255) / 256);
-    // depth digits: sort the visible splats by their 32 depth bits (four passes, result back in the "0" buffers)
-    hipError_t e = launch_radix_sort32(dk, dv, status + kStNumVis, (uint32_t)sp.n, 32, totals, tile_hist, s);
-    if (e != hipSuccess) return e;
-    const uint32_t* order = dv[radix_pass_count(32) & 1];
-    {
-        ProfScope prof(kKCountPack, s);
-        hipLaunchKernelGGL(k_rank_counts, dim3((unsigned)(sp.n / 1024 + 1)), dim3(256), 0, s, sp.n, status, order, touched, offsets);
-    }
-    e = launch_exclusive_scan(offsets, offsets, (uint32_t)sp.n + 1u, part, status + kStNumDup, s);
-    if (e != hipSuccess) return e;
-    {
-        ProfScope prof(kKDuplicate, s);
-        hipLaunchKernelGGL(k_duplicate, dim3(nblk), dim3(256), 0, s, sp, cam, order, offsets, tk[0], tv[0], slot_base,
-                           reinterpret_cast<uint32_t*>(ws + L.off_chunk_rank), L.cap, status);
-    }
     // tile digits: stable sort of the P pairs by tile id
-    e = launch_radix_sort32(tk, tv, status + kStNumDup, L.cap, L.tile_bits, totals + kRadixMaxBins, tile_hist, s);
+    hipError_t e = launch_radix_sort32(tk, tv, status + kStNumDup, L.cap, L.tile_bits, totals, tile_hist, s);
     if (e != hipSuccess) return e;
+    const int fin = L.tile_passes & 1;
+    const uint32_t ntiles = (uint32_t)(cam.TX * cam.TY);      // the call's tile grid (a patch covers fewer tiles than the image the workspace is sized for)
+    uint32_t* tile_order = reinterpret_cast<uint32_t*>(ws + L.off_tile_order);
     {
         ProfScope prof(kKTileRanges, s);
-        const uint32_t* sorted = reinterpret_cast<const uint32_t*>(ws + sorted_tkeys_off(L));
-        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 1023u) / 1024u), dim3(256), 0, s, sorted, status, L.cap, (uint32_t)L.tiles, ranges);
-        // the call's tile grid (a patch covers fewer tiles than the image the workspace is sized for)
-        hipLaunchKernelGGL(k_tile_order, dim3(1), dim3(1024), 0, s, ranges, (uint32_t)(cam.TX * cam.TY),
-                           reinterpret_cast<uint32_t*>(ws + L.off_tile_order));
+        hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 1023u) / 1024u), dim3(256), 0, s, tk[fin], status, L.cap, (uint32_t)L.tiles, ranges);
+        hipLaunchKernelGGL(k_tile_order, dim3(1), dim3(1024), 0, s, ranges, ntiles, tile_order, status);
     }
-    return hipGetLastError();
+    // depth digits: every tile's list, now in point order, into depth order (the tile ids in tk[fin] are spent: that
+    // array and the other pair of buffers are the scratch of lists too long for LDS)
+    return launch_tile_depth_sort(ranges, tile_order, ntiles, status, reinterpret_cast<const uint32_t*>(ws + L.off_depth_bits), L.cap,
+                                  tk[fin], tv[fin], tk[fin ^ 1], tv[fin ^ 1], s);
 }
 
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     if (sp.n == 0) return launch_bin_begin(L, ws, s);      // nothing to count: only the cleared status words and ranges
-    hipError_t e = launch_count_pack(sp, cam, L, ws, s);
+    hipError_t e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
     if (e != hipSuccess) return e;
+    {
+        ProfScope prof(kKDuplicate, s);
+        hipLaunchKernelGGL(k_pack_dup, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam, bin_arrays(L, ws),
+                           reinterpret_cast<Packed*>(ws + L.off_packed));
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     return launch_bin_finish(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
 }
 

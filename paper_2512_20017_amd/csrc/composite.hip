@@ -459,7 +459,7 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
     const Packed* packed = reinterpret_cast<const Packed*>(ws + L.off_packed);
     const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
     const uint32_t* slot_base = reinterpret_cast<const uint32_t*>(ws + L.off_slot_base);
-    const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_dval0);
+    const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_order);
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     float4* partial = reinterpret_cast<float4*>(ws + L.off_partial);
     {

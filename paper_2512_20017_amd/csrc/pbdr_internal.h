@@ -112,9 +112,10 @@ struct Splat2DGradDev {
 };
 
 // Status words at the head of the workspace.
-// pair count, overflow flag, visible-point count: cleared by every binning. kStEpoch is never cleared: a counter that
+// pair count, overflow flag, visible-point count, number of tiles whose list is too long for one wavefront to sort
+// (written by k_tile_order): cleared by every binning. kStEpoch is never cleared: a counter that
 // the backward pass bumps once per call and stamps into the per-pair records it writes (see k_composite_bwd).
-enum { kStNumDup = 0, kStOverflow = 1, kStNumVis = 2, kStCleared = 32, kStEpoch = 32, kStWords = 64 };
+enum { kStNumDup = 0, kStOverflow = 1, kStNumVis = 2, kStNumBig = 3, kStCleared = 32, kStEpoch = 32, kStWords = 64 };
 
 // Workspace layout for (n, W, H, capacity). All offsets are multiples of 256 bytes.
 enum Variant { kVariant3D = 0, kVariant2D = 1 };   // 3D Gaussians / 2D Gaussian surfels
@@ -126,14 +127,13 @@ struct Layout {
     int partial_vec4;         // float4s of partial gradient sums per pair: 3 (3D) or 4 (2D)
     uint32_t cap;
     int tile_bits, tile_passes;   // key bits / radix passes spent on the tile id
-    size_t off_status, off_packed, off_depth_bits, off_vis_block, off_touched, off_offsets, off_slot_base, off_scan_part, off_dkey0, off_dkey1, off_dval0,
-        off_dval1, off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
+    size_t off_status, off_packed, off_depth_bits, off_blk_vis, off_blk_pairs, off_touched, off_offsets, off_slot_base, off_order,
+        off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
         off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, off_reach, off_tile_order, total;
 };
 constexpr int kSortItems = 2048;   // pairs per radix-sort block
 constexpr int kRadixMaxBins = 256;   // widest digit: 8 bits
 int radix_pass_count(int key_bits);  // passes launch_radix_sort32 takes for this many key bits
-constexpr int kScanItems = 4096;   // elements per scan block
 bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L);
 
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
@@ -157,9 +157,10 @@ struct BinInput {
     const float* mean2d;      // [2][n]
     const int32_t* radius;    // [n]
 };
+struct BinArrays;
+BinArrays bin_arrays(const Layout& L, char* ws);                                             // see binning_common.h
 hipError_t launch_bin_begin(const Layout& L, char* ws, hipStream_t s);                       // zero status / totals / ranges
 hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
-hipError_t launch_count_pack(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_finish(const BinInput& in, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_bin_sort(const SplatsDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
@@ -170,10 +171,10 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
 
 hipError_t launch_render_stats(const CamDev& cam, const Layout& L, char* ws, uint64_t* counters, hipStream_t s);
 
-// exclusive prefix sum of n uint32 (in -> out, may alias), total written to *total_out if non-null.
-// `partials` needs ceil(n / kScanItems) + 1 uint32.
-hipError_t launch_exclusive_scan(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* partials,
-                                 uint32_t* total_out, hipStream_t s);
+// stable sort of every tile's list [ranges[2t], ranges[2t+1]) of (keysA, valsA) by depth_bits[val]; keysA's contents are
+// overwritten, (keysB, valsB) are scratch; the result is in valsA
+hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_order, uint32_t ntiles, const uint32_t* status,
+                                  const uint32_t* depth_bits, uint32_t cap, uint32_t* keysA, uint32_t* valsA, uint32_t* keysB, uint32_t* valsB, hipStream_t s);
 hipError_t launch_radix_sort32(uint32_t* keys[2], uint32_t* vals[2], const uint32_t* count_ptr, uint32_t count_cap,
                                int key_bits, uint32_t* totals, uint32_t* tile_hist, hipStream_t s);
 hipError_t launch_make_keys64(const Layout& L, char* ws, hipStream_t s);

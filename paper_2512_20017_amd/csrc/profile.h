@@ -7,7 +7,7 @@ namespace pbdr {
 
 enum KernelId {
     kKPreprocess = 0, kKCountPack, kKScan, kKDuplicate, kKRadixHist, kKRadixScatter, kKTileRanges, kKFill,
-    kKCompositeFwd, kKCompositeBwd, kKPreprocessBwd, kKStats, kKGather, kKGroupCull, kKLoss, kKAdam, kKernelCount
+    kKCompositeFwd, kKCompositeBwd, kKPreprocessBwd, kKStats, kKGather, kKGroupCull, kKLoss, kKAdam, kKTileDepthSort, kKernelCount
 };
 
 struct ProfState {

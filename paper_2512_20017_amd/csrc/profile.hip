@@ -8,8 +8,9 @@ namespace pbdr {
 ProfState g_prof;
 
 static const char* const kKernelNames[kKernelCount] = {
-    "k_preprocess", "k_count_pack", "scan(3 kernels)", "k_duplicate", "k_radix_hist", "k_radix_scatter", "k_tile_ranges",
-    "fill", "k_composite_fwd", "k_composite_bwd", "k_preprocess_bwd", "k_render_stats", "k_gather_splat_grads", "k_group_cull", "k_l1_loss", "k_adam_selective"};
+    "k_preprocess", "k_count_visible", "(unused)", "k_pack_dup", "k_radix_hist", "k_radix_scatter", "k_tile_ranges",
+    "fill", "k_composite_fwd", "k_composite_bwd", "k_preprocess_bwd", "k_render_stats", "k_gather_splat_grads", "k_group_cull", "k_l1_loss", "k_adam_selective",
+    "k_tile_depth_sort"};
 
 static void release()
 {

@@ -217,6 +217,422 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Depth order inside each tile's list. After the stable sort by tile id every tile's list holds its splats in point
+// order; the list is then sorted stably by the 32 depth bits, which leaves the order of the key
+// (tile << 32 | depth bits), ties by point index. One launch, every list on its own:
+//   - fewer than 511 entries (k_tile_order lists the tiles longest first and says how many have more): one WAVEFRONT
+//     per list, four lists per workgroup, no workgroup barrier anywhere: up to 64 entries by counting (every lane
+//     compares its key with all others through the scalar unit), else least-significant-digit radix passes with 8-bit
+//     digits over the bit positions in which the list's keys differ at all (depths of one tile share sign, most
+//     exponent bits and often more). Keys and positions live in registers in list order; a pass scatters them into the
+//     wavefront's 4 KB of LDS and reads them back in the new order;
+//   - up to 6144 entries: the same passes by a whole workgroup, two barriers per pass. Only the permutation (16-bit
+//     positions) is in LDS; the keys stay in the global scratch array (the spent tile ids) and are fetched through it;
+//   - longer lists: the passes in chunks of 2048 through the global scratch arrays, whole-list digit counts first,
+//     then chunk by chunk in order.
+// 20 KB of LDS per workgroup, so that eight workgroups share a compute unit: the work is a chain of dependent LDS and
+// cross-lane steps per list, and what hides it is other lists in flight.
+// A pass ranks its entries per wavefront and round of 64 by ballots (lanes with the same digit find each other), the
+// first lane of each group adds the group's size to the digit's counter in LDS and gets back how many entries of that
+// digit came before (earlier rounds of the wavefront: LDS executes a wavefront's operations in order), and hands that
+// to its group through the LDS crossbar: equal digits keep their incoming order.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWaveListMax = 512;                     // a wavefront's own list holds fewer than kWaveListMax - 1 entries (8 rounds)
+constexpr int kWgListMax = 6144;                      // a workgroup's list with its permutation in LDS (24 rounds per wavefront)
+constexpr int kListChunk = 2048;                      // entries per chunk of a list that goes through global memory
+constexpr int kListRounds = kListChunk / 256;
+
+struct WaveSortLds {      // a wavefront's share of the LDS when it sorts a list of its own
+    uint32_t key[kWaveListMax];
+    uint16_t idx[kWaveListMax];
+    uint32_t hist[256];
+};
+struct WgSortLds {        // the workgroup's LDS when it sorts one list together
+    uint16_t idx[kWgListMax];                         // the permutation: idx[i] = incoming position of the entry now at i
+    uint32_t cnt[4][256];                             // per wavefront and digit: entries in the wavefront's part of the list
+    uint32_t start[4][256];                           // per wavefront and digit: where its first entry of that digit goes
+    uint32_t scan[4];
+    uint32_t mask;
+};
+union ListSortLds { WgSortLds wg; WaveSortLds wave[4]; };
+static_assert(sizeof(ListSortLds) <= 20 * 1024 + 64, "eight workgroups per compute unit");
+
+// bit range [lo, hi] in which the keys differ -> number of 8-bit passes and the shift of pass p (the topmost digit
+// may reach past bit hi into bits all keys share; it never reaches past bit 31)
+__device__ __forceinline__ int list_passes(uint32_t diff, int& lo)
+{
+    lo = __builtin_ctz(diff);
+    const int hi = 31 - __builtin_clz(diff);
+    return (hi - lo + 8) / 8;
+}
+__device__ __forceinline__ int list_shift(int lo, int p) { return min(lo + 8 * p, 24); }
+
+// Entries of this wavefront with the same digit as this lane's that come before it: earlier rounds (through the digit's
+// counter in `hist`, a row no other wavefront touches) plus lower lanes of this round.
+__device__ __forceinline__ uint32_t digit_prefix(uint32_t* hist, uint32_t digit, bool valid)
+{
+    const int lane = threadIdx.x & 63;
+    const uint64_t peers = digit_peers<8>(digit, valid);
+    const uint32_t rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+    uint32_t before = 0u;
+    if (valid && rank == 0u) before = atomicAdd(&hist[digit], (uint32_t)__popcll(peers));
+    const int leader = valid ? __builtin_ctzll(peers) : lane;
+    before = (uint32_t)__builtin_amdgcn_ds_bpermute(leader << 2, (int)before);
+    return before + rank;
+}
+
+// exclusive scan over a wavefront's 256 digit counters, four consecutive digits per lane, in place
+__device__ __forceinline__ void wave_scan_digits(uint32_t* hist)
+{
+    const int lane = threadIdx.x & 63;
+    const uint32_t c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+    const uint32_t tot = c0 + c1 + c2 + c3;
+    uint32_t inc = tot;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    const uint32_t start = inc - tot;
+    hist[4 * lane] = start; hist[4 * lane + 1] = start + c0; hist[4 * lane + 2] = start + c0 + c1;
+    hist[4 * lane + 3] = start + c0 + c1 + c2;
+}
+
+__device__ __forceinline__ void wave_lds_sync()      // orders this wavefront's LDS writes before its later LDS reads
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// One wavefront sorts the list vals[0 .. L), 1 < L < kWaveListMax - 1, stably by depth_bits[val], in place.
+__device__ __forceinline__ void wave_sort_list(WaveSortLds& W, uint32_t L, const uint32_t* __restrict__ depth_bits,
+                                               uint32_t* __restrict__ vals)
+{
+    constexpr int R = kWaveListMax / 64;
+    const int lane = threadIdx.x & 63;
+    if (L <= 64u) {
+        // rank by counting: entry j precedes entry i if its key is smaller, or equal and j < i
+        uint32_t v = 0u, k = 0u;
+        if ((uint32_t)lane < L) { v = vals[lane]; k = depth_bits[v]; }
+        uint32_t before = 0u;
+        for (uint32_t j = 0; j < L; ++j) {
+            const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)k, (int)j);
+            before += (kj < k || (kj == k && j < (uint32_t)lane)) ? 1u : 0u;
+        }
+        if ((uint32_t)lane < L) vals[min(before, L - 1u)] = v;       // every lane read its entry above
+        return;
+    }
+    const int nr = (int)((L + 63u) / 64u);
+    uint32_t key[R], id[R];      // the list in its current order: entry r * 64 + lane
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        id[r] = 0u;
+        if (r < nr && r * 64u + lane < L) id[r] = vals[r * 64u + lane];      // (the point index, for the key fetch below)
+    }
+    uint32_t diff = 0u;
+    const uint32_t k0 = depth_bits[(uint32_t)__builtin_amdgcn_readfirstlane((int)id[0])];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        key[r] = k0;
+        if (r < nr && r * 64u + lane < L) key[r] = depth_bits[id[r]];
+        diff |= key[r] ^ k0;
+        id[r] = r * 64u + lane;                                              // from here on: the incoming position
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) diff |= (uint32_t)__shfl_xor((int)diff, d, 64);
+    if (diff == 0u) return;                        // one depth throughout: point order is the order
+    int lo;
+    const int passes = list_passes(diff, lo);
+    for (int p = 0; p < passes; ++p) {
+        const int shift = list_shift(lo, p);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) W.hist[q * 64 + lane] = 0u;
+        wave_lds_sync();
+        uint32_t pre[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (r < nr) pre[r] = digit_prefix(W.hist, (key[r] >> shift) & 255u, r * 64u + lane < L);
+        wave_lds_sync();
+        wave_scan_digits(W.hist);
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (r < nr && r * 64u + lane < L) {
+                const uint32_t pos = min(W.hist[(key[r] >> shift) & 255u] + pre[r], L - 1u);
+                W.key[pos] = key[r]; W.idx[pos] = (uint16_t)id[r];
+            }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (r < nr && r * 64u + lane < L) { key[r] = W.key[r * 64u + lane]; id[r] = W.idx[r * 64u + lane]; }
+        }
+        wave_lds_sync();      // (the next pass, or the next list of this wavefront, writes the buffer again)
+    }
+    // the point indices, through the sorted positions: every entry is fetched before the first is stored
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        if (r < nr && r * 64u + lane < L) key[r] = vals[id[r]];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        if (r < nr && r * 64u + lane < L) vals[r * 64u + lane] = key[r];
+}
+
+// A workgroup sorts the list vals[0 .. L), L <= kWgListMax. keys: L words of global scratch.
+__device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uint32_t* __restrict__ depth_bits,
+                                             uint32_t* __restrict__ vals, uint32_t* __restrict__ keys)
+{
+    constexpr int R = kWgListMax / 256;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // keys of the list, in incoming order, and the bit positions in which they differ
+    uint32_t diff = 0u;
+    const uint32_t k0 = depth_bits[vals[0]];
+    if (threadIdx.x == 0) S.mask = 0u;
+    for (uint32_t i0 = 0; i0 < L; i0 += 8u * 256u) {      // eight independent fetches in flight, twice
+        uint32_t t[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t i = i0 + r * 256u + threadIdx.x;
+            t[r] = i < L ? vals[i] : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t i = i0 + r * 256u + threadIdx.x;
+            if (i < L) t[r] = depth_bits[t[r]];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t i = i0 + r * 256u + threadIdx.x;
+            if (i < L) { diff |= t[r] ^ k0; keys[i] = t[r]; S.idx[i] = (uint16_t)i; }
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) diff |= (uint32_t)__shfl_xor((int)diff, d, 64);
+    __syncthreads();                               // S.mask is cleared; keys and permutation are in place
+    if (lane == 0 && diff) atomicOr(&S.mask, diff);
+    __syncthreads();
+    const uint32_t mask = S.mask;
+    if (mask == 0u) return;                        // one depth throughout (uniform for the workgroup)
+    int lo;
+    const int passes = list_passes(mask, lo);
+    // each wavefront takes a contiguous quarter of the list, in rounds of 64
+    const uint32_t per_wave = ((L + 255u) / 256u) * 64u;
+    const int nr = (int)(per_wave / 64u);
+    const uint32_t wb = wave * per_wave, we = min(L, wb + per_wave);
+    uint32_t ent[R];      // this lane's entries of the current order: incoming position | (entries of its digit before it) << 16
+    for (int p = 0; p < passes; ++p) {
+        const int shift = list_shift(lo, p);
+        // (this wavefront's count row was last read by the others before the barrier that ended the previous pass)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) S.cnt[wave][q * 64 + lane] = 0u;
+        wave_lds_sync();
+        uint32_t k[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (r < nr) {
+                const uint32_t i = wb + r * 64u + lane;
+                ent[r] = i < we ? S.idx[i] : 0u;
+                k[r] = i < we ? keys[ent[r]] : 0u;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (r < nr) ent[r] |= digit_prefix(S.cnt[wave], (k[r] >> shift) & 255u, wb + r * 64u + lane < we) << 16;
+        __syncthreads();      // every wavefront has read its part of the permutation and counted
+        {   // every wavefront works out where its own entries of each digit go: digits before, then the wavefronts before it
+            uint32_t mine[4], tot4 = 0u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int d = 4 * lane + q;
+                const uint32_t c0 = S.cnt[0][d], c1 = S.cnt[1][d], c2 = S.cnt[2][d], c3 = S.cnt[3][d];
+                mine[q] = tot4 + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+                tot4 += c0 + c1 + c2 + c3;
+            }
+            uint32_t inc = tot4;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t t = __shfl_up(inc, d, 64);
+                if (lane >= d) inc += t;
+            }
+            const uint32_t below = inc - tot4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) S.start[wave][4 * lane + q] = below + mine[q];
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (r < nr && wb + r * 64u + lane < we) {
+                const uint32_t pos = min(S.start[wave][(k[r] >> shift) & 255u] + (ent[r] >> 16), L - 1u);
+                S.idx[pos] = (uint16_t)(ent[r] & 0xffffu);
+            }
+        }
+        __syncthreads();
+    }
+    // the point indices, through the sorted positions: every entry is fetched before the first is stored
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t i = r * 256u + threadIdx.x;
+        if (i < L) ent[r] = vals[S.idx[i]];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t i = r * 256u + threadIdx.x;
+        if (i < L) vals[i] = ent[r];
+    }
+}
+
+// exclusive scan of one value per thread over the workgroup's 256 threads
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* sScan)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    if (lane == 63) sScan[wave] = inc;
+    __syncthreads();
+    uint32_t below = inc - v;
+#pragma unroll
+    for (int w = 0; w < 3; ++w) if (w < wave) below += sScan[w];
+    __syncthreads();
+    return below;
+}
+
+// Lists too long for LDS: one stable pass by the 8-bit digit at `shift` from (kin, vin) to (kout, vout), all of length L
+// in global memory, in chunks of kListChunk. base: 256 words of LDS, each digit's next position in the list.
+__device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t* base, uint32_t L, int shift, const uint32_t* __restrict__ kin,
+                                               const uint32_t* __restrict__ vin, uint32_t* __restrict__ kout, uint32_t* __restrict__ vout)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    base[threadIdx.x] = 0u;
+    __syncthreads();
+    for (uint32_t i0 = wave * 64u; i0 < L; i0 += 256u) {      // digit counts of the whole list
+        const uint32_t i = i0 + lane;
+        const bool valid = i < L;
+        const uint32_t digit = valid ? (kin[i] >> shift) & 255u : 0u;
+        const uint64_t peers = digit_peers<8>(digit, valid);
+        if (valid && (peers & lt_mask) == 0ull) atomicAdd(&base[digit], (uint32_t)__popcll(peers));
+    }
+    __syncthreads();
+    {
+        const uint32_t c = base[threadIdx.x];
+        const uint32_t start = block_exclusive_scan(c, S.scan);      // where each digit's run starts
+        base[threadIdx.x] = start;
+    }
+    __syncthreads();
+    for (uint32_t c0 = 0; c0 < L; c0 += kListChunk) {
+        const uint32_t cn = min((uint32_t)kListChunk, L - c0);
+        const uint32_t per_wave = ((cn + 255u) / 256u) * 64u;
+        const int nr = (int)(per_wave / 64u);
+        const uint32_t wb = c0 + wave * per_wave, we = min(c0 + cn, wb + per_wave);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) S.cnt[wave][q * 64 + lane] = 0u;
+        wave_lds_sync();
+        uint32_t key[kListRounds], val[kListRounds], pre[kListRounds];
+#pragma unroll
+        for (int r = 0; r < kListRounds; ++r) {      // the chunk's loads first, all in flight together
+            const uint32_t i = wb + r * 64u + lane;
+            key[r] = 0u; val[r] = 0u;
+            if (r < nr && i < we) { key[r] = kin[i]; val[r] = vin[i]; }
+        }
+#pragma unroll
+        for (int r = 0; r < kListRounds; ++r)
+            if (r < nr) pre[r] = digit_prefix(S.cnt[wave], (key[r] >> shift) & 255u, wb + r * 64u + lane < we);
+        __syncthreads();
+        {   // thread = digit: where each wavefront's entries of this digit go; the digit's run moves on by the chunk's count
+            const uint32_t c0w = S.cnt[0][threadIdx.x], c1w = S.cnt[1][threadIdx.x], c2w = S.cnt[2][threadIdx.x], c3w = S.cnt[3][threadIdx.x];
+            const uint32_t start = base[threadIdx.x];
+            S.start[0][threadIdx.x] = start;
+            S.start[1][threadIdx.x] = start + c0w;
+            S.start[2][threadIdx.x] = start + c0w + c1w;
+            S.start[3][threadIdx.x] = start + c0w + c1w + c2w;
+            base[threadIdx.x] = start + c0w + c1w + c2w + c3w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kListRounds; ++r) {
+            if (r < nr && wb + r * 64u + lane < we) {
+                const uint32_t pos = min(S.start[wave][(key[r] >> shift) & 255u] + pre[r], L - 1u);      // < L for consistent counts
+                kout[pos] = key[r]; vout[pos] = val[r];
+            }
+        }
+        __syncthreads();      // the count rows are cleared and the position rows rewritten by the next chunk
+    }
+}
+
+__global__ __launch_bounds__(256) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+                                                         uint32_t ntiles, const uint32_t* __restrict__ status,
+                                                         const uint32_t* __restrict__ depth_bits, uint32_t cap,
+                                                         uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
+                                                         uint32_t* __restrict__ keysB, uint32_t* __restrict__ valsB)
+{
+    __shared__ ListSortLds U;
+    // tile_order lists the tiles longest first; its first `nbig` tiles are too long for one wavefront. Workgroups
+    // 0 .. nbig - 1 take one of those each; every later workgroup takes four shorter lists, one per wavefront.
+    const uint32_t nbig = min(status[kStNumBig], ntiles);
+    const int wave = threadIdx.x >> 6;
+    if (blockIdx.x >= nbig) {
+        const uint32_t idx = nbig + (blockIdx.x - nbig) * 4u + (uint32_t)wave;
+        if (idx >= ntiles) return;
+        const uint32_t tile = tile_order[idx];
+        const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
+        if (e <= s + 1u) return;
+        // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
+        if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
+        return;
+    }
+    WgSortLds& S = U.wg;
+    const uint32_t tile = tile_order[blockIdx.x];
+    const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
+    if (e <= s + 1u) return;                     // uniform for the workgroup
+    const uint32_t L = e - s;
+    if (L <= (uint32_t)kWgListMax) { wg_sort_list(S, L, depth_bits, valsA + s, keysA + s); return; }
+    // through global memory: keys of the list and the bit positions in which they differ
+    const int lane = threadIdx.x & 63;
+    const uint32_t k0 = depth_bits[valsA[s]];
+    uint32_t diff = 0u;
+    if (threadIdx.x == 0) S.mask = 0u;
+    for (uint32_t i = threadIdx.x; i < L; i += 256u) {
+        const uint32_t k = depth_bits[valsA[s + i]];
+        diff |= k ^ k0;
+        keysA[s + i] = k;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) diff |= (uint32_t)__shfl_xor((int)diff, d, 64);
+    __syncthreads();                               // S.mask is cleared, the keys are in place
+    if (lane == 0 && diff) atomicOr(&S.mask, diff);
+    __syncthreads();
+    const uint32_t mask = S.mask;
+    if (mask == 0u) return;                        // one depth throughout: point order is the order
+    int lo;
+    const int passes = list_passes(mask, lo);
+    uint32_t* base = reinterpret_cast<uint32_t*>(S.idx);      // the permutation array is idle on this path
+    for (int p = 0; p < passes; ++p) {
+        if ((p & 1) == 0) long_list_pass(S, base, L, list_shift(lo, p), keysA + s, valsA + s, keysB + s, valsB + s);
+        else long_list_pass(S, base, L, list_shift(lo, p), keysB + s, valsB + s, keysA + s, valsA + s);
+    }
+    if (passes & 1)
+        for (uint32_t i = threadIdx.x; i < L; i += 256u) valsA[s + i] = valsB[s + i];
+}
+
+hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_order, uint32_t ntiles, const uint32_t* status,
+                                  const uint32_t* depth_bits, uint32_t cap, uint32_t* keysA, uint32_t* valsA, uint32_t* keysB,
+                                  uint32_t* valsB, hipStream_t s)
+{
+    if (ntiles == 0) return hipSuccess;
+    ProfScope prof(kKTileDepthSort, s);
+    hipLaunchKernelGGL(k_tile_depth_sort, dim3(ntiles), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits, cap, keysA, valsA,
+                       keysB, valsB);
+    return hipGetLastError();
+}
+
 template <int kBits>
 static void launch_pass(uint32_t* keys[2], uint32_t* vals[2], int src, const uint32_t* count_ptr, uint32_t count_cap, int shift,
                         uint32_t* totals, uint32_t* tile_hist, uint32_t nb, hipStream_t s)

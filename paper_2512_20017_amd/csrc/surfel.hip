@@ -14,6 +14,7 @@
 // mx is used on both sides, so this is the same number as x T_2 - T_0, without the cancellation.
 #include "composite_common.h"
 #include "pair_reduce.h"
+#include "binning_common.h"
 
 namespace pbdr {
 
@@ -309,38 +310,22 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
     }
 }
 
-// One thread per point; a visible point gets its tile count, the 64-byte raster record with centred rows, and its
-// (depth bits, index) pair in the compact, index-ordered list of visible points (see the 3D variant).
-__global__ __launch_bounds__(256) void k_count_pack2d(Splats2DDev sp, CamDev cam, const uint32_t* __restrict__ vis_block,
-                                                      const uint32_t* __restrict__ tiles_touched, Packed2D* __restrict__ packed,
-                                                      uint32_t* __restrict__ dkey, uint32_t* __restrict__ dval,
-                                                      uint32_t* __restrict__ depth_bits)
+// Surfels: the 64-byte raster record of a listed point, with centred rows (see binning_common.h for the rest of the
+// block's work: compaction and pair emission as for 3D Gaussians).
+__global__ __launch_bounds__(256) void k_pack_dup2d(Splats2DDev sp, CamDev cam, BinArrays A, Packed2D* __restrict__ packed)
 {
-    __shared__ uint32_t sWave[4];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t N = (size_t)sp.n;
-    const bool vis = (i < sp.n) && tiles_touched[i] > 0;
-    const unsigned long long m = __ballot(vis);
-    if (lane == 0) sWave[wave] = (uint32_t)__popcll(m);
-    __syncthreads();
-    if (!vis) return;
-    uint32_t slot = vis_block[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-#pragma unroll
-    for (int w = 0; w < 3; ++w) if (w < wave) slot += sWave[w];
-    const int r = sp.radius[i];
-    const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
-    const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
-    float4* dst = reinterpret_cast<float4*>(packed + i);
-    dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
-                         fmaf(-my, t2y, sp.T[4 * N + i]));
-    dst[1] = make_float4(t2x, t2y, t2z, sp.opacity[i]);
-    dst[2] = make_float4(mx, my, sp.color[i], sp.color[N + i]);
-    dst[3] = make_float4(sp.color[2 * N + i], __int_as_float(r), fmaf(-mx, t2z, sp.T[2 * N + i]), fmaf(-my, t2z, sp.T[5 * N + i]));
-    const uint32_t key = __float_as_uint(sp.depth[i]);
-    dkey[slot] = key;
-    dval[slot] = (uint32_t)i;
-    depth_bits[i] = key;
+    pack_dup_block(BinInput{sp.n, sp.mean2d, sp.radius}, cam, A, sp.depth, [&](int i) {
+        const float mx = sp.mean2d[i], my = sp.mean2d[N + i];
+        const float t2x = sp.T[6 * N + i], t2y = sp.T[7 * N + i], t2z = sp.T[8 * N + i];
+        float4* dst = reinterpret_cast<float4*>(packed + i);
+        dst[0] = make_float4(fmaf(-mx, t2x, sp.T[i]), fmaf(-mx, t2y, sp.T[N + i]), fmaf(-my, t2x, sp.T[3 * N + i]),
+                             fmaf(-my, t2y, sp.T[4 * N + i]));
+        dst[1] = make_float4(t2x, t2y, t2z, sp.opacity[i]);
+        dst[2] = make_float4(mx, my, sp.color[i], sp.color[N + i]);
+        dst[3] = make_float4(sp.color[2 * N + i], __int_as_float(sp.radius[i]), fmaf(-mx, t2z, sp.T[2 * N + i]),
+                             fmaf(-my, t2z, sp.T[5 * N + i]));
+    });
 }
 
 constexpr int kAccStride2D = 17;   // floats between the LDS accumulators of consecutive surfels of a batch (odd)
@@ -807,15 +792,14 @@ hipError_t launch_preprocess2d_bwd_records(const Scene2DDev& sc, const CamDev& c
 hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s)
 {
     if (sp.n == 0) return launch_bin_begin(L, ws, s);      // nothing to count: only the cleared status words and ranges
-    hipError_t e = hipSuccess;
+    hipError_t e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
+    if (e != hipSuccess) return e;
     {
-        e = launch_count_visible(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
+        ProfScope prof(kKDuplicate, s);
+        hipLaunchKernelGGL(k_pack_dup2d, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam, bin_arrays(L, ws),
+                           reinterpret_cast<Packed2D*>(ws + L.off_packed));
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
-        ProfScope prof(kKCountPack, s);
-        hipLaunchKernelGGL(k_count_pack2d, dim3((unsigned)((sp.n + 255) / 256)), dim3(256), 0, s, sp, cam,
-                           reinterpret_cast<const uint32_t*>(ws + L.off_vis_block), reinterpret_cast<const uint32_t*>(ws + L.off_touched), reinterpret_cast<Packed2D*>(ws + L.off_packed),
-                           reinterpret_cast<uint32_t*>(ws + L.off_dkey0), reinterpret_cast<uint32_t*>(ws + L.off_dval0),
-                           reinterpret_cast<uint32_t*>(ws + L.off_depth_bits));
     }
     return launch_bin_finish(BinInput{sp.n, sp.mean2d, sp.radius}, cam, L, ws, s);
 }
@@ -846,7 +830,7 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
     }
     if (n > 0) {
         ProfScope prof(kKGather, s);
-        const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_dval0);
+        const uint32_t* order = reinterpret_cast<const uint32_t*>(ws + L.off_order);
         const uint32_t* offsets = reinterpret_cast<const uint32_t*>(ws + L.off_offsets);
         const uint32_t* chunk_rank = reinterpret_cast<const uint32_t*>(ws + L.off_chunk_rank);
         float* carry = reinterpret_cast<float*>(ws + L.off_carry);

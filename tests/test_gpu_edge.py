@@ -57,6 +57,30 @@ def test_lists_all_equal_depth_one_tile():
     assert np.array_equal(got["keys"], ref["keys"])
 
 
+@pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 257, 600, 1022, 1023, 2048, 2049, 4097, 6016, 6017, 9000])
+@pytest.mark.parametrize("kind", ["narrow", "wide", "two_values"])
+def test_one_crowded_tile_depth_order(n, kind):
+    """Every splat in one tile: the list's depth order is made by one workgroup - by counting up to 256 entries, in LDS up
+    to 2048, through the global scratch arrays beyond - over the bit positions in which the depths differ: depths from a
+    narrow band (few differing bits), from many octaves (all exponent bits differ), and only two distinct values; a
+    third of the entries tied in every case, so that the order among equals (point index) is exercised too."""
+    rng = np.random.default_rng(n * 7 + len(kind))
+    st = dict(mean2d=rng.uniform(17.0, 30.0, (n, 2)).astype(np.float32), conic=np.tile([0.1, 0, 0.1], (n, 1)),
+              opacity=np.full(n, 0.01), color=np.zeros((n, 3)), radius=np.full(n, 1, dtype=np.int32))
+    if kind == "narrow":
+        depth = rng.uniform(7.0, 7.01, n).astype(np.float32)
+    elif kind == "wide":
+        depth = np.exp(rng.uniform(np.log(1e-3), np.log(1e9), n)).astype(np.float32)
+    else:
+        depth = rng.choice(np.array([2.5, 2.5000002], dtype=np.float32), n)
+    depth[rng.integers(0, n, n // 3)] = depth[0]
+    got, ref, _ = _lists_case(st, depth, 48, 48)
+    assert ref["ranges"][4].tolist() == [0, n]             # tile (1, 1) of the 3 x 3 grid holds them all
+    assert np.array_equal(got["vals"], ref["vals"])
+    assert np.array_equal(got["keys"], ref["keys"])
+    assert np.array_equal(got["ranges"], ref["ranges"])
+
+
 def test_lists_empty_single_and_adversarial_bits():
     # nothing visible
     st = dict(mean2d=np.zeros((7, 2)), conic=np.zeros((7, 3)), opacity=np.zeros(7), color=np.zeros((7, 3)), radius=np.zeros(7, dtype=np.int32))
