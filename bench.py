@@ -7,8 +7,16 @@ A step = one pass of the whole per-view path over one synthetic view, inputs res
 on the 1M-Gaussian / SH degree 3 / 1920x1080 configuration (fwd+bwd views per second).  dL/dimage is the gradient of
 a mean-L1 loss against a seeded target, computed once from the warm-up image (the loss itself is harness, not path).
 
-Prints ONE JSON line with the contract fields plus `roofline` (dominant kernel, timed live with HIP events recorded
-on the launch stream inside the timed region) and `cpu_baseline` (the CPU oracle timed on the host cores).
+Prints ONE JSON line with the contract fields plus
+  `roofline`       dominant kernel, timed live with HIP events recorded on the launch stream inside the timed region;
+                   flop fraction of the fp32 vector peak and, from the committed shader-counter profile, the share of
+                   the vector ALU's issue capacity its instructions take (`valu_issue_frac`);
+  `cpu_baseline`   the CPU oracle timed on the host cores on one full view;
+  `step_ms`        median / min / max of single steps (one event pair per step, after the timed region);
+  `measured_peaks` plain-FMA rate of this box (a child process run before the GPU is touched) and a device copy;
+  `configs`        the other benchmark configurations, each a short timed loop of its own: the tiny scene, the batch of 16
+                   views, the 8M-point street scene as a batch of 8 views at 4K with point-group culling, 2D surfels -
+                   with throughput, dominant kernel, pairs / cull rate, staged parity and the oracle's time on one view.
 """
 import argparse
 import json
@@ -59,10 +67,121 @@ def profiled_traffic(kernel):
     return None
 
 
-def run_batched(args):
-    """Not the headline metric: the B views of a batch of the mid scene, preprocessing and its backward done for the
-    whole batch in one pass each (pbdr_preprocess_batch, pbdr_preprocess_bwd_batch), next to the same work done with
-    the per-view calls. One step = one batch; value = views per second."""
+def profiled_valu_cycles(kernel):
+    """Vector-ALU issue cycles per launch of `kernel`, summed over the chip's SIMDs, from the committed shader-counter
+    summary of the benchmark workload: SQ_INSTS_VALU wavefront instructions at the cost of a plain instruction plus the
+    extra cost of the transcendental ones (SQ_INSTS_VALU_TRANS_F32), both costs calibrated on the FMA / exp micro-benchmark
+    (profiles/valu_issue_pmc_calibration.txt: a kernel of plain FMAs that keeps every SIMD issuing reads one SQ_INSTS_VALU
+    per instruction). DPP and row-swap instructions cost more than a plain one too and have no counter of their own, so
+    this is a lower bound of the kernel's share of the issue capacity. None if a file or the kernel is missing."""
+    try:
+        cal = open(os.path.join(ROOT, "profiles", "valu_issue_pmc_calibration.txt")).read().splitlines()
+        rows = open(os.path.join(ROOT, "profiles", "bench_mid_pmc_sq.txt")).read().splitlines()
+    except OSError:
+        return None
+    c_plain = c_trans = None
+    for ln in cal:
+        if ln.startswith("cycles_per_plain_inst="):
+            parts = dict(kv.split("=") for kv in ln.split())
+            c_plain, c_trans = float(parts["cycles_per_plain_inst"]), float(parts["cycles_per_trans_inst"])
+    header = None
+    for ln in rows:
+        cols = ln.split("\t")
+        if cols[0] == "kernel":
+            header = cols
+        elif header and len(cols) == len(header) and cols[0].split("::")[-1].split("<")[0] == kernel and c_plain:
+            rec = dict(zip(header, cols))
+            return float(rec["SQ_INSTS_VALU"]) * c_plain + float(rec["SQ_INSTS_VALU_TRANS_F32"]) * (c_trans - c_plain)
+    return None
+
+
+def measured_peaks():
+    """The instruction-issue micro-benchmark as a child process, before this process touches the GPU: the rate of
+    independent plain v_fma_f32 this box reaches (the fp32 vector peak reachable without packed math)."""
+    import re
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2512_20017_amd", "ubench", "valu_issue.bin")
+    if not os.path.exists(exe):
+        try:
+            from paper_2512_20017_amd import build as hip_build
+            hip_build.build_ubench()
+        except Exception:
+            return None
+    try:
+        txt = subprocess.run([exe], capture_output=True, text=True, timeout=120).stdout
+    except Exception:
+        return None
+    m = re.search(r"plain v_fma_f32[^:]*: ([0-9.]+) TFLOP/s, ([0-9.]+) cycles", txt)
+    if not m:
+        return None
+    out = dict(fma_tflops=float(m.group(1)), cycles_per_plain_inst=float(m.group(2)))
+    for key, pat in (("cycles_per_dpp_add", r"v_add_f32_dpp\s+([0-9.]+)"), ("cycles_per_exp", r"v_exp_f32\s+([0-9.]+)"),
+                     ("cycles_per_row_swap", r"v_permlane16_swap_b32\s+([0-9.]+)")):
+        mm = re.search(pat, txt)
+        if mm:
+            out[key] = float(mm.group(1))
+    return out
+
+
+def per_step_times(torch, step, count):
+    """One event pair per step on the current stream; returns the steps' durations in ms."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(count)]
+    torch.cuda.synchronize()
+    for e0, e1 in ev:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    return [e0.elapsed_time(e1) for e0, e1 in ev]
+
+
+def spread(ms_list):
+    xs = sorted(ms_list)
+    return dict(median_ms=xs[len(xs) // 2], min_ms=xs[0], max_ms=xs[-1], steps=len(xs))
+
+
+def oracle_view_check(np, oracle, sc, cam, sp_np, image_chw, P_gpu, bg, dL_chw, surfels=False, time_full=True):
+    """The CPU oracle on one view: (1) timed from raw parameters through forward and backward on the host cores; (2) its
+    compositing fed with the GPU's own fp32 splat state, for the staged parity figures over the whole image."""
+    import time as _t
+    W, H = cam["width"], cam["height"]
+    keys = ("mean2d", "T", "opacity", "color") if surfels else ("mean2d", "conic", "opacity", "color")
+    o_pre, o_fwd, o_bwd, o_pbwd = ((oracle.preprocess2d, oracle.render_fwd2d, oracle.render_bwd2d, oracle.preprocess_bwd2d)
+                                   if surfels else
+                                   (oracle.preprocess, oracle.render_fwd, oracle.render_bwd, oracle.preprocess_bwd))
+    cpu = None
+    if time_full:
+        t0 = _t.perf_counter()
+        o_sp = o_pre(sc, cam)
+        st = {k: o_sp[k].astype(np.float32).astype(np.float64) for k in keys}
+        st["radius"] = o_sp["radius"]
+        lists = oracle.bin_sort(st["mean2d"], st["radius"], o_sp["depth"].astype(np.float32), W, H)
+        o_fwd(st, lists, W, H, bg)
+        G = dL_chw.permute(1, 2, 0).contiguous().cpu().numpy().astype(np.float64)
+        o_b = o_bwd(st, lists, W, H, bg, G)
+        o_pbwd(sc, cam, o_b)
+        t1 = _t.perf_counter()
+        cpu = dict(value=1.0 / (t1 - t0), unit="views/s", cores=oracle.num_threads(), kind="oracle",
+                   sample="1 full view (forward + backward) of the same workload, fp64, OpenMP", seconds=t1 - t0)
+    stg = {k: sp_np[k].astype(np.float64) for k in keys}
+    stg["radius"] = sp_np["radius"]
+    lg = oracle.bin_sort(stg["mean2d"], stg["radius"], sp_np["depth"], W, H)
+    rf = o_fwd(stg, lg, W, H, bg)
+    got = image_chw.permute(1, 2, 0).cpu().numpy()
+    ok = rf["fragile"] == 0
+    parity = dict(max_abs_image_err=float(np.abs(got - rf["image"])[ok].max()), fragile_pixels=int((~ok).sum()),
+                  pairs_oracle=int(lg["P"]), pairs_gpu=int(P_gpu), examined_oracle=int(rf["n_eval"]),
+                  blended_oracle=int(rf["n_blend"]))
+    return cpu, parity, rf
+
+
+def bench_batch(args, workload, nb, group, streams, steps, with_oracle=True):
+    """The B views of a batch (Alg. 1 lines 2-4 and 21-24 for a batch): preprocessing and its backward for the whole batch in
+    one pass over the points each (pbdr_preprocess_batch, pbdr_preprocess_bwd_batch, optionally with point-group culling),
+    the views rendered between them on `streams` streams; next to the same work with the per-view calls. One step = one
+    batch; views_per_s counts views. workload: "mid" (1M points, 16 cameras on a sphere, 1080p) or "large" (8M points,
+    8 street-level cameras at 4K)."""
+    import numpy as np
     import torch
 
     from paper_2512_20017_amd import binding as B
@@ -71,9 +190,15 @@ def run_batched(args):
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.lib()
-    nb = args.batch_views
-    sc = synth.scene_mid(args.seed)
-    cams = synth.cameras_sphere()[:nb]
+    if workload == "large":
+        sc = synth.scene_large(args.seed)
+        cams = synth.cameras_street(args.seed)[:nb]
+        wl = f"large, batched: 8M Gaussians, SH degree 3, street-level cameras 0..{nb - 1} of 8 at 3840x2160"
+    else:
+        sc = synth.scene_mid(args.seed)
+        cams = synth.cameras_sphere()[:nb]
+        wl = f"batched: the mid scene (1M Gaussians, SH degree 3) from cameras 0..{nb - 1} of 16, 1920x1080"
+    nb = len(cams)
     n = int(sc["mean"].shape[0])
     W, H = cams[0]["width"], cams[0]["height"]
     bg = [0.0, 0.0, 0.0]
@@ -84,7 +209,6 @@ def run_batched(args):
     image = torch.empty((3, H, W), device="cuda")
     final_T = torch.empty((H, W), device="cuda")
     last_idx = torch.empty((H, W), dtype=torch.int32, device="cuda")
-    group = args.group_size
     bounds = keep = None
     if group > 0:
         ng = B.pbdr_group_count(n, group)
@@ -96,12 +220,13 @@ def run_batched(args):
     cap = max(min(16 * n, 32_000_000), 1 << 16)
     ws = B.alloc_workspace(n, W, H, cap)
     B.pbdr_preprocess_batch(scene, cams, splats, group, bounds, keep)
-    pairs = []
+    pairs, visible = [], []
     for v, cam in enumerate(cams):
         B.pbdr_render_fwd(splats[v], cam, bg, cap, image, final_T, last_idx, ws)
         P, over = B.pbdr_query_lists(ws, n, W, H, cap)
         assert not over
-        pairs.append(P)
+        pairs.append(int(P))
+        visible.append(int((splats[v].radius > 0).sum().item()))
     del ws
     cap = int(max(pairs) * 1.25) + 4096
     ws = B.alloc_workspace(n, W, H, cap)
@@ -110,7 +235,7 @@ def run_batched(args):
 
     # the views of a batch are independent between the two batched calls: they are rendered on `ns` streams, each with
     # its own workspace and outputs
-    ns = max(1, min(args.streams, nb))
+    ns = max(1, min(streams, nb))
     main = torch.cuda.current_stream()
     lanes = [dict(stream=torch.cuda.Stream(), ws=B.alloc_workspace(n, W, H, cap), image=torch.empty((3, H, W), device="cuda"),
                   final_T=torch.empty((H, W), device="cuda"), last_idx=torch.empty((H, W), dtype=torch.int32, device="cuda"))
@@ -149,7 +274,7 @@ def run_batched(args):
     names = B.profile_kernel_names()
     out = {}
     for label, step in (("batch_calls", step_batch), ("per_view_calls", step_per_view)):
-        for _ in range(max(args.warmup, 1)):
+        for _ in range(max(args.warmup, 1) if label == "batch_calls" else 1):
             step()
         torch.cuda.synchronize()
         B.pbdr_profile_begin((1 << len(names)) - 1, 64 * nb * 2)
@@ -162,21 +287,43 @@ def run_batched(args):
                 kern[name] = dict(ms_per_batch=ms, launches=cnt)
         B.pbdr_profile_end()
         torch.cuda.synchronize()
+        k_steps = steps if label == "batch_calls" else max(2, steps // 3)
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(k_steps):
             step()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        out[label] = dict(views_per_s=nb * args.steps / (t1 - t0), ms_per_batch=(t1 - t0) * 1e3 / args.steps,
-                          kernels={k: kern[k] for k in ("k_preprocess", "k_preprocess_bwd", "k_group_cull") if k in kern})
-    print(json.dumps({
-        "metric": "fwd+bwd views/sec at 1080p, 1M Gaussians, batch of views (not the headline)",
-        "value": out["batch_calls"]["views_per_s"], "unit": "views/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": out["batch_calls"]["ms_per_batch"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"batched: the mid scene from cameras 0..{nb - 1} of 16, 1920x1080", "views_per_batch": nb,
-                   "group_size": group, "render_streams": ns, "pairs_min": min(pairs), "pairs_max": max(pairs)},
-        "batch_calls": out["batch_calls"], "per_view_calls": out["per_view_calls"]}))
+        out[label] = dict(views_per_s=nb * k_steps / (t1 - t0), ms_per_batch=(t1 - t0) * 1e3 / k_steps, steps=k_steps,
+                          kernels={k: kern[k] for k in ("k_preprocess", "k_preprocess_bwd", "k_group_cull", "k_composite_fwd",
+                                                        "k_composite_bwd") if k in kern})
+        if label == "batch_calls":
+            out[label].update(spread(per_step_times(torch, step, max(5, min(20, steps)))))
+    res = {
+        "metric": "fwd+bwd views/sec, batch of views (not the headline)",
+        "value": out["batch_calls"]["views_per_s"], "unit": "views/s", "ms_per_view": out["batch_calls"]["ms_per_batch"] / nb,
+        "config": {"workload": wl, "n_gaussians": n, "width": W, "height": H, "views_per_batch": nb, "group_size": group,
+                   "render_streams": ns, "pairs_per_view": pairs, "visible_per_view": visible,
+                   "cull_rate": 1.0 - float(sum(visible)) / float(nb * n),
+                   "groups_kept": float(keep.float().mean().item()) if group > 0 else None},
+        "batch_calls": out["batch_calls"], "per_view_calls": out["per_view_calls"]}
+    if with_oracle:
+        import oracle
+        # the view with the most pairs, alone: the oracle timed on it, and the staged parity of its image
+        v = int(np.argmax(pairs))
+        B.pbdr_render_fwd(splats[v], cams[v], bg, cap, image, final_T, last_idx, ws)
+        torch.cuda.synchronize()
+        cpu, parity, _ = oracle_view_check(np, oracle, sc, cams[v], splats[v].to_numpy(), image, pairs[v], bg, dL)
+        res["cpu_baseline"] = cpu
+        res["parity"] = dict(parity, view=v)
+    return res
+
+
+def run_batched(args):
+    res = bench_batch(args, args.workload if args.workload in ("mid", "large") else "mid", args.batch_views, args.group_size,
+                      args.streams, args.steps, with_oracle=not args.no_cpu_baseline)
+    res.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["batch_calls"]["ms_per_batch"],
+                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"})
+    print(json.dumps(res))
 
 
 def main():
@@ -210,6 +357,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the leg that replays the step from a HIP graph")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-secondary", action="store_true", help="skip the other configurations after the headline")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the child process that measures the FMA issue rate")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -219,12 +368,55 @@ def main():
         sys.exit(2)
 
     if args.batch_views > 0:
-        assert args.batch_views <= 16 and args.workload == "mid"
+        assert args.batch_views <= 16 and args.workload in ("mid", "large")
         if args.steps == 50:
             args.steps = 10
         run_batched(args)
         return
 
+    # the micro-benchmark of the vector ALU's issue rate, as a child process, before this process touches the GPU
+    peaks = None if args.no_peaks else measured_peaks()
+    out = bench_view(args, args.workload, headline=True)
+    out["measured_peaks"] = dict(peaks or {}, device_copy_gbs=out.get("device_copy_gbs"))
+    if peaks and out["roofline"].get("bound") == "alu":
+        out["roofline"]["frac_of_measured_fma"] = out["roofline"]["achieved"] / peaks["fma_tflops"]
+    if args.workload == "mid" and not args.train_step and not args.no_secondary:
+        out["configs"] = secondary_configs(args)
+    print(json.dumps(out))
+
+
+def secondary_configs(args):
+    """The other benchmark configurations, each a short timed loop after the headline's timed region (their figures are
+    not `value`): the tiny scene, the batch of 16 views of the 1M scene, the 8 street-level 4K views of the 8M scene as a
+    batch with point-group culling, and the 2D surfel variant."""
+    import copy
+    import gc
+
+    import torch
+    res = {}
+
+    def pick(o):
+        keep = ("value", "unit", "ms_per_step", "step_ms", "config", "roofline", "cpu_baseline", "parity", "kernels")
+        return {k: o[k] for k in keep if k in o}
+
+    a = copy.copy(args)
+    a.streams, a.no_graph, a.train_step, a.group_size, a.separate_zero, a.splat_grads = 1, True, False, 0, False, False
+    a.steps, a.warmup = 200, 10
+    res["tiny"] = pick(bench_view(a, "tiny", headline=False))
+    gc.collect(); torch.cuda.empty_cache()
+    a.steps, a.warmup = 20, 3
+    res["surfels"] = pick(bench_view(a, "surfels", headline=False))
+    gc.collect(); torch.cuda.empty_cache()
+    a.warmup = 2
+    res["batch16"] = bench_batch(a, "mid", 16, 0, 3, 4, with_oracle=False)      # the oracle's time on one such view: cpu_baseline above
+    gc.collect(); torch.cuda.empty_cache()
+    res["large_batch8"] = bench_batch(a, "large", 8, 1024, 3, 4, with_oracle=not args.no_cpu_baseline)
+    gc.collect(); torch.cuda.empty_cache()
+    return res
+
+
+def bench_view(args, workload, headline):
+    """One view per step of `workload` through the whole path; returns the result record (the caller prints it)."""
     import numpy as np
     import torch
 
@@ -235,15 +427,15 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
 
-    if args.workload == "mid":
+    if workload == "mid":
         sc = synth.scene_mid(args.seed)
         cam = synth.cameras_sphere()[0]
         wl = "mid: 1M Gaussians, SH degree 3, 1920x1080, camera 0 of 16 on a radius-15 sphere"
-    elif args.workload == "large":
+    elif workload == "large":
         sc = synth.scene_large(args.seed)
         cam = synth.cameras_street(args.seed)[2]
         wl = "large: 8M Gaussians, SH degree 3, 3840x2160, street-level camera 2 (far plane and radius clip active)"
-    elif args.workload == "surfels":
+    elif workload == "surfels":
         sc = synth.scene_surfels(args.seed)
         cam = synth.cameras_sphere()[0]
         wl = "surfels: 1M 2D Gaussian disks, SH degree 3, 1920x1080, camera 0 of 16 on a radius-15 sphere"
@@ -251,7 +443,7 @@ def main():
         sc = synth.scene_tiny(args.seed)
         cam = synth.camera_tiny()
         wl = "tiny: 4096 Gaussians, SH degree 0, 128x128"
-    surfels = args.workload == "surfels"
+    surfels = workload == "surfels"
     n = int(sc["mean"].shape[0])
     W, H = cam["width"], cam["height"]
     bg = [0.0, 0.0, 0.0]
@@ -349,7 +541,7 @@ def main():
 
     # a plain device copy as the yardstick for the HBM-bound kernels: 256 MiB read + 256 MiB written, timed with events
     copy_gbs = None
-    if not args.train_step:
+    if headline and not args.train_step:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -403,6 +595,8 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     views_per_s = args.steps / (t1 - t0)
     dom_avg_ms = dom_ms / max(dom_cnt, 1)
+    # the spread of single steps: one event pair per step, outside the kernels (>= 20 steps), after the timed region
+    step_ms = spread(per_step_times(torch, step, max(20, min(args.steps, 100))))
 
     # ---- roofline of the dominant kernel
     K = (scene.sh_degree + 1) ** 2
@@ -445,8 +639,18 @@ def main():
     else:
         roofline = dict(kernel=dominant, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None,
                         traffic=None, avg_launch_ms=dom_avg_ms, launches_timed=dom_cnt)
-    if args.workload == "mid":
+    if workload == "mid":
         roofline["traffic"] = profiled_traffic(dominant)
+        # share of the vector ALU's issue capacity (1024 SIMDs x 2.4 GHz x duration) that the compositing kernels' counted
+        # instructions take, next to the flop fraction: counters of the committed profile, durations of this run
+        issue = {}
+        for kname in ("k_composite_fwd", "k_composite_bwd"):
+            cyc = profiled_valu_cycles(kname)
+            if cyc and kname in per_kernel:
+                t_k = dom_avg_ms if kname == dominant else per_kernel[kname]["ms_per_step"] / per_kernel[kname]["launches_per_step"]
+                issue[kname] = cyc / (1024 * 2.4e9 * t_k * 1e-3)
+        roofline["valu_issue_frac"] = issue.get(dominant)
+        roofline["valu_issue_frac_by_kernel"] = issue
     for name, rec in per_kernel.items():
         t = rec["ms_per_step"] * 1e-3
         if name in alu_flops:
@@ -459,34 +663,9 @@ def main():
     parity = None
     if not args.no_cpu_baseline:
         import oracle
-        sp = splats.to_numpy()
-        keys = ("mean2d", "T", "opacity", "color") if surfels else ("mean2d", "conic", "opacity", "color")
-        o_pre, o_fwd, o_bwd, o_pbwd = ((oracle.preprocess2d, oracle.render_fwd2d, oracle.render_bwd2d, oracle.preprocess_bwd2d)
-                                       if surfels else
-                                       (oracle.preprocess, oracle.render_fwd, oracle.render_bwd, oracle.preprocess_bwd))
-        t_c0 = time.perf_counter()
-        o_sp = o_pre(sc, cam)
-        st = {k: o_sp[k].astype(np.float32).astype(np.float64) for k in keys}
-        st["radius"] = o_sp["radius"]
-        lists = oracle.bin_sort(st["mean2d"], st["radius"], o_sp["depth"].astype(np.float32), W, H)
-        o_f = o_fwd(st, lists, W, H, bg)
-        G = dL.permute(1, 2, 0).contiguous().cpu().numpy().astype(np.float64)
-        o_b = o_bwd(st, lists, W, H, bg, G)
-        o_pbwd(sc, cam, o_b)
-        t_c1 = time.perf_counter()
-        cpu = dict(value=1.0 / (t_c1 - t_c0), unit="views/s", cores=oracle.num_threads(), kind="oracle",
-                   sample="1 full view (forward + backward) of the same workload, fp64, OpenMP",
-                   seconds=t_c1 - t_c0)
-        # staged parity at full size: oracle compositing fed with the GPU's own fp32 splats
-        stg = {k: sp[k].astype(np.float64) for k in keys}
-        stg["radius"] = sp["radius"]
-        lg = oracle.bin_sort(stg["mean2d"], stg["radius"], sp["depth"], W, H)
-        rf = o_fwd(stg, lg, W, H, bg)
-        got = image.permute(1, 2, 0).cpu().numpy()
+        cpu, parity, rf = oracle_view_check(np, oracle, sc, cam, splats.to_numpy(), image, P, bg, dL, surfels=surfels)
         ok = rf["fragile"] == 0
-        parity = dict(max_abs_image_err=float(np.abs(got - rf["image"])[ok].max()), fragile_pixels=int((~ok).sum()),
-                      pairs_oracle=int(lg["P"]), pairs_gpu=int(P), examined_oracle=int(rf["n_eval"]),
-                      examined_gpu=int(examined), blended_oracle=int(rf["n_blend"]), blended_gpu=int(blended),
+        parity.update(examined_gpu=int(examined), blended_gpu=int(blended),
                       last_idx_mismatch=int((last_idx.cpu().numpy().astype(np.uint32) != rf["last_idx"])[ok].sum()))
 
     # ---- the same step with several views in flight (not `value`): every view has its own splat state, workspace and
@@ -494,7 +673,7 @@ def main():
     # another's compositing kernels. Per-kernel durations stretch under sharing, which is why the roofline above is
     # taken with one view in flight.
     overlapped = None
-    if args.streams > 1 and not args.train_step and not surfels:
+    if headline and args.streams > 1 and not args.train_step and not surfels:
         ctxs = []
         for _ in range(args.streams):
             ctxs.append(dict(stream=torch.cuda.Stream(), splats=B.Splats.empty(n), g2=B.SplatGrads.empty(n), grads=scene.zeros_like(),
@@ -530,7 +709,7 @@ def main():
     # ---- the same step recorded once into a HIP graph and replayed (not `value`): the calls are kernel launches on the
     # caller's stream and nothing else, so the step can be captured; one graph launch then stands for its ~45 launches
     graph_replay = None
-    if not args.no_graph and not args.train_step:
+    if headline and not args.no_graph and not args.train_step:
         graph = torch.cuda.CUDAGraph()
         before = grads.flat.clone() if hasattr(grads, "flat") else None
         with torch.cuda.graph(graph):
@@ -553,9 +732,9 @@ def main():
         "metric": "training iterations/sec (splat, render, L1 loss, backward, selective Adam), one view" if args.train_step else
                   {"mid": "fwd+bwd views/sec at 1080p, 1M Gaussians",
                    "surfels": "fwd+bwd views/sec at 1080p, 1M 2D Gaussian surfels",
-                   "large": "fwd+bwd views/sec at 4K, 8M Gaussians, street view"}.get(args.workload, "fwd+bwd views/sec"),
+                   "large": "fwd+bwd views/sec at 4K, 8M Gaussians, street view"}.get(workload, "fwd+bwd views/sec"),
         "value": views_per_s, "unit": "views/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "step_ms": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl, "n_gaussians": n, "width": W, "height": H, "sh_degree": scene.sh_degree,
                    "visible": n_vis, "tile_pairs": int(P), "pairs_examined_fwd": int(examined),
@@ -570,7 +749,7 @@ def main():
         "overlapped": overlapped,
         "graph_replay": graph_replay,
     }
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":

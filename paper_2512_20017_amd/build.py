@@ -21,12 +21,12 @@ def build(verbose: bool = False, extra=()) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    build_ubench(verbose)
     return LIB
 
 
 def build_ubench(verbose: bool = False) -> str:
-    """The instruction-issue micro-benchmark behind the ALU roofline figures (a stand-alone program, not in the library)."""
+    """The instruction-issue micro-benchmark behind the ALU roofline figures: a stand-alone program, not part of the
+    library and not built by build(); bench.py builds it on demand (python paper_2512_20017_amd/build.py --ubench)."""
     src = os.path.join(HERE, "ubench", "valu_issue.hip")
     exe = os.path.join(HERE, "ubench", "valu_issue.bin")
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -38,4 +38,7 @@ def build_ubench(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, extra=sys.argv[1:]))
+    if "--ubench" in sys.argv[1:]:
+        print(build_ubench(verbose=True))
+    else:
+        print(build(verbose=True, extra=sys.argv[1:]))
