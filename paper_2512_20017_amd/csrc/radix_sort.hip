@@ -227,19 +227,21 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 //     digits over the bit positions in which the list's keys differ at all (depths of one tile share sign, most
 //     exponent bits and often more). Keys and positions live in registers in list order; a pass scatters them into the
 //     wavefront's 4 KB of LDS and reads them back in the new order;
-//   - up to 6144 entries: the same passes by a whole workgroup, two barriers per pass. Only the permutation (16-bit
-//     positions) is in LDS; the keys stay in the global scratch array (the spent tile ids) and are fetched through it;
+//   - up to 6016 entries: the same passes by a whole workgroup, two barriers per pass. What moves is the permutation
+//     (16-bit positions, two copies in LDS); the keys stay where they are, in incoming order - in LDS for lists of up
+//     to 2048 entries, in the global scratch array (the spent tile ids) beyond - and are fetched through it;
 //   - longer lists: the passes in chunks of 2048 through the global scratch arrays, whole-list digit counts first,
 //     then chunk by chunk in order.
-// 20 KB of LDS per workgroup, so that eight workgroups share a compute unit: the work is a chain of dependent LDS and
-// cross-lane steps per list, and what hides it is other lists in flight.
+// 32 KB of LDS and at most 100 registers, so that five workgroups share a compute unit: the work is a chain of dependent
+// LDS and cross-lane steps per list, and what hides it is other lists in flight.
 // A pass ranks its entries per wavefront and round of 64 by ballots (lanes with the same digit find each other), the
 // first lane of each group adds the group's size to the digit's counter in LDS and gets back how many entries of that
 // digit came before (earlier rounds of the wavefront: LDS executes a wavefront's operations in order), and hands that
 // to its group through the LDS crossbar: equal digits keep their incoming order.
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveListMax = 512;                     // a wavefront's own list holds fewer than kWaveListMax - 1 entries (8 rounds)
-constexpr int kWgListMax = 6144;                      // a workgroup's list with its permutation in LDS (24 rounds per wavefront)
+constexpr int kWgKeyMax = 2048;                       // a workgroup's list with its keys in LDS (8 rounds per wavefront)
+constexpr int kWgListMax = 6016;                      // a workgroup's list with its permutation in LDS (24 rounds per wavefront)
 constexpr int kListChunk = 2048;                      // entries per chunk of a list that goes through global memory
 constexpr int kListRounds = kListChunk / 256;
 
@@ -249,14 +251,17 @@ struct WaveSortLds {      // a wavefront's share of the LDS when it sorts a list
     uint32_t hist[256];
 };
 struct WgSortLds {        // the workgroup's LDS when it sorts one list together
-    uint16_t idx[kWgListMax];                         // the permutation: idx[i] = incoming position of the entry now at i
+    union {
+        struct { uint32_t key[kWgKeyMax]; uint16_t idx[2][kWgKeyMax]; } a;      // keys in incoming order + the permutation, twice
+        struct { uint16_t idx[2][kWgListMax]; } b;                              // the permutation alone
+    } u;
     uint32_t cnt[4][256];                             // per wavefront and digit: entries in the wavefront's part of the list
     uint32_t start[4][256];                           // per wavefront and digit: where its first entry of that digit goes
     uint32_t scan[4];
     uint32_t mask;
 };
 union ListSortLds { WgSortLds wg; WaveSortLds wave[4]; };
-static_assert(sizeof(ListSortLds) <= 20 * 1024 + 64, "eight workgroups per compute unit");
+static_assert(sizeof(ListSortLds) <= 160 * 1024 / 5, "five workgroups per compute unit");
 
 // bit range [lo, hi] in which the keys differ -> number of 8-bit passes and the shift of pass p (the topmost digit
 // may reach past bit hi into bits all keys share; it never reaches past bit 31)
@@ -268,16 +273,29 @@ __device__ __forceinline__ int list_passes(uint32_t diff, int& lo)
 }
 __device__ __forceinline__ int list_shift(int lo, int p) { return min(lo + 8 * p, 24); }
 
-// Entries of this wavefront with the same digit as this lane's that come before it: earlier rounds (through the digit's
-// counter in `hist`, a row no other wavefront touches) plus lower lanes of this round.
+// Entries of this wavefront with the same 8-bit digit as this lane's that come before it: earlier rounds (through the
+// digit's counter in `hist`, a row no other wavefront touches) plus lower lanes of this round. The lanes that share the
+// digit are found bit by bit: a lane differs from this one if, for some bit, its bit (one ballot per bit) is not this
+// lane's bit (sign-extended to a mask); both halves of the 64-lane sets are kept in 32-bit registers.
 __device__ __forceinline__ uint32_t digit_prefix(uint32_t* hist, uint32_t digit, bool valid)
 {
     const int lane = threadIdx.x & 63;
-    const uint64_t peers = digit_peers<8>(digit, valid);
-    const uint32_t rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+    uint32_t dlo = 0u, dhi = 0u;
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+        const uint32_t ext = (uint32_t)__builtin_amdgcn_sbfe((int)digit, bit, 1);      // 0 or ~0
+        const uint64_t m = __ballot(ext != 0u);
+        dlo |= (uint32_t)m ^ ext;
+        dhi |= (uint32_t)(m >> 32) ^ ext;
+    }
+    const uint64_t vm = __ballot(valid);
+    const uint32_t plo = ~dlo & (uint32_t)vm, phi = ~dhi & (uint32_t)(vm >> 32);       // valid lanes with this lane's digit
+    // lanes below this one among them
+    const uint32_t below_lo = lane < 32 ? (1u << lane) - 1u : ~0u, below_hi = lane < 32 ? 0u : (1u << (lane - 32)) - 1u;
+    const uint32_t rank = (uint32_t)__popc(plo & below_lo) + (uint32_t)__popc(phi & below_hi);
     uint32_t before = 0u;
-    if (valid && rank == 0u) before = atomicAdd(&hist[digit], (uint32_t)__popcll(peers));
-    const int leader = valid ? __builtin_ctzll(peers) : lane;
+    if (valid && rank == 0u) before = atomicAdd(&hist[digit], (uint32_t)__popc(plo) + (uint32_t)__popc(phi));
+    const int leader = !valid ? lane : (plo ? __builtin_ctz(plo) : 32 + __builtin_ctz(phi));
     before = (uint32_t)__builtin_amdgcn_ds_bpermute(leader << 2, (int)before);
     return before + rank;
 }
@@ -344,8 +362,7 @@ __device__ __forceinline__ void wave_sort_list(WaveSortLds& W, uint32_t L, const
     if (diff == 0u) return;                        // one depth throughout: point order is the order
     int lo;
     const int passes = list_passes(diff, lo);
-    for (int p = 0; p < passes; ++p) {
-        const int shift = list_shift(lo, p);
+    auto one_pass = [&](int shift) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) W.hist[q * 64 + lane] = 0u;
         wave_lds_sync();
@@ -369,7 +386,8 @@ __device__ __forceinline__ void wave_sort_list(WaveSortLds& W, uint32_t L, const
             if (r < nr && r * 64u + lane < L) { key[r] = W.key[r * 64u + lane]; id[r] = W.idx[r * 64u + lane]; }
         }
         wave_lds_sync();      // (the next pass, or the next list of this wavefront, writes the buffer again)
-    }
+    };
+    for (int p = 0; p < passes; ++p) one_pass(list_shift(lo, p));
     // the point indices, through the sorted positions: every entry is fetched before the first is stored
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -381,12 +399,17 @@ __device__ __forceinline__ void wave_sort_list(WaveSortLds& W, uint32_t L, const
         if (r < nr && r * 64u + lane < L) vals[r * 64u + lane] = key[r];
 }
 
-// A workgroup sorts the list vals[0 .. L), L <= kWgListMax. keys: L words of global scratch.
+// A workgroup sorts the list vals[0 .. L). kKeysInLds: L <= kWgKeyMax and the keys are kept in LDS; else L <= kWgListMax
+// and they are kept in `keys`, L words of global scratch. The permutation idx[c][i] = incoming position of the entry now
+// at i goes back and forth between its two copies in LDS.
+template <bool kKeysInLds>
 __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uint32_t* __restrict__ depth_bits,
                                              uint32_t* __restrict__ vals, uint32_t* __restrict__ keys)
 {
-    constexpr int R = kWgListMax / 256;
+    constexpr int R = ((kKeysInLds ? kWgKeyMax : kWgListMax) + 255) / 256;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint16_t* idx0 = kKeysInLds ? S.u.a.idx[0] : S.u.b.idx[0];
+    uint16_t* idx1 = kKeysInLds ? S.u.a.idx[1] : S.u.b.idx[1];
     // keys of the list, in incoming order, and the bit positions in which they differ
     uint32_t diff = 0u;
     const uint32_t k0 = depth_bits[vals[0]];
@@ -406,7 +429,11 @@ __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uin
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint32_t i = i0 + r * 256u + threadIdx.x;
-            if (i < L) { diff |= t[r] ^ k0; keys[i] = t[r]; S.idx[i] = (uint16_t)i; }
+            if (i < L) {
+                diff |= t[r] ^ k0;
+                if (kKeysInLds) S.u.a.key[i] = t[r]; else keys[i] = t[r];
+                idx0[i] = (uint16_t)i;
+            }
         }
     }
 #pragma unroll
@@ -422,26 +449,34 @@ __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uin
     const uint32_t per_wave = ((L + 255u) / 256u) * 64u;
     const int nr = (int)(per_wave / 64u);
     const uint32_t wb = wave * per_wave, we = min(L, wb + per_wave);
-    uint32_t ent[R];      // this lane's entries of the current order: incoming position | (entries of its digit before it) << 16
-    for (int p = 0; p < passes; ++p) {
-        const int shift = list_shift(lo, p);
+    uint16_t* src = idx0;
+    uint16_t* dst = idx1;
+    auto one_pass = [&](int shift) {
         // (this wavefront's count row was last read by the others before the barrier that ended the previous pass)
 #pragma unroll
         for (int q = 0; q < 4; ++q) S.cnt[wave][q * 64 + lane] = 0u;
         wave_lds_sync();
-        uint32_t k[R];
+        uint32_t dp[R];      // per entry of this lane: digit | (entries of that digit before it in this wavefront's part) << 8
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (r < nr) {
-                const uint32_t i = wb + r * 64u + lane;
-                ent[r] = i < we ? S.idx[i] : 0u;
-                k[r] = i < we ? keys[ent[r]] : 0u;
+        for (int r0 = 0; r0 < R; r0 += 8) {       // eight key fetches in flight at a time
+            if (r0 >= nr) break;
+            uint32_t k[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t i = wb + (r0 + j) * 64u + lane;
+                k[j] = 0u;
+                if (r0 + j < nr && i < we) k[j] = kKeysInLds ? S.u.a.key[src[i]] : keys[src[i]];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (r0 + j < nr) {
+                    const uint32_t digit = (k[j] >> shift) & 255u;
+                    const uint32_t v = digit | (digit_prefix(S.cnt[wave], digit, wb + (r0 + j) * 64u + lane < we) << 8);
+                    if (r0 + j < R) dp[r0 + j] = v;
+                }
             }
         }
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (r < nr) ent[r] |= digit_prefix(S.cnt[wave], (k[r] >> shift) & 255u, wb + r * 64u + lane < we) << 16;
-        __syncthreads();      // every wavefront has read its part of the permutation and counted
+        __syncthreads();      // every wavefront has counted
         {   // every wavefront works out where its own entries of each digit go: digits before, then the wavefronts before it
             uint32_t mine[4], tot4 = 0u;
 #pragma unroll
@@ -465,23 +500,26 @@ __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uin
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (r < nr && wb + r * 64u + lane < we) {
-                const uint32_t pos = min(S.start[wave][(k[r] >> shift) & 255u] + (ent[r] >> 16), L - 1u);
-                S.idx[pos] = (uint16_t)(ent[r] & 0xffffu);
+                const uint32_t pos = min(S.start[wave][dp[r] & 255u] + (dp[r] >> 8), L - 1u);
+                dst[pos] = src[wb + r * 64u + lane];
             }
         }
-        __syncthreads();
-    }
+        __syncthreads();      // the pass is written; the other copy of the permutation may be overwritten
+        uint16_t* t = src; src = dst; dst = t;
+    };
+    for (int p = 0; p < passes; ++p) one_pass(list_shift(lo, p));
     // the point indices, through the sorted positions: every entry is fetched before the first is stored
+    uint32_t out[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t i = r * 256u + threadIdx.x;
-        if (i < L) ent[r] = vals[S.idx[i]];
+        out[r] = i < L ? vals[src[i]] : 0u;
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t i = r * 256u + threadIdx.x;
-        if (i < L) vals[i] = ent[r];
+        if (i < L) vals[i] = out[r];
     }
 }
 
@@ -567,17 +605,30 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t* base, uin
     }
 }
 
-__global__ __launch_bounds__(256) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
-                                                         uint32_t ntiles, const uint32_t* __restrict__ status,
-                                                         const uint32_t* __restrict__ depth_bits, uint32_t cap,
-                                                         uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
-                                                         uint32_t* __restrict__ keysB, uint32_t* __restrict__ valsB)
+#ifdef PBDR_EXP_TIMING
+__device__ unsigned long long g_dbg[4 * 65536];
+extern "C" int pbdr_dbg_fetch(unsigned long long* host, int count)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(unsigned long long) * (size_t)count);
+}
+#define DBG_BEGIN const unsigned long long dbg_t0 = wall_clock64();
+#define DBG_END(len) if ((threadIdx.x & 63) == 0) { const size_t q = ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4; if (q + 3 < 4 * 65536) { g_dbg[q] = (len); g_dbg[q + 1] = dbg_t0; g_dbg[q + 2] = wall_clock64(); g_dbg[q + 3] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)); } }
+#else
+#define DBG_BEGIN
+#define DBG_END(len)
+#endif
+__global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+                                                            uint32_t ntiles, const uint32_t* __restrict__ status,
+                                                            const uint32_t* __restrict__ depth_bits, uint32_t cap,
+                                                            uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
+                                                            uint32_t* __restrict__ keysB, uint32_t* __restrict__ valsB)
 {
     __shared__ ListSortLds U;
     // tile_order lists the tiles longest first; its first `nbig` tiles are too long for one wavefront. Workgroups
     // 0 .. nbig - 1 take one of those each; every later workgroup takes four shorter lists, one per wavefront.
     const uint32_t nbig = min(status[kStNumBig], ntiles);
     const int wave = threadIdx.x >> 6;
+    DBG_BEGIN
     if (blockIdx.x >= nbig) {
         const uint32_t idx = nbig + (blockIdx.x - nbig) * 4u + (uint32_t)wave;
         if (idx >= ntiles) return;
@@ -586,6 +637,7 @@ __global__ __launch_bounds__(256) void k_tile_depth_sort(const uint32_t* __restr
         if (e <= s + 1u) return;
         // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
         if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
+        DBG_END(e - s)
         return;
     }
     WgSortLds& S = U.wg;
@@ -593,7 +645,8 @@ __global__ __launch_bounds__(256) void k_tile_depth_sort(const uint32_t* __restr
     const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
     if (e <= s + 1u) return;                     // uniform for the workgroup
     const uint32_t L = e - s;
-    if (L <= (uint32_t)kWgListMax) { wg_sort_list(S, L, depth_bits, valsA + s, keysA + s); return; }
+    if (L <= (uint32_t)kWgKeyMax) { wg_sort_list<true>(S, L, depth_bits, valsA + s, keysA + s); DBG_END(L) return; }
+    if (L <= (uint32_t)kWgListMax) { wg_sort_list<false>(S, L, depth_bits, valsA + s, keysA + s); DBG_END(L) return; }
     // through global memory: keys of the list and the bit positions in which they differ
     const int lane = threadIdx.x & 63;
     const uint32_t k0 = depth_bits[valsA[s]];
@@ -613,13 +666,14 @@ __global__ __launch_bounds__(256) void k_tile_depth_sort(const uint32_t* __restr
     if (mask == 0u) return;                        // one depth throughout: point order is the order
     int lo;
     const int passes = list_passes(mask, lo);
-    uint32_t* base = reinterpret_cast<uint32_t*>(S.idx);      // the permutation array is idle on this path
+    uint32_t* base = reinterpret_cast<uint32_t*>(&S.u);      // the key / permutation area is idle on this path
     for (int p = 0; p < passes; ++p) {
         if ((p & 1) == 0) long_list_pass(S, base, L, list_shift(lo, p), keysA + s, valsA + s, keysB + s, valsB + s);
         else long_list_pass(S, base, L, list_shift(lo, p), keysB + s, valsB + s, keysA + s, valsA + s);
     }
     if (passes & 1)
         for (uint32_t i = threadIdx.x; i < L; i += 256u) valsA[s + i] = valsB[s + i];
+    DBG_END(L)
 }
 
 hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_order, uint32_t ntiles, const uint32_t* status,

@@ -58,12 +58,13 @@ def test_lists_all_equal_depth_one_tile():
 
 
 @pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 257, 600, 1022, 1023, 2048, 2049, 4097, 6016, 6017, 9000])
-@pytest.mark.parametrize("kind", ["narrow", "wide", "two_values"])
+@pytest.mark.parametrize("kind", ["narrow", "wide", "two_values", "wide_short_runs"])
 def test_one_crowded_tile_depth_order(n, kind):
     """Every splat in one tile: the list's depth order is made by one workgroup - by counting up to 256 entries, in LDS up
     to 2048, through the global scratch arrays beyond - over the bit positions in which the depths differ: depths from a
     narrow band (few differing bits), from many octaves (all exponent bits differ), and only two distinct values; a
-    third of the entries tied in every case, so that the order among equals (point index) is exercised too."""
+    third of the entries tied in each of these, so that the order among equals (point index) is exercised too; and depths over
+    many octaves with short runs of near-equal values out of point order."""
     rng = np.random.default_rng(n * 7 + len(kind))
     st = dict(mean2d=rng.uniform(17.0, 30.0, (n, 2)).astype(np.float32), conic=np.tile([0.1, 0, 0.1], (n, 1)),
               opacity=np.full(n, 0.01), color=np.zeros((n, 3)), radius=np.full(n, 1, dtype=np.int32))
@@ -71,9 +72,19 @@ def test_one_crowded_tile_depth_order(n, kind):
         depth = rng.uniform(7.0, 7.01, n).astype(np.float32)
     elif kind == "wide":
         depth = np.exp(rng.uniform(np.log(1e-3), np.log(1e9), n)).astype(np.float32)
+    elif kind == "wide_short_runs":
+        # many bit positions differ, and entries that agree in the top 16 of them come in runs of two to eight: exact
+        # ties, and neighbours a few units in the last place apart, out of order by point index
+        depth = np.exp(rng.uniform(np.log(0.5), np.log(300.0), n)).astype(np.float32)
+        for start in rng.integers(0, max(n - 8, 1), max(n // 6, 1)):
+            run = int(rng.integers(2, 9))
+            bits = depth[start:start + 1].view(np.uint32)[0] + rng.integers(0, 40, run).astype(np.uint32)
+            where = rng.integers(0, n, run)
+            depth[where] = bits.view(np.float32)
     else:
         depth = rng.choice(np.array([2.5, 2.5000002], dtype=np.float32), n)
-    depth[rng.integers(0, n, n // 3)] = depth[0]
+    if kind != "wide_short_runs":
+        depth[rng.integers(0, n, n // 3)] = depth[0]
     got, ref, _ = _lists_case(st, depth, 48, 48)
     assert ref["ranges"][4].tolist() == [0, n]             # tile (1, 1) of the 3 x 3 grid holds them all
     assert np.array_equal(got["vals"], ref["vals"])
