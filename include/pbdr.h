@@ -113,8 +113,14 @@ typedef struct pbdr_splat_grads {
 } pbdr_splat_grads;
 
 /* Bytes of workspace that pbdr_render_fwd / pbdr_render_bwd / pbdr_bin_sort need for n points, a width x height
- * image and at most dup_capacity (tile, splat) pairs. The workspace must be 256-byte aligned. */
+ * image and at most dup_capacity (tile, splat) pairs. The workspace must be 256-byte aligned and ZERO-FILLED ONCE
+ * before its first use (pbdr_workspace_init, or any device memset of the caller's): the backward pass tells the
+ * per-pair records it wrote from older ones by the number of the call, which the workspace counts from zero. Calls
+ * never need it cleared again, and a workspace may be reused for other sizes after being zero-filled again. */
 int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes);
+
+/* Zero-fills `bytes` bytes of workspace (a fill kernel on hip_stream; bytes a multiple of 16). Once per allocation. */
+int pbdr_workspace_init(void* workspace, size_t bytes, void* hip_stream);
 
 /* pts_culling + pts_splatting (Sec. 3.1, Sec. 3.2 "3DGS"; Alg. 1 lines 2-4). One pass over the shard: near/far
  * cull, covariance projection, conic, extent, off-screen and radius_clip cull, SH colour. Writes all of `out`. */
@@ -246,6 +252,13 @@ int pbdr_lists_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t 
  * + the next lower bit of L + 1, classes of 2^19.5 and more merged), and within a class in ascending id. */
 int pbdr_tile_order_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
                          uint64_t dup_capacity, int32_t surfel_workspace, const uint32_t** tile_order);
+
+/* Device address, inside a workspace of either kind laid out for these sizes, of three words that the last
+ * pbdr_bin_sort / pbdr_render_fwd / pbdr2d_render_fwd on it left: {pairs found (before clamping to dup_capacity;
+ * saturates at 2^31 - 1), overflow flag (1 = pairs beyond dup_capacity were dropped), listed points}. The caller can
+ * poll them with a copy of its own, ordered after the call on its stream: nothing here synchronises. */
+int pbdr_status_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                     uint64_t dup_capacity, const uint32_t** status_words);
 
 /* Synchronises hip_stream and reads back the number of (tile, splat) pairs found by the last pbdr_bin_sort /
  * pbdr_render_fwd on this workspace. Returns PBDR_ERR_CAPACITY if it exceeded dup_capacity (the lists were then

@@ -36,7 +36,8 @@ EXPORTS = ("pbdr_workspace_bytes", "pbdr_preprocess", "pbdr_bin_sort", "pbdr_ren
            "pbdr_preprocess_patch", "pbdr_render_fwd_patch", "pbdr_render_bwd_patch",
            "pbdr2d_preprocess_patch", "pbdr2d_render_fwd_patch", "pbdr2d_render_bwd_patch",
            "pbdr_l1_loss", "pbdr_mark_visible", "pbdr_adam_selective", "pbdr_preprocess_batch", "pbdr_preprocess_bwd_batch",
-           "pbdr_preprocess_bwd_batch_adam", "pbdr_tile_order_view", "pbdr_render_fwd_static")
+           "pbdr_preprocess_bwd_batch_adam", "pbdr_tile_order_view", "pbdr_render_fwd_static", "pbdr_workspace_init",
+           "pbdr_status_view")
 
 _f = C.POINTER(C.c_float)
 
@@ -265,11 +266,26 @@ def pbdr_workspace_bytes(n, width, height, dup_capacity) -> int:
     return int(out.value)
 
 
-def alloc_workspace(n, width, height, dup_capacity, device="cuda") -> torch.Tensor:
-    nbytes = pbdr_workspace_bytes(n, width, height, dup_capacity)
+def _alloc_ws(nbytes, device):
+    """256-byte aligned and zero-filled once (pbdr_workspace_init), as the library asks of a workspace."""
     ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
     off = (-ws.data_ptr()) % 256
-    return ws[off:off + nbytes]
+    ws = ws[off:off + nbytes]
+    _check(lib().pbdr_workspace_init(C.c_void_p(ws.data_ptr()), C.c_size_t(nbytes), _stream(None)))
+    return ws
+
+
+def alloc_workspace(n, width, height, dup_capacity, device="cuda") -> torch.Tensor:
+    return _alloc_ws(pbdr_workspace_bytes(n, width, height, dup_capacity), device)
+
+
+def pbdr_status_view(ws, n, width, height, dup_capacity) -> torch.Tensor:
+    """The three status words {pairs found, overflow flag, listed points} as a device tensor (a view into ws)."""
+    p = C.POINTER(C.c_uint32)()
+    _check(lib().pbdr_status_view(C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), C.c_int32(n), C.c_int32(width),
+                                  C.c_int32(height), C.c_uint64(dup_capacity), C.byref(p)))
+    off = C.cast(p, C.c_void_p).value - ws.data_ptr()
+    return ws[off:off + 12].view(torch.int32)
 
 
 def pbdr_preprocess(scene: Scene, cam: dict, out: Splats, stream=None) -> None:
@@ -623,10 +639,7 @@ def pbdr2d_workspace_bytes(n, width, height, dup_capacity) -> int:
 
 
 def alloc_workspace2d(n, width, height, dup_capacity, device="cuda") -> torch.Tensor:
-    nbytes = pbdr2d_workspace_bytes(n, width, height, dup_capacity)
-    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
-    off = (-ws.data_ptr()) % 256
-    return ws[off:off + nbytes]
+    return _alloc_ws(pbdr2d_workspace_bytes(n, width, height, dup_capacity), device)
 
 
 def pbdr2d_preprocess(scene: Scene2D, cam: dict, out: Splats2D, stream=None) -> None:

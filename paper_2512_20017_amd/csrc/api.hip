@@ -33,6 +33,11 @@ static hipError_t static_scratch(void** out)
     return hipSuccess;
 }
 
+__global__ __launch_bounds__(256) void k_zero_fill(uint4* __restrict__ p, size_t count)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 __global__ void k_copy_word(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
@@ -231,6 +236,28 @@ const char* pbdr_status_string(int status)
         case PBDR_ERR_STATIC_LIMIT: return "more points or a larger image than the static scratch buffer serves";
         default: return "unknown status";
     }
+}
+
+int pbdr_workspace_init(void* workspace, size_t bytes, void* hip_stream)
+{
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0 || (bytes & 15u) != 0) return PBDR_ERR_INVALID_ARG;
+    if (bytes == 0) return PBDR_OK;
+    const size_t count = bytes / 16;
+    const unsigned blocks = (unsigned)((count + 255) / 256 < 16384 ? (count + 255) / 256 : 16384);
+    hipLaunchKernelGGL(k_zero_fill, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, reinterpret_cast<uint4*>(workspace), count);
+    return hip_result(hipGetLastError());
+}
+
+int pbdr_status_view(void* workspace, size_t workspace_bytes, int32_t n, int32_t width, int32_t height,
+                     uint64_t dup_capacity, const uint32_t** status_words)
+{
+    Layout L;
+    if (!status_words) return PBDR_ERR_INVALID_ARG;
+    // the status block heads both kinds of workspace; the 3D layout is the smaller one, so its size check serves both
+    const int st = workspace_ok(workspace, workspace_bytes, n, width, height, dup_capacity, &L);
+    if (st != PBDR_OK) return st;
+    *status_words = reinterpret_cast<const uint32_t*>((char*)workspace + L.off_status);
+    return PBDR_OK;
 }
 
 int pbdr_workspace_bytes(int32_t n, int32_t width, int32_t height, uint64_t dup_capacity, size_t* out_bytes)

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     const size_t HW = (size_t)cam.W * cam.H;
-    const uint32_t epoch = status[kStEpoch];
+    const uint32_t epoch_lo = status[kStEpoch] + 1u, epoch_hi = status[kStEpoch + 1] + (epoch_lo == 0u ? 1u : 0u);      // this call, counted from one
     float T = 1.f, g0 = 0.f, g1 = 0.f, g2c = 0.f;
     uint32_t last = 0;
     if (c.inside) {
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                 dst[1] = make_float4(0.5f * acc[7], raw.w > 0.f ? -s0 / raw.w : 0.f,                   // d conic c, d opacity
                                      acc[0], acc[1]);                                                 // d red, d green
                 // d blue, then the stamp that tells the gather this record belongs to this backward call
-                dst[2] = make_float4(acc[8], 0.f, __uint_as_float(epoch), __uint_as_float(~epoch));
+                dst[2] = make_float4(acc[8], 0.f, __uint_as_float(epoch_lo), __uint_as_float(epoch_hi));
             }
         }
         __syncthreads();   // sAcc and the stage are rewritten by the next batch
@@ -366,7 +366,11 @@ __global__ __launch_bounds__(256) void k_gather_fixup(int n, uint32_t* __restric
                                                       uint32_t cap, const float* __restrict__ carry, float4* __restrict__ rec)
 {
     gather_fixup<9>(blockIdx.x * 256u + threadIdx.x, status, cap, carry, StoreSplatGrad{rec, order});
-    if (blockIdx.x == 0 && threadIdx.x == 0) status[kStEpoch] = status[kStEpoch] + 1u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {      // 64-bit count of backward calls on this workspace
+        const uint32_t lo = status[kStEpoch] + 1u;
+        status[kStEpoch] = lo;
+        if (lo == 0u) status[kStEpoch + 1] = status[kStEpoch + 1] + 1u;
+    }
 }
 
 // records -> planes, for the points binning listed (tiles_touched > 0)

@@ -74,9 +74,10 @@ __device__ __forceinline__ void seg_scan_sorted(float (&v)[kVals], int owner)
 
 // One wavefront's 256 pairs. kVec4 float4 per record, of which the first kVals floats are summed. `store(rank, v)`
 // writes a finished sum for depth rank `rank`. sEnd: 64 words of LDS private to the wavefront.
-// kTagged: the last two words of a record carry (epoch, ~epoch) of the backward call that wrote it; a record with any
-// other tag was not written by this call (its pair lies beyond the last splat its tile blended) and counts as zero.
-// That replaces clearing all records before every backward pass.
+// kTagged: the last two words of a record carry the 64-bit number of the backward call that wrote it (the workspace
+// counts its backward calls from one; it starts zero-filled, so no record of an earlier call, and no record never
+// written, carries the current number); a record with any other tag was not written by this call (its pair lies beyond
+// the last splat its tile blended) and counts as zero. That replaces clearing all records before every backward pass.
 template <int kVec4, int kVals, bool kTagged, class Store>
 __device__ __forceinline__ void gather_wave(uint32_t w, int n, const uint32_t* __restrict__ status,
                                             const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ chunk_rank,
@@ -86,7 +87,7 @@ __device__ __forceinline__ void gather_wave(uint32_t w, int n, const uint32_t* _
     const int lane = threadIdx.x & 63;
     const uint32_t Pc = min(status[kStNumDup], cap);
     const uint32_t m = min(status[kStNumVis], (uint32_t)n);
-    const uint32_t epoch = status[kStEpoch];
+    const uint32_t epoch_lo = status[kStEpoch] + 1u, epoch_hi = status[kStEpoch + 1] + (epoch_lo == 0u ? 1u : 0u);
     const uint32_t wbeg = w * (uint32_t)kChunkPairs;
     if (wbeg >= Pc) return;
     const uint32_t wend = min(wbeg + (uint32_t)kChunkPairs, Pc);
@@ -110,7 +111,7 @@ __device__ __forceinline__ void gather_wave(uint32_t w, int n, const uint32_t* _
             float4 rec[kVec4];
 #pragma unroll
             for (int q = 0; q < kVec4; ++q) rec[q] = partial[(size_t)kVec4 * u + q];
-            const bool written = !kTagged || (__float_as_uint(rec[kVec4 - 1].z) == epoch && __float_as_uint(rec[kVec4 - 1].w) == ~epoch);
+            const bool written = !kTagged || (__float_as_uint(rec[kVec4 - 1].z) == epoch_lo && __float_as_uint(rec[kVec4 - 1].w) == epoch_hi);
 #pragma unroll
             for (int k = 0; k < kVals; ++k) {
                 const float4 r = rec[k >> 2];

@@ -113,8 +113,9 @@ struct Splat2DGradDev {
 
 // Status words at the head of the workspace.
 // pair count, overflow flag, visible-point count, number of tiles whose list is too long for one wavefront to sort
-// (written by k_tile_order): cleared by every binning. kStEpoch is never cleared: a counter that
-// the backward pass bumps once per call and stamps into the per-pair records it writes (see k_composite_bwd).
+// (written by k_tile_order): cleared by every binning. kStEpoch (two words) is never cleared by a call: the 64-bit
+// number of backward passes this workspace has seen plus one, stamped into the per-pair records a pass writes (see
+// k_composite_bwd); it relies on the workspace having been zero-filled once before its first use.
 enum { kStNumDup = 0, kStOverflow = 1, kStNumVis = 2, kStNumBig = 3, kStCleared = 32, kStEpoch = 32, kStWords = 64 };
 
 // Workspace layout for (n, W, H, capacity). All offsets are multiples of 256 bytes.

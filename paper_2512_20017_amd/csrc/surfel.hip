@@ -15,6 +15,7 @@
 #include "composite_common.h"
 #include "pair_reduce.h"
 #include "binning_common.h"
+#include "sh_basis.h"
 
 namespace pbdr {
 
@@ -26,55 +27,6 @@ struct __attribute__((aligned(16))) Packed2D {
     float b, radius_bits, t0z, t1z;  // blue, integer extent (bit-cast), third components of the centred rows (rounding residue)
 };
 static_assert(sizeof(Packed2D) == 64, "surfel raster record is 64 bytes");
-
-__device__ __forceinline__ void sh_basis2(int deg, float x, float y, float z, float Y[16])
-{
-    Y[0] = 0.28209479177387814f;
-    if (deg < 1) return;
-    Y[1] = -0.4886025119029199f * y; Y[2] = 0.4886025119029199f * z; Y[3] = -0.4886025119029199f * x;
-    if (deg < 2) return;
-    const float xx = x * x, yy = y * y, zz = z * z;
-    Y[4] = 1.0925484305920792f * x * y;
-    Y[5] = -1.0925484305920792f * y * z;
-    Y[6] = 0.31539156525252005f * (2.f * zz - xx - yy);
-    Y[7] = -1.0925484305920792f * x * z;
-    Y[8] = 0.5462742152960396f * (xx - yy);
-    if (deg < 3) return;
-    Y[9] = -0.5900435899266435f * y * (3.f * xx - yy);
-    Y[10] = 2.890611442640554f * x * y * z;
-    Y[11] = -0.4570457994644658f * y * (4.f * zz - xx - yy);
-    Y[12] = 0.3731763325901154f * z * (2.f * zz - 3.f * xx - 3.f * yy);
-    Y[13] = -0.4570457994644658f * x * (4.f * zz - xx - yy);
-    Y[14] = 1.445305721320277f * z * (xx - yy);
-    Y[15] = -0.5900435899266435f * x * (xx - 3.f * yy);
-}
-
-__device__ __forceinline__ void sh_basis_grad2(int deg, float x, float y, float z, float dY[16][3])
-{
-#pragma unroll
-    for (int k = 0; k < 16; ++k) dY[k][0] = dY[k][1] = dY[k][2] = 0.f;
-    if (deg < 1) return;
-    const float c1 = 0.4886025119029199f;
-    dY[1][1] = -c1; dY[2][2] = c1; dY[3][0] = -c1;
-    if (deg < 2) return;
-    const float c2a = 1.0925484305920792f, c2b = 0.31539156525252005f, c2c = 0.5462742152960396f;
-    dY[4][0] = c2a * y; dY[4][1] = c2a * x;
-    dY[5][1] = -c2a * z; dY[5][2] = -c2a * y;
-    dY[6][0] = -2.f * c2b * x; dY[6][1] = -2.f * c2b * y; dY[6][2] = 4.f * c2b * z;
-    dY[7][0] = -c2a * z; dY[7][2] = -c2a * x;
-    dY[8][0] = 2.f * c2c * x; dY[8][1] = -2.f * c2c * y;
-    if (deg < 3) return;
-    const float c3a = 0.5900435899266435f, c3b = 2.890611442640554f, c3c = 0.4570457994644658f,
-                c3d = 0.3731763325901154f, c3e = 1.445305721320277f;
-    const float xx = x * x, yy = y * y, zz = z * z;
-    dY[9][0] = -6.f * c3a * x * y;             dY[9][1] = -3.f * c3a * (xx - yy);
-    dY[10][0] = c3b * y * z;                   dY[10][1] = c3b * x * z;                  dY[10][2] = c3b * x * y;
-    dY[11][0] = 2.f * c3c * x * y;             dY[11][1] = -c3c * (4.f * zz - xx - 3.f * yy); dY[11][2] = -8.f * c3c * y * z;
-    dY[12][0] = -6.f * c3d * x * z;            dY[12][1] = -6.f * c3d * y * z;           dY[12][2] = 3.f * c3d * (2.f * zz - xx - yy);
-    dY[13][0] = -c3c * (4.f * zz - 3.f * xx - yy); dY[13][1] = 2.f * c3c * x * y;        dY[13][2] = -8.f * c3c * x * z;
-    dY[14][0] = 2.f * c3e * x * z;             dY[14][1] = -2.f * c3e * y * z;           dY[14][2] = c3e * (xx - yy);
-    dY[15][0] = -3.f * c3a * (xx - yy);        dY[15][1] = 6.f * c3a * x * y;
-}
 
 struct Frame2D {
     float tu[3], tv[3], w[3], ainv, winv, btu, su, sv;
@@ -158,7 +110,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     const float vx = m[0] - cam.campos[0], vy = m[1] - cam.campos[1], vz = m[2] - cam.campos[2];
     const float vinv = 1.0f / sqrtf(vx * vx + vy * vy + vz * vz);
     float Y[16];
-    sh_basis2(kDeg, vx * vinv, vy * vinv, vz * vinv, Y);
+    sh_basis(kDeg, vx * vinv, vy * vinv, vz * vinv, Y);
     constexpr int K = (kDeg + 1) * (kDeg + 1);
     float rgb[3] = {0.5f, 0.5f, 0.5f};
 #pragma unroll
@@ -241,8 +193,8 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
         const float dx = vx * vinv, dy = vy * vinv, dz = vz * vinv;
         float Y[16];
         float dY[16][3];
-        sh_basis2(kDeg, dx, dy, dz, Y);
-        sh_basis_grad2(kDeg, dx, dy, dz, dY);
+        sh_basis(kDeg, dx, dy, dz, Y);
+        sh_basis_grad(kDeg, dx, dy, dz, dY);
         constexpr int K = (kDeg + 1) * (kDeg + 1);
         float gd0 = 0.f, gd1 = 0.f, gd2 = 0.f;
 #pragma unroll

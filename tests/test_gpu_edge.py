@@ -130,17 +130,34 @@ def test_zero_points():
     torch.cuda.synchronize()
 
 
+def _untouched(st, w, h):
+    """Points with radius > 0 whose tile rectangle misses the image (binning does not list them)."""
+    r = np.asarray(st["radius"], dtype=np.int64)
+    ix = np.floor(np.asarray(st["mean2d"], dtype=np.float32)[:, 0]).astype(np.int64)
+    iy = np.floor(np.asarray(st["mean2d"], dtype=np.float32)[:, 1]).astype(np.int64)
+    tx, ty = (w + 15) // 16, (h + 15) // 16
+    x0, x1 = np.clip((ix - r) >> 4, 0, tx), np.clip((ix + r + 15) >> 4, 0, tx)
+    y0, y1 = np.clip((iy - r) >> 4, 0, ty), np.clip((iy + r + 15) >> 4, 0, ty)
+    return int(((r > 0) & ((x1 - x0) * (y1 - y0) == 0)).sum())
+
+
 def test_capacity_overflow_is_reported_and_in_bounds():
     rng = np.random.default_rng(5)
     n, w, h = 2000, 128, 96
     st = _rand_state(rng, n, w, h)
     depth = rng.uniform(0.3, 50, n).astype(np.float32)
-    full, ref, _ = _lists_case(st, depth, w, h)
+    full, ref, roomy = _lists_case(st, depth, w, h)
+    assert np.array_equal(full["vals"], ref["vals"])
     cap = ref["P"] // 3
     got, _, view = _lists_case(st, depth, w, h, cap=cap)
     n_dup, over = B.pbdr_query_lists(view.ws, n, w, h, cap)
     assert over and n_dup == ref["P"]
     assert got["P"] == cap
+    # the same through the status words a caller can poll without a synchronising call: {pairs found, overflow, listed}
+    words = B.pbdr_status_view(view.ws, n, w, h, cap).cpu().numpy()
+    assert words.tolist() == [ref["P"], 1, int((np.asarray(st["radius"]) > 0).sum() - _untouched(st, w, h))]
+    words_ok = B.pbdr_status_view(roomy.ws, n, w, h, roomy.cap).cpu().numpy()      # the run with room for every pair
+    assert words_ok[0] == ref["P"] and words_ok[1] == 0
     # what was kept is a sorted subset of the true pairs, and ranges stay inside the capacity
     assert (np.diff(got["keys"].astype(np.uint64).astype(object)) >= 0).all()
     assert got["ranges"].max() <= cap
