@@ -41,26 +41,24 @@ __device__ __forceinline__ float qform_min_rect(float A, float B, float C, float
 
 constexpr int kAccStride = 9;    // floats between the LDS accumulators of consecutive splats of a batch (odd)
 
-// LDS image of one staged batch
-struct StageRec {                     // 48 bytes: one LDS address register serves all three reads of a visit
-    float4 a;                         // mx, my, A = log2e/2 * qa, B = log2e * qb
-    float4 b;                         // C = log2e/2 * qc, L = log2(opacity), red, green
-    float c, pad[3];                  // blue
-};
+// LDS image of one staged batch of kB splats (kB a multiple of 64, at most the workgroup size)
+template <int kB>
 struct Stage {
-    StageRec rec[kBatch];
-    unsigned long long mask[4][4];    // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
-    uint32_t definite[4];             // [staging wavefront]: all of its splats have a positive-definite conic, with margin
+    float4 a[kB];                          // mx, my, A = log2e/2 * qa, B = log2e * qb
+    float4 b[kB];                          // C = log2e/2 * qc, L = log2(opacity), red, green
+    float c[kB];                           // blue
+    unsigned long long mask[4][kB / 64];   // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
+    uint32_t definite[kB / 64];            // [staging wavefront]: all of its splats have a positive-definite conic, with margin
 };
 
-// Stage list entries [first, first+count) of the tile: one per thread. Returns this thread's splat index, raw
+// Stage list entries [first, first+count) of the tile, count <= kB: one per thread. Returns this thread's splat index, raw
 // conic/opacity and (mean2d, extent) for callers that need them (backward). All 256 threads must call it.
 // reach: one byte per list position, bit q = "this splat can reach quadrant q", bit 4 = "its conic is positive
 // definite with a margin that rounding cannot bridge" (then the quadratic form is never negative and the per-pixel
 // sign test can be left out for the batch, see walk loops). The forward pass works the bits out and stores them
 // (kReuse = false); the backward pass, which walks a prefix of the same lists, reads them back.
-template <bool kReuse>
-__device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const uint32_t* __restrict__ vals,
+template <bool kReuse, int kB>
+__device__ __forceinline__ void stage_batch(Stage<kB>& S, const TileCtx& t, const uint32_t* __restrict__ vals,
                                             const Packed* __restrict__ packed, uint8_t* __restrict__ reach_bits, uint32_t first,
                                             int count, uint32_t& id, float4& raw, float4& geo)
 {
@@ -78,9 +76,9 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
         geo = make_float4(mx, my, r2.y, 0.f);   // r2.y carries the extent (integer bits)
         const float A = 0.5f * kLog2e * qa, B = kLog2e * qb, C = 0.5f * kLog2e * qc;
         const float L = __log2f(o);
-        S.rec[threadIdx.x].a = make_float4(mx, my, A, B);
-        S.rec[threadIdx.x].b = make_float4(C, L, r1.z, r1.w);
-        S.rec[threadIdx.x].c = r2.x;
+        S.a[threadIdx.x] = make_float4(mx, my, A, B);
+        S.b[threadIdx.x] = make_float4(C, L, r1.z, r1.w);
+        S.c[threadIdx.x] = r2.x;
         if (kReuse) {
             const uint32_t bits = reach_bits[first + threadIdx.x];
 #pragma unroll
@@ -113,10 +111,10 @@ __device__ __forceinline__ void stage_batch(Stage& S, const TileCtx& t, const ui
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const unsigned long long m = __ballot(reach[q]);
-        if (lane == 0) S.mask[q][wave] = m;
+        if (lane == 0 && wave < kB / 64) S.mask[q][wave] = m;
     }
     const unsigned long long dm = __ballot(definite);
-    if (lane == 0) S.definite[wave] = (dm == ~0ull) ? 1u : 0u;
+    if (lane == 0 && wave < kB / 64) S.definite[wave] = (dm == ~0ull) ? 1u : 0u;
 }
 
 __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
@@ -125,7 +123,7 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
                                                        float* __restrict__ image, float* __restrict__ final_T,
                                                        uint32_t* __restrict__ last_idx)
 {
-    __shared__ Stage S;
+    __shared__ Stage<kBatch> S;
     const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
@@ -146,9 +144,9 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
             constexpr bool kSign = decltype(sign_test)::value;
             // alpha of one visit: everything that does not depend on the pixel's running state
             auto eval = [&](int j, float& alpha, bool& ok, float& r, float& g, float& bl) {
-                const float4 a = S.rec[j].a;
-                const float4 b = S.rec[j].b;
-                bl = S.rec[j].c; r = b.z; g = b.w;
+                const float4 a = S.a[j];
+                const float4 b = S.b[j];
+                bl = S.c[j]; r = b.z; g = b.w;
                 const float dx = fx - a.x, dy = fy - a.y;
                 const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                 alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
@@ -206,16 +204,31 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
 
 // Backward. Per pixel, back to front from its last blended splat: T_k = T_{k+1} / (1 - alpha_k),
 //   dL/dalpha_k = T_k (c_k . g) - S_k / (1 - alpha_k),  S_k = sum_{i>k} w_i (c_i . g) + T_final (bg . g).
-// With ds = dL/dsigma = -alpha dL/dalpha (zero where alpha was clamped), every splat gradient is a lane sum of
+// With ds = dL/dsigma = -alpha dL/dalpha (zero where alpha was clamped), every splat gradient is a sum over pixels of
 //   w g_c (3 colours)  and the six moments  ds (1, dx, dy, dx^2, dx dy, dy^2):
 //   d conic = (S3/2, S4, S5/2), d mean2d = -(qa S1 + qb S2, qc S2 + qb S1), d opacity = -S0 / o.
 //
-// No global atomics: each wavefront reduces its rows of 16 pixels with DPP, the 16 rows of the tile meet in an LDS
-// accumulator (ds_add_f32), and the thread that staged splat j writes the tile's nine sums for it to partial[u]
-// (12 floats per pair), where u is the pair's position in the unsorted duplicate list (slot_base[id] + rank of this
-// tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them up afterwards
-// (k_gather_splat_grads).
-__global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+// The sums over pixels are taken four visits at a time. A visit only stores its ds and w as two rows of 64 floats in
+// LDS (a transpose: the values of one visit sit across the lanes, the sums want the pixels of one visit inside a lane).
+// After four visits a quarter of the wavefront (16 lanes, one DPP row) takes each visit: a lane reads ds and w of four
+// neighbouring pixels, forms their nine weighted sums with weights it holds for the whole tile (the pixels' dL/dcolour
+// and their coordinates X, Y inside the tile: with dx = X0 + X, dy = Y0 + Y for a per-(tile, splat) offset (X0, Y0),
+// the six moments follow from the moments of ds against 1, X, Y, X^2, XY, Y^2, whatever the splat), and one butterfly
+// over the row finishes four visits at once: about 13 vector instructions per visit instead of 39 when every visit
+// reduced its own nine products over the 64 lanes.
+// (Measured and dropped: the same contraction as sixteen v_mfma_f32_16x16x4_f32 per eight visits. An fp32 matrix
+// instruction holds the SIMD for its 32 cycles - plain vector instructions of other wavefronts do not overlap with it -
+// and only 9 of its 32 output columns are of use, so it came out slower than the butterfly it replaced.)
+//
+// No global atomics: the row results are added to an LDS accumulator per staged splat (ds_add_f32), where the four
+// quadrants meet, and the thread that staged splat j turns the tile's nine sums for it into gradients and writes them
+// to partial[u] (12 floats per pair), where u is the pair's position in the unsorted duplicate list (slot_base[id] +
+// rank of this tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them
+// up afterwards (k_gather_splat_grads).
+constexpr int kVisitSlots = 4;    // visits staged per reduction: one per row of 16 lanes
+constexpr int kBwdBatch = 128;    // splats staged at a time by the backward kernel: what the per-quadrant accumulators leave room for
+
+__global__ __launch_bounds__(256, 5) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        uint8_t* __restrict__ reach_bits, const uint32_t* __restrict__ slot_base,
                                                        float bg0, float bg1, float bg2, const float* __restrict__ final_T,
@@ -223,9 +236,14 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                                                        const float* __restrict__ dL_dimage, uint32_t cap,
                                                        const uint32_t* __restrict__ status, float4* __restrict__ partial)
 {
-    __shared__ Stage S;
-    // [splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are conflict-free)
-    __shared__ float sAcc[kAccStride * kBatch];
+    __shared__ Stage<kBwdBatch> S;
+    // [quadrant][splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are
+    // conflict-free): three colour sums, then the moments of ds against 1, X, Y, X^2, XY, Y^2. A wavefront visits a splat
+    // at most once per batch, so it writes its quadrant's sums with plain stores; the thread that staged the splat adds
+    // the four up. (One accumulator per splat shared by the quadrants takes LDS float atomics, which cost the LDS about
+    // 2.5 cycles per active lane: a quarter of this kernel's time when it was built that way.)
+    __shared__ float sAcc[4][kAccStride * kBwdBatch];
+    __shared__ __align__(16) float sV[4][2 * kVisitSlots * 64];   // per wavefront: rows 2s (ds) and 2s + 1 (w) of visit slot s
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -248,38 +266,75 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
     const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
     if (tile_last == 0) return;
     const int tile_x = c.tix, tile_y = c.tiy;
-    // One LDS add per visit, by nine lanes. After the row butterfly (row_sum8) lanes 2k and 2k+1 of each row carry
-    // value k and lane 15 is given the row's blue sum; the four rows are then added lane by lane (every row ends up
-    // with the total) and the even lanes of the last row and lane 63 add. (LDS float adds cost LDS time per active lane and per address clash, and the LDS
-    // pipe, not the VALU, bounded this kernel when all four rows issued their own adds.)
+    float* const sVw = sV[wave];
+    float* const sAccW = sAcc[wave];
+    // In a reduction lane l takes visit slot l / 16 and the four pixels held by the wavefront's lanes 4 pg .. 4 pg + 3,
+    // pg = l % 16: half a pixel row of the quadrant. Their dL/dcolour come from those lanes, through LDS.
+    const int pg = lane & 15;
+    float4 G0, G1, G2;
+    {
+        sVw[lane] = g0; sVw[64 + lane] = g1; sVw[128 + lane] = g2c;
+        __builtin_amdgcn_wave_barrier();
+        G0 = *reinterpret_cast<const float4*>(sVw + 4 * pg);
+        G1 = *reinterpret_cast<const float4*>(sVw + 64 + 4 * pg);
+        G2 = *reinterpret_cast<const float4*>(sVw + 128 + 4 * pg);
+        __builtin_amdgcn_wave_barrier();
+    }
+    // tile coordinates of the first of the four pixels; the others are X + 1, X + 2, X + 3 on the same row
+    const float PX = (float)((wave & 1) * 8 + 4 * (pg & 1)), PY = (float)((wave >> 1) * 8 + (pg >> 1));
+    const float PX2 = 2.f * PX, PXX = PX * PX, PYY = PY * PY;
+    const float* const rd_row = sVw + 128 * (lane >> 4) + 4 * pg;
+    float* const wr_row = sVw + lane;
     const bool bit1 = (lane & 2) != 0;
-    const bool blue_lane = (lane & 15) == 15;
-    const bool add_lane = lane >= 48 && (blue_lane || (lane & 1) == 0);
-    const int acc_slot = blue_lane ? 8 : (lane >> 1) & 7;
-    const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
+    const bool ninth_lane = pg == 15;
+    const bool add_lane = ninth_lane || (lane & 1) == 0;
+    const int acc_slot = ninth_lane ? 8 : (lane >> 1) & 7;
+    int slot_acc = 0;      // lane s: where visit slot s adds its sums (kAccStride * its splat's position in the batch)
+    int nslot = 0;         // visits staged since the last reduction (uniform)
+    // Reduces the staged rows and adds the sums of the first `count` visit slots to their splats' accumulators.
+    auto reduce_slots = [&](int count) {
+        __builtin_amdgcn_wave_barrier();
+        const float4 d = *reinterpret_cast<const float4*>(rd_row);
+        const float4 w = *reinterpret_cast<const float4*>(rd_row + 64);
+        __builtin_amdgcn_wave_barrier();
+        const float m0 = (d.x + d.y) + (d.z + d.w);
+        const float s1 = d.y + 2.f * d.z + 3.f * d.w;             // sum of ds i and of ds i^2 over the pixels X + i
+        const float s2 = d.y + 4.f * d.z + 9.f * d.w;
+        const float mx = PX * m0 + s1;
+        const float mxx = PXX * m0 + (PX2 * s1 + s2);
+        const float v8[8] = {w.x * G0.x + w.y * G0.y + w.z * G0.z + w.w * G0.w,
+                             w.x * G1.x + w.y * G1.y + w.z * G1.z + w.w * G1.w,
+                             w.x * G2.x + w.y * G2.y + w.z * G2.z + w.w * G2.w,
+                             m0, mx, PY * m0, mxx, PY * mx};
+        const float part = row_sum8(v8, bit1);
+        const float ninth = row_sum16(PYY * m0);
+        const int base = __shfl(slot_acc, lane >> 4, 64);
+        if (add_lane && (lane >> 4) < count) sAccW[base + acc_slot] = ninth_lane ? ninth : part;
+    };
+    const int nbatch = (int)((tile_last + kBwdBatch - 1) / kBwdBatch);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
-        const uint32_t boff = (uint32_t)bi * kBatch;               // 0-based list position of the batch's first splat
-        const int cnt = (int)min((uint32_t)kBatch, tile_last - boff);
+        const uint32_t boff = (uint32_t)bi * kBwdBatch;            // 0-based list position of the batch's first splat
+        const int cnt = (int)min((uint32_t)kBwdBatch, tile_last - boff);
         uint32_t id; float4 raw, geo;
         stage_batch<true>(S, c, vals, packed, reach_bits, c.start + boff, cnt, id, raw, geo);
 #pragma unroll
-        for (int k = 0; k < kAccStride; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
+        for (int k = 0; k < 4 * kAccStride * kBwdBatch / 256; ++k) (&sAcc[0][0])[k * 256 + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {            // else nothing of this batch was blended by this wavefront (uniform per wave)
             // kSign: as in the forward kernel, the per-pixel sign test of the quadratic form is only kept for batches that
             // hold a splat whose conic is not safely positive definite
             auto walk = [&](auto sign_test) {
                 constexpr bool kSign = decltype(sign_test)::value;
-                for (int k = 3; k >= 0; --k) {
+                for (int k = kBwdBatch / 64 - 1; k >= 0; --k) {
                     unsigned long long m = uniform_u64(S.mask[wave][k]);
                     while (m) {
                         const int bit = 63 - __builtin_clzll(m);
                         m &= ~(1ull << bit);
                         const int j = k * 64 + bit;
                         const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
-                        const float4 a = S.rec[j].a;
-                        const float4 b = S.rec[j].b;
-                        const float cb = S.rec[j].c;
+                        const float4 a = S.a[j];
+                        const float4 b = S.b[j];
+                        const float cb = S.c[j];
                         const float dx = fx - a.x, dy = fy - a.y;
                         const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                         const float e = __builtin_amdgcn_exp2f(b.y - q);
@@ -294,19 +349,17 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
                         const float ds = (hit && e < kAlphaMax) ? -alpha * dL_dalpha : 0.f;
                         T = hit ? Tk : T;
                         Sfx += w * cg;
-                        const float dsx = ds * dx, dsy = ds * dy;
-                        const float v8[8] = {w * g0, w * g1, ds, dsx, dsy, dsx * dx, dsx * dy, dsy * dy};
-                        const float part = row_sum8(v8, bit1);
-                        const float blue = row_sum16(w * g2c);
-                        const float tot = sum_rows(blue_lane ? blue : part);
-                        int acc_base = kAccStride * j;
-                        asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (else a quarter-rate VALU mad)
-                        if (add_lane) atomicAdd(&sAcc[acc_base + acc_slot], tot);
+                        float* const rows = wr_row + 128 * nslot;
+                        rows[0] = ds;
+                        rows[64] = w;
+                        slot_acc = lane == nslot ? kAccStride * j : slot_acc;
+                        if (++nslot == kVisitSlots) { reduce_slots(kVisitSlots); nslot = 0; }
                     }
                 }
             };
-            if (S.definite[0] & S.definite[1] & S.definite[2] & S.definite[3]) walk(std::false_type{});
+            if (S.definite[0] & S.definite[1]) walk(std::false_type{});
             else walk(std::true_type{});
+            if (nslot) { reduce_slots(nslot); nslot = 0; }
         }
         __syncthreads();
         if ((int)threadIdx.x < cnt) {
@@ -315,15 +368,26 @@ __global__ __launch_bounds__(256) void k_composite_bwd(CamDev cam, const uint32_
             tile_rect(cam, geo.x, geo.y, __float_as_int(geo.z), x0, y0, x1, y1);
             const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
-                const float* acc = sAcc + kAccStride * threadIdx.x;
-                const float s0 = acc[2], s1 = acc[3], s2 = acc[4];
+                float acc[kAccStride];
+#pragma unroll
+                for (int k = 0; k < kAccStride; ++k) {
+                    const int e = kAccStride * (int)threadIdx.x + k;
+                    acc[k] = (sAcc[0][e] + sAcc[1][e]) + (sAcc[2][e] + sAcc[3][e]);
+                }
+                // from the tile's frame to offsets from the splat centre: dx = X0 + X, dy = Y0 + Y
+                const float X0 = (float)c.tx0 + 0.5f - geo.x, Y0 = (float)c.ty0 + 0.5f - geo.y;
+                const float m0 = acc[3], mx = acc[4], my = acc[5];
+                const float s0 = m0, s1 = X0 * m0 + mx, s2 = Y0 * m0 + my;
+                const float s3 = X0 * (X0 * m0 + 2.f * mx) + acc[6];
+                const float s4 = X0 * (Y0 * m0 + my) + Y0 * mx + acc[7];
+                const float s5 = Y0 * (Y0 * m0 + 2.f * my) + acc[8];
                 float4* dst = partial + (size_t)3 * u;
                 dst[0] = make_float4(-(raw.x * s1 + raw.y * s2), -(raw.z * s2 + raw.y * s1),          // d mean2d
-                                     0.5f * acc[5], acc[6]);                                         // d conic a, b
-                dst[1] = make_float4(0.5f * acc[7], raw.w > 0.f ? -s0 / raw.w : 0.f,                   // d conic c, d opacity
+                                     0.5f * s3, s4);                                                  // d conic a, b
+                dst[1] = make_float4(0.5f * s5, raw.w > 0.f ? -s0 / raw.w : 0.f,                       // d conic c, d opacity
                                      acc[0], acc[1]);                                                 // d red, d green
                 // d blue, then the stamp that tells the gather this record belongs to this backward call
-                dst[2] = make_float4(acc[8], 0.f, __uint_as_float(epoch_lo), __uint_as_float(epoch_hi));
+                dst[2] = make_float4(acc[2], 0.f, __uint_as_float(epoch_lo), __uint_as_float(epoch_hi));
             }
         }
         __syncthreads();   // sAcc and the stage are rewritten by the next batch
