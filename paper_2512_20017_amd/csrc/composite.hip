@@ -216,12 +216,15 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
 // the six moments follow from the moments of ds against 1, X, Y, X^2, XY, Y^2, whatever the splat), and one butterfly
 // over the row finishes four visits at once: about 13 vector instructions per visit instead of 39 when every visit
 // reduced its own nine products over the 64 lanes.
-// (Measured and dropped: the same contraction as sixteen v_mfma_f32_16x16x4_f32 per eight visits. An fp32 matrix
+// (Measured and dropped: one wavefront per tile that takes the four quadrants in turn, with no barriers and plain
+// read-modify-writes: 371 us against 239, the few tiles with thousands of splats then run four times longer on one
+// wavefront and the launch waits for them. Reading the next splat's staged record while the current one is worked on:
+// no change. The same contraction as sixteen v_mfma_f32_16x16x4_f32 per eight visits: an fp32 matrix
 // instruction holds the SIMD for its 32 cycles - plain vector instructions of other wavefronts do not overlap with it -
 // and only 9 of its 32 output columns are of use, so it came out slower than the butterfly it replaced.)
 //
-// No global atomics: the row results are added to an LDS accumulator per staged splat (ds_add_f32), where the four
-// quadrants meet, and the thread that staged splat j turns the tile's nine sums for it into gradients and writes them
+// No atomics, global or LDS: a wavefront stores the row results in its quadrant's accumulator of the staged splat, and
+// the thread that staged splat j adds the four quadrants' nine sums, turns them into gradients and writes them
 // to partial[u] (12 floats per pair), where u is the pair's position in the unsorted duplicate list (slot_base[id] +
 // rank of this tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them
 // up afterwards (k_gather_splat_grads).
