@@ -41,14 +41,37 @@ __device__ __forceinline__ float qform_min_rect(float A, float B, float C, float
 
 constexpr int kAccStride = 9;    // floats between the LDS accumulators of consecutive splats of a batch (odd)
 
-// LDS image of one staged batch of kB splats (kB a multiple of 64, at most the workgroup size)
+// LDS image of one staged batch of kB splats (kB a multiple of 64, at most the workgroup size). kPacked: the three
+// parts of a record in arrays of their own, 36 bytes a splat instead of 48 - for the backward kernel, whose occupancy
+// is set by its LDS (the forward kernel measured 7 % slower with it and keeps whole records, which one address serves).
+struct StageRec {
+    float4 a;                              // mx, my, A = log2e/2 * qa, B = log2e * qb
+    float4 b;                              // C = log2e/2 * qc, L = log2(opacity), red, green
+    float c, pad[3];                       // blue
+};
+template <int kB, bool kPacked>
+struct Stage;
 template <int kB>
-struct Stage {
-    float4 a[kB];                          // mx, my, A = log2e/2 * qa, B = log2e * qb
-    float4 b[kB];                          // C = log2e/2 * qc, L = log2(opacity), red, green
-    float c[kB];                           // blue
+struct Stage<kB, false> {
+    StageRec rec[kB];
     unsigned long long mask[4][kB / 64];   // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
     uint32_t definite[kB / 64];            // [staging wavefront]: all of its splats have a positive-definite conic, with margin
+    __device__ __forceinline__ void put(int j, const float4& a, const float4& b, float c) { rec[j].a = a; rec[j].b = b; rec[j].c = c; }
+    __device__ __forceinline__ float4 a(int j) const { return rec[j].a; }
+    __device__ __forceinline__ float4 b(int j) const { return rec[j].b; }
+    __device__ __forceinline__ float c(int j) const { return rec[j].c; }
+};
+template <int kB>
+struct Stage<kB, true> {
+    float4 va[kB];
+    float4 vb[kB];
+    float vc[kB];
+    unsigned long long mask[4][kB / 64];
+    uint32_t definite[kB / 64];
+    __device__ __forceinline__ void put(int j, const float4& a, const float4& b, float c) { va[j] = a; vb[j] = b; vc[j] = c; }
+    __device__ __forceinline__ float4 a(int j) const { return va[j]; }
+    __device__ __forceinline__ float4 b(int j) const { return vb[j]; }
+    __device__ __forceinline__ float c(int j) const { return vc[j]; }
 };
 
 // Stage list entries [first, first+count) of the tile, count <= kB: one per thread. Returns this thread's splat index, raw
@@ -57,8 +80,8 @@ struct Stage {
 // definite with a margin that rounding cannot bridge" (then the quadratic form is never negative and the per-pixel
 // sign test can be left out for the batch, see walk loops). The forward pass works the bits out and stores them
 // (kReuse = false); the backward pass, which walks a prefix of the same lists, reads them back.
-template <bool kReuse, int kB>
-__device__ __forceinline__ void stage_batch(Stage<kB>& S, const TileCtx& t, const uint32_t* __restrict__ vals,
+template <bool kReuse, int kB, bool kPacked>
+__device__ __forceinline__ void stage_batch(Stage<kB, kPacked>& S, const TileCtx& t, const uint32_t* __restrict__ vals,
                                             const Packed* __restrict__ packed, uint8_t* __restrict__ reach_bits, uint32_t first,
                                             int count, uint32_t& id, float4& raw, float4& geo)
 {
@@ -76,9 +99,7 @@ __device__ __forceinline__ void stage_batch(Stage<kB>& S, const TileCtx& t, cons
         geo = make_float4(mx, my, r2.y, 0.f);   // r2.y carries the extent (integer bits)
         const float A = 0.5f * kLog2e * qa, B = kLog2e * qb, C = 0.5f * kLog2e * qc;
         const float L = __log2f(o);
-        S.a[threadIdx.x] = make_float4(mx, my, A, B);
-        S.b[threadIdx.x] = make_float4(C, L, r1.z, r1.w);
-        S.c[threadIdx.x] = r2.x;
+        S.put(threadIdx.x, make_float4(mx, my, A, B), make_float4(C, L, r1.z, r1.w), r2.x);
         if (kReuse) {
             const uint32_t bits = reach_bits[first + threadIdx.x];
 #pragma unroll
@@ -123,7 +144,7 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
                                                        float* __restrict__ image, float* __restrict__ final_T,
                                                        uint32_t* __restrict__ last_idx)
 {
-    __shared__ Stage<kBatch> S;
+    __shared__ Stage<kBatch, false> S;
     const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
@@ -144,9 +165,9 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
             constexpr bool kSign = decltype(sign_test)::value;
             // alpha of one visit: everything that does not depend on the pixel's running state
             auto eval = [&](int j, float& alpha, bool& ok, float& r, float& g, float& bl) {
-                const float4 a = S.a[j];
-                const float4 b = S.b[j];
-                bl = S.c[j]; r = b.z; g = b.w;
+                const float4 a = S.a(j);
+                const float4 b = S.b(j);
+                bl = S.c(j); r = b.z; g = b.w;
                 const float dx = fx - a.x, dy = fy - a.y;
                 const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                 alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
@@ -229,9 +250,15 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
 // rank of this tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them
 // up afterwards (k_gather_splat_grads).
 constexpr int kVisitSlots = 4;    // visits staged per reduction: one per row of 16 lanes
-constexpr int kBwdBatch = 128;    // splats staged at a time by the backward kernel: what the per-quadrant accumulators leave room for
+#ifndef PBDR_BWD_BATCH
+#define PBDR_BWD_BATCH 64
+#endif
+#ifndef PBDR_BWD_OCC
+#define PBDR_BWD_OCC 7
+#endif
+constexpr int kBwdBatch = PBDR_BWD_BATCH;    // splats staged at a time by the backward kernel: what the per-quadrant accumulators leave room for
 
-__global__ __launch_bounds__(256, 5) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+__global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        uint8_t* __restrict__ reach_bits, const uint32_t* __restrict__ slot_base,
                                                        float bg0, float bg1, float bg2, const float* __restrict__ final_T,
@@ -239,7 +266,7 @@ __global__ __launch_bounds__(256, 5) void k_composite_bwd(CamDev cam, const uint
                                                        const float* __restrict__ dL_dimage, uint32_t cap,
                                                        const uint32_t* __restrict__ status, float4* __restrict__ partial)
 {
-    __shared__ Stage<kBwdBatch> S;
+    __shared__ Stage<kBwdBatch, true> S;
     // [quadrant][splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are
     // conflict-free): three colour sums, then the moments of ds against 1, X, Y, X^2, XY, Y^2. A wavefront visits a splat
     // at most once per batch, so it writes its quadrant's sums with plain stores; the thread that staged the splat adds
@@ -335,9 +362,9 @@ __global__ __launch_bounds__(256, 5) void k_composite_bwd(CamDev cam, const uint
                         m &= ~(1ull << bit);
                         const int j = k * 64 + bit;
                         const uint32_t pos = boff + (uint32_t)j + 1u;           // 1-based list position
-                        const float4 a = S.a[j];
-                        const float4 b = S.b[j];
-                        const float cb = S.c[j];
+                        const float4 a = S.a(j);
+                        const float4 b = S.b(j);
+                        const float cb = S.c(j);
                         const float dx = fx - a.x, dy = fy - a.y;
                         const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                         const float e = __builtin_amdgcn_exp2f(b.y - q);
@@ -360,7 +387,10 @@ __global__ __launch_bounds__(256, 5) void k_composite_bwd(CamDev cam, const uint
                     }
                 }
             };
-            if (S.definite[0] & S.definite[1]) walk(std::false_type{});
+            bool all_definite = true;
+#pragma unroll
+            for (int k = 0; k < kBwdBatch / 64; ++k) all_definite = all_definite && S.definite[k] != 0u;
+            if (all_definite) walk(std::false_type{});
             else walk(std::true_type{});
             if (nslot) { reduce_slots(nslot); nslot = 0; }
         }
