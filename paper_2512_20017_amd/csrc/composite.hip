@@ -279,7 +279,9 @@ __global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam,
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
     const size_t HW = (size_t)cam.W * cam.H;
-    const uint32_t epoch_lo = status[kStEpoch] + 1u, epoch_hi = status[kStEpoch + 1] + (epoch_lo == 0u ? 1u : 0u);      // this call, counted from one
+    // this call, counted from one (uniform values, kept on the scalar side: the kernel has no vector register to spare)
+    const uint32_t epoch_lo = __builtin_amdgcn_readfirstlane(status[kStEpoch]) + 1u;
+    const uint32_t epoch_hi = __builtin_amdgcn_readfirstlane(status[kStEpoch + 1]) + (epoch_lo == 0u ? 1u : 0u);
     float T = 1.f, g0 = 0.f, g1 = 0.f, g2c = 0.f;
     uint32_t last = 0;
     if (c.inside) {
@@ -293,7 +295,7 @@ __global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam,
     for (int d = 32; d >= 1; d >>= 1) wmax = max(wmax, (uint32_t)__shfl_xor((int)wmax, d, 64));
     if (lane == 0) sMax[wave] = wmax;
     __syncthreads();
-    const uint32_t tile_last = max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3]));
+    const uint32_t tile_last = __builtin_amdgcn_readfirstlane(max(max(sMax[0], sMax[1]), max(sMax[2], sMax[3])));
     if (tile_last == 0) return;
     const int tile_x = c.tix, tile_y = c.tiy;
     float* const sVw = sV[wave];
@@ -312,7 +314,6 @@ __global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam,
     }
     // tile coordinates of the first of the four pixels; the others are X + 1, X + 2, X + 3 on the same row
     const float PX = (float)((wave & 1) * 8 + 4 * (pg & 1)), PY = (float)((wave >> 1) * 8 + (pg >> 1));
-    const float PX2 = 2.f * PX, PXX = PX * PX, PYY = PY * PY;
     const float* const rd_row = sVw + 128 * (lane >> 4) + 4 * pg;
     float* const wr_row = sVw + lane;
     const bool bit1 = (lane & 2) != 0;
@@ -331,13 +332,14 @@ __global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam,
         const float s1 = d.y + 2.f * d.z + 3.f * d.w;             // sum of ds i and of ds i^2 over the pixels X + i
         const float s2 = d.y + 4.f * d.z + 9.f * d.w;
         const float mx = PX * m0 + s1;
-        const float mxx = PXX * m0 + (PX2 * s1 + s2);
+        const float mxx = PX * (mx + s1) + s2;                    // sum of ds (PX + i)^2 = PX (PX m0 + 2 s1) + s2
+        const float my = PY * m0;
         const float v8[8] = {w.x * G0.x + w.y * G0.y + w.z * G0.z + w.w * G0.w,
                              w.x * G1.x + w.y * G1.y + w.z * G1.z + w.w * G1.w,
                              w.x * G2.x + w.y * G2.y + w.z * G2.z + w.w * G2.w,
-                             m0, mx, PY * m0, mxx, PY * mx};
+                             m0, mx, my, mxx, PY * mx};
         const float part = row_sum8(v8, bit1);
-        const float ninth = row_sum16(PYY * m0);
+        const float ninth = row_sum16(PY * my);
         const int base = __shfl(slot_acc, lane >> 4, 64);
         if (add_lane && (lane >> 4) < count) sAccW[base + acc_slot] = ninth_lane ? ninth : part;
     };
@@ -408,7 +410,9 @@ __global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam,
                     acc[k] = (sAcc[0][e] + sAcc[1][e]) + (sAcc[2][e] + sAcc[3][e]);
                 }
                 // from the tile's frame to offsets from the splat centre: dx = X0 + X, dy = Y0 + Y
-                const float X0 = (float)c.tx0 + 0.5f - geo.x, Y0 = (float)c.ty0 + 0.5f - geo.y;
+                int ox = c.tx0, oy = c.ty0;
+                asm volatile("" : "+s"(ox), "+s"(oy));      // converted here, per batch: hoisted out of the loop the two floats cost vector registers the walk has not got
+                const float X0 = (float)ox + 0.5f - geo.x, Y0 = (float)oy + 0.5f - geo.y;
                 const float m0 = acc[3], mx = acc[4], my = acc[5];
                 const float s0 = m0, s1 = X0 * m0 + mx, s2 = Y0 * m0 + my;
                 const float s3 = X0 * (X0 * m0 + 2.f * mx) + acc[6];
