@@ -282,19 +282,21 @@ __global__ __launch_bounds__(256) void k_pack_dup2d(Splats2DDev sp, CamDev cam, 
 
 constexpr int kAccStride2D = 17;   // floats between the LDS accumulators of consecutive surfels of a batch (odd)
 
-// LDS image of one staged batch of surfels
+// LDS image of one staged batch of kB surfels (kB a multiple of 64, at most the workgroup size)
+template <int kB>
 struct Stage2D {
-    float4 a[kBatch];   // t0x, t0y, t1x, t1y
-    float4 b[kBatch];   // t2x, t2y, t2z, log2(opacity)
-    float4 c[kBatch];   // mx, my, red, green
-    float4 d[kBatch];   // blue, t0z, t1z, -
-    unsigned long long mask[4][4];
+    float4 a[kB];   // t0x, t0y, t1x, t1y
+    float4 b[kB];   // t2x, t2y, t2z, log2(opacity)
+    float4 c[kB];   // mx, my, red, green
+    float4 d[kB];   // blue, t0z, t1z, -
+    unsigned long long mask[4][kB / 64];
 };
 
 // Stage list entries [first, first+count): one per thread. A quadrant is kept for a splat if the bounding box of the
 // image of the disk rim where alpha falls to 1/255 (rho^2 = 2 ln(255 o)), or the low-pass support around the centre,
-// meets the quadrant's pixel centres; taken conservatively. All 256 threads must call it.
-__device__ __forceinline__ void stage_batch2d(Stage2D& S, const TileCtx& t, const uint32_t* __restrict__ vals,
+// meets the quadrant's pixel centres; taken conservatively. count <= kB. All 256 threads must call it.
+template <int kB>
+__device__ __forceinline__ void stage_batch2d(Stage2D<kB>& S, const TileCtx& t, const uint32_t* __restrict__ vals,
                                               const Packed2D* __restrict__ packed, uint32_t first, int count, uint32_t& id,
                                               float4& r0, float4& r1, float4& r2, float4& r3)
 {
@@ -342,7 +344,7 @@ __device__ __forceinline__ void stage_batch2d(Stage2D& S, const TileCtx& t, cons
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const unsigned long long m = __ballot(reach[q]);
-        if (lane == 0) S.mask[q][wave] = m;
+        if (lane == 0 && wave < kB / 64) S.mask[q][wave] = m;
     }
 }
 
@@ -371,7 +373,7 @@ __global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint3
                                                          float bg0, float bg1, float bg2, float* __restrict__ image,
                                                          float* __restrict__ final_T, uint32_t* __restrict__ last_idx)
 {
-    __shared__ Stage2D S;
+    __shared__ Stage2D<kBatch> S;
     const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int wave = threadIdx.x >> 6;
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
@@ -448,17 +450,21 @@ __global__ __launch_bounds__(256) void k_composite2d_fwd(CamDev cam, const uint3
 //   dT_0 = -sum dL/dh_u, dT_1 = -sum dL/dh_v, dT_2 = mx sum dL/dh_u + my sum dL/dh_v - T_1' x Sx - Sy x T_0'.
 // Together with 3 colour sums, d opacity and the 2 low-pass sums for mean2d: 15 sums per splat, through two row
 // butterflies, an LDS accumulator for the tile and one 64-byte record per (tile, splat) pair.
-__global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+constexpr int kBwdBatch2D = 64;    // surfels staged at a time by the backward kernel: what the per-quadrant accumulators leave room for
+
+__global__ __launch_bounds__(256, 6) void k_composite2d_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                          const uint32_t* __restrict__ vals, const Packed2D* __restrict__ packed,
                                                          const uint32_t* __restrict__ slot_base, float bg0, float bg1, float bg2,
                                                          const float* __restrict__ final_T, const uint32_t* __restrict__ last_idx,
                                                          const float* __restrict__ dL_dimage, uint32_t cap,
                                                          float4* __restrict__ partial)
 {
-    __shared__ Stage2D S;
-    // [splat of the batch][value], 17 floats apart (odd: the adds of one visit and the per-thread reads at the end of
-    // a batch spread over the LDS banks)
-    __shared__ float sAcc[kAccStride2D * kBatch];
+    __shared__ Stage2D<kBwdBatch2D> S;
+    // [quadrant][splat of the batch][value], 17 floats apart (odd: the stores of one visit and the per-thread reads at
+    // the end of a batch spread over the LDS banks). A wavefront visits a splat at most once per batch, so it writes its
+    // quadrant's sums with plain stores and the thread that staged the splat adds the four up: no LDS float atomics,
+    // which cost the LDS about 2.5 cycles per active lane.
+    __shared__ float sAcc[4][kAccStride2D * kBwdBatch2D];
     __shared__ uint32_t sMax[4];
     const TileCtx c = tile_ctx(cam, ranges, tile_order);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -498,17 +504,18 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
     if (tile_last == 0) return;
     const bool bit1 = (lane & 2) != 0;
     const int acc_slot = ((lane & 1) ? 8 : 0) + ((lane >> 1) & 7);     // see row_sum8: odd lanes take the second eight sums
-    const int nbatch = (int)((tile_last + kBatch - 1) / kBatch);
+    float* const sAccW = sAcc[wave];
+    const int nbatch = (int)((tile_last + kBwdBatch2D - 1) / kBwdBatch2D);
     for (int bi = nbatch - 1; bi >= 0; --bi) {
-        const uint32_t boff = (uint32_t)bi * kBatch;
-        const int cnt = (int)min((uint32_t)kBatch, tile_last - boff);
+        const uint32_t boff = (uint32_t)bi * kBwdBatch2D;
+        const int cnt = (int)min((uint32_t)kBwdBatch2D, tile_last - boff);
         uint32_t id; float4 q0, q1, q2, q3;
         stage_batch2d(S, c, vals, packed, c.start + boff, cnt, id, q0, q1, q2, q3);
 #pragma unroll
-        for (int k = 0; k < kAccStride2D; ++k) sAcc[k * kBatch + threadIdx.x] = 0.f;
+        for (int k = 0; k < 4 * kAccStride2D * kBwdBatch2D / 256; ++k) (&sAcc[0][0])[k * 256 + threadIdx.x] = 0.f;
         __syncthreads();
         if (wmax > boff) {
-            for (int k = 3; k >= 0; --k) {
+            for (int k = kBwdBatch2D / 64 - 1; k >= 0; --k) {
                 unsigned long long m = uniform_u64(S.mask[wave][k]);
                 while (m) {
                     const int bit = 63 - __builtin_clzll(m);
@@ -548,11 +555,11 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
                     const float pa = row_sum8(va, bit1);
                     const float pb = row_sum8(vb, bit1);
                     // even lanes of a row keep the first eight sums, odd lanes (their copies) take the second eight;
-                    // the four rows are added lane by lane, and the 16 lanes of the last row issue the one LDS add
+                    // the four rows are added lane by lane, and the 16 lanes of the last row store the sums
                     const float tot = sum_rows((lane & 1) ? pb : pa);
                     int acc_base = kAccStride2D * j;
                     asm volatile("" : "+s"(acc_base));      // keep the product on the scalar unit (as in the 3D kernel)
-                    if (lane >= 48) atomicAdd(&sAcc[acc_base + acc_slot], tot);
+                    if (lane >= 48) sAccW[acc_base + acc_slot] = tot;
                 }
             }
         }
@@ -562,7 +569,12 @@ __global__ __launch_bounds__(256) void k_composite2d_bwd(CamDev cam, const uint3
             tile_rect(cam, q2.x, q2.y, __float_as_int(q3.y), x0, y0, x1, y1);
             const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
-                const float* acc = sAcc + kAccStride2D * threadIdx.x;
+                float acc[15];
+#pragma unroll
+                for (int k = 0; k < 15; ++k) {
+                    const int e = kAccStride2D * (int)threadIdx.x + k;
+                    acc[k] = (sAcc[0][e] + sAcc[1][e]) + (sAcc[2][e] + sAcc[3][e]);
+                }
                 const float s0[3] = {acc[0], acc[1], acc[2]};
                 const float sx[3] = {acc[3], acc[4], acc[5]};
                 const float sy[3] = {acc[6], acc[7], acc[8]};
