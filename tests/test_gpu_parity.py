@@ -114,6 +114,23 @@ def test_composite_backward_matches_oracle(case):
     assert np.abs(ref["mean2d"]).max() > 0
 
 
+def test_render_is_bitwise_repeatable(case):
+    """No result of the rendering path goes through a floating-point atomic: two calls on the same inputs give the same
+    bits, image and gradients alike (the four quadrants of a tile and the pairs of a point are added in a fixed order)."""
+    view, cam = case["view"], case["cam"]
+    W, H = cam["width"], cam["height"]
+    G = np.random.default_rng(5).normal(size=(H, W, 3)).astype(np.float32)
+    runs = []
+    for _ in range(3):
+        fwd = view.render_fwd(BG)
+        got = view.render_bwd(BG, G)
+        runs.append((fwd["image"].copy(), {k: got[k].copy() for k in ("mean2d", "conic", "opacity", "color")}))
+    for img, g in runs[1:]:
+        assert np.array_equal(img, runs[0][0])
+        for k in g:
+            assert np.array_equal(g[k], runs[0][1][k]), k
+
+
 def test_splatting_backward_matches_oracle(case):
     sc, cam, n = case["sc"], case["cam"], case["n"]
     rng = np.random.default_rng(4)
