@@ -250,15 +250,10 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
 // rank of this tile in the splat's rectangle). A splat's pairs are contiguous there, so a per-splat kernel adds them
 // up afterwards (k_gather_splat_grads).
 constexpr int kVisitSlots = 4;    // visits staged per reduction: one per row of 16 lanes
-#ifndef PBDR_BWD_BATCH
-#define PBDR_BWD_BATCH 64
-#endif
-#ifndef PBDR_BWD_OCC
-#define PBDR_BWD_OCC 7
-#endif
-constexpr int kBwdBatch = PBDR_BWD_BATCH;    // splats staged at a time by the backward kernel: what the per-quadrant accumulators leave room for
+constexpr int kBwdBatch = 64;    // splats staged at a time by the backward kernel: what the per-quadrant accumulators leave room for
 
-__global__ __launch_bounds__(256, PBDR_BWD_OCC) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+// 7 workgroups per compute unit: 72 registers
+__global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
                                                        uint8_t* __restrict__ reach_bits, const uint32_t* __restrict__ slot_base,
                                                        float bg0, float bg1, float bg2, const float* __restrict__ final_T,

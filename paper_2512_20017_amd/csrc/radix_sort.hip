@@ -605,18 +605,6 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t* base, uin
     }
 }
 
-#ifdef PBDR_EXP_TIMING
-__device__ unsigned long long g_dbg[4 * 65536];
-extern "C" int pbdr_dbg_fetch(unsigned long long* host, int count)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(unsigned long long) * (size_t)count);
-}
-#define DBG_BEGIN const unsigned long long dbg_t0 = wall_clock64();
-#define DBG_END(len) if ((threadIdx.x & 63) == 0) { const size_t q = ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4; if (q + 3 < 4 * 65536) { g_dbg[q] = (len); g_dbg[q + 1] = dbg_t0; g_dbg[q + 2] = wall_clock64(); g_dbg[q + 3] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)); } }
-#else
-#define DBG_BEGIN
-#define DBG_END(len)
-#endif
 __global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                             uint32_t ntiles, const uint32_t* __restrict__ status,
                                                             const uint32_t* __restrict__ depth_bits, uint32_t cap,
@@ -628,7 +616,6 @@ __global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __re
     // 0 .. nbig - 1 take one of those each; every later workgroup takes four shorter lists, one per wavefront.
     const uint32_t nbig = min(status[kStNumBig], ntiles);
     const int wave = threadIdx.x >> 6;
-    DBG_BEGIN
     if (blockIdx.x >= nbig) {
         const uint32_t idx = nbig + (blockIdx.x - nbig) * 4u + (uint32_t)wave;
         if (idx >= ntiles) return;
@@ -637,7 +624,6 @@ __global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __re
         if (e <= s + 1u) return;
         // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
         if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
-        DBG_END(e - s)
         return;
     }
     WgSortLds& S = U.wg;
@@ -645,8 +631,8 @@ __global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __re
     const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
     if (e <= s + 1u) return;                     // uniform for the workgroup
     const uint32_t L = e - s;
-    if (L <= (uint32_t)kWgKeyMax) { wg_sort_list<true>(S, L, depth_bits, valsA + s, keysA + s); DBG_END(L) return; }
-    if (L <= (uint32_t)kWgListMax) { wg_sort_list<false>(S, L, depth_bits, valsA + s, keysA + s); DBG_END(L) return; }
+    if (L <= (uint32_t)kWgKeyMax) { wg_sort_list<true>(S, L, depth_bits, valsA + s, keysA + s); return; }
+    if (L <= (uint32_t)kWgListMax) { wg_sort_list<false>(S, L, depth_bits, valsA + s, keysA + s); return; }
     // through global memory: keys of the list and the bit positions in which they differ
     const int lane = threadIdx.x & 63;
     const uint32_t k0 = depth_bits[valsA[s]];
@@ -673,7 +659,6 @@ __global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __re
     }
     if (passes & 1)
         for (uint32_t i = threadIdx.x; i < L; i += 256u) valsA[s + i] = valsB[s + i];
-    DBG_END(L)
 }
 
 hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_order, uint32_t ntiles, const uint32_t* status,
