@@ -86,7 +86,7 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->off_chunk_rank = take(((size_t)cap / 256 + 2) * sizeof(uint32_t));         // see pair_reduce.h
     L->off_carry = take(((size_t)cap / 256 + 2) * 36 * sizeof(float));
     L->off_grad_rec = take((size_t)n * L->partial_vec4 * 4 * sizeof(float));      // per-point gradient records, by point index
-    L->off_reach = take((size_t)cap);      // per sorted pair: which quadrants of its tile the splat reaches (forward -> backward)
+    L->off_reach = take((size_t)4 * cap);  // per sorted pair and quadrant of its tile: can the splat reach it (forward -> backward)
     L->off_tile_order = take((size_t)L->tiles * sizeof(uint32_t));   // tiles in the order the compositing kernels take them
     L->total = off;
     return true;

@@ -74,24 +74,47 @@ struct Stage<kB, true> {
     __device__ __forceinline__ float c(int j) const { return vc[j]; }
 };
 
-// Stage list entries [first, first+count) of the tile, count <= kB: one per thread. Returns this thread's splat index, raw
-// conic/opacity and (mean2d, extent) for callers that need them (backward). All 256 threads must call it.
-// reach: one byte per list position, bit q = "this splat can reach quadrant q", bit 4 = "its conic is positive
-// definite with a margin that rounding cannot bridge" (then the quadratic form is never negative and the per-pixel
-// sign test can be left out for the batch, see walk loops). The forward pass works the bits out and stores them
-// (kReuse = false); the backward pass, which walks a prefix of the same lists, reads them back.
-template <bool kReuse, int kB, bool kPacked>
-__device__ __forceinline__ void stage_batch(Stage<kB, kPacked>& S, const TileCtx& t, const uint32_t* __restrict__ vals,
-                                            const Packed* __restrict__ packed, uint8_t* __restrict__ reach_bits, uint32_t first,
-                                            int count, uint32_t& id, float4& raw, float4& geo)
+// Can the splat reach the quadrant whose first pixel centre lies at (lx, ly) from the splat centre, with alpha >= 1/255,
+// i.e. q(d) <= tau = L + log2(255) somewhere on it? Exact minimum of the form over the rectangle, kept when in doubt:
+// rounding can only keep more. pd: the conic is positive definite (else every quadrant is kept).
+__device__ __forceinline__ bool quadrant_reach(float A, float B, float C, float tau, bool pd, float lx, float ly)
+{
+    if (tau < -0.05f) return false;
+    if (!pd) return true;
+    const float hx = lx + 7.f, hy = ly + 7.f;
+    const float mn = qform_min_rect(A, B, C, lx, hx, ly, hy);
+    const float mxd = fmaxf(fabsf(lx), fabsf(hx)), myd = fmaxf(fabsf(ly), fabsf(hy));
+    const float big = A * mxd * mxd + C * myd * myd + fabsf(B) * mxd * myd;
+    return !(mn > tau + 0.05f + 4e-6f * big);
+}
+
+// "positive definite with a margin that rounding cannot bridge": the quadratic form is then never negative and the
+// per-pixel sign test can be left out (see the walk loops)
+__device__ __forceinline__ bool safely_definite(float A, float B, float C)
+{
+    return (A > 0.f) && (C > 0.f) && (4.f * A * C > 1.00001f * (B * B));
+}
+
+// Backward pass: stage list entries [first, first+count) of the tile, count <= kB, one per thread. Returns this thread's
+// splat index, raw conic/opacity and (mean2d, extent). All 256 threads must call it.
+// reach_bits: four bytes per list position, one per quadrant, written by the forward pass's wavefront of that quadrant
+// for the positions it staged (bit 0: the splat can reach the quadrant). The backward pass walks a prefix of what each
+// forward wavefront walked, so every byte it acts on was written by this view's forward pass; the bytes of positions a
+// quadrant never came to are stale or zero, and the walk of that quadrant never gets there (its pixels' last indices
+// end earlier).
+template <int kB, bool kPacked>
+__device__ __forceinline__ void stage_batch_bwd(Stage<kB, kPacked>& S, const uint32_t* __restrict__ vals,
+                                                const Packed* __restrict__ packed, const uint32_t* __restrict__ reach_words,
+                                                uint32_t first, int count, uint32_t& id, float4& raw, float4& geo)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool have = (int)threadIdx.x < count;
-    bool reach[4] = {false, false, false, false};
+    uint32_t bits = 0;
     bool definite = true;
     id = 0; raw = make_float4(0.f, 0.f, 0.f, 0.f); geo = raw;
     if (have) {
         id = vals[first + threadIdx.x];
+        bits = reach_words[first + threadIdx.x];
         const float4* rec = reinterpret_cast<const float4*>(packed + id);
         const float4 r0 = rec[0], r1 = rec[1], r2 = rec[2];
         const float mx = r0.x, my = r0.y, qa = r0.z, qb = r0.w, qc = r1.x, o = r1.y;
@@ -100,43 +123,22 @@ __device__ __forceinline__ void stage_batch(Stage<kB, kPacked>& S, const TileCtx
         const float A = 0.5f * kLog2e * qa, B = kLog2e * qb, C = 0.5f * kLog2e * qc;
         const float L = __log2f(o);
         S.put(threadIdx.x, make_float4(mx, my, A, B), make_float4(C, L, r1.z, r1.w), r2.x);
-        if (kReuse) {
-            const uint32_t bits = reach_bits[first + threadIdx.x];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) reach[q] = ((bits >> q) & 1u) != 0;
-            definite = ((bits >> 4) & 1u) != 0;
-        } else {
-            // alpha >= 1/255  <=>  q(d) <= L + log2(255)
-            const float tau = L + kLog2_255;
-            const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
-            definite = (A > 0.f) && (C > 0.f) && (4.f * A * C > 1.00001f * (B * B));
-            if (!(tau < -0.05f)) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float lx = (float)(t.tx0 + (q & 1) * 8) + 0.5f - mx, hx = lx + 7.f;
-                    const float ly = (float)(t.ty0 + (q >> 1) * 8) + 0.5f - my, hy = ly + 7.f;
-                    bool keep = true;
-                    if (pd) {
-                        const float mn = qform_min_rect(A, B, C, lx, hx, ly, hy);
-                        const float mxd = fmaxf(fabsf(lx), fabsf(hx)), myd = fmaxf(fabsf(ly), fabsf(hy));
-                        const float big = A * mxd * mxd + C * myd * myd + fabsf(B) * mxd * myd;
-                        keep = !(mn > tau + 0.05f + 4e-6f * big);   // conservative: rounding can only keep more
-                    }
-                    reach[q] = keep;
-                }
-            }
-            reach_bits[first + threadIdx.x] = (uint8_t)((reach[0] ? 1u : 0u) | (reach[1] ? 2u : 0u) | (reach[2] ? 4u : 0u) |
-                                                        (reach[3] ? 8u : 0u) | (definite ? 16u : 0u));
-        }
+        definite = safely_definite(A, B, C);
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const unsigned long long m = __ballot(reach[q]);
+        const unsigned long long m = __ballot(((bits >> (8 * q)) & 1u) != 0u);
         if (lane == 0 && wave < kB / 64) S.mask[q][wave] = m;
     }
     const unsigned long long dm = __ballot(definite);
     if (lane == 0 && wave < kB / 64) S.definite[wave] = (dm == ~0ull) ? 1u : 0u;
 }
+
+// Forward. The four wavefronts of a tile do not wait for each other: each stages the list for itself, 64 splats at a
+// time (one per lane, into its own 3 KB of LDS), tests them against its own quadrant only, and stops when its 64 pixels
+// have ended. (When the four staged 256 splats together, every batch ended with the quadrants waiting at a barrier for
+// the one with the most splats to visit; the records are read four times now, from L2.)
+constexpr int kFwdBatch = 64;
 
 __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                        const uint32_t* __restrict__ vals, const Packed* __restrict__ packed,
@@ -144,20 +146,39 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
                                                        float* __restrict__ image, float* __restrict__ final_T,
                                                        uint32_t* __restrict__ last_idx)
 {
-    __shared__ Stage<kBatch, false> S;
+    __shared__ StageRec sRec[4][kFwdBatch];
     const TileCtx c = tile_ctx(cam, ranges, tile_order);
-    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    StageRec* const rec_w = sRec[wave];
     const float fx = (float)c.px + 0.5f, fy = (float)c.py + 0.5f;
+    // centre of the quadrant's first pixel
+    const float qx0 = (float)(c.tx0 + (wave & 1) * 8) + 0.5f, qy0 = (float)(c.ty0 + (wave >> 1) * 8) + 0.5f;
     float T = 1.f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
     uint32_t last = 0;
     bool live = c.inside;
-    for (uint32_t base = c.start; base < c.end; base += kBatch) {
-        if (__syncthreads_count(live) == 0) break;   // also fences the previous batch's LDS reads
-        const int cnt = (int)min((uint32_t)kBatch, c.end - base);
-        uint32_t id; float4 raw, geo;
-        stage_batch<false>(S, c, vals, packed, reach_bits, base, cnt, id, raw, geo);
-        __syncthreads();
-        if (__ballot(live) == 0ull) continue;          // this quadrant is finished (uniform per wavefront)
+    for (uint32_t base = c.start; base < c.end; base += kFwdBatch) {
+        if (__ballot(live) == 0ull) break;           // every pixel of the quadrant has ended
+        const int cnt = (int)min((uint32_t)kFwdBatch, c.end - base);
+        bool reach = false, definite = true;
+        if (lane < cnt) {
+            const uint32_t id = vals[base + lane];
+            const float4* rec = reinterpret_cast<const float4*>(packed + id);
+            const float4 r0 = rec[0], r1 = rec[1], r2 = rec[2];
+            const float mx = r0.x, my = r0.y;
+            const float A = 0.5f * kLog2e * r0.z, B = kLog2e * r0.w, C = 0.5f * kLog2e * r1.x;
+            const float L = __log2f(r1.y);
+            rec_w[lane].a = make_float4(mx, my, A, B);
+            rec_w[lane].b = make_float4(C, L, r1.z, r1.w);
+            rec_w[lane].c = r2.x;
+            const bool pd = (A > 0.f) && (C > 0.f) && (4.f * A * C > B * B);
+            definite = safely_definite(A, B, C);
+            reach = quadrant_reach(A, B, C, L + kLog2_255, pd, qx0 - mx, qy0 - my);      // alpha >= 1/255 <=> q(d) <= L + log2(255)
+            reach_bits[(size_t)4 * (base + lane) + wave] = reach ? 1 : 0;
+        }
+        unsigned long long m = __ballot(reach);
+        const bool all_definite = __ballot(!definite) == 0ull;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         const uint32_t pos0 = base - c.start + 1u;
         // kSign: keep the "quadratic form < 0 -> skip" test per pixel; not needed when every splat of the batch has a
         // positive-definite conic (every state that pbdr_preprocess writes)
@@ -165,9 +186,9 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
             constexpr bool kSign = decltype(sign_test)::value;
             // alpha of one visit: everything that does not depend on the pixel's running state
             auto eval = [&](int j, float& alpha, bool& ok, float& r, float& g, float& bl) {
-                const float4 a = S.a(j);
-                const float4 b = S.b(j);
-                bl = S.c(j); r = b.z; g = b.w;
+                const float4 a = rec_w[j].a;
+                const float4 b = rec_w[j].b;
+                bl = rec_w[j].c; r = b.z; g = b.w;
                 const float dx = fx - a.x, dy = fy - a.y;
                 const float q = (a.z * dx + a.w * dy) * dx + b.x * dy * dy;
                 alpha = fminf(kAlphaMax, __builtin_amdgcn_exp2f(b.y - q));
@@ -185,33 +206,32 @@ __global__ __launch_bounds__(256) void k_composite_fwd(CamDev cam, const uint32_
                 T = blend ? Tn : T;
                 last = blend ? pos0 + (uint32_t)j : last;
             };
-            for (int k = 0; k < 4; ++k) {
-                unsigned long long m = uniform_u64(S.mask[wave][k]);
-                // two visits per trip while there are two: their alphas do not depend on each other, which gives the
-                // vector ALU two independent chains to interleave; the blends stay in list order (four per trip measured slower)
-                while (m & (m - 1ull)) {
-                    const int j0 = k * 64 + __builtin_ctzll(m);
-                    m &= m - 1ull;
-                    const int j1 = k * 64 + __builtin_ctzll(m);
-                    m &= m - 1ull;
-                    float al0, r0, g0, b0, al1, r1, g1, b1;
-                    bool ok0, ok1;
-                    eval(j0, al0, ok0, r0, g0, b0);
-                    eval(j1, al1, ok1, r1, g1, b1);
-                    blend_one(j0, al0, ok0, r0, g0, b0);
-                    blend_one(j1, al1, ok1, r1, g1, b1);
-                }
-                if (m) {
-                    const int j0 = k * 64 + __builtin_ctzll(m);
-                    float al0, r0, g0, b0;
-                    bool ok0;
-                    eval(j0, al0, ok0, r0, g0, b0);
-                    blend_one(j0, al0, ok0, r0, g0, b0);
-                }
+            // two visits per trip while there are two: their alphas do not depend on each other, which gives the
+            // vector ALU two independent chains to interleave; the blends stay in list order (four per trip measured slower)
+            while (m & (m - 1ull)) {
+                const int j0 = __builtin_ctzll(m);
+                m &= m - 1ull;
+                const int j1 = __builtin_ctzll(m);
+                m &= m - 1ull;
+                float al0, r0, g0, b0, al1, r1, g1, b1;
+                bool ok0, ok1;
+                eval(j0, al0, ok0, r0, g0, b0);
+                eval(j1, al1, ok1, r1, g1, b1);
+                blend_one(j0, al0, ok0, r0, g0, b0);
+                blend_one(j1, al1, ok1, r1, g1, b1);
+            }
+            if (m) {
+                const int j0 = __builtin_ctzll(m);
+                float al0, r0, g0, b0;
+                bool ok0;
+                eval(j0, al0, ok0, r0, g0, b0);
+                blend_one(j0, al0, ok0, r0, g0, b0);
             }
         };
-        if (S.definite[0] & S.definite[1] & S.definite[2] & S.definite[3]) walk(std::false_type{});
+        if (all_definite) walk(std::false_type{});
         else walk(std::true_type{});
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();             // the next batch overwrites the staged records
     }
     if (c.inside) {
         const size_t HW = (size_t)cam.W * cam.H;
@@ -343,7 +363,7 @@ __global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint
         const uint32_t boff = (uint32_t)bi * kBwdBatch;            // 0-based list position of the batch's first splat
         const int cnt = (int)min((uint32_t)kBwdBatch, tile_last - boff);
         uint32_t id; float4 raw, geo;
-        stage_batch<true>(S, c, vals, packed, reach_bits, c.start + boff, cnt, id, raw, geo);
+        stage_batch_bwd(S, vals, packed, reinterpret_cast<const uint32_t*>(reach_bits), c.start + boff, cnt, id, raw, geo);
 #pragma unroll
         for (int k = 0; k < 4 * kAccStride * kBwdBatch / 256; ++k) (&sAcc[0][0])[k * 256 + threadIdx.x] = 0.f;
         __syncthreads();

@@ -33,9 +33,9 @@ def test_workspace_bytes():
     assert 0 < small < big
     assert big % 256 == 0
     # dominated by 116 B/point (raster record, tile count, offset, slot base, rank -> point, depth bits, 48-byte
-    # gradient record) + 74.1 B/pair (tile keys, values, their ping-pong copies, 48 B of partial gradient sums, 8 B of
-    # inspection keys, per-2048-pair digit counts, per-256-pair chunk data, one byte of quadrant bits)
-    assert abs(big - (116e6 + 74.1 * 8e6)) < 0.02 * big
+    # gradient record) + 77.1 B/pair (tile keys, values, their ping-pong copies, 48 B of partial gradient sums, 8 B of
+    # inspection keys, per-2048-pair digit counts, per-256-pair chunk data, four bytes of quadrant bits)
+    assert abs(big - (116e6 + 77.1 * 8e6)) < 0.02 * big
     # surfels: 32 B more per point (64-byte raster and gradient records) and 16 B more per pair (64 B of partial sums)
     big2 = B.pbdr2d_workspace_bytes(1_000_000, 1920, 1080, 8_000_000)
     assert abs((big2 - big) - (32e6 + 16 * 8e6)) < 1e5
