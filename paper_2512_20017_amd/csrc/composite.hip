@@ -41,33 +41,23 @@ __device__ __forceinline__ float qform_min_rect(float A, float B, float C, float
 
 constexpr int kAccStride = 9;    // floats between the LDS accumulators of consecutive splats of a batch (odd)
 
-// LDS image of one staged batch of kB splats (kB a multiple of 64, at most the workgroup size). kPacked: the three
-// parts of a record in arrays of their own, 36 bytes a splat instead of 48 - for the backward kernel, whose occupancy
-// is set by its LDS (the forward kernel measured 7 % slower with it and keeps whole records, which one address serves).
+// A staged splat of the forward kernel: 48 bytes, so that one LDS address register serves the three reads of a visit.
 struct StageRec {
     float4 a;                              // mx, my, A = log2e/2 * qa, B = log2e * qb
     float4 b;                              // C = log2e/2 * qc, L = log2(opacity), red, green
     float c, pad[3];                       // blue
 };
-template <int kB, bool kPacked>
-struct Stage;
+
+// LDS image of one staged batch of kB splats of the backward kernel (kB a multiple of 64, at most the workgroup size):
+// the three parts of a record in arrays of their own, 36 bytes a splat - that kernel's occupancy is set by its LDS
+// (the forward kernel measured 7 % slower with this layout).
 template <int kB>
-struct Stage<kB, false> {
-    StageRec rec[kB];
-    unsigned long long mask[4][kB / 64];   // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
-    uint32_t definite[kB / 64];            // [staging wavefront]: all of its splats have a positive-definite conic, with margin
-    __device__ __forceinline__ void put(int j, const float4& a, const float4& b, float c) { rec[j].a = a; rec[j].b = b; rec[j].c = c; }
-    __device__ __forceinline__ float4 a(int j) const { return rec[j].a; }
-    __device__ __forceinline__ float4 b(int j) const { return rec[j].b; }
-    __device__ __forceinline__ float c(int j) const { return rec[j].c; }
-};
-template <int kB>
-struct Stage<kB, true> {
+struct Stage {
     float4 va[kB];
     float4 vb[kB];
     float vc[kB];
-    unsigned long long mask[4][kB / 64];
-    uint32_t definite[kB / 64];
+    unsigned long long mask[4][kB / 64];   // [quadrant][staging wavefront]: which of its 64 splats reach the quadrant
+    uint32_t definite[kB / 64];            // [staging wavefront]: all of its splats have a positive-definite conic, with margin
     __device__ __forceinline__ void put(int j, const float4& a, const float4& b, float c) { va[j] = a; vb[j] = b; vc[j] = c; }
     __device__ __forceinline__ float4 a(int j) const { return va[j]; }
     __device__ __forceinline__ float4 b(int j) const { return vb[j]; }
@@ -102,8 +92,8 @@ __device__ __forceinline__ bool safely_definite(float A, float B, float C)
 // forward wavefront walked, so every byte it acts on was written by this view's forward pass; the bytes of positions a
 // quadrant never came to are stale or zero, and the walk of that quadrant never gets there (its pixels' last indices
 // end earlier).
-template <int kB, bool kPacked>
-__device__ __forceinline__ void stage_batch_bwd(Stage<kB, kPacked>& S, const uint32_t* __restrict__ vals,
+template <int kB>
+__device__ __forceinline__ void stage_batch_bwd(Stage<kB>& S, const uint32_t* __restrict__ vals,
                                                 const Packed* __restrict__ packed, const uint32_t* __restrict__ reach_words,
                                                 uint32_t first, int count, uint32_t& id, float4& raw, float4& geo)
 {
@@ -281,7 +271,7 @@ __global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint
                                                        const float* __restrict__ dL_dimage, uint32_t cap,
                                                        const uint32_t* __restrict__ status, float4* __restrict__ partial)
 {
-    __shared__ Stage<kBwdBatch, true> S;
+    __shared__ Stage<kBwdBatch> S;
     // [quadrant][splat of the batch][value], 9 floats apart (odd: the per-thread reads at the end of a batch are
     // conflict-free): three colour sums, then the moments of ds against 1, X, Y, X^2, XY, Y^2. A wavefront visits a splat
     // at most once per batch, so it writes its quadrant's sums with plain stores; the thread that staged the splat adds
