@@ -95,7 +95,7 @@ __device__ __forceinline__ bool safely_definite(float A, float B, float C)
 template <int kB>
 __device__ __forceinline__ void stage_batch_bwd(Stage<kB>& S, const uint32_t* __restrict__ vals,
                                                 const Packed* __restrict__ packed, const uint32_t* __restrict__ reach_words,
-                                                uint32_t first, int count, uint32_t& id, float4& raw, float4& geo)
+                                                uint32_t first, int count, uint32_t id_ahead, uint32_t& id, float4& raw, float4& geo)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool have = (int)threadIdx.x < count;
@@ -103,7 +103,7 @@ __device__ __forceinline__ void stage_batch_bwd(Stage<kB>& S, const uint32_t* __
     bool definite = true;
     id = 0; raw = make_float4(0.f, 0.f, 0.f, 0.f); geo = raw;
     if (have) {
-        id = vals[first + threadIdx.x];
+        id = id_ahead;                 // vals[first + threadIdx.x], asked for a batch ahead
         bits = reach_words[first + threadIdx.x];
         const float4* rec = reinterpret_cast<const float4*>(packed + id);
         const float4 r0 = rec[0], r1 = rec[1], r2 = rec[2];
@@ -349,11 +349,19 @@ __global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint
         if (add_lane && (lane >> 4) < count) sAccW[base + acc_slot] = ninth_lane ? ninth : part;
     };
     const int nbatch = (int)((tile_last + kBwdBatch - 1) / kBwdBatch);
+    // the splat index of a thread's entry is asked for one batch ahead: one trip to memory per batch (the record) instead
+    // of two in a row
+    uint32_t id_ahead = 0;
+    {
+        const uint32_t p = (uint32_t)(nbatch - 1) * kBwdBatch + threadIdx.x;
+        if (threadIdx.x < kBwdBatch && p < tile_last) id_ahead = vals[c.start + p];
+    }
     for (int bi = nbatch - 1; bi >= 0; --bi) {
         const uint32_t boff = (uint32_t)bi * kBwdBatch;            // 0-based list position of the batch's first splat
         const int cnt = (int)min((uint32_t)kBwdBatch, tile_last - boff);
         uint32_t id; float4 raw, geo;
-        stage_batch_bwd(S, vals, packed, reinterpret_cast<const uint32_t*>(reach_bits), c.start + boff, cnt, id, raw, geo);
+        stage_batch_bwd(S, vals, packed, reinterpret_cast<const uint32_t*>(reach_bits), c.start + boff, cnt, id_ahead, id, raw, geo);
+        if (bi > 0 && threadIdx.x < kBwdBatch) id_ahead = vals[c.start + boff - kBwdBatch + threadIdx.x];
 #pragma unroll
         for (int k = 0; k < 4 * kAccStride * kBwdBatch / 256; ++k) (&sAcc[0][0])[k * 256 + threadIdx.x] = 0.f;
         __syncthreads();
