@@ -49,40 +49,66 @@ __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, 
 }
 
 // One workgroup: exclusive prefix sums, in place, of the per-block counts of listed points and of pairs (the latter
-// saturating). Leaves the totals in the status words and the pair total behind the last rank's offset.
+// saturating). Leaves the totals in the status words and the pair total behind the last rank's offset. Also the order
+// in which the packing kernel takes the blocks: those with kHeavyBlockPairs pairs or more first (in index order), the
+// others after them (from the back, in reverse index order: one pass, no second scan).
+constexpr uint32_t kHeavyBlockPairs = 1536;      // about twice the benchmark view's mean
+
 __global__ __launch_bounds__(1024) void k_scan_blocks(uint32_t* __restrict__ blk_vis, uint32_t* __restrict__ blk_pairs, uint32_t nb,
-                                                      uint32_t* __restrict__ status, uint32_t* __restrict__ offsets, uint32_t n)
+                                                      uint32_t* __restrict__ status, uint32_t* __restrict__ offsets, uint32_t n,
+                                                      uint32_t* __restrict__ blk_order)
 {
-    __shared__ uint32_t sV[16], sP[16];
-    __shared__ uint32_t carry_v, carry_p;
+    constexpr uint32_t kPer = 4;                 // consecutive blocks per thread: a million points are one trip
+    __shared__ uint32_t sV[16], sP[16], sH[16];
+    __shared__ uint32_t carry_v, carry_p, carry_h;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) { carry_v = 0; carry_p = 0; }
+    if (threadIdx.x == 0) { carry_v = 0; carry_p = 0; carry_h = 0; }
     __syncthreads();
-    for (uint32_t start = 0; start < nb; start += 1024) {
-        const uint32_t idx = start + threadIdx.x;
-        const uint32_t v = idx < nb ? blk_vis[idx] : 0u, p = idx < nb ? blk_pairs[idx] : 0u;
-        uint32_t iv = v, ip = p;
+    for (uint32_t start = 0; start < nb; start += 1024u * kPer) {
+        const uint32_t idx0 = start + threadIdx.x * kPer;
+        uint32_t v[kPer], p[kPer], h[kPer];
+        uint32_t tv = 0, tp = 0, th = 0;         // this thread's totals
+#pragma unroll
+        for (uint32_t k = 0; k < kPer; ++k) {
+            v[k] = idx0 + k < nb ? blk_vis[idx0 + k] : 0u;
+            p[k] = idx0 + k < nb ? blk_pairs[idx0 + k] : 0u;
+            h[k] = p[k] >= kHeavyBlockPairs ? 1u : 0u;
+            tv += v[k]; tp = sat_add(tp, p[k]); th += h[k];
+        }
+        uint32_t iv = tv, ip = tp, ih = th;      // inclusive over the wavefront's threads
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t tv = __shfl_up(iv, d, 64), tp = __shfl_up(ip, d, 64);
-            if (lane >= d) { iv += tv; ip = sat_add(ip, tp); }
+            const uint32_t uv = __shfl_up(iv, d, 64), up = __shfl_up(ip, d, 64), uh = __shfl_up(ih, d, 64);
+            if (lane >= d) { iv += uv; ip = sat_add(ip, up); ih += uh; }
         }
-        if (lane == 63) { sV[wave] = iv; sP[wave] = ip; }
+        if (lane == 63) { sV[wave] = iv; sP[wave] = ip; sH[wave] = ih; }
         __syncthreads();
-        uint32_t bv = carry_v, bp = carry_p, cv = 0, cp = 0;
+        uint32_t bv = carry_v, bp = carry_p, bh = carry_h, cv = 0, cp = 0, ch = 0;
 #pragma unroll
         for (int w = 0; w < 16; ++w) {
-            const uint32_t tv = sV[w], tp = sP[w];
-            if (w < wave) { bv += tv; bp = sat_add(bp, tp); }
-            cv += tv; cp = sat_add(cp, tp);
+            const uint32_t wv = sV[w], wp = sP[w], wh = sH[w];
+            if (w < wave) { bv += wv; bp = sat_add(bp, wp); bh += wh; }
+            cv += wv; cp = sat_add(cp, wp); ch += wh;
         }
-        const uint32_t ep = __shfl_up(ip, 1, 64);      // exclusive within the wavefront = the lane below's inclusive sum
-        if (idx < nb) {
-            blk_vis[idx] = bv + iv - v;
-            blk_pairs[idx] = sat_add(bp, lane == 0 ? 0u : ep);
+        // exclusive over the threads before this one = the lane below's inclusive sum
+        const uint32_t ep = __shfl_up(ip, 1, 64);
+        uint32_t ev = bv + iv - tv, eh = bh + ih - th;
+        uint32_t epairs = sat_add(bp, lane == 0 ? 0u : ep);
+#pragma unroll
+        for (uint32_t k = 0; k < kPer; ++k) {
+            const uint32_t idx = idx0 + k;
+            if (idx < nb) {
+                blk_vis[idx] = ev;
+                blk_pairs[idx] = epairs;
+                eh += h[k];                      // heavy blocks among 0 .. idx
+                if (h[k]) blk_order[eh - 1u] = idx;
+                else blk_order[nb - 1u - (idx - eh)] = idx;
+            }
+            ev += v[k];
+            epairs = sat_add(epairs, p[k]);
         }
         __syncthreads();
-        if (threadIdx.x == 0) { carry_v += cv; carry_p = sat_add(carry_p, cp); }
+        if (threadIdx.x == 0) { carry_v += cv; carry_p = sat_add(carry_p, cp); carry_h += ch; }
         __syncthreads();
     }
     if (threadIdx.x == 0) {
@@ -280,6 +306,7 @@ BinArrays bin_arrays(const Layout& L, char* ws)
     A.touched = reinterpret_cast<const uint32_t*>(ws + L.off_touched);
     A.blk_vis = reinterpret_cast<const uint32_t*>(ws + L.off_blk_vis);
     A.blk_pairs = reinterpret_cast<const uint32_t*>(ws + L.off_blk_pairs);
+    A.blk_order = reinterpret_cast<const uint32_t*>(ws + L.off_blk_order);
     A.order = reinterpret_cast<uint32_t*>(ws + L.off_order);
     A.offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
     A.slot_base = reinterpret_cast<uint32_t*>(ws + L.off_slot_base);
@@ -306,7 +333,7 @@ hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Lay
     hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), blk_vis,
                        blk_pairs, status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
     hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, s, blk_vis, blk_pairs, nb, status,
-                       reinterpret_cast<uint32_t*>(ws + L.off_offsets), (uint32_t)n);
+                       reinterpret_cast<uint32_t*>(ws + L.off_offsets), (uint32_t)n, reinterpret_cast<uint32_t*>(ws + L.off_blk_order));
     return hipGetLastError();
 }
 
