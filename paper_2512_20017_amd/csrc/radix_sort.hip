@@ -68,21 +68,22 @@ __global__ __launch_bounds__(256) void k_radix_tile_hist(const uint32_t* __restr
 }
 
 // one workgroup per digit: exclusive scan of that digit's counts over the tiles that hold keys (in place);
-// totals[digit] = their sum
-__global__ __launch_bounds__(256) void k_radix_digit_scan(uint32_t* __restrict__ hist, uint32_t row_stride,
-                                                          const uint32_t* __restrict__ count_ptr, uint32_t count_cap,
-                                                          uint32_t* __restrict__ totals)
+// totals[digit] = their sum. 1024 threads, two consecutive counts each: 2048 tiles (4 M pairs) are one trip.
+__global__ __launch_bounds__(1024) void k_radix_digit_scan(uint32_t* __restrict__ hist, uint32_t row_stride,
+                                                           const uint32_t* __restrict__ count_ptr, uint32_t count_cap,
+                                                           uint32_t* __restrict__ totals)
 {
-    __shared__ uint32_t lds[4];
+    __shared__ uint32_t lds[16];
     __shared__ uint32_t carry_s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t ntiles = (sort_count(count_ptr, count_cap) + kSortItems - 1) / kSortItems;
     uint32_t* row = hist + (size_t)blockIdx.x * row_stride;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
-    for (uint32_t start = 0; start < ntiles; start += 256) {
-        const uint32_t idx = start + threadIdx.x;
-        const uint32_t v = idx < ntiles ? row[idx] : 0u;
+    for (uint32_t start = 0; start < ntiles; start += 2048) {
+        const uint32_t idx = start + 2u * threadIdx.x;
+        const uint32_t v0 = idx < ntiles ? row[idx] : 0u, v1 = idx + 1u < ntiles ? row[idx + 1u] : 0u;
+        const uint32_t v = v0 + v1;
         uint32_t inc = v;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -93,8 +94,9 @@ __global__ __launch_bounds__(256) void k_radix_digit_scan(uint32_t* __restrict__
         __syncthreads();
         uint32_t base = carry_s, chunk = 0;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) { const uint32_t t = lds[w]; if (w < wave) base += t; chunk += t; }
+        for (int w = 0; w < 16; ++w) { const uint32_t t = lds[w]; if (w < wave) base += t; chunk += t; }
         if (idx < ntiles) row[idx] = base + inc - v;
+        if (idx + 1u < ntiles) row[idx + 1u] = base + inc - v1;
         __syncthreads();
         if (threadIdx.x == 0) carry_s += chunk;
         __syncthreads();
@@ -680,7 +682,7 @@ static void launch_pass(uint32_t* keys[2], uint32_t* vals[2], int src, const uin
     {
         ProfScope prof(kKRadixHist, s);
         hipLaunchKernelGGL(k_radix_tile_hist<kBits>, dim3(nb), dim3(256), 0, s, keys[src], count_ptr, count_cap, shift, tile_hist, nb);
-        hipLaunchKernelGGL(k_radix_digit_scan, dim3(1u << kBits), dim3(256), 0, s, tile_hist, nb, count_ptr, count_cap, totals);
+        hipLaunchKernelGGL(k_radix_digit_scan, dim3(1u << kBits), dim3(1024), 0, s, tile_hist, nb, count_ptr, count_cap, totals);
     }
     ProfScope prof(kKRadixScatter, s);
     hipLaunchKernelGGL(k_radix_scatter<kBits>, dim3(nb), dim3(256), 0, s, keys[src], vals[src], keys[dst], vals[dst], count_ptr,
