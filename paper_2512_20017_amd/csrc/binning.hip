@@ -175,9 +175,9 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict_
 // over the classes present: the kernel runs on one compute unit, so its instruction count is its duration.
 constexpr int kOrderClasses = 40;           // < 63; class 63 stands for "no tile"
 constexpr uint32_t kOrderRounds = 8;        // rounds of 64 tiles whose ranges are loaded together (one trip to memory, not eight)
-// lists of 511 entries or more are sorted by a whole workgroup (radix_sort.hip: kWaveListMax - 1); length + 1 < 512 =
-// 2^9 means a class code of at most 2 * 8 + 1
-constexpr uint32_t kFirstSmallClass = (uint32_t)(kOrderClasses - 1) - 17u;
+// lists of 1023 entries or more are sorted by a whole workgroup (radix_sort.hip: kWaveListMax - 1); length + 1 < 1024 =
+// 2^10 means a class code of at most 2 * 9 + 1
+constexpr uint32_t kFirstSmallClass = (uint32_t)(kOrderClasses - 1) - 19u;
 
 __device__ __forceinline__ uint32_t order_class(uint32_t len)
 {
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
         for (int k = 0; k < kPer; ++k) { count[lane * kPer + k] = at; at += v[k]; }
     }
     __syncthreads();
-    // how many tiles hold 511 entries or more: they come first in the order, and the depth sort gives each a whole
+    // how many tiles hold 1023 entries or more: they come first in the order, and the depth sort gives each a whole
     // workgroup (the classes are cut at powers of two of length + 1, so this is where a class starts)
     if (threadIdx.x == 0) status[kStNumBig] = count[kFirstSmallClass * 16u];
     __syncthreads();

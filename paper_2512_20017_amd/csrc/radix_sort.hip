@@ -223,12 +223,13 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 // Depth order inside each tile's list. After the stable sort by tile id every tile's list holds its splats in point
 // order; the list is then sorted stably by the 32 depth bits, which leaves the order of the key
 // (tile << 32 | depth bits), ties by point index. One launch, every list on its own:
-//   - fewer than 511 entries (k_tile_order lists the tiles longest first and says how many have more): one WAVEFRONT
+//   - fewer than 1023 entries (k_tile_order lists the tiles longest first and says how many have more): one WAVEFRONT
 //     per list, four lists per workgroup, no workgroup barrier anywhere: up to 64 entries by counting (every lane
 //     compares its key with all others through the scalar unit), else least-significant-digit radix passes with 8-bit
 //     digits over the bit positions in which the list's keys differ at all (depths of one tile share sign, most
 //     exponent bits and often more). Keys and positions live in registers in list order; a pass scatters them into the
-//     wavefront's 4 KB of LDS and reads them back in the new order;
+//     wavefront's 7 KB of LDS and reads them back in the new order (lists of 511 to 1022 entries took a whole workgroup
+//     before: four wavefront slots for 16 us each where one wavefront now takes them, 57 -> 53 us);
 //   - up to 6016 entries: the same passes by a whole workgroup, two barriers per pass. What moves is the permutation
 //     (16-bit positions, two copies in LDS); the keys stay where they are, in incoming order - in LDS for lists of up
 //     to 2048 entries, in the global scratch array (the spent tile ids) beyond - and are fetched through it;
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 // digit came before (earlier rounds of the wavefront: LDS executes a wavefront's operations in order), and hands that
 // to its group through the LDS crossbar: equal digits keep their incoming order.
 // ---------------------------------------------------------------------------------------------
-constexpr int kWaveListMax = 512;                     // a wavefront's own list holds fewer than kWaveListMax - 1 entries (8 rounds)
+constexpr int kWaveListMax = 1024;                    // a wavefront's own list holds fewer than kWaveListMax - 1 entries (16 rounds)
 constexpr int kWgKeyMax = 2048;                       // a workgroup's list with its keys in LDS (8 rounds per wavefront)
 constexpr int kWgListMax = 6016;                      // a workgroup's list with its permutation in LDS (24 rounds per wavefront)
 constexpr int kListChunk = 2048;                      // entries per chunk of a list that goes through global memory
