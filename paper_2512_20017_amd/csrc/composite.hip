@@ -362,6 +362,8 @@ __global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint
         uint32_t id; float4 raw, geo;
         stage_batch_bwd(S, vals, packed, reinterpret_cast<const uint32_t*>(reach_bits), c.start + boff, cnt, id_ahead, id, raw, geo);
         if (bi > 0 && threadIdx.x < kBwdBatch) id_ahead = vals[c.start + boff - kBwdBatch + threadIdx.x];
+        // asked for now, used when the batch's records are written: the walk hides the trip
+        const uint32_t pair_base = (int)threadIdx.x < cnt ? slot_base[id] : 0u;
 #pragma unroll
         for (int k = 0; k < 4 * kAccStride * kBwdBatch / 256; ++k) (&sAcc[0][0])[k * 256 + threadIdx.x] = 0.f;
         __syncthreads();
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint
             // where this (tile, splat) pair sits in the unsorted duplicate list
             int x0, y0, x1, y1;
             tile_rect(cam, geo.x, geo.y, __float_as_int(geo.z), x0, y0, x1, y1);
-            const uint32_t u = slot_base[id] + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
+            const uint32_t u = pair_base + (uint32_t)((tile_y - y0) * (x1 - x0) + (tile_x - x0));
             if (u < cap && tile_x >= x0 && tile_x < x1 && tile_y >= y0 && tile_y < y1) {
                 float acc[kAccStride];
 #pragma unroll
