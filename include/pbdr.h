@@ -186,8 +186,9 @@ int pbdr_render_bwd_patch(const pbdr_scene* scene, const pbdr_splats* splats, co
                           pbdr_scene_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* The sorting half of image_render (Sec. 2.1: "sorts these view-dependent splats by their distance to the camera
- * plane"): per-splat tile count, radix sort in the order of the key (tile << 32 | depth bits) - depth digits on the
- * splats, device prefix sum, duplication, tile digits on the pairs - and per-tile ranges.
+ * plane"): per-splat tile count, device prefix sum, duplication in point order, and a sort into the order of the key
+ * (tile << 32 | depth bits), ties by point index - a stable radix sort of the pairs by tile id, then every tile's
+ * list by depth bits - and per-tile ranges.
  * Results stay in the workspace; pbdr_lists_view gives their addresses. If more than dup_capacity pairs exist the
  * excess is dropped, nothing is written out of bounds, and pbdr_query_lists reports PBDR_ERR_CAPACITY. */
 int pbdr_bin_sort(const pbdr_splats* splats, const pbdr_camera* cam, uint64_t dup_capacity, void* workspace,

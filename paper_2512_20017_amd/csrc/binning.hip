@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict_
 #pragma unroll
     for (uint32_t k = 0; k < 4u; ++k) {
         const uint32_t i = i0 + k, tile = t[1 + k];
-        if (i >= P || tile >= ntiles) continue;     // tile >= ntiles cannot happen for keys written by k_duplicate; keeps the writes in bounds regardless
+        if (i >= P || tile >= ntiles) continue;     // tile >= ntiles cannot happen for keys written by the packing kernels; keeps the writes in bounds regardless
         if (i == 0u || t[k] != tile) ranges[2 * tile] = i;
         if (i + 1u == P || t[2 + k] != tile) ranges[2 * tile + 1] = i + 1u;
     }

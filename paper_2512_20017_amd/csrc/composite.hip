@@ -449,8 +449,8 @@ __global__ __launch_bounds__(256, 7) void k_composite_bwd(CamDev cam, const uint
 // Adds up, per point, the per-tile partial sums of its pairs (contiguous in the unsorted duplicate list, 48 bytes
 // each) into dL/d(splat state) of the visible points; culled points are not written. Balanced by pairs: see
 // pair_reduce.h.
-// The sums are first stored as one 48-byte record per point, by point index (ranks are in depth order, points in
-// storage order: nine 4-byte stores per point into nine planes would touch nine cache lines where this touches one),
+// The sums are first stored as one 48-byte record per point, by point index (nine 4-byte stores per point into nine
+// planes touch nine cache lines where this touches one),
 // then a streaming kernel over all points copies the records of listed points into the planes of the splat-state
 // gradient.
 struct StoreSplatGrad {

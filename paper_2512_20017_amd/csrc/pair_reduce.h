@@ -1,6 +1,6 @@
 // Per-point sums over the per-pair records of the backward pass, balanced by pairs.
 //
-// The pairs of the point with depth rank r occupy [offsets[r], offsets[r+1]) of the unsorted duplicate list, so the
+// The pairs of the listed point with rank r (its place among the listed points, in index order) occupy [offsets[r], offsets[r+1]) of the unsorted duplicate list, so the
 // records to add up for one point are contiguous, but their number varies from one to thousands. Work is therefore
 // cut by pairs, not by points: a wavefront owns 256 consecutive pairs (four steps of 64), finds the owning rank of
 // each pair by binary search over a window of 64 range ends in LDS (64 pairs span at most 64 ranks: every visible
@@ -20,8 +20,8 @@ constexpr int kChunkPairs = 256;   // pairs per wavefront
 constexpr int kCarryFloats = 36;
 enum { kCarryHasLeft = 1, kCarryLeftThrough = 2, kCarryHasRight = 4 };
 
-// chunk_rank[c] = depth rank that owns pair c * 256; written by the duplication kernel (a rank writes one entry per 256
-// pairs it spans).
+// chunk_rank[c] = rank that owns pair c * 256; written by the packing kernel (a rank writes one entry per 256 pairs it
+// spans).
 
 template <int kCtrl>
 __device__ __forceinline__ float dpp_shift0(float v)    // shifted-in lanes read 0
@@ -73,7 +73,7 @@ __device__ __forceinline__ void seg_scan_sorted(float (&v)[kVals], int owner)
 }
 
 // One wavefront's 256 pairs. kVec4 float4 per record, of which the first kVals floats are summed. `store(rank, v)`
-// writes a finished sum for depth rank `rank`. sEnd: 64 words of LDS private to the wavefront.
+// writes a finished sum for rank `rank`. sEnd: 64 words of LDS private to the wavefront.
 // kTagged: the last two words of a record carry the 64-bit number of the backward call that wrote it (the workspace
 // counts its backward calls from one; it starts zero-filled, so no record of an earlier call, and no record never
 // written, carries the current number); a record with any other tag was not written by this call (its pair lies beyond
