@@ -70,6 +70,8 @@ bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L)
     L->off_depth_bits = take((size_t)n * sizeof(uint32_t));
     L->off_blk_vis = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
     L->off_blk_pairs = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
+    L->off_blk_vis_at = take(((size_t)n / 256 + 8) * sizeof(uint32_t));  // exclusive sums of the two above
+    L->off_blk_pairs_at = take(((size_t)n / 256 + 8) * sizeof(uint32_t));
     L->off_blk_order = take(((size_t)n / 256 + 8) * sizeof(uint32_t));   // blocks of points in the order the packing kernel takes them
     L->off_touched = take((size_t)n * sizeof(uint32_t));
     L->off_offsets = take(((size_t)n + 1) * sizeof(uint32_t));

@@ -48,74 +48,96 @@ __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, 
     }
 }
 
-// One workgroup: exclusive prefix sums, in place, of the per-block counts of listed points and of pairs (the latter
-// saturating). Leaves the totals in the status words and the pair total behind the last rank's offset. Also the order
-// in which the packing kernel takes the blocks: those with kHeavyBlockPairs pairs or more first (in index order), the
-// others after them (from the back, in reverse index order: one pass, no second scan).
+// Exclusive prefix sums of the per-block counts of listed points and of pairs (the latter saturating), the totals into the
+// status words and the pair total behind the last rank's offset. Also the order in which the packing kernel takes the
+// blocks: those with kHeavyBlockPairs pairs or more first (in index order), the others after them (from the back, in
+// reverse index order: one pass, no second scan).
+// Workgroup g takes the kScanChunk blocks from g * kScanChunk on. What came before them it adds up by itself from the
+// counts (a few coalesced loads per thread), so no workgroup waits for another: a million points are one workgroup, and
+// eight million are eight that each do one chunk instead of one that does eight in a row.
 constexpr uint32_t kHeavyBlockPairs = 1536;      // about twice the benchmark view's mean
+constexpr uint32_t kScanPer = 4;                 // consecutive blocks per thread
+constexpr uint32_t kScanChunk = 1024u * kScanPer;
 
-__global__ __launch_bounds__(1024) void k_scan_blocks(uint32_t* __restrict__ blk_vis, uint32_t* __restrict__ blk_pairs, uint32_t nb,
+__global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t* __restrict__ blk_vis, const uint32_t* __restrict__ blk_pairs, uint32_t nb,
+                                                      uint32_t* __restrict__ blk_vis_at, uint32_t* __restrict__ blk_pairs_at,
                                                       uint32_t* __restrict__ status, uint32_t* __restrict__ offsets, uint32_t n,
                                                       uint32_t* __restrict__ blk_order)
 {
-    constexpr uint32_t kPer = 4;                 // consecutive blocks per thread: a million points are one trip
+    constexpr uint32_t kPer = kScanPer;
     __shared__ uint32_t sV[16], sP[16], sH[16];
-    __shared__ uint32_t carry_v, carry_p, carry_h;
+    __shared__ uint32_t cV[16], cP[16], cH[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) { carry_v = 0; carry_p = 0; carry_h = 0; }
-    __syncthreads();
-    for (uint32_t start = 0; start < nb; start += 1024u * kPer) {
-        const uint32_t idx0 = start + threadIdx.x * kPer;
-        uint32_t v[kPer], p[kPer], h[kPer];
-        uint32_t tv = 0, tp = 0, th = 0;         // this thread's totals
+    const uint32_t start = blockIdx.x * kScanChunk;
+    // totals of the chunks before this one
+    uint32_t carry_v = 0, carry_p = 0, carry_h = 0;
+    if (start > 0u) {
+        for (uint32_t i = threadIdx.x; i < start; i += kScanChunk) {      // (start is a multiple of kScanChunk: no tail)
+            uint32_t vv[kPer], pv[kPer];
 #pragma unroll
-        for (uint32_t k = 0; k < kPer; ++k) {
-            v[k] = idx0 + k < nb ? blk_vis[idx0 + k] : 0u;
-            p[k] = idx0 + k < nb ? blk_pairs[idx0 + k] : 0u;
-            h[k] = p[k] >= kHeavyBlockPairs ? 1u : 0u;
-            tv += v[k]; tp = sat_add(tp, p[k]); th += h[k];
-        }
-        uint32_t iv = tv, ip = tp, ih = th;      // inclusive over the wavefront's threads
+            for (uint32_t k = 0; k < kPer; ++k) { vv[k] = blk_vis[i + k * 1024u]; pv[k] = blk_pairs[i + k * 1024u]; }
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t uv = __shfl_up(iv, d, 64), up = __shfl_up(ip, d, 64), uh = __shfl_up(ih, d, 64);
-            if (lane >= d) { iv += uv; ip = sat_add(ip, up); ih += uh; }
-        }
-        if (lane == 63) { sV[wave] = iv; sP[wave] = ip; sH[wave] = ih; }
-        __syncthreads();
-        uint32_t bv = carry_v, bp = carry_p, bh = carry_h, cv = 0, cp = 0, ch = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const uint32_t wv = sV[w], wp = sP[w], wh = sH[w];
-            if (w < wave) { bv += wv; bp = sat_add(bp, wp); bh += wh; }
-            cv += wv; cp = sat_add(cp, wp); ch += wh;
-        }
-        // exclusive over the threads before this one = the lane below's inclusive sum
-        const uint32_t ep = __shfl_up(ip, 1, 64);
-        uint32_t ev = bv + iv - tv, eh = bh + ih - th;
-        uint32_t epairs = sat_add(bp, lane == 0 ? 0u : ep);
-#pragma unroll
-        for (uint32_t k = 0; k < kPer; ++k) {
-            const uint32_t idx = idx0 + k;
-            if (idx < nb) {
-                blk_vis[idx] = ev;
-                blk_pairs[idx] = epairs;
-                eh += h[k];                      // heavy blocks among 0 .. idx
-                if (h[k]) blk_order[eh - 1u] = idx;
-                else blk_order[nb - 1u - (idx - eh)] = idx;
+            for (uint32_t k = 0; k < kPer; ++k) {
+                carry_v += vv[k]; carry_p = sat_add(carry_p, pv[k]); carry_h += pv[k] >= kHeavyBlockPairs ? 1u : 0u;
             }
-            ev += v[k];
-            epairs = sat_add(epairs, p[k]);
         }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            carry_v += __shfl_xor(carry_v, d, 64); carry_p = sat_add(carry_p, __shfl_xor(carry_p, d, 64)); carry_h += __shfl_xor(carry_h, d, 64);
+        }
+        if (lane == 0) { cV[wave] = carry_v; cP[wave] = carry_p; cH[wave] = carry_h; }
         __syncthreads();
-        if (threadIdx.x == 0) { carry_v += cv; carry_p = sat_add(carry_p, cp); carry_h += ch; }
-        __syncthreads();
+        carry_v = 0; carry_p = 0; carry_h = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { carry_v += cV[w]; carry_p = sat_add(carry_p, cP[w]); carry_h += cH[w]; }
     }
-    if (threadIdx.x == 0) {
-        const uint32_t m = min(carry_v, n);
+    const uint32_t idx0 = start + threadIdx.x * kPer;
+    uint32_t v[kPer], p[kPer], h[kPer];
+    uint32_t tv = 0, tp = 0, th = 0;         // this thread's totals
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+        v[k] = idx0 + k < nb ? blk_vis[idx0 + k] : 0u;
+        p[k] = idx0 + k < nb ? blk_pairs[idx0 + k] : 0u;
+        h[k] = p[k] >= kHeavyBlockPairs ? 1u : 0u;
+        tv += v[k]; tp = sat_add(tp, p[k]); th += h[k];
+    }
+    uint32_t iv = tv, ip = tp, ih = th;      // inclusive over the wavefront's threads
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t uv = __shfl_up(iv, d, 64), up = __shfl_up(ip, d, 64), uh = __shfl_up(ih, d, 64);
+        if (lane >= d) { iv += uv; ip = sat_add(ip, up); ih += uh; }
+    }
+    if (lane == 63) { sV[wave] = iv; sP[wave] = ip; sH[wave] = ih; }
+    __syncthreads();
+    uint32_t bv = carry_v, bp = carry_p, bh = carry_h, cv = carry_v, cp = carry_p;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const uint32_t wv = sV[w], wp = sP[w], wh = sH[w];
+        if (w < wave) { bv += wv; bp = sat_add(bp, wp); bh += wh; }
+        cv += wv; cp = sat_add(cp, wp);
+    }
+    // exclusive over the threads before this one = the lane below's inclusive sum
+    const uint32_t ep = __shfl_up(ip, 1, 64);
+    uint32_t ev = bv + iv - tv, eh = bh + ih - th;
+    uint32_t epairs = sat_add(bp, lane == 0 ? 0u : ep);
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+        const uint32_t idx = idx0 + k;
+        if (idx < nb) {
+            blk_vis_at[idx] = ev;
+            blk_pairs_at[idx] = epairs;
+            eh += h[k];                      // heavy blocks among 0 .. idx
+            if (h[k]) blk_order[eh - 1u] = idx;
+            else blk_order[nb - 1u - (idx - eh)] = idx;
+        }
+        ev += v[k];
+        epairs = sat_add(epairs, p[k]);
+    }
+    if (threadIdx.x == 0 && start + kScanChunk >= nb) {      // the last chunk: cv, cp are the totals
+        const uint32_t m = min(cv, n);
         status[kStNumVis] = m;
-        status[kStNumDup] = carry_p;
-        offsets[m] = carry_p;
+        status[kStNumDup] = cp;
+        offsets[m] = cp;
     }
 }
 
@@ -214,30 +236,64 @@ __device__ __forceinline__ uint64_t lanes_of_my_class(uint32_t cls)
     return same;
 }
 
+// Workgroup g orders the kOrderChunk tiles from g * kOrderChunk on (an image of up to 8192 tiles is one workgroup). Where
+// they go also depends on the other workgroups' tiles: how many of each class lie in earlier chunks, and in later ones.
+// Every workgroup counts those for itself from the ranges, so none waits for another.
+constexpr uint32_t kOrderChunk = 16u * kOrderRounds * 64u;
+template <bool kMulti>                      // more than one chunk
 __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict__ ranges, uint32_t ntiles, uint32_t* __restrict__ tile_order,
                                                      uint32_t* __restrict__ status)
 {
-    __shared__ uint32_t count[64 * 16];      // [class][wavefront]: tiles, then where the wavefront's next tile of the class goes
+    // per class: (earlier chunks,) the 16 wavefronts of this one(, later chunks)
+    constexpr uint32_t kOrderSlots = kMulti ? 18u : 16u, kFirst = kMulti ? 1u : 0u;
+    constexpr int kPer = (kOrderClasses * kOrderSlots + 63) / 64;
+    __shared__ uint32_t count[64 * kOrderSlots];      // [class][slot]: tiles, then where the next tile of (class, slot) goes (class 63: unused, in bounds)
     const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
-    const uint32_t per_wave = ((ntiles + 1023u) / 1024u) * 64u;
-    const uint32_t t0 = w * per_wave, t1 = min(ntiles, t0 + per_wave);
+    const uint32_t c0 = blockIdx.x * kOrderChunk, c1 = min(ntiles, c0 + kOrderChunk);
+    const uint32_t t0 = min(c1, c0 + w * (kOrderRounds * 64u)), t1 = min(c1, t0 + kOrderRounds * 64u);
     const uint64_t below = (1ull << lane) - 1ull;
     const uint2* range2 = reinterpret_cast<const uint2*>(ranges);
 
-    count[threadIdx.x] = 0u;
+    __shared__ uint32_t other[kMulti ? 2 * kOrderClasses * 16 : 1];      // [earlier, later chunks][class][lane % 16]
+    for (uint32_t i = threadIdx.x; i < 64u * kOrderSlots; i += 1024u) count[i] = 0u;
+    if (kMulti)
+        for (uint32_t i = threadIdx.x; i < 2u * kOrderClasses * 16u; i += 1024u) other[i] = 0u;
     __syncthreads();
     uint32_t cls[kOrderRounds];
-    for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
-        order_classes(range2, tb, t1, lane, cls);
+    order_classes(range2, t0, t1, lane, cls);
 #pragma unroll
-        for (uint32_t k = 0; k < kOrderRounds; ++k) {
-            const uint64_t same = lanes_of_my_class(cls[k]);
-            if ((same & below) == 0ull && cls[k] != 63u) count[cls[k] * 16u + w] += (uint32_t)__popcll(same);      // first lane of its class
+    for (uint32_t k = 0; k < kOrderRounds; ++k) {
+        const uint64_t same = lanes_of_my_class(cls[k]);
+        if ((same & below) == 0ull && cls[k] != 63u) count[cls[k] * kOrderSlots + kFirst + w] += (uint32_t)__popcll(same);      // first lane of its class
+    }
+    if (kMulti) {      // the tiles of the other chunks, by class
+        // (one of 16 counters per side and class, by lane: a wavefront's tiles are mostly of one class, and additions to
+        // one LDS address take their turns)
+        for (uint32_t ib = threadIdx.x; ib < ntiles; ib += 4u * 1024u) {
+            uint2 r[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4u; ++k) {
+                const uint32_t i = ib + k * 1024u;
+                r[k] = i < ntiles ? range2[i] : make_uint2(0u, 0u);
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4u; ++k) {
+                const uint32_t i = ib + k * 1024u;
+                if (i < ntiles && (i < c0 || i >= c1))
+                    atomicAdd(&other[((i < c0 ? 0u : (uint32_t)kOrderClasses) + order_class(r[k].y - r[k].x)) * 16u + (lane & 15u)], 1u);
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 2u * kOrderClasses) {
+            uint32_t sum = 0;
+#pragma unroll
+            for (uint32_t k = 0; k < 16u; ++k) sum += other[threadIdx.x * 16u + k];
+            const uint32_t c = threadIdx.x < (uint32_t)kOrderClasses ? threadIdx.x : threadIdx.x - (uint32_t)kOrderClasses;
+            count[c * kOrderSlots + (threadIdx.x < (uint32_t)kOrderClasses ? 0u : kOrderSlots - 1u)] = sum;
         }
     }
     __syncthreads();
-    if (w == 0) {      // exclusive prefix sums over (class, wavefront), classes 0 .. kOrderClasses - 1: 10 consecutive entries per lane
-        constexpr int kPer = kOrderClasses * 16 / 64;
+    if (w == 0) {      // exclusive prefix sums over (class, slot), classes 0 .. kOrderClasses - 1: kPer consecutive entries per lane
         uint32_t v[kPer], sum = 0;
 #pragma unroll
         for (int k = 0; k < kPer; ++k) { v[k] = count[lane * kPer + k]; sum += v[k]; }
@@ -254,19 +310,15 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
     __syncthreads();
     // how many tiles hold 1023 entries or more: they come first in the order, and the depth sort gives each a whole
     // workgroup (the classes are cut at powers of two of length + 1, so this is where a class starts)
-    if (threadIdx.x == 0) status[kStNumBig] = count[kFirstSmallClass * 16u];
-    __syncthreads();
-    for (uint32_t tb = t0; tb < t1; tb += kOrderRounds * 64u) {
-        if (per_wave > kOrderRounds * 64u) order_classes(range2, tb, t1, lane, cls);      // else still there from the counting pass
+    if (threadIdx.x == 0 && blockIdx.x == 0) status[kStNumBig] = count[kFirstSmallClass * kOrderSlots];
 #pragma unroll
-        for (uint32_t k = 0; k < kOrderRounds; ++k) {
-            const uint64_t same = lanes_of_my_class(cls[k]);
-            const uint32_t slot = cls[k] * 16u + w;
-            const uint32_t at = count[slot];      // every lane of the class reads it before its first lane moves it on
-            if (cls[k] != 63u) {
-                tile_order[at + (uint32_t)__popcll(same & below)] = tb + k * 64u + lane;
-                if ((same & below) == 0ull) count[slot] = at + (uint32_t)__popcll(same);
-            }
+    for (uint32_t k = 0; k < kOrderRounds; ++k) {
+        const uint64_t same = lanes_of_my_class(cls[k]);
+        const uint32_t slot = cls[k] * kOrderSlots + kFirst + w;
+        const uint32_t at = count[slot];      // every lane of the class reads it before its first lane moves it on
+        if (cls[k] != 63u) {
+            tile_order[at + (uint32_t)__popcll(same & below)] = t0 + k * 64u + lane;
+            if ((same & below) == 0ull) count[slot] = at + (uint32_t)__popcll(same);
         }
     }
 }
@@ -304,8 +356,8 @@ BinArrays bin_arrays(const Layout& L, char* ws)
 {
     BinArrays A;
     A.touched = reinterpret_cast<const uint32_t*>(ws + L.off_touched);
-    A.blk_vis = reinterpret_cast<const uint32_t*>(ws + L.off_blk_vis);
-    A.blk_pairs = reinterpret_cast<const uint32_t*>(ws + L.off_blk_pairs);
+    A.blk_vis = reinterpret_cast<const uint32_t*>(ws + L.off_blk_vis_at);
+    A.blk_pairs = reinterpret_cast<const uint32_t*>(ws + L.off_blk_pairs_at);
     A.blk_order = reinterpret_cast<const uint32_t*>(ws + L.off_blk_order);
     A.order = reinterpret_cast<uint32_t*>(ws + L.off_order);
     A.offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
@@ -332,7 +384,8 @@ hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Lay
     ProfScope prof(kKCountPack, s);
     hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), blk_vis,
                        blk_pairs, status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
-    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, s, blk_vis, blk_pairs, nb, status,
+    hipLaunchKernelGGL(k_scan_blocks, dim3((nb + kScanChunk - 1u) / kScanChunk), dim3(1024), 0, s, blk_vis, blk_pairs, nb,
+                       reinterpret_cast<uint32_t*>(ws + L.off_blk_vis_at), reinterpret_cast<uint32_t*>(ws + L.off_blk_pairs_at), status,
                        reinterpret_cast<uint32_t*>(ws + L.off_offsets), (uint32_t)n, reinterpret_cast<uint32_t*>(ws + L.off_blk_order));
     return hipGetLastError();
 }
@@ -357,7 +410,8 @@ hipError_t launch_bin_finish(const BinInput& sp, const CamDev& cam, const Layout
     {
         ProfScope prof(kKTileRanges, s);
         hipLaunchKernelGGL(k_tile_ranges, dim3((L.cap + 1023u) / 1024u), dim3(256), 0, s, tk[fin], status, L.cap, (uint32_t)L.tiles, ranges);
-        hipLaunchKernelGGL(k_tile_order, dim3(1), dim3(1024), 0, s, ranges, ntiles, tile_order, status);
+        if (ntiles <= kOrderChunk) hipLaunchKernelGGL(k_tile_order<false>, dim3(1), dim3(1024), 0, s, ranges, ntiles, tile_order, status);
+        else hipLaunchKernelGGL(k_tile_order<true>, dim3((ntiles + kOrderChunk - 1u) / kOrderChunk), dim3(1024), 0, s, ranges, ntiles, tile_order, status);
     }
     // depth digits: every tile's list, now in point order, into depth order (the tile ids in tk[fin] are spent: that
     // array and the other pair of buffers are the scratch of lists too long for LDS)

@@ -128,7 +128,7 @@ struct Layout {
     int partial_vec4;         // float4s of partial gradient sums per pair: 3 (3D) or 4 (2D)
     uint32_t cap;
     int tile_bits, tile_passes;   // key bits / radix passes spent on the tile id
-    size_t off_status, off_packed, off_depth_bits, off_blk_vis, off_blk_pairs, off_blk_order, off_touched, off_offsets, off_slot_base, off_order,
+    size_t off_status, off_packed, off_depth_bits, off_blk_vis, off_blk_pairs, off_blk_vis_at, off_blk_pairs_at, off_blk_order, off_touched, off_offsets, off_slot_base, off_order,
         off_tkey0, off_tval0, off_tkey1, off_tval1, off_totals, off_tile_hist, off_ranges,
         off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, off_reach, off_tile_order, total;
 };

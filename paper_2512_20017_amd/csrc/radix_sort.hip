@@ -244,6 +244,7 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveListMax = 1024;                    // a wavefront's own list holds fewer than kWaveListMax - 1 entries (16 rounds)
 constexpr int kWgKeyMax = 2048;                       // a workgroup's list with its keys in LDS (8 rounds per wavefront)
+constexpr int kDepthSortGridMax = 8192;               // workgroups of k_tile_depth_sort: eight times what is resident at once
 constexpr int kWgListMax = 6016;                      // a workgroup's list with its permutation in LDS (24 rounds per wavefront)
 constexpr int kListChunk = 2048;                      // entries per chunk of a list that goes through global memory
 constexpr int kListRounds = kListChunk / 256;
@@ -608,31 +609,12 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t* base, uin
     }
 }
 
-__global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
-                                                            uint32_t ntiles, const uint32_t* __restrict__ status,
-                                                            const uint32_t* __restrict__ depth_bits, uint32_t cap,
-                                                            uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
-                                                            uint32_t* __restrict__ keysB, uint32_t* __restrict__ valsB)
+// One list too long for a wavefront, sorted by the whole workgroup (every exit is uniform for the workgroup).
+__device__ __forceinline__ void wg_sort_big(WgSortLds& S, uint32_t s, uint32_t e, const uint32_t* __restrict__ depth_bits,
+                                            uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
+                                            uint32_t* __restrict__ keysB, uint32_t* __restrict__ valsB)
 {
-    __shared__ ListSortLds U;
-    // tile_order lists the tiles longest first; its first `nbig` tiles are too long for one wavefront. Workgroups
-    // 0 .. nbig - 1 take one of those each; every later workgroup takes four shorter lists, one per wavefront.
-    const uint32_t nbig = min(status[kStNumBig], ntiles);
-    const int wave = threadIdx.x >> 6;
-    if (blockIdx.x >= nbig) {
-        const uint32_t idx = nbig + (blockIdx.x - nbig) * 4u + (uint32_t)wave;
-        if (idx >= ntiles) return;
-        const uint32_t tile = tile_order[idx];
-        const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
-        if (e <= s + 1u) return;
-        // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
-        if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
-        return;
-    }
-    WgSortLds& S = U.wg;
-    const uint32_t tile = tile_order[blockIdx.x];
-    const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
-    if (e <= s + 1u) return;                     // uniform for the workgroup
+    if (e <= s + 1u) return;
     const uint32_t L = e - s;
     if (L <= (uint32_t)kWgKeyMax) { wg_sort_list<true>(S, L, depth_bits, valsA + s, keysA + s); return; }
     if (L <= (uint32_t)kWgListMax) { wg_sort_list<false>(S, L, depth_bits, valsA + s, keysA + s); return; }
@@ -664,14 +646,59 @@ __global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __re
         for (uint32_t i = threadIdx.x; i < L; i += 256u) valsA[s + i] = valsB[s + i];
 }
 
+// Work items: tile_order lists the tiles longest first and its first `nbig` tiles are too long for one wavefront, so
+// items 0 .. nbig - 1 are one such list each, for the whole workgroup, and every later item is four shorter lists, one
+// per wavefront. Workgroup b takes items b, b + gridDim.x, ...: a fixed assignment with no queue, so a workgroup's big
+// items all come before its small ones, and the launch does not pay for one workgroup per tile on images whose tiles
+// are mostly short lists (an idle workgroup still costs the dispatcher a few nanoseconds).
+template <bool kLoop>
+__global__ __launch_bounds__(256, kLoop ? 4 : 5) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+                                                            uint32_t ntiles, const uint32_t* __restrict__ status,
+                                                            const uint32_t* __restrict__ depth_bits, uint32_t cap,
+                                                            uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
+                                                            uint32_t* __restrict__ keysB, uint32_t* __restrict__ valsB)
+{
+    __shared__ ListSortLds U;
+    const uint32_t nbig = min(status[kStNumBig], ntiles);
+    const uint32_t nitems = nbig + (ntiles - nbig + 3u) / 4u;
+    const int wave = threadIdx.x >> 6;
+    uint32_t item = blockIdx.x;
+    if (item >= nitems) return;
+    do {
+        if (item < nbig) {
+            const uint32_t tile = tile_order[item];
+            wg_sort_big(U.wg, ranges[2 * tile], min(ranges[2 * tile + 1], cap), depth_bits, keysA, valsA, keysB, valsB);
+            __syncthreads();                       // the next item reuses the shared area
+            continue;
+        }
+        // from here on the four wavefronts go their own way: each has its own part of the shared area
+        const uint32_t idx = nbig + (item - nbig) * 4u + (uint32_t)wave;
+        if (idx >= ntiles) break;
+        const uint32_t tile = tile_order[idx];
+        const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
+        if (e <= s + 1u) continue;
+        // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
+        if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
+    } while (kLoop && (item += gridDim.x) < nitems);
+}
+
 hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_order, uint32_t ntiles, const uint32_t* status,
                                   const uint32_t* depth_bits, uint32_t cap, uint32_t* keysA, uint32_t* valsA, uint32_t* keysB,
                                   uint32_t* valsB, hipStream_t s)
 {
     if (ntiles == 0) return hipSuccess;
     ProfScope prof(kKTileDepthSort, s);
-    hipLaunchKernelGGL(k_tile_depth_sort, dim3(ntiles), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits, cap, keysA, valsA,
-                       keysB, valsB);
+    // a list of the workgroup kind has at least kWaveListMax - 1 entries, which bounds how many of them `cap` pairs can
+    // hold and so how many items there can be; one workgroup per item up to kDepthSortGridMax of them, else that many
+    // workgroups that each take every gridDim.x-th item
+    const uint32_t big_max = min(ntiles, cap / (uint32_t)(kWaveListMax - 1) + 1u);
+    const uint32_t items_max = min(ntiles, big_max + (ntiles + 3u) / 4u);
+    if (items_max <= (uint32_t)kDepthSortGridMax)
+        hipLaunchKernelGGL(k_tile_depth_sort<false>, dim3(items_max), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits, cap,
+                           keysA, valsA, keysB, valsB);
+    else
+        hipLaunchKernelGGL(k_tile_depth_sort<true>, dim3(kDepthSortGridMax), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits,
+                           cap, keysA, valsA, keysB, valsB);
     return hipGetLastError();
 }
 
