@@ -54,12 +54,24 @@ __global__ __launch_bounds__(256) void k_radix_tile_hist(const uint32_t* __restr
     for (int d = threadIdx.x; d < kBins; d += 256) h[d] = 0;
     __syncthreads();
     const uint64_t lt_mask = (1ull << (threadIdx.x & 63)) - 1ull;
+    // four consecutive keys per load (a histogram does not care which lane counts which key)
+    uint32_t key[kSortPerThread];
+#pragma unroll
+    for (int k = 0; k < kSortPerThread / 4; ++k) {
+        const uint32_t idx = base + (k * 256 + threadIdx.x) * 4u;
+        if (idx + 4u <= count) {
+            const uint4 v = *reinterpret_cast<const uint4*>(keys + idx);
+            key[4 * k] = v.x; key[4 * k + 1] = v.y; key[4 * k + 2] = v.z; key[4 * k + 3] = v.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) key[4 * k + j] = idx + j < count ? keys[idx + j] : 0u;
+        }
+    }
 #pragma unroll
     for (int k = 0; k < kSortPerThread; ++k) {
-        const uint32_t idx = base + k * 256 + threadIdx.x;
+        const uint32_t idx = base + ((k >> 2) * 256 + threadIdx.x) * 4u + (uint32_t)(k & 3);
         const bool valid = idx < count;
-        const uint32_t key = valid ? keys[idx] : 0u;
-        const uint32_t digit = (key >> shift) & kMask;
+        const uint32_t digit = (key[k] >> shift) & kMask;
         const uint64_t peers = digit_peers<kBits>(digit, valid);
         if (valid && (peers & lt_mask) == 0ull) atomicAdd(&h[digit], (uint32_t)__popcll(peers));
     }
@@ -230,13 +242,15 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 //     exponent bits and often more). Keys and positions live in registers in list order; a pass scatters them into the
 //     wavefront's 7 KB of LDS and reads them back in the new order (lists of 511 to 1022 entries took a whole workgroup
 //     before: four wavefront slots for 16 us each where one wavefront now takes them, 57 -> 53 us);
-//   - up to 6016 entries: the same passes by a whole workgroup, two barriers per pass. What moves is the permutation
+//   - up to 6400 entries: the same passes by a whole workgroup, three barriers per pass. What moves is the permutation
 //     (16-bit positions, two copies in LDS); the keys stay where they are, in incoming order - in LDS for lists of up
 //     to 2048 entries, in the global scratch array (the spent tile ids) beyond - and are fetched through it;
 //   - longer lists: the passes in chunks of 2048 through the global scratch arrays, whole-list digit counts first,
 //     then chunk by chunk in order.
-// 32 KB of LDS and at most 100 registers, so that five workgroups share a compute unit: the work is a chain of dependent
-// LDS and cross-lane steps per list, and what hides it is other lists in flight.
+// Under 30 KB of LDS and at most 96 registers, so that five workgroups share a compute unit: the work is a chain of
+// dependent LDS and cross-lane steps per list, and what hides it is other lists in flight (measured: with 32.3 KB only
+// four were resident, and the benchmark view's sort took 53.6 us instead of 50.6). That is why the per-wavefront digit
+// counters double as the starting positions, at the price of the third barrier.
 // A pass ranks its entries per wavefront and round of 64 by ballots (lanes with the same digit find each other), the
 // first lane of each group adds the group's size to the digit's counter in LDS and gets back how many entries of that
 // digit came before (earlier rounds of the wavefront: LDS executes a wavefront's operations in order), and hands that
@@ -244,8 +258,7 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveListMax = 1024;                    // a wavefront's own list holds fewer than kWaveListMax - 1 entries (16 rounds)
 constexpr int kWgKeyMax = 2048;                       // a workgroup's list with its keys in LDS (8 rounds per wavefront)
-constexpr int kDepthSortGridMax = 8192;               // workgroups of k_tile_depth_sort: eight times what is resident at once
-constexpr int kWgListMax = 6016;                      // a workgroup's list with its permutation in LDS (24 rounds per wavefront)
+constexpr int kWgListMax = 6400;                      // a workgroup's list with its permutation in LDS (25 rounds per wavefront)
 constexpr int kListChunk = 2048;                      // entries per chunk of a list that goes through global memory
 constexpr int kListRounds = kListChunk / 256;
 
@@ -259,13 +272,12 @@ struct WgSortLds {        // the workgroup's LDS when it sorts one list together
         struct { uint32_t key[kWgKeyMax]; uint16_t idx[2][kWgKeyMax]; } a;      // keys in incoming order + the permutation, twice
         struct { uint16_t idx[2][kWgListMax]; } b;                              // the permutation alone
     } u;
-    uint32_t cnt[4][256];                             // per wavefront and digit: entries in the wavefront's part of the list
-    uint32_t start[4][256];                           // per wavefront and digit: where its first entry of that digit goes
+    uint32_t cnt[4][256];                             // per wavefront and digit: entries in the wavefront's part of the list, then where its first entry of that digit goes
     uint32_t scan[4];
     uint32_t mask;
 };
 union ListSortLds { WgSortLds wg; WaveSortLds wave[4]; };
-static_assert(sizeof(ListSortLds) <= 160 * 1024 / 5, "five workgroups per compute unit");
+static_assert(sizeof(ListSortLds) <= 30 * 1024 + 512, "five workgroups per compute unit (32.3 KB did not fit five times)");
 
 // bit range [lo, hi] in which the keys differ -> number of 8-bit passes and the shift of pass p (the topmost digit
 // may reach past bit hi into bits all keys share; it never reaches past bit 31)
@@ -497,14 +509,15 @@ __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uin
                 if (lane >= d) inc += t;
             }
             const uint32_t below = inc - tot4;
+            __syncthreads();      // every wavefront has read the counts: its row now takes its starting positions
 #pragma unroll
-            for (int q = 0; q < 4; ++q) S.start[wave][4 * lane + q] = below + mine[q];
+            for (int q = 0; q < 4; ++q) S.cnt[wave][4 * lane + q] = below + mine[q];
         }
         wave_lds_sync();
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (r < nr && wb + r * 64u + lane < we) {
-                const uint32_t pos = min(S.start[wave][dp[r] & 255u] + (dp[r] >> 8), L - 1u);
+                const uint32_t pos = min(S.cnt[wave][dp[r] & 255u] + (dp[r] >> 8), L - 1u);
                 dst[pos] = src[wb + r * 64u + lane];
             }
         }
@@ -591,17 +604,17 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t* base, uin
         {   // thread = digit: where each wavefront's entries of this digit go; the digit's run moves on by the chunk's count
             const uint32_t c0w = S.cnt[0][threadIdx.x], c1w = S.cnt[1][threadIdx.x], c2w = S.cnt[2][threadIdx.x], c3w = S.cnt[3][threadIdx.x];
             const uint32_t start = base[threadIdx.x];
-            S.start[0][threadIdx.x] = start;
-            S.start[1][threadIdx.x] = start + c0w;
-            S.start[2][threadIdx.x] = start + c0w + c1w;
-            S.start[3][threadIdx.x] = start + c0w + c1w + c2w;
+            S.cnt[0][threadIdx.x] = start;
+            S.cnt[1][threadIdx.x] = start + c0w;
+            S.cnt[2][threadIdx.x] = start + c0w + c1w;
+            S.cnt[3][threadIdx.x] = start + c0w + c1w + c2w;
             base[threadIdx.x] = start + c0w + c1w + c2w + c3w;
         }
         __syncthreads();
 #pragma unroll
         for (int r = 0; r < kListRounds; ++r) {
             if (r < nr && wb + r * 64u + lane < we) {
-                const uint32_t pos = min(S.start[wave][(key[r] >> shift) & 255u] + pre[r], L - 1u);      // < L for consistent counts
+                const uint32_t pos = min(S.cnt[wave][(key[r] >> shift) & 255u] + pre[r], L - 1u);      // < L for consistent counts
                 kout[pos] = key[r]; vout[pos] = val[r];
             }
         }
@@ -647,12 +660,9 @@ __device__ __forceinline__ void wg_sort_big(WgSortLds& S, uint32_t s, uint32_t e
 }
 
 // Work items: tile_order lists the tiles longest first and its first `nbig` tiles are too long for one wavefront, so
-// items 0 .. nbig - 1 are one such list each, for the whole workgroup, and every later item is four shorter lists, one
-// per wavefront. Workgroup b takes items b, b + gridDim.x, ...: a fixed assignment with no queue, so a workgroup's big
-// items all come before its small ones, and the launch does not pay for one workgroup per tile on images whose tiles
-// are mostly short lists (an idle workgroup still costs the dispatcher a few nanoseconds).
-template <bool kLoop>
-__global__ __launch_bounds__(256, kLoop ? 4 : 5) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+// workgroups 0 .. nbig - 1 take one such list each, and every later workgroup takes four shorter lists, one per
+// wavefront.
+__global__ __launch_bounds__(256, 5) void k_tile_depth_sort(const uint32_t* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
                                                             uint32_t ntiles, const uint32_t* __restrict__ status,
                                                             const uint32_t* __restrict__ depth_bits, uint32_t cap,
                                                             uint32_t* __restrict__ keysA, uint32_t* __restrict__ valsA,
@@ -660,26 +670,19 @@ __global__ __launch_bounds__(256, kLoop ? 4 : 5) void k_tile_depth_sort(const ui
 {
     __shared__ ListSortLds U;
     const uint32_t nbig = min(status[kStNumBig], ntiles);
-    const uint32_t nitems = nbig + (ntiles - nbig + 3u) / 4u;
+    if (blockIdx.x < nbig) {
+        const uint32_t tile = tile_order[blockIdx.x];
+        wg_sort_big(U.wg, ranges[2 * tile], min(ranges[2 * tile + 1], cap), depth_bits, keysA, valsA, keysB, valsB);
+        return;
+    }
     const int wave = threadIdx.x >> 6;
-    uint32_t item = blockIdx.x;
-    if (item >= nitems) return;
-    do {
-        if (item < nbig) {
-            const uint32_t tile = tile_order[item];
-            wg_sort_big(U.wg, ranges[2 * tile], min(ranges[2 * tile + 1], cap), depth_bits, keysA, valsA, keysB, valsB);
-            __syncthreads();                       // the next item reuses the shared area
-            continue;
-        }
-        // from here on the four wavefronts go their own way: each has its own part of the shared area
-        const uint32_t idx = nbig + (item - nbig) * 4u + (uint32_t)wave;
-        if (idx >= ntiles) break;
-        const uint32_t tile = tile_order[idx];
-        const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
-        if (e <= s + 1u) continue;
-        // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
-        if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
-    } while (kLoop && (item += gridDim.x) < nitems);
+    const uint32_t idx = nbig + (blockIdx.x - nbig) * 4u + (uint32_t)wave;
+    if (idx >= ntiles) return;
+    const uint32_t tile = tile_order[idx];
+    const uint32_t s = ranges[2 * tile], e = min(ranges[2 * tile + 1], cap);
+    if (e <= s + 1u) return;
+    // (a list of kWaveListMax - 1 entries or more cannot come here: k_tile_order counted it among the first nbig)
+    if (e - s < (uint32_t)kWaveListMax - 1u) wave_sort_list(U.wave[wave], e - s, depth_bits, valsA + s);
 }
 
 hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_order, uint32_t ntiles, const uint32_t* status,
@@ -689,16 +692,12 @@ hipError_t launch_tile_depth_sort(const uint32_t* ranges, const uint32_t* tile_o
     if (ntiles == 0) return hipSuccess;
     ProfScope prof(kKTileDepthSort, s);
     // a list of the workgroup kind has at least kWaveListMax - 1 entries, which bounds how many of them `cap` pairs can
-    // hold and so how many items there can be; one workgroup per item up to kDepthSortGridMax of them, else that many
-    // workgroups that each take every gridDim.x-th item
+    // hold, and so how many workgroups can have work: the rest would only start and leave, which is not free on an
+    // image of 32,400 tiles
     const uint32_t big_max = min(ntiles, cap / (uint32_t)(kWaveListMax - 1) + 1u);
     const uint32_t items_max = min(ntiles, big_max + (ntiles + 3u) / 4u);
-    if (items_max <= (uint32_t)kDepthSortGridMax)
-        hipLaunchKernelGGL(k_tile_depth_sort<false>, dim3(items_max), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits, cap,
-                           keysA, valsA, keysB, valsB);
-    else
-        hipLaunchKernelGGL(k_tile_depth_sort<true>, dim3(kDepthSortGridMax), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits,
-                           cap, keysA, valsA, keysB, valsB);
+    hipLaunchKernelGGL(k_tile_depth_sort, dim3(items_max), dim3(256), 0, s, ranges, tile_order, ntiles, status, depth_bits, cap, keysA, valsA,
+                       keysB, valsB);
     return hipGetLastError();
 }
 
