@@ -245,8 +245,8 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 //   - up to 6400 entries: the same passes by a whole workgroup, three barriers per pass. What moves is the permutation
 //     (16-bit positions, two copies in LDS); the keys stay where they are, in incoming order - in LDS for lists of up
 //     to 2048 entries, in the global scratch array (the spent tile ids) beyond - and are fetched through it;
-//   - longer lists: the passes in chunks of 2048 through the global scratch arrays, whole-list digit counts first,
-//     then chunk by chunk in order.
+//   - longer lists: keys and values move between the global scratch arrays, each wavefront sweeping its quarter of
+//     the list once per pass (the first pass twice: count, then place; a placing sweep counts for the next pass).
 // Under 30 KB of LDS and at most 96 registers, so that five workgroups share a compute unit: the work is a chain of
 // dependent LDS and cross-lane steps per list, and what hides it is other lists in flight (measured: with 32.3 KB only
 // four were resident, and the benchmark view's sort took 53.6 us instead of 50.6). That is why the per-wavefront digit
@@ -259,8 +259,6 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 constexpr int kWaveListMax = 1024;                    // a wavefront's own list holds fewer than kWaveListMax - 1 entries (16 rounds)
 constexpr int kWgKeyMax = 2048;                       // a workgroup's list with its keys in LDS (8 rounds per wavefront)
 constexpr int kWgListMax = 6400;                      // a workgroup's list with its permutation in LDS (25 rounds per wavefront)
-constexpr int kListChunk = 2048;                      // entries per chunk of a list that goes through global memory
-constexpr int kListRounds = kListChunk / 256;
 
 struct WaveSortLds {      // a wavefront's share of the LDS when it sorts a list of its own
     uint32_t key[kWaveListMax];
@@ -560,66 +558,72 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
 }
 
 // Lists too long for LDS: one stable pass by the 8-bit digit at `shift` from (kin, vin) to (kout, vout), all of length L
-// in global memory, in chunks of kListChunk. base: 256 words of LDS, each digit's next position in the list.
-__device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t* base, uint32_t L, int shift, const uint32_t* __restrict__ kin,
+// in global memory. Each wavefront takes a contiguous quarter of the list, in rounds of 64. `cur` holds, per wavefront
+// and digit, how many of its entries have that digit: counted here in a sweep of its own if `count_first`, else by
+// the previous pass, which knew where every entry went and so in whose quarter it would be (that is what `nxt` and
+// `next_shift` are for: pass a negative shift when no pass follows). The counters are then turned into where the
+// wavefront's first entry of each digit goes, and a sweep places the entries: digit_prefix() hands back the counter's
+// value before the round's entries were added plus the lane's rank among them, which now is the entry's position.
+// Nothing is kept per entry between the sweeps, so the list may be of any length.
+__device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t (*cur)[256], uint32_t (*nxt)[256], bool count_first, uint32_t L,
+                                               int shift, int next_shift, const uint32_t* __restrict__ kin,
                                                const uint32_t* __restrict__ vin, uint32_t* __restrict__ kout, uint32_t* __restrict__ vout)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-    base[threadIdx.x] = 0u;
-    __syncthreads();
-    for (uint32_t i0 = wave * 64u; i0 < L; i0 += 256u) {      // digit counts of the whole list
-        const uint32_t i = i0 + lane;
-        const bool valid = i < L;
-        const uint32_t digit = valid ? (kin[i] >> shift) & 255u : 0u;
-        const uint64_t peers = digit_peers<8>(digit, valid);
-        if (valid && (peers & lt_mask) == 0ull) atomicAdd(&base[digit], (uint32_t)__popcll(peers));
-    }
-    __syncthreads();
-    {
-        const uint32_t c = base[threadIdx.x];
-        const uint32_t start = block_exclusive_scan(c, S.scan);      // where each digit's run starts
-        base[threadIdx.x] = start;
-    }
-    __syncthreads();
-    for (uint32_t c0 = 0; c0 < L; c0 += kListChunk) {
-        const uint32_t cn = min((uint32_t)kListChunk, L - c0);
-        const uint32_t per_wave = ((cn + 255u) / 256u) * 64u;
-        const int nr = (int)(per_wave / 64u);
-        const uint32_t wb = c0 + wave * per_wave, we = min(c0 + cn, wb + per_wave);
+    const uint32_t per_wave = ((L + 255u) / 256u) * 64u;
+    const uint32_t wb = min(L, wave * per_wave), we = min(L, wb + per_wave);
+    if (count_first) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) S.cnt[wave][q * 64 + lane] = 0u;
+        for (int q = 0; q < 4; ++q) cur[wave][q * 64 + lane] = 0u;
         wave_lds_sync();
-        uint32_t key[kListRounds], val[kListRounds], pre[kListRounds];
+        for (uint32_t i0 = wb; i0 < we; i0 += 8u * 64u) {      // eight key fetches in flight at a time
+            uint32_t k[8];
 #pragma unroll
-        for (int r = 0; r < kListRounds; ++r) {      // the chunk's loads first, all in flight together
-            const uint32_t i = wb + r * 64u + lane;
-            key[r] = 0u; val[r] = 0u;
-            if (r < nr && i < we) { key[r] = kin[i]; val[r] = vin[i]; }
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t i = i0 + j * 64u + lane;
+                k[j] = i < we ? kin[i] : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (i0 + j * 64u < we) digit_prefix(cur[wave], (k[j] >> shift) & 255u, i0 + j * 64u + lane < we);
+        }
+    }
+    __syncthreads();      // every wavefront's counts are in
+    {   // thread = digit: the digit's run starts after all smaller digits; inside it the wavefronts follow each other
+        const uint32_t c0w = cur[0][threadIdx.x], c1w = cur[1][threadIdx.x], c2w = cur[2][threadIdx.x], c3w = cur[3][threadIdx.x];
+        const uint32_t start = block_exclusive_scan(c0w + c1w + c2w + c3w, S.scan);
+        cur[0][threadIdx.x] = start;
+        cur[1][threadIdx.x] = start + c0w;
+        cur[2][threadIdx.x] = start + c0w + c1w;
+        cur[3][threadIdx.x] = start + c0w + c1w + c2w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) nxt[q][threadIdx.x] = 0u;
+    }
+    __syncthreads();
+    for (uint32_t i0 = wb; i0 < we; i0 += 8u * 64u) {
+        uint32_t k[8], v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = i0 + j * 64u + lane;
+            k[j] = 0u; v[j] = 0u;
+            if (i < we) { k[j] = kin[i]; v[j] = vin[i]; }
         }
 #pragma unroll
-        for (int r = 0; r < kListRounds; ++r)
-            if (r < nr) pre[r] = digit_prefix(S.cnt[wave], (key[r] >> shift) & 255u, wb + r * 64u + lane < we);
-        __syncthreads();
-        {   // thread = digit: where each wavefront's entries of this digit go; the digit's run moves on by the chunk's count
-            const uint32_t c0w = S.cnt[0][threadIdx.x], c1w = S.cnt[1][threadIdx.x], c2w = S.cnt[2][threadIdx.x], c3w = S.cnt[3][threadIdx.x];
-            const uint32_t start = base[threadIdx.x];
-            S.cnt[0][threadIdx.x] = start;
-            S.cnt[1][threadIdx.x] = start + c0w;
-            S.cnt[2][threadIdx.x] = start + c0w + c1w;
-            S.cnt[3][threadIdx.x] = start + c0w + c1w + c2w;
-            base[threadIdx.x] = start + c0w + c1w + c2w + c3w;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < kListRounds; ++r) {
-            if (r < nr && wb + r * 64u + lane < we) {
-                const uint32_t pos = min(S.cnt[wave][(key[r] >> shift) & 255u] + pre[r], L - 1u);      // < L for consistent counts
-                kout[pos] = key[r]; vout[pos] = val[r];
+        for (int j = 0; j < 8; ++j) {
+            if (i0 + j * 64u < we) {
+                const bool valid = i0 + j * 64u + lane < we;
+                const uint32_t pos = min(digit_prefix(cur[wave], (k[j] >> shift) & 255u, valid), L - 1u);      // < L for consistent counts
+                if (valid) {
+                    kout[pos] = k[j]; vout[pos] = v[j];
+                    if (next_shift >= 0) {      // the next pass finds this entry in the quarter of wavefront pos / per_wave
+                        const uint32_t w2 = (pos >= per_wave ? 1u : 0u) + (pos >= 2u * per_wave ? 1u : 0u) + (pos >= 3u * per_wave ? 1u : 0u);
+                        atomicAdd(&nxt[w2][(k[j] >> next_shift) & 255u], 1u);
+                    }
+                }
             }
         }
-        __syncthreads();      // the count rows are cleared and the position rows rewritten by the next chunk
     }
+    __syncthreads();      // the pass is written and the next pass's counts are complete
 }
 
 // One list too long for a wavefront, sorted by the whole workgroup (every exit is uniform for the workgroup).
@@ -650,10 +654,13 @@ __device__ __forceinline__ void wg_sort_big(WgSortLds& S, uint32_t s, uint32_t e
     if (mask == 0u) return;                        // one depth throughout: point order is the order
     int lo;
     const int passes = list_passes(mask, lo);
-    uint32_t* base = reinterpret_cast<uint32_t*>(&S.u);      // the key / permutation area is idle on this path
+    // two sets of counters that swap roles from pass to pass: S.cnt and a piece of the key / permutation area, idle here
+    uint32_t (*c0)[256] = S.cnt;
+    uint32_t (*c1)[256] = reinterpret_cast<uint32_t (*)[256]>(&S.u);
     for (int p = 0; p < passes; ++p) {
-        if ((p & 1) == 0) long_list_pass(S, base, L, list_shift(lo, p), keysA + s, valsA + s, keysB + s, valsB + s);
-        else long_list_pass(S, base, L, list_shift(lo, p), keysB + s, valsB + s, keysA + s, valsA + s);
+        const int next_shift = p + 1 < passes ? list_shift(lo, p + 1) : -1;
+        if ((p & 1) == 0) long_list_pass(S, c0, c1, p == 0, L, list_shift(lo, p), next_shift, keysA + s, valsA + s, keysB + s, valsB + s);
+        else long_list_pass(S, c1, c0, false, L, list_shift(lo, p), next_shift, keysB + s, valsB + s, keysA + s, valsA + s);
     }
     if (passes & 1)
         for (uint32_t i = threadIdx.x; i < L; i += 256u) valsA[s + i] = valsB[s + i];

@@ -57,7 +57,7 @@ def test_lists_all_equal_depth_one_tile():
     assert np.array_equal(got["keys"], ref["keys"])
 
 
-@pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 257, 511, 600, 1021, 1022, 1023, 2048, 2049, 4097, 6400, 6401, 9000])
+@pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 257, 511, 600, 1021, 1022, 1023, 2048, 2049, 4097, 6400, 6401, 9000, 70001])
 @pytest.mark.parametrize("kind", ["narrow", "wide", "two_values", "wide_short_runs"])
 def test_one_crowded_tile_depth_order(n, kind):
     """Every splat in one tile: the list's depth order is made by one workgroup - by counting up to 256 entries, in LDS up
