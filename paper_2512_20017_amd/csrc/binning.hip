@@ -197,8 +197,9 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint32_t* __restrict_
 // over the classes present: the kernel runs on one compute unit, so its instruction count is its duration.
 constexpr int kOrderClasses = 40;           // < 63; class 63 stands for "no tile"
 constexpr uint32_t kOrderRounds = 8;        // rounds of 64 tiles whose ranges are loaded together (one trip to memory, not eight)
-// lists of 1023 entries or more are sorted by a whole workgroup (radix_sort.hip: kWaveListMax - 1); length + 1 < 1024 =
-// 2^10 means a class code of at most 2 * 9 + 1
+// lists of kWaveListMax - 1 = 1023 entries or more are sorted by a whole workgroup; length + 1 < 1024 = 2^10 means a
+// class code of at most 2 * 9 + 1
+static_assert(kWaveListMax == 1024, "kFirstSmallClass is the class that starts at this length");
 constexpr uint32_t kFirstSmallClass = (uint32_t)(kOrderClasses - 1) - 19u;
 
 __device__ __forceinline__ uint32_t order_class(uint32_t len)
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(1024) void k_tile_order(const uint32_t* __restrict_
         for (int k = 0; k < kPer; ++k) { count[lane * kPer + k] = at; at += v[k]; }
     }
     __syncthreads();
-    // how many tiles hold 1023 entries or more: they come first in the order, and the depth sort gives each a whole
+    // how many tiles hold kWaveListMax - 1 entries or more: they come first in the order, and the depth sort gives each a whole
     // workgroup (the classes are cut at powers of two of length + 1, so this is where a class starts)
     if (threadIdx.x == 0 && blockIdx.x == 0) status[kStNumBig] = count[kFirstSmallClass * kOrderSlots];
 #pragma unroll

@@ -133,6 +133,10 @@ struct Layout {
         off_partial, off_keys64, off_chunk_rank, off_carry, off_grad_rec, off_reach, off_tile_order, total;
 };
 constexpr int kSortItems = 2048;   // pairs per radix-sort block
+// A tile's list of fewer than kWaveListMax - 1 entries is put in depth order by one wavefront, a longer one by a whole
+// workgroup (radix_sort.hip); k_tile_order (binning.hip) counts the longer ones, so the value must be where two of its
+// length classes meet: a power of two or 1.5 times one.
+constexpr int kWaveListMax = 1024;
 constexpr int kRadixMaxBins = 256;   // widest digit: 8 bits
 int radix_pass_count(int key_bits);  // passes launch_radix_sort32 takes for this many key bits
 bool make_layout(int n, int W, int H, uint64_t cap, int variant, Layout* L);

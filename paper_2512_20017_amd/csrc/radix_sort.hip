@@ -237,10 +237,11 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 // (tile << 32 | depth bits), ties by point index. One launch, every list on its own:
 //   - fewer than 1023 entries (k_tile_order lists the tiles longest first and says how many have more): one WAVEFRONT
 //     per list, four lists per workgroup, no workgroup barrier anywhere: up to 64 entries by counting (every lane
-//     compares its key with all others through the scalar unit), else least-significant-digit radix passes with 8-bit
-//     digits over the bit positions in which the list's keys differ at all (depths of one tile share sign, most
-//     exponent bits and often more). Keys and positions live in registers in list order; a pass scatters them into the
-//     wavefront's 7 KB of LDS and reads them back in the new order (lists of 511 to 1022 entries took a whole workgroup
+//     compares its key with all others through the scalar unit), else least-significant-digit radix passes with 9-bit
+//     digits over the bit positions in which the list's keys differ at all (depths of one tile share sign and most
+//     exponent bits: about 26 bits differ, which is three 9-bit digits where 8-bit digits took four passes; the 512
+//     counters fit the space of 256 because they are 16 bits wide, two to a word). Keys and positions live in
+//     registers in list order; a pass scatters them into the wavefront's 7 KB of LDS and reads them back in the new order (lists of 511 to 1022 entries took a whole workgroup
 //     before: four wavefront slots for 16 us each where one wavefront now takes them, 57 -> 53 us);
 //   - up to 6400 entries: the same passes by a whole workgroup, three barriers per pass. What moves is the permutation
 //     (16-bit positions, two copies in LDS); the keys stay where they are, in incoming order - in LDS for lists of up
@@ -256,47 +257,56 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
 // digit came before (earlier rounds of the wavefront: LDS executes a wavefront's operations in order), and hands that
 // to its group through the LDS crossbar: equal digits keep their incoming order.
 // ---------------------------------------------------------------------------------------------
-constexpr int kWaveListMax = 1024;                    // a wavefront's own list holds fewer than kWaveListMax - 1 entries (16 rounds)
+constexpr int kListBits = 9;                          // digit width of the list sorts: depths of one tile differ in about 26 bits, three digits
+constexpr int kListBins = 1 << kListBits;
+constexpr int kListWords = kListBins / 2;             // counters in LDS are 16 bits wide, two digits to a word (the LDS adds 32-bit words)
+constexpr int kPerLane = kListWords / 64;             // a wavefront's counter words, per lane
+static_assert(kWaveListMax % 64 == 0, "whole rounds");
 constexpr int kWgKeyMax = 2048;                       // a workgroup's list with its keys in LDS (8 rounds per wavefront)
 constexpr int kWgListMax = 6400;                      // a workgroup's list with its permutation in LDS (25 rounds per wavefront)
 
 struct WaveSortLds {      // a wavefront's share of the LDS when it sorts a list of its own
     uint32_t key[kWaveListMax];
     uint16_t idx[kWaveListMax];
-    uint32_t hist[256];
+    uint32_t hist[kListWords];
 };
 struct WgSortLds {        // the workgroup's LDS when it sorts one list together
     union {
         struct { uint32_t key[kWgKeyMax]; uint16_t idx[2][kWgKeyMax]; } a;      // keys in incoming order + the permutation, twice
         struct { uint16_t idx[2][kWgListMax]; } b;                              // the permutation alone
     } u;
-    uint32_t cnt[4][256];                             // per wavefront and digit: entries in the wavefront's part of the list, then where its first entry of that digit goes
+    uint32_t cnt[4][kListWords];                             // per wavefront and digit: entries in the wavefront's part of the list, then where its first entry of that digit goes
     uint32_t scan[4];
     uint32_t mask;
 };
 union ListSortLds { WgSortLds wg; WaveSortLds wave[4]; };
 static_assert(sizeof(ListSortLds) <= 30 * 1024 + 512, "five workgroups per compute unit (32.3 KB did not fit five times)");
 
-// bit range [lo, hi] in which the keys differ -> number of 8-bit passes and the shift of pass p (the topmost digit
+// bit range [lo, hi] in which the keys differ -> number of kListBits-bit passes and the shift of pass p (the topmost digit
 // may reach past bit hi into bits all keys share; it never reaches past bit 31)
 __device__ __forceinline__ int list_passes(uint32_t diff, int& lo)
 {
     lo = __builtin_ctz(diff);
     const int hi = 31 - __builtin_clz(diff);
-    return (hi - lo + 8) / 8;
+    return (hi - lo + kListBits) / kListBits;
 }
-__device__ __forceinline__ int list_shift(int lo, int p) { return min(lo + 8 * p, 24); }
+__device__ __forceinline__ int list_shift(int lo, int p) { return min(lo + kListBits * p, 32 - kListBits); }
 
-// Entries of this wavefront with the same 8-bit digit as this lane's that come before it: earlier rounds (through the
+// Entries of this wavefront with the same digit as this lane's that come before it: earlier rounds (through the
 // digit's counter in `hist`, a row no other wavefront touches) plus lower lanes of this round. The lanes that share the
 // digit are found bit by bit: a lane differs from this one if, for some bit, its bit (one ballot per bit) is not this
 // lane's bit (sign-extended to a mask); both halves of the 64-lane sets are kept in 32-bit registers.
+// kPacked: the counters are 16 bits wide, digit d in half d & 1 of word d >> 1 (for lists of fewer than 65,536 entries:
+// no half ever carries into its neighbour); else one word per digit.
+__device__ __forceinline__ uint32_t packed_half(uint32_t word, uint32_t digit) { return (word >> ((digit & 1u) << 4)) & 0xffffu; }
+
+template <bool kPacked>
 __device__ __forceinline__ uint32_t digit_prefix(uint32_t* hist, uint32_t digit, bool valid)
 {
     const int lane = threadIdx.x & 63;
     uint32_t dlo = 0u, dhi = 0u;
 #pragma unroll
-    for (int bit = 0; bit < 8; ++bit) {
+    for (int bit = 0; bit < kListBits; ++bit) {
         const uint32_t ext = (uint32_t)__builtin_amdgcn_sbfe((int)digit, bit, 1);      // 0 or ~0
         const uint64_t m = __ballot(ext != 0u);
         dlo |= (uint32_t)m ^ ext;
@@ -308,27 +318,40 @@ __device__ __forceinline__ uint32_t digit_prefix(uint32_t* hist, uint32_t digit,
     const uint32_t below_lo = lane < 32 ? (1u << lane) - 1u : ~0u, below_hi = lane < 32 ? 0u : (1u << (lane - 32)) - 1u;
     const uint32_t rank = (uint32_t)__popc(plo & below_lo) + (uint32_t)__popc(phi & below_hi);
     uint32_t before = 0u;
-    if (valid && rank == 0u) before = atomicAdd(&hist[digit], (uint32_t)__popc(plo) + (uint32_t)__popc(phi));
+    if (valid && rank == 0u) {
+        const uint32_t group = (uint32_t)__popc(plo) + (uint32_t)__popc(phi);
+        if (kPacked) before = packed_half(atomicAdd(&hist[digit >> 1], group << ((digit & 1u) << 4)), digit);
+        else before = atomicAdd(&hist[digit], group);
+    }
     const int leader = !valid ? lane : (plo ? __builtin_ctz(plo) : 32 + __builtin_ctz(phi));
     before = (uint32_t)__builtin_amdgcn_ds_bpermute(leader << 2, (int)before);
     return before + rank;
 }
 
-// exclusive scan over a wavefront's 256 digit counters, four consecutive digits per lane, in place
+// exclusive scan over a wavefront's packed digit counters, 2 * kPerLane consecutive digits per lane, in place
 __device__ __forceinline__ void wave_scan_digits(uint32_t* hist)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
-    const uint32_t tot = c0 + c1 + c2 + c3;
+    uint32_t c[2 * kPerLane], tot = 0u;
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) {
+        const uint32_t w = hist[kPerLane * lane + q];
+        c[2 * q] = w & 0xffffu; c[2 * q + 1] = w >> 16;
+        tot += c[2 * q] + c[2 * q + 1];
+    }
     uint32_t inc = tot;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t t = __shfl_up(inc, d, 64);
         if (lane >= d) inc += t;
     }
-    const uint32_t start = inc - tot;
-    hist[4 * lane] = start; hist[4 * lane + 1] = start + c0; hist[4 * lane + 2] = start + c0 + c1;
-    hist[4 * lane + 3] = start + c0 + c1 + c2;
+    uint32_t at = inc - tot;
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) {
+        const uint32_t a0 = at, a1 = at + c[2 * q];
+        hist[kPerLane * lane + q] = a0 | (a1 << 16);
+        at = a1 + c[2 * q + 1];
+    }
 }
 
 __device__ __forceinline__ void wave_lds_sync()      // orders this wavefront's LDS writes before its later LDS reads
@@ -378,19 +401,20 @@ __device__ __forceinline__ void wave_sort_list(WaveSortLds& W, uint32_t L, const
     const int passes = list_passes(diff, lo);
     auto one_pass = [&](int shift) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) W.hist[q * 64 + lane] = 0u;
+        for (int q = 0; q < kPerLane; ++q) W.hist[q * 64 + lane] = 0u;
         wave_lds_sync();
         uint32_t pre[R];
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            if (r < nr) pre[r] = digit_prefix(W.hist, (key[r] >> shift) & 255u, r * 64u + lane < L);
+            if (r < nr) pre[r] = digit_prefix<true>(W.hist, (key[r] >> shift) & (kListBins - 1u), r * 64u + lane < L);
         wave_lds_sync();
         wave_scan_digits(W.hist);
         wave_lds_sync();
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (r < nr && r * 64u + lane < L) {
-                const uint32_t pos = min(W.hist[(key[r] >> shift) & 255u] + pre[r], L - 1u);
+                const uint32_t digit = (key[r] >> shift) & (kListBins - 1u);
+                const uint32_t pos = min(packed_half(W.hist[digit >> 1], digit) + pre[r], L - 1u);
                 W.key[pos] = key[r]; W.idx[pos] = (uint16_t)id[r];
             }
         }
@@ -468,9 +492,9 @@ __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uin
     auto one_pass = [&](int shift) {
         // (this wavefront's count row was last read by the others before the barrier that ended the previous pass)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) S.cnt[wave][q * 64 + lane] = 0u;
+        for (int q = 0; q < kPerLane; ++q) S.cnt[wave][q * 64 + lane] = 0u;
         wave_lds_sync();
-        uint32_t dp[R];      // per entry of this lane: digit | (entries of that digit before it in this wavefront's part) << 8
+        uint32_t dp[R];      // per entry of this lane: digit | (entries of that digit before it in this wavefront's part) << kListBits
 #pragma unroll
         for (int r0 = 0; r0 < R; r0 += 8) {       // eight key fetches in flight at a time
             if (r0 >= nr) break;
@@ -484,38 +508,43 @@ __device__ __forceinline__ void wg_sort_list(WgSortLds& S, uint32_t L, const uin
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 if (r0 + j < nr) {
-                    const uint32_t digit = (k[j] >> shift) & 255u;
-                    const uint32_t v = digit | (digit_prefix(S.cnt[wave], digit, wb + (r0 + j) * 64u + lane < we) << 8);
+                    const uint32_t digit = (k[j] >> shift) & (kListBins - 1u);
+                    const uint32_t v = digit | (digit_prefix<true>(S.cnt[wave], digit, wb + (r0 + j) * 64u + lane < we) << kListBits);
                     if (r0 + j < R) dp[r0 + j] = v;
                 }
             }
         }
         __syncthreads();      // every wavefront has counted
         {   // every wavefront works out where its own entries of each digit go: digits before, then the wavefronts before it
-            uint32_t mine[4], tot4 = 0u;
+            uint32_t mine[2 * kPerLane], tot = 0u;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int d = 4 * lane + q;
-                const uint32_t c0 = S.cnt[0][d], c1 = S.cnt[1][d], c2 = S.cnt[2][d], c3 = S.cnt[3][d];
-                mine[q] = tot4 + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
-                tot4 += c0 + c1 + c2 + c3;
+            for (int q = 0; q < kPerLane; ++q) {
+                const int d = kPerLane * lane + q;
+                const uint32_t w0 = S.cnt[0][d], w1 = S.cnt[1][d], w2 = S.cnt[2][d], w3 = S.cnt[3][d];
+                const uint32_t before = (wave > 0 ? w0 : 0u) + (wave > 1 ? w1 : 0u) + (wave > 2 ? w2 : 0u);      // both halves at once
+                const uint32_t all = w0 + w1 + w2 + w3;      // (a digit's count over the list is below 65,536)
+                mine[2 * q] = tot + (before & 0xffffu);
+                tot += all & 0xffffu;
+                mine[2 * q + 1] = tot + (before >> 16);
+                tot += all >> 16;
             }
-            uint32_t inc = tot4;
+            uint32_t inc = tot;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
                 const uint32_t t = __shfl_up(inc, d, 64);
                 if (lane >= d) inc += t;
             }
-            const uint32_t below = inc - tot4;
+            const uint32_t below = inc - tot;
             __syncthreads();      // every wavefront has read the counts: its row now takes its starting positions
 #pragma unroll
-            for (int q = 0; q < 4; ++q) S.cnt[wave][4 * lane + q] = below + mine[q];
+            for (int q = 0; q < kPerLane; ++q) S.cnt[wave][kPerLane * lane + q] = (below + mine[2 * q]) | ((below + mine[2 * q + 1]) << 16);
         }
         wave_lds_sync();
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (r < nr && wb + r * 64u + lane < we) {
-                const uint32_t pos = min(S.cnt[wave][dp[r] & 255u] + (dp[r] >> 8), L - 1u);
+                const uint32_t digit = dp[r] & (kListBins - 1u);
+                const uint32_t pos = min(packed_half(S.cnt[wave][digit >> 1], digit) + (dp[r] >> kListBits), L - 1u);
                 dst[pos] = src[wb + r * 64u + lane];
             }
         }
@@ -557,7 +586,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
     return below;
 }
 
-// Lists too long for LDS: one stable pass by the 8-bit digit at `shift` from (kin, vin) to (kout, vout), all of length L
+// Lists too long for LDS: one stable pass by the digit at `shift` from (kin, vin) to (kout, vout), all of length L
 // in global memory. Each wavefront takes a contiguous quarter of the list, in rounds of 64. `cur` holds, per wavefront
 // and digit, how many of its entries have that digit: counted here in a sweep of its own if `count_first`, else by
 // the previous pass, which knew where every entry went and so in whose quarter it would be (that is what `nxt` and
@@ -565,7 +594,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
 // wavefront's first entry of each digit goes, and a sweep places the entries: digit_prefix() hands back the counter's
 // value before the round's entries were added plus the lane's rank among them, which now is the entry's position.
 // Nothing is kept per entry between the sweeps, so the list may be of any length.
-__device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t (*cur)[256], uint32_t (*nxt)[256], bool count_first, uint32_t L,
+__device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t (*cur)[kListBins], uint32_t (*nxt)[kListBins], bool count_first, uint32_t L,
                                                int shift, int next_shift, const uint32_t* __restrict__ kin,
                                                const uint32_t* __restrict__ vin, uint32_t* __restrict__ kout, uint32_t* __restrict__ vout)
 {
@@ -574,7 +603,7 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t (*cur)[256
     const uint32_t wb = min(L, wave * per_wave), we = min(L, wb + per_wave);
     if (count_first) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) cur[wave][q * 64 + lane] = 0u;
+        for (int q = 0; q < kListBins / 64; ++q) cur[wave][q * 64 + lane] = 0u;
         wave_lds_sync();
         for (uint32_t i0 = wb; i0 < we; i0 += 8u * 64u) {      // eight key fetches in flight at a time
             uint32_t k[8];
@@ -585,19 +614,28 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t (*cur)[256
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                if (i0 + j * 64u < we) digit_prefix(cur[wave], (k[j] >> shift) & 255u, i0 + j * 64u + lane < we);
+                if (i0 + j * 64u < we) digit_prefix<false>(cur[wave], (k[j] >> shift) & (kListBins - 1u), i0 + j * 64u + lane < we);
         }
     }
     __syncthreads();      // every wavefront's counts are in
-    {   // thread = digit: the digit's run starts after all smaller digits; inside it the wavefronts follow each other
-        const uint32_t c0w = cur[0][threadIdx.x], c1w = cur[1][threadIdx.x], c2w = cur[2][threadIdx.x], c3w = cur[3][threadIdx.x];
-        const uint32_t start = block_exclusive_scan(c0w + c1w + c2w + c3w, S.scan);
-        cur[0][threadIdx.x] = start;
-        cur[1][threadIdx.x] = start + c0w;
-        cur[2][threadIdx.x] = start + c0w + c1w;
-        cur[3][threadIdx.x] = start + c0w + c1w + c2w;
+    {   // two consecutive digits per thread: a digit's run starts after all smaller digits; inside it the wavefronts follow each other
+        static_assert(kListBins == 2 * 256, "two digits per thread");
+        const uint32_t d0 = 2u * threadIdx.x;
+        uint32_t c[2][4], tot[2];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) nxt[q][threadIdx.x] = 0u;
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) c[h][w] = cur[w][d0 + h];
+            tot[h] = (c[h][0] + c[h][1]) + (c[h][2] + c[h][3]);
+        }
+        uint32_t start = block_exclusive_scan(tot[0] + tot[1], S.scan);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t at = start;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { cur[w][d0 + h] = at; at += c[h][w]; nxt[w][d0 + h] = 0u; }
+            start += tot[h];
+        }
     }
     __syncthreads();
     for (uint32_t i0 = wb; i0 < we; i0 += 8u * 64u) {
@@ -612,12 +650,12 @@ __device__ __forceinline__ void long_list_pass(WgSortLds& S, uint32_t (*cur)[256
         for (int j = 0; j < 8; ++j) {
             if (i0 + j * 64u < we) {
                 const bool valid = i0 + j * 64u + lane < we;
-                const uint32_t pos = min(digit_prefix(cur[wave], (k[j] >> shift) & 255u, valid), L - 1u);      // < L for consistent counts
+                const uint32_t pos = min(digit_prefix<false>(cur[wave], (k[j] >> shift) & (kListBins - 1u), valid), L - 1u);      // < L for consistent counts
                 if (valid) {
                     kout[pos] = k[j]; vout[pos] = v[j];
                     if (next_shift >= 0) {      // the next pass finds this entry in the quarter of wavefront pos / per_wave
                         const uint32_t w2 = (pos >= per_wave ? 1u : 0u) + (pos >= 2u * per_wave ? 1u : 0u) + (pos >= 3u * per_wave ? 1u : 0u);
-                        atomicAdd(&nxt[w2][(k[j] >> next_shift) & 255u], 1u);
+                        atomicAdd(&nxt[w2][(k[j] >> next_shift) & (kListBins - 1u)], 1u);
                     }
                 }
             }
@@ -654,9 +692,10 @@ __device__ __forceinline__ void wg_sort_big(WgSortLds& S, uint32_t s, uint32_t e
     if (mask == 0u) return;                        // one depth throughout: point order is the order
     int lo;
     const int passes = list_passes(mask, lo);
-    // two sets of counters that swap roles from pass to pass: S.cnt and a piece of the key / permutation area, idle here
-    uint32_t (*c0)[256] = S.cnt;
-    uint32_t (*c1)[256] = reinterpret_cast<uint32_t (*)[256]>(&S.u);
+    // two sets of full-width counters that swap roles from pass to pass, in the key / permutation area, idle here
+    uint32_t (*c0)[kListBins] = reinterpret_cast<uint32_t (*)[kListBins]>(&S.u);
+    uint32_t (*c1)[kListBins] = c0 + 4;
+    static_assert(sizeof(S.u) >= 2 * 4 * kListBins * sizeof(uint32_t), "room for both sets of counters");
     for (int p = 0; p < passes; ++p) {
         const int next_shift = p + 1 < passes ? list_shift(lo, p + 1) : -1;
         if ((p & 1) == 0) long_list_pass(S, c0, c1, p == 0, L, list_shift(lo, p), next_shift, keysA + s, valsA + s, keysB + s, valsB + s);
