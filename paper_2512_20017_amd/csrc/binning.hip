@@ -52,19 +52,20 @@ __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, 
 // status words and the pair total behind the last rank's offset. Also the order in which the packing kernel takes the
 // blocks: those with kHeavyBlockPairs pairs or more first (in index order), the others after them (from the back, in
 // reverse index order: one pass, no second scan).
-// Workgroup g takes the kScanChunk blocks from g * kScanChunk on. What came before them it adds up by itself from the
-// counts (a few coalesced loads per thread), so no workgroup waits for another: a million points are one workgroup, and
-// eight million are eight that each do one chunk instead of one that does eight in a row.
+// Workgroup g takes the 1024 kPer blocks from g * 1024 kPer on. What came before them it adds up by itself from the
+// counts (a few coalesced loads per thread), so no workgroup waits for another, and eight million points are eight
+// workgroups that each do one chunk instead of one that does eight in a row.
 constexpr uint32_t kHeavyBlockPairs = 1536;      // about twice the benchmark view's mean
-constexpr uint32_t kScanPer = 4;                 // consecutive blocks per thread
-constexpr uint32_t kScanChunk = 1024u * kScanPer;
-
+// kPer consecutive blocks per thread, 1024 kPer per workgroup: one up to two million points (four workgroups at a
+// million: 5.4 us against 6.9 for one), four beyond (eight million points: 10.7 us against 13.8 for 31 workgroups
+// of 1024 blocks, whose sums over what precedes them then take longer than their own chunk)
+template <uint32_t kPer>
 __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t* __restrict__ blk_vis, const uint32_t* __restrict__ blk_pairs, uint32_t nb,
                                                       uint32_t* __restrict__ blk_vis_at, uint32_t* __restrict__ blk_pairs_at,
                                                       uint32_t* __restrict__ status, uint32_t* __restrict__ offsets, uint32_t n,
                                                       uint32_t* __restrict__ blk_order)
 {
-    constexpr uint32_t kPer = kScanPer;
+    constexpr uint32_t kScanChunk = 1024u * kPer;
     __shared__ uint32_t sV[16], sP[16], sH[16];
     __shared__ uint32_t cV[16], cP[16], cH[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -385,9 +386,16 @@ hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Lay
     ProfScope prof(kKCountPack, s);
     hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), blk_vis,
                        blk_pairs, status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
-    hipLaunchKernelGGL(k_scan_blocks, dim3((nb + kScanChunk - 1u) / kScanChunk), dim3(1024), 0, s, blk_vis, blk_pairs, nb,
-                       reinterpret_cast<uint32_t*>(ws + L.off_blk_vis_at), reinterpret_cast<uint32_t*>(ws + L.off_blk_pairs_at), status,
-                       reinterpret_cast<uint32_t*>(ws + L.off_offsets), (uint32_t)n, reinterpret_cast<uint32_t*>(ws + L.off_blk_order));
+    uint32_t* const vis_at = reinterpret_cast<uint32_t*>(ws + L.off_blk_vis_at);
+    uint32_t* const pairs_at = reinterpret_cast<uint32_t*>(ws + L.off_blk_pairs_at);
+    uint32_t* const offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
+    uint32_t* const blk_order = reinterpret_cast<uint32_t*>(ws + L.off_blk_order);
+    if (nb <= 8192u)
+        hipLaunchKernelGGL(k_scan_blocks<1>, dim3((nb + 1023u) / 1024u), dim3(1024), 0, s, blk_vis, blk_pairs, nb, vis_at, pairs_at, status,
+                           offsets, (uint32_t)n, blk_order);
+    else
+        hipLaunchKernelGGL(k_scan_blocks<4>, dim3((nb + 4095u) / 4096u), dim3(1024), 0, s, blk_vis, blk_pairs, nb, vis_at, pairs_at, status,
+                           offsets, (uint32_t)n, blk_order);
     return hipGetLastError();
 }
 
