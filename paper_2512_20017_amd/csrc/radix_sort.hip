@@ -155,21 +155,26 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint32_t* __restric
         tot[j] = d < kBins ? totals[d] : 0u;
         tile_off[j] = d < kBins ? hist_scanned[(size_t)d * ntiles + blockIdx.x] : 0u;
     }
+    // this wavefront's consecutive pairs, in rounds of 64, kept in registers together with each pair's rank among
+    // the equal digits of its round and the size of that group
+    uint32_t key[kSortPerThread], val[kSortPerThread], rank[kSortPerThread], group[kSortPerThread];
+    // (all sixteen loads first: written as one loop with the ranking, each round waited for its own two)
+#pragma unroll
+    for (int k = 0; k < kSortPerThread; ++k) {
+        const uint32_t idx = wbase + k * 64 + lane;
+        key[k] = 0u; val[k] = 0u;
+        if (idx < count) { key[k] = keys_in[idx]; val[k] = vals_in[idx]; }
+    }
     for (int d = threadIdx.x; d < kBins; d += 256) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) wave_base[w][d] = 0;
     }
     __syncthreads();
-    // this wavefront's consecutive pairs, in rounds of 64, kept in registers together with each pair's rank among
-    // the equal digits of its round and the size of that group
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    uint32_t key[kSortPerThread], val[kSortPerThread], rank[kSortPerThread], group[kSortPerThread];
 #pragma unroll
     for (int k = 0; k < kSortPerThread; ++k) {
         const uint32_t idx = wbase + k * 64 + lane;
         const bool valid = idx < count;
-        key[k] = 0u; val[k] = 0u;
-        if (valid) { key[k] = keys_in[idx]; val[k] = vals_in[idx]; }
         const uint32_t digit = (key[k] >> shift) & kMask;
         const uint64_t peers = digit_peers<kBits>(digit, valid);
         rank[k] = (uint32_t)__popcll(peers & lt_mask);
