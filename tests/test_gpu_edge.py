@@ -47,6 +47,26 @@ def test_lists_random_states_with_ties(w, h, n, seed):
     assert np.array_equal(got["ranges"], ref["ranges"])
 
 
+@pytest.mark.parametrize("n", [262144, 262145, 263000, 1048577 + 256, 2097152 + 300])
+def test_lists_point_counts_around_a_scan_chunk(n):
+    """The block scan and the packing order are made by one workgroup per 1,024 blocks of 256 points, each adding up what
+    precedes its chunk by itself: point counts of exactly one chunk, one point more, a short second chunk, and a fifth
+    chunk of two blocks, and just past two million points (from where a workgroup takes 4,096 blocks), with heavy and
+    light blocks mixed (a few splats of large radius)."""
+    rng = np.random.default_rng(n % 1000)
+    w, h = 640, 360
+    st = _rand_state(rng, n, w, h, rmax=3)
+    big = rng.integers(0, n, 40)
+    st["radius"][big] = rng.integers(100, 400, 40)
+    st["radius"][rng.integers(0, n, n // 2)] = 0
+    depth = rng.uniform(0.3, 50, n).astype(np.float32)
+    got, ref, _ = _lists_case(st, depth, w, h)
+    assert got["P_raw"] == ref["P"]
+    assert np.array_equal(got["vals"], ref["vals"])
+    assert np.array_equal(got["keys"], ref["keys"])
+    assert np.array_equal(got["ranges"], ref["ranges"])
+
+
 def test_lists_all_equal_depth_one_tile():
     n = 5000                                               # one tile, one depth: pure index order, several sort blocks
     st = dict(mean2d=np.full((n, 2), 8.0, dtype=np.float32), conic=np.tile([0.1, 0, 0.1], (n, 1)), opacity=np.full(n, 0.01),
