@@ -47,10 +47,14 @@ __device__ __forceinline__ void tile_rect(const CamDev& cam, float mx, float my,
 
 // Gradient write-out of the splatting backward: "+=" into the caller's buffer (Alg. 1 lines 22-24), or a plain store
 // for the first view of a batch, which folds the zero-initialisation of line 21 into it.
+// The "+=" is an add performed by the memory side with no value returned (one thread per address and launch, so the
+// sum is what load, add, store would give, and the same on every run): as load, add, store the compiler keeps the 59
+// entries of a point in program order, each load waiting behind the store before it - a chain of 59 round trips.
 template <bool kFirst>
 __device__ __forceinline__ void grad_out(float* __restrict__ p, float v)
 {
-    if (kFirst) *p = v; else *p += v;
+    if (kFirst) *p = v;
+    else (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Raster record: everything the compositing kernels need about one splat, gathered with three 16-byte loads.

@@ -112,11 +112,17 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     float Y[16];
     sh_basis(kDeg, vx * vinv, vy * vinv, vz * vinv, Y);
     constexpr int K = (kDeg + 1) * (kDeg + 1);
+    // all coefficients asked for before the first is used (written as one loop with the sums, every load was waited for
+    // on its own: 48 round trips in a row per point)
+    float coef[3 * K];
+#pragma unroll
+    for (int j = 0; j < 3 * K; ++j) coef[j] = __builtin_nontemporal_load(&sc.sh[(size_t)j * N + i]);
+    const float lg = __builtin_nontemporal_load(&sc.logit[i]);
     float rgb[3] = {0.5f, 0.5f, 0.5f};
 #pragma unroll
     for (int k = 0; k < K; ++k) {
 #pragma unroll
-        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * __builtin_nontemporal_load(&sc.sh[(size_t)(3 * k + c) * N + i]);
+        for (int c = 0; c < 3; ++c) rgb[c] += Y[k] * coef[3 * k + c];
     }
     // normal = R (t_u x t_v), turned towards the camera
     float nw[3] = {F.tu[1] * F.tv[2] - F.tu[2] * F.tv[1], F.tu[2] * F.tv[0] - F.tu[0] * F.tv[2], F.tu[0] * F.tv[1] - F.tu[1] * F.tv[0]};
@@ -128,7 +134,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
     out.mean2d[i] = mx; out.mean2d[N + i] = my;
 #pragma unroll
     for (int k = 0; k < 9; ++k) out.T[(size_t)k * N + i] = T[k];
-    out.opacity[i] = 1.0f / (1.0f + expf(-__builtin_nontemporal_load(&sc.logit[i])));
+    out.opacity[i] = 1.0f / (1.0f + expf(-lg));
 #pragma unroll
     for (int c = 0; c < 3; ++c) { out.color[(size_t)c * N + i] = fmaxf(rgb[c], 0.f); out.normal[(size_t)c * N + i] = sgn * nc[c]; }
     out.radius[i] = r;
