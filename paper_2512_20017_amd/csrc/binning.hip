@@ -18,33 +18,55 @@ namespace pbdr {
 // that touch at least one tile - those are the points binning lists ("visible" below) - and the number of their pairs.
 // A state made by the preprocessing calls has radius == 0 for every point without a tile; a caller-made state with
 // radius > 0 and an empty tile rectangle is treated as culled here, so every listed point owns at least one pair.
+// Four consecutive points per thread (one 16-byte load of the radii, one 16-byte store of the counts: with one point
+// per thread the launch did not keep enough bytes in flight, 2 TB/s at eight million points: 32 -> 21 us there), so a
+// wavefront covers exactly one block of 256 points and its two sums need no LDS and no barrier.
 __global__ __launch_bounds__(256) void k_count_visible(BinInput in, CamDev cam, uint32_t* __restrict__ tiles_touched,
                                                        uint32_t* __restrict__ blk_vis, uint32_t* __restrict__ blk_pairs,
                                                        uint32_t* __restrict__ status, uint32_t* __restrict__ ranges, uint32_t nranges)
 {
-    __shared__ uint32_t sPairs[4];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
+    const int lane = threadIdx.x & 63;
     // first launch of a binning call: the status words and the tile ranges start at zero (every later kernel of the call
     // comes after this one on the stream)
-    if (i < kStCleared) status[i] = 0u;
-    for (uint32_t k = (uint32_t)i; k < nranges; k += gridDim.x * 256u) ranges[k] = 0u;
-    uint32_t t = 0;
-    if (i < in.n) {
-        const int r = in.radius[i];
-        if (r > 0) {
-            int x0, y0, x1, y1;
-            tile_rect(cam, in.mean2d[i], in.mean2d[(size_t)in.n + i], r, x0, y0, x1, y1);
-            t = (uint32_t)(max(x1 - x0, 0) * max(y1 - y0, 0));       // <= 2^24: the grid has at most 4096 x 4096 tiles
-        }
-        tiles_touched[i] = t;
+    if (gid < (uint32_t)kStCleared) status[gid] = 0u;
+    for (uint32_t k = gid; k < nranges; k += gridDim.x * 256u) ranges[k] = 0u;
+    const size_t i0 = (size_t)gid * 4u;
+    const size_t n = (size_t)in.n;
+    int r[4] = {0, 0, 0, 0};
+    if (i0 + 4u <= n && (reinterpret_cast<uintptr_t>(in.radius) & 15u) == 0u) {
+        const int4 v = *reinterpret_cast<const int4*>(in.radius + i0);
+        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (i0 + k < n) r[k] = in.radius[i0 + k];
     }
-    const uint32_t inc = wave_inclusive_scan_sat(t);
-    if (lane == 63) sPairs[wave] = inc;
-    const int c = __syncthreads_count(t > 0);
-    if (threadIdx.x == 0) {
-        blk_vis[blockIdx.x] = (uint32_t)c;
-        blk_pairs[blockIdx.x] = sat_add(sat_add(sPairs[0], sPairs[1]), sat_add(sPairs[2], sPairs[3]));
+    uint32_t t[4];
+    uint32_t vis = 0u, pairs = 0u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        t[k] = 0u;
+        if (r[k] > 0) {      // (r[k] is 0 past the end)
+            int x0, y0, x1, y1;
+            tile_rect(cam, in.mean2d[i0 + k], in.mean2d[n + i0 + k], r[k], x0, y0, x1, y1);
+            t[k] = (uint32_t)(max(x1 - x0, 0) * max(y1 - y0, 0));       // <= 2^24: the grid has at most 4096 x 4096 tiles
+        }
+        vis += t[k] > 0u ? 1u : 0u;
+        pairs = sat_add(pairs, t[k]);
+    }
+    if (i0 + 4u <= n) {
+        *reinterpret_cast<uint4*>(tiles_touched + i0) = make_uint4(t[0], t[1], t[2], t[3]);      // (the array starts on a 256-byte boundary)
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (i0 + k < n) tiles_touched[i0 + k] = t[k];
+    }
+    const uint32_t inc = wave_inclusive_scan_sat(pairs);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) vis += (uint32_t)__shfl_xor((int)vis, d, 64);
+    const size_t blk = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);      // the wavefront's 256 points
+    if (lane == 63 && blk * 256u < n) {
+        blk_vis[blk] = vis;
+        blk_pairs[blk] = inc;
     }
 }
 
@@ -361,6 +383,7 @@ BinArrays bin_arrays(const Layout& L, char* ws)
     A.blk_vis = reinterpret_cast<const uint32_t*>(ws + L.off_blk_vis_at);
     A.blk_pairs = reinterpret_cast<const uint32_t*>(ws + L.off_blk_pairs_at);
     A.blk_order = reinterpret_cast<const uint32_t*>(ws + L.off_blk_order);
+    A.blk_count = reinterpret_cast<const uint32_t*>(ws + L.off_blk_vis);
     A.order = reinterpret_cast<uint32_t*>(ws + L.off_order);
     A.offsets = reinterpret_cast<uint32_t*>(ws + L.off_offsets);
     A.slot_base = reinterpret_cast<uint32_t*>(ws + L.off_slot_base);
@@ -384,7 +407,7 @@ hipError_t launch_count_visible(const BinInput& in, const CamDev& cam, const Lay
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + L.off_status);
     const unsigned nb = (unsigned)((n + 255) / 256);
     ProfScope prof(kKCountPack, s);
-    hipLaunchKernelGGL(k_count_visible, dim3(nb), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), blk_vis,
+    hipLaunchKernelGGL(k_count_visible, dim3((nb + 3u) / 4u), dim3(256), 0, s, in, cam, reinterpret_cast<uint32_t*>(ws + L.off_touched), blk_vis,
                        blk_pairs, status, reinterpret_cast<uint32_t*>(ws + L.off_ranges), (uint32_t)(2 * (size_t)L.tiles));
     uint32_t* const vis_at = reinterpret_cast<uint32_t*>(ws + L.off_blk_vis_at);
     uint32_t* const pairs_at = reinterpret_cast<uint32_t*>(ws + L.off_blk_pairs_at);

@@ -31,6 +31,7 @@ struct BinArrays {
     const uint32_t* blk_vis;     // [blocks] listed points in the blocks before this one
     const uint32_t* blk_pairs;   // [blocks] pairs of the blocks before this one (saturating)
     const uint32_t* blk_order;   // [blocks] the block of points each workgroup takes: those with the most pairs first
+    const uint32_t* blk_count;   // [blocks] listed points of each block
     uint32_t* order;             // [n] listed points in index order ("rank" -> point)
     uint32_t* offsets;           // [n + 1] first pair of each rank; offsets[listed] = pair total (written by the block scan)
     uint32_t* slot_base;         // [n] first pair of each listed point, by point index
@@ -58,6 +59,8 @@ __device__ __forceinline__ void pack_dup_block(const BinInput& in, const CamDev&
     // the blocks with many pairs are started first: their wavefronts run longest (64 slots per step), and in index order
     // the launch ended on the few that happened to come late
     const uint32_t blk = A.blk_order[blockIdx.x];
+    // a block none of whose points is listed has nothing to write (most blocks, when the view sees a tenth of a large cloud)
+    if (A.blk_count[blk] == 0u) return;
     const int i = (int)(blk * 256u + threadIdx.x);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t cnt = (i < in.n) ? A.touched[i] : 0u;
