@@ -495,8 +495,9 @@ static int render_bwd_impl(const pbdr_scene* scene, const pbdr_splats* splats, c
     if (e != hipSuccess || !scene) return hip_result(e);
     if (!g_splats)      // no splat-state gradient asked for: the splatting backward reads the workspace's per-point records
         return hip_result(launch_preprocess_bwd_records(dev(scene), c, reinterpret_cast<const uint32_t*>((char*)workspace + L.off_touched),
-                                                        reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec), dev(grads),
-                                                        grads->first_view != 0, (hipStream_t)hip_stream));
+                                                        reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec),
+                                                        carry_fold(L, (char*)workspace), dev(grads), grads->first_view != 0,
+                                                        (hipStream_t)hip_stream));
     // g_splats holds this call's values for exactly the points binning listed (tile count > 0), so those, not
     // radius > 0, are the points the second half may read: a whole-image state rendered through a patch, or a
     // caller-made state with an empty tile rectangle, has radius > 0 points that were never listed
@@ -689,8 +690,9 @@ static int render2d_bwd_impl(const pbdr2d_scene* scene, const pbdr2d_splats* spl
     if (!g_splats)      // no splat-state gradient asked for: the splatting backward reads the workspace's per-point records
         return hip_result(launch_preprocess2d_bwd_records(dev(scene), c, dev(splats),
                                                           reinterpret_cast<const uint32_t*>((char*)workspace + L.off_touched),
-                                                          reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec), dev(grads),
-                                                          grads->first_view != 0, (hipStream_t)hip_stream));
+                                                          reinterpret_cast<const float4*>((char*)workspace + L.off_grad_rec),
+                                                          carry_fold(L, (char*)workspace), dev(grads), grads->first_view != 0,
+                                                          (hipStream_t)hip_stream));
     Splats2DDev listed = dev(splats);      // as in the 3D call: the points binning listed are the ones g_splats was written for
     listed.radius = reinterpret_cast<int32_t*>((char*)workspace + L.off_touched);
     return hip_result(launch_preprocess2d_bwd(dev(scene), c, listed, dev(g_splats), dev(grads), grads->first_view != 0,

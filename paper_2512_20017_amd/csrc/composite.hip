@@ -570,6 +570,12 @@ hipError_t launch_composite_fwd(const CamDev& cam, const Layout& L, char* ws, co
     return hipGetLastError();
 }
 
+CarryFold carry_fold(const Layout& L, char* ws)
+{
+    return CarryFold{reinterpret_cast<const float*>(ws + L.off_carry), reinterpret_cast<const uint32_t*>(ws + L.off_slot_base),
+                     reinterpret_cast<uint32_t*>(ws + L.off_status), L.cap};
+}
+
 hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, int n, const float bg[3], const float* final_T, const uint32_t* last_idx, const float* dL_dimage,
                                 const SplatGradDev& g2, hipStream_t s)
 {
@@ -596,10 +602,13 @@ hipError_t launch_composite_bwd(const CamDev& cam, const Layout& L, char* ws, in
         float4* rec = reinterpret_cast<float4*>(ws + L.off_grad_rec);
         hipLaunchKernelGGL(k_gather_splat_grads, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank,
                            partial, L.cap, carry, rec);
-        hipLaunchKernelGGL(k_gather_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
-        if (g2.mean2d != nullptr)       // else the caller goes on from the records (launch_preprocess_bwd_records)
+        if (g2.mean2d != nullptr) {
+            hipLaunchKernelGGL(k_gather_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
             hipLaunchKernelGGL(k_grad_records_to_planes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
                                reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
+        }
+        // else the caller goes on from the records with launch_preprocess_bwd_records, whose kernel puts the records cut
+        // by wavefront boundaries together itself and closes the epoch (carry_fold below): one launch fewer
     }
     return hipGetLastError();
 }

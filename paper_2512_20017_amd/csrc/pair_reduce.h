@@ -214,4 +214,42 @@ __device__ __forceinline__ void gather_fixup(uint32_t w, const uint32_t* __restr
     store(rank, v);
 }
 
+// What k_gather_fixup does, from the side of the point: used by the kernels that read a point's record right after the
+// gather, so that the fixup launch (a few microseconds for ten thousand additions) can be left out. at, count: the
+// point's first pair and its number of pairs. Returns false if all of its pairs lie in one wavefront's 256 (the gather
+// stored the record itself); else v = the right piece of the wavefront its first pair lies in, plus the left pieces of
+// the following wavefronts up to and including the first that is not a through piece - the pieces and the order of
+// gather_fixup, so the sum is bit for bit the record that kernel would store.
+template <int kVals>
+__device__ __forceinline__ bool record_from_carries(const CarryFold& cf, uint32_t at, uint32_t count, float (&v)[kVals])
+{
+    const uint32_t Pc = min(cf.status[kStNumDup], cf.cap);
+    const uint32_t beg = min(at, Pc), end = min(at + count, Pc);      // (at < 2^31, count <= 2^24)
+    const uint32_t w = beg / (uint32_t)kChunkPairs;
+    if (end <= (w + 1u) * (uint32_t)kChunkPairs) return false;
+    const uint32_t nw = (Pc + kChunkPairs - 1) / kChunkPairs;
+    const float* c = cf.carry + (size_t)w * kCarryFloats;
+    const uint32_t rank = reinterpret_cast<const uint32_t*>(c + 32)[2];
+#pragma unroll
+    for (int k = 0; k < kVals; ++k) v[k] = c[16 + k];
+    for (uint32_t w2 = w + 1; w2 < nw; ++w2) {
+        const float* c2 = cf.carry + (size_t)w2 * kCarryFloats;
+        const uint32_t* m2 = reinterpret_cast<const uint32_t*>(c2 + 32);
+        const uint32_t f2 = m2[0];
+        if (!(f2 & kCarryHasLeft) || m2[1] != rank) break;
+#pragma unroll
+        for (int k = 0; k < kVals; ++k) v[k] += c2[k];
+        if (!(f2 & kCarryLeftThrough)) break;
+    }
+    return true;
+}
+
+// the count of backward calls on this workspace goes up by one (k_gather_fixup does it when it runs)
+__device__ __forceinline__ void close_backward_epoch(uint32_t* status)
+{
+    const uint32_t lo = status[kStEpoch] + 1u;
+    status[kStEpoch] = lo;
+    if (lo == 0u) status[kStEpoch + 1] = status[kStEpoch + 1] + 1u;
+}
+
 }  // namespace pbdr

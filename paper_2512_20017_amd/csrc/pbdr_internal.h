@@ -151,7 +151,17 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
                              int group_size, hipStream_t s);
 hipError_t launch_group_bounds(const SceneDev& sc, int group_size, float* bounds, hipStream_t s);
 hipError_t launch_group_cull(const CamDev& cam, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
-hipError_t launch_preprocess_bwd_records(const SceneDev& sc, const CamDev& cam, const uint32_t* tiles_touched, const float4* rec,
+// For the kernels that read a point's gradient record straight after the gather and finish the records cut by
+// wavefront boundaries themselves (pair_reduce.h: record_from_carries), in place of the k_gather_fixup launch.
+struct CarryFold {
+    const float* carry;             // null: the records are complete (k_gather_fixup has run)
+    const uint32_t* slot_base;      // [n] first pair of each listed point
+    uint32_t* status;
+    uint32_t cap;
+};
+CarryFold carry_fold(const Layout& L, char* ws);
+
+hipError_t launch_preprocess_bwd_records(const SceneDev& sc, const CamDev& cam, const uint32_t* tiles_touched, const float4* rec, const CarryFold& cf,
                                          const SceneGradDev& g, bool first_view, hipStream_t s);
 hipError_t launch_group_cull_batch(const BatchCams& cams, int n_groups, const float* bounds, uint8_t* keep, hipStream_t s);
 hipError_t launch_preprocess_batch(const SceneDev& sc, const BatchCams& cams, const BatchSplats& outs, const uint8_t* keep,
@@ -193,7 +203,7 @@ hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Sp
 hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const Splat2DGradDev& g2,
                                    const Scene2DGradDev& g, bool first_view, hipStream_t s);
 hipError_t launch_preprocess2d_bwd_records(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const uint32_t* tiles_touched,
-                                           const float4* rec, const Scene2DGradDev& g, bool first_view, hipStream_t s);
+                                           const float4* rec, const CarryFold& cf, const Scene2DGradDev& g, bool first_view, hipStream_t s);
 hipError_t launch_bin_sort2d(const Splats2DDev& sp, const CamDev& cam, const Layout& L, char* ws, hipStream_t s);
 hipError_t launch_composite2d_fwd(const CamDev& cam, const Layout& L, char* ws, const float bg[3], float* image,
                                   float* final_T, uint32_t* last_idx, hipStream_t s);

@@ -5,6 +5,7 @@
 // attribute (256-byte coalesced segments); the 48 SH planes are only touched by points that survive culling.
 // HBM-bound: 236 B read + 44 B written per surviving point, 12 B + 4 B per point culled by depth.
 #include "pbdr_internal.h"
+#include "pair_reduce.h"
 
 // No fused multiply-adds formed by the compiler in this file. Which products get fused into which sums depends on how
 // the surrounding code is laid out (what shares a basic block after inlining, hoisting and unrolling), so the one-view
@@ -230,6 +231,14 @@ struct SplatGradIn {
         opacity = g2.opacity[i];
         color[0] = g2.color[i]; color[1] = g2.color[N + i]; color[2] = g2.color[2 * N + i];
     }
+    // from the nine sums in the record's order
+    __device__ __forceinline__ void from_values(const float (&v)[9])
+    {
+        mean2d[0] = v[0]; mean2d[1] = v[1];
+        conic[0] = v[2]; conic[1] = v[3]; conic[2] = v[4];
+        opacity = v[5];
+        color[0] = v[6]; color[1] = v[7]; color[2] = v[8];
+    }
     // from the 48-byte per-point record the gather of the compositing backward leaves in the workspace
     __device__ __forceinline__ void load_record(const float4* __restrict__ rec, int i)
     {
@@ -429,10 +438,12 @@ __device__ __forceinline__ void zero_point_grads(const SceneGradDev& g, int i, s
 // g2, for the points with radius > 0 (`used` = radius).
 template <int kDeg, bool kFirst, bool kFromRecords>
 __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam, const int32_t* __restrict__ used,
-                                                        SplatGradDev g2, const float4* __restrict__ rec, SceneGradDev g)
+                                                        SplatGradDev g2, const float4* __restrict__ rec, CarryFold cf, SceneGradDev g)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
+    // (with cf.carry this launch stands in for k_gather_fixup: it also closes the backward call's epoch)
+    if (kFromRecords && cf.carry != nullptr && i == 0) close_backward_epoch(cf.status);
     if (i >= n) return;
     const size_t N = (size_t)n;
     if (used[i] <= 0) {
@@ -442,8 +453,15 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(SceneDev sc, CamDev cam,
     DirectSrc<kDeg> src(sc, i);
     src.need_shape();
     SplatGradIn in;
-    if (kFromRecords) in.load_record(rec, i);
-    else in.load(g2, i, N);
+    if (kFromRecords) {
+        in.load_record(rec, i);
+        if (cf.carry != nullptr) {      // a point whose pairs are cut by a wavefront boundary of the gather: its record is still in pieces
+            float v[9];
+            if (record_from_carries<9>(cf, cf.slot_base[i], (uint32_t)used[i], v)) in.from_values(v);
+        }
+    } else {
+        in.load(g2, i, N);
+    }
     MemSink<kDeg, kFirst> sink{g, i, N};
     preprocess_point_bwd<kDeg>(cam, src, in, sink);
 }
@@ -562,13 +580,13 @@ hipError_t launch_preprocess(const SceneDev& sc, const CamDev& cam, const Splats
 
 template <bool kFirst, bool kFromRecords>
 static void launch_preprocess_bwd_t(const SceneDev& sc, const CamDev& cam, const int32_t* used, const SplatGradDev& g2,
-                                    const float4* rec, const SceneGradDev& g, unsigned blocks, hipStream_t s)
+                                    const float4* rec, const CarryFold& cf, const SceneGradDev& g, unsigned blocks, hipStream_t s)
 {
     switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL((k_preprocess_bwd<0, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
-        case 1: hipLaunchKernelGGL((k_preprocess_bwd<1, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
-        case 2: hipLaunchKernelGGL((k_preprocess_bwd<2, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
-        default: hipLaunchKernelGGL((k_preprocess_bwd<3, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, g); break;
+        case 0: hipLaunchKernelGGL((k_preprocess_bwd<0, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, cf, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess_bwd<1, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, cf, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess_bwd<2, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, cf, g); break;
+        default: hipLaunchKernelGGL((k_preprocess_bwd<3, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, g2, rec, cf, g); break;
     }
 }
 
@@ -578,22 +596,23 @@ hipError_t launch_preprocess_bwd(const SceneDev& sc, const CamDev& cam, const in
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    if (first_view) launch_preprocess_bwd_t<true, false>(sc, cam, radius, g2, nullptr, g, blocks, s);
-    else launch_preprocess_bwd_t<false, false>(sc, cam, radius, g2, nullptr, g, blocks, s);
+    const CarryFold none{nullptr, nullptr, nullptr, 0u};
+    if (first_view) launch_preprocess_bwd_t<true, false>(sc, cam, radius, g2, nullptr, none, g, blocks, s);
+    else launch_preprocess_bwd_t<false, false>(sc, cam, radius, g2, nullptr, none, g, blocks, s);
     return hipGetLastError();
 }
 
 // the same from the per-point gradient records in the workspace (see k_preprocess_bwd)
 hipError_t launch_preprocess_bwd_records(const SceneDev& sc, const CamDev& cam, const uint32_t* tiles_touched, const float4* rec,
-                                         const SceneGradDev& g, bool first_view, hipStream_t s)
+                                         const CarryFold& cf, const SceneGradDev& g, bool first_view, hipStream_t s)
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     const int32_t* used = reinterpret_cast<const int32_t*>(tiles_touched);     // counts are far below 2^31
     const SplatGradDev none{nullptr, nullptr, nullptr, nullptr};
     ProfScope prof(kKPreprocessBwd, s);
-    if (first_view) launch_preprocess_bwd_t<true, true>(sc, cam, used, none, rec, g, blocks, s);
-    else launch_preprocess_bwd_t<false, true>(sc, cam, used, none, rec, g, blocks, s);
+    if (first_view) launch_preprocess_bwd_t<true, true>(sc, cam, used, none, rec, cf, g, blocks, s);
+    else launch_preprocess_bwd_t<false, true>(sc, cam, used, none, rec, cf, g, blocks, s);
     return hipGetLastError();
 }
 

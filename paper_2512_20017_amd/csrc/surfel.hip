@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void k_preprocess2d(Scene2DDev sc, CamDev cam,
 template <int kDeg, bool kFirst, bool kFromRecords>
 __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev cam, const int32_t* __restrict__ radius,
                                                           const float* __restrict__ Tst, Splat2DGradDev g2,
-                                                          const float4* __restrict__ rec, Scene2DGradDev g)
+                                                          const float4* __restrict__ rec, CarryFold cf, Scene2DGradDev g)
 {
     const int n = sc.n;
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -176,6 +176,9 @@ __global__ __launch_bounds__(256) void k_preprocess2d_bwd(Scene2DDev sc, CamDev 
         const float v[15] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w, rc.x, rc.y, rc.z, rc.w, rd.x, rd.y, rd.z};
 #pragma unroll
         for (int k = 0; k < 15; ++k) gs[k] = v[k];
+        // a point whose pairs are cut by a wavefront boundary of the gather: its record is still in pieces (this launch
+        // stands in for k_gather2d_fixup, see pair_reduce.h)
+        if (cf.carry != nullptr) (void)record_from_carries<15>(cf, cf.slot_base[i], (uint32_t)radius[i], gs);
     } else {
 #pragma unroll
         for (int k = 0; k < 9; ++k) gs[k] = g2.T[(size_t)k * N + i];
@@ -724,13 +727,14 @@ hipError_t launch_preprocess2d(const Scene2DDev& sc, const CamDev& cam, const Sp
 
 template <bool kFirst, bool kFromRecords>
 static void launch_preprocess2d_bwd_t(const Scene2DDev& sc, const CamDev& cam, const int32_t* used, const float* Tst,
-                                      const Splat2DGradDev& g2, const float4* rec, const Scene2DGradDev& g, unsigned blocks, hipStream_t s)
+                                      const Splat2DGradDev& g2, const float4* rec, const CarryFold& cf, const Scene2DGradDev& g, unsigned blocks,
+                                      hipStream_t s)
 {
     switch (sc.sh_degree) {
-        case 0: hipLaunchKernelGGL((k_preprocess2d_bwd<0, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
-        case 1: hipLaunchKernelGGL((k_preprocess2d_bwd<1, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
-        case 2: hipLaunchKernelGGL((k_preprocess2d_bwd<2, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
-        default: hipLaunchKernelGGL((k_preprocess2d_bwd<3, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, g); break;
+        case 0: hipLaunchKernelGGL((k_preprocess2d_bwd<0, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, cf, g); break;
+        case 1: hipLaunchKernelGGL((k_preprocess2d_bwd<1, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, cf, g); break;
+        case 2: hipLaunchKernelGGL((k_preprocess2d_bwd<2, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, cf, g); break;
+        default: hipLaunchKernelGGL((k_preprocess2d_bwd<3, kFirst, kFromRecords>), dim3(blocks), dim3(256), 0, s, sc, cam, used, Tst, g2, rec, cf, g); break;
     }
 }
 
@@ -740,22 +744,23 @@ hipError_t launch_preprocess2d_bwd(const Scene2DDev& sc, const CamDev& cam, cons
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     ProfScope prof(kKPreprocessBwd, s);
-    if (first_view) launch_preprocess2d_bwd_t<true, false>(sc, cam, sp.radius, sp.T, g2, nullptr, g, blocks, s);
-    else launch_preprocess2d_bwd_t<false, false>(sc, cam, sp.radius, sp.T, g2, nullptr, g, blocks, s);
+    const CarryFold no_fold{nullptr, nullptr, nullptr, 0u};
+    if (first_view) launch_preprocess2d_bwd_t<true, false>(sc, cam, sp.radius, sp.T, g2, nullptr, no_fold, g, blocks, s);
+    else launch_preprocess2d_bwd_t<false, false>(sc, cam, sp.radius, sp.T, g2, nullptr, no_fold, g, blocks, s);
     return hipGetLastError();
 }
 
 // the same from the per-point gradient records in the workspace (see k_preprocess2d_bwd)
 hipError_t launch_preprocess2d_bwd_records(const Scene2DDev& sc, const CamDev& cam, const Splats2DDev& sp, const uint32_t* tiles_touched,
-                                           const float4* rec, const Scene2DGradDev& g, bool first_view, hipStream_t s)
+                                           const float4* rec, const CarryFold& cf, const Scene2DGradDev& g, bool first_view, hipStream_t s)
 {
     if (sc.n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)((sc.n + 255) / 256);
     const int32_t* used = reinterpret_cast<const int32_t*>(tiles_touched);     // counts are far below 2^31
     const Splat2DGradDev none{nullptr, nullptr, nullptr, nullptr};
     ProfScope prof(kKPreprocessBwd, s);
-    if (first_view) launch_preprocess2d_bwd_t<true, true>(sc, cam, used, sp.T, none, rec, g, blocks, s);
-    else launch_preprocess2d_bwd_t<false, true>(sc, cam, used, sp.T, none, rec, g, blocks, s);
+    if (first_view) launch_preprocess2d_bwd_t<true, true>(sc, cam, used, sp.T, none, rec, cf, g, blocks, s);
+    else launch_preprocess2d_bwd_t<false, true>(sc, cam, used, sp.T, none, rec, cf, g, blocks, s);
     return hipGetLastError();
 }
 
@@ -808,10 +813,11 @@ hipError_t launch_composite2d_bwd(const CamDev& cam, const Layout& L, char* ws, 
         float4* rec = reinterpret_cast<float4*>(ws + L.off_grad_rec);
         hipLaunchKernelGGL(k_gather2d, dim3((nwave + 3) / 4), dim3(256), 0, s, n, status, order, offsets, chunk_rank, partial,
                            L.cap, carry, rec);
-        hipLaunchKernelGGL(k_gather2d_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
-        if (g2.mean2d != nullptr)       // else the caller goes on from the records (launch_preprocess2d_bwd_records)
+        if (g2.mean2d != nullptr) {      // else the caller goes on from the records, pieces included (launch_preprocess2d_bwd_records)
+            hipLaunchKernelGGL(k_gather2d_fixup, dim3((nwave + 255) / 256), dim3(256), 0, s, n, status, order, L.cap, carry, rec);
             hipLaunchKernelGGL(k_grad_records_to_planes2d, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n,
                                reinterpret_cast<const uint32_t*>(ws + L.off_touched), rec, g2);
+        }
     }
     return hipGetLastError();
 }
